@@ -1,0 +1,155 @@
+"""ctypes + numpy front end of the CPU oracle (test infrastructure only).
+
+Only tests, ``__graft_entry__.smoke()`` and the benchmark's CPU-baseline leg may
+import this module.  Every function marshals arrays and calls fvdb_oracle.c; the
+passages each routine follows are cited there.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Optional, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+LEAF_DTYPE = np.dtype([("offset", "<i8"), ("prefix", "<u8"), ("mask", "<u8", (8,)),
+                       ("origin", "<i4", (3,)), ("batch", "<i4")])
+assert LEAF_DTYPE.itemsize == 96
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        L.fo_grid_create.restype = vp
+        L.fo_grid_create.argtypes = [vp, vp, i32]
+        L.fo_grid_destroy.argtypes = [vp]
+        L.fo_grid_num_voxels.restype = i64
+        L.fo_grid_num_voxels.argtypes = [vp]
+        L.fo_grid_batch_size.restype = i32
+        L.fo_grid_batch_size.argtypes = [vp]
+        L.fo_grid_num_leaves.restype = i64
+        L.fo_grid_num_leaves.argtypes = [vp]
+        L.fo_grid_counts.argtypes = [vp, vp]
+        L.fo_grid_voxel_joffsets.argtypes = [vp, vp]
+        L.fo_grid_ijk.argtypes = [vp, vp, vp]
+        L.fo_grid_leaf_table.argtypes = [vp, vp]
+        L.fo_grid_lookup.argtypes = [vp, vp, vp, i64, vp]
+        L.fo_grid_coarsen2.restype = vp
+        L.fo_grid_coarsen2.argtypes = [vp]
+        L.fo_kernel_map.restype = i64
+        L.fo_kernel_map.argtypes = [vp, vp, C.c_int, C.c_int, vp]
+        L.fo_conv.restype = i64
+        L.fo_conv.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp, i64, i64]
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class OracleGrid:
+    """Index grid of a jagged batch of voxel coordinates (O1)."""
+
+    def __init__(self, ijk: Optional[np.ndarray], joffsets: Optional[np.ndarray], _handle=None):
+        L = lib()
+        if _handle is not None:
+            self._h = _handle
+        else:
+            ijk = np.ascontiguousarray(ijk, dtype=np.int32).reshape(-1, 3)
+            joffsets = np.ascontiguousarray(joffsets, dtype=np.int64).reshape(-1, 2)
+            self._h = L.fo_grid_create(_p(ijk), _p(joffsets), joffsets.shape[0])
+        if not self._h:
+            raise MemoryError("oracle grid allocation failed")
+
+    def __del__(self):
+        h = getattr(self, "_h", None)
+        if h and _lib is not None:
+            _lib.fo_grid_destroy(h)
+            self._h = None
+
+    @property
+    def num_voxels(self) -> int:
+        return int(lib().fo_grid_num_voxels(self._h))
+
+    @property
+    def batch_size(self) -> int:
+        return int(lib().fo_grid_batch_size(self._h))
+
+    def counts(self) -> Tuple[int, int, int]:
+        """(leaf, lower, upper) node counts."""
+        c = np.zeros(3, dtype=np.int64)
+        lib().fo_grid_counts(self._h, _p(c))
+        return int(c[0]), int(c[1]), int(c[2])
+
+    def voxel_joffsets(self) -> np.ndarray:
+        out = np.zeros((self.batch_size, 2), dtype=np.int64)
+        lib().fo_grid_voxel_joffsets(self._h, _p(out))
+        return out
+
+    def ijk(self) -> Tuple[np.ndarray, np.ndarray]:
+        """Coordinates [N,3] and batch ids [N] in index order."""
+        n = self.num_voxels
+        out = np.zeros((n, 3), dtype=np.int32)
+        jidx = np.zeros(n, dtype=np.int32)
+        lib().fo_grid_ijk(self._h, _p(out), _p(jidx))
+        return out, jidx
+
+    def leaf_table(self) -> np.ndarray:
+        n = int(lib().fo_grid_num_leaves(self._h))
+        out = np.zeros(n, dtype=LEAF_DTYPE)
+        lib().fo_grid_leaf_table(self._h, _p(out))
+        return out
+
+    def lookup(self, ijk: np.ndarray, jidx: Optional[np.ndarray] = None) -> np.ndarray:
+        ijk = np.ascontiguousarray(ijk, dtype=np.int32).reshape(-1, 3)
+        if jidx is not None:
+            jidx = np.ascontiguousarray(jidx, dtype=np.int32)
+        out = np.zeros(ijk.shape[0], dtype=np.int64)
+        lib().fo_grid_lookup(self._h, _p(ijk), _p(jidx), ijk.shape[0], _p(out))
+        return out
+
+    def coarsen2(self) -> "OracleGrid":
+        return OracleGrid(None, None, _handle=lib().fo_grid_coarsen2(self._h))
+
+
+def output_grid(gin: OracleGrid, kernel_size: int, stride: int) -> OracleGrid:
+    if stride == 1:
+        return gin
+    if stride == 2:
+        return gin.coarsen2()
+    raise ValueError("stride must be 1 or 2")
+
+
+def kernel_map(gin: OracleGrid, gout: OracleGrid, kernel_size: int, stride: int) -> np.ndarray:
+    """nbmap [N_out, K^3] int64, -1 = no active input voxel (O2)."""
+    k3 = kernel_size ** 3
+    out = np.zeros((gout.num_voxels, k3), dtype=np.int64)
+    r = lib().fo_kernel_map(gin._h, gout._h, kernel_size, stride, _p(out))
+    if r < 0:
+        raise ValueError("bad kernel-map arguments")
+    return out
+
+
+def conv(gin: OracleGrid, gout: OracleGrid, kernel_size: int, stride: int, feat: np.ndarray,
+         w: np.ndarray, o_begin: int = 0, o_end: Optional[int] = None) -> np.ndarray:
+    """out [N_out, C_out] float64 (O3); rows outside [o_begin, o_end) are zero."""
+    feat = np.ascontiguousarray(feat, dtype=np.float64)
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    k3, c_in, c_out = w.shape
+    assert k3 == kernel_size ** 3 and feat.shape == (gin.num_voxels, c_in)
+    n_out = gout.num_voxels
+    if o_end is None:
+        o_end = n_out
+    out = np.zeros((n_out, c_out), dtype=np.float64)
+    r = lib().fo_conv(gin._h, gout._h, kernel_size, stride, _p(feat), _p(w), c_in, c_out, _p(out),
+                      o_begin, o_end)
+    if r < 0:
+        raise ValueError("bad conv arguments")
+    return out
