@@ -1,0 +1,161 @@
+/*
+ * fvdb_hotpath.h -- C ABI of the MI355X (gfx950) sparse-convolution hot path of fVDB
+ * (arXiv 2407.01781): index-grid build, kernel-map build, sparse convolution forward.
+ *
+ * Conventions that hold for every call
+ *   - Pointers named d_* are DEVICE pointers (HIP, current device); h_* are HOST pointers.
+ *   - Inputs are borrowed for the duration of the stream-ordered work; outputs named d_*
+ *     are caller-allocated.  Handles (fx_grid, fx_kmap) are library-owned, reference
+ *     counted and released with the matching *_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device
+ *     work is enqueued on it.  Calls that must read a count back (documented below)
+ *     synchronise that stream internally.
+ *   - Every call returns an fx_status.  Out-parameters are written only on FX_OK.  No C++
+ *     exception and no abort crosses this boundary.  fx_last_error() gives a thread-local
+ *     message for the last non-OK status.
+ *   - Voxel indices are 0-based row numbers of the side-car feature arrays (jdata);
+ *     -1 means "no active voxel" (Sec. 3.2: only active voxels get an index).
+ *   - A batch of grids is described as a JaggedTensor (Sec. 3.6.1): jdata rows of all
+ *     grids back to back plus joffsets [B,2] = (start,end) row of each grid.
+ */
+#ifndef FVDB_HOTPATH_H
+#define FVDB_HOTPATH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fx_grid fx_grid; /* one GridBatch: B IndexGrids in one flat device buffer (Sec. 3.6) */
+typedef struct fx_kmap fx_kmap; /* kernel map of one (g_in, kernel_size, stride); holds refs on its grids */
+
+typedef enum {
+    FX_OK = 0,
+    FX_EINVAL = -1,       /* bad argument (null pointer, negative size, malformed joffsets, ...) */
+    FX_EUNSUPPORTED = -2, /* valid request this build does not implement                       */
+    FX_ENOMEM = -3,       /* device or host allocation failed                                  */
+    FX_EDEVICE = -4,      /* a HIP call failed; fx_last_error() carries hipGetErrorString      */
+    FX_ERANGE = -5        /* input exceeds a documented limit                                  */
+} fx_status;
+
+typedef enum { FX_F32 = 0, FX_F16 = 1, FX_BF16 = 2 } fx_dtype;
+
+/* One leaf node as exported by fx_grid_leaf_table: the 80-byte record of Listing 1
+ * (mOffset, mPrefixSum, mBitMask[8]) followed by the leaf's origin and grid id.
+ *   offset : index of the leaf's first active voxel (0-based, global over the batch)
+ *   prefix : bits 9w..9w+8 (w = 0..6) = popcount of mask words 0..w
+ *   mask   : word = i&7, bit = (j&7)<<3 | (k&7)   (Listing 1's `off`)
+ *   origin : 8*(i>>3), 8*(j>>3), 8*(k>>3)                                              */
+typedef struct {
+    int64_t  offset;
+    uint64_t prefix;
+    uint64_t mask[8];
+    int32_t  origin[3];
+    int32_t  batch;
+} fx_leaf;
+
+/* Library version string and a no-op device check (returns FX_EDEVICE if no HIP device). */
+const char* fx_version(void);
+fx_status   fx_init(void);
+const char* fx_last_error(void);
+
+/* ---------------------------------------------------------------------------------------
+ * Index-grid build (Sec. 3.3: build an IndexGrid from N signed voxel coordinates; Sec. 3.2
+ * and Listings 1-2: the leaf / lower / upper node layout and offsets; Sec. 3.6: batches).
+ *
+ *   d_ijk      device [n_rows,3] int32, row-major (i,j,k); any order, duplicates allowed
+ *   h_joffsets host   [B,2] int64: grid b owns rows [start_b,end_b); ranges must lie in
+ *              [0,n_rows], be non-overlapping and in increasing order; empty ranges and
+ *              B == 0 are valid
+ *   out        new grid handle.  Active voxels of grid b are ordered by (root tile signed
+ *              i,j,k; upper offset; lower offset; leaf offset) -- the order produced by the
+ *              two sorts of Sec. 3.3 -- and numbered base_b + rank, base_b = number of
+ *              voxels in grids 0..b-1.
+ * Synchronises `stream` internally (node counts are read back to size the tree: step 10).
+ * Limits: at most 65536 root tiles (4096^3 regions) per batch, 2^31-1 voxels -> FX_ERANGE.
+ */
+fx_status fx_build_index_grid(const int32_t* d_ijk, int64_t n_rows, const int64_t* h_joffsets,
+                              int32_t B, void* stream, fx_grid** out);
+
+/* Sizes of a grid: total active voxels, batch size, per-grid voxel ranges [B,2] (host, may
+ * be NULL) and node counts {leaf, lower, upper} (host, may be NULL). */
+fx_status fx_grid_info(const fx_grid* g, int64_t* n_voxels, int32_t* B,
+                       int64_t* h_voxel_joffsets, int64_t* h_counts3);
+
+/* Coordinates of all active voxels in index order: d_ijk_out [N,3] int32, and the grid id
+ * of each (d_jidx_out [N] int32, may be NULL) -- the jidx of Sec. 3.6.1. */
+fx_status fx_grid_ijk(const fx_grid* g, int32_t* d_ijk_out, int32_t* d_jidx_out, void* stream);
+
+/* Listing 1's getValue for n query coordinates: d_index_out[r] = index of voxel d_ijk[r] in
+ * grid d_jidx[r] (NULL = grid 0), or -1 if inactive / grid id out of range. */
+fx_status fx_grid_ijk_to_index(const fx_grid* g, const int32_t* d_ijk, const int32_t* d_jidx,
+                               int64_t n, int32_t* d_index_out, void* stream);
+
+/* Copy the leaf table (n_leaf records of fx_leaf, index order) to HOST memory.
+ * `bytes` must be >= n_leaf * sizeof(fx_leaf).  Synchronises `stream`. */
+fx_status fx_grid_leaf_table(const fx_grid* g, fx_leaf* h_out, size_t bytes, void* stream);
+
+/* Output grid of a stride-2 operator: active set = distinct floor(ijk/2) per grid (the
+ * coarsening of Sec. 3.6.2 "Grid Construction Operators").  Synchronises `stream`. */
+fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** out);
+
+void fx_grid_retain(fx_grid* g);
+void fx_grid_destroy(fx_grid* g);
+
+/* ---------------------------------------------------------------------------------------
+ * Kernel map (Sec. 3.5: for every output voxel and stencil offset, the input voxel linked
+ * by that offset, found through the tree's index lookup; scenario 3 (a)-(c): blocks of
+ * consecutive output indices with per-offset packed pairs).
+ *
+ *   kernel_size K, stride s: supported (K,s) = (1,1), (3,1), (5,1), (2,2).
+ *   Offsets: K odd -> delta in {-(K-1)/2..(K-1)/2}^3; K even -> {0..K-1}^3;
+ *            kappa = (di-dmin)*K*K + (dj-dmin)*K + (dk-dmin)   (i slowest).
+ *   Output grid: s == 1 -> g_in itself (submanifold; *g_out = g_in with one more reference);
+ *                s == 2 -> fx_grid_coarsen2(g_in).
+ *   map(o,kappa) = index in g_in of voxel  s*p_o + delta_kappa  (same grid of the batch), or -1.
+ * Both handles must be destroyed by the caller.  Synchronises `stream` when s == 2.
+ */
+fx_status fx_build_kernel_map(fx_grid* g_in, int32_t kernel_size, int32_t stride, void* stream,
+                              fx_grid** g_out, fx_kmap** out);
+
+/* n_out, K^3, number of active (output, offset) pairs and pairs per offset (host [K^3], may
+ * be NULL).  Synchronises the stream the map was built on. */
+fx_status fx_kmap_info(const fx_kmap* km, int64_t* n_out, int32_t* k3, int64_t* n_pairs,
+                       int64_t* h_pairs_per_offset);
+
+/* The map as a dense table d_nbmap [N_out, K^3] int32 (-1 = none), decoded from the tiled
+ * form the convolution kernels consume. */
+fx_status fx_kmap_dense(const fx_kmap* km, int32_t* d_nbmap, void* stream);
+
+/* Tiling statistics (host): h_stats[0] = MFMA rows issued by the tiled convolution (16 per
+ * non-empty (group, offset) block), [1] = number of tiles, [2] = staged input rows summed
+ * over tiles, [3] = tile size T.  Synchronises the build stream. */
+fx_status fx_kmap_tile_stats(const fx_kmap* km, int64_t* h_stats4);
+
+void fx_kmap_destroy(fx_kmap* km);
+
+/* ---------------------------------------------------------------------------------------
+ * Sparse convolution forward (Sec. 3.6.2: G_in, kernel, Z_in -> Z_out on G_out; Sec. 3.5
+ * scenario 3: gather, per-offset GEMM, accumulate, sequential write-back; Sec. 4.1.3:
+ * only taps with an active input voxel contribute):
+ *     out[o,:] = sum_{kappa : map(o,kappa) >= 0}  feat[map(o,kappa),:] . W[kappa]
+ *
+ *   d_feat  device [N_in, C_in]  row-major, dtype in_dt
+ *   d_w     device [K^3, C_in, C_out] row-major, dtype in_dt
+ *   d_out   device [N_out, C_out] row-major, dtype out_dt (= in_dt or FX_F32); every row is
+ *           written (rows without any active tap become 0)
+ * Products are exact in the input precision's product format and accumulated in fp32
+ * (FX_F32 inputs: fp32 FMA; FX_F16 / FX_BF16: MFMA with fp32 accumulators); the result is
+ * rounded to out_dt with round-to-nearest-even.
+ * C_in, C_out >= 1.  The MFMA path needs C_in % 64 == 0 and C_out % 64 == 0; other
+ * shapes and FX_F32 take the scalar path.
+ */
+fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w,
+                             int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FVDB_HOTPATH_H */

@@ -1,0 +1,208 @@
+"""Thin ctypes binding of the C ABI in include/fvdb_hotpath.h.
+
+Argument marshalling only: every step of the path runs inside the HIP library.  PyTorch is
+used for device memory and for the current stream.  There is no CPU fallback: if the built
+library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfvdb_hotpath.so")
+
+FX_OK = 0
+DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
+_TORCH_DT = {torch.float32: 0, torch.float16: 1, torch.bfloat16: 2}
+STATUS_NAMES = {0: "FX_OK", -1: "FX_EINVAL", -2: "FX_EUNSUPPORTED", -3: "FX_ENOMEM", -4: "FX_EDEVICE",
+                -5: "FX_ERANGE"}
+
+LEAF_DTYPE = np.dtype([("offset", "<i8"), ("prefix", "<u8"), ("mask", "<u8", (8,)),
+                       ("origin", "<i4", (3,)), ("batch", "<i4")])
+
+
+class FxError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2407_01781_amd.build` "
+            "(there is no fallback implementation)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    L.fx_version.restype = C.c_char_p
+    L.fx_last_error.restype = C.c_char_p
+    L.fx_init.restype = C.c_int
+    L.fx_build_index_grid.restype = C.c_int
+    L.fx_build_index_grid.argtypes = [vp, i64, vp, i32, vp, C.POINTER(vp)]
+    L.fx_grid_info.restype = C.c_int
+    L.fx_grid_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), vp, vp]
+    L.fx_grid_ijk.restype = C.c_int
+    L.fx_grid_ijk.argtypes = [vp, vp, vp, vp]
+    L.fx_grid_ijk_to_index.restype = C.c_int
+    L.fx_grid_ijk_to_index.argtypes = [vp, vp, vp, i64, vp, vp]
+    L.fx_grid_leaf_table.restype = C.c_int
+    L.fx_grid_leaf_table.argtypes = [vp, vp, C.c_size_t, vp]
+    L.fx_grid_coarsen2.restype = C.c_int
+    L.fx_grid_coarsen2.argtypes = [vp, vp, C.POINTER(vp)]
+    L.fx_grid_retain.argtypes = [vp]
+    L.fx_grid_destroy.argtypes = [vp]
+    L.fx_build_kernel_map.restype = C.c_int
+    L.fx_build_kernel_map.argtypes = [vp, i32, i32, vp, C.POINTER(vp), C.POINTER(vp)]
+    L.fx_kmap_info.restype = C.c_int
+    L.fx_kmap_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i64), vp]
+    L.fx_kmap_dense.restype = C.c_int
+    L.fx_kmap_dense.argtypes = [vp, vp, vp]
+    L.fx_kmap_tile_stats.restype = C.c_int
+    L.fx_kmap_tile_stats.argtypes = [vp, vp]
+    L.fx_kmap_destroy.argtypes = [vp]
+    L.fx_sparse_conv_fwd.restype = C.c_int
+    L.fx_sparse_conv_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
+    return L
+
+
+lib = _load()
+
+
+def _check(status: int):
+    if status != FX_OK:
+        raise FxError(status, lib.fx_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def version() -> str:
+    return lib.fx_version().decode()
+
+
+class IndexGrid:
+    """Handle on a GridBatch built by fx_build_index_grid (or a coarsened / output grid)."""
+
+    def __init__(self, handle: int):
+        self._h = C.c_void_p(handle)
+        n, b = C.c_int64(), C.c_int32()
+        _check(lib.fx_grid_info(self._h, C.byref(n), C.byref(b), None, None))
+        self.num_voxels, self.batch_size = int(n.value), int(b.value)
+
+    def __del__(self):
+        h = getattr(self, "_h", None)
+        if h is not None and h.value:
+            lib.fx_grid_destroy(h)
+            self._h = None
+
+    def counts(self) -> Tuple[int, int, int]:
+        c = np.zeros(3, dtype=np.int64)
+        _check(lib.fx_grid_info(self._h, None, None, None, c.ctypes.data_as(C.c_void_p)))
+        return int(c[0]), int(c[1]), int(c[2])
+
+    def voxel_joffsets(self) -> np.ndarray:
+        out = np.zeros((self.batch_size, 2), dtype=np.int64)
+        _check(lib.fx_grid_info(self._h, None, None, out.ctypes.data_as(C.c_void_p), None))
+        return out
+
+    def ijk(self) -> Tuple[torch.Tensor, torch.Tensor]:
+        out = torch.empty((self.num_voxels, 3), dtype=torch.int32, device="cuda")
+        jidx = torch.empty((self.num_voxels,), dtype=torch.int32, device="cuda")
+        _check(lib.fx_grid_ijk(self._h, _ptr(out), _ptr(jidx), _stream()))
+        return out, jidx
+
+    def ijk_to_index(self, ijk: torch.Tensor, jidx: Optional[torch.Tensor] = None) -> torch.Tensor:
+        assert ijk.is_cuda and ijk.dtype == torch.int32 and ijk.is_contiguous()
+        n = ijk.shape[0]
+        if jidx is not None:
+            assert jidx.is_cuda and jidx.dtype == torch.int32 and jidx.is_contiguous() and jidx.shape[0] == n
+        out = torch.empty((n,), dtype=torch.int32, device="cuda")
+        _check(lib.fx_grid_ijk_to_index(self._h, _ptr(ijk), _ptr(jidx), n, _ptr(out), _stream()))
+        return out
+
+    def leaf_table(self) -> np.ndarray:
+        n_leaf = self.counts()[0]
+        out = np.zeros(n_leaf, dtype=LEAF_DTYPE)
+        _check(lib.fx_grid_leaf_table(self._h, out.ctypes.data_as(C.c_void_p), out.nbytes, _stream()))
+        return out
+
+    def coarsen2(self) -> "IndexGrid":
+        h = C.c_void_p()
+        _check(lib.fx_grid_coarsen2(self._h, _stream(), C.byref(h)))
+        return IndexGrid(h.value)
+
+
+def build_index_grid(ijk: torch.Tensor, joffsets) -> IndexGrid:
+    """ijk: CUDA int32 [n_rows,3]; joffsets: host int64 [B,2]."""
+    assert ijk.is_cuda and ijk.dtype == torch.int32 and ijk.is_contiguous()
+    jo = np.ascontiguousarray(np.asarray(joffsets, dtype=np.int64).reshape(-1, 2))
+    h = C.c_void_p()
+    _check(lib.fx_build_index_grid(_ptr(ijk), ijk.shape[0], jo.ctypes.data_as(C.c_void_p), jo.shape[0],
+                                   _stream(), C.byref(h)))
+    return IndexGrid(h.value)
+
+
+class KernelMap:
+    def __init__(self, handle: int, g_in: IndexGrid, g_out: IndexGrid, kernel_size: int, stride: int):
+        self._h = C.c_void_p(handle)
+        self.g_in, self.g_out = g_in, g_out
+        self.kernel_size, self.stride = kernel_size, stride
+        self.k3 = kernel_size ** 3
+        self.n_out = g_out.num_voxels
+
+    def __del__(self):
+        h = getattr(self, "_h", None)
+        if h is not None and h.value:
+            lib.fx_kmap_destroy(h)
+            self._h = None
+
+    def info(self) -> Tuple[int, np.ndarray]:
+        """(number of active pairs, pairs per offset [K^3])."""
+        n_out, k3, n_pairs = C.c_int64(), C.c_int32(), C.c_int64()
+        per = np.zeros(self.k3, dtype=np.int64)
+        _check(lib.fx_kmap_info(self._h, C.byref(n_out), C.byref(k3), C.byref(n_pairs),
+                                per.ctypes.data_as(C.c_void_p)))
+        return int(n_pairs.value), per
+
+    def tile_stats(self) -> dict:
+        s = np.zeros(4, dtype=np.int64)
+        _check(lib.fx_kmap_tile_stats(self._h, s.ctypes.data_as(C.c_void_p)))
+        return {"mfma_rows_issued": int(s[0]), "n_tiles": int(s[1]), "staged_rows": int(s[2]), "tile": int(s[3])}
+
+    def dense(self) -> torch.Tensor:
+        out = torch.empty((self.n_out, self.k3), dtype=torch.int32, device="cuda")
+        _check(lib.fx_kmap_dense(self._h, _ptr(out), _stream()))
+        return out
+
+
+def build_kernel_map(g_in: IndexGrid, kernel_size: int, stride: int) -> KernelMap:
+    hg, hk = C.c_void_p(), C.c_void_p()
+    _check(lib.fx_build_kernel_map(g_in._h, kernel_size, stride, _stream(), C.byref(hg), C.byref(hk)))
+    g_out = IndexGrid(hg.value)
+    return KernelMap(hk.value, g_in, g_out, kernel_size, stride)
+
+
+def sparse_conv_fwd(kmap: KernelMap, feat: torch.Tensor, weights: torch.Tensor,
+                    out_dtype: Optional[torch.dtype] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """feat [N_in, C_in], weights [K^3, C_in, C_out] (same dtype, CUDA, contiguous)."""
+    assert feat.is_cuda and weights.is_cuda and feat.is_contiguous() and weights.is_contiguous()
+    assert feat.dtype == weights.dtype and feat.dtype in _TORCH_DT
+    k3, c_in, c_out = weights.shape
+    assert k3 == kmap.k3 and feat.shape == (kmap.g_in.num_voxels, c_in)
+    out_dtype = out_dtype or feat.dtype
+    if out is None:
+        out = torch.empty((kmap.n_out, c_out), dtype=out_dtype, device="cuda")
+    assert out.is_cuda and out.is_contiguous() and out.shape == (kmap.n_out, c_out) and out.dtype == out_dtype
+    _check(lib.fx_sparse_conv_fwd(kmap._h, _ptr(feat), _TORCH_DT[feat.dtype], _ptr(weights), c_in, c_out,
+                                  _ptr(out), _TORCH_DT[out_dtype], _stream()))
+    return out

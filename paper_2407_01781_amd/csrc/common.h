@@ -1,0 +1,102 @@
+// Shared host/device declarations of the fVDB hot-path library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <atomic>
+#include <string>
+
+#include "../../include/fvdb_hotpath.h"
+
+namespace fx {
+
+// ------------------------------------------------------------------ errors
+void set_error(const char* fmt, ...);
+
+#define FX_HIP_TRY(expr)                                                                   \
+    do {                                                                                   \
+        hipError_t _e = (expr);                                                            \
+        if (_e != hipSuccess) {                                                            \
+            fx::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e), __FILE__, \
+                          __LINE__);                                                       \
+            return FX_EDEVICE;                                                             \
+        }                                                                                  \
+    } while (0)
+
+#define FX_TRY(expr)                   \
+    do {                               \
+        fx_status _s = (expr);         \
+        if (_s != FX_OK) return _s;    \
+    } while (0)
+
+// ------------------------------------------------------------------ device memory
+fx_status dev_alloc(void** p, size_t bytes, hipStream_t s);
+void dev_free(void* p, hipStream_t s);
+
+// pinned host staging area owned by the library (per thread), at least `bytes` large
+fx_status host_staging(void** p, size_t bytes);
+
+// ------------------------------------------------------------------ tree layout
+// Node fan-outs of the VDB tree (Sec. 3.1): upper 32^3 children, lower 16^3, leaf 8^3 voxels.
+constexpr int kUpperWords = 32 * 32 * 32 / 64;  // 512 child-mask words per upper node
+constexpr int kLowerWords = 16 * 16 * 16 / 64;  // 64 child-mask words per lower node
+constexpr int kMaxTiles = 65536;                // root tiles per batch (documented limit)
+constexpr int kTileHashSlots = 1 << 17;
+
+// counts kept at the head of the grid buffer (device) and mirrored on the host
+struct GridHeader {
+    int32_t n_tiles_raw;  // distinct root tiles found (may exceed capacity)
+    int32_t n_upper;
+    int32_t n_lower;
+    int32_t n_leaf;
+    int32_t overflow;     // bit0: upper capacity, bit1: lower, bit2: leaf, bit3: tile limit
+    int32_t pad[3];
+    int64_t n_voxels;
+    int64_t pad2;
+};
+
+// Device view of one GridBatch.  Internal nodes keep only a child bitmask and, per mask
+// word, the global id of the first child in that word: child id = prefix[w] +
+// popcount(mask[w] & (bit-1)) -- the indexing of Listing 1 applied at every level.
+struct TreeView {
+    const uint64_t* root_key;      // [n_upper] biased tile key, sorted by (root_batch, root_key)
+    const int32_t*  root_batch;    // [n_upper]
+    const uint64_t* upper_mask;    // [n_upper][512]
+    const uint32_t* upper_prefix;  // [n_upper][512]
+    const uint64_t* lower_mask;    // [n_lower][64]
+    const uint32_t* lower_prefix;  // [n_lower][64]
+    const fx_leaf*  leaf;          // [n_leaf]
+    int32_t n_upper, n_lower, n_leaf, B;
+};
+
+}  // namespace fx
+
+struct fx_grid {
+    std::atomic<int> refs{1};
+    hipStream_t stream = nullptr;
+    void* buf = nullptr;          // the one flat device buffer
+    size_t buf_bytes = 0;
+    int32_t B = 0;
+    int32_t cap_upper = 0, cap_lower = 0, cap_leaf = 0;
+    fx::GridHeader hdr{};         // host mirror
+    int64_t* h_vox_base = nullptr;  // [B+1] host copy of per-grid first indices
+    // device section pointers inside buf
+    fx::GridHeader* d_hdr = nullptr;
+    int64_t* d_vox_base = nullptr;  // [B+1]
+    uint64_t* d_root_key = nullptr;
+    int32_t* d_root_batch = nullptr;
+    uint64_t* d_upper_mask = nullptr;
+    uint32_t* d_upper_prefix = nullptr;
+    uint64_t* d_lower_mask = nullptr;
+    uint32_t* d_lower_prefix = nullptr;
+    fx_leaf* d_leaf = nullptr;
+    fx::TreeView view() const {
+        fx::TreeView v;
+        v.root_key = d_root_key; v.root_batch = d_root_batch;
+        v.upper_mask = d_upper_mask; v.upper_prefix = d_upper_prefix;
+        v.lower_mask = d_lower_mask; v.lower_prefix = d_lower_prefix;
+        v.leaf = d_leaf;
+        v.n_upper = hdr.n_upper; v.n_lower = hdr.n_lower; v.n_leaf = hdr.n_leaf; v.B = B;
+        return v;
+    }
+};

@@ -1,0 +1,689 @@
+// Index-grid build on the GPU (Sec. 3.3) and the grid queries (Listing 1).
+//
+// The paper orders the voxels with two radix sorts (tile key a, then key b) and derives the
+// nodes from runs of equal key prefixes.  Here the tree does the ordering itself: every level
+// keeps a child bitmask, a voxel pass sets the bits of the nodes it touches (the paper's
+// "register ... into its parent" steps 11.1-11.4), and a popcount prefix scan over the masks
+// numbers the children in exactly the order the sorts would give (bit order of a mask =
+// Listing 2's offset order; node order = parent order).  Only the few root tiles are ranked
+// by comparison.  Four streaming passes over ijk replace the sorts.
+#include "common.h"
+#include "tree_device.h"
+
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+namespace fx {
+
+// ---------------------------------------------------------------------------------- helpers
+struct GridPtrs {
+    GridHeader* hdr;
+    int64_t* vox_base;
+    uint64_t* root_key;
+    int32_t* root_batch;
+    uint64_t* upper_mask;
+    uint32_t* upper_prefix;
+    uint64_t* lower_mask;
+    uint32_t* lower_prefix;
+    fx_leaf* leaf;
+    int32_t cap_upper, cap_lower, cap_leaf, B;
+};
+
+// grid that owns row r (joffsets sorted, non-overlapping), or -1
+__device__ __forceinline__ int find_batch(const int64_t* __restrict__ joff, int B, int64_t r) {
+    int lo = 0, hi = B;  // last b with start_b <= r
+    while (lo < hi) {
+        int mid = (lo + hi) >> 1;
+        if (joff[2 * mid] <= r) lo = mid + 1; else hi = mid;
+    }
+    int b = lo - 1;
+    if (b < 0 || r >= joff[2 * b + 1]) return -1;
+    return b;
+}
+
+__device__ __forceinline__ uint32_t mix32(uint32_t h, uint32_t v) {
+    h ^= v;
+    h *= 0x9E3779B1u;
+    h ^= h >> 15;
+    return h;
+}
+
+// ---------------------------------------------------------------------------------- pass 1: root tiles
+// Distinct (grid, tile) pairs are collected in a small open-addressing table whose slots hold a
+// representative input row (the key is read back through that row), so one 32-bit CAS suffices.
+__global__ void k_find_tiles(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff,
+                             int B, int32_t* __restrict__ slots, int32_t* __restrict__ rep_rows,
+                             GridHeader* hdr) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n_rows; r += stride) {
+        const int b = find_batch(joff, B, r);
+        if (b < 0) continue;
+        const int ti = ijk[3 * r] >> 12, tj = ijk[3 * r + 1] >> 12, tk = ijk[3 * r + 2] >> 12;
+        // lanes that share the first active lane's tile let that lane insert for them
+        const uint64_t active = __ballot(1);
+        const int leader = __ffsll((long long)active) - 1;
+        const int lb = __shfl(b, leader), li = __shfl(ti, leader), lj = __shfl(tj, leader),
+                  lk = __shfl(tk, leader);
+        const int lane = threadIdx.x & 63;
+        if (lane != leader && lb == b && li == ti && lj == tj && lk == tk) continue;
+        uint32_t h = mix32(mix32(mix32(mix32(0x811C9DC5u, (uint32_t)b), (uint32_t)ti), (uint32_t)tj), (uint32_t)tk);
+        h &= (kTileHashSlots - 1);
+        for (int probe = 0; probe < kTileHashSlots; ++probe) {
+            int32_t s = slots[h];
+            if (s < 0) {
+                if (hdr->n_tiles_raw > kMaxTiles) break;  // over the limit: reported by the ranking kernel
+                const int32_t old = atomicCAS(&slots[h], -1, (int32_t)r);
+                if (old < 0) {
+                    const int pos = atomicAdd(&hdr->n_tiles_raw, 1);
+                    if (pos < kMaxTiles) rep_rows[pos] = (int32_t)r;
+                    break;
+                }
+                s = old;
+            }
+            const int sb = find_batch(joff, B, s);
+            if (sb == b && (ijk[3 * (int64_t)s] >> 12) == ti && (ijk[3 * (int64_t)s + 1] >> 12) == tj &&
+                (ijk[3 * (int64_t)s + 2] >> 12) == tk)
+                break;
+            h = (h + 1) & (kTileHashSlots - 1);
+        }
+    }
+}
+
+// Rank every tile among all tiles by (grid, signed tile i, j, k): its rank is its upper-node id
+// (the run index M of Sec. 3.3 step 5).  O(T^2) comparisons; T is tiny for real scenes.
+__global__ void k_rank_tiles(const int32_t* __restrict__ ijk, const int64_t* __restrict__ joff, int B,
+                             const int32_t* __restrict__ rep_rows, GridPtrs g) {
+    const int raw = g.hdr->n_tiles_raw;
+    const int T = raw < kMaxTiles ? raw : kMaxTiles;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t == 0) {
+        int ov = 0;
+        if (raw > kMaxTiles) ov |= 8;
+        if (T > g.cap_upper) ov |= 1;
+        g.hdr->n_upper = T;
+        if (ov) g.hdr->overflow = ov;
+    }
+    if (t >= T || T > g.cap_upper) return;
+    const int64_t r = rep_rows[t];
+    const int b = find_batch(joff, B, r);
+    const uint64_t key = tile_key(ijk[3 * r], ijk[3 * r + 1], ijk[3 * r + 2]);
+    int rank = 0;
+    for (int o = 0; o < T; ++o) {
+        const int64_t ro = rep_rows[o];
+        const int bo = find_batch(joff, B, ro);
+        const uint64_t ko = tile_key(ijk[3 * ro], ijk[3 * ro + 1], ijk[3 * ro + 2]);
+        rank += (bo < b) || (bo == b && ko < key);
+    }
+    g.root_key[rank] = key;
+    g.root_batch[rank] = b;
+}
+
+// ---------------------------------------------------------------------------------- passes 2-4: set bits
+// LEVEL 0: lower-node bit in the upper node's child mask   (step 11.2)
+// LEVEL 1: leaf bit in the lower node's child mask         (step 11.3)
+// LEVEL 2: voxel bit in the leaf's mBitMask                (step 11.4)
+template <int LEVEL>
+__global__ void k_insert(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff,
+                         GridPtrs g) {
+    if (g.hdr->overflow) return;
+    const int n_upper = g.hdr->n_upper;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n_rows; r += stride) {
+        const int b = find_batch(joff, g.B, r);
+        if (b < 0) continue;
+        const int i = ijk[3 * r], j = ijk[3 * r + 1], k = ijk[3 * r + 2];
+        const int u = find_upper(g.root_key, g.root_batch, n_upper, b, tile_key(i, j, k));
+        if (u < 0) continue;
+        uint64_t* word;
+        uint64_t bit;
+        int f = -1;
+        if (LEVEL == 0) {
+            const int off = upper_off(i, j, k);
+            word = g.upper_mask + (size_t)u * kUpperWords + (off >> 6);
+            bit = 1ull << (off & 63);
+        } else {
+            const int l = child_of(g.upper_mask + (size_t)u * kUpperWords,
+                                   g.upper_prefix + (size_t)u * kUpperWords, upper_off(i, j, k));
+            if (l < 0) continue;
+            if (LEVEL == 1) {
+                const int off = lower_off(i, j, k);
+                word = g.lower_mask + (size_t)l * kLowerWords + (off >> 6);
+                bit = 1ull << (off & 63);
+            } else {
+                f = child_of(g.lower_mask + (size_t)l * kLowerWords, g.lower_prefix + (size_t)l * kLowerWords,
+                             lower_off(i, j, k));
+                if (f < 0) continue;
+                word = &g.leaf[f].mask[i & 7];
+                bit = 1ull << (((j & 7) << 3) | (k & 7));
+            }
+        }
+        if (*word & bit) continue;  // already registered (stale reads only cost a redundant atomic)
+        const uint64_t old = atomicOr((unsigned long long*)word, (unsigned long long)bit);
+        if (LEVEL == 2 && old == 0) {
+            // first voxel of this mask word: record where the leaf sits (all writers agree)
+            fx_leaf* lf = &g.leaf[f];
+            lf->origin[0] = (i >> 3) * 8;
+            lf->origin[1] = (j >> 3) * 8;
+            lf->origin[2] = (k >> 3) * 8;
+            lf->batch = b;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------- popcount scans
+constexpr int kScanThreads = 1024;
+constexpr int kWordsPerThread = 8;
+constexpr int kWordChunk = kScanThreads * kWordsPerThread;  // mask words per block
+constexpr int kLeavesPerThread = 2;
+constexpr int kLeafChunk = kScanThreads * kLeavesPerThread;
+
+// exclusive scan of one value per thread over a 1024-thread block; returns the block total
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* total) {
+    __shared__ uint32_t wave_sums[kScanThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t o = __shfl_up(incl, d);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) wave_sums[wave] = incl;
+    __syncthreads();
+    if (wave == 0) {
+        uint32_t s = lane < kScanThreads / 64 ? wave_sums[lane] : 0;
+#pragma unroll
+        for (int d = 1; d < kScanThreads / 64; d <<= 1) {
+            uint32_t o = __shfl_up(s, d);
+            if (lane >= d) s += o;
+        }
+        if (lane < kScanThreads / 64) wave_sums[lane] = s;  // inclusive over waves
+    }
+    __syncthreads();
+    const uint32_t wave_base = wave ? wave_sums[wave - 1] : 0;
+    *total = wave_sums[kScanThreads / 64 - 1];
+    __syncthreads();
+    return wave_base + incl - v;
+}
+
+// which level's masks a scan runs over
+struct LevelScan {
+    const uint64_t* words;
+    uint32_t* prefix;
+    const int32_t* n_nodes;   // device count of nodes at this level
+    int words_per_node;
+    int32_t* n_children;      // device count to write (next level)
+    int32_t child_cap;
+    int32_t overflow_bit;
+};
+
+// phase A: block-local exclusive popcount prefix per word, block totals
+__global__ void __launch_bounds__(kScanThreads) k_scan_words_local(LevelScan s, GridHeader* hdr,
+                                                                    uint32_t* __restrict__ block_sums,
+                                                                    int single) {
+    if (hdr->overflow) return;
+    const int64_t n_words = (int64_t)(*s.n_nodes) * s.words_per_node;
+    const int64_t base = (int64_t)blockIdx.x * kWordChunk;
+    if (base >= n_words && !(single && blockIdx.x == 0)) return;
+    const int64_t w0 = base + (int64_t)threadIdx.x * kWordsPerThread;
+    uint32_t pc[kWordsPerThread];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int q = 0; q < kWordsPerThread; ++q) {
+        pc[q] = (w0 + q < n_words) ? (uint32_t)__popcll(s.words[w0 + q]) : 0u;
+        sum += pc[q];
+    }
+    uint32_t total;
+    uint32_t run = block_exclusive_scan(sum, &total);
+#pragma unroll
+    for (int q = 0; q < kWordsPerThread; ++q) {
+        if (w0 + q < n_words) s.prefix[w0 + q] = run;
+        run += pc[q];
+    }
+    if (threadIdx.x == 0) {
+        if (single) {
+            *s.n_children = (int32_t)total;
+            if ((int64_t)total > s.child_cap) atomicOr(&hdr->overflow, s.overflow_bit);
+        } else {
+            block_sums[blockIdx.x] = total;
+        }
+    }
+}
+
+// phase B: one block turns the block totals into block bases (in place) and publishes the total
+__global__ void __launch_bounds__(kScanThreads) k_scan_block_sums(const int32_t* n_nodes, int items_per_node,
+                                                                   int chunk, uint32_t* __restrict__ block_sums,
+                                                                   GridHeader* hdr, int32_t* n_children,
+                                                                   int64_t* n_children64, int64_t child_cap,
+                                                                   int32_t overflow_bit) {
+    if (hdr->overflow) return;
+    const int64_t n_items = (int64_t)(*n_nodes) * items_per_node;
+    const int n_blocks = (int)((n_items + chunk - 1) / chunk);
+    uint32_t carry = 0;
+    for (int base = 0; base < n_blocks; base += kScanThreads) {
+        const int idx = base + threadIdx.x;
+        const uint32_t v = idx < n_blocks ? block_sums[idx] : 0u;
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan(v, &total);
+        if (idx < n_blocks) block_sums[idx] = carry + ex;
+        carry += total;
+    }
+    if (threadIdx.x == 0) {
+        if (n_children) *n_children = (int32_t)carry;
+        if (n_children64) *n_children64 = (int64_t)carry;
+        if ((int64_t)carry > child_cap) atomicOr(&hdr->overflow, overflow_bit);
+    }
+}
+
+// phase C: add the block bases
+__global__ void __launch_bounds__(kScanThreads) k_scan_words_apply(LevelScan s, GridHeader* hdr,
+                                                                    const uint32_t* __restrict__ block_sums) {
+    if (hdr->overflow) return;
+    const int64_t n_words = (int64_t)(*s.n_nodes) * s.words_per_node;
+    const int64_t base = (int64_t)blockIdx.x * kWordChunk;
+    if (base >= n_words || blockIdx.x == 0) return;
+    const uint32_t add = block_sums[blockIdx.x];
+    const int64_t w0 = base + (int64_t)threadIdx.x * kWordsPerThread;
+#pragma unroll
+    for (int q = 0; q < kWordsPerThread; ++q)
+        if (w0 + q < n_words) s.prefix[w0 + q] += add;
+}
+
+// Leaf level: mOffset = exclusive scan of the leaves' active-voxel counts; mPrefixSum = the
+// seven 9-bit inclusive word prefixes of Listing 1.
+__global__ void __launch_bounds__(kScanThreads) k_scan_leaves_local(fx_leaf* __restrict__ leaf, GridHeader* hdr,
+                                                                     uint32_t* __restrict__ block_sums, int single) {
+    if (hdr->overflow) return;
+    const int64_t n_leaf = hdr->n_leaf;
+    const int64_t base = (int64_t)blockIdx.x * kLeafChunk;
+    if (base >= n_leaf && !(single && blockIdx.x == 0)) return;
+    const int64_t l0 = base + (int64_t)threadIdx.x * kLeavesPerThread;
+    uint32_t cnt[kLeavesPerThread];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int q = 0; q < kLeavesPerThread; ++q) {
+        cnt[q] = 0;
+        if (l0 + q < n_leaf) {
+            uint64_t pre = 0;
+            uint32_t acc = 0;
+#pragma unroll
+            for (int w = 0; w < 8; ++w) {
+                acc += (uint32_t)__popcll(leaf[l0 + q].mask[w]);
+                if (w < 7) pre |= (uint64_t)acc << (9 * w);
+            }
+            leaf[l0 + q].prefix = pre;
+            cnt[q] = acc;
+        }
+        sum += cnt[q];
+    }
+    uint32_t total;
+    uint32_t run = block_exclusive_scan(sum, &total);
+#pragma unroll
+    for (int q = 0; q < kLeavesPerThread; ++q) {
+        if (l0 + q < n_leaf) leaf[l0 + q].offset = (int64_t)run;
+        run += cnt[q];
+    }
+    if (threadIdx.x == 0) {
+        if (single) hdr->n_voxels = (int64_t)total;
+        else block_sums[blockIdx.x] = total;
+    }
+}
+
+__global__ void __launch_bounds__(kScanThreads) k_scan_leaves_apply(fx_leaf* __restrict__ leaf, GridHeader* hdr,
+                                                                     const uint32_t* __restrict__ block_sums) {
+    if (hdr->overflow) return;
+    const int64_t n_leaf = hdr->n_leaf;
+    const int64_t base = (int64_t)blockIdx.x * kLeafChunk;
+    if (base >= n_leaf || blockIdx.x == 0) return;
+    const int64_t add = block_sums[blockIdx.x];
+    const int64_t l0 = base + (int64_t)threadIdx.x * kLeavesPerThread;
+#pragma unroll
+    for (int q = 0; q < kLeavesPerThread; ++q)
+        if (l0 + q < n_leaf) leaf[l0 + q].offset += add;
+}
+
+// first voxel index of every grid of the batch (leaves are ordered by grid)
+__global__ void k_vox_base(GridPtrs g) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b > g.B) return;
+    if (g.hdr->overflow) { g.vox_base[b] = 0; return; }
+    const int n_leaf = g.hdr->n_leaf;
+    int lo = 0, hi = n_leaf;  // first leaf with batch >= b
+    while (lo < hi) {
+        int mid = (lo + hi) >> 1;
+        if (g.leaf[mid].batch < b) lo = mid + 1; else hi = mid;
+    }
+    g.vox_base[b] = lo < n_leaf ? g.leaf[lo].offset : g.hdr->n_voxels;
+}
+
+// ---------------------------------------------------------------------------------- queries
+// one wave per leaf: lane = bit of the current mask word (ballot-free: every lane tests its bit)
+__global__ void k_grid_ijk(TreeView t, int32_t* __restrict__ ijk_out, int32_t* __restrict__ jidx_out, int shift) {
+    const int f = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    if (f >= t.n_leaf) return;
+    const int lane = threadIdx.x & 63;
+    const fx_leaf* lf = t.leaf + f;
+    const uint64_t lt = (1ull << lane) - 1;
+    int64_t run = lf->offset;
+    for (int w = 0; w < 8; ++w) {
+        const uint64_t m = lf->mask[w];
+        if ((m >> lane) & 1) {
+            const int64_t o = run + __popcll(m & lt);
+            ijk_out[3 * o + 0] = (lf->origin[0] + w) >> shift;
+            ijk_out[3 * o + 1] = (lf->origin[1] + (lane >> 3)) >> shift;
+            ijk_out[3 * o + 2] = (lf->origin[2] + (lane & 7)) >> shift;
+            if (jidx_out) jidx_out[o] = lf->batch;
+        }
+        run += __popcll(m);
+    }
+}
+
+__global__ void k_ijk_to_index(TreeView t, const int32_t* __restrict__ ijk, const int32_t* __restrict__ jidx,
+                               int64_t n, int32_t* __restrict__ out) {
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n) return;
+    const int b = jidx ? jidx[r] : 0;
+    int v = -1;
+    if (b >= 0 && b < t.B) v = get_value(t, b, ijk[3 * r], ijk[3 * r + 1], ijk[3 * r + 2]);
+    out[r] = v;
+}
+
+// ---------------------------------------------------------------------------------- host side
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static void layout(fx_grid* g) {
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const size_t o_hdr = take(sizeof(GridHeader));
+    const size_t o_vox = take(sizeof(int64_t) * ((size_t)g->B + 1));
+    const size_t o_rk = take(sizeof(uint64_t) * g->cap_upper);
+    const size_t o_rb = take(sizeof(int32_t) * g->cap_upper);
+    const size_t o_um = take(sizeof(uint64_t) * kUpperWords * (size_t)g->cap_upper);
+    const size_t o_up = take(sizeof(uint32_t) * kUpperWords * (size_t)g->cap_upper);
+    const size_t o_lm = take(sizeof(uint64_t) * kLowerWords * (size_t)g->cap_lower);
+    const size_t o_lp = take(sizeof(uint32_t) * kLowerWords * (size_t)g->cap_lower);
+    const size_t o_lf = take(sizeof(fx_leaf) * (size_t)g->cap_leaf);
+    g->buf_bytes = off;
+    char* p = (char*)g->buf;
+    if (!p) return;
+    g->d_hdr = (GridHeader*)(p + o_hdr);
+    g->d_vox_base = (int64_t*)(p + o_vox);
+    g->d_root_key = (uint64_t*)(p + o_rk);
+    g->d_root_batch = (int32_t*)(p + o_rb);
+    g->d_upper_mask = (uint64_t*)(p + o_um);
+    g->d_upper_prefix = (uint32_t*)(p + o_up);
+    g->d_lower_mask = (uint64_t*)(p + o_lm);
+    g->d_lower_prefix = (uint32_t*)(p + o_lp);
+    g->d_leaf = (fx_leaf*)(p + o_lf);
+}
+
+static GridPtrs ptrs_of(const fx_grid* g) {
+    GridPtrs q;
+    q.hdr = g->d_hdr; q.vox_base = g->d_vox_base; q.root_key = g->d_root_key; q.root_batch = g->d_root_batch;
+    q.upper_mask = g->d_upper_mask; q.upper_prefix = g->d_upper_prefix;
+    q.lower_mask = g->d_lower_mask; q.lower_prefix = g->d_lower_prefix; q.leaf = g->d_leaf;
+    q.cap_upper = g->cap_upper; q.cap_lower = g->cap_lower; q.cap_leaf = g->cap_leaf; q.B = g->B;
+    return q;
+}
+
+static int blocks_for_rows(int64_t n_rows) {
+    // 8 rows per thread, 256 threads per block, at most 8 blocks per CU of a 256-CU part
+    int64_t b = (n_rows + 256 * 8 - 1) / (256 * 8);
+    return (int)std::max<int64_t>(1, std::min<int64_t>(b, 2048));
+}
+
+static fx_status scan_level(const fx_grid* g, LevelScan s, int cap_nodes, uint32_t* d_block_sums, hipStream_t st) {
+    const int64_t cap_words = (int64_t)cap_nodes * s.words_per_node;
+    const int n_blocks = (int)std::max<int64_t>(1, (cap_words + kWordChunk - 1) / kWordChunk);
+    if (n_blocks == 1) {
+        k_scan_words_local<<<1, kScanThreads, 0, st>>>(s, g->d_hdr, d_block_sums, 1);
+    } else {
+        k_scan_words_local<<<n_blocks, kScanThreads, 0, st>>>(s, g->d_hdr, d_block_sums, 0);
+        k_scan_block_sums<<<1, kScanThreads, 0, st>>>(s.n_nodes, s.words_per_node, kWordChunk, d_block_sums,
+                                                      g->d_hdr, s.n_children, nullptr, s.child_cap, s.overflow_bit);
+        k_scan_words_apply<<<n_blocks, kScanThreads, 0, st>>>(s, g->d_hdr, d_block_sums);
+    }
+    FX_HIP_TRY(hipGetLastError());
+    return FX_OK;
+}
+
+// One attempt with the given node capacities.  On FX_OK, (*out)->hdr.overflow tells whether a
+// capacity was too small (the counts found so far are valid up to the overflowing level).
+static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64_t* d_joff, int32_t B,
+                               int cap_upper, int cap_lower, int cap_leaf, hipStream_t st, fx_grid** out) {
+    fx_grid* g = new (std::nothrow) fx_grid();
+    if (!g) { set_error("host allocation failed"); return FX_ENOMEM; }
+    g->B = B; g->stream = st;
+    g->cap_upper = std::max(cap_upper, 1); g->cap_lower = std::max(cap_lower, 1); g->cap_leaf = std::max(cap_leaf, 1);
+    layout(g);
+    fx_status rc = dev_alloc(&g->buf, g->buf_bytes, st);
+    if (rc != FX_OK) { delete g; return rc; }
+    layout(g);
+    g->h_vox_base = (int64_t*)calloc((size_t)B + 1, sizeof(int64_t));
+
+    // scratch: tile table, representative rows, scan block sums
+    const int64_t max_items = std::max<int64_t>((int64_t)g->cap_lower * kLowerWords / kWordChunk,
+                                                std::max<int64_t>((int64_t)g->cap_upper * kUpperWords / kWordChunk,
+                                                                  (int64_t)g->cap_leaf / kLeafChunk)) + 2;
+    const size_t scratch_bytes = sizeof(int32_t) * kTileHashSlots + sizeof(int32_t) * kMaxTiles +
+                                 sizeof(uint32_t) * (size_t)max_items;
+    void* scratch = nullptr;
+    rc = dev_alloc(&scratch, scratch_bytes, st);
+    if (rc != FX_OK) { fx_grid_destroy(g); return rc; }
+    int32_t* d_slots = (int32_t*)scratch;
+    int32_t* d_rep = d_slots + kTileHashSlots;
+    uint32_t* d_block_sums = (uint32_t*)(d_rep + kMaxTiles);
+
+    auto fail = [&](fx_status s) { dev_free(scratch, st); fx_grid_destroy(g); return s; };
+#define FX_TRY_OR_FAIL(expr) do { hipError_t _e = (expr); if (_e != hipSuccess) { \
+        set_error("%s failed: %s", #expr, hipGetErrorString(_e)); return fail(FX_EDEVICE); } } while (0)
+
+    FX_TRY_OR_FAIL(hipMemsetAsync(g->buf, 0, g->buf_bytes, st));
+    FX_TRY_OR_FAIL(hipMemsetAsync(d_slots, 0xFF, sizeof(int32_t) * kTileHashSlots, st));
+    const GridPtrs q = ptrs_of(g);
+    if (n_rows > 0 && B > 0) {
+        const int nb = blocks_for_rows(n_rows);
+        k_find_tiles<<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, B, d_slots, d_rep, g->d_hdr);
+        k_rank_tiles<<<kMaxTiles / 256, 256, 0, st>>>(d_ijk, d_joff, B, d_rep, q);
+        k_insert<0><<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, q);
+        LevelScan su{g->d_upper_mask, g->d_upper_prefix, &g->d_hdr->n_upper, kUpperWords, &g->d_hdr->n_lower,
+                     g->cap_lower, 2};
+        if (scan_level(g, su, g->cap_upper, d_block_sums, st) != FX_OK) return fail(FX_EDEVICE);
+        k_insert<1><<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, q);
+        LevelScan sl{g->d_lower_mask, g->d_lower_prefix, &g->d_hdr->n_lower, kLowerWords, &g->d_hdr->n_leaf,
+                     g->cap_leaf, 4};
+        if (scan_level(g, sl, g->cap_lower, d_block_sums, st) != FX_OK) return fail(FX_EDEVICE);
+        k_insert<2><<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, q);
+        const int lb = std::max(1, (g->cap_leaf + kLeafChunk - 1) / kLeafChunk);
+        if (lb == 1) {
+            k_scan_leaves_local<<<1, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums, 1);
+        } else {
+            k_scan_leaves_local<<<lb, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums, 0);
+            k_scan_block_sums<<<1, kScanThreads, 0, st>>>(&g->d_hdr->n_leaf, 1, kLeafChunk, d_block_sums, g->d_hdr,
+                                                          nullptr, &g->d_hdr->n_voxels, INT32_MAX, 16);
+            k_scan_leaves_apply<<<lb, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums);
+        }
+        k_vox_base<<<(B + 1 + 255) / 256, 256, 0, st>>>(q);
+        FX_TRY_OR_FAIL(hipGetLastError());
+    }
+    // one read-back: counts + per-grid ranges (Sec. 3.3 step 10)
+    const size_t hdr_bytes = sizeof(GridHeader);
+    const size_t vb_bytes = sizeof(int64_t) * ((size_t)B + 1);
+    void* stage = nullptr;
+    rc = host_staging(&stage, hdr_bytes + vb_bytes);
+    if (rc != FX_OK) return fail(rc);
+    FX_TRY_OR_FAIL(hipMemcpyAsync(stage, g->d_hdr, hdr_bytes, hipMemcpyDeviceToHost, st));
+    FX_TRY_OR_FAIL(hipMemcpyAsync((char*)stage + hdr_bytes, g->d_vox_base, vb_bytes, hipMemcpyDeviceToHost, st));
+    FX_TRY_OR_FAIL(hipStreamSynchronize(st));
+    memcpy(&g->hdr, stage, hdr_bytes);
+    memcpy(g->h_vox_base, (char*)stage + hdr_bytes, vb_bytes);
+    dev_free(scratch, st);
+#undef FX_TRY_OR_FAIL
+    *out = g;
+    return FX_OK;
+}
+
+fx_status build_index_grid_device_joff(const int32_t* d_ijk, int64_t n_rows, const int64_t* d_joff, int32_t B,
+                                       hipStream_t st, fx_grid** out) {
+    // First attempt with capacities that fit typical occupancy; an attempt that overflows has
+    // still counted the nodes of the overflowing level exactly, so it is repeated with those.
+    int cap_upper = B + 8;
+    int cap_lower = (int)std::min<int64_t>(std::max<int64_t>(n_rows, 1), 64 * (int64_t)std::max(B, 1) + n_rows / 256);
+    int cap_leaf = (int)std::min<int64_t>(std::max<int64_t>(n_rows, 1), 1024 + n_rows / 8);
+    for (int attempt = 0; attempt < 4; ++attempt) {
+        fx_grid* g = nullptr;
+        FX_TRY(build_attempt(d_ijk, n_rows, d_joff, B, cap_upper, cap_lower, cap_leaf, st, &g));
+        const int ov = g->hdr.overflow;
+        if (!ov) { *out = g; return FX_OK; }
+        if (ov & 8) {
+            fx_grid_destroy(g);
+            set_error("more than %d root tiles (4096^3 regions) in the batch", kMaxTiles);
+            return FX_ERANGE;
+        }
+        if (ov & 16) {
+            fx_grid_destroy(g);
+            set_error("more than 2^31-1 active voxels");
+            return FX_ERANGE;
+        }
+        if (ov & 1) cap_upper = g->hdr.n_upper;
+        if (ov & 2) { cap_upper = g->hdr.n_upper; cap_lower = g->hdr.n_lower; }
+        if (ov & 4) { cap_upper = g->hdr.n_upper; cap_lower = g->hdr.n_lower; cap_leaf = g->hdr.n_leaf; }
+        fx_grid_destroy(g);
+    }
+    set_error("grid build did not converge");
+    return FX_EDEVICE;
+}
+
+}  // namespace fx
+
+// ====================================================================================== C ABI
+using namespace fx;
+
+extern "C" fx_status fx_build_index_grid(const int32_t* d_ijk, int64_t n_rows, const int64_t* h_joffsets,
+                                         int32_t B, void* stream, fx_grid** out) {
+    if (!out || B < 0 || n_rows < 0 || (B > 0 && !h_joffsets) || (n_rows > 0 && !d_ijk)) {
+        set_error("fx_build_index_grid: null pointer or negative size");
+        return FX_EINVAL;
+    }
+    if (n_rows > (int64_t)INT32_MAX) { set_error("more than 2^31-1 input rows"); return FX_ERANGE; }
+    int64_t prev_end = 0;
+    for (int32_t b = 0; b < B; ++b) {
+        const int64_t s = h_joffsets[2 * b], e = h_joffsets[2 * b + 1];
+        if (s < prev_end || e < s || e > n_rows) {
+            set_error("joffsets[%d] = (%lld, %lld) is out of range, overlapping or out of order", b, (long long)s,
+                      (long long)e);
+            return FX_EINVAL;
+        }
+        prev_end = e;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    int64_t* d_joff = nullptr;
+    const size_t jb = sizeof(int64_t) * 2 * (size_t)std::max(B, 1);
+    FX_TRY(dev_alloc((void**)&d_joff, jb, st));
+    if (B > 0) {
+        void* stage = nullptr;
+        fx_status rc = host_staging(&stage, jb);
+        if (rc != FX_OK) { dev_free(d_joff, st); return rc; }
+        memcpy(stage, h_joffsets, sizeof(int64_t) * 2 * (size_t)B);
+        hipError_t e = hipMemcpyAsync(d_joff, stage, sizeof(int64_t) * 2 * (size_t)B, hipMemcpyHostToDevice, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);  // the staging area is reused below
+        if (e != hipSuccess) { dev_free(d_joff, st); set_error("joffsets upload failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
+    }
+    fx_grid* g = nullptr;
+    fx_status rc = build_index_grid_device_joff(d_ijk, n_rows, d_joff, B, st, &g);
+    dev_free(d_joff, st);
+    if (rc != FX_OK) return rc;
+    *out = g;
+    return FX_OK;
+}
+
+extern "C" fx_status fx_grid_info(const fx_grid* g, int64_t* n_voxels, int32_t* B, int64_t* h_voxel_joffsets,
+                                  int64_t* h_counts3) {
+    if (!g) { set_error("fx_grid_info: null grid"); return FX_EINVAL; }
+    if (n_voxels) *n_voxels = g->hdr.n_voxels;
+    if (B) *B = g->B;
+    if (h_voxel_joffsets)
+        for (int b = 0; b < g->B; ++b) {
+            h_voxel_joffsets[2 * b] = g->h_vox_base[b];
+            h_voxel_joffsets[2 * b + 1] = g->h_vox_base[b + 1];
+        }
+    if (h_counts3) { h_counts3[0] = g->hdr.n_leaf; h_counts3[1] = g->hdr.n_lower; h_counts3[2] = g->hdr.n_upper; }
+    return FX_OK;
+}
+
+extern "C" fx_status fx_grid_ijk(const fx_grid* g, int32_t* d_ijk_out, int32_t* d_jidx_out, void* stream) {
+    if (!g || (!d_ijk_out && g->hdr.n_voxels > 0)) { set_error("fx_grid_ijk: null pointer"); return FX_EINVAL; }
+    if (g->hdr.n_leaf == 0) return FX_OK;
+    const int64_t threads = (int64_t)g->hdr.n_leaf * 64;
+    k_grid_ijk<<<(unsigned)((threads + 255) / 256), 256, 0, (hipStream_t)stream>>>(g->view(), d_ijk_out, d_jidx_out, 0);
+    FX_HIP_TRY(hipGetLastError());
+    return FX_OK;
+}
+
+extern "C" fx_status fx_grid_ijk_to_index(const fx_grid* g, const int32_t* d_ijk, const int32_t* d_jidx, int64_t n,
+                                          int32_t* d_index_out, void* stream) {
+    if (!g || n < 0 || (n > 0 && (!d_ijk || !d_index_out))) {
+        set_error("fx_grid_ijk_to_index: null pointer or negative size");
+        return FX_EINVAL;
+    }
+    if (n == 0) return FX_OK;
+    k_ijk_to_index<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>(g->view(), d_ijk, d_jidx, n,
+                                                                                  d_index_out);
+    FX_HIP_TRY(hipGetLastError());
+    return FX_OK;
+}
+
+extern "C" fx_status fx_grid_leaf_table(const fx_grid* g, fx_leaf* h_out, size_t bytes, void* stream) {
+    if (!g) { set_error("fx_grid_leaf_table: null grid"); return FX_EINVAL; }
+    const size_t need = sizeof(fx_leaf) * (size_t)g->hdr.n_leaf;
+    if (bytes < need || (need && !h_out)) { set_error("fx_grid_leaf_table: buffer too small"); return FX_EINVAL; }
+    if (!need) return FX_OK;
+    FX_HIP_TRY(hipMemcpyAsync(h_out, g->d_leaf, need, hipMemcpyDeviceToHost, (hipStream_t)stream));
+    FX_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    return FX_OK;
+}
+
+extern "C" fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** out) {
+    if (!g || !out) { set_error("fx_grid_coarsen2: null pointer"); return FX_EINVAL; }
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t n = g->hdr.n_voxels;
+    int32_t* d_c = nullptr;
+    int64_t* d_joff = nullptr;
+    FX_TRY(dev_alloc((void**)&d_c, sizeof(int32_t) * 3 * (size_t)std::max<int64_t>(n, 1), st));
+    fx_status rc = dev_alloc((void**)&d_joff, sizeof(int64_t) * 2 * (size_t)std::max(g->B, 1), st);
+    if (rc != FX_OK) { dev_free(d_c, st); return rc; }
+    auto cleanup = [&]() { dev_free(d_c, st); dev_free(d_joff, st); };
+    if (g->hdr.n_leaf > 0) {
+        const int64_t threads = (int64_t)g->hdr.n_leaf * 64;
+        k_grid_ijk<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(g->view(), d_c, nullptr, 1);
+    }
+    if (g->B > 0) {
+        void* stage = nullptr;
+        rc = host_staging(&stage, sizeof(int64_t) * 2 * (size_t)g->B);
+        if (rc != FX_OK) { cleanup(); return rc; }
+        int64_t* hj = (int64_t*)stage;
+        for (int b = 0; b < g->B; ++b) { hj[2 * b] = g->h_vox_base[b]; hj[2 * b + 1] = g->h_vox_base[b + 1]; }
+        hipError_t e = hipMemcpyAsync(d_joff, stage, sizeof(int64_t) * 2 * (size_t)g->B, hipMemcpyHostToDevice, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) { cleanup(); set_error("joffsets upload failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
+    }
+    fx_grid* o = nullptr;
+    rc = build_index_grid_device_joff(d_c, n, d_joff, g->B, st, &o);
+    cleanup();
+    if (rc != FX_OK) return rc;
+    *out = o;
+    return FX_OK;
+}
+
+extern "C" void fx_grid_retain(fx_grid* g) {
+    if (g) g->refs.fetch_add(1);
+}
+
+extern "C" void fx_grid_destroy(fx_grid* g) {
+    if (!g) return;
+    if (g->refs.fetch_sub(1) != 1) return;
+    if (g->buf) dev_free(g->buf, g->stream);
+    free(g->h_vox_base);
+    delete g;
+}

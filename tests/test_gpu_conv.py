@@ -1,0 +1,108 @@
+"""GPU parity: sparse convolution forward against the oracle, within the stated tolerances."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_common as H
+import paper_2407_01781_amd as fx
+from oracle import cpu_oracle as O
+from workloads import generators as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(w: G.Workload, out_f32=False, c_in=None, c_out=None, dtype=None, dup=0.01):
+    c_in, c_out, dtype = c_in or w.c_in, c_out or w.c_out, dtype or w.dtype
+    ijk, jo = w.jagged_ijk(dup_fraction=dup)
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, w.kernel_size, w.stride)
+    ogo = O.output_grid(og, w.kernel_size, w.stride)
+    feat, wt = G.features_and_weights(w.feat_seed, og.num_voxels, c_in, c_out, w.k3, dtype)
+    y = fx.sparse_conv_fwd(km, H.to_device_storage(feat, dtype), H.to_device_storage(wt, dtype),
+                           out_dtype=torch.float32 if out_f32 else None)
+    ref = O.conv(og, ogo, w.kernel_size, w.stride, feat, wt)
+    return y.float().cpu().numpy(), ref, dtype, w.k3, c_in
+
+
+def test_config1_sphere_fp32():
+    y, ref, dt, k3, c_in = _run(G.workload("sphere64"))
+    H.conv_tolerance_check(y, ref, dt, k3, c_in)
+
+
+@pytest.mark.parametrize("name", ["indoor_small", "lidar_small", "lidar_small_down"])
+@pytest.mark.parametrize("out_f32", [False, True])
+def test_mfma_path_small_workloads(name, out_f32):
+    y, ref, dt, k3, c_in = _run(G.workload(name), out_f32=out_f32)
+    H.conv_tolerance_check(y, ref, dt, k3, c_in)
+
+
+def test_mfma_path_deep_channels():
+    y, ref, dt, k3, c_in = _run(G.workload("sheets_small"))
+    H.conv_tolerance_check(y, ref, dt, k3, c_in)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("c_in,c_out", [(64, 192), (128, 64), (48, 40), (8, 16)])
+def test_channel_shapes_mfma_and_scalar(dtype, c_in, c_out):
+    y, ref, dt, k3, ci = _run(G.workload("sheets_small"), c_in=c_in, c_out=c_out, dtype=dtype)
+    H.conv_tolerance_check(y, ref, dt, k3, ci)
+
+
+def test_identity_tap_is_bit_exact_in_bf16():
+    w = G.workload("lidar_small")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 3, 1)
+    nb = O.kernel_map(og, og, 3, 1)
+    feat = G.round_to_dtype(np.random.default_rng(5).standard_normal((og.num_voxels, 64)).astype(np.float32), "bf16")
+    d_feat = H.to_device_storage(feat, "bf16")
+    for kappa in (0, 13, 20):
+        wt = np.zeros((27, 64, 64), dtype=np.float32)
+        wt[kappa] = np.eye(64)
+        y = fx.sparse_conv_fwd(km, d_feat, H.to_device_storage(wt, "bf16")).float().cpu().numpy()
+        expect = np.where(nb[:, kappa:kappa + 1] >= 0, feat[np.maximum(nb[:, kappa], 0)], 0.0)
+        assert np.array_equal(y, expect)
+
+
+def test_all_ones_counts_neighbours_exactly_in_f16():
+    w = G.workload("sheets_small")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 3, 1)
+    nb = O.kernel_map(og, og, 3, 1)
+    ones_f = torch.ones((og.num_voxels, 64), dtype=torch.float16, device="cuda")
+    ones_w = torch.ones((27, 64, 64), dtype=torch.float16, device="cuda")
+    y = fx.sparse_conv_fwd(km, ones_f, ones_w).float().cpu().numpy()
+    assert np.array_equal(y, np.repeat(64.0 * (nb >= 0).sum(1)[:, None], 64, axis=1))
+
+
+def test_scalar_and_mfma_paths_agree_with_oracle_on_empty_and_tiny_grids():
+    g, og = H.both_grids(np.zeros((0, 3), np.int32), np.array([[0, 0]], np.int64))
+    km = fx.build_kernel_map(g, 3, 1)
+    y = fx.sparse_conv_fwd(km, torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda"),
+                           torch.zeros((27, 64, 64), dtype=torch.bfloat16, device="cuda"))
+    assert y.shape == (0, 64)
+    pts = np.array([[0, 0, 0], [0, 0, 1], [5, 5, 5], [-1, 0, 0]], dtype=np.int32)   # a single partial tile
+    g, og = H.both_grids(pts, np.array([[0, 4]], np.int64))
+    km = fx.build_kernel_map(g, 3, 1)
+    feat, wt = G.features_and_weights(7, 4, 64, 64, 27, "bf16")
+    y = fx.sparse_conv_fwd(km, H.to_device_storage(feat, "bf16"), H.to_device_storage(wt, "bf16"))
+    H.conv_tolerance_check(y.float().cpu().numpy(), O.conv(og, og, 3, 1, feat, wt), "bf16", 27, 64)
+
+
+def test_full_size_lidar_bf16_sampled_rows():
+    """Config 3 at full size in the benchmark's launch configuration; the oracle computes a
+    sample of output rows one by one (a few thousand rows spread over the grid)."""
+    w = G.workload("lidar1m")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 3, 1)
+    feat, wt = w.feats_weights()
+    y = fx.sparse_conv_fwd(km, H.to_device_storage(feat, "bf16"), H.to_device_storage(wt, "bf16"))
+    y = y.float().cpu().numpy()
+    n = og.num_voxels
+    starts = list(range(0, n - 300, n // 12)) + [n - 300]
+    f64, w64 = feat.astype(np.float64), wt.astype(np.float64)
+    for s in starts:
+        ref = O.conv(og, og, 3, 1, f64, w64, s, s + 300)
+        H.conv_tolerance_check(y[s:s + 300], ref[s:s + 300], "bf16", 27, 64)

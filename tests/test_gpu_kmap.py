@@ -1,0 +1,83 @@
+"""GPU parity: kernel maps, bit-exact against the oracle (decoded from the tiled form the
+convolution consumes)."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_common as H
+import paper_2407_01781_amd as fx
+from oracle import cpu_oracle as O
+from workloads import generators as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _cloud(seed, n, lo, hi):
+    return np.random.default_rng(seed).integers(lo, hi, size=(n, 3)).astype(np.int32)
+
+
+def _check_map(g, og, K, s):
+    km = fx.build_kernel_map(g, K, s)
+    ogo = O.output_grid(og, K, s)
+    H.check_grid(km.g_out, ogo)
+    ref = O.kernel_map(og, ogo, K, s)
+    got = km.dense().cpu().numpy()
+    assert got.dtype == np.int32 and got.shape == ref.shape
+    assert np.array_equal(got, ref)
+    n_pairs, per = km.info()
+    assert n_pairs == int((ref >= 0).sum())
+    assert np.array_equal(per, (ref >= 0).sum(axis=0))
+    return km, ref
+
+
+@pytest.mark.parametrize("name,K,s", [("sphere64", 3, 1), ("sheets_small", 3, 1), ("lidar_small", 3, 1),
+                                      ("indoor_small", 3, 1), ("lidar_small", 2, 2), ("sheets_small", 1, 1),
+                                      ("sphere64", 5, 1), ("sheets_small", 2, 2)])
+def test_workload_maps_match_oracle(name, K, s):
+    w = G.workload(name)
+    ijk, jo = w.jagged_ijk(dup_fraction=0.01)
+    g, og = H.both_grids(ijk, jo)
+    _check_map(g, og, K, s)
+
+
+@pytest.mark.parametrize("K,s", [(3, 1), (2, 2)])
+def test_negative_coordinates_and_tile_borders(K, s):
+    grids = [_cloud(1, 4000, -20, 20), _cloud(2, 4000, 4080, 4112), np.zeros((0, 3), np.int32),
+             _cloud(3, 300, -4100, -4090)]
+    ijk, jo = G.make_jagged(grids)
+    g, og = H.both_grids(ijk, jo)
+    _check_map(g, og, K, s)
+
+
+def test_dense_block_has_many_rows_per_tile():
+    # a dense 20^3 block: tiles with the largest number of distinct input rows
+    a = np.arange(20, dtype=np.int32)
+    pts = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3)
+    g, og = H.both_grids(pts, np.array([[0, pts.shape[0]]]))
+    km, ref = _check_map(g, og, 3, 1)
+    st = km.tile_stats()
+    assert st["mfma_rows_issued"] >= int((ref >= 0).sum())
+
+
+def test_empty_grid_map():
+    g, og = H.both_grids(np.zeros((0, 3), np.int32), np.array([[0, 0]], np.int64))
+    km = fx.build_kernel_map(g, 3, 1)
+    assert km.n_out == 0 and km.dense().shape == (0, 27) and km.info()[0] == 0
+
+
+def test_unsupported_kernel_stride_is_reported():
+    g, _ = H.both_grids(_cloud(5, 100, 0, 10), np.array([[0, 100]], np.int64))
+    with pytest.raises(fx.FxError) as e:
+        fx.build_kernel_map(g, 3, 2)
+    assert e.value.status == -2
+
+
+def test_full_size_lidar_map_sampled_rows_and_invariants():
+    w = G.workload("lidar1m")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 3, 1)
+    got = km.dense().cpu().numpy()
+    ref = O.kernel_map(og, og, 3, 1)                      # ~2 s on the host
+    assert np.array_equal(got, ref)
+    assert km.info()[0] == 7983738
