@@ -155,6 +155,18 @@ void fx_kmap_destroy(fx_kmap* km);
 fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w,
                              int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream);
 
+/* ---------------------------------------------------------------------------------------
+ * Measurement support (the paper's protocol, Sec. 4.1: per-operator times).  While enabled,
+ * every kernel launch of the library is bracketed by hipEvents on its launch stream;
+ * fx_profile_read waits for the recorded events and returns the summed time and launch count
+ * of one slot (slot names: fx_profile_slot_name, e.g. "k_conv_mfma", "k_nbmap").
+ */
+void        fx_profile_enable(int on);
+void        fx_profile_reset(void);
+int         fx_profile_slot_count(void);
+const char* fx_profile_slot_name(int slot);
+fx_status   fx_profile_read(int slot, double* total_ms, int64_t* count);
+
 #ifdef __cplusplus
 }
 #endif

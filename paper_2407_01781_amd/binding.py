@@ -67,6 +67,12 @@ def _load():
     L.fx_kmap_destroy.argtypes = [vp]
     L.fx_sparse_conv_fwd.restype = C.c_int
     L.fx_sparse_conv_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
+    L.fx_profile_enable.argtypes = [C.c_int]
+    L.fx_profile_slot_count.restype = C.c_int
+    L.fx_profile_slot_name.restype = C.c_char_p
+    L.fx_profile_slot_name.argtypes = [C.c_int]
+    L.fx_profile_read.restype = C.c_int
+    L.fx_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
     return L
 
 
@@ -88,6 +94,25 @@ def _ptr(t: Optional[torch.Tensor]):
 
 def version() -> str:
     return lib.fx_version().decode()
+
+
+def profile_enable(on: bool) -> None:
+    lib.fx_profile_enable(1 if on else 0)
+
+
+def profile_reset() -> None:
+    lib.fx_profile_reset()
+
+
+def profile_read() -> dict:
+    """{kernel slot name: (total ms, launches)} for slots with at least one launch."""
+    out = {}
+    for slot in range(lib.fx_profile_slot_count()):
+        ms, cnt = C.c_double(), C.c_int64()
+        _check(lib.fx_profile_read(slot, C.byref(ms), C.byref(cnt)))
+        if cnt.value:
+            out[lib.fx_profile_slot_name(slot).decode()] = (float(ms.value), int(cnt.value))
+    return out
 
 
 class IndexGrid:

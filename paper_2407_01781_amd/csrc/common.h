@@ -36,6 +36,23 @@ void dev_free(void* p, hipStream_t s);
 // pinned host staging area owned by the library (per thread), at least `bytes` large
 fx_status host_staging(void** p, size_t bytes);
 
+// ------------------------------------------------------------------ per-kernel timing
+// When enabled (fx_profile_enable), every kernel launch of the library is bracketed by a pair
+// of hipEvents on the launch stream; fx_profile_read sums the elapsed times per slot.
+enum ProfSlot {
+    kProfFindTiles = 0, kProfRankTiles, kProfInsertUpper, kProfScanUpper, kProfInsertLower, kProfScanLower,
+    kProfInsertLeaf, kProfScanLeaf, kProfVoxBase, kProfGridIjk, kProfNbmap, kProfPackTiles, kProfPackWeights,
+    kProfConvMfma, kProfConvScalar, kProfMemset, kProfSlotCount
+};
+bool prof_enabled();
+void prof_begin(int slot, hipStream_t s);
+void prof_end(int slot, hipStream_t s);
+struct ProfScope {
+    int slot; hipStream_t s; bool on;
+    ProfScope(int slot_, hipStream_t s_) : slot(slot_), s(s_), on(prof_enabled()) { if (on) prof_begin(slot, s); }
+    ~ProfScope() { if (on) prof_end(slot, s); }
+};
+
 // ------------------------------------------------------------------ tree layout
 // Node fan-outs of the VDB tree (Sec. 3.1): upper 32^3 children, lower 16^3, leaf 8^3 voxels.
 constexpr int kUpperWords = 32 * 32 * 32 / 64;  // 512 child-mask words per upper node

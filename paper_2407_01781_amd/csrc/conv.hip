@@ -308,10 +308,14 @@ extern "C" fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, f
         const size_t wbytes = sizeof(uint16_t) * (size_t)km->K3 * C_in * C_out;
         FX_TRY(dev_alloc((void**)&wp, wbytes, st));
         const int64_t total = (int64_t)km->K3 * C_in * C_out;
-        k_pack_weights<<<(unsigned)std::min<int64_t>((total + 255) / 256, 4096), 256, 0, st>>>(
-            (const uint16_t*)d_w, wp, km->K3, C_in, C_out);
+        {
+            ProfScope ps(kProfPackWeights, st);
+            k_pack_weights<<<(unsigned)std::min<int64_t>((total + 255) / 256, 4096), 256, 0, st>>>(
+                (const uint16_t*)d_w, wp, km->K3, C_in, C_out);
+        }
         hipError_t e = hipGetLastError();
         if (e == hipSuccess) {
+            ProfScope ps(kProfConvMfma, st);
             const bool two = (C_out % (2 * kCoutSlice) == 0);
             if (in_dt == FX_BF16) {
                 if (two) e = out_f32 ? launch_mfma<__bf16, 2, true>(km, d_feat, wp, C_in, C_out, d_out, st)
@@ -338,6 +342,7 @@ extern "C" fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, f
         else k_conv_scalar<DT, false><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_w, C_in,     \
                                                           C_out, d_out);                                         \
     } while (0)
+    ProfScope ps(kProfConvScalar, st);
     if (in_dt == FX_F32) FX_SCALAR(FX_F32);
     else if (in_dt == FX_F16) FX_SCALAR(FX_F16);
     else FX_SCALAR(FX_BF16);

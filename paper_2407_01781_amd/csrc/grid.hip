@@ -479,23 +479,28 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
 #define FX_TRY_OR_FAIL(expr) do { hipError_t _e = (expr); if (_e != hipSuccess) { \
         set_error("%s failed: %s", #expr, hipGetErrorString(_e)); return fail(FX_EDEVICE); } } while (0)
 
-    FX_TRY_OR_FAIL(hipMemsetAsync(g->buf, 0, g->buf_bytes, st));
-    FX_TRY_OR_FAIL(hipMemsetAsync(d_slots, 0xFF, sizeof(int32_t) * kTileHashSlots, st));
+    {
+        ProfScope ps(kProfMemset, st);
+        FX_TRY_OR_FAIL(hipMemsetAsync(g->buf, 0, g->buf_bytes, st));
+        FX_TRY_OR_FAIL(hipMemsetAsync(d_slots, 0xFF, sizeof(int32_t) * kTileHashSlots, st));
+    }
     const GridPtrs q = ptrs_of(g);
     if (n_rows > 0 && B > 0) {
         const int nb = blocks_for_rows(n_rows);
-        k_find_tiles<<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, B, d_slots, d_rep, g->d_hdr);
-        k_rank_tiles<<<kMaxTiles / 256, 256, 0, st>>>(d_ijk, d_joff, B, d_rep, q);
-        k_insert<0><<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, q);
+        { ProfScope ps(kProfFindTiles, st); k_find_tiles<<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, B, d_slots, d_rep, g->d_hdr); }
+        { ProfScope ps(kProfRankTiles, st); k_rank_tiles<<<kMaxTiles / 256, 256, 0, st>>>(d_ijk, d_joff, B, d_rep, q); }
+        { ProfScope ps(kProfInsertUpper, st); k_insert<0><<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, q); }
         LevelScan su{g->d_upper_mask, g->d_upper_prefix, &g->d_hdr->n_upper, kUpperWords, &g->d_hdr->n_lower,
                      g->cap_lower, 2};
-        if (scan_level(g, su, g->cap_upper, d_block_sums, st) != FX_OK) return fail(FX_EDEVICE);
-        k_insert<1><<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, q);
+        { ProfScope ps(kProfScanUpper, st); if (scan_level(g, su, g->cap_upper, d_block_sums, st) != FX_OK) return fail(FX_EDEVICE); }
+        { ProfScope ps(kProfInsertLower, st); k_insert<1><<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, q); }
         LevelScan sl{g->d_lower_mask, g->d_lower_prefix, &g->d_hdr->n_lower, kLowerWords, &g->d_hdr->n_leaf,
                      g->cap_leaf, 4};
-        if (scan_level(g, sl, g->cap_lower, d_block_sums, st) != FX_OK) return fail(FX_EDEVICE);
-        k_insert<2><<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, q);
+        { ProfScope ps(kProfScanLower, st); if (scan_level(g, sl, g->cap_lower, d_block_sums, st) != FX_OK) return fail(FX_EDEVICE); }
+        { ProfScope ps(kProfInsertLeaf, st); k_insert<2><<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, q); }
         const int lb = std::max(1, (g->cap_leaf + kLeafChunk - 1) / kLeafChunk);
+        {
+        ProfScope ps(kProfScanLeaf, st);
         if (lb == 1) {
             k_scan_leaves_local<<<1, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums, 1);
         } else {
@@ -504,7 +509,8 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
                                                           nullptr, &g->d_hdr->n_voxels, INT32_MAX, 16);
             k_scan_leaves_apply<<<lb, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums);
         }
-        k_vox_base<<<(B + 1 + 255) / 256, 256, 0, st>>>(q);
+        }
+        { ProfScope ps(kProfVoxBase, st); k_vox_base<<<(B + 1 + 255) / 256, 256, 0, st>>>(q); }
         FX_TRY_OR_FAIL(hipGetLastError());
     }
     // one read-back: counts + per-grid ranges (Sec. 3.3 step 10)
@@ -656,6 +662,7 @@ extern "C" fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** 
     auto cleanup = [&]() { dev_free(d_c, st); dev_free(d_joff, st); };
     if (g->hdr.n_leaf > 0) {
         const int64_t threads = (int64_t)g->hdr.n_leaf * 64;
+        ProfScope ps(kProfGridIjk, st);
         k_grid_ijk<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(g->view(), d_c, nullptr, 1);
     }
     if (g->B > 0) {

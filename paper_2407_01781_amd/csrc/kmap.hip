@@ -340,6 +340,7 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     if (e == hipSuccess && gout->hdr.n_leaf > 0) {
         const unsigned nb = (unsigned)((gout->hdr.n_leaf + kNbWavesPerBlock - 1) / kNbWavesPerBlock);
         const TreeView tin = g_in->view(), tout = gout->view();
+        ProfScope ps(kProfNbmap, st);
         switch (K) {
             case 1: k_nbmap<1><<<nb, 64 * kNbWavesPerBlock, 0, st>>>(tin, tout, stride, km->d_nbmap); break;
             case 2: k_nbmap<2><<<nb, 64 * kNbWavesPerBlock, 0, st>>>(tin, tout, stride, km->d_nbmap); break;
@@ -352,6 +353,7 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
         unsigned long long* stats = (unsigned long long*)km->d_stats;
         const size_t lds = sizeof(PackLds);
         const unsigned nt = (unsigned)km->n_tiles;
+        ProfScope ps(kProfPackTiles, st);
 #define FX_PACK(K3V)                                                                                         \
     do {                                                                                                     \
         e = hipFuncSetAttribute((const void*)k_pack_tiles<K3V>, hipFuncAttributeMaxDynamicSharedMemorySize,  \

@@ -4,6 +4,9 @@
 #include <stdarg.h>
 #include <stdlib.h>
 
+#include <mutex>
+#include <vector>
+
 namespace fx {
 
 static thread_local char g_err[512] = "";
@@ -92,7 +95,79 @@ fx_status host_staging(void** p, size_t bytes) {
     return FX_OK;
 }
 
+// ---------------------------------------------------------------------------------- profiler
+struct ProfRec { int slot; hipEvent_t a, b; };
+static std::atomic<bool> g_prof_on{false};
+static std::mutex g_prof_mu;
+static std::vector<ProfRec> g_prof_open;     // begun, not yet ended
+static std::vector<ProfRec> g_prof_done;
+static double g_prof_ms[kProfSlotCount];
+static long long g_prof_count[kProfSlotCount];
+
+bool prof_enabled() { return g_prof_on.load(std::memory_order_relaxed); }
+
+void prof_begin(int slot, hipStream_t s) {
+    ProfRec r{slot, nullptr, nullptr};
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+    (void)hipEventRecord(r.a, s);
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_open.push_back(r);
+}
+
+void prof_end(int slot, hipStream_t s) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (size_t i = g_prof_open.size(); i-- > 0;) {
+        if (g_prof_open[i].slot == slot) {
+            ProfRec r = g_prof_open[i];
+            g_prof_open.erase(g_prof_open.begin() + (long)i);
+            (void)hipEventRecord(r.b, s);
+            g_prof_done.push_back(r);
+            return;
+        }
+    }
+}
+
+static void prof_drain() {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (ProfRec& r : g_prof_done) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+            g_prof_ms[r.slot] += ms;
+            g_prof_count[r.slot] += 1;
+        }
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    g_prof_done.clear();
+}
+
+static const char* kProfNames[kProfSlotCount] = {
+    "k_find_tiles", "k_rank_tiles", "k_insert<0>", "scan_upper", "k_insert<1>", "scan_lower", "k_insert<2>",
+    "scan_leaves", "k_vox_base", "k_grid_ijk", "k_nbmap", "k_pack_tiles", "k_pack_weights", "k_conv_mfma",
+    "k_conv_scalar", "memset"};
+
 }  // namespace fx
+
+extern "C" void fx_profile_enable(int on) { fx::g_prof_on.store(on != 0); }
+
+extern "C" void fx_profile_reset(void) {
+    fx::prof_drain();
+    for (int i = 0; i < fx::kProfSlotCount; ++i) { fx::g_prof_ms[i] = 0; fx::g_prof_count[i] = 0; }
+}
+
+extern "C" int fx_profile_slot_count(void) { return fx::kProfSlotCount; }
+
+extern "C" const char* fx_profile_slot_name(int slot) {
+    return (slot >= 0 && slot < fx::kProfSlotCount) ? fx::kProfNames[slot] : "";
+}
+
+extern "C" fx_status fx_profile_read(int slot, double* total_ms, int64_t* count) {
+    if (slot < 0 || slot >= fx::kProfSlotCount) { fx::set_error("fx_profile_read: bad slot"); return FX_EINVAL; }
+    fx::prof_drain();
+    if (total_ms) *total_ms = fx::g_prof_ms[slot];
+    if (count) *count = fx::g_prof_count[slot];
+    return FX_OK;
+}
 
 extern "C" const char* fx_version(void) { return "fvdb-hotpath-gfx950 0.1"; }
 
