@@ -149,7 +149,7 @@ void fx_kmap_destroy(fx_kmap* km);
  * Products are exact in the input precision's product format and accumulated in fp32
  * (FX_F32 inputs: fp32 FMA; FX_F16 / FX_BF16: MFMA with fp32 accumulators); the result is
  * rounded to out_dt with round-to-nearest-even.
- * C_in, C_out >= 1.  The MFMA path needs C_in % 64 == 0 and C_out % 64 == 0; other
+ * C_in, C_out >= 1.  The MFMA path needs C_in % 32 == 0 and C_out % 64 == 0; other
  * shapes and FX_F32 take the scalar path.
  */
 fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w,

@@ -25,11 +25,14 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int kCinChunk = 64;       // input channels staged in LDS at a time
+constexpr int kCinChunk = 32;       // input channels staged in LDS at a time (one MFMA k-step)
 constexpr int kCoutSlice = 64;      // output channels per wave
-constexpr int kRowCap = 448;        // LDS rows per tile; row kRowCap is the zero row
 constexpr int kRowBytes = kCinChunk * 2;
-constexpr int kMaxBlocks = kGroupsPerTile * 27;
+constexpr int kRowCap = 832;        // LDS rows per tile; row kRowCap is the zero row
+constexpr int kLdsBlocks = 640;     // blocks kept in LDS; further blocks are read from global memory
+constexpr int kConvThreads = 256;
+constexpr int kConvWaves = kConvThreads / 64;
+constexpr int kGroupsPerWave = kGroupsPerTile / kConvWaves;   // 8 column blocks of 16 outputs
 
 // ---------------------------------------------------------------------------------- element types
 template <typename T> struct Elem;
@@ -65,9 +68,10 @@ template <> struct Elem<_Float16> {
 };
 
 // ---------------------------------------------------------------------------------- weight packing
-// Wp[kappa][cin chunk][cout slice][kstep 0..1][mtile 0..3][lane 0..63][8]: the 16-byte A-operand
-// fragment of each lane.  Row m of m-tile t holds output channel 16*(m/4) + 4*t + (m%4) of the
-// slice, so that a lane's 16 accumulators are 16 consecutive output channels.
+// Wp[kappa][cin chunk][cout slice][mtile 0..3][lane 0..63][8]: the 16-byte A-operand fragment
+// of each lane for one (offset, 32 input channels, 64 output channels).  Row m of m-tile t holds
+// output channel 16*(m/4) + 4*t + (m%4) of the slice, so that a lane's 16 accumulators are 16
+// consecutive output channels.
 __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wp, int K3, int C_in, int C_out) {
     const int64_t total = (int64_t)K3 * C_in * C_out;
     const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
@@ -76,12 +80,11 @@ __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restr
         const int el = (int)(r & 7); r >>= 3;
         const int lane = (int)(r & 63); r >>= 6;
         const int mt = (int)(r & 3); r >>= 2;
-        const int ks = (int)(r & 1); r >>= 1;
         const int s = (int)(r % nslice); r /= nslice;
         const int c = (int)(r % nchunk); r /= nchunk;
         const int kappa = (int)r;
         const int m = lane & 15, kq = lane >> 4;
-        const int cin = c * kCinChunk + ks * 32 + kq * 8 + el;
+        const int cin = c * kCinChunk + kq * 8 + el;
         const int cout = s * kCoutSlice + 16 * (m >> 2) + 4 * mt + (m & 3);
         wp[e] = w[((int64_t)kappa * C_in + cin) * C_out + cout];
     }
@@ -89,43 +92,50 @@ __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restr
 
 // ---------------------------------------------------------------------------------- MFMA kernel
 struct ConvLds {
-    unsigned char rows[(kRowCap + 1) * kRowBytes];  // 16-byte chunks XOR-swizzled by (row & 7)
-    uint16_t blocks[kMaxBlocks * kGroup];
+    unsigned char rows[(kRowCap + 1) * kRowBytes];  // 64-byte rows; 16-byte chunk q stored at q ^ ((row >> 2) & 3)
+    uint16_t blocks[kLdsBlocks * kGroup];
     uint16_t perm[kTileT];
     uint32_t group_mask[kGroupsPerTile];
     uint32_t group_block0[kGroupsPerTile];
 };
 
-template <typename T, int S /* cout slices per workgroup: 1 or 2 */, bool OUT_F32>
-__global__ void __launch_bounds__(256)
+__device__ __forceinline__ int lds_row_offset(int row, int q) { return row * kRowBytes + ((q ^ ((row >> 2) & 3)) << 4); }
+
+// One workgroup = one tile of 512 consecutive outputs x one slice of 64 output channels.
+// Wave w owns column blocks 8w..8w+7 (128 outputs): 8 x 4 accumulator tiles of 16x16.
+template <typename T, bool OUT_F32>
+__global__ void __launch_bounds__(kConvThreads, 2)
 k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
             const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
             int block_stride, int K3, const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp,
             int C_in, int C_out, void* __restrict__ out) {
     typedef typename Elem<T>::vec8 vec8;
-    constexpr int NG = 4 * S;  // groups per wave
+    constexpr int NG = kGroupsPerWave;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     ConvLds& L = *reinterpret_cast<ConvLds*>(lds_raw);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, q = lane >> 4;
     const int64_t tile = blockIdx.x;
-    const int slice = blockIdx.y * S + (wave % S);   // cout slice of this wave
-    const int g0 = (wave / S) * NG;                  // first group of this wave
+    const int slice = blockIdx.y;
+    const int g0 = wave * NG;
     const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
 
     const TileHeader* H = tile_hdr + tile;
-    const int n_rows = H->n_rows, n_blocks = H->n_blocks, n_valid = H->n_out;
-    const int n_staged = min(n_rows, kRowCap);
+    const int win_lo = H->win_lo, win_n = H->win_n, n_list = H->n_list;
+    const int n_blocks = H->n_blocks, n_valid = H->n_out;
+    const int n_staged = (H->flags & kTileDirect) ? 0 : min(win_n + n_list, kRowCap);
     const int32_t* my_rows = tile_rows + tile * (int64_t)row_stride;
+    const uint16_t* my_blocks = tile_blocks + (size_t)tile * block_stride * kGroup;
 
     // tile metadata -> LDS
     if (tid < kGroupsPerTile) { L.group_mask[tid] = H->group_mask[tid]; L.group_block0[tid] = H->group_block0[tid]; }
-    L.perm[tid] = tile_perm[tile * kTileT + tid];
+    for (int e = tid; e < kTileT; e += kConvThreads) L.perm[e] = tile_perm[tile * kTileT + e];
     {
-        const u32x4* src = reinterpret_cast<const u32x4*>(tile_blocks + (size_t)tile * block_stride * kGroup);
+        const u32x4* src = reinterpret_cast<const u32x4*>(my_blocks);
         u32x4* dst = reinterpret_cast<u32x4*>(L.blocks);
-        for (int e = tid; e < n_blocks * 2; e += 256) dst[e] = src[e];
+        const int nb2 = min(n_blocks, kLdsBlocks) * 2;
+        for (int e = tid; e < nb2; e += kConvThreads) dst[e] = src[e];
     }
     if (tid < kRowBytes / 16) reinterpret_cast<u32x4*>(L.rows + kRowCap * kRowBytes)[tid] = u32x4{0, 0, 0, 0};
 
@@ -137,75 +147,76 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
 
     __syncthreads();
     uint32_t gmask[NG], gblock0[NG];
+    uint32_t wave_mask = 0;
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
         gmask[gi] = __builtin_amdgcn_readfirstlane(L.group_mask[g0 + gi]);
         gblock0[gi] = __builtin_amdgcn_readfirstlane(L.group_block0[g0 + gi]);
+        wave_mask |= gmask[gi];
     }
 
     for (int c = 0; c < nchunk; ++c) {
         if (c > 0) __syncthreads();  // all waves are done reading the previous chunk
-        // stage the tile's input rows, channels [64c, 64c+64): 8 lanes x 16 bytes per row
+        // stage the tile's input rows, channels [32c, 32c+32): 4 lanes x 16 bytes per row
         {
-            const int sub = tid & 7;
-            for (int r0 = tid >> 3; r0 < n_staged; r0 += 32 * 4) {
+            const int sub = tid & 3;
+            for (int r0 = tid >> 2; r0 < n_staged; r0 += 64 * 4) {
                 u32x4 v[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const int r = r0 + 32 * u;
+                    const int r = r0 + 64 * u;
                     if (r < n_staged) {
-                        const int64_t gr = my_rows[r];
+                        const int64_t gr = r < win_n ? (int64_t)win_lo + r : (int64_t)my_rows[r - win_n];
                         v[u] = *reinterpret_cast<const u32x4*>(feat + gr * C_in + c * kCinChunk + sub * 8);
                     }
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const int r = r0 + 32 * u;
-                    if (r < n_staged)
-                        *reinterpret_cast<u32x4*>(L.rows + r * kRowBytes + ((sub ^ (r & 7)) << 4)) = v[u];
+                    const int r = r0 + 64 * u;
+                    if (r < n_staged) *reinterpret_cast<u32x4*>(L.rows + lds_row_offset(r, sub)) = v[u];
                 }
             }
         }
         __syncthreads();
 
-        for (int kappa = 0; kappa < K3; ++kappa) {
-            uint32_t present = 0;
+        // offsets this wave needs, in order; the weights of the next one are fetched while the
+        // current one is multiplied
+        uint32_t todo = wave_mask;
+        if (!todo) continue;
+        const vec8* wbase = reinterpret_cast<const vec8*>(wp) + lane;
+        auto w_ptr = [&](int kappa) { return wbase + ((((int64_t)kappa * nchunk + c) * nslice + slice) * 4) * 64; };
+        vec8 wf[4], wn[4];
+        {
+            const vec8* ws = w_ptr(__ffs(todo) - 1);
 #pragma unroll
-            for (int gi = 0; gi < NG; ++gi) present |= ((gmask[gi] >> kappa) & 1u) << gi;
-            if (!present) continue;
-            // A fragments of W[kappa][chunk c][slice]
-            vec8 wf[2][4];
-            {
-                const vec8* wsrc = reinterpret_cast<const vec8*>(wp) +
-                                   ((((int64_t)kappa * nchunk + c) * nslice + slice) * 8) * 64 + lane;
+            for (int mt = 0; mt < 4; ++mt) wf[mt] = ws[mt * 64];
+        }
+        while (todo) {
+            const int kappa = __ffs(todo) - 1;
+            todo &= todo - 1;
+            if (todo) {
+                const vec8* ws = w_ptr(__ffs(todo) - 1);
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                    for (int mt = 0; mt < 4; ++mt) wf[ks][mt] = wsrc[(ks * 4 + mt) * 64];
+                for (int mt = 0; mt < 4; ++mt) wn[mt] = ws[mt * 64];
             }
 #pragma unroll
             for (int gi = 0; gi < NG; ++gi) {
-                if (!((present >> gi) & 1u)) continue;
+                if (!((gmask[gi] >> kappa) & 1u)) continue;
                 const int blk = (int)gblock0[gi] + __popc(gmask[gi] & ((1u << kappa) - 1u));
-                const uint32_t id = L.blocks[blk * kGroup + n];
-                vec8 bf[2];
-                if (id < (uint32_t)kRowCap || id == kNoRow) {
+                const uint32_t id = blk < kLdsBlocks ? L.blocks[blk * kGroup + n] : my_blocks[blk * kGroup + n];
+                vec8 bf;
+                if (id < (uint32_t)n_staged || id == kNoRow) {
                     const int row = (id == kNoRow) ? kRowCap : (int)id;
-                    const unsigned char* base = L.rows + row * kRowBytes;
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks)
-                        bf[ks] = *reinterpret_cast<const vec8*>(base + (((ks * 4 + q) ^ (row & 7)) << 4));
-                } else {  // row beyond the LDS budget: read it from global memory
-                    const int64_t gr = my_rows[id];
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks)
-                        bf[ks] = *reinterpret_cast<const vec8*>(feat + gr * C_in + c * kCinChunk + ks * 32 + q * 8);
+                    bf = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, q));
+                } else {  // row not staged (direct tile, or beyond the LDS budget): read it from global memory
+                    const int64_t gr = id < (uint32_t)win_n ? (int64_t)win_lo + id : (int64_t)my_rows[id - win_n];
+                    bf = *reinterpret_cast<const vec8*>(feat + gr * C_in + c * kCinChunk + q * 8);
                 }
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                    for (int mt = 0; mt < 4; ++mt) acc[gi][mt] = Elem<T>::mfma(wf[ks][mt], bf[ks], acc[gi][mt]);
+                for (int mt = 0; mt < 4; ++mt) acc[gi][mt] = Elem<T>::mfma(wf[mt], bf, acc[gi][mt]);
             }
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) wf[mt] = wn[mt];
         }
     }
 
@@ -268,17 +279,18 @@ __global__ void k_conv_scalar(const int32_t* __restrict__ nbmap, int64_t n_out, 
     }
 }
 
-template <typename T, int S, bool OUT_F32>
+template <typename T, bool OUT_F32>
 static hipError_t launch_mfma(const fx_kmap* km, const void* feat, const void* wp, int C_in, int C_out, void* out,
                               hipStream_t st) {
     const size_t lds = sizeof(ConvLds);
-    hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<T, S, OUT_F32>,
+    hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<T, OUT_F32>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    dim3 grid((unsigned)km->n_tiles, (unsigned)(C_out / (kCoutSlice * S)));
-    k_conv_mfma<T, S, OUT_F32><<<grid, 256, lds, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,
-                                                       km->row_stride, km->d_tile_blocks, km->block_stride, km->K3,
-                                                       (const uint16_t*)feat, (const uint16_t*)wp, C_in, C_out, out);
+    dim3 grid((unsigned)km->n_tiles, (unsigned)(C_out / kCoutSlice));
+    k_conv_mfma<T, OUT_F32><<<grid, kConvThreads, lds, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,
+                                                             km->row_stride, km->d_tile_blocks, km->block_stride,
+                                                             km->K3, (const uint16_t*)feat, (const uint16_t*)wp, C_in,
+                                                             C_out, out);
     return hipGetLastError();
 }
 
@@ -316,23 +328,18 @@ extern "C" fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, f
         hipError_t e = hipGetLastError();
         if (e == hipSuccess) {
             ProfScope ps(kProfConvMfma, st);
-            const bool two = (C_out % (2 * kCoutSlice) == 0);
-            if (in_dt == FX_BF16) {
-                if (two) e = out_f32 ? launch_mfma<__bf16, 2, true>(km, d_feat, wp, C_in, C_out, d_out, st)
-                                     : launch_mfma<__bf16, 2, false>(km, d_feat, wp, C_in, C_out, d_out, st);
-                else e = out_f32 ? launch_mfma<__bf16, 1, true>(km, d_feat, wp, C_in, C_out, d_out, st)
-                                 : launch_mfma<__bf16, 1, false>(km, d_feat, wp, C_in, C_out, d_out, st);
-            } else {
-                if (two) e = out_f32 ? launch_mfma<_Float16, 2, true>(km, d_feat, wp, C_in, C_out, d_out, st)
-                                     : launch_mfma<_Float16, 2, false>(km, d_feat, wp, C_in, C_out, d_out, st);
-                else e = out_f32 ? launch_mfma<_Float16, 1, true>(km, d_feat, wp, C_in, C_out, d_out, st)
-                                 : launch_mfma<_Float16, 1, false>(km, d_feat, wp, C_in, C_out, d_out, st);
-            }
+            if (in_dt == FX_BF16)
+                e = out_f32 ? launch_mfma<__bf16, true>(km, d_feat, wp, C_in, C_out, d_out, st)
+                            : launch_mfma<__bf16, false>(km, d_feat, wp, C_in, C_out, d_out, st);
+            else
+                e = out_f32 ? launch_mfma<_Float16, true>(km, d_feat, wp, C_in, C_out, d_out, st)
+                            : launch_mfma<_Float16, false>(km, d_feat, wp, C_in, C_out, d_out, st);
         }
         dev_free(wp, st);
         if (e != hipSuccess) { set_error("convolution launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
         return FX_OK;
     }
+    FX_TRY(kmap_ensure_dense(const_cast<fx_kmap*>(km), st));
     const int64_t total = km->n_out * C_out;
     const unsigned nb = (unsigned)std::min<int64_t>((total + 255) / 256, 1 << 20);
 #define FX_SCALAR(DT)                                                                                            \

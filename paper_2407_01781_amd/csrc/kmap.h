@@ -10,19 +10,32 @@ namespace fx {
 // Outputs are cut into tiles of kTileT consecutive indices.  Inside a tile the outputs are
 // reordered so that voxels with equal neighbour masks sit together, then cut into groups of
 // 16 (one MFMA column block).  For every (group, offset) with at least one active pair a
-// "block" of 16 local row ids is stored; id r < n_rows points into the tile's list of distinct
-// input rows (staged once in LDS), kNoRow means "no input" (multiplies a zero row).
-constexpr int kTileT = 256;                 // outputs per tile
+// "block" of 16 local row ids is stored.  A local id r addresses the tile's input rows:
+//     r <  win_n            -> global row win_lo + r          (a contiguous window; for a
+//                              submanifold map the tile's own index range, which the centre
+//                              tap needs anyway)
+//     r >= win_n            -> global row rows[r - win_n]     (the halo: distinct rows outside
+//                              the window, ascending)
+//     r == kNoRow           -> no input (multiplies a zero row)
+// A tile flagged kTileDirect keeps no window and lists one row per active pair (no
+// de-duplication): used for strided maps, where every input row is used exactly once, and as
+// the fallback when a tile's halo exceeds the builder's table.
+constexpr int kTileT = 512;                 // outputs per tile
 constexpr int kGroup = 16;                  // outputs per MFMA column block
 constexpr int kGroupsPerTile = kTileT / kGroup;
-constexpr int kMaxStagedRows = 768;         // LDS rows per tile; further rows are read from global
+constexpr int kMaxK3Tiled = 27;             // offsets supported by the tiled form
+constexpr int kMaxHalo = 1024;              // distinct halo rows a tile may de-duplicate
 constexpr uint16_t kNoRow = 0xFFFF;
+constexpr int32_t kTileDirect = 1;
 
-struct TileHeader {                         // 64 + 16*4 bytes
-    int32_t n_rows;                         // distinct input rows of the tile
+struct TileHeader {
+    int32_t win_lo;                         // first global row of the window
+    int32_t win_n;                          // rows in the window
+    int32_t n_list;                         // entries in the tile's row list (halo or direct)
     int32_t n_blocks;                       // non-empty (group, offset) blocks
     int32_t n_out;                          // valid outputs in the tile (<= kTileT)
-    int32_t pad;
+    int32_t flags;                          // kTileDirect
+    int32_t pad[2];
     uint32_t group_mask[kGroupsPerTile];    // per group: bit kappa set = block present
     uint32_t group_block0[kGroupsPerTile];  // first block of each group
 };
@@ -36,18 +49,23 @@ struct fx_kmap {
     fx_grid* gout = nullptr;
     int32_t K = 0, stride = 0, K3 = 0;
     int64_t n_in = 0, n_out = 0;
-    int32_t* d_nbmap = nullptr;        // dense [n_out, K3] (scalar path, export)
+    int32_t* d_nbmap = nullptr;             // dense [n_out, K3]; only when the map is not tiled
     // tiled form
     int64_t n_tiles = 0;
     fx::TileHeader* d_tile_hdr = nullptr;   // [n_tiles]
     uint16_t* d_tile_perm = nullptr;        // [n_tiles][kTileT] output slot -> local output (0..T-1)
-    int32_t* d_tile_rows = nullptr;         // [n_tiles][row_stride] global input rows
+    int32_t* d_tile_rows = nullptr;         // [n_tiles][row_stride] global input rows (halo / direct)
     uint16_t* d_tile_blocks = nullptr;      // [n_tiles][block_stride][16] local row ids
     int32_t row_stride = 0, block_stride = 0;
-    int64_t* d_stats = nullptr;             // [4 + K3]: rows issued, staged rows, spare, pairs, pairs per offset
+    int64_t* d_stats = nullptr;             // [4 + K3]: MFMA rows issued, staged rows, direct tiles, spare, pairs per offset
     void* d_alloc = nullptr;                // single allocation backing all of the above
     bool stats_valid = false;
     int64_t h_stats[4] = {0, 0, 0, 0};
     int64_t* h_pairs = nullptr;             // [K3]
     int64_t h_n_pairs = 0;
 };
+
+namespace fx {
+// dense [n_out, K3] table for the scalar convolution path, built on first use (not thread-safe)
+fx_status kmap_ensure_dense(fx_kmap* km, hipStream_t st);
+}

@@ -1,5 +1,5 @@
 // Kernel-map build (Sec. 3.5): neighbour lookup through the tree for every output voxel and
-// stencil offset, then the tiled form the MFMA convolution consumes.
+// stencil offset, and the tiled form the MFMA convolution consumes.
 #include "kmap.h"
 #include "tree_device.h"
 
@@ -12,14 +12,12 @@ namespace fx {
 
 __host__ __device__ constexpr int delta_min(int K) { return (K & 1) ? -(K - 1) / 2 : 0; }
 
-// ---------------------------------------------------------------------------------- dense map
-// One wave per OUTPUT leaf (Sec. 3.5 scenario 1: gather offsets come straight from the tree's
-// light metadata, amortised over the leaf).  The wave resolves the <= 27 input leaves that the
-// leaf's stencil footprint can touch once, keeps their 80-byte records in LDS, lists the leaf's
-// active voxels with mask popcounts, and then every lane evaluates Listing 1 for one
-// (voxel, offset) entry at a time -- consecutive lanes write consecutive map entries.
-constexpr int kNbWavesPerBlock = 4;
-
+// ---------------------------------------------------------------------------------- leaf-centric lookup
+// The unit of lookup work is one OUTPUT leaf handled by one wave (Sec. 3.5 scenario 1: gather
+// offsets come straight from the tree's light metadata, amortised over the leaf).  The wave
+// resolves the <= 27 input leaves that the leaf's stencil footprint can touch once, keeps
+// their 80-byte records in LDS, lists the leaf's active voxels with mask popcounts, and then
+// every lane evaluates Listing 1 for one (voxel, offset) entry at a time.
 struct NbLeafLds {
     uint64_t mask[27][8];
     uint64_t prefix[27];
@@ -27,30 +25,22 @@ struct NbLeafLds {
     uint16_t active[512];
 };
 
+// Stage the neighbour records of output leaf `lf` (wave-wide; lanes 0..26 do one tree descent
+// each) and list its active voxels.  Returns the number of active voxels.
 template <int K>
-__global__ void __launch_bounds__(64 * kNbWavesPerBlock)
-k_nbmap(TreeView tin, TreeView tout, int stride, int32_t* __restrict__ nbmap) {
-    constexpr int K3 = K * K * K;
+__device__ __forceinline__ int stage_leaf(const TreeView& tin, const fx_leaf* __restrict__ lf, int stride, int lane,
+                                          NbLeafLds& lds) {
     constexpr int D0 = delta_min(K);
-    __shared__ NbLeafLds lds_all[kNbWavesPerBlock];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int f_raw = blockIdx.x * kNbWavesPerBlock + wave;
-    const bool valid = f_raw < tout.n_leaf;
-    const int f = valid ? f_raw : tout.n_leaf - 1;  // surplus waves repeat the last leaf's set-up, write nothing
-    NbLeafLds& lds = lds_all[wave];
-    const fx_leaf* lf = tout.leaf + f;
     const int b = lf->batch;
     const int oi = lf->origin[0], oj = lf->origin[1], ok = lf->origin[2];
-    // leaf coordinates of the first input leaf the footprint touches
     const int bi = (stride * oi + D0) >> 3, bj = (stride * oj + D0) >> 3, bk = (stride * ok + D0) >> 3;
     if (lane < 27) {
         const int a = lane / 9, c = (lane / 3) % 3, d = lane % 3;
-        const int li = (bi + a) * 8, lj = (bj + c) * 8, lk = (bk + d) * 8;
-        // only slots inside the footprint are looked up
         const int hi_i = (stride * (oi + 7) + D0 + K - 1) >> 3, hi_j = (stride * (oj + 7) + D0 + K - 1) >> 3,
                   hi_k = (stride * (ok + 7) + D0 + K - 1) >> 3;
         int id = -1;
-        if (bi + a <= hi_i && bj + c <= hi_j && bk + d <= hi_k) id = find_leaf(tin, b, li, lj, lk);
+        if (bi + a <= hi_i && bj + c <= hi_j && bk + d <= hi_k)
+            id = find_leaf(tin, b, (bi + a) * 8, (bj + c) * 8, (bk + d) * 8);
         if (id >= 0) {
             const fx_leaf* nl = tin.leaf + id;
 #pragma unroll
@@ -64,61 +54,123 @@ k_nbmap(TreeView tin, TreeView tout, int stride, int32_t* __restrict__ nbmap) {
             lds.offset[lane] = -1;
         }
     }
-    // active voxels of the output leaf, in index order
     int n_act = 0;
-    {
-        const uint64_t lt = (1ull << lane) - 1;
+    const uint64_t lt = (1ull << lane) - 1;
 #pragma unroll
-        for (int w = 0; w < 8; ++w) {
-            const uint64_t m = lf->mask[w];
-            if ((m >> lane) & 1) lds.active[n_act + __popcll(m & lt)] = (uint16_t)(w * 64 + lane);
-            n_act += __popcll(m);
-        }
+    for (int w = 0; w < 8; ++w) {
+        const uint64_t m = lf->mask[w];
+        if ((m >> lane) & 1) lds.active[n_act + __popcll(m & lt)] = (uint16_t)(w * 64 + lane);
+        n_act += __popcll(m);
     }
+    return n_act;
+}
+
+// map entry (active voxel v of the staged leaf, offset kappa)
+template <int K>
+__device__ __forceinline__ int lookup_entry(const NbLeafLds& lds, int oi, int oj, int ok, int stride, int v, int kappa) {
+    constexpr int D0 = delta_min(K);
+    const int bi = (stride * oi + D0) >> 3, bj = (stride * oj + D0) >> 3, bk = (stride * ok + D0) >> 3;
+    const int loc = lds.active[v];
+    const int da = kappa / (K * K), db = (kappa / K) % K, dc = kappa % K;
+    const int qi = stride * (oi + (loc >> 6)) + D0 + da;
+    const int qj = stride * (oj + ((loc >> 3) & 7)) + D0 + db;
+    const int qk = stride * (ok + (loc & 7)) + D0 + dc;
+    const int slot = (((qi >> 3) - bi) * 3 + ((qj >> 3) - bj)) * 3 + ((qk >> 3) - bk);
+    const int n = qi & 7;
+    const uint64_t w = lds.mask[slot][n];
+    const uint64_t bit = 1ull << (((qj & 7) << 3) | (qk & 7));
+    if (!(w & bit)) return -1;
+    const uint64_t sum = n ? (lds.prefix[slot] >> (9 * (n - 1))) & 511 : 0;
+    return lds.offset[slot] + (int)sum + __popcll(w & (bit - 1));
+}
+
+// ---------------------------------------------------------------------------------- dense map
+// [n_out, K^3] int32, written offset-minor so that consecutive lanes write consecutive entries.
+constexpr int kNbWavesPerBlock = 4;
+
+template <int K>
+__global__ void __launch_bounds__(64 * kNbWavesPerBlock)
+k_nbmap(TreeView tin, TreeView tout, int stride, int32_t* __restrict__ nbmap) {
+    constexpr int K3 = K * K * K;
+    __shared__ NbLeafLds lds_all[kNbWavesPerBlock];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int f_raw = blockIdx.x * kNbWavesPerBlock + wave;
+    const bool valid = f_raw < tout.n_leaf;
+    const int f = valid ? f_raw : tout.n_leaf - 1;  // surplus waves repeat the last leaf's set-up, write nothing
+    NbLeafLds& lds = lds_all[wave];
+    const fx_leaf* lf = tout.leaf + f;
+    const int n_act = stage_leaf<K>(tin, lf, stride, lane, lds);
     __syncthreads();
+    const int oi = lf->origin[0], oj = lf->origin[1], ok = lf->origin[2];
     const int64_t out0 = lf->offset * (int64_t)K3;
     const int total = valid ? n_act * K3 : 0;
     for (int e = lane; e < total; e += 64) {
         const int v = e / K3, kappa = e - v * K3;
-        const int loc = lds.active[v];
-        const int da = kappa / (K * K), db = (kappa / K) % K, dc = kappa % K;
-        const int qi = stride * (oi + (loc >> 6)) + D0 + da;
-        const int qj = stride * (oj + ((loc >> 3) & 7)) + D0 + db;
-        const int qk = stride * (ok + (loc & 7)) + D0 + dc;
-        const int slot = (((qi >> 3) - bi) * 3 + ((qj >> 3) - bj)) * 3 + ((qk >> 3) - bk);
-        const int n = qi & 7;
-        const uint64_t w = lds.mask[slot][n];
-        const uint64_t bit = 1ull << (((qj & 7) << 3) | (qk & 7));
-        int idx = -1;
-        if (w & bit) {
-            const uint64_t sum = n ? (lds.prefix[slot] >> (9 * (n - 1))) & 511 : 0;
-            idx = lds.offset[slot] + (int)sum + __popcll(w & (bit - 1));
-        }
-        nbmap[out0 + e] = idx;
+        nbmap[out0 + e] = lookup_entry<K>(lds, oi, oj, ok, stride, v, kappa);
     }
 }
 
 // ---------------------------------------------------------------------------------- tiled form
-struct PackLds {
-    int32_t nb[kTileT * 27];           // the tile's dense map rows (K3 <= 27 on this path)
-    uint64_t key[kTileT];              // (mask << 16 | slot), sorted
-    int32_t hash[8192];                // open addressing over input rows
-    int32_t uniq[8192];                // distinct rows, then sorted
-    uint32_t group_mask[kGroupsPerTile];
-    uint32_t group_block0[kGroupsPerTile];
-    int32_t n_uniq;
-    int32_t n_blocks;
+constexpr int kPackThreads = kTileT;          // one thread per output slot
+constexpr int kPackWaves = kPackThreads / 64;
+constexpr int kHaloHashSlots = 2048;
+
+struct PackScratch {                          // live after the lookup phase
+    uint64_t key[kTileT];                     // (mask << 16 | slot), sorted by mask
+    int32_t hash[kHaloHashSlots];
+    int32_t halo[kMaxHalo];
+    uint32_t slot_mask[kTileT];
+    uint32_t slot_base[kTileT];
 };
 
-template <typename T>
-__device__ __forceinline__ void lds_bitonic_sort(T* a, int P) {
-    // P: power of two >= number of elements (padded with the maximum value)
+struct PackLds {
+    int32_t nb[kTileT * kMaxK3Tiled];         // the tile's map entries [slot][kappa]
+    union {
+        NbLeafLds leaf[kPackWaves];           // lookup phase: one staging area per wave
+        PackScratch s;
+    } u;
+    uint32_t group_mask[kGroupsPerTile];
+    uint32_t group_block0[kGroupsPerTile];
+    uint32_t wave_sums[kPackWaves];
+    int32_t n_halo, n_blocks, overflow, f_lo, n_leaves;
+};
+
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int j) {
+    const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, j);
+    const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(v >> 32), j);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// bitonic sort of one key per thread over the whole block (ascending by thread id)
+__device__ __forceinline__ uint64_t block_sort_keys(uint64_t v, uint64_t* lds) {
+    const int tid = threadIdx.x;
+    for (int k = 2; k <= kPackThreads; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            uint64_t o;
+            if (j >= 64) {
+                lds[tid] = v;
+                __syncthreads();
+                o = lds[tid ^ j];
+                __syncthreads();
+            } else {
+                o = shfl_xor_u64(v, j);
+            }
+            const bool up = ((tid & k) == 0), lower = ((tid & j) == 0);
+            const bool take_min = (lower == up);
+            v = take_min ? (v < o ? v : o) : (v > o ? v : o);
+        }
+    }
+    return v;
+}
+
+// in-LDS bitonic sort of P (power of two) int32 values
+__device__ __forceinline__ void lds_bitonic_sort(int32_t* a, int P) {
     for (int k = 2; k <= P; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
             for (int t = threadIdx.x; t < P; t += blockDim.x) {
                 const int p = t ^ j;
                 if (p > t) {
-                    const T x = a[t], y = a[p];
+                    const int32_t x = a[t], y = a[p];
                     const bool up = ((t & k) == 0);
                     if ((x > y) == up) { a[t] = y; a[p] = x; }
                 }
@@ -128,61 +180,149 @@ __device__ __forceinline__ void lds_bitonic_sort(T* a, int P) {
     }
 }
 
-__device__ __forceinline__ uint32_t hash_row(int32_t r) { return ((uint32_t)r * 0x9E3779B1u) >> 19; }  // 13 bits
+// exclusive scan of one value per thread over the block
+__device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wave_sums, uint32_t* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) wave_sums[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kPackWaves; ++w) {
+        const uint32_t s = wave_sums[w];
+        if (w < wave) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + incl - v;
+}
 
-template <int K3>
-__global__ void __launch_bounds__(kTileT)
-k_pack_tiles(const int32_t* __restrict__ nbmap, int64_t n_out, TileHeader* __restrict__ tile_hdr,
-             uint16_t* __restrict__ tile_perm, int32_t* __restrict__ tile_rows, int row_stride,
-             uint16_t* __restrict__ tile_blocks, int block_stride, unsigned long long* __restrict__ stats) {
-    static_assert(K3 <= 27, "tiled path supports up to 27 offsets");
+// One workgroup per tile of kTileT consecutive outputs: lookups (leaf by leaf, straight into
+// LDS), mask sort, row de-duplication, block emission.  SUBM: input grid == output grid, so the
+// tile's own index range is the window; otherwise the tile is "direct".
+template <int K, bool SUBM>
+__global__ void __launch_bounds__(kPackThreads)
+k_build_tiles(TreeView tin, TreeView tout, int stride, int64_t n_out, TileHeader* __restrict__ tile_hdr,
+              uint16_t* __restrict__ tile_perm, int32_t* __restrict__ tile_rows, int row_stride,
+              uint16_t* __restrict__ tile_blocks, int block_stride, unsigned long long* __restrict__ stats) {
+    constexpr int K3 = K * K * K;
+    static_assert(K3 <= kMaxK3Tiled, "tiled path supports up to 27 offsets");
     extern __shared__ __align__(16) unsigned char lds_raw[];
     PackLds& L = *reinterpret_cast<PackLds*>(lds_raw);
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t tile = blockIdx.x;
     const int64_t o0 = tile * kTileT;
     const int n_valid = (int)min((int64_t)kTileT, n_out - o0);
 
-    // stage the tile's map rows (coalesced), clear the hash
-    for (int e = tid; e < kTileT * K3; e += kTileT) {
-        const int64_t ge = o0 * K3 + e;
-        L.nb[e] = (e < n_valid * K3) ? nbmap[ge] : -1;
+    // ---- which output leaves overlap [o0, o0 + n_valid)
+    if (tid == 0) {
+        int lo = 0, hi = tout.n_leaf;  // last leaf with offset <= o0
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (tout.leaf[mid].offset <= o0) lo = mid; else hi = mid;
+        }
+        int a = lo, b = tout.n_leaf;   // last leaf with offset < o0 + n_valid
+        while (b - a > 1) {
+            const int mid = (a + b) >> 1;
+            if (tout.leaf[mid].offset < o0 + n_valid) a = mid; else b = mid;
+        }
+        L.f_lo = lo;
+        L.n_leaves = a + 1 - lo;
+        L.n_halo = 0; L.n_blocks = 0; L.overflow = 0;
     }
-    for (int e = tid; e < 8192; e += kTileT) { L.hash[e] = -1; L.uniq[e] = INT32_MAX; }
-    if (tid == 0) { L.n_uniq = 0; L.n_blocks = 0; }
+    for (int e = tid; e < kTileT * K3; e += kPackThreads) L.nb[e] = -1;
     __syncthreads();
 
-    // neighbour mask of this thread's output; insert its input rows into the hash
+    // ---- lookups: waves take the tile's leaves round-robin
+    {
+        const int f_lo = L.f_lo, n_leaves = L.n_leaves;
+        NbLeafLds& lds = L.u.leaf[wave];
+        for (int it = 0; it * kPackWaves < n_leaves; ++it) {
+            const int li = it * kPackWaves + wave;
+            const bool valid = li < n_leaves;
+            const fx_leaf* lf = tout.leaf + (valid ? f_lo + li : f_lo);
+            const int n_act = stage_leaf<K>(tin, lf, stride, lane, lds);
+            __syncthreads();
+            if (valid) {
+                const int oi = lf->origin[0], oj = lf->origin[1], ok = lf->origin[2];
+                // voxels of this leaf that fall inside the tile
+                const int64_t first = lf->offset;
+                const int v_lo = (int)max((int64_t)0, o0 - first);
+                const int v_hi = (int)min((int64_t)n_act, o0 + n_valid - first);
+                const int slot0 = (int)(first - o0);
+                const int total = (v_hi - v_lo) * K3;
+                for (int e = lane; e < total; e += 64) {
+                    const int vv = e / K3, kappa = e - vv * K3;
+                    const int v = v_lo + vv;
+                    L.nb[(slot0 + v) * K3 + kappa] = lookup_entry<K>(lds, oi, oj, ok, stride, v, kappa);
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    // ---- per-slot mask; halo rows into the hash
+    PackScratch& S = L.u.s;
+    for (int e = tid; e < kHaloHashSlots; e += kPackThreads) S.hash[e] = -1;
+    for (int e = tid; e < kMaxHalo; e += kPackThreads) S.halo[e] = INT32_MAX;
+    __syncthreads();
+    const int32_t win_lo = SUBM ? (int32_t)o0 : 0;
+    const int32_t win_n = SUBM ? n_valid : 0;
     uint32_t mask = 0;
     for (int kappa = 0; kappa < K3; ++kappa) {
         const int32_t r = L.nb[tid * K3 + kappa];
         if (r < 0) continue;
         mask |= 1u << kappa;
-        uint32_t h = hash_row(r);
+        if (!SUBM) continue;
+        if (r >= win_lo && r < win_lo + win_n) continue;
+        uint32_t h = ((uint32_t)r * 0x9E3779B1u) >> 21;  // 11 bits
         for (;;) {
-            const int32_t cur = ((volatile int32_t*)L.hash)[h];
+            const int32_t cur = ((volatile int32_t*)S.hash)[h];
             if (cur == r) break;
             if (cur < 0) {
-                const int32_t old = atomicCAS(&L.hash[h], -1, r);
-                if (old < 0) { L.uniq[atomicAdd(&L.n_uniq, 1)] = r; break; }
+                if (((volatile int32_t*)&L.overflow)[0]) break;
+                const int32_t old = atomicCAS(&S.hash[h], -1, r);
+                if (old < 0) {
+                    const int pos = atomicAdd(&L.n_halo, 1);
+                    if (pos < kMaxHalo) S.halo[pos] = r; else L.overflow = 1;
+                    break;
+                }
                 if (old == r) break;
             }
-            h = (h + 1) & 8191;
+            h = (h + 1) & (kHaloHashSlots - 1);
         }
     }
-    L.key[tid] = ((uint64_t)mask << 16) | (uint64_t)tid;
+    S.slot_mask[tid] = mask;
     __syncthreads();
+    const bool direct = !SUBM || L.overflow != 0;
+    const int n_halo = direct ? 0 : L.n_halo;
 
-    // order outputs by mask so that a group of 16 shares its offsets; order the rows by index
-    lds_bitonic_sort(L.key, kTileT);
-    const int n_uniq = L.n_uniq;
-    int P = 2;
-    while (P < n_uniq) P <<= 1;
-    lds_bitonic_sort(L.uniq, P);
-
+    // ---- order outputs by mask; order halo rows by index; per-slot list base (direct tiles)
+    const uint64_t sorted = block_sort_keys(((uint64_t)mask << 16) | (uint64_t)tid, S.key);
+    __syncthreads();
+    S.key[tid] = sorted;
+    __syncthreads();
+    if (!direct) {
+        int P = 2;
+        while (P < n_halo) P <<= 1;
+        lds_bitonic_sort(S.halo, P);
+    }
+    uint32_t n_list;
+    {
+        uint32_t total;
+        const uint32_t base = block_scan_excl(direct ? (uint32_t)__popc(mask) : 0u, L.wave_sums, &total);
+        S.slot_base[tid] = base;
+        n_list = direct ? total : (uint32_t)n_halo;
+    }
     if (tid < kGroupsPerTile) {
         uint32_t gm = 0;
-        for (int n = 0; n < kGroup; ++n) gm |= (uint32_t)(L.key[tid * kGroup + n] >> 16);
+        for (int n = 0; n < kGroup; ++n) gm |= (uint32_t)(S.key[tid * kGroup + n] >> 16);
         L.group_mask[tid] = gm;
     }
     __syncthreads();
@@ -193,67 +333,98 @@ k_pack_tiles(const int32_t* __restrict__ nbmap, int64_t n_out, TileHeader* __res
     }
     __syncthreads();
 
-    // header, permutation, row list
+    // ---- header, permutation, row list
     TileHeader* H = tile_hdr + tile;
     if (tid == 0) {
-        H->n_rows = n_uniq; H->n_blocks = L.n_blocks; H->n_out = n_valid; H->pad = 0;
+        H->win_lo = direct ? 0 : win_lo; H->win_n = direct ? 0 : win_n; H->n_list = (int32_t)n_list;
+        H->n_blocks = L.n_blocks; H->n_out = n_valid; H->flags = direct ? kTileDirect : 0;
+        H->pad[0] = 0; H->pad[1] = 0;
         atomicAdd(&stats[0], (unsigned long long)L.n_blocks * kGroup);
-        atomicAdd(&stats[1], (unsigned long long)n_uniq);
+        atomicAdd(&stats[1], (unsigned long long)(direct ? n_list : (uint32_t)(win_n + n_halo)));
+        if (direct) atomicAdd(&stats[2], 1ull);
     }
     if (tid < kGroupsPerTile) { H->group_mask[tid] = L.group_mask[tid]; H->group_block0[tid] = L.group_block0[tid]; }
-    tile_perm[tile * kTileT + tid] = (uint16_t)(L.key[tid] & 0xFFFF);
-    for (int e = tid; e < n_uniq; e += kTileT) tile_rows[tile * row_stride + e] = L.uniq[e];
-
-    // blocks: 16 threads write one block of 16 local row ids
-    const int n_blocks = L.n_blocks;
-    const int sub = tid & 15;
-    for (int blk = tid >> 4; blk < n_blocks; blk += kTileT / 16) {
-        // group of this block: last g with group_block0[g] <= blk
-        int g = 0;
-        for (int q = 0; q < kGroupsPerTile; ++q)
-            if (L.group_mask[q] != 0 && L.group_block0[q] <= (uint32_t)blk) g = q;
-        // kappa: the (blk - block0)-th set bit of the group's mask
-        uint32_t gm = L.group_mask[g];
-        int skip = blk - (int)L.group_block0[g];
-        while (skip-- > 0) gm &= gm - 1;
-        const int kappa = __ffs(gm) - 1;
-        const int slot = (int)(L.key[g * kGroup + sub] & 0xFFFF);
-        const int32_t r = L.nb[slot * K3 + kappa];
-        uint16_t id = kNoRow;
-        if (r >= 0) {
-            int lo = 0, hi = n_uniq - 1;
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (L.uniq[mid] < r) lo = mid + 1; else hi = mid;
-            }
-            id = (uint16_t)lo;
+    tile_perm[tile * kTileT + tid] = (uint16_t)(sorted & 0xFFFF);
+    int32_t* my_rows = tile_rows + tile * (int64_t)row_stride;
+    if (direct) {
+        uint32_t pos = S.slot_base[tid];
+        for (int kappa = 0; kappa < K3; ++kappa) {
+            const int32_t r = L.nb[tid * K3 + kappa];
+            if (r >= 0) my_rows[pos++] = r;
         }
-        tile_blocks[((size_t)tile * block_stride + blk) * kGroup + sub] = id;
+    } else {
+        for (int e = tid; e < n_halo; e += kPackThreads) my_rows[e] = S.halo[e];
+    }
+
+    // ---- blocks: 16 threads per group walk the group's offsets
+    {
+        const int g = tid >> 4, sub = tid & 15;
+        const int slot = (int)(S.key[g * kGroup + sub] & 0xFFFF);
+        const uint32_t smask = S.slot_mask[slot];
+        const uint32_t sbase = S.slot_base[slot];
+        uint32_t gm = L.group_mask[g];
+        size_t blk = (size_t)tile * block_stride + L.group_block0[g];
+        while (gm) {
+            const int kappa = __ffs(gm) - 1;
+            gm &= gm - 1;
+            uint16_t id = kNoRow;
+            if ((smask >> kappa) & 1u) {
+                if (direct) {
+                    id = (uint16_t)(sbase + __popc(smask & ((1u << kappa) - 1u)));
+                } else {
+                    const int32_t r = L.nb[slot * K3 + kappa];
+                    if (r >= win_lo && r < win_lo + win_n) {
+                        id = (uint16_t)(r - win_lo);
+                    } else {
+                        int lo = 0, hi = n_halo - 1;
+                        while (lo < hi) {
+                            const int mid = (lo + hi) >> 1;
+                            if (S.halo[mid] < r) lo = mid + 1; else hi = mid;
+                        }
+                        id = (uint16_t)(win_n + lo);
+                    }
+                }
+            }
+            tile_blocks[blk * kGroup + sub] = id;
+            ++blk;
+        }
     }
 }
 
-// decode the tiled form back into the dense table
-__global__ void k_tiles_to_dense(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
-                                 const int32_t* __restrict__ tile_rows, int row_stride,
-                                 const uint16_t* __restrict__ tile_blocks, int block_stride, int K3,
-                                 int32_t* __restrict__ nbmap) {
+// global input row of a tile-local id
+__device__ __forceinline__ int32_t tile_global_row(const TileHeader* H, const int32_t* rows, uint32_t id) {
+    return id < (uint32_t)H->win_n ? H->win_lo + (int32_t)id : rows[id - (uint32_t)H->win_n];
+}
+
+// decode the tiled form back into the dense table and / or count pairs per offset
+__global__ void __launch_bounds__(kTileT)
+k_tiles_to_dense(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
+                 const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
+                 int block_stride, int K3, int32_t* __restrict__ nbmap, unsigned long long* __restrict__ pairs) {
+    __shared__ unsigned int cnt[32];
+    if (threadIdx.x < 32) cnt[threadIdx.x] = 0;
+    __syncthreads();
     const int64_t tile = blockIdx.x;
     const TileHeader* H = tile_hdr + tile;
-    const int n_blocks = H->n_blocks, n_valid = H->n_out;
-    const int sub = threadIdx.x & 15;
-    for (int blk = threadIdx.x >> 4; blk < n_blocks; blk += blockDim.x / 16) {
-        int g = 0;
-        for (int q = 0; q < kGroupsPerTile; ++q)
-            if (H->group_mask[q] != 0 && H->group_block0[q] <= (uint32_t)blk) g = q;
-        uint32_t gm = H->group_mask[g];
-        int skip = blk - (int)H->group_block0[g];
-        while (skip-- > 0) gm &= gm - 1;
+    const int n_valid = H->n_out;
+    const int g = threadIdx.x >> 4, sub = threadIdx.x & 15;   // blockDim.x == kTileT: one thread per slot
+    const int local = tile_perm[tile * kTileT + g * kGroup + sub];
+    uint32_t gm = H->group_mask[g];
+    size_t blk = (size_t)tile * block_stride + H->group_block0[g];
+    const int32_t* rows = tile_rows + tile * (int64_t)row_stride;
+    while (gm) {
         const int kappa = __ffs(gm) - 1;
-        const int local = tile_perm[tile * kTileT + g * kGroup + sub];
-        const uint16_t id = tile_blocks[((size_t)tile * block_stride + blk) * kGroup + sub];
-        if (id != kNoRow && local < n_valid)
-            nbmap[(tile * kTileT + local) * K3 + kappa] = tile_rows[tile * row_stride + id];
+        gm &= gm - 1;
+        const uint16_t id = tile_blocks[blk * kGroup + sub];
+        ++blk;
+        if (id != kNoRow && local < n_valid) {
+            if (nbmap) nbmap[(tile * kTileT + local) * K3 + kappa] = tile_global_row(H, rows, id);
+            if (pairs) atomicAdd(&cnt[kappa], 1u);
+        }
     }
+    __syncthreads();
+    if (pairs && threadIdx.x < K3 && cnt[threadIdx.x])
+        atomicAdd(&pairs[threadIdx.x], (unsigned long long)cnt[threadIdx.x]);
 }
 
 __global__ void k_fill_i32(int32_t* __restrict__ p, int64_t n, int32_t v) {
@@ -261,7 +432,7 @@ __global__ void k_fill_i32(int32_t* __restrict__ p, int64_t n, int32_t v) {
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) p[e] = v;
 }
 
-// pairs per offset from the dense table (statistics only)
+// pairs per offset from the dense table (maps that are not tiled)
 __global__ void k_pair_counts(const int32_t* __restrict__ nbmap, int64_t n_out, int K3,
                               unsigned long long* __restrict__ pairs) {
     __shared__ unsigned int cnt[128];
@@ -278,6 +449,36 @@ __global__ void k_pair_counts(const int32_t* __restrict__ nbmap, int64_t n_out, 
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// dense [n_out, K3] table computed by the leaf-centric lookup kernel
+static hipError_t launch_nbmap(const fx_kmap* km, int32_t* d_nbmap, hipStream_t st) {
+    if (km->gout->hdr.n_leaf == 0) return hipSuccess;
+    const unsigned nb = (unsigned)((km->gout->hdr.n_leaf + kNbWavesPerBlock - 1) / kNbWavesPerBlock);
+    const TreeView tin = km->gin->view(), tout = km->gout->view();
+    ProfScope ps(kProfNbmap, st);
+    switch (km->K) {
+        case 1: k_nbmap<1><<<nb, 64 * kNbWavesPerBlock, 0, st>>>(tin, tout, km->stride, d_nbmap); break;
+        case 2: k_nbmap<2><<<nb, 64 * kNbWavesPerBlock, 0, st>>>(tin, tout, km->stride, d_nbmap); break;
+        case 3: k_nbmap<3><<<nb, 64 * kNbWavesPerBlock, 0, st>>>(tin, tout, km->stride, d_nbmap); break;
+        default: k_nbmap<5><<<nb, 64 * kNbWavesPerBlock, 0, st>>>(tin, tout, km->stride, d_nbmap); break;
+    }
+    return hipGetLastError();
+}
+
+// The scalar convolution reads the dense table; it is built on first use.
+fx_status kmap_ensure_dense(fx_kmap* km, hipStream_t st) {
+    if (km->d_nbmap || km->n_out == 0) return FX_OK;
+    void* p = nullptr;
+    FX_TRY(dev_alloc(&p, sizeof(int32_t) * (size_t)(km->n_out * km->K3), st));
+    hipError_t e = launch_nbmap(km, (int32_t*)p, st);
+    if (e != hipSuccess) {
+        dev_free(p, st);
+        set_error("dense kernel-map build failed: %s", hipGetErrorString(e));
+        return FX_EDEVICE;
+    }
+    km->d_nbmap = (int32_t*)p;
+    return FX_OK;
+}
+
 }  // namespace fx
 
 using namespace fx;
@@ -286,6 +487,7 @@ extern "C" void fx_kmap_destroy(fx_kmap* km) {
     if (!km) return;
     if (km->refs.fetch_sub(1) != 1) return;
     if (km->d_alloc) dev_free(km->d_alloc, km->stream);
+    if (km->d_nbmap) dev_free(km->d_nbmap, km->stream);
     if (km->gin) fx_grid_destroy(km->gin);
     if (km->gout) fx_grid_destroy(km->gout);
     free(km->h_pairs);
@@ -311,25 +513,23 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     km->K = K; km->stride = stride; km->K3 = K * K * K;
     km->n_in = g_in->hdr.n_voxels; km->n_out = gout->hdr.n_voxels;
     km->h_pairs = (int64_t*)calloc((size_t)km->K3, sizeof(int64_t));
-    const bool tiled = km->K3 <= 27;
+    const bool tiled = km->K3 <= kMaxK3Tiled;
     km->n_tiles = tiled ? (km->n_out + kTileT - 1) / kTileT : 0;
-    km->row_stride = (int32_t)std::min<int64_t>((int64_t)kTileT * km->K3, std::max<int64_t>(km->n_in, 1));
+    km->row_stride = kTileT * km->K3;
     km->block_stride = kGroupsPerTile * km->K3;
 
-    // one allocation: dense map | stats | tile headers | perm | rows | blocks
+    // one allocation: stats | tile headers | perm | rows | blocks
+    const size_t nt = (size_t)std::max<int64_t>(km->n_tiles, 1);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-    const size_t o_nb = take(sizeof(int32_t) * (size_t)std::max<int64_t>(km->n_out * km->K3, 1));
     const size_t o_st = take(sizeof(int64_t) * (size_t)(4 + km->K3));
-    const size_t o_th = take(sizeof(TileHeader) * (size_t)std::max<int64_t>(km->n_tiles, 1));
-    const size_t o_tp = take(sizeof(uint16_t) * kTileT * (size_t)std::max<int64_t>(km->n_tiles, 1));
-    const size_t o_tr = take(sizeof(int32_t) * (size_t)km->row_stride * (size_t)std::max<int64_t>(km->n_tiles, 1));
-    const size_t o_tb = take(sizeof(uint16_t) * kGroup * (size_t)km->block_stride *
-                             (size_t)std::max<int64_t>(km->n_tiles, 1));
+    const size_t o_th = take(sizeof(TileHeader) * nt);
+    const size_t o_tp = take(sizeof(uint16_t) * kTileT * nt);
+    const size_t o_tr = take(tiled ? sizeof(int32_t) * (size_t)km->row_stride * nt : 0);
+    const size_t o_tb = take(tiled ? sizeof(uint16_t) * kGroup * (size_t)km->block_stride * nt : 0);
     fx_status rc = dev_alloc(&km->d_alloc, off, st);
     if (rc != FX_OK) { fx_kmap_destroy(km); return rc; }
     char* p = (char*)km->d_alloc;
-    km->d_nbmap = (int32_t*)(p + o_nb);
     km->d_stats = (int64_t*)(p + o_st);
     km->d_tile_hdr = (TileHeader*)(p + o_th);
     km->d_tile_perm = (uint16_t*)(p + o_tp);
@@ -337,42 +537,37 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     km->d_tile_blocks = (uint16_t*)(p + o_tb);
 
     hipError_t e = hipMemsetAsync(km->d_stats, 0, sizeof(int64_t) * (size_t)(4 + km->K3), st);
-    if (e == hipSuccess && gout->hdr.n_leaf > 0) {
-        const unsigned nb = (unsigned)((gout->hdr.n_leaf + kNbWavesPerBlock - 1) / kNbWavesPerBlock);
-        const TreeView tin = g_in->view(), tout = gout->view();
-        ProfScope ps(kProfNbmap, st);
-        switch (K) {
-            case 1: k_nbmap<1><<<nb, 64 * kNbWavesPerBlock, 0, st>>>(tin, tout, stride, km->d_nbmap); break;
-            case 2: k_nbmap<2><<<nb, 64 * kNbWavesPerBlock, 0, st>>>(tin, tout, stride, km->d_nbmap); break;
-            case 3: k_nbmap<3><<<nb, 64 * kNbWavesPerBlock, 0, st>>>(tin, tout, stride, km->d_nbmap); break;
-            default: k_nbmap<5><<<nb, 64 * kNbWavesPerBlock, 0, st>>>(tin, tout, stride, km->d_nbmap); break;
-        }
-        e = hipGetLastError();
-    }
     if (e == hipSuccess && km->n_tiles > 0) {
         unsigned long long* stats = (unsigned long long*)km->d_stats;
         const size_t lds = sizeof(PackLds);
-        const unsigned nt = (unsigned)km->n_tiles;
+        const unsigned ntl = (unsigned)km->n_tiles;
+        const TreeView tin = g_in->view(), tout = gout->view();
         ProfScope ps(kProfPackTiles, st);
-#define FX_PACK(K3V)                                                                                         \
-    do {                                                                                                     \
-        e = hipFuncSetAttribute((const void*)k_pack_tiles<K3V>, hipFuncAttributeMaxDynamicSharedMemorySize,  \
-                                (int)lds);                                                                   \
-        if (e == hipSuccess)                                                                                 \
-            k_pack_tiles<K3V><<<nt, kTileT, lds, st>>>(km->d_nbmap, km->n_out, km->d_tile_hdr,               \
-                                                       km->d_tile_perm, km->d_tile_rows, km->row_stride,     \
-                                                       km->d_tile_blocks, km->block_stride, stats);          \
+#define FX_TILES(KV, SUBMV)                                                                                    \
+    do {                                                                                                       \
+        e = hipFuncSetAttribute((const void*)k_build_tiles<KV, SUBMV>,                                         \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                         \
+        if (e == hipSuccess)                                                                                   \
+            k_build_tiles<KV, SUBMV><<<ntl, kPackThreads, lds, st>>>(tin, tout, stride, km->n_out,             \
+                                                                     km->d_tile_hdr, km->d_tile_perm,          \
+                                                                     km->d_tile_rows, km->row_stride,          \
+                                                                     km->d_tile_blocks, km->block_stride,      \
+                                                                     stats);                                   \
     } while (0)
-        if (km->K3 == 1) FX_PACK(1);
-        else if (km->K3 == 8) FX_PACK(8);
-        else FX_PACK(27);
-#undef FX_PACK
+        if (K == 1) FX_TILES(1, true);
+        else if (K == 2) FX_TILES(2, false);
+        else FX_TILES(3, true);
+#undef FX_TILES
         if (e == hipSuccess) e = hipGetLastError();
     }
     if (e != hipSuccess) {
         set_error("kernel-map build failed: %s", hipGetErrorString(e));
         fx_kmap_destroy(km);
         return FX_EDEVICE;
+    }
+    if (!tiled) {
+        rc = kmap_ensure_dense(km, st);
+        if (rc != FX_OK) { fx_kmap_destroy(km); return rc; }
     }
     *g_out = gout;
     fx_grid_retain(gout);
@@ -385,7 +580,12 @@ static fx_status kmap_fetch_stats(fx_kmap* km) {
     hipStream_t st = km->stream;
     unsigned long long* pairs = (unsigned long long*)(km->d_stats + 4);
     FX_HIP_TRY(hipMemsetAsync(pairs, 0, sizeof(int64_t) * (size_t)km->K3, st));
-    if (km->n_out > 0) {
+    if (km->n_tiles > 0) {
+        k_tiles_to_dense<<<(unsigned)km->n_tiles, kTileT, 0, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,
+                                                                  km->row_stride, km->d_tile_blocks, km->block_stride,
+                                                                  km->K3, nullptr, pairs);
+        FX_HIP_TRY(hipGetLastError());
+    } else if (km->n_out > 0) {
         const int64_t total = km->n_out * km->K3;
         const unsigned nb = (unsigned)std::min<int64_t>((total + 256 * 16 - 1) / (256 * 16), 4096);
         k_pair_counts<<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, pairs);
@@ -434,9 +634,9 @@ extern "C" fx_status fx_kmap_dense(const fx_kmap* km, int32_t* d_nbmap, void* st
     if (km->n_tiles > 0) {
         const unsigned nb = (unsigned)std::min<int64_t>((total + 256 * 8 - 1) / (256 * 8), 8192);
         k_fill_i32<<<nb, 256, 0, st>>>(d_nbmap, total, -1);
-        k_tiles_to_dense<<<(unsigned)km->n_tiles, 256, 0, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,
-                                                               km->row_stride, km->d_tile_blocks, km->block_stride,
-                                                               km->K3, d_nbmap);
+        k_tiles_to_dense<<<(unsigned)km->n_tiles, kTileT, 0, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,
+                                                                  km->row_stride, km->d_tile_blocks, km->block_stride,
+                                                                  km->K3, d_nbmap, nullptr);
         FX_HIP_TRY(hipGetLastError());
     } else {
         FX_HIP_TRY(hipMemcpyAsync(d_nbmap, km->d_nbmap, sizeof(int32_t) * (size_t)total, hipMemcpyDeviceToDevice, st));

@@ -42,7 +42,7 @@ def test_mfma_path_deep_channels():
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("c_in,c_out", [(64, 192), (128, 64), (48, 40), (8, 16)])
+@pytest.mark.parametrize("c_in,c_out", [(64, 192), (128, 64), (32, 64), (48, 40), (8, 16)])
 def test_channel_shapes_mfma_and_scalar(dtype, c_in, c_out):
     y, ref, dt, k3, ci = _run(G.workload("sheets_small"), c_in=c_in, c_out=c_out, dtype=dtype)
     H.conv_tolerance_check(y, ref, dt, k3, ci)
@@ -86,6 +86,18 @@ def test_scalar_and_mfma_paths_agree_with_oracle_on_empty_and_tiny_grids():
     g, og = H.both_grids(pts, np.array([[0, 4]], np.int64))
     km = fx.build_kernel_map(g, 3, 1)
     feat, wt = G.features_and_weights(7, 4, 64, 64, 27, "bf16")
+    y = fx.sparse_conv_fwd(km, H.to_device_storage(feat, "bf16"), H.to_device_storage(wt, "bf16"))
+    H.conv_tolerance_check(y.float().cpu().numpy(), O.conv(og, og, 3, 1, feat, wt), "bf16", 27, 64)
+
+
+def test_dense_block_uses_rows_beyond_the_lds_budget():
+    # a dense 24^3 block: every tile is one full leaf whose 10^3 footprint has more distinct
+    # input rows than the convolution stages in LDS, so part of them is read from global memory
+    a = np.arange(24, dtype=np.int32)
+    pts = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3)
+    g, og = H.both_grids(pts, np.array([[0, pts.shape[0]]]))
+    km = fx.build_kernel_map(g, 3, 1)
+    feat, wt = G.features_and_weights(11, og.num_voxels, 64, 64, 27, "bf16")
     y = fx.sparse_conv_fwd(km, H.to_device_storage(feat, "bf16"), H.to_device_storage(wt, "bf16"))
     H.conv_tolerance_check(y.float().cpu().numpy(), O.conv(og, og, 3, 1, feat, wt), "bf16", 27, 64)
 
