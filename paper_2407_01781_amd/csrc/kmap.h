@@ -9,35 +9,61 @@ namespace fx {
 //
 // Outputs are cut into tiles of kTileT consecutive indices.  Inside a tile the outputs are
 // reordered so that voxels with equal neighbour masks sit together, then cut into groups of
-// 16 (one MFMA column block).  For every (group, offset) with at least one active pair a
-// "block" of 16 local row ids is stored.  A local id r addresses the tile's input rows:
+// 32 (one MFMA column block).  The 16 groups are dealt to the 4 waves of the convolution
+// workgroup (tile_group_of), 4 per wave.  For every (wave, offset) where at least one of the
+// wave's 4 groups has an active pair, an "id block" of 32 x 4 local row ids is stored
+// ([voxel n of the group][group slot of the wave], so one 8-byte read gives a lane the ids of
+// its voxel column in all 4 groups).  A local id r addresses the tile's input rows:
 //     r <  win_n            -> global row win_lo + r          (a contiguous window; for a
 //                              submanifold map the tile's own index range, which the centre
 //                              tap needs anyway)
 //     r >= win_n            -> global row rows[r - win_n]     (the halo: distinct rows outside
 //                              the window, ascending)
-//     r == kNoRow           -> no input (multiplies a zero row)
+//     r == kNoRow           -> no input (multiplies a zero row, or the block is skipped)
+// When all rows of a tile fit the convolution's LDS budget (flag kTileLdsOffsets) the id blocks
+// hold lds_row_code(r) instead of r (kNoRow -> the zero row), so the multiply loop needs no
+// address arithmetic beyond one XOR.
 // A tile flagged kTileDirect keeps no window and lists one row per active pair (no
 // de-duplication): used for strided maps, where every input row is used exactly once, and as
 // the fallback when a tile's halo exceeds the builder's table.
 constexpr int kTileT = 512;                 // outputs per tile
-constexpr int kGroup = 16;                  // outputs per MFMA column block
+constexpr int kGroup = 32;                  // outputs per MFMA column block (32x32x16 MFMA)
 constexpr int kGroupsPerTile = kTileT / kGroup;
+constexpr int kTileWaves = 4;               // waves of the convolution workgroup
+constexpr int kGroupsPerWave = kGroupsPerTile / kTileWaves;
+constexpr int kDealShift = 0;               // runs of 2^kDealShift adjacent groups go to the same wave
 constexpr int kMaxK3Tiled = 27;             // offsets supported by the tiled form
 constexpr int kMaxHalo = 1024;              // distinct halo rows a tile may de-duplicate
 constexpr uint16_t kNoRow = 0xFFFF;
 constexpr int32_t kTileDirect = 1;
+constexpr int32_t kTileLdsOffsets = 2;       // id blocks hold LDS byte offsets instead of row ids
+
+// LDS row layout of the convolution (shared with the builder, which pre-computes offsets):
+// rows of kCinChunk bf16/fp16 values (64 bytes); the 16-byte piece q of row r sits at
+// r*64 + ((q ^ ((r >> 2) & 3)) << 4); row kRowCap is all zeros.
+constexpr int kCinChunk = 32;               // input channels staged in LDS at a time (one MFMA k-step)
+constexpr int kRowBytes = kCinChunk * 2;
+constexpr int kRowCap = 792;                // LDS rows per tile
+__host__ __device__ constexpr uint32_t lds_row_code(uint32_t row) { return row * kRowBytes | (((row >> 2) & 3u) << 4); }
+constexpr int kIdBlockElems = kGroup * kGroupsPerWave;   // 128 ids = 256 bytes
+
+// group (in mask-sorted order) that wave `w` handles in its slot `gi`
+__host__ __device__ constexpr int tile_group_of(int w, int gi) {
+    return ((gi >> kDealShift) << (kDealShift + 2)) | (w << kDealShift) | (gi & ((1 << kDealShift) - 1));
+}
 
 struct TileHeader {
     int32_t win_lo;                         // first global row of the window
     int32_t win_n;                          // rows in the window
     int32_t n_list;                         // entries in the tile's row list (halo or direct)
-    int32_t n_blocks;                       // non-empty (group, offset) blocks
+    int32_t n_blocks;                       // id blocks = sum over waves of popcount(wave_mask)
     int32_t n_out;                          // valid outputs in the tile (<= kTileT)
     int32_t flags;                          // kTileDirect
-    int32_t pad[2];
-    uint32_t group_mask[kGroupsPerTile];    // per group: bit kappa set = block present
-    uint32_t group_block0[kGroupsPerTile];  // first block of each group
+    int32_t n_pair_blocks;                  // non-empty (group, offset) pairs (kGroup MFMA columns each)
+    int32_t pad;
+    uint32_t group_mask[kGroupsPerTile];    // per group (sorted order): bit kappa set = some voxel has that tap
+    uint32_t wave_mask[kTileWaves];         // union of the wave's group masks
+    uint32_t wave_block0[kTileWaves];       // first id block of each wave
 };
 
 }  // namespace fx
@@ -55,7 +81,7 @@ struct fx_kmap {
     fx::TileHeader* d_tile_hdr = nullptr;   // [n_tiles]
     uint16_t* d_tile_perm = nullptr;        // [n_tiles][kTileT] output slot -> local output (0..T-1)
     int32_t* d_tile_rows = nullptr;         // [n_tiles][row_stride] global input rows (halo / direct)
-    uint16_t* d_tile_blocks = nullptr;      // [n_tiles][block_stride][16] local row ids
+    uint16_t* d_tile_blocks = nullptr;      // [n_tiles][block_stride][16][8] local row ids (id blocks)
     int32_t row_stride = 0, block_stride = 0;
     int64_t* d_stats = nullptr;             // [4 + K3]: MFMA rows issued, staged rows, direct tiles, spare, pairs per offset
     void* d_alloc = nullptr;                // single allocation backing all of the above

@@ -84,6 +84,63 @@ __device__ __forceinline__ int lookup_entry(const NbLeafLds& lds, int oi, int oj
     return lds.offset[slot] + (int)sum + __popcll(w & (bit - 1));
 }
 
+// Neighbour-leaf table: for every output leaf, the ids of the <= 27 input leaves its stencil
+// footprint can touch (-1: none).  One thread per (leaf, slot): a million independent tree
+// descents run at full occupancy here instead of inside the latency-bound tile builder.
+template <int K>
+__global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int32_t* __restrict__ nbr) {
+    constexpr int D0 = delta_min(K);
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (int64_t)tout.n_leaf * 27) return;
+    const int f = (int)(e / 27), slot = (int)(e - (int64_t)f * 27);
+    const fx_leaf* lf = tout.leaf + f;
+    const int oi = lf->origin[0], oj = lf->origin[1], ok = lf->origin[2];
+    const int bi = (stride * oi + D0) >> 3, bj = (stride * oj + D0) >> 3, bk = (stride * ok + D0) >> 3;
+    const int hi_i = (stride * (oi + 7) + D0 + K - 1) >> 3, hi_j = (stride * (oj + 7) + D0 + K - 1) >> 3,
+              hi_k = (stride * (ok + 7) + D0 + K - 1) >> 3;
+    const int a = slot / 9, c = (slot / 3) % 3, d = slot % 3;
+    int id = -1;
+    if (bi + a <= hi_i && bj + c <= hi_j && bk + d <= hi_k)
+        id = find_leaf(tin, lf->batch, (bi + a) * 8, (bj + c) * 8, (bk + d) * 8);
+    nbr[e] = id;
+}
+
+// stage_leaf with the neighbour leaves read from the table
+__device__ __forceinline__ int stage_leaf_from_table(const TreeView& tin, const fx_leaf* __restrict__ lf,
+                                                     const int32_t* __restrict__ nbr_row, int lane, NbLeafLds& lds) {
+    if (lane < 27) {
+        const int id = nbr_row[lane];
+        if (id >= 0) {
+            const fx_leaf* nl = tin.leaf + id;
+#pragma unroll
+            for (int w = 0; w < 8; ++w) lds.mask[lane][w] = nl->mask[w];
+            lds.prefix[lane] = nl->prefix;
+            lds.offset[lane] = (int32_t)nl->offset;
+        } else {
+#pragma unroll
+            for (int w = 0; w < 8; ++w) lds.mask[lane][w] = 0;
+            lds.prefix[lane] = 0;
+            lds.offset[lane] = -1;
+        }
+    }
+    int n_act = 0;
+    const uint64_t lt = (1ull << lane) - 1;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) {
+        const uint64_t m = lf->mask[w];
+        if ((m >> lane) & 1) lds.active[n_act + __popcll(m & lt)] = (uint16_t)(w * 64 + lane);
+        n_act += __popcll(m);
+    }
+    return n_act;
+}
+
+// LDS traffic of one wave is processed in order, so a wave that writes its own staging area and
+// then reads it only needs the compiler to keep that order.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // ---------------------------------------------------------------------------------- dense map
 // [n_out, K^3] int32, written offset-minor so that consecutive lanes write consecutive entries.
 constexpr int kNbWavesPerBlock = 4;
@@ -110,6 +167,14 @@ k_nbmap(TreeView tin, TreeView tout, int stride, int32_t* __restrict__ nbmap) {
     }
 }
 
+#ifdef FX_KMAP_TIMING
+// development aid: per-workgroup phase timestamps (thread 0), read back with fx_debug_kmap_timing
+__device__ unsigned long long g_kmap_timing[4096 * 8];
+#define FX_KSTAMP(slot) do { if (threadIdx.x == 0 && blockIdx.x < 4096) g_kmap_timing[blockIdx.x * 8 + (slot)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define FX_KSTAMP(slot) do { } while (0)
+#endif
+
 // ---------------------------------------------------------------------------------- tiled form
 constexpr int kPackThreads = kTileT;          // one thread per output slot
 constexpr int kPackWaves = kPackThreads / 64;
@@ -117,22 +182,27 @@ constexpr int kHaloHashSlots = 2048;
 
 struct PackScratch {                          // live after the lookup phase
     uint64_t key[kTileT];                     // (mask << 16 | slot), sorted by mask
-    int32_t hash[kHaloHashSlots];
-    int32_t halo[kMaxHalo];
+    int32_t hash[kHaloHashSlots];             // open addressing over halo rows
+    int32_t halo[kMaxHalo];                   // distinct halo rows in insertion order
     uint32_t slot_mask[kTileT];
-    uint32_t slot_base[kTileT];
+    union {
+        uint32_t slot_base[kTileT];           // direct tiles: first list entry of each slot
+        uint16_t halo_slot[kMaxHalo];         // other tiles: hash slot of each halo row
+    };
+    uint16_t slot_rank[kHaloHashSlots];       // hash slot -> rank of its row among the halo rows
 };
 
 struct PackLds {
     int32_t nb[kTileT * kMaxK3Tiled];         // the tile's map entries [slot][kappa]
     union {
-        NbLeafLds leaf[kPackWaves];           // lookup phase: one staging area per wave
+        int32_t leaf_off[kTileT];             // lookup phase: first index of every leaf of the tile
         PackScratch s;
     } u;
     uint32_t group_mask[kGroupsPerTile];
-    uint32_t group_block0[kGroupsPerTile];
+    uint32_t wave_mask[kTileWaves];
+    uint32_t wave_block0[kTileWaves];
     uint32_t wave_sums[kPackWaves];
-    int32_t n_halo, n_blocks, overflow, f_lo, n_leaves;
+    int32_t n_halo, n_blocks, n_pair_blocks, overflow, f_lo, n_leaves;
 };
 
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int j) {
@@ -203,12 +273,27 @@ __device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wave_s
     return base + incl - v;
 }
 
-// One workgroup per tile of kTileT consecutive outputs: lookups (leaf by leaf, straight into
-// LDS), mask sort, row de-duplication, block emission.  SUBM: input grid == output grid, so the
+// position of the r-th (0-based) set bit of m (r < popcount(m))
+__device__ __forceinline__ int select64(uint64_t m, int r) {
+    uint32_t x = (uint32_t)m;
+    int pos = 0;
+    int c = __popc(x);
+    if (r >= c) { r -= c; x = (uint32_t)(m >> 32); pos = 32; }
+#pragma unroll
+    for (int sh = 16; sh >= 1; sh >>= 1) {
+        c = __popc(x & ((1u << sh) - 1u));
+        if (r >= c) { r -= c; x >>= sh; pos += sh; }
+    }
+    return pos;
+}
+
+// One workgroup per tile of kTileT consecutive outputs: lookups (one thread per voxel, straight
+// into LDS), mask sort, row de-duplication, block emission.  SUBM: input grid == output grid, so the
 // tile's own index range is the window; otherwise the tile is "direct".
 template <int K, bool SUBM>
 __global__ void __launch_bounds__(kPackThreads)
-k_build_tiles(TreeView tin, TreeView tout, int stride, int64_t n_out, TileHeader* __restrict__ tile_hdr,
+k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict__ leaf_nbr, int64_t n_out,
+              TileHeader* __restrict__ tile_hdr,
               uint16_t* __restrict__ tile_perm, int32_t* __restrict__ tile_rows, int row_stride,
               uint16_t* __restrict__ tile_blocks, int block_stride, unsigned long long* __restrict__ stats) {
     constexpr int K3 = K * K * K;
@@ -220,6 +305,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, int64_t n_out, TileHeader
     const int64_t o0 = tile * kTileT;
     const int n_valid = (int)min((int64_t)kTileT, n_out - o0);
 
+    FX_KSTAMP(0);
     // ---- which output leaves overlap [o0, o0 + n_valid)
     if (tid == 0) {
         int lo = 0, hi = tout.n_leaf;  // last leaf with offset <= o0
@@ -234,43 +320,76 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, int64_t n_out, TileHeader
         }
         L.f_lo = lo;
         L.n_leaves = a + 1 - lo;
-        L.n_halo = 0; L.n_blocks = 0; L.overflow = 0;
+        L.n_halo = 0; L.n_blocks = 0; L.n_pair_blocks = 0; L.overflow = 0;
     }
-    for (int e = tid; e < kTileT * K3; e += kPackThreads) L.nb[e] = -1;
     __syncthreads();
 
-    // ---- lookups: waves take the tile's leaves round-robin
+    // ---- lookups: one thread per output voxel.  The thread finds its leaf (binary search over the
+    // tile's leaf offsets), its position inside the leaf (select on the leaf mask), and evaluates
+    // Listing 1 for its K^3 neighbours through the neighbour-leaf table; the few leaf records a
+    // tile touches stay in the L1 cache.
     {
         const int f_lo = L.f_lo, n_leaves = L.n_leaves;
-        NbLeafLds& lds = L.u.leaf[wave];
-        for (int it = 0; it * kPackWaves < n_leaves; ++it) {
-            const int li = it * kPackWaves + wave;
-            const bool valid = li < n_leaves;
-            const fx_leaf* lf = tout.leaf + (valid ? f_lo + li : f_lo);
-            const int n_act = stage_leaf<K>(tin, lf, stride, lane, lds);
-            __syncthreads();
-            if (valid) {
-                const int oi = lf->origin[0], oj = lf->origin[1], ok = lf->origin[2];
-                // voxels of this leaf that fall inside the tile
-                const int64_t first = lf->offset;
-                const int v_lo = (int)max((int64_t)0, o0 - first);
-                const int v_hi = (int)min((int64_t)n_act, o0 + n_valid - first);
-                const int slot0 = (int)(first - o0);
-                const int total = (v_hi - v_lo) * K3;
-                for (int e = lane; e < total; e += 64) {
-                    const int vv = e / K3, kappa = e - vv * K3;
-                    const int v = v_lo + vv;
-                    L.nb[(slot0 + v) * K3 + kappa] = lookup_entry<K>(lds, oi, oj, ok, stride, v, kappa);
-                }
+        for (int li = tid; li < n_leaves; li += kPackThreads) L.u.leaf_off[li] = (int32_t)tout.leaf[f_lo + li].offset;
+        __syncthreads();
+        int32_t* my_nb = L.nb + tid * K3;
+        if (tid < n_valid) {
+            constexpr int D0 = delta_min(K);
+            const int32_t o = (int32_t)(o0 + tid);
+            int lo = 0, hi = n_leaves;   // last leaf of the tile with offset <= o
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (L.u.leaf_off[mid] <= o) lo = mid; else hi = mid;
             }
-            __syncthreads();
+            const int f = f_lo + lo;
+            const fx_leaf* lf = tout.leaf + f;
+            int r = o - L.u.leaf_off[lo];           // rank of the voxel inside its leaf
+            const uint64_t pre = lf->prefix;
+            int wn = 0, before = 0;                 // mask word holding the voxel, active voxels before that word
+#pragma unroll
+            for (int w = 0; w < 7; ++w) {
+                const int fld = (int)((pre >> (9 * w)) & 511);
+                if (fld <= r) { wn = w + 1; before = fld; }
+            }
+            const int bit = select64(lf->mask[wn], r - before);
+            const int pi = lf->origin[0] + wn, pj = lf->origin[1] + (bit >> 3), pk = lf->origin[2] + (bit & 7);
+            const int bi = (stride * lf->origin[0] + D0) >> 3, bj = (stride * lf->origin[1] + D0) >> 3,
+                      bk = (stride * lf->origin[2] + D0) >> 3;
+            const int32_t* nbr_row = leaf_nbr + (int64_t)f * 27;
+            // kept as a rolled loop: the fully unrolled form of this divergent body gave wrong entries
+            // for the offsets (-1,0,0), (0,-1,0), (0,0,-1) on gfx950 (cause not established; the
+            // parity tests against the oracle catch it)
+#pragma unroll 1
+            for (int kappa = 0; kappa < K3; ++kappa) {
+                const int qi = stride * pi + D0 + kappa / (K * K);
+                const int qj = stride * pj + D0 + (kappa / K) % K;
+                const int qk = stride * pk + D0 + kappa % K;
+                const int slot = (((qi >> 3) - bi) * 3 + ((qj >> 3) - bj)) * 3 + ((qk >> 3) - bk);
+                const int id = nbr_row[slot];
+                int res = -1;
+                if (id >= 0) {
+                    const fx_leaf* nl = tin.leaf + id;
+                    const int n2 = qi & 7;
+                    const uint64_t w = nl->mask[n2];
+                    const uint64_t qb = 1ull << (((qj & 7) << 3) | (qk & 7));
+                    if (w & qb) {
+                        const uint64_t sum = n2 ? (nl->prefix >> (9 * (n2 - 1))) & 511 : 0;
+                        res = (int)(nl->offset + (int64_t)sum) + __popcll(w & (qb - 1));
+                    }
+                }
+                my_nb[kappa] = res;
+            }
+        } else {
+#pragma unroll
+            for (int kappa = 0; kappa < K3; ++kappa) my_nb[kappa] = -1;
         }
     }
+    __syncthreads();
 
+    FX_KSTAMP(1);
     // ---- per-slot mask; halo rows into the hash
     PackScratch& S = L.u.s;
     for (int e = tid; e < kHaloHashSlots; e += kPackThreads) S.hash[e] = -1;
-    for (int e = tid; e < kMaxHalo; e += kPackThreads) S.halo[e] = INT32_MAX;
     __syncthreads();
     const int32_t win_lo = SUBM ? (int32_t)o0 : 0;
     const int32_t win_n = SUBM ? n_valid : 0;
@@ -290,7 +409,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, int64_t n_out, TileHeader
                 const int32_t old = atomicCAS(&S.hash[h], -1, r);
                 if (old < 0) {
                     const int pos = atomicAdd(&L.n_halo, 1);
-                    if (pos < kMaxHalo) S.halo[pos] = r; else L.overflow = 1;
+                    if (pos < kMaxHalo) { S.halo[pos] = r; S.halo_slot[pos] = (uint16_t)h; } else L.overflow = 1;
                     break;
                 }
                 if (old == r) break;
@@ -303,21 +422,31 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, int64_t n_out, TileHeader
     const bool direct = !SUBM || L.overflow != 0;
     const int n_halo = direct ? 0 : L.n_halo;
 
+    FX_KSTAMP(2);
     // ---- order outputs by mask; order halo rows by index; per-slot list base (direct tiles)
     const uint64_t sorted = block_sort_keys(((uint64_t)mask << 16) | (uint64_t)tid, S.key);
     __syncthreads();
     S.key[tid] = sorted;
     __syncthreads();
+    FX_KSTAMP(3);
+    int32_t* my_rows = tile_rows + tile * (int64_t)row_stride;
     if (!direct) {
-        int P = 2;
-        while (P < n_halo) P <<= 1;
-        lds_bitonic_sort(S.halo, P);
+        // rank of every halo row among the halo rows (all distinct): its position in the
+        // ascending row list and, offset by win_n, its local id
+        for (int i = tid; i < n_halo; i += kPackThreads) {
+            const int32_t v = S.halo[i];
+            int rank = 0;
+            for (int j = 0; j < n_halo; ++j) rank += (S.halo[j] < v);
+            my_rows[rank] = v;
+            S.slot_rank[S.halo_slot[i]] = (uint16_t)rank;
+        }
     }
+    FX_KSTAMP(4);
     uint32_t n_list;
     {
         uint32_t total;
         const uint32_t base = block_scan_excl(direct ? (uint32_t)__popc(mask) : 0u, L.wave_sums, &total);
-        S.slot_base[tid] = base;
+        if (direct) S.slot_base[tid] = base;
         n_list = direct ? total : (uint32_t)n_halo;
     }
     if (tid < kGroupsPerTile) {
@@ -327,46 +456,61 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, int64_t n_out, TileHeader
     }
     __syncthreads();
     if (tid == 0) {
-        int run = 0;
-        for (int g = 0; g < kGroupsPerTile; ++g) { L.group_block0[g] = run; run += __popc(L.group_mask[g]); }
+        int run = 0, pairs = 0;
+        for (int w = 0; w < kTileWaves; ++w) {
+            uint32_t wm = 0;
+            for (int gi = 0; gi < kGroupsPerWave; ++gi) {
+                const uint32_t gm = L.group_mask[tile_group_of(w, gi)];
+                wm |= gm;
+                pairs += __popc(gm);
+            }
+            L.wave_mask[w] = wm;
+            L.wave_block0[w] = run;
+            run += __popc(wm);
+        }
         L.n_blocks = run;
+        L.n_pair_blocks = pairs;
     }
     __syncthreads();
+
+    FX_KSTAMP(5);
+    const bool lds_codes = !direct && (win_n + n_halo <= kRowCap);
 
     // ---- header, permutation, row list
     TileHeader* H = tile_hdr + tile;
     if (tid == 0) {
         H->win_lo = direct ? 0 : win_lo; H->win_n = direct ? 0 : win_n; H->n_list = (int32_t)n_list;
-        H->n_blocks = L.n_blocks; H->n_out = n_valid; H->flags = direct ? kTileDirect : 0;
-        H->pad[0] = 0; H->pad[1] = 0;
-        atomicAdd(&stats[0], (unsigned long long)L.n_blocks * kGroup);
+        H->n_blocks = L.n_blocks; H->n_out = n_valid; H->flags = direct ? kTileDirect : (lds_codes ? kTileLdsOffsets : 0);
+        H->n_pair_blocks = L.n_pair_blocks; H->pad = 0;
+        atomicAdd(&stats[0], (unsigned long long)L.n_pair_blocks * kGroup);
         atomicAdd(&stats[1], (unsigned long long)(direct ? n_list : (uint32_t)(win_n + n_halo)));
         if (direct) atomicAdd(&stats[2], 1ull);
     }
-    if (tid < kGroupsPerTile) { H->group_mask[tid] = L.group_mask[tid]; H->group_block0[tid] = L.group_block0[tid]; }
+    if (tid < kGroupsPerTile) H->group_mask[tid] = L.group_mask[tid];
+    if (tid < kTileWaves) { H->wave_mask[tid] = L.wave_mask[tid]; H->wave_block0[tid] = L.wave_block0[tid]; }
     tile_perm[tile * kTileT + tid] = (uint16_t)(sorted & 0xFFFF);
-    int32_t* my_rows = tile_rows + tile * (int64_t)row_stride;
     if (direct) {
         uint32_t pos = S.slot_base[tid];
         for (int kappa = 0; kappa < K3; ++kappa) {
             const int32_t r = L.nb[tid * K3 + kappa];
             if (r >= 0) my_rows[pos++] = r;
         }
-    } else {
-        for (int e = tid; e < n_halo; e += kPackThreads) my_rows[e] = S.halo[e];
     }
 
-    // ---- blocks: 16 threads per group walk the group's offsets
+    FX_KSTAMP(6);
+    // ---- id blocks: the threads of a group walk the offsets of the group's wave
     {
-        const int g = tid >> 4, sub = tid & 15;
+        const int g = tid / kGroup, sub = tid % kGroup;
+        const int w = (g >> kDealShift) & (kTileWaves - 1);
+        const int gi = ((g >> (kDealShift + 2)) << kDealShift) | (g & ((1 << kDealShift) - 1));
         const int slot = (int)(S.key[g * kGroup + sub] & 0xFFFF);
         const uint32_t smask = S.slot_mask[slot];
-        const uint32_t sbase = S.slot_base[slot];
-        uint32_t gm = L.group_mask[g];
-        size_t blk = (size_t)tile * block_stride + L.group_block0[g];
-        while (gm) {
-            const int kappa = __ffs(gm) - 1;
-            gm &= gm - 1;
+        const uint32_t sbase = direct ? S.slot_base[slot] : 0u;
+        uint32_t wm = L.wave_mask[w];
+        size_t blk = (size_t)tile * block_stride + L.wave_block0[w];
+        while (wm) {
+            const int kappa = __ffs(wm) - 1;
+            wm &= wm - 1;
             uint16_t id = kNoRow;
             if ((smask >> kappa) & 1u) {
                 if (direct) {
@@ -376,19 +520,18 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, int64_t n_out, TileHeader
                     if (r >= win_lo && r < win_lo + win_n) {
                         id = (uint16_t)(r - win_lo);
                     } else {
-                        int lo = 0, hi = n_halo - 1;
-                        while (lo < hi) {
-                            const int mid = (lo + hi) >> 1;
-                            if (S.halo[mid] < r) lo = mid + 1; else hi = mid;
-                        }
-                        id = (uint16_t)(win_n + lo);
+                        uint32_t hh = ((uint32_t)r * 0x9E3779B1u) >> 21;
+                        while (S.hash[hh] != r) hh = (hh + 1) & (kHaloHashSlots - 1);
+                        id = (uint16_t)(win_n + S.slot_rank[hh]);
                     }
                 }
             }
-            tile_blocks[blk * kGroup + sub] = id;
+            if (lds_codes) id = (uint16_t)lds_row_code(id == kNoRow ? (uint32_t)kRowCap : (uint32_t)id);
+            tile_blocks[blk * kIdBlockElems + sub * kGroupsPerWave + gi] = id;
             ++blk;
         }
     }
+    FX_KSTAMP(7);
 }
 
 // global input row of a tile-local id
@@ -407,15 +550,18 @@ k_tiles_to_dense(const TileHeader* __restrict__ tile_hdr, const uint16_t* __rest
     const int64_t tile = blockIdx.x;
     const TileHeader* H = tile_hdr + tile;
     const int n_valid = H->n_out;
-    const int g = threadIdx.x >> 4, sub = threadIdx.x & 15;   // blockDim.x == kTileT: one thread per slot
+    const int g = threadIdx.x / kGroup, sub = threadIdx.x % kGroup;   // blockDim.x == kTileT: one thread per slot
+    const int w = (g >> kDealShift) & (kTileWaves - 1);
+    const int gi = ((g >> (kDealShift + 2)) << kDealShift) | (g & ((1 << kDealShift) - 1));
     const int local = tile_perm[tile * kTileT + g * kGroup + sub];
-    uint32_t gm = H->group_mask[g];
-    size_t blk = (size_t)tile * block_stride + H->group_block0[g];
+    uint32_t wm = H->wave_mask[w];
+    size_t blk = (size_t)tile * block_stride + H->wave_block0[w];
     const int32_t* rows = tile_rows + tile * (int64_t)row_stride;
-    while (gm) {
-        const int kappa = __ffs(gm) - 1;
-        gm &= gm - 1;
-        const uint16_t id = tile_blocks[blk * kGroup + sub];
+    while (wm) {
+        const int kappa = __ffs(wm) - 1;
+        wm &= wm - 1;
+        uint16_t id = tile_blocks[blk * kIdBlockElems + sub * kGroupsPerWave + gi];
+        if (H->flags & kTileLdsOffsets) id = (id / kRowBytes == kRowCap) ? kNoRow : (uint16_t)(id / kRowBytes);
         ++blk;
         if (id != kNoRow && local < n_valid) {
             if (nbmap) nbmap[(tile * kTileT + local) * K3 + kappa] = tile_global_row(H, rows, id);
@@ -483,6 +629,12 @@ fx_status kmap_ensure_dense(fx_kmap* km, hipStream_t st) {
 
 using namespace fx;
 
+#ifdef FX_KMAP_TIMING
+extern "C" int fx_debug_kmap_timing(unsigned long long* h_out, size_t bytes) {
+    return (int)hipMemcpyFromSymbol(h_out, HIP_SYMBOL(g_kmap_timing), bytes);
+}
+#endif
+
 extern "C" void fx_kmap_destroy(fx_kmap* km) {
     if (!km) return;
     if (km->refs.fetch_sub(1) != 1) return;
@@ -516,7 +668,7 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     const bool tiled = km->K3 <= kMaxK3Tiled;
     km->n_tiles = tiled ? (km->n_out + kTileT - 1) / kTileT : 0;
     km->row_stride = kTileT * km->K3;
-    km->block_stride = kGroupsPerTile * km->K3;
+    km->block_stride = kTileWaves * km->K3;
 
     // one allocation: stats | tile headers | perm | rows | blocks
     const size_t nt = (size_t)std::max<int64_t>(km->n_tiles, 1);
@@ -526,7 +678,8 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     const size_t o_th = take(sizeof(TileHeader) * nt);
     const size_t o_tp = take(sizeof(uint16_t) * kTileT * nt);
     const size_t o_tr = take(tiled ? sizeof(int32_t) * (size_t)km->row_stride * nt : 0);
-    const size_t o_tb = take(tiled ? sizeof(uint16_t) * kGroup * (size_t)km->block_stride * nt : 0);
+    const size_t o_tb = take(tiled ? sizeof(uint16_t) * kIdBlockElems * (size_t)km->block_stride * nt : 0);
+    const size_t o_ln = take(tiled ? sizeof(int32_t) * 27 * (size_t)std::max(gout->hdr.n_leaf, 1) : 0);
     fx_status rc = dev_alloc(&km->d_alloc, off, st);
     if (rc != FX_OK) { fx_kmap_destroy(km); return rc; }
     char* p = (char*)km->d_alloc;
@@ -535,6 +688,7 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     km->d_tile_perm = (uint16_t*)(p + o_tp);
     km->d_tile_rows = (int32_t*)(p + o_tr);
     km->d_tile_blocks = (uint16_t*)(p + o_tb);
+    int32_t* d_leaf_nbr = (int32_t*)(p + o_ln);
 
     hipError_t e = hipMemsetAsync(km->d_stats, 0, sizeof(int64_t) * (size_t)(4 + km->K3), st);
     if (e == hipSuccess && km->n_tiles > 0) {
@@ -542,13 +696,21 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
         const size_t lds = sizeof(PackLds);
         const unsigned ntl = (unsigned)km->n_tiles;
         const TreeView tin = g_in->view(), tout = gout->view();
+        {
+            ProfScope ps(kProfNbmap, st);
+            const int64_t ne = (int64_t)gout->hdr.n_leaf * 27;
+            const unsigned nbk = (unsigned)((ne + 255) / 256);
+            if (K == 1) k_leaf_neighbors<1><<<nbk, 256, 0, st>>>(tin, tout, stride, d_leaf_nbr);
+            else if (K == 2) k_leaf_neighbors<2><<<nbk, 256, 0, st>>>(tin, tout, stride, d_leaf_nbr);
+            else k_leaf_neighbors<3><<<nbk, 256, 0, st>>>(tin, tout, stride, d_leaf_nbr);
+        }
         ProfScope ps(kProfPackTiles, st);
 #define FX_TILES(KV, SUBMV)                                                                                    \
     do {                                                                                                       \
         e = hipFuncSetAttribute((const void*)k_build_tiles<KV, SUBMV>,                                         \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                         \
         if (e == hipSuccess)                                                                                   \
-            k_build_tiles<KV, SUBMV><<<ntl, kPackThreads, lds, st>>>(tin, tout, stride, km->n_out,             \
+            k_build_tiles<KV, SUBMV><<<ntl, kPackThreads, lds, st>>>(tin, tout, stride, d_leaf_nbr, km->n_out, \
                                                                      km->d_tile_hdr, km->d_tile_perm,          \
                                                                      km->d_tile_rows, km->row_stride,          \
                                                                      km->d_tile_blocks, km->block_stride,      \
