@@ -29,7 +29,8 @@ typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kCoutSlice = 64;      // output channels per wave
-constexpr int kConvThreads = 64 * kTileWaves;
+constexpr int kProducerWaves = 4;
+constexpr int kConvThreads = 64 * (kTileWaves + kProducerWaves);
 constexpr int kMaxIdBlocks = kTileWaves * kMaxK3Tiled;
 
 // ---------------------------------------------------------------------------------- element types
@@ -102,30 +103,51 @@ __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restr
     }
 }
 
+#ifndef FX_CONV_EXPERIMENT
+#define FX_CONV_EXPERIMENT 0
+#endif
 #ifdef FX_CONV_TIMING
-// development aid: per-workgroup phase timestamps (thread 0), read back with fx_debug_conv_timing
-__device__ unsigned long long g_conv_timing[4096 * 8];
-#define FX_STAMP(slot) do { if (tid == 0 && tile < 4096) g_conv_timing[tile * 8 + (slot)] = __builtin_readcyclecounter(); } while (0)
+// development aid: per-workgroup cycle totals, read back with fx_debug_conv_timing
+__device__ unsigned long long g_conv_timing[1024 * 8];
+#define FX_T0() const unsigned long long _t0 = __builtin_readcyclecounter()
+#define FX_TACC(var) var += __builtin_readcyclecounter() - _t0
 #else
-#define FX_STAMP(slot) do { } while (0)
+#define FX_T0() do { } while (0)
+#define FX_TACC(var) do { } while (0)
 #endif
 
 // ---------------------------------------------------------------------------------- MFMA kernel
+constexpr int kRowBufBytes = (kRowCap + 1) * kRowBytes;           // staged rows + the zero row
+constexpr int kBlockBufBytes = kMaxIdBlocks * kIdBlockElems * 2;
+
+// Everything is double-buffered: while the consumer waves multiply out of one half, the
+// producer waves fill the other half straight from global memory.
 struct ConvLds {
-    unsigned char rows[(kRowCap + 1) * kRowBytes];  // 64-byte rows; 16-byte chunk q stored at q ^ ((row >> 2) & 3)
-    uint16_t blocks[kMaxIdBlocks * kIdBlockElems];  // id blocks [block][voxel n][group slot]
-    uint16_t perm[kTileT];
+    unsigned char rows[2][kRowBufBytes];     // 64-byte rows; 16-byte piece p stored at p ^ ((row >> 2) & 3)
+    unsigned char blocks[2][kBlockBufBytes]; // id blocks [block][voxel n][group slot], u16
+    uint16_t perm[2][kTileT];
+};
+static_assert(sizeof(ConvLds) <= 160 * 1024, "LDS budget of one compute unit");
+
+__device__ __forceinline__ int lds_row_offset(int row, int p) { return (int)(lds_row_code((uint32_t)row) ^ (uint32_t)(p << 4)); }
+
+// What a workgroup needs to know about one work item (tile x output-channel slice); all fields
+// are wave-uniform.
+struct Item {
+    int64_t tile;
+    int slice;
+    int win_lo, win_n, n_list, n_blocks, n_valid, n_staged;
+    bool general;
 };
 
-__device__ __forceinline__ int lds_row_offset(int row, int q) { return (int)(lds_row_code((uint32_t)row) ^ (uint32_t)(q << 4)); }
-
-// Loop over the stencil offsets a wave needs for one 32-channel chunk.  Per offset: the ids of
-// the lane's voxel column in the wave's 4 column blocks arrive with one 8-byte LDS read (fetched
-// one offset ahead), the B fragments of the present column blocks are read (2 x 16 bytes per
-// lane), then 4 MFMAs (2 m-tiles x 2 k-steps) per present block.  GENERAL adds the fallback for
-// rows that are not staged in LDS.
+// Loop over the stencil offsets a wave needs for one 32-channel chunk.  Software pipeline per
+// offset step i: the weights and B fragments of step i+1 and the ids of step i+2 are fetched,
+// then the MFMAs of step i are issued (2 m-tiles x 2 k-steps per present column block) while
+// those loads are in flight.  Registers are rotated by unrolling (two weight sets, two fragment
+// sets), never copied.  GENERAL adds the fallback for rows that are not staged in LDS.
 template <typename T, bool GENERAL>
-__device__ __forceinline__ void offsets_loop(const ConvLds& L, f32x16 (&acc)[kGroupsPerWave][2],
+__device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, const unsigned char* lds_blocks,
+                                             f32x16 (&acc)[kGroupsPerWave][2],
                                              const uint32_t (&gmask)[kGroupsPerWave], uint32_t wave_mask,
                                              int wave_block0, const typename Elem<T>::vec8* __restrict__ wbase,
                                              int64_t w_kappa_stride, int n, int h, int n_staged, int win_lo, int win_n,
@@ -133,13 +155,10 @@ __device__ __forceinline__ void offsets_loop(const ConvLds& L, f32x16 (&acc)[kGr
                                              int C_in, int c) {
     typedef typename Elem<T>::vec8 vec8;
     constexpr int NG = kGroupsPerWave;
-    // The wave's offsets in ascending order.  Weights run two offsets ahead of the multiply in a
-    // ring of three register sets (the loop is unrolled by three so that no set is ever copied);
-    // ids run one offset ahead.  Steps past the last offset use offset 31, which no group has.
     const int n_off = __popc(wave_mask);
     const int k_last = 31 - __clz(wave_mask);
-    const u32x2* idp = reinterpret_cast<const u32x2*>(L.blocks) + (size_t)wave_block0 * kGroup + n;
-    uint32_t rest = wave_mask;            // offsets not yet fetched
+    const u32x2* idp = reinterpret_cast<const u32x2*>(lds_blocks) + (size_t)wave_block0 * kGroup + n;
+    uint32_t rest = wave_mask;            // offsets not yet fetched; 31 (which no group has) once exhausted
     auto pop_kappa = [&]() {
         if (!rest) return 31;
         const int k = __ffs(rest) - 1;
@@ -151,25 +170,17 @@ __device__ __forceinline__ void offsets_loop(const ConvLds& L, f32x16 (&acc)[kGr
 #pragma unroll
         for (int f = 0; f < 4; ++f) w[f] = ws[f * 64];
     };
-    vec8 w0[4], w1[4], w2[4];
-    u32x2 idv = idp[0], idn;
-    int ka = pop_kappa(), kb = pop_kappa(), it = 0;
-    fetch_w(w0, ka);
-    fetch_w(w1, kb);
-    // one step: fetch the weights of the offset two ahead into `wfill`, multiply offset `kappa` with `wcur`
-    auto step = [&](const vec8 (&wcur)[4], vec8 (&wfill)[4], int kappa, int k_fill) {
-        fetch_w(wfill, k_fill);
-        idn = idp[min(it + 1, n_off - 1) * kGroup];
-        vec8 bf[NG][2];
+    // B fragments (16 channels x 32 voxels, two k-steps) of the column blocks that have offset kappa
+    auto fetch_b = [&](vec8 (&bf)[NG][2], const u32x2& ids, int kappa) {
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi) {
             if (!((gmask[gi] >> kappa) & 1u)) continue;
-            const uint32_t id = (idv[gi >> 1] >> (16 * (gi & 1))) & 0xFFFFu;
+            const uint32_t id = (ids[gi >> 1] >> (16 * (gi & 1))) & 0xFFFFu;
             if (GENERAL) {
                 const bool staged = id < (uint32_t)n_staged;
                 const int row = staged ? (int)id : kRowCap;
-                bf[gi][0] = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, h));
-                bf[gi][1] = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, h + 2));
+                bf[gi][0] = *reinterpret_cast<const vec8*>(lds_rows + lds_row_offset(row, h));
+                bf[gi][1] = *reinterpret_cast<const vec8*>(lds_rows + lds_row_offset(row, h + 2));
                 const bool from_global = !staged && id != kNoRow;
                 if (__any(from_global)) {
                     if (from_global) {
@@ -180,85 +191,117 @@ __device__ __forceinline__ void offsets_loop(const ConvLds& L, f32x16 (&acc)[kGr
                     }
                 }
             } else {   // id = lds_row_code(row): 16-byte piece p of the row sits at id ^ (p << 4)
-                bf[gi][0] = *reinterpret_cast<const vec8*>(L.rows + (id ^ (uint32_t)(h << 4)));
-                bf[gi][1] = *reinterpret_cast<const vec8*>(L.rows + (id ^ (uint32_t)((h + 2) << 4)));
+                bf[gi][0] = *reinterpret_cast<const vec8*>(lds_rows + (id ^ (uint32_t)(h << 4)));
+                bf[gi][1] = *reinterpret_cast<const vec8*>(lds_rows + (id ^ (uint32_t)((h + 2) << 4)));
             }
         }
+    };
+    vec8 wa[4], wb[4];
+    vec8 bfa[NG][2], bfb[NG][2];
+    int ka = pop_kappa(), kb = pop_kappa(), it = 0;
+    fetch_w(wa, ka);
+    u32x2 idn = idp[min(1, n_off - 1) * kGroup];   // ids of step 1
+    fetch_b(bfa, idp[0], ka);
+    // one step: fetch weights, ids and fragments of the following offsets, then multiply offset
+    // `kappa` (weights wcur, fragments bcur) while those loads are in flight
+    auto step = [&](const vec8 (&wcur)[4], vec8 (&wnext)[4], const vec8 (&bcur)[NG][2], vec8 (&bnext)[NG][2], int kappa,
+                    int k_next) {
+#if FX_CONV_EXPERIMENT != 1
+        fetch_w(wnext, k_next);
+#endif
+        const u32x2 ids_next = idn;
+        idn = idp[min(it + 2, n_off - 1) * kGroup];
+#if FX_CONV_EXPERIMENT != 2
+        fetch_b(bnext, ids_next, k_next);
+#endif
+#if FX_CONV_EXPERIMENT != 3
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi) {
             if (!((gmask[gi] >> kappa) & 1u)) continue;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+            for (int ks = 0; ks < 2; ++ks)      // k-step outermost: consecutive MFMAs never share an accumulator
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) acc[gi][mt] = Elem<T>::mfma(wcur[mt * 2 + ks], bf[gi][ks], acc[gi][mt]);
+                for (int mt = 0; mt < 2; ++mt) acc[gi][mt] = Elem<T>::mfma(wcur[mt * 2 + ks], bcur[gi][ks], acc[gi][mt]);
         }
-        idv = idn;
+#endif
         ++it;
     };
     while (it < n_off) {
-        int kc = pop_kappa();
-        step(w0, w2, ka, kc);
+        step(wa, wb, bfa, bfb, ka, kb);
         ka = pop_kappa();
-        step(w1, w0, kb, ka);
+        step(wb, wa, bfb, bfa, kb, ka);
         kb = pop_kappa();
-        step(w2, w1, kc, kb);
     }
 }
 
-// stage channels [32c, 32c+32) of the tile's input rows: 4 lanes x 16 bytes per row
-__device__ __forceinline__ void stage_rows(ConvLds& L, int tid, int n_staged, int win_lo, int win_n,
-                                           const int32_t* __restrict__ my_rows, const uint16_t* __restrict__ feat,
-                                           int C_in, int c) {
-    const int sub = tid & 3;
-    for (int r0 = tid >> 2; r0 < n_staged; r0 += 64 * 4) {
-        u32x4 v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int r = r0 + 64 * u;
-            if (r < n_staged) {
-                const int64_t gr = r < win_n ? (int64_t)win_lo + r : (int64_t)my_rows[r - win_n];
-                v[u] = *reinterpret_cast<const u32x4*>(feat + gr * C_in + c * kCinChunk + sub * 8);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int r = r0 + 64 * u;
-            if (r < n_staged) *reinterpret_cast<u32x4*>(L.rows + lds_row_offset(r, sub)) = v[u];
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// Producer side: one wave copies 1 KB slabs (16 rows of 64 bytes, or 4 id blocks) from global
+// memory straight into LDS; lane l of a slab load writes the 16 bytes at slab + 16*l.
+__device__ __forceinline__ void produce_rows(unsigned char* lds_rows, const Item& I, int pwave, int lane,
+                                             const int32_t* __restrict__ tile_rows, int row_stride,
+                                             const uint16_t* __restrict__ feat, int C_in, int c) {
+    const int32_t* my_rows = tile_rows + I.tile * (int64_t)row_stride;
+    const int n_slabs = (I.n_staged + 15) >> 4;
+    const int piece = (lane & 3) ^ ((lane >> 4) & 3);   // stored position lane&3 holds piece (lane&3) ^ ((row >> 2) & 3)
+    for (int s = pwave; s < n_slabs; s += kProducerWaves) {
+        const int r = 16 * s + (lane >> 2);
+        if (r < I.n_staged) {
+            const int64_t gr = r < I.win_n ? (int64_t)I.win_lo + r : (int64_t)my_rows[r - I.win_n];
+            const uint16_t* src = feat + gr * C_in + c * kCinChunk + piece * 8;
+            __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(lds_rows + s * 1024), 16, 0, 0);
         }
     }
 }
 
-// Everything a workgroup does once the tile header is known: stage, multiply, write back.
+__device__ __forceinline__ void produce_meta(unsigned char* lds_blocks, uint16_t* lds_perm, const Item& I, int pwave, int lane,
+                                             const uint16_t* __restrict__ tile_perm,
+                                             const uint16_t* __restrict__ tile_blocks, int block_stride) {
+    const unsigned char* src = reinterpret_cast<const unsigned char*>(tile_blocks + (size_t)I.tile * block_stride * kIdBlockElems);
+    const int bytes = I.n_blocks * kIdBlockElems * 2;
+    for (int s = pwave; s * 1024 < bytes; s += kProducerWaves) {
+        const int off = s * 1024 + lane * 16;
+        if (off < bytes) __builtin_amdgcn_global_load_lds(src + off, (lds_ptr_t)(lds_blocks + s * 1024), 16, 0, 0);
+    }
+    if (pwave == 0)
+        __builtin_amdgcn_global_load_lds(reinterpret_cast<const unsigned char*>(tile_perm + I.tile * kTileT) + lane * 16,
+                                         (lds_ptr_t)lds_perm, 16, 0, 0);
+}
+
+__device__ __forceinline__ Item load_item(int64_t work, int nslice, const TileHeader* __restrict__ tile_hdr) {
+    Item I;
+    I.tile = work / nslice;
+    I.slice = (int)(work - I.tile * nslice);
+    const TileHeader* H = tile_hdr + I.tile;
+    I.win_lo = H->win_lo; I.win_n = H->win_n; I.n_list = H->n_list;
+    I.n_blocks = H->n_blocks; I.n_valid = H->n_out;
+    const int flags = H->flags;
+    I.n_staged = (flags & kTileDirect) ? 0 : min(I.win_n + I.n_list, kRowCap);
+    I.general = !(flags & kTileLdsOffsets);
+    return I;
+}
+
+// Consumer side of one work item: multiply all chunks (one barrier after each, matching the
+// producers' barriers), then write the tile's outputs back (lane (n, h) holds channels
+// slice*64 + 32h .. +31 of output slot g*32 + n).  `step` counts chunks since kernel start and
+// selects the LDS half; `mb` selects the half that holds this tile's id blocks.
 template <typename T, bool OUT_F32, bool GENERAL>
-__device__ __forceinline__ void tile_body(ConvLds& L, const TileHeader* __restrict__ H, int64_t tile, int slice, int tid,
-                                          const uint16_t* __restrict__ tile_perm, const int32_t* __restrict__ my_rows,
-                                          const uint16_t* __restrict__ my_blocks, const uint16_t* __restrict__ feat,
-                                          const uint16_t* __restrict__ wp, int C_in, int C_out, void* __restrict__ out) {
+__device__ __forceinline__ void consume_item(ConvLds& L, const Item& I, int step, int mb, bool barrier_after_last, int nchunk,
+                                             int nslice, int wave, int lane, const TileHeader* __restrict__ tile_hdr,
+                                             const int32_t* __restrict__ tile_rows, int row_stride,
+                                             const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp, int C_in,
+                                             int C_out, void* __restrict__ out, unsigned long long (&tm)[4]) {
     typedef typename Elem<T>::vec8 vec8;
     constexpr int NG = kGroupsPerWave;
-    const int lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, h = lane >> 5;
-    const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
-    const int win_lo = H->win_lo, win_n = H->win_n, n_list = H->n_list;
-    const int n_blocks = H->n_blocks, n_valid = H->n_out;
-    const int n_staged = (H->flags & kTileDirect) ? 0 : min(win_n + n_list, kRowCap);
-
-    // tile metadata and the first chunk of rows -> LDS
-    for (int e = tid; e < kTileT; e += kConvThreads) L.perm[e] = tile_perm[tile * kTileT + e];
-    {
-        const u32x4* src = reinterpret_cast<const u32x4*>(my_blocks);
-        u32x4* dst = reinterpret_cast<u32x4*>(L.blocks);
-        const int nb16 = n_blocks * (kIdBlockElems * 2 / 16);
-        for (int e = tid; e < nb16; e += kConvThreads) dst[e] = src[e];
-    }
-    if (tid < kRowBytes / 16) reinterpret_cast<u32x4*>(L.rows + kRowCap * kRowBytes)[tid] = u32x4{0, 0, 0, 0};
-    stage_rows(L, tid, n_staged, win_lo, win_n, my_rows, feat, C_in, 0);
-
+    const TileHeader* H = tile_hdr + I.tile;
     uint32_t gmask[NG];
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) gmask[gi] = __builtin_amdgcn_readfirstlane(H->group_mask[tile_group_of(wave, gi)]);
     const uint32_t wave_mask = __builtin_amdgcn_readfirstlane(H->wave_mask[wave]);
     const int wave_block0 = __builtin_amdgcn_readfirstlane(H->wave_block0[wave]);
+    const int32_t* my_rows = tile_rows + I.tile * (int64_t)row_stride;
+    const int64_t w_kappa_stride = (int64_t)nchunk * nslice * 4 * 64;
 
     f32x16 acc[NG][2];
 #pragma unroll
@@ -267,34 +310,25 @@ __device__ __forceinline__ void tile_body(ConvLds& L, const TileHeader* __restri
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[gi][mt][v] = 0.f;
-    FX_STAMP(1);
 
     for (int c = 0; c < nchunk; ++c) {
-        if (c > 0) {
-            __syncthreads();  // all waves are done reading the previous chunk
-            stage_rows(L, tid, n_staged, win_lo, win_n, my_rows, feat, C_in, c);
-        }
-        __syncthreads();
-        if (c == 0) FX_STAMP(2);
-        if (c == 1) FX_STAMP(4);
         if (wave_mask) {
-            const vec8* wbase = reinterpret_cast<const vec8*>(wp) + lane + (((int64_t)c * nslice + slice) * 4) * 64;
-            const int64_t w_kappa_stride = (int64_t)nchunk * nslice * 4 * 64;
-            offsets_loop<T, GENERAL>(L, acc, gmask, wave_mask, wave_block0, wbase, w_kappa_stride, n, h, n_staged, win_lo,
-                                     win_n, my_rows, feat, C_in, c);
+            FX_T0();
+            const vec8* wbase = reinterpret_cast<const vec8*>(wp) + lane + (((int64_t)c * nslice + I.slice) * 4) * 64;
+            offsets_loop<T, GENERAL>(L.rows[(step + c) & 1], L.blocks[mb], acc, gmask, wave_mask, wave_block0, wbase,
+                                     w_kappa_stride, n, h, I.n_staged, I.win_lo, I.win_n, my_rows, feat, C_in, c);
+            FX_TACC(tm[0]);
         }
-        if (c == 0) FX_STAMP(3);
-        if (c == 1) FX_STAMP(5);
+        if (c != nchunk - 1) { FX_T0(); __syncthreads(); FX_TACC(tm[1]); }
     }
-    FX_STAMP(6);
-
-    // write-back: lane (n, h) holds output channels slice*64 + 32h .. +31 of output slot g*32 + n
+    {
+    FX_T0();
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
-        const int local = L.perm[tile_group_of(wave, gi) * kGroup + n];
-        if (local >= n_valid) continue;
-        const int64_t o = tile * kTileT + local;
-        const int64_t col = (int64_t)slice * kCoutSlice + 32 * h;
+        const int local = L.perm[mb][tile_group_of(wave, gi) * kGroup + n];
+        if (local >= I.n_valid) continue;
+        const int64_t o = I.tile * kTileT + local;
+        const int64_t col = (int64_t)I.slice * kCoutSlice + 32 * h;
         if (OUT_F32) {
             float* dst = reinterpret_cast<float*>(out) + o * C_out + col;
 #pragma unroll
@@ -317,34 +351,118 @@ __device__ __forceinline__ void tile_body(ConvLds& L, const TileHeader* __restri
                 }
         }
     }
+    FX_TACC(tm[2]);
+    }
+    if (barrier_after_last) { FX_T0(); __syncthreads(); FX_TACC(tm[1]); }
 }
 
-// One workgroup = one tile of 512 consecutive outputs x one slice of 64 output channels.
-// Wave w owns 4 of the tile's 16 column blocks (128 outputs): 4 x 2 accumulator tiles of 32x32.
+// Persistent workgroups, one per compute unit, each walking a strided list of work items (tile
+// of 512 consecutive outputs x slice of 64 output channels) in steps of one 32-channel chunk.
+// Waves 0-3 are consumers: wave w owns 4 of the tile's 16 column blocks (128 outputs, 4 x 2
+// accumulator tiles of 32x32) and multiplies out of one half of LDS.  Waves 4-7 are producers:
+// meanwhile they copy the rows of the next step (and, at a tile change, its id blocks) from
+// global memory straight into the other half.  One barrier per step hands the halves over
+// (both roles execute the same number of barriers).  Producers and consumers are separate
+// waves because a wave's loads complete in order: the consumer's short weight fetches must not
+// queue behind the long HBM reads.
 template <typename T, bool OUT_F32>
-__global__ void __launch_bounds__(kConvThreads, 2)
+__global__ void __launch_bounds__(kConvThreads, 1)
 k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
             const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
-            int block_stride, const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp,
-            int C_in, int C_out, void* __restrict__ out) {
+            int block_stride, int64_t n_work, int per_xcd, const uint16_t* __restrict__ feat,
+            const uint16_t* __restrict__ wp, int C_in, int C_out, void* __restrict__ out) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     ConvLds& L = *reinterpret_cast<ConvLds*>(lds_raw);
-    const int tid = threadIdx.x;
-    const int64_t tile = blockIdx.x;
-    const int slice = blockIdx.y;
-    FX_STAMP(0);
-    const TileHeader* H = tile_hdr + tile;
-    const int32_t* my_rows = tile_rows + tile * (int64_t)row_stride;
-    const uint16_t* my_blocks = tile_blocks + (size_t)tile * block_stride * kIdBlockElems;
-    // a tile is "general" when some of its rows do not fit the LDS budget (or it is a direct tile):
-    // its loop carries the global-memory fallback; all other tiles run a loop whose only global
-    // loads are the weights
-    const bool general = !(H->flags & kTileLdsOffsets);
-    if (general)
-        tile_body<T, OUT_F32, true>(L, H, tile, slice, tid, tile_perm, my_rows, my_blocks, feat, wp, C_in, C_out, out);
-    else
-        tile_body<T, OUT_F32, false>(L, H, tile, slice, tid, tile_perm, my_rows, my_blocks, feat, wp, C_in, C_out, out);
-    FX_STAMP(7);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
+
+    // Work order: workgroup b runs on XCD b % 8 (round-robin dispatch); XCD x takes the x-th
+    // eighth of the work list and its workgroups walk it side by side, so that neighbouring tiles,
+    // which share halo rows, meet in the same L2.
+    const int xcd = blockIdx.x & 7, in_xcd = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
+    const int64_t w_begin = (int64_t)xcd * per_xcd;
+    const int64_t w_end = min(n_work, w_begin + per_xcd);
+    int64_t work = w_begin + in_xcd;
+    if (work >= w_end) return;
+
+    if (tid < 2 * (kRowBytes / 16))   // the zero row of both halves
+        reinterpret_cast<u32x4*>(L.rows[tid >> 2] + kRowCap * kRowBytes)[tid & 3] = u32x4{0, 0, 0, 0};
+
+    if (wave >= kTileWaves) {
+        // ---------------- producers
+        const int pwave = wave - kTileWaves;
+        Item cur = load_item(work, nslice, tile_hdr);
+        produce_meta(L.blocks[0], L.perm[0], cur, pwave, lane, tile_perm, tile_blocks, block_stride);
+        produce_rows(L.rows[0], cur, pwave, lane, tile_rows, row_stride, feat, C_in, 0);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+#ifdef FX_CONV_TIMING
+        unsigned long long ptm = 0;
+        const unsigned long long pt_start = __builtin_readcyclecounter();
+#endif
+        int step = 0, item_no = 0;
+        while (true) {
+            const int64_t next_work = work + wg_per_xcd;
+            const bool has_next = next_work < w_end;
+            for (int c = 0; c < nchunk; ++c, ++step) {
+                const int rb = step & 1, mb = item_no & 1;
+                if (c != nchunk - 1) {
+                    produce_rows(L.rows[rb ^ 1], cur, pwave, lane, tile_rows, row_stride, feat, C_in, c + 1);
+                } else if (has_next) {
+                    const Item nxt = load_item(next_work, nslice, tile_hdr);
+                    produce_meta(L.blocks[mb ^ 1], L.perm[mb ^ 1], nxt, pwave, lane, tile_perm, tile_blocks, block_stride);
+                    produce_rows(L.rows[rb ^ 1], nxt, pwave, lane, tile_rows, row_stride, feat, C_in, 0);
+                }
+                __builtin_amdgcn_s_waitcnt(0);
+#ifdef FX_CONV_TIMING
+                const unsigned long long tb = __builtin_readcyclecounter();
+#endif
+                if (c != nchunk - 1 || has_next) __syncthreads();
+#ifdef FX_CONV_TIMING
+                ptm += __builtin_readcyclecounter() - tb;
+#endif
+            }
+            if (!has_next) break;
+            cur = load_item(next_work, nslice, tile_hdr);
+            work = next_work;
+            ++item_no;
+        }
+#ifdef FX_CONV_TIMING
+        if (tid == kTileWaves * 64 && blockIdx.x < 1024) {
+            unsigned long long* d = g_conv_timing + blockIdx.x * 8;
+            d[5] = ptm; d[6] = __builtin_readcyclecounter() - pt_start;
+        }
+#endif
+    } else {
+        // ---------------- consumers
+        unsigned long long tm[4] = {0, 0, 0, 0};
+#ifdef FX_CONV_TIMING
+        const unsigned long long t_start = __builtin_readcyclecounter();
+#endif
+        __syncthreads();
+        int step = 0, item_no = 0;
+        while (true) {
+            const int64_t next_work = work + wg_per_xcd;
+            const bool has_next = next_work < w_end;
+            const Item cur = load_item(work, nslice, tile_hdr);
+            if (cur.general)
+                consume_item<T, OUT_F32, true>(L, cur, step, item_no & 1, has_next, nchunk, nslice, wave, lane, tile_hdr,
+                                               tile_rows, row_stride, feat, wp, C_in, C_out, out, tm);
+            else
+                consume_item<T, OUT_F32, false>(L, cur, step, item_no & 1, has_next, nchunk, nslice, wave, lane, tile_hdr,
+                                                tile_rows, row_stride, feat, wp, C_in, C_out, out, tm);
+            if (!has_next) break;
+            step += nchunk;
+            work = next_work;
+            ++item_no;
+        }
+#ifdef FX_CONV_TIMING
+        if (tid == 0 && blockIdx.x < 1024) {
+            unsigned long long* d = g_conv_timing + blockIdx.x * 8;
+            d[0] = tm[0]; d[1] = tm[1]; d[2] = tm[2]; d[3] = __builtin_readcyclecounter() - t_start; d[4] = item_no + 1;
+        }
+#endif
+    }
 }
 
 // ---------------------------------------------------------------------------------- scalar path
@@ -386,11 +504,22 @@ static hipError_t launch_mfma(const fx_kmap* km, const void* feat, const void* w
     hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<T, OUT_F32>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    dim3 grid((unsigned)km->n_tiles, (unsigned)(C_out / kCoutSlice));
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
+        if (n_cu <= 0) n_cu = 256;
+    }
+    const int64_t n_work = km->n_tiles * (int64_t)(C_out / kCoutSlice);
+    const int per_xcd = (int)((n_work + 7) / 8);
+    // one workgroup per compute unit, a multiple of 8 (one share per XCD), no more than the work needs
+    int grid = std::max(8, (n_cu / 8) * 8);
+    grid = (int)std::min<int64_t>(grid, (int64_t)8 * per_xcd);
     k_conv_mfma<T, OUT_F32><<<grid, kConvThreads, lds, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,
-                                                             km->row_stride, km->d_tile_blocks, km->block_stride,
-                                                             (const uint16_t*)feat, (const uint16_t*)wp, C_in, C_out,
-                                                             out);
+                                                             km->row_stride, km->d_tile_blocks, km->block_stride, n_work,
+                                                             per_xcd, (const uint16_t*)feat, (const uint16_t*)wp, C_in,
+                                                             C_out, out);
     return hipGetLastError();
 }
 

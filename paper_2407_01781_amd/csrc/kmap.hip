@@ -179,6 +179,7 @@ __device__ unsigned long long g_kmap_timing[4096 * 8];
 constexpr int kPackThreads = kTileT;          // one thread per output slot
 constexpr int kPackWaves = kPackThreads / 64;
 constexpr int kHaloHashSlots = 2048;
+constexpr int kLdsLeafRows = 160;            // leaves of a tile whose neighbour rows are kept in LDS
 
 struct PackScratch {                          // live after the lookup phase
     uint64_t key[kTileT];                     // (mask << 16 | slot), sorted by mask
@@ -195,7 +196,10 @@ struct PackScratch {                          // live after the lookup phase
 struct PackLds {
     int32_t nb[kTileT * kMaxK3Tiled];         // the tile's map entries [slot][kappa]
     union {
-        int32_t leaf_off[kTileT];             // lookup phase: first index of every leaf of the tile
+        struct {                              // lookup phase
+            int32_t leaf_off[kTileT];         // first index of every leaf of the tile
+            int32_t nbr_rows[kLdsLeafRows * 27];  // neighbour-leaf ids of the tile's first leaves
+        } look;
         PackScratch s;
     } u;
     uint32_t group_mask[kGroupsPerTile];
@@ -330,7 +334,12 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     // tile touches stay in the L1 cache.
     {
         const int f_lo = L.f_lo, n_leaves = L.n_leaves;
-        for (int li = tid; li < n_leaves; li += kPackThreads) L.u.leaf_off[li] = (int32_t)tout.leaf[f_lo + li].offset;
+        for (int li = tid; li < n_leaves; li += kPackThreads) L.u.look.leaf_off[li] = (int32_t)tout.leaf[f_lo + li].offset;
+        {
+            const int n_rows_lds = min(n_leaves, kLdsLeafRows) * 27;
+            const int32_t* src = leaf_nbr + (int64_t)f_lo * 27;
+            for (int e = tid; e < n_rows_lds; e += kPackThreads) L.u.look.nbr_rows[e] = src[e];
+        }
         __syncthreads();
         int32_t* my_nb = L.nb + tid * K3;
         if (tid < n_valid) {
@@ -339,11 +348,11 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
             int lo = 0, hi = n_leaves;   // last leaf of the tile with offset <= o
             while (hi - lo > 1) {
                 const int mid = (lo + hi) >> 1;
-                if (L.u.leaf_off[mid] <= o) lo = mid; else hi = mid;
+                if (L.u.look.leaf_off[mid] <= o) lo = mid; else hi = mid;
             }
             const int f = f_lo + lo;
             const fx_leaf* lf = tout.leaf + f;
-            int r = o - L.u.leaf_off[lo];           // rank of the voxel inside its leaf
+            int r = o - L.u.look.leaf_off[lo];           // rank of the voxel inside its leaf
             const uint64_t pre = lf->prefix;
             int wn = 0, before = 0;                 // mask word holding the voxel, active voxels before that word
 #pragma unroll
@@ -356,6 +365,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
             const int bi = (stride * lf->origin[0] + D0) >> 3, bj = (stride * lf->origin[1] + D0) >> 3,
                       bk = (stride * lf->origin[2] + D0) >> 3;
             const int32_t* nbr_row = leaf_nbr + (int64_t)f * 27;
+            const bool row_in_lds = lo < kLdsLeafRows;
             // kept as a rolled loop: the fully unrolled form of this divergent body gave wrong entries
             // for the offsets (-1,0,0), (0,-1,0), (0,0,-1) on gfx950 (cause not established; the
             // parity tests against the oracle catch it)
@@ -365,17 +375,18 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
                 const int qj = stride * pj + D0 + (kappa / K) % K;
                 const int qk = stride * pk + D0 + kappa % K;
                 const int slot = (((qi >> 3) - bi) * 3 + ((qj >> 3) - bj)) * 3 + ((qk >> 3) - bk);
-                const int id = nbr_row[slot];
+                const int id = row_in_lds ? L.u.look.nbr_rows[lo * 27 + slot] : nbr_row[slot];
                 int res = -1;
                 if (id >= 0) {
                     const fx_leaf* nl = tin.leaf + id;
                     const int n2 = qi & 7;
+                    // the three loads are independent: one memory round trip per offset
                     const uint64_t w = nl->mask[n2];
+                    const uint64_t npre = nl->prefix;
+                    const int32_t noff = (int32_t)nl->offset;
                     const uint64_t qb = 1ull << (((qj & 7) << 3) | (qk & 7));
-                    if (w & qb) {
-                        const uint64_t sum = n2 ? (nl->prefix >> (9 * (n2 - 1))) & 511 : 0;
-                        res = (int)(nl->offset + (int64_t)sum) + __popcll(w & (qb - 1));
-                    }
+                    const int sum = n2 ? (int)((npre >> (9 * (n2 - 1))) & 511) : 0;
+                    if (w & qb) res = noff + sum + __popcll(w & (qb - 1));
                 }
                 my_nb[kappa] = res;
             }
