@@ -45,6 +45,38 @@ def accounting(n_in, n_out, pairs, k3, c_in, c_out, elem_bytes, out_bytes):
     return flops, conv_bytes, kmap_bytes, grid_bytes
 
 
+def pmc_summary(directory):
+    """Per-kernel averages of the counters in a `rocprofv3 --pmc ... --output-format csv` run."""
+    import collections
+    import csv
+    import glob
+    files = glob.glob(os.path.join(directory, "**", "*counter_collection.csv"), recursive=True)
+    if not files:
+        print(f"no *counter_collection.csv under {directory}", file=sys.stderr)
+        sys.exit(1)
+    acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    for f in files:
+        for row in csv.DictReader(open(f)):
+            name = row["Kernel_Name"].split("(")[0]
+            acc[name][row["Counter_Name"]].append(float(row["Counter_Value"]))
+    for name in sorted(acc):
+        for ctr, v in sorted(acc[name].items()):
+            print(f"{name[:90]:90s} {ctr:28s} dispatches {len(v):4d}  mean {sum(v) / len(v):16.1f}  max {max(v):16.1f}")
+
+
+def committed_traffic(kernel, workload):
+    """HBM bytes per launch measured with rocprofv3 counters and committed under profiles/
+    (a line `traffic_bytes_per_launch: N` in profiles/<kernel>_<workload>_hbm_traffic.md)."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,7 +85,14 @@ def main():
     ap.add_argument("--workload", default="lidar1m", choices=sorted(WORKLOAD_DESC))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=300000)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch a plain elementwise copy kernel of known size (256 MiB read + 256 MiB "
+                         "written), the yardstick for the FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--pmc-summary", metavar="DIR", help="print per-kernel counter averages of a rocprofv3 --pmc run")
     args = ap.parse_args()
+    if args.pmc_summary:
+        pmc_summary(args.pmc_summary)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards by grid of the batch; see DESIGN.md); "
               "--gpus must be 1", file=sys.stderr)
@@ -74,6 +113,14 @@ def main():
     d_w = torch.from_numpy(wt).to(tdt).cuda().contiguous()
     elem = 4 if w.dtype == "f32" else 2
 
+    if args.copy_calibration:
+        src = torch.zeros(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)        # one vectorised elementwise kernel: 4 B read + 4 B written per element
+        torch.cuda.synchronize()
+        del src, dst
+
     def step(out=None):
         g = fx.build_index_grid(d_ijk, joffsets)
         km = fx.build_kernel_map(g, w.kernel_size, w.stride)
@@ -85,6 +132,8 @@ def main():
     n_in, n_out = g.num_voxels, km.n_out
     pairs, _ = km.info()
     tstats = km.tile_stats()
+    tiled_bytes = km.tiled_bytes()
+    n_leaf_out = km.g_out.counts()[0]
     flops, conv_bytes, kmap_bytes, grid_bytes = accounting(n_in, n_out, pairs, w.k3, w.c_in, w.c_out, elem, elem)
     out_buf = torch.empty_like(y)
     del g, km, y
@@ -150,15 +199,19 @@ def main():
         roof = {"kernel": dom, "bound": "alu", "achieved": flops / (dom_ms * 1e-3) / 1e12,
                 "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = committed_traffic(dom, args.workload)
     roof["avg_launch_ms"] = dom_ms
     roof["hbm_view"] = {"algorithmic_bytes": conv_bytes, "GB/s": conv_bytes / (dom_ms * 1e-3) / 1e9,
                         "frac_of_8TBs": conv_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
-    nb_ms = kern_ms.get("k_nbmap")
+    # map build: bytes of the tiled map actually written + the 96-byte leaf records read once
+    bt_ms = kern_ms.get("k_build_tiles")
     kmap_roof = None
-    if nb_ms:
-        kmap_roof = {"kernel": "k_nbmap", "bound": "hbm", "achieved": kmap_bytes / (nb_ms * 1e-3) / 1e9,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "avg_launch_ms": nb_ms}
+    if bt_ms:
+        bt_bytes = tiled_bytes + 96 * n_leaf_out
+        kmap_roof = {"kernel": "k_build_tiles", "bound": "hbm", "achieved": bt_bytes / (bt_ms * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "avg_launch_ms": bt_ms, "algorithmic_bytes": bt_bytes,
+                     "dense_map_equivalent_GBs": kmap_bytes / (bt_ms * 1e-3) / 1e9,
+                     "traffic": committed_traffic("k_build_tiles", args.workload)}
         kmap_roof["frac"] = kmap_roof["achieved"] / HBM_PEAK_GBS
 
     result = {

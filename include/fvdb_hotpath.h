@@ -134,6 +134,11 @@ fx_status fx_kmap_dense(const fx_kmap* km, int32_t* d_nbmap, void* stream);
  * over tiles, [3] = tile size T.  Synchronises the build stream. */
 fx_status fx_kmap_tile_stats(const fx_kmap* km, int64_t* h_stats4);
 
+/* Bytes of the tiled form that the map build wrote to device memory (tile headers, output
+ * permutations, row lists, id blocks): the figure the map build's bandwidth is quoted on.
+ * 0 for maps that are kept as a dense table only (K = 5).  Synchronises the build stream. */
+fx_status fx_kmap_tiled_bytes(const fx_kmap* km, int64_t* h_bytes);
+
 void fx_kmap_destroy(fx_kmap* km);
 
 /* ---------------------------------------------------------------------------------------
@@ -159,7 +164,7 @@ fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, fx_dtype in_
  * Measurement support (the paper's protocol, Sec. 4.1: per-operator times).  While enabled,
  * every kernel launch of the library is bracketed by hipEvents on its launch stream;
  * fx_profile_read waits for the recorded events and returns the summed time and launch count
- * of one slot (slot names: fx_profile_slot_name, e.g. "k_conv_mfma", "k_nbmap").
+ * of one slot (slot names: fx_profile_slot_name, e.g. "k_conv_mfma", "k_build_tiles").
  */
 void        fx_profile_enable(int on);
 void        fx_profile_reset(void);

@@ -64,6 +64,8 @@ def _load():
     L.fx_kmap_dense.argtypes = [vp, vp, vp]
     L.fx_kmap_tile_stats.restype = C.c_int
     L.fx_kmap_tile_stats.argtypes = [vp, vp]
+    L.fx_kmap_tiled_bytes.restype = C.c_int
+    L.fx_kmap_tiled_bytes.argtypes = [vp, C.POINTER(i64)]
     L.fx_kmap_destroy.argtypes = [vp]
     L.fx_sparse_conv_fwd.restype = C.c_int
     L.fx_sparse_conv_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
@@ -203,6 +205,11 @@ class KernelMap:
         s = np.zeros(4, dtype=np.int64)
         _check(lib.fx_kmap_tile_stats(self._h, s.ctypes.data_as(C.c_void_p)))
         return {"mfma_rows_issued": int(s[0]), "n_tiles": int(s[1]), "staged_rows": int(s[2]), "tile": int(s[3])}
+
+    def tiled_bytes(self) -> int:
+        b = C.c_int64()
+        _check(lib.fx_kmap_tiled_bytes(self._h, C.byref(b)))
+        return int(b.value)
 
     def dense(self) -> torch.Tensor:
         out = torch.empty((self.n_out, self.k3), dtype=torch.int32, device="cuda")

@@ -41,8 +41,8 @@ fx_status host_staging(void** p, size_t bytes);
 // of hipEvents on the launch stream; fx_profile_read sums the elapsed times per slot.
 enum ProfSlot {
     kProfFindTiles = 0, kProfRankTiles, kProfInsertUpper, kProfScanUpper, kProfInsertLower, kProfScanLower,
-    kProfInsertLeaf, kProfScanLeaf, kProfVoxBase, kProfGridIjk, kProfNbmap, kProfPackTiles, kProfPackWeights,
-    kProfConvMfma, kProfConvScalar, kProfMemset, kProfSlotCount
+    kProfInsertLeaf, kProfScanLeaf, kProfVoxBase, kProfGridIjk, kProfNbmap, kProfLeafNeighbors, kProfBuildTiles,
+    kProfPackWeights, kProfConvMfma, kProfConvScalar, kProfMemset, kProfSlotCount
 };
 bool prof_enabled();
 void prof_begin(int slot, hipStream_t s);

@@ -83,12 +83,13 @@ struct fx_kmap {
     int32_t* d_tile_rows = nullptr;         // [n_tiles][row_stride] global input rows (halo / direct)
     uint16_t* d_tile_blocks = nullptr;      // [n_tiles][block_stride][16][8] local row ids (id blocks)
     int32_t row_stride = 0, block_stride = 0;
-    int64_t* d_stats = nullptr;             // [4 + K3]: MFMA rows issued, staged rows, direct tiles, spare, pairs per offset
+    int64_t* d_stats = nullptr;             // [4 + K3]: MFMA rows issued, staged rows, direct tiles, tiled bytes, pairs per offset
     void* d_alloc = nullptr;                // single allocation backing all of the above
     bool stats_valid = false;
     int64_t h_stats[4] = {0, 0, 0, 0};
     int64_t* h_pairs = nullptr;             // [K3]
     int64_t h_n_pairs = 0;
+    int64_t h_tiled_bytes = 0;              // bytes of the tiled form the builder wrote
 };
 
 namespace fx {

@@ -496,6 +496,8 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
         atomicAdd(&stats[0], (unsigned long long)L.n_pair_blocks * kGroup);
         atomicAdd(&stats[1], (unsigned long long)(direct ? n_list : (uint32_t)(win_n + n_halo)));
         if (direct) atomicAdd(&stats[2], 1ull);
+        atomicAdd(&stats[3], (unsigned long long)(sizeof(TileHeader) + sizeof(uint16_t) * kTileT + sizeof(int32_t) * n_list +
+                                                  sizeof(uint16_t) * kIdBlockElems * (size_t)L.n_blocks));
     }
     if (tid < kGroupsPerTile) H->group_mask[tid] = L.group_mask[tid];
     if (tid < kTileWaves) { H->wave_mask[tid] = L.wave_mask[tid]; H->wave_block0[tid] = L.wave_block0[tid]; }
@@ -708,14 +710,14 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
         const unsigned ntl = (unsigned)km->n_tiles;
         const TreeView tin = g_in->view(), tout = gout->view();
         {
-            ProfScope ps(kProfNbmap, st);
+            ProfScope ps(kProfLeafNeighbors, st);
             const int64_t ne = (int64_t)gout->hdr.n_leaf * 27;
             const unsigned nbk = (unsigned)((ne + 255) / 256);
             if (K == 1) k_leaf_neighbors<1><<<nbk, 256, 0, st>>>(tin, tout, stride, d_leaf_nbr);
             else if (K == 2) k_leaf_neighbors<2><<<nbk, 256, 0, st>>>(tin, tout, stride, d_leaf_nbr);
             else k_leaf_neighbors<3><<<nbk, 256, 0, st>>>(tin, tout, stride, d_leaf_nbr);
         }
-        ProfScope ps(kProfPackTiles, st);
+        ProfScope ps(kProfBuildTiles, st);
 #define FX_TILES(KV, SUBMV)                                                                                    \
     do {                                                                                                       \
         e = hipFuncSetAttribute((const void*)k_build_tiles<KV, SUBMV>,                                         \
@@ -771,6 +773,7 @@ static fx_status kmap_fetch_stats(fx_kmap* km) {
     FX_HIP_TRY(hipStreamSynchronize(st));
     const int64_t* h = (const int64_t*)stage;
     km->h_stats[0] = h[0]; km->h_stats[1] = km->n_tiles; km->h_stats[2] = h[1]; km->h_stats[3] = kTileT;
+    km->h_tiled_bytes = h[3];
     km->h_n_pairs = 0;
     for (int k = 0; k < km->K3; ++k) { km->h_pairs[k] = h[4 + k]; km->h_n_pairs += h[4 + k]; }
     km->stats_valid = true;
@@ -796,6 +799,14 @@ extern "C" fx_status fx_kmap_tile_stats(const fx_kmap* km_, int64_t* h_stats4) {
     if (!km || !h_stats4) { set_error("fx_kmap_tile_stats: null pointer"); return FX_EINVAL; }
     FX_TRY(kmap_fetch_stats(km));
     memcpy(h_stats4, km->h_stats, sizeof(km->h_stats));
+    return FX_OK;
+}
+
+extern "C" fx_status fx_kmap_tiled_bytes(const fx_kmap* km_, int64_t* h_bytes) {
+    fx_kmap* km = const_cast<fx_kmap*>(km_);
+    if (!km || !h_bytes) { set_error("fx_kmap_tiled_bytes: null pointer"); return FX_EINVAL; }
+    FX_TRY(kmap_fetch_stats(km));
+    *h_bytes = km->h_tiled_bytes;
     return FX_OK;
 }
 
