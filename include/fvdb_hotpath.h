@@ -61,6 +61,11 @@ const char* fx_version(void);
 fx_status   fx_init(void);
 const char* fx_last_error(void);
 
+/* Device memory released by the library's calls is cached for reuse by later calls (bounded by
+ * the environment variable FVDB_HOTPATH_CACHE_MB, default 16384).  This returns all cached blocks
+ * to the driver; it waits for the device first. */
+void fx_release_cached_memory(void);
+
 /* ---------------------------------------------------------------------------------------
  * Index-grid build (Sec. 3.3: build an IndexGrid from N signed voxel coordinates; Sec. 3.2
  * and Listings 1-2: the leaf / lower / upper node layout and offsets; Sec. 3.6: batches).

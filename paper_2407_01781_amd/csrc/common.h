@@ -33,8 +33,10 @@ void set_error(const char* fmt, ...);
 fx_status dev_alloc(void** p, size_t bytes, hipStream_t s);
 void dev_free(void* p, hipStream_t s);
 
-// pinned host staging area owned by the library (per thread), at least `bytes` large
-fx_status host_staging(void** p, size_t bytes);
+// Pinned host staging owned by the library (per thread), at least `bytes` large.  Area 0 is
+// for read-backs (the caller synchronises before using the data), area 1 for uploads that stay
+// in flight until the caller's next synchronisation on the same stream.
+fx_status host_staging(void** p, size_t bytes, int area = 0);
 
 // ------------------------------------------------------------------ per-kernel timing
 // When enabled (fx_profile_enable), every kernel launch of the library is bracketed by a pair
@@ -52,6 +54,14 @@ struct ProfScope {
     ProfScope(int slot_, hipStream_t s_) : slot(slot_), s(s_), on(prof_enabled()) { if (on) prof_begin(slot, s); }
     ~ProfScope() { if (on) prof_end(slot, s); }
 };
+
+// development aid (-DFX_HOST_TIMING): host time between consecutive marks, summed per label
+#ifdef FX_HOST_TIMING
+void ht_mark(const char* label);
+#define FX_HT(label) fx::ht_mark(label)
+#else
+#define FX_HT(label) do { } while (0)
+#endif
 
 // ------------------------------------------------------------------ tree layout
 // Node fan-outs of the VDB tree (Sec. 3.1): upper 32^3 children, lower 16^3, leaf 8^3 voxels.

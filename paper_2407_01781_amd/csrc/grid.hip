@@ -452,6 +452,7 @@ static fx_status scan_level(const fx_grid* g, LevelScan s, int cap_nodes, uint32
 // capacity was too small (the counts found so far are valid up to the overflowing level).
 static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64_t* d_joff, int32_t B,
                                int cap_upper, int cap_lower, int cap_leaf, hipStream_t st, fx_grid** out) {
+    FX_HT("(outside)");
     fx_grid* g = new (std::nothrow) fx_grid();
     if (!g) { set_error("host allocation failed"); return FX_ENOMEM; }
     g->B = B; g->stream = st;
@@ -475,6 +476,7 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     int32_t* d_rep = d_slots + kTileHashSlots;
     uint32_t* d_block_sums = (uint32_t*)(d_rep + kMaxTiles);
 
+    FX_HT("grid: allocs");
     auto fail = [&](fx_status s) { dev_free(scratch, st); fx_grid_destroy(g); return s; };
 #define FX_TRY_OR_FAIL(expr) do { hipError_t _e = (expr); if (_e != hipSuccess) { \
         set_error("%s failed: %s", #expr, hipGetErrorString(_e)); return fail(FX_EDEVICE); } } while (0)
@@ -484,6 +486,7 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
         FX_TRY_OR_FAIL(hipMemsetAsync(g->buf, 0, g->buf_bytes, st));
         FX_TRY_OR_FAIL(hipMemsetAsync(d_slots, 0xFF, sizeof(int32_t) * kTileHashSlots, st));
     }
+    FX_HT("grid: memsets");
     const GridPtrs q = ptrs_of(g);
     if (n_rows > 0 && B > 0) {
         const int nb = blocks_for_rows(n_rows);
@@ -513,6 +516,7 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
         { ProfScope ps(kProfVoxBase, st); k_vox_base<<<(B + 1 + 255) / 256, 256, 0, st>>>(q); }
         FX_TRY_OR_FAIL(hipGetLastError());
     }
+    FX_HT("grid: kernel launches");
     // one read-back: counts + per-grid ranges (Sec. 3.3 step 10)
     const size_t hdr_bytes = sizeof(GridHeader);
     const size_t vb_bytes = sizeof(int64_t) * ((size_t)B + 1);
@@ -521,10 +525,13 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     if (rc != FX_OK) return fail(rc);
     FX_TRY_OR_FAIL(hipMemcpyAsync(stage, g->d_hdr, hdr_bytes, hipMemcpyDeviceToHost, st));
     FX_TRY_OR_FAIL(hipMemcpyAsync((char*)stage + hdr_bytes, g->d_vox_base, vb_bytes, hipMemcpyDeviceToHost, st));
+    FX_HT("grid: d2h enqueue");
     FX_TRY_OR_FAIL(hipStreamSynchronize(st));
+    FX_HT("grid: sync");
     memcpy(&g->hdr, stage, hdr_bytes);
     memcpy(g->h_vox_base, (char*)stage + hdr_bytes, vb_bytes);
     dev_free(scratch, st);
+    FX_HT("grid: free scratch");
 #undef FX_TRY_OR_FAIL
     *out = g;
     return FX_OK;
@@ -586,19 +593,23 @@ extern "C" fx_status fx_build_index_grid(const int32_t* d_ijk, int64_t n_rows, c
     hipStream_t st = (hipStream_t)stream;
     int64_t* d_joff = nullptr;
     const size_t jb = sizeof(int64_t) * 2 * (size_t)std::max(B, 1);
+    FX_HT("(outside)");
     FX_TRY(dev_alloc((void**)&d_joff, jb, st));
+    FX_HT("grid: joff alloc");
     if (B > 0) {
         void* stage = nullptr;
-        fx_status rc = host_staging(&stage, jb);
+        fx_status rc = host_staging(&stage, jb, 1);
         if (rc != FX_OK) { dev_free(d_joff, st); return rc; }
         memcpy(stage, h_joffsets, sizeof(int64_t) * 2 * (size_t)B);
+        // no wait here: the build below synchronises the stream before it returns
         hipError_t e = hipMemcpyAsync(d_joff, stage, sizeof(int64_t) * 2 * (size_t)B, hipMemcpyHostToDevice, st);
-        if (e == hipSuccess) e = hipStreamSynchronize(st);  // the staging area is reused below
         if (e != hipSuccess) { dev_free(d_joff, st); set_error("joffsets upload failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
     }
+    FX_HT("grid: joff upload+sync");
     fx_grid* g = nullptr;
     fx_status rc = build_index_grid_device_joff(d_ijk, n_rows, d_joff, B, st, &g);
     dev_free(d_joff, st);
+    FX_HT("grid: free joff");
     if (rc != FX_OK) return rc;
     *out = g;
     return FX_OK;
@@ -667,12 +678,11 @@ extern "C" fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** 
     }
     if (g->B > 0) {
         void* stage = nullptr;
-        rc = host_staging(&stage, sizeof(int64_t) * 2 * (size_t)g->B);
+        rc = host_staging(&stage, sizeof(int64_t) * 2 * (size_t)g->B, 1);
         if (rc != FX_OK) { cleanup(); return rc; }
         int64_t* hj = (int64_t*)stage;
         for (int b = 0; b < g->B; ++b) { hj[2 * b] = g->h_vox_base[b]; hj[2 * b + 1] = g->h_vox_base[b + 1]; }
         hipError_t e = hipMemcpyAsync(d_joff, stage, sizeof(int64_t) * 2 * (size_t)g->B, hipMemcpyHostToDevice, st);
-        if (e == hipSuccess) e = hipStreamSynchronize(st);
         if (e != hipSuccess) { cleanup(); set_error("joffsets upload failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
     }
     fx_grid* o = nullptr;

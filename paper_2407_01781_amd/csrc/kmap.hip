@@ -669,6 +669,7 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     }
     hipStream_t st = (hipStream_t)stream;
     fx_grid* gout = nullptr;
+    FX_HT("(outside)");
     if (stride == 1) { gout = g_in; fx_grid_retain(gout); }
     else FX_TRY(fx_grid_coarsen2(g_in, stream, &gout));
 
@@ -693,7 +694,9 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     const size_t o_tr = take(tiled ? sizeof(int32_t) * (size_t)km->row_stride * nt : 0);
     const size_t o_tb = take(tiled ? sizeof(uint16_t) * kIdBlockElems * (size_t)km->block_stride * nt : 0);
     const size_t o_ln = take(tiled ? sizeof(int32_t) * 27 * (size_t)std::max(gout->hdr.n_leaf, 1) : 0);
+    FX_HT("kmap: host setup");
     fx_status rc = dev_alloc(&km->d_alloc, off, st);
+    FX_HT("kmap: alloc");
     if (rc != FX_OK) { fx_kmap_destroy(km); return rc; }
     char* p = (char*)km->d_alloc;
     km->d_stats = (int64_t*)(p + o_st);
@@ -735,6 +738,7 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
 #undef FX_TILES
         if (e == hipSuccess) e = hipGetLastError();
     }
+    FX_HT("kmap: memset + launches");
     if (e != hipSuccess) {
         set_error("kernel-map build failed: %s", hipGetErrorString(e));
         fx_kmap_destroy(km);

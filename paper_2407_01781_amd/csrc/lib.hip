@@ -18,9 +18,13 @@ void set_error(const char* fmt, ...) {
     va_end(ap);
 }
 
-// Stream-ordered allocation from the device's default memory pool; the pool keeps freed
-// blocks (release threshold = max) so steady-state builds do not reach the driver.
-// FVDB_HOTPATH_SYNC_ALLOC=1 switches to plain hipMalloc / hipFree.
+// Device memory comes from a cache of blocks owned by the library: a freed block is kept and
+// handed to the next request of a similar size, so steady-state calls (same shapes every step)
+// never reach the driver -- hipMallocAsync / hipFreeAsync cost 70-300 us per call here.  All
+// work of this library is stream-ordered, so a block released on stream S can be reused at once
+// by later work on S; reuse from another stream first waits for the device.
+// FVDB_HOTPATH_SYNC_ALLOC=1 switches to plain hipMalloc / hipFree; FVDB_HOTPATH_CACHE_MB bounds
+// the bytes kept (default 16384).
 static int use_sync_alloc() {
     static int v = -1;
     if (v < 0) {
@@ -30,46 +34,115 @@ static int use_sync_alloc() {
     return v;
 }
 
-static void ensure_pool_configured() {
-    static thread_local int done_for_device = -1;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return;
-    if (done_for_device == dev) return;
-    hipMemPool_t pool;
-    if (hipDeviceGetDefaultMemPool(&pool, dev) == hipSuccess) {
-        uint64_t thr = UINT64_MAX;
-        (void)hipMemPoolSetAttribute(pool, hipMemPoolAttrReleaseThreshold, &thr);
+struct Block { void* p; size_t bytes; hipStream_t stream; int device; };
+static std::mutex g_mem_mu;
+static std::vector<Block> g_mem_free;              // cached, oldest first
+static std::vector<Block> g_mem_live;
+static size_t g_mem_cached = 0;
+
+static size_t cache_limit() {
+    static size_t v = 0;
+    if (!v) {
+        const char* e = getenv("FVDB_HOTPATH_CACHE_MB");
+        const long mb = e ? atol(e) : 16384;
+        v = (size_t)(mb > 0 ? mb : 1) << 20;
     }
-    done_for_device = dev;
+    return v;
+}
+
+static size_t round_size(size_t bytes) {   // at most 12.5 % above the request, few distinct sizes
+    if (bytes < 4096) return 4096;
+    size_t p2 = (size_t)1 << (63 - __builtin_clzll((unsigned long long)bytes));
+    const size_t step = p2 >> 3;
+    return (bytes + step - 1) / step * step;
+}
+
+static void release_cached_locked() {
+    for (auto& b : g_mem_free) (void)hipFree(b.p);
+    g_mem_free.clear();
+    g_mem_cached = 0;
 }
 
 fx_status dev_alloc(void** p, size_t bytes, hipStream_t s) {
-    if (bytes == 0) bytes = 256;
-    hipError_t e;
+    *p = nullptr;
     if (use_sync_alloc()) {
-        e = hipMalloc(p, bytes);
+        hipError_t e = hipMalloc(p, bytes ? bytes : 256);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            set_error("device allocation of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+            return e == hipErrorOutOfMemory ? FX_ENOMEM : FX_EDEVICE;
+        }
+        return FX_OK;
+    }
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { set_error("hipGetDevice failed"); return FX_EDEVICE; }
+    const size_t need = round_size(bytes);
+    std::lock_guard<std::mutex> lock(g_mem_mu);
+    int best = -1;
+    for (int i = 0; i < (int)g_mem_free.size(); ++i) {
+        const Block& b = g_mem_free[i];
+        if (b.device != dev || b.bytes < need || b.bytes > 2 * need) continue;
+        if (best < 0 || b.bytes < g_mem_free[best].bytes || (b.bytes == g_mem_free[best].bytes && b.stream == s)) best = i;
+    }
+    Block blk;
+    if (best >= 0) {
+        blk = g_mem_free[best];
+        g_mem_free.erase(g_mem_free.begin() + best);
+        g_mem_cached -= blk.bytes;
+        if (blk.stream != s && hipDeviceSynchronize() != hipSuccess) {
+            (void)hipFree(blk.p);
+            set_error("hipDeviceSynchronize failed while reusing a cached block");
+            return FX_EDEVICE;
+        }
+        blk.stream = s;
     } else {
-        ensure_pool_configured();
-        e = hipMallocAsync(p, bytes, s);
+        hipError_t e = hipMalloc(&blk.p, need);
+        if (e == hipErrorOutOfMemory) {       // give the cache back and try once more
+            (void)hipGetLastError();
+            release_cached_locked();
+            e = hipMalloc(&blk.p, need);
+        }
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            set_error("device allocation of %zu bytes failed: %s", need, hipGetErrorString(e));
+            return e == hipErrorOutOfMemory ? FX_ENOMEM : FX_EDEVICE;
+        }
+        blk.bytes = need; blk.stream = s; blk.device = dev;
     }
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        set_error("device allocation of %zu bytes failed: %s", bytes, hipGetErrorString(e));
-        *p = nullptr;
-        return e == hipErrorOutOfMemory ? FX_ENOMEM : FX_EDEVICE;
-    }
+    g_mem_live.push_back(blk);
+    *p = blk.p;
     return FX_OK;
 }
 
 void dev_free(void* p, hipStream_t s) {
     if (!p) return;
-    if (use_sync_alloc()) {
-        (void)hipFree(p);
-    } else if (hipFreeAsync(p, s) != hipSuccess) {
-        (void)hipGetLastError();
-        (void)hipFree(p);
+    if (use_sync_alloc()) { (void)hipFree(p); return; }
+    std::lock_guard<std::mutex> lock(g_mem_mu);
+    for (int i = (int)g_mem_live.size() - 1; i >= 0; --i) {
+        if (g_mem_live[i].p != p) continue;
+        Block blk = g_mem_live[i];
+        g_mem_live[i] = g_mem_live.back();
+        g_mem_live.pop_back();
+        blk.stream = s;
+        g_mem_free.push_back(blk);
+        g_mem_cached += blk.bytes;
+        while (g_mem_cached > cache_limit() && !g_mem_free.empty()) {   // hipFree waits for the device
+            g_mem_cached -= g_mem_free.front().bytes;
+            (void)hipFree(g_mem_free.front().p);
+            g_mem_free.erase(g_mem_free.begin());
+        }
+        return;
     }
+    (void)hipFree(p);   // not ours (allocated before a mode switch)
 }
+
+}  // namespace fx
+extern "C" void fx_release_cached_memory(void) {
+    std::lock_guard<std::mutex> lock(fx::g_mem_mu);
+    (void)hipDeviceSynchronize();
+    fx::release_cached_locked();
+}
+namespace fx {
 
 struct Staging {
     void* p = nullptr;
@@ -77,10 +150,14 @@ struct Staging {
     ~Staging() { if (p) (void)hipHostFree(p); }
 };
 
-fx_status host_staging(void** p, size_t bytes) {
-    static thread_local Staging st;
+fx_status host_staging(void** p, size_t bytes, int area) {
+    static thread_local Staging areas[2];
+    Staging& st = areas[area & 1];
     if (st.bytes < bytes) {
-        if (st.p) (void)hipHostFree(st.p);
+        if (st.p) {
+            (void)hipDeviceSynchronize();   // an upload from the old area may still be in flight
+            (void)hipHostFree(st.p);
+        }
         st.p = nullptr;
         size_t want = bytes < 65536 ? 65536 : bytes;
         hipError_t e = hipHostMalloc(&st.p, want, hipHostMallocDefault);
@@ -94,6 +171,29 @@ fx_status host_staging(void** p, size_t bytes) {
     *p = st.p;
     return FX_OK;
 }
+
+#ifdef FX_HOST_TIMING
+}  // namespace fx
+#include <chrono>
+#include <map>
+namespace fx {
+static std::map<std::string, std::pair<double, long>> g_ht;
+static std::vector<std::string> g_ht_order;
+static std::chrono::steady_clock::time_point g_ht_last = std::chrono::steady_clock::now();
+void ht_mark(const char* label) {
+    const auto now = std::chrono::steady_clock::now();
+    const double us = std::chrono::duration<double, std::micro>(now - g_ht_last).count();
+    g_ht_last = now;
+    auto it = g_ht.find(label);
+    if (it == g_ht.end()) { g_ht[label] = {us, 1}; g_ht_order.push_back(label); }
+    else { it->second.first += us; it->second.second++; }
+}
+extern "C" void fx_debug_host_timing_dump(int reset) {
+    for (auto& l : g_ht_order) printf("  %-28s %9.1f us avg over %ld\n", l.c_str(), g_ht[l].first / g_ht[l].second, g_ht[l].second);
+    if (reset) { g_ht.clear(); g_ht_order.clear(); }
+    g_ht_last = std::chrono::steady_clock::now();
+}
+#endif
 
 // ---------------------------------------------------------------------------------- profiler
 struct ProfRec { int slot; hipEvent_t a, b; };
