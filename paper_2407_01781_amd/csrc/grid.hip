@@ -2,11 +2,12 @@
 //
 // The paper orders the voxels with two radix sorts (tile key a, then key b) and derives the
 // nodes from runs of equal key prefixes.  Here the tree does the ordering itself: every level
-// keeps a child bitmask, a voxel pass sets the bits of the nodes it touches (the paper's
-// "register ... into its parent" steps 11.1-11.4), and a popcount prefix scan over the masks
-// numbers the children in exactly the order the sorts would give (bit order of a mask =
-// Listing 2's offset order; node order = parent order).  Only the few root tiles are ranked
-// by comparison.  Four streaming passes over ijk replace the sorts.
+// keeps a child bitmask, set bit by bit (the paper's "register ... into its parent" steps
+// 11.1-11.4), and a popcount prefix scan over the masks numbers the children in exactly the
+// order the sorts would give (bit order of a mask = Listing 2's offset order; node order =
+// parent order).  Only the few root tiles are ranked by comparison.  One streaming pass over
+// ijk collects the distinct leaves and their voxel masks in a hash table; the levels above are
+// built from those leaves (tens of thousands) instead of from the voxels (millions).
 #include "common.h"
 #include "tree_device.h"
 
@@ -50,44 +51,113 @@ __device__ __forceinline__ uint32_t mix32(uint32_t h, uint32_t v) {
     return h;
 }
 
-// ---------------------------------------------------------------------------------- pass 1: root tiles
-// Distinct (grid, tile) pairs are collected in a small open-addressing table whose slots hold a
-// representative input row (the key is read back through that row), so one 32-bit CAS suffices.
-__global__ void k_find_tiles(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff,
-                             int B, int32_t* __restrict__ slots, int32_t* __restrict__ rep_rows,
-                             GridHeader* hdr) {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n_rows; r += stride) {
-        const int b = find_batch(joff, B, r);
-        if (b < 0) continue;
-        const int ti = ijk[3 * r] >> 12, tj = ijk[3 * r + 1] >> 12, tk = ijk[3 * r + 2] >> 12;
-        // lanes that share the first active lane's tile let that lane insert for them
-        const uint64_t active = __ballot(1);
-        const int leader = __ffsll((long long)active) - 1;
-        const int lb = __shfl(b, leader), li = __shfl(ti, leader), lj = __shfl(tj, leader),
-                  lk = __shfl(tk, leader);
-        const int lane = threadIdx.x & 63;
-        if (lane != leader && lb == b && li == ti && lj == tj && lk == tk) continue;
-        uint32_t h = mix32(mix32(mix32(mix32(0x811C9DC5u, (uint32_t)b), (uint32_t)ti), (uint32_t)tj), (uint32_t)tk);
-        h &= (kTileHashSlots - 1);
-        for (int probe = 0; probe < kTileHashSlots; ++probe) {
-            int32_t s = slots[h];
-            if (s < 0) {
-                if (hdr->n_tiles_raw > kMaxTiles) break;  // over the limit: reported by the ranking kernel
-                const int32_t old = atomicCAS(&slots[h], -1, (int32_t)r);
-                if (old < 0) {
-                    const int pos = atomicAdd(&hdr->n_tiles_raw, 1);
-                    if (pos < kMaxTiles) rep_rows[pos] = (int32_t)r;
-                    break;
-                }
+// ---------------------------------------------------------------------------------- pass 1: voxels -> leaves
+// The only pass over the input rows.  Distinct (grid, leaf) pairs are collected in an
+// open-addressing table whose slots hold a representative input row (+1; 0 = empty), so one
+// 32-bit CAS claims a slot and the key is read back through that row.  Each row then sets its
+// voxel bit in the 512-bit mask that belongs to the slot (step 11.4; duplicates collapse in
+// the bit).  Everything above the leaves -- root tiles, upper and lower nodes, the order of
+// the leaves -- is derived afterwards from the few distinct leaves instead of from the rows.
+struct LeafHash {
+    int32_t* slots;    // [n_slots]
+    uint64_t* mask;    // [n_slots][8]
+    int32_t* list;     // [cap_leaf] slot of every distinct leaf, in arrival order
+    uint32_t slot_mask;  // n_slots - 1 (power of two)
+    int32_t cap_leaf;
+};
+
+__global__ void __launch_bounds__(256)
+k_voxels_to_leaves(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff, int B,
+                   LeafHash H, GridHeader* hdr) {
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int b = r < n_rows ? find_batch(joff, B, r) : -1;
+    int i = 0, j = 0, k = 0;
+    uint32_t h = 0;
+    bool found = false, claimed = false;
+    if (b >= 0) {
+        i = ijk[3 * r]; j = ijk[3 * r + 1]; k = ijk[3 * r + 2];
+        const int li = i >> 3, lj = j >> 3, lk = k >> 3;
+        h = mix32(mix32(mix32(mix32(0x811C9DC5u, (uint32_t)b), (uint32_t)li), (uint32_t)lj), (uint32_t)lk);
+        h &= H.slot_mask;
+        for (uint32_t probe = 0; probe <= H.slot_mask; ++probe) {
+            // device-coherent read: a slot claimed from another XCD must be seen
+            int32_t s = __hip_atomic_load(&H.slots[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (s == 0) {
+                const int32_t old = atomicCAS(&H.slots[h], 0, (int32_t)r + 1);
+                if (old == 0) { found = claimed = true; break; }
                 s = old;
             }
-            const int sb = find_batch(joff, B, s);
-            if (sb == b && (ijk[3 * (int64_t)s] >> 12) == ti && (ijk[3 * (int64_t)s + 1] >> 12) == tj &&
-                (ijk[3 * (int64_t)s + 2] >> 12) == tk)
+            const int64_t q = s - 1;
+            if ((ijk[3 * q] >> 3) == li && (ijk[3 * q + 1] >> 3) == lj && (ijk[3 * q + 2] >> 3) == lk &&
+                find_batch(joff, B, q) == b) {
+                found = true;
                 break;
-            h = (h + 1) & (kTileHashSlots - 1);
+            }
+            h = (h + 1) & H.slot_mask;
         }
+        if (!found) atomicOr(&hdr->overflow, 4 | 32);   // table full: the leaf count is incomplete
+        else atomicOr((unsigned long long*)&H.mask[(size_t)h * 8 + (i & 7)], 1ull << (((j & 7) << 3) | (k & 7)));
+    }
+    // list the newly claimed leaves: one counter update per wave, not per leaf
+    const uint64_t cl = __ballot(claimed);
+    if (cl) {
+        const int lane = threadIdx.x & 63;
+        const int leader = __ffsll((long long)cl) - 1;
+        int base = 0;
+        if (lane == leader) base = atomicAdd(&hdr->n_leaf_raw, __popcll(cl));
+        base = __shfl(base, leader);
+        if (claimed) {
+            const int pos = base + __popcll(cl & ((1ull << lane) - 1));
+            if (pos < H.cap_leaf) H.list[pos] = (int32_t)h;
+            else atomicOr(&hdr->overflow, 4);
+        }
+    }
+}
+
+// representative input row of distinct leaf `idx`, or -1 past the end
+__device__ __forceinline__ int64_t leaf_rep_row(const LeafHash& H, const GridHeader* hdr, int64_t idx, int32_t* slot) {
+    const int n = min(hdr->n_leaf_raw, H.cap_leaf);
+    if (idx >= n) return -1;
+    const int32_t h = H.list[idx];
+    *slot = h;
+    return (int64_t)H.slots[h] - 1;
+}
+
+// ---------------------------------------------------------------------------------- root tiles
+// Distinct (grid, tile) pairs of the leaves go into a second small table of the same kind.
+__global__ void k_find_tiles(const int32_t* __restrict__ ijk, const int64_t* __restrict__ joff, int B, LeafHash H,
+                             int32_t* __restrict__ tile_slots, int32_t* __restrict__ rep_rows, GridHeader* hdr) {
+    if (hdr->overflow) return;
+    int32_t slot;
+    const int64_t r = leaf_rep_row(H, hdr, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, &slot);
+    if (r < 0) return;
+    const int b = find_batch(joff, B, r);
+    const int ti = ijk[3 * r] >> 12, tj = ijk[3 * r + 1] >> 12, tk = ijk[3 * r + 2] >> 12;
+    // lanes that share the first active lane's tile let that lane insert for them
+    const uint64_t active = __ballot(1);
+    const int leader = __ffsll((long long)active) - 1;
+    const int lb = __shfl(b, leader), li = __shfl(ti, leader), lj = __shfl(tj, leader), lk = __shfl(tk, leader);
+    const int lane = threadIdx.x & 63;
+    if (lane != leader && lb == b && li == ti && lj == tj && lk == tk) return;
+    uint32_t h = mix32(mix32(mix32(mix32(0x811C9DC5u, (uint32_t)b), (uint32_t)ti), (uint32_t)tj), (uint32_t)tk);
+    h &= (kTileHashSlots - 1);
+    for (int probe = 0; probe < kTileHashSlots; ++probe) {
+        int32_t s = tile_slots[h];
+        if (s == 0) {
+            if (hdr->n_tiles_raw > kMaxTiles) break;  // over the limit: reported by the ranking kernel
+            const int32_t old = atomicCAS(&tile_slots[h], 0, (int32_t)r + 1);
+            if (old == 0) {
+                const int pos = atomicAdd(&hdr->n_tiles_raw, 1);
+                if (pos < kMaxTiles) rep_rows[pos] = (int32_t)r;
+                break;
+            }
+            s = old;
+        }
+        const int64_t q = s - 1;
+        if (find_batch(joff, B, q) == b && (ijk[3 * q] >> 12) == ti && (ijk[3 * q + 1] >> 12) == tj &&
+            (ijk[3 * q + 2] >> 12) == tk)
+            break;
+        h = (h + 1) & (kTileHashSlots - 1);
     }
 }
 
@@ -95,6 +165,7 @@ __global__ void k_find_tiles(const int32_t* __restrict__ ijk, int64_t n_rows, co
 // (the run index M of Sec. 3.3 step 5).  O(T^2) comparisons; T is tiny for real scenes.
 __global__ void k_rank_tiles(const int32_t* __restrict__ ijk, const int64_t* __restrict__ joff, int B,
                              const int32_t* __restrict__ rep_rows, GridPtrs g) {
+    if (g.hdr->overflow) return;
     const int raw = g.hdr->n_tiles_raw;
     const int T = raw < kMaxTiles ? raw : kMaxTiles;
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
@@ -103,7 +174,7 @@ __global__ void k_rank_tiles(const int32_t* __restrict__ ijk, const int64_t* __r
         if (raw > kMaxTiles) ov |= 8;
         if (T > g.cap_upper) ov |= 1;
         g.hdr->n_upper = T;
-        if (ov) g.hdr->overflow = ov;
+        if (ov) atomicOr(&g.hdr->overflow, ov);
     }
     if (t >= T || T > g.cap_upper) return;
     const int64_t r = rep_rows[t];
@@ -120,56 +191,48 @@ __global__ void k_rank_tiles(const int32_t* __restrict__ ijk, const int64_t* __r
     g.root_batch[rank] = b;
 }
 
-// ---------------------------------------------------------------------------------- passes 2-4: set bits
+// ---------------------------------------------------------------------------------- leaves -> tree
+// One thread per distinct leaf.
 // LEVEL 0: lower-node bit in the upper node's child mask   (step 11.2)
 // LEVEL 1: leaf bit in the lower node's child mask         (step 11.3)
-// LEVEL 2: voxel bit in the leaf's mBitMask                (step 11.4)
+// LEVEL 2: the leaf's final id is known: move its mask from the table into the leaf record
 template <int LEVEL>
-__global__ void k_insert(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff,
-                         GridPtrs g) {
+__global__ void k_insert(const int32_t* __restrict__ ijk, const int64_t* __restrict__ joff, LeafHash H, GridPtrs g) {
     if (g.hdr->overflow) return;
-    const int n_upper = g.hdr->n_upper;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n_rows; r += stride) {
-        const int b = find_batch(joff, g.B, r);
-        if (b < 0) continue;
-        const int i = ijk[3 * r], j = ijk[3 * r + 1], k = ijk[3 * r + 2];
-        const int u = find_upper(g.root_key, g.root_batch, n_upper, b, tile_key(i, j, k));
-        if (u < 0) continue;
-        uint64_t* word;
-        uint64_t bit;
-        int f = -1;
-        if (LEVEL == 0) {
-            const int off = upper_off(i, j, k);
-            word = g.upper_mask + (size_t)u * kUpperWords + (off >> 6);
-            bit = 1ull << (off & 63);
-        } else {
-            const int l = child_of(g.upper_mask + (size_t)u * kUpperWords,
-                                   g.upper_prefix + (size_t)u * kUpperWords, upper_off(i, j, k));
-            if (l < 0) continue;
-            if (LEVEL == 1) {
-                const int off = lower_off(i, j, k);
-                word = g.lower_mask + (size_t)l * kLowerWords + (off >> 6);
-                bit = 1ull << (off & 63);
-            } else {
-                f = child_of(g.lower_mask + (size_t)l * kLowerWords, g.lower_prefix + (size_t)l * kLowerWords,
-                             lower_off(i, j, k));
-                if (f < 0) continue;
-                word = &g.leaf[f].mask[i & 7];
-                bit = 1ull << (((j & 7) << 3) | (k & 7));
-            }
-        }
-        if (*word & bit) continue;  // already registered (stale reads only cost a redundant atomic)
-        const uint64_t old = atomicOr((unsigned long long*)word, (unsigned long long)bit);
-        if (LEVEL == 2 && old == 0) {
-            // first voxel of this mask word: record where the leaf sits (all writers agree)
-            fx_leaf* lf = &g.leaf[f];
-            lf->origin[0] = (i >> 3) * 8;
-            lf->origin[1] = (j >> 3) * 8;
-            lf->origin[2] = (k >> 3) * 8;
-            lf->batch = b;
-        }
+    int32_t slot;
+    const int64_t r = leaf_rep_row(H, g.hdr, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, &slot);
+    if (r < 0) return;
+    const int b = find_batch(joff, g.B, r);
+    const int i = ijk[3 * r], j = ijk[3 * r + 1], k = ijk[3 * r + 2];
+    const int u = find_upper(g.root_key, g.root_batch, g.hdr->n_upper, b, tile_key(i, j, k));
+    if (u < 0) return;
+    if (LEVEL == 0) {
+        const int off = upper_off(i, j, k);
+        uint64_t* word = g.upper_mask + (size_t)u * kUpperWords + (off >> 6);
+        const uint64_t bit = 1ull << (off & 63);
+        if (!(*word & bit)) atomicOr((unsigned long long*)word, (unsigned long long)bit);  // stale reads only cost an atomic
+        return;
     }
+    const int l = child_of(g.upper_mask + (size_t)u * kUpperWords, g.upper_prefix + (size_t)u * kUpperWords,
+                           upper_off(i, j, k));
+    if (l < 0) return;
+    if (LEVEL == 1) {
+        const int off = lower_off(i, j, k);
+        uint64_t* word = g.lower_mask + (size_t)l * kLowerWords + (off >> 6);
+        atomicOr((unsigned long long*)word, 1ull << (off & 63));
+        return;
+    }
+    const int f = child_of(g.lower_mask + (size_t)l * kLowerWords, g.lower_prefix + (size_t)l * kLowerWords,
+                           lower_off(i, j, k));
+    if (f < 0) return;
+    fx_leaf* lf = &g.leaf[f];
+    const uint64_t* src = H.mask + (size_t)slot * 8;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) lf->mask[w] = src[w];
+    lf->origin[0] = (i >> 3) * 8;
+    lf->origin[1] = (j >> 3) * 8;
+    lf->origin[2] = (k >> 3) * 8;
+    lf->batch = b;
 }
 
 // ---------------------------------------------------------------------------------- popcount scans
@@ -427,12 +490,6 @@ static GridPtrs ptrs_of(const fx_grid* g) {
     return q;
 }
 
-static int blocks_for_rows(int64_t n_rows) {
-    // 8 rows per thread, 256 threads per block, at most 8 blocks per CU of a 256-CU part
-    int64_t b = (n_rows + 256 * 8 - 1) / (256 * 8);
-    return (int)std::max<int64_t>(1, std::min<int64_t>(b, 2048));
-}
-
 static fx_status scan_level(const fx_grid* g, LevelScan s, int cap_nodes, uint32_t* d_block_sums, hipStream_t st) {
     const int64_t cap_words = (int64_t)cap_nodes * s.words_per_node;
     const int n_blocks = (int)std::max<int64_t>(1, (cap_words + kWordChunk - 1) / kWordChunk);
@@ -463,18 +520,28 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     layout(g);
     g->h_vox_base = (int64_t*)calloc((size_t)B + 1, sizeof(int64_t));
 
-    // scratch: tile table, representative rows, scan block sums
+    // scratch: [tile table | leaf table slots | leaf table masks] cleared, then
+    //          [tile representative rows | leaf list | scan block sums] not cleared
     const int64_t max_items = std::max<int64_t>((int64_t)g->cap_lower * kLowerWords / kWordChunk,
                                                 std::max<int64_t>((int64_t)g->cap_upper * kUpperWords / kWordChunk,
                                                                   (int64_t)g->cap_leaf / kLeafChunk)) + 2;
-    const size_t scratch_bytes = sizeof(int32_t) * kTileHashSlots + sizeof(int32_t) * kMaxTiles +
+    size_t n_slots = 1024;
+    while (n_slots < 2 * (size_t)g->cap_leaf) n_slots <<= 1;
+    const size_t clear_bytes = sizeof(int32_t) * kTileHashSlots + (sizeof(int32_t) + 8 * sizeof(uint64_t)) * n_slots;
+    const size_t scratch_bytes = clear_bytes + sizeof(int32_t) * kMaxTiles + sizeof(int32_t) * (size_t)g->cap_leaf +
                                  sizeof(uint32_t) * (size_t)max_items;
     void* scratch = nullptr;
     rc = dev_alloc(&scratch, scratch_bytes, st);
     if (rc != FX_OK) { fx_grid_destroy(g); return rc; }
-    int32_t* d_slots = (int32_t*)scratch;
-    int32_t* d_rep = d_slots + kTileHashSlots;
-    uint32_t* d_block_sums = (uint32_t*)(d_rep + kMaxTiles);
+    LeafHash H;
+    H.mask = (uint64_t*)scratch;
+    int32_t* d_tile_slots = (int32_t*)(H.mask + 8 * n_slots);
+    H.slots = d_tile_slots + kTileHashSlots;
+    int32_t* d_rep = H.slots + n_slots;
+    H.list = d_rep + kMaxTiles;
+    uint32_t* d_block_sums = (uint32_t*)(H.list + g->cap_leaf);
+    H.slot_mask = (uint32_t)(n_slots - 1);
+    H.cap_leaf = g->cap_leaf;
 
     FX_HT("grid: allocs");
     auto fail = [&](fx_status s) { dev_free(scratch, st); fx_grid_destroy(g); return s; };
@@ -484,23 +551,25 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     {
         ProfScope ps(kProfMemset, st);
         FX_TRY_OR_FAIL(hipMemsetAsync(g->buf, 0, g->buf_bytes, st));
-        FX_TRY_OR_FAIL(hipMemsetAsync(d_slots, 0xFF, sizeof(int32_t) * kTileHashSlots, st));
+        FX_TRY_OR_FAIL(hipMemsetAsync(scratch, 0, clear_bytes, st));
     }
     FX_HT("grid: memsets");
     const GridPtrs q = ptrs_of(g);
     if (n_rows > 0 && B > 0) {
-        const int nb = blocks_for_rows(n_rows);
-        { ProfScope ps(kProfFindTiles, st); k_find_tiles<<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, B, d_slots, d_rep, g->d_hdr); }
+        const unsigned nb_rows = (unsigned)((n_rows + 255) / 256);
+        const unsigned nb_leaf = (unsigned)((g->cap_leaf + 255) / 256);
+        { ProfScope ps(kProfVoxelsToLeaves, st); k_voxels_to_leaves<<<nb_rows, 256, 0, st>>>(d_ijk, n_rows, d_joff, B, H, g->d_hdr); }
+        { ProfScope ps(kProfFindTiles, st); k_find_tiles<<<nb_leaf, 256, 0, st>>>(d_ijk, d_joff, B, H, d_tile_slots, d_rep, g->d_hdr); }
         { ProfScope ps(kProfRankTiles, st); k_rank_tiles<<<kMaxTiles / 256, 256, 0, st>>>(d_ijk, d_joff, B, d_rep, q); }
-        { ProfScope ps(kProfInsertUpper, st); k_insert<0><<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, q); }
+        { ProfScope ps(kProfInsertUpper, st); k_insert<0><<<nb_leaf, 256, 0, st>>>(d_ijk, d_joff, H, q); }
         LevelScan su{g->d_upper_mask, g->d_upper_prefix, &g->d_hdr->n_upper, kUpperWords, &g->d_hdr->n_lower,
                      g->cap_lower, 2};
         { ProfScope ps(kProfScanUpper, st); if (scan_level(g, su, g->cap_upper, d_block_sums, st) != FX_OK) return fail(FX_EDEVICE); }
-        { ProfScope ps(kProfInsertLower, st); k_insert<1><<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, q); }
+        { ProfScope ps(kProfInsertLower, st); k_insert<1><<<nb_leaf, 256, 0, st>>>(d_ijk, d_joff, H, q); }
         LevelScan sl{g->d_lower_mask, g->d_lower_prefix, &g->d_hdr->n_lower, kLowerWords, &g->d_hdr->n_leaf,
                      g->cap_leaf, 4};
         { ProfScope ps(kProfScanLower, st); if (scan_level(g, sl, g->cap_lower, d_block_sums, st) != FX_OK) return fail(FX_EDEVICE); }
-        { ProfScope ps(kProfInsertLeaf, st); k_insert<2><<<nb, 256, 0, st>>>(d_ijk, n_rows, d_joff, q); }
+        { ProfScope ps(kProfInsertLeaf, st); k_insert<2><<<nb_leaf, 256, 0, st>>>(d_ijk, d_joff, H, q); }
         const int lb = std::max(1, (g->cap_leaf + kLeafChunk - 1) / kLeafChunk);
         {
         ProfScope ps(kProfScanLeaf, st);
@@ -540,11 +609,11 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
 fx_status build_index_grid_device_joff(const int32_t* d_ijk, int64_t n_rows, const int64_t* d_joff, int32_t B,
                                        hipStream_t st, fx_grid** out) {
     // First attempt with capacities that fit typical occupancy; an attempt that overflows has
-    // still counted the nodes of the overflowing level exactly, so it is repeated with those.
+    // (almost always) counted the nodes of the overflowing level exactly and is repeated with those.
     int cap_upper = B + 8;
     int cap_lower = (int)std::min<int64_t>(std::max<int64_t>(n_rows, 1), 64 * (int64_t)std::max(B, 1) + n_rows / 256);
     int cap_leaf = (int)std::min<int64_t>(std::max<int64_t>(n_rows, 1), 1024 + n_rows / 8);
-    for (int attempt = 0; attempt < 4; ++attempt) {
+    for (int attempt = 0; attempt < 8; ++attempt) {
         fx_grid* g = nullptr;
         FX_TRY(build_attempt(d_ijk, n_rows, d_joff, B, cap_upper, cap_lower, cap_leaf, st, &g));
         const int ov = g->hdr.overflow;
@@ -561,7 +630,13 @@ fx_status build_index_grid_device_joff(const int32_t* d_ijk, int64_t n_rows, con
         }
         if (ov & 1) cap_upper = g->hdr.n_upper;
         if (ov & 2) { cap_upper = g->hdr.n_upper; cap_lower = g->hdr.n_lower; }
-        if (ov & 4) { cap_upper = g->hdr.n_upper; cap_lower = g->hdr.n_lower; cap_leaf = g->hdr.n_leaf; }
+        if (ov & 4) {
+            // The voxel pass counts every distinct leaf it can put in its table (twice the
+            // capacity); only when the table itself filled up is the count a lower bound, and
+            // the capacity grows geometrically instead (at most one leaf per input row exists).
+            if (ov & 32) cap_leaf = (int)std::min<int64_t>(std::max<int64_t>(n_rows, 1), 4 * (int64_t)cap_leaf);
+            else cap_leaf = g->hdr.n_leaf_raw;
+        }
         fx_grid_destroy(g);
     }
     set_error("grid build did not converge");
