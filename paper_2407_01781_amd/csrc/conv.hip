@@ -174,7 +174,12 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
     auto fetch_b = [&](vec8 (&bf)[NG][2], const u32x2& ids, int kappa) {
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi) {
-            if (!((gmask[gi] >> kappa) & 1u)) continue;
+            // In the LDS-only variant the reads are issued for every group: an absent group's ids all
+            // point at the zero row (one broadcast address).  With the reads unconditional every
+            // path issues the same number of LDS instructions and the compiler waits for exactly the
+            // fragments it needs; behind uniform branches it assumed the worst and drained the
+            // freshly issued prefetch before every multiply.
+            if (GENERAL && !((gmask[gi] >> kappa) & 1u)) continue;
             const uint32_t id = (ids[gi >> 1] >> (16 * (gi & 1))) & 0xFFFFu;
             if (GENERAL) {
                 const bool staged = id < (uint32_t)n_staged;
