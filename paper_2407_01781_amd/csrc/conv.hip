@@ -84,7 +84,9 @@ template <> struct Elem<_Float16> {
 // 32x32 accumulator layout (lane half h, register v -> row 8*(v/4) + 4*h + v%4) a lane's
 // accumulators are then the 32 consecutive channels 32*h .. 32*h+31 (m-tile t = channels
 // 32*h + 16*t + v).
-__global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wp, int K3, int C_in, int C_out) {
+__global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wp, int K3, int C_in, int C_out,
+                               int32_t* __restrict__ counters) {
+    if (blockIdx.x == 0 && threadIdx.x < 8) counters[threadIdx.x] = 0;   // the convolution's work-list counters
     const int64_t total = (int64_t)K3 * C_in * C_out;
     const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
@@ -103,9 +105,6 @@ __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restr
     }
 }
 
-#ifndef FX_CONV_EXPERIMENT
-#define FX_CONV_EXPERIMENT 0
-#endif
 #ifdef FX_CONV_TIMING
 // development aid: per-workgroup cycle totals, read back with fx_debug_conv_timing
 __device__ unsigned long long g_conv_timing[1024 * 8];
@@ -119,20 +118,30 @@ __device__ unsigned long long g_conv_timing[1024 * 8];
 // ---------------------------------------------------------------------------------- MFMA kernel
 constexpr int kRowBufBytes = (kRowCap + 1) * kRowBytes;           // staged rows + the zero row
 constexpr int kBlockBufBytes = kMaxIdBlocks * kIdBlockElems * 2;
+constexpr int kMetaSlots = 3;
 
-// Everything is double-buffered: while the consumer waves multiply out of one half, the
-// producer waves fill the other half straight from global memory.
+// A work item (tile x 64-channel output slice) as the workgroup sees it: its number in the work
+// list (-1: the list is exhausted) and a copy of the tile header.
+struct MetaSlot {
+    int64_t work;
+    int64_t pad;
+    TileHeader hdr;
+};
+
+// Rows and id blocks are double-buffered: while the consumer waves multiply out of one half, the
+// producer waves fill the other half straight from global memory.  The work items themselves are
+// announced two steps ahead in a ring of three slots.
 struct ConvLds {
     unsigned char rows[2][kRowBufBytes];     // 64-byte rows; 16-byte piece p stored at p ^ ((row >> 2) & 3)
     unsigned char blocks[2][kBlockBufBytes]; // id blocks [block][voxel n][group slot], u16
     uint16_t perm[2][kTileT];
+    MetaSlot meta[kMetaSlots];
 };
 static_assert(sizeof(ConvLds) <= 160 * 1024, "LDS budget of one compute unit");
 
 __device__ __forceinline__ int lds_row_offset(int row, int p) { return (int)(lds_row_code((uint32_t)row) ^ (uint32_t)(p << 4)); }
 
-// What a workgroup needs to know about one work item (tile x output-channel slice); all fields
-// are wave-uniform.
+// What a wave needs to know about one work item; all fields are wave-uniform.
 struct Item {
     int64_t tile;
     int slice;
@@ -140,23 +149,51 @@ struct Item {
     bool general;
 };
 
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+__device__ __forceinline__ int64_t slot_work(const MetaSlot& M) {
+    const int lo = uni((int)(uint32_t)(M.work & 0xFFFFFFFFll)), hi = uni((int)(M.work >> 32));
+    return ((int64_t)hi << 32) | (uint32_t)lo;
+}
+
+__device__ __forceinline__ Item item_of(const MetaSlot& M, int64_t work, int nslice) {
+    Item I;
+    I.tile = work / nslice;
+    I.slice = (int)(work - I.tile * nslice);
+    I.win_lo = uni(M.hdr.win_lo); I.win_n = uni(M.hdr.win_n); I.n_list = uni(M.hdr.n_list);
+    I.n_blocks = uni(M.hdr.n_blocks); I.n_valid = uni(M.hdr.n_out);
+    const int flags = uni(M.hdr.flags);
+    I.n_staged = (flags & kTileDirect) ? 0 : min(I.win_n + I.n_list, kRowCap);
+    I.general = !(flags & kTileLdsOffsets);
+    return I;
+}
+
 // Loop over the stencil offsets a wave needs for one 32-channel chunk.  Software pipeline per
-// offset step i: the weights and B fragments of step i+1 and the ids of step i+2 are fetched,
-// then the MFMAs of step i are issued (2 m-tiles x 2 k-steps per present column block) while
-// those loads are in flight.  Registers are rotated by unrolling (two weight sets, two fragment
-// sets), never copied.  GENERAL adds the fallback for rows that are not staged in LDS.
+// offset step i: the weights of step i+2, the B fragments of step i+1 and the ids of step i+2
+// are fetched while the MFMAs of step i are issued (2 m-tiles x 2 k-steps per present column
+// block).  The weights come from L2, whose latency exceeds one step, hence two steps of lead and
+// three register sets; the sets are rotated by unrolling, never copied, and steps run in triples
+// (the surplus steps multiply nothing) so that the rotation is the same at every exit.  Weight
+// fragments are addressed as wbase0 (the packed array) + a wave-uniform offset + the lane's 16 bytes.
+// The pipeline runs across calls: the last two steps fetch the fragments at offsets w_after0 and
+// w_after1 -- the first two offsets of whatever this wave multiplies next -- into wa and wb, and
+// wa_at / wb_at record what the two sets hold, so that a call normally starts with both in
+// flight (and fetches them itself if a call in between was skipped).  GENERAL adds the fallback
+// for rows that are not staged in LDS.
 template <typename T, bool GENERAL>
 __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, const unsigned char* lds_blocks,
                                              f32x16 (&acc)[kGroupsPerWave][2],
                                              const uint32_t (&gmask)[kGroupsPerWave], uint32_t wave_mask,
-                                             int wave_block0, const typename Elem<T>::vec8* __restrict__ wbase,
-                                             int64_t w_kappa_stride, int n, int h, int n_staged, int win_lo, int win_n,
+                                             int wave_block0, const typename Elem<T>::vec8* __restrict__ wbase0,
+                                             uint32_t lane_off, int w_base, int w_kappa_stride, typename Elem<T>::vec8 (&wa)[4],
+                                             typename Elem<T>::vec8 (&wb)[4], int& wa_at, int& wb_at, int w_after0,
+                                             int w_after1, int n, int h, int n_staged, int win_lo, int win_n,
                                              const int32_t* __restrict__ my_rows, const uint16_t* __restrict__ feat,
                                              int C_in, int c) {
     typedef typename Elem<T>::vec8 vec8;
     constexpr int NG = kGroupsPerWave;
     const int n_off = __popc(wave_mask);
-    const int k_last = 31 - __clz(wave_mask);
+    const int n_steps = (n_off + 2) / 3 * 3;
     const u32x2* idp = reinterpret_cast<const u32x2*>(lds_blocks) + (size_t)wave_block0 * kGroup + n;
     uint32_t rest = wave_mask;            // offsets not yet fetched; 31 (which no group has) once exhausted
     auto pop_kappa = [&]() {
@@ -165,77 +202,82 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
         rest &= rest - 1;
         return k;
     };
-    auto fetch_w = [&](vec8 (&w)[4], int k) {   // [mtile*2 + kstep]
-        const vec8* ws = wbase + (int64_t)min(k, k_last) * w_kappa_stride;
-#pragma unroll
-        for (int f = 0; f < 4; ++f) w[f] = ws[f * 64];
+    // wave-uniform offset of the weights that step t multiplies (t may lie past this call's end)
+    auto w_offset = [&](int t, int k) {
+        if (t < n_off) return w_base + k * w_kappa_stride;
+        return t == n_steps + 1 ? w_after1 : w_after0;
     };
-    // B fragments (16 channels x 32 voxels, two k-steps) of the column blocks that have offset kappa
-    auto fetch_b = [&](vec8 (&bf)[NG][2], const u32x2& ids, int kappa) {
+    auto fetch_w = [&](vec8 (&w)[4], int off) {   // [mtile*2 + kstep]; uniform base + 32-bit lane offset
+        const unsigned char* ws = reinterpret_cast<const unsigned char*>(wbase0 + off);
 #pragma unroll
-        for (int gi = 0; gi < NG; ++gi) {
-            // In the LDS-only variant the reads are issued for every group: an absent group's ids all
-            // point at the zero row (one broadcast address).  With the reads unconditional every
-            // path issues the same number of LDS instructions and the compiler waits for exactly the
-            // fragments it needs; behind uniform branches it assumed the worst and drained the
-            // freshly issued prefetch before every multiply.
-            if (GENERAL && !((gmask[gi] >> kappa) & 1u)) continue;
-            const uint32_t id = (ids[gi >> 1] >> (16 * (gi & 1))) & 0xFFFFu;
-            if (GENERAL) {
-                const bool staged = id < (uint32_t)n_staged;
-                const int row = staged ? (int)id : kRowCap;
-                bf[gi][0] = *reinterpret_cast<const vec8*>(lds_rows + lds_row_offset(row, h));
-                bf[gi][1] = *reinterpret_cast<const vec8*>(lds_rows + lds_row_offset(row, h + 2));
-                const bool from_global = !staged && id != kNoRow;
-                if (__any(from_global)) {
-                    if (from_global) {
-                        const int64_t gr = id < (uint32_t)win_n ? (int64_t)win_lo + id : (int64_t)my_rows[id - win_n];
-                        const uint16_t* src = feat + gr * C_in + c * kCinChunk + h * 8;
-                        bf[gi][0] = *reinterpret_cast<const vec8*>(src);
-                        bf[gi][1] = *reinterpret_cast<const vec8*>(src + 16);
-                    }
+        for (int f = 0; f < 4; ++f) w[f] = *reinterpret_cast<const vec8*>(ws + lane_off + f * 1024);
+    };
+    const uint32_t hsel = (uint32_t)h << 4;
+    // B fragments (16 channels x 32 voxels, two k-steps) of column block gi for offset kappa
+    auto fetch_b = [&](vec8 (&bf)[2], const u32x2& ids, int gi, int kappa) {
+        // In the LDS-only variant the reads are issued for every group: an absent group's ids all
+        // point at the zero row (one broadcast address).  With the reads unconditional every path
+        // issues the same number of LDS instructions and the compiler waits for exactly the
+        // fragments it needs; behind uniform branches it assumed the worst and drained the freshly
+        // issued prefetch before every multiply.
+        if (GENERAL && !((gmask[gi] >> kappa) & 1u)) return;
+        const uint32_t id = (ids[gi >> 1] >> (16 * (gi & 1))) & 0xFFFFu;
+        if (GENERAL) {
+            const bool staged = id < (uint32_t)n_staged;
+            const int row = staged ? (int)id : kRowCap;
+            bf[0] = *reinterpret_cast<const vec8*>(lds_rows + lds_row_offset(row, h));
+            bf[1] = *reinterpret_cast<const vec8*>(lds_rows + lds_row_offset(row, h + 2));
+            const bool from_global = !staged && id != kNoRow;
+            if (__any(from_global)) {
+                if (from_global) {
+                    const int64_t gr = id < (uint32_t)win_n ? (int64_t)win_lo + id : (int64_t)my_rows[id - win_n];
+                    const uint16_t* src = feat + gr * C_in + c * kCinChunk + h * 8;
+                    bf[0] = *reinterpret_cast<const vec8*>(src);
+                    bf[1] = *reinterpret_cast<const vec8*>(src + 16);
                 }
-            } else {   // id = lds_row_code(row): 16-byte piece p of the row sits at id ^ (p << 4)
-                bf[gi][0] = *reinterpret_cast<const vec8*>(lds_rows + (id ^ (uint32_t)(h << 4)));
-                bf[gi][1] = *reinterpret_cast<const vec8*>(lds_rows + (id ^ (uint32_t)((h + 2) << 4)));
             }
+        } else {   // id = lds_row_code(row): 16-byte piece p of the row sits at id ^ (p << 4); pieces h and h + 2
+            const uint32_t a0 = id ^ hsel;
+            bf[0] = *reinterpret_cast<const vec8*>(lds_rows + a0);
+            bf[1] = *reinterpret_cast<const vec8*>(lds_rows + (a0 ^ 32u));
         }
     };
-    vec8 wa[4], wb[4];
-    vec8 bfa[NG][2], bfb[NG][2];
-    int ka = pop_kappa(), kb = pop_kappa(), it = 0;
-    fetch_w(wa, ka);
+    vec8 wc[4];
+    vec8 bf[NG][2];   // one set: a group's fragments for the next offset are fetched right after its multiplies
+    int q0 = pop_kappa(), q1 = pop_kappa(), q2 = pop_kappa(), it = 0;   // offsets of steps it, it+1, it+2
+    if (wa_at != w_offset(0, q0)) fetch_w(wa, w_offset(0, q0));          // only after a call was skipped
+    if (wb_at != w_offset(1, q1)) fetch_w(wb, w_offset(1, q1));
+    wa_at = w_after0;
+    wb_at = w_after1;
     u32x2 idn = idp[min(1, n_off - 1) * kGroup];   // ids of step 1
-    fetch_b(bfa, idp[0], ka);
-    // one step: fetch weights, ids and fragments of the following offsets, then multiply offset
-    // `kappa` (weights wcur, fragments bcur) while those loads are in flight
-    auto step = [&](const vec8 (&wcur)[4], vec8 (&wnext)[4], const vec8 (&bcur)[NG][2], vec8 (&bnext)[NG][2], int kappa,
-                    int k_next) {
-#if FX_CONV_EXPERIMENT != 1
-        fetch_w(wnext, k_next);
-#endif
+    {
+        const u32x2 id0 = idp[0];
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) fetch_b(bf[gi], id0, gi, q0);
+    }
+    // one step: fetch the weights of step it+2 and the ids of step it+2, then, group by group,
+    // multiply the current offset and fetch the group's fragments for the next one
+    auto step = [&](const vec8 (&wcur)[4], vec8 (&wload)[4]) {
+        fetch_w(wload, w_offset(it + 2, q2));
         const u32x2 ids_next = idn;
         idn = idp[min(it + 2, n_off - 1) * kGroup];
-#if FX_CONV_EXPERIMENT != 2
-        fetch_b(bnext, ids_next, k_next);
-#endif
-#if FX_CONV_EXPERIMENT != 3
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi) {
-            if (!((gmask[gi] >> kappa) & 1u)) continue;
+            if ((gmask[gi] >> q0) & 1u) {
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks)      // k-step outermost: consecutive MFMAs never share an accumulator
+                for (int ks = 0; ks < 2; ++ks)      // k-step outermost: consecutive MFMAs never share an accumulator
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt) acc[gi][mt] = Elem<T>::mfma(wcur[mt * 2 + ks], bcur[gi][ks], acc[gi][mt]);
+                    for (int mt = 0; mt < 2; ++mt) acc[gi][mt] = Elem<T>::mfma(wcur[mt * 2 + ks], bf[gi][ks], acc[gi][mt]);
+            }
+            fetch_b(bf[gi], ids_next, gi, q1);
         }
-#endif
         ++it;
+        q0 = q1; q1 = q2; q2 = pop_kappa();
     };
     while (it < n_off) {
-        step(wa, wb, bfa, bfb, ka, kb);
-        ka = pop_kappa();
-        step(wb, wa, bfb, bfa, kb, ka);
-        kb = pop_kappa();
+        step(wa, wc);
+        step(wb, wa);
+        step(wc, wb);
     }
 }
 
@@ -273,40 +315,59 @@ __device__ __forceinline__ void produce_meta(unsigned char* lds_blocks, uint16_t
                                          (lds_ptr_t)lds_perm, 16, 0, 0);
 }
 
-__device__ __forceinline__ Item load_item(int64_t work, int nslice, const TileHeader* __restrict__ tile_hdr) {
-    Item I;
-    I.tile = work / nslice;
-    I.slice = (int)(work - I.tile * nslice);
-    const TileHeader* H = tile_hdr + I.tile;
-    I.win_lo = H->win_lo; I.win_n = H->win_n; I.n_list = H->n_list;
-    I.n_blocks = H->n_blocks; I.n_valid = H->n_out;
-    const int flags = H->flags;
-    I.n_staged = (flags & kTileDirect) ? 0 : min(I.win_n + I.n_list, kRowCap);
-    I.general = !(flags & kTileLdsOffsets);
-    return I;
+// Next unclaimed work item: first from the list of the workgroup's own XCD, then from the others'.
+// The first wg_per_xcd items of every list are taken statically by that XCD's workgroups.
+__device__ __forceinline__ int64_t take_work(int32_t* __restrict__ counters, int xcd, int per_xcd, int wg_per_xcd,
+                                             int64_t n_work) {
+    for (int v = 0; v < 8; ++v) {
+        const int x = (xcd + v) & 7;
+        const int64_t begin = (int64_t)x * per_xcd;
+        const int64_t end = min(n_work, begin + per_xcd);
+        if (begin + wg_per_xcd >= end) continue;
+        const int64_t w = begin + wg_per_xcd + atomicAdd(&counters[x], 1);
+        if (w < end) return w;
+    }
+    return -1;
 }
+
+// One wave announces work item `work` (or the end of the list) in a slot of the ring.
+__device__ __forceinline__ void announce(MetaSlot& M, int64_t work, int nslice, const TileHeader* __restrict__ tile_hdr,
+                                         int lane) {
+    if (work >= 0) {
+        const int32_t* src = reinterpret_cast<const int32_t*>(tile_hdr + work / nslice);
+        if (lane < (int)(sizeof(TileHeader) / 4)) reinterpret_cast<int32_t*>(&M.hdr)[lane] = src[lane];
+    }
+    if (lane == 0) M.work = work;
+}
+
+// offset (in 16-byte fragments, wave-uniform) of the first weight fragment for (slice, chunk, offset)
+// (the packed weights of one call stay far below 2^31 fragments)
+__device__ __forceinline__ int w_frag(int nslice, int w_kappa_stride, int slice, int c, int kappa) {
+    return ((c * nslice + slice) * 4) * 64 + kappa * w_kappa_stride;
+}
+
+__device__ __forceinline__ int first_offset(uint32_t mask) { return mask ? __ffs(mask) - 1 : 0; }
 
 // Consumer side of one work item: multiply all chunks (one barrier after each, matching the
 // producers' barriers), then write the tile's outputs back (lane (n, h) holds channels
-// slice*64 + 32h .. +31 of output slot g*32 + n).  `step` counts chunks since kernel start and
+// slice*64 + 32h .. +31 of output slot g*32 + n).  `phase` counts chunks since kernel start and
 // selects the LDS half; `mb` selects the half that holds this tile's id blocks.
 template <typename T, bool OUT_F32, bool GENERAL>
-__device__ __forceinline__ void consume_item(ConvLds& L, const Item& I, int step, int mb, bool barrier_after_last, int nchunk,
-                                             int nslice, int wave, int lane, const TileHeader* __restrict__ tile_hdr,
+__device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, const Item& I, int phase,
+                                             int mb, int nchunk, int nslice, int wave, int lane,
                                              const int32_t* __restrict__ tile_rows, int row_stride,
                                              const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp, int C_in,
                                              int C_out, void* __restrict__ out, unsigned long long (&tm)[4]) {
     typedef typename Elem<T>::vec8 vec8;
     constexpr int NG = kGroupsPerWave;
     const int n = lane & 31, h = lane >> 5;
-    const TileHeader* H = tile_hdr + I.tile;
     uint32_t gmask[NG];
 #pragma unroll
-    for (int gi = 0; gi < NG; ++gi) gmask[gi] = __builtin_amdgcn_readfirstlane(H->group_mask[tile_group_of(wave, gi)]);
-    const uint32_t wave_mask = __builtin_amdgcn_readfirstlane(H->wave_mask[wave]);
-    const int wave_block0 = __builtin_amdgcn_readfirstlane(H->wave_block0[wave]);
+    for (int gi = 0; gi < NG; ++gi) gmask[gi] = (uint32_t)uni((int)M.hdr.group_mask[tile_group_of(wave, gi)]);
+    const uint32_t wave_mask = (uint32_t)uni((int)M.hdr.wave_mask[wave]);
+    const int wave_block0 = uni((int)M.hdr.wave_block0[wave]);
     const int32_t* my_rows = tile_rows + I.tile * (int64_t)row_stride;
-    const int64_t w_kappa_stride = (int64_t)nchunk * nslice * 4 * 64;
+    const int w_kappa_stride = nchunk * nslice * 4 * 64;
 
     f32x16 acc[NG][2];
 #pragma unroll
@@ -316,23 +377,39 @@ __device__ __forceinline__ void consume_item(ConvLds& L, const Item& I, int step
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[gi][mt][v] = 0.f;
 
+    // The weight pipeline runs across the chunks of one item; it restarts with every item (the
+    // two code variants of this function do not share registers well enough to hand it over).
+    vec8 wa[4], wb[4];
+    int wa_at = -1, wb_at = -1;
+    int local[NG];
     for (int c = 0; c < nchunk; ++c) {
+        // where this wave's weights come from after this chunk
+        int w_after0, w_after1;
+        {
+            const int nc = c + 1 < nchunk ? c + 1 : c;   // after the last chunk the fetches are not used
+            w_after0 = w_frag(nslice, w_kappa_stride, I.slice, nc, first_offset(wave_mask));
+            const uint32_t more = wave_mask & (wave_mask - 1);
+            w_after1 = more ? w_frag(nslice, w_kappa_stride, I.slice, nc, first_offset(more)) : w_after0;
+        }
         if (wave_mask) {
             FX_T0();
-            const vec8* wbase = reinterpret_cast<const vec8*>(wp) + lane + (((int64_t)c * nslice + I.slice) * 4) * 64;
-            offsets_loop<T, GENERAL>(L.rows[(step + c) & 1], L.blocks[mb], acc, gmask, wave_mask, wave_block0, wbase,
-                                     w_kappa_stride, n, h, I.n_staged, I.win_lo, I.win_n, my_rows, feat, C_in, c);
+            offsets_loop<T, GENERAL>(L.rows[(phase + c) & 1], L.blocks[mb], acc, gmask, wave_mask, wave_block0,
+                                     reinterpret_cast<const vec8*>(wp), (uint32_t)lane * 16u,
+                                     w_frag(nslice, w_kappa_stride, I.slice, c, 0), w_kappa_stride, wa, wb, wa_at, wb_at,
+                                     w_after0, w_after1, n, h, I.n_staged, I.win_lo, I.win_n, my_rows, feat, C_in, c);
             FX_TACC(tm[0]);
         }
-        if (c != nchunk - 1) { FX_T0(); __syncthreads(); FX_TACC(tm[1]); }
+        if (c == nchunk - 1) {   // the permutation's half is recycled right after the barrier when there is one chunk
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi) local[gi] = L.perm[mb][tile_group_of(wave, gi) * kGroup + n];
+        }
+        { FX_T0(); __syncthreads(); FX_TACC(tm[1]); }
     }
-    {
     FX_T0();
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
-        const int local = L.perm[mb][tile_group_of(wave, gi) * kGroup + n];
-        if (local >= I.n_valid) continue;
-        const int64_t o = I.tile * kTileT + local;
+        if (local[gi] >= I.n_valid) continue;
+        const int64_t o = I.tile * kTileT + local[gi];
         const int64_t col = (int64_t)I.slice * kCoutSlice + 32 * h;
         if (OUT_F32) {
             float* dst = reinterpret_cast<float*>(out) + o * C_out + col;
@@ -357,38 +434,38 @@ __device__ __forceinline__ void consume_item(ConvLds& L, const Item& I, int step
         }
     }
     FX_TACC(tm[2]);
-    }
-    if (barrier_after_last) { FX_T0(); __syncthreads(); FX_TACC(tm[1]); }
 }
 
-// Persistent workgroups, one per compute unit, each walking a strided list of work items (tile
-// of 512 consecutive outputs x slice of 64 output channels) in steps of one 32-channel chunk.
+// Persistent workgroups, one per compute unit.  Work items (tile of 512 consecutive outputs x
+// slice of 64 output channels) are cut into eight contiguous lists, one per XCD, so that
+// neighbouring tiles, which share halo rows, meet in the same L2; a workgroup starts with a fixed
+// item of its XCD's list and then claims items through per-list counters (its own list first),
+// which evens out tiles of different cost.  Time advances in phases of one 32-channel chunk.
 // Waves 0-3 are consumers: wave w owns 4 of the tile's 16 column blocks (128 outputs, 4 x 2
 // accumulator tiles of 32x32) and multiplies out of one half of LDS.  Waves 4-7 are producers:
-// meanwhile they copy the rows of the next step (and, at a tile change, its id blocks) from
-// global memory straight into the other half.  One barrier per step hands the halves over
-// (both roles execute the same number of barriers).  Producers and consumers are separate
-// waves because a wave's loads complete in order: the consumer's short weight fetches must not
-// queue behind the long HBM reads.
+// meanwhile they copy the rows of the next phase (and, at a tile change, its id blocks) from
+// global memory straight into the other half, and the first of them announces the item that
+// starts two phases later (claim + tile header) in a ring of three slots.  One barrier per phase
+// hands everything over; both roles walk the same ring and execute the same barriers.
+// Producers and consumers are separate waves because a wave's loads complete in order: the
+// consumer's short weight fetches must not queue behind the long HBM reads.
 template <typename T, bool OUT_F32>
 __global__ void __launch_bounds__(kConvThreads, 1)
 k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
             const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
-            int block_stride, int64_t n_work, int per_xcd, const uint16_t* __restrict__ feat,
-            const uint16_t* __restrict__ wp, int C_in, int C_out, void* __restrict__ out) {
+            int block_stride, int64_t n_work, int per_xcd, int32_t* __restrict__ counters,
+            const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp, int C_in, int C_out,
+            void* __restrict__ out) {
+    typedef typename Elem<T>::vec8 vec8;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     ConvLds& L = *reinterpret_cast<ConvLds*>(lds_raw);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
 
-    // Work order: workgroup b runs on XCD b % 8 (round-robin dispatch); XCD x takes the x-th
-    // eighth of the work list and its workgroups walk it side by side, so that neighbouring tiles,
-    // which share halo rows, meet in the same L2.
+    // workgroup b runs on XCD b % 8 (round-robin dispatch)
     const int xcd = blockIdx.x & 7, in_xcd = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
-    const int64_t w_begin = (int64_t)xcd * per_xcd;
-    const int64_t w_end = min(n_work, w_begin + per_xcd);
-    int64_t work = w_begin + in_xcd;
-    if (work >= w_end) return;
+    const int64_t first = (int64_t)xcd * per_xcd + in_xcd;
+    if (in_xcd >= per_xcd || first >= n_work) return;
 
     if (tid < 2 * (kRowBytes / 16))   // the zero row of both halves
         reinterpret_cast<u32x4*>(L.rows[tid >> 2] + kRowCap * kRowBytes)[tid & 3] = u32x4{0, 0, 0, 0};
@@ -396,41 +473,63 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
     if (wave >= kTileWaves) {
         // ---------------- producers
         const int pwave = wave - kTileWaves;
-        Item cur = load_item(work, nslice, tile_hdr);
-        produce_meta(L.blocks[0], L.perm[0], cur, pwave, lane, tile_perm, tile_blocks, block_stride);
-        produce_rows(L.rows[0], cur, pwave, lane, tile_rows, row_stride, feat, C_in, 0);
+        if (pwave == 0) {   // items that start in phases 0 and 1
+            announce(L.meta[0], first, nslice, tile_hdr, lane);
+            if (nchunk == 1) {
+                int64_t w = 0;
+                if (lane == 0) w = take_work(counters, xcd, per_xcd, wg_per_xcd, n_work);
+                w = __shfl(w, 0);
+                announce(L.meta[1], w, nslice, tile_hdr, lane);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        {
+            const Item cur = item_of(L.meta[0], first, nslice);
+            produce_meta(L.blocks[0], L.perm[0], cur, pwave, lane, tile_perm, tile_blocks, block_stride);
+            produce_rows(L.rows[0], cur, pwave, lane, tile_rows, row_stride, feat, C_in, 0);
+        }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
 #ifdef FX_CONV_TIMING
         unsigned long long ptm = 0;
         const unsigned long long pt_start = __builtin_readcyclecounter();
 #endif
-        int step = 0, item_no = 0;
-        while (true) {
-            const int64_t next_work = work + wg_per_xcd;
-            const bool has_next = next_work < w_end;
-            for (int c = 0; c < nchunk; ++c, ++step) {
-                const int rb = step & 1, mb = item_no & 1;
+        int phase = 0;
+        for (int item_no = 0;; ++item_no) {
+            const MetaSlot& M = L.meta[item_no % kMetaSlots];
+            const int64_t work = slot_work(M);
+            if (work < 0) break;
+            const Item cur = item_of(M, work, nslice);
+            for (int c = 0; c < nchunk; ++c, ++phase) {
+                const int rb = (phase + 1) & 1;
                 if (c != nchunk - 1) {
-                    produce_rows(L.rows[rb ^ 1], cur, pwave, lane, tile_rows, row_stride, feat, C_in, c + 1);
-                } else if (has_next) {
-                    const Item nxt = load_item(next_work, nslice, tile_hdr);
-                    produce_meta(L.blocks[mb ^ 1], L.perm[mb ^ 1], nxt, pwave, lane, tile_perm, tile_blocks, block_stride);
-                    produce_rows(L.rows[rb ^ 1], nxt, pwave, lane, tile_rows, row_stride, feat, C_in, 0);
+                    produce_rows(L.rows[rb], cur, pwave, lane, tile_rows, row_stride, feat, C_in, c + 1);
+                } else {
+                    const MetaSlot& MN = L.meta[(item_no + 1) % kMetaSlots];
+                    const int64_t nwork = slot_work(MN);
+                    if (nwork >= 0) {
+                        const Item nxt = item_of(MN, nwork, nslice);
+                        const int nb = (item_no + 1) & 1;
+                        produce_meta(L.blocks[nb], L.perm[nb], nxt, pwave, lane, tile_perm, tile_blocks, block_stride);
+                        produce_rows(L.rows[rb], nxt, pwave, lane, tile_rows, row_stride, feat, C_in, 0);
+                    }
+                }
+                if (pwave == 0 && (phase + 2) % nchunk == 0) {   // an item starts two phases from now
+                    int64_t w = 0;
+                    if (lane == 0) w = take_work(counters, xcd, per_xcd, wg_per_xcd, n_work);
+                    w = __shfl(w, 0);
+                    announce(L.meta[((phase + 2) / nchunk) % kMetaSlots], w, nslice, tile_hdr, lane);
                 }
                 __builtin_amdgcn_s_waitcnt(0);
 #ifdef FX_CONV_TIMING
                 const unsigned long long tb = __builtin_readcyclecounter();
 #endif
-                if (c != nchunk - 1 || has_next) __syncthreads();
+                __syncthreads();
 #ifdef FX_CONV_TIMING
                 ptm += __builtin_readcyclecounter() - tb;
 #endif
             }
-            if (!has_next) break;
-            cur = load_item(next_work, nslice, tile_hdr);
-            work = next_work;
-            ++item_no;
         }
 #ifdef FX_CONV_TIMING
         if (tid == kTileWaves * 64 && blockIdx.x < 1024) {
@@ -445,26 +544,25 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
         const unsigned long long t_start = __builtin_readcyclecounter();
 #endif
         __syncthreads();
-        int step = 0, item_no = 0;
-        while (true) {
-            const int64_t next_work = work + wg_per_xcd;
-            const bool has_next = next_work < w_end;
-            const Item cur = load_item(work, nslice, tile_hdr);
+        __syncthreads();
+        int phase = 0, n_items = 0;
+        for (int item_no = 0;; ++item_no, phase += nchunk) {
+            const MetaSlot& M = L.meta[item_no % kMetaSlots];
+            const int64_t work = slot_work(M);
+            if (work < 0) break;
+            const Item cur = item_of(M, work, nslice);
             if (cur.general)
-                consume_item<T, OUT_F32, true>(L, cur, step, item_no & 1, has_next, nchunk, nslice, wave, lane, tile_hdr,
-                                               tile_rows, row_stride, feat, wp, C_in, C_out, out, tm);
+                consume_item<T, OUT_F32, true>(L, M, cur, phase, item_no & 1, nchunk, nslice, wave, lane, tile_rows,
+                                               row_stride, feat, wp, C_in, C_out, out, tm);
             else
-                consume_item<T, OUT_F32, false>(L, cur, step, item_no & 1, has_next, nchunk, nslice, wave, lane, tile_hdr,
-                                                tile_rows, row_stride, feat, wp, C_in, C_out, out, tm);
-            if (!has_next) break;
-            step += nchunk;
-            work = next_work;
-            ++item_no;
+                consume_item<T, OUT_F32, false>(L, M, cur, phase, item_no & 1, nchunk, nslice, wave, lane, tile_rows,
+                                                row_stride, feat, wp, C_in, C_out, out, tm);
+            ++n_items;
         }
 #ifdef FX_CONV_TIMING
         if (tid == 0 && blockIdx.x < 1024) {
             unsigned long long* d = g_conv_timing + blockIdx.x * 8;
-            d[0] = tm[0]; d[1] = tm[1]; d[2] = tm[2]; d[3] = __builtin_readcyclecounter() - t_start; d[4] = item_no + 1;
+            d[0] = tm[0]; d[1] = tm[1]; d[2] = tm[2]; d[3] = __builtin_readcyclecounter() - t_start; d[4] = n_items;
         }
 #endif
     }
@@ -503,8 +601,8 @@ __global__ void k_conv_scalar(const int32_t* __restrict__ nbmap, int64_t n_out, 
 }
 
 template <typename T, bool OUT_F32>
-static hipError_t launch_mfma(const fx_kmap* km, const void* feat, const void* wp, int C_in, int C_out, void* out,
-                              hipStream_t st) {
+static hipError_t launch_mfma(const fx_kmap* km, const void* feat, const void* wp, int32_t* counters, int C_in, int C_out,
+                              void* out, hipStream_t st) {
     const size_t lds = sizeof(ConvLds);
     hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<T, OUT_F32>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -523,8 +621,8 @@ static hipError_t launch_mfma(const fx_kmap* km, const void* feat, const void* w
     grid = (int)std::min<int64_t>(grid, (int64_t)8 * per_xcd);
     k_conv_mfma<T, OUT_F32><<<grid, kConvThreads, lds, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,
                                                              km->row_stride, km->d_tile_blocks, km->block_stride, n_work,
-                                                             per_xcd, (const uint16_t*)feat, (const uint16_t*)wp, C_in,
-                                                             C_out, out);
+                                                             per_xcd, counters, (const uint16_t*)feat,
+                                                             (const uint16_t*)wp, C_in, C_out, out);
     return hipGetLastError();
 }
 
@@ -557,23 +655,24 @@ extern "C" fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, f
                       !(force && force[0] == '1');
     if (mfma) {
         uint16_t* wp = nullptr;
-        const size_t wbytes = sizeof(uint16_t) * (size_t)km->K3 * C_in * C_out;
-        FX_TRY(dev_alloc((void**)&wp, wbytes, st));
+        const size_t wbytes = sizeof(uint16_t) * (size_t)km->K3 * C_in * C_out;   // a multiple of 64 bytes
+        FX_TRY(dev_alloc((void**)&wp, wbytes + 8 * sizeof(int32_t), st));
+        int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
         const int64_t total = (int64_t)km->K3 * C_in * C_out;
         {
             ProfScope ps(kProfPackWeights, st);
             k_pack_weights<<<(unsigned)std::min<int64_t>((total + 255) / 256, 4096), 256, 0, st>>>(
-                (const uint16_t*)d_w, wp, km->K3, C_in, C_out);
+                (const uint16_t*)d_w, wp, km->K3, C_in, C_out, counters);
         }
         hipError_t e = hipGetLastError();
         if (e == hipSuccess) {
             ProfScope ps(kProfConvMfma, st);
             if (in_dt == FX_BF16)
-                e = out_f32 ? launch_mfma<__bf16, true>(km, d_feat, wp, C_in, C_out, d_out, st)
-                            : launch_mfma<__bf16, false>(km, d_feat, wp, C_in, C_out, d_out, st);
+                e = out_f32 ? launch_mfma<__bf16, true>(km, d_feat, wp, counters, C_in, C_out, d_out, st)
+                            : launch_mfma<__bf16, false>(km, d_feat, wp, counters, C_in, C_out, d_out, st);
             else
-                e = out_f32 ? launch_mfma<_Float16, true>(km, d_feat, wp, C_in, C_out, d_out, st)
-                            : launch_mfma<_Float16, false>(km, d_feat, wp, C_in, C_out, d_out, st);
+                e = out_f32 ? launch_mfma<_Float16, true>(km, d_feat, wp, counters, C_in, C_out, d_out, st)
+                            : launch_mfma<_Float16, false>(km, d_feat, wp, counters, C_in, C_out, d_out, st);
         }
         dev_free(wp, st);
         if (e != hipSuccess) { set_error("convolution launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
