@@ -42,7 +42,7 @@ fx_status host_staging(void** p, size_t bytes, int area = 0);
 // When enabled (fx_profile_enable), every kernel launch of the library is bracketed by a pair
 // of hipEvents on the launch stream; fx_profile_read sums the elapsed times per slot.
 enum ProfSlot {
-    kProfVoxelsToLeaves = 0, kProfFindTiles, kProfRankTiles, kProfInsertUpper, kProfScanUpper, kProfInsertLower, kProfScanLower,
+    kProfBucketCount = 0, kProfBucketScan, kProfBucketScatter, kProfBucketLeaves, kProfVoxelsToLeaves, kProfFindTiles, kProfRankTiles, kProfInsertUpper, kProfScanUpper, kProfInsertLower, kProfScanLower,
     kProfInsertLeaf, kProfScanLeaf, kProfVoxBase, kProfGridIjk, kProfNbmap, kProfLeafNeighbors, kProfBuildTiles,
     kProfPackWeights, kProfConvMfma, kProfConvScalar, kProfMemset, kProfSlotCount
 };
@@ -76,7 +76,7 @@ struct GridHeader {
     int32_t n_upper;
     int32_t n_lower;
     int32_t n_leaf;
-    int32_t overflow;     // bit0: upper capacity, bit1: lower, bit2: leaf, bit3: tile limit, bit4: voxel count, bit5: leaf table full
+    int32_t overflow;     // bit0: upper capacity, bit1: lower, bit2: leaf, bit3: tile limit, bit4: voxel count, bit5: leaf table full, bit6: a bucket's LDS table full
     int32_t n_leaf_raw;   // distinct leaves found by the voxel pass (may exceed capacity)
     int32_t pad[2];
     int64_t n_voxels;

@@ -51,191 +51,7 @@ __device__ __forceinline__ uint32_t mix32(uint32_t h, uint32_t v) {
     return h;
 }
 
-// ---------------------------------------------------------------------------------- pass 1: voxels -> leaves
-// The only pass over the input rows.  Distinct (grid, leaf) pairs are collected in an
-// open-addressing table whose slots hold a representative input row (+1; 0 = empty), so one
-// 32-bit CAS claims a slot and the key is read back through that row.  Each row then sets its
-// voxel bit in the 512-bit mask that belongs to the slot (step 11.4; duplicates collapse in
-// the bit).  Everything above the leaves -- root tiles, upper and lower nodes, the order of
-// the leaves -- is derived afterwards from the few distinct leaves instead of from the rows.
-struct LeafHash {
-    int32_t* slots;    // [n_slots]
-    uint64_t* mask;    // [n_slots][8]
-    int32_t* list;     // [cap_leaf] slot of every distinct leaf, in arrival order
-    uint32_t slot_mask;  // n_slots - 1 (power of two)
-    int32_t cap_leaf;
-};
-
-__global__ void __launch_bounds__(256)
-k_voxels_to_leaves(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff, int B,
-                   LeafHash H, GridHeader* hdr) {
-    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int b = r < n_rows ? find_batch(joff, B, r) : -1;
-    int i = 0, j = 0, k = 0;
-    uint32_t h = 0;
-    bool found = false, claimed = false;
-    if (b >= 0) {
-        i = ijk[3 * r]; j = ijk[3 * r + 1]; k = ijk[3 * r + 2];
-        const int li = i >> 3, lj = j >> 3, lk = k >> 3;
-        h = mix32(mix32(mix32(mix32(0x811C9DC5u, (uint32_t)b), (uint32_t)li), (uint32_t)lj), (uint32_t)lk);
-        h &= H.slot_mask;
-        for (uint32_t probe = 0; probe <= H.slot_mask; ++probe) {
-            // device-coherent read: a slot claimed from another XCD must be seen
-            int32_t s = __hip_atomic_load(&H.slots[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (s == 0) {
-                const int32_t old = atomicCAS(&H.slots[h], 0, (int32_t)r + 1);
-                if (old == 0) { found = claimed = true; break; }
-                s = old;
-            }
-            const int64_t q = s - 1;
-            if ((ijk[3 * q] >> 3) == li && (ijk[3 * q + 1] >> 3) == lj && (ijk[3 * q + 2] >> 3) == lk &&
-                find_batch(joff, B, q) == b) {
-                found = true;
-                break;
-            }
-            h = (h + 1) & H.slot_mask;
-        }
-        if (!found) atomicOr(&hdr->overflow, 4 | 32);   // table full: the leaf count is incomplete
-        else atomicOr((unsigned long long*)&H.mask[(size_t)h * 8 + (i & 7)], 1ull << (((j & 7) << 3) | (k & 7)));
-    }
-    // list the newly claimed leaves: one counter update per wave, not per leaf
-    const uint64_t cl = __ballot(claimed);
-    if (cl) {
-        const int lane = threadIdx.x & 63;
-        const int leader = __ffsll((long long)cl) - 1;
-        int base = 0;
-        if (lane == leader) base = atomicAdd(&hdr->n_leaf_raw, __popcll(cl));
-        base = __shfl(base, leader);
-        if (claimed) {
-            const int pos = base + __popcll(cl & ((1ull << lane) - 1));
-            if (pos < H.cap_leaf) H.list[pos] = (int32_t)h;
-            else atomicOr(&hdr->overflow, 4);
-        }
-    }
-}
-
-// representative input row of distinct leaf `idx`, or -1 past the end
-__device__ __forceinline__ int64_t leaf_rep_row(const LeafHash& H, const GridHeader* hdr, int64_t idx, int32_t* slot) {
-    const int n = min(hdr->n_leaf_raw, H.cap_leaf);
-    if (idx >= n) return -1;
-    const int32_t h = H.list[idx];
-    *slot = h;
-    return (int64_t)H.slots[h] - 1;
-}
-
-// ---------------------------------------------------------------------------------- root tiles
-// Distinct (grid, tile) pairs of the leaves go into a second small table of the same kind.
-__global__ void k_find_tiles(const int32_t* __restrict__ ijk, const int64_t* __restrict__ joff, int B, LeafHash H,
-                             int32_t* __restrict__ tile_slots, int32_t* __restrict__ rep_rows, GridHeader* hdr) {
-    if (hdr->overflow) return;
-    int32_t slot;
-    const int64_t r = leaf_rep_row(H, hdr, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, &slot);
-    if (r < 0) return;
-    const int b = find_batch(joff, B, r);
-    const int ti = ijk[3 * r] >> 12, tj = ijk[3 * r + 1] >> 12, tk = ijk[3 * r + 2] >> 12;
-    // lanes that share the first active lane's tile let that lane insert for them
-    const uint64_t active = __ballot(1);
-    const int leader = __ffsll((long long)active) - 1;
-    const int lb = __shfl(b, leader), li = __shfl(ti, leader), lj = __shfl(tj, leader), lk = __shfl(tk, leader);
-    const int lane = threadIdx.x & 63;
-    if (lane != leader && lb == b && li == ti && lj == tj && lk == tk) return;
-    uint32_t h = mix32(mix32(mix32(mix32(0x811C9DC5u, (uint32_t)b), (uint32_t)ti), (uint32_t)tj), (uint32_t)tk);
-    h &= (kTileHashSlots - 1);
-    for (int probe = 0; probe < kTileHashSlots; ++probe) {
-        int32_t s = tile_slots[h];
-        if (s == 0) {
-            if (hdr->n_tiles_raw > kMaxTiles) break;  // over the limit: reported by the ranking kernel
-            const int32_t old = atomicCAS(&tile_slots[h], 0, (int32_t)r + 1);
-            if (old == 0) {
-                const int pos = atomicAdd(&hdr->n_tiles_raw, 1);
-                if (pos < kMaxTiles) rep_rows[pos] = (int32_t)r;
-                break;
-            }
-            s = old;
-        }
-        const int64_t q = s - 1;
-        if (find_batch(joff, B, q) == b && (ijk[3 * q] >> 12) == ti && (ijk[3 * q + 1] >> 12) == tj &&
-            (ijk[3 * q + 2] >> 12) == tk)
-            break;
-        h = (h + 1) & (kTileHashSlots - 1);
-    }
-}
-
-// Rank every tile among all tiles by (grid, signed tile i, j, k): its rank is its upper-node id
-// (the run index M of Sec. 3.3 step 5).  O(T^2) comparisons; T is tiny for real scenes.
-__global__ void k_rank_tiles(const int32_t* __restrict__ ijk, const int64_t* __restrict__ joff, int B,
-                             const int32_t* __restrict__ rep_rows, GridPtrs g) {
-    if (g.hdr->overflow) return;
-    const int raw = g.hdr->n_tiles_raw;
-    const int T = raw < kMaxTiles ? raw : kMaxTiles;
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t == 0) {
-        int ov = 0;
-        if (raw > kMaxTiles) ov |= 8;
-        if (T > g.cap_upper) ov |= 1;
-        g.hdr->n_upper = T;
-        if (ov) atomicOr(&g.hdr->overflow, ov);
-    }
-    if (t >= T || T > g.cap_upper) return;
-    const int64_t r = rep_rows[t];
-    const int b = find_batch(joff, B, r);
-    const uint64_t key = tile_key(ijk[3 * r], ijk[3 * r + 1], ijk[3 * r + 2]);
-    int rank = 0;
-    for (int o = 0; o < T; ++o) {
-        const int64_t ro = rep_rows[o];
-        const int bo = find_batch(joff, B, ro);
-        const uint64_t ko = tile_key(ijk[3 * ro], ijk[3 * ro + 1], ijk[3 * ro + 2]);
-        rank += (bo < b) || (bo == b && ko < key);
-    }
-    g.root_key[rank] = key;
-    g.root_batch[rank] = b;
-}
-
-// ---------------------------------------------------------------------------------- leaves -> tree
-// One thread per distinct leaf.
-// LEVEL 0: lower-node bit in the upper node's child mask   (step 11.2)
-// LEVEL 1: leaf bit in the lower node's child mask         (step 11.3)
-// LEVEL 2: the leaf's final id is known: move its mask from the table into the leaf record
-template <int LEVEL>
-__global__ void k_insert(const int32_t* __restrict__ ijk, const int64_t* __restrict__ joff, LeafHash H, GridPtrs g) {
-    if (g.hdr->overflow) return;
-    int32_t slot;
-    const int64_t r = leaf_rep_row(H, g.hdr, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, &slot);
-    if (r < 0) return;
-    const int b = find_batch(joff, g.B, r);
-    const int i = ijk[3 * r], j = ijk[3 * r + 1], k = ijk[3 * r + 2];
-    const int u = find_upper(g.root_key, g.root_batch, g.hdr->n_upper, b, tile_key(i, j, k));
-    if (u < 0) return;
-    if (LEVEL == 0) {
-        const int off = upper_off(i, j, k);
-        uint64_t* word = g.upper_mask + (size_t)u * kUpperWords + (off >> 6);
-        const uint64_t bit = 1ull << (off & 63);
-        if (!(*word & bit)) atomicOr((unsigned long long*)word, (unsigned long long)bit);  // stale reads only cost an atomic
-        return;
-    }
-    const int l = child_of(g.upper_mask + (size_t)u * kUpperWords, g.upper_prefix + (size_t)u * kUpperWords,
-                           upper_off(i, j, k));
-    if (l < 0) return;
-    if (LEVEL == 1) {
-        const int off = lower_off(i, j, k);
-        uint64_t* word = g.lower_mask + (size_t)l * kLowerWords + (off >> 6);
-        atomicOr((unsigned long long*)word, 1ull << (off & 63));
-        return;
-    }
-    const int f = child_of(g.lower_mask + (size_t)l * kLowerWords, g.lower_prefix + (size_t)l * kLowerWords,
-                           lower_off(i, j, k));
-    if (f < 0) return;
-    fx_leaf* lf = &g.leaf[f];
-    const uint64_t* src = H.mask + (size_t)slot * 8;
-#pragma unroll
-    for (int w = 0; w < 8; ++w) lf->mask[w] = src[w];
-    lf->origin[0] = (i >> 3) * 8;
-    lf->origin[1] = (j >> 3) * 8;
-    lf->origin[2] = (k >> 3) * 8;
-    lf->batch = b;
-}
-
-// ---------------------------------------------------------------------------------- popcount scans
+// ---------------------------------------------------------------------------------- block scan
 constexpr int kScanThreads = 1024;
 constexpr int kWordsPerThread = 8;
 constexpr int kWordChunk = kScanThreads * kWordsPerThread;  // mask words per block
@@ -270,6 +86,399 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* t
     return wave_base + incl - v;
 }
 
+// ---------------------------------------------------------------------------------- voxels -> leaves
+// The input rows are reduced to the set of distinct (grid, leaf) pairs, each with the 512-bit
+// mask of its voxels (step 11.4; duplicates collapse in the bit).  Everything above the leaves
+// -- root tiles, upper and lower nodes, the order of the leaves -- is derived afterwards from
+// these few leaves instead of from the rows.  Two ways to get there:
+//   * partitioned (large inputs): the rows are first scattered into buckets by a hash of their
+//     leaf, so that all voxels of a leaf meet in one workgroup, which then builds the masks
+//     of its bucket in LDS -- no global atomic per voxel (device-scope atomics run at memory,
+//     about 13 G/s on this part, and would cost more than the rest of the build together);
+//   * direct (small inputs, or when a bucket holds more leaves than its LDS table): one global
+//     open-addressing table, one compare-and-swap per new leaf and one atomic OR per voxel.
+struct LeafList {
+    int4* key;           // [cap] (leaf i, leaf j, leaf k, grid): leaf coordinates = voxel coordinates >> 3
+    int32_t* mask_idx;   // [cap] where the leaf's mask sits in `mask` (units of 8 words)
+    uint64_t* mask;
+    int32_t cap;
+};
+
+__device__ __forceinline__ uint32_t leaf_hash(int b, int li, int lj, int lk) {
+    return mix32(mix32(mix32(mix32(0x811C9DC5u, (uint32_t)b), (uint32_t)li), (uint32_t)lj), (uint32_t)lk);
+}
+
+// ---- direct path
+__global__ void __launch_bounds__(256)
+k_voxels_to_leaves(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff, int B,
+                   int32_t* __restrict__ slots, uint32_t slot_mask, LeafList L, GridHeader* hdr) {
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int b = r < n_rows ? find_batch(joff, B, r) : -1;
+    int li = 0, lj = 0, lk = 0;
+    uint32_t h = 0;
+    bool claimed = false;
+    if (b >= 0) {
+        const int i = ijk[3 * r], j = ijk[3 * r + 1], k = ijk[3 * r + 2];
+        li = i >> 3; lj = j >> 3; lk = k >> 3;
+        h = leaf_hash(b, li, lj, lk) & slot_mask;
+        bool found = false;
+        for (uint32_t probe = 0; probe <= slot_mask; ++probe) {
+            // slots hold a representative input row + 1 (0 = empty); device-coherent read: a slot
+            // claimed from another XCD must be seen
+            int32_t s = __hip_atomic_load(&slots[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (s == 0) {
+                const int32_t old = atomicCAS(&slots[h], 0, (int32_t)r + 1);
+                if (old == 0) { found = claimed = true; break; }
+                s = old;
+            }
+            const int64_t q = s - 1;
+            if ((ijk[3 * q] >> 3) == li && (ijk[3 * q + 1] >> 3) == lj && (ijk[3 * q + 2] >> 3) == lk &&
+                find_batch(joff, B, q) == b) {
+                found = true;
+                break;
+            }
+            h = (h + 1) & slot_mask;
+        }
+        if (!found) atomicOr(&hdr->overflow, 4 | 32);   // table full: the leaf count is incomplete
+        else atomicOr((unsigned long long*)&L.mask[(size_t)h * 8 + (i & 7)], 1ull << (((j & 7) << 3) | (k & 7)));
+    }
+    // list the newly claimed leaves: one counter update per wave, not per leaf
+    const uint64_t cl = __ballot(claimed);
+    if (cl) {
+        const int lane = threadIdx.x & 63;
+        const int leader = __ffsll((long long)cl) - 1;
+        int base = 0;
+        if (lane == leader) base = atomicAdd(&hdr->n_leaf_raw, __popcll(cl));
+        base = __shfl(base, leader);
+        if (claimed) {
+            const int pos = base + __popcll(cl & ((1ull << lane) - 1));
+            if (pos < L.cap) { L.key[pos] = make_int4(li, lj, lk, b); L.mask_idx[pos] = (int32_t)h; }
+            else atomicOr(&hdr->overflow, 4);
+        }
+    }
+}
+
+// ---- partitioned path
+constexpr int kPartThreads = 1024;
+constexpr int kPartRowsPerThread = 4;
+constexpr int kPartChunk = kPartThreads * kPartRowsPerThread;   // rows per workgroup of the two row passes
+constexpr int kMaxBuckets = 2048;
+constexpr int kBucketSlots = 1024;                               // LDS leaf table of one bucket
+
+struct PartRow { int i, j, k, b; uint32_t bucket; };
+
+__device__ __forceinline__ PartRow load_part_row(const int32_t* __restrict__ ijk, int64_t n_rows,
+                                                 const int64_t* __restrict__ joff, int B, int64_t r, uint32_t bucket_mask) {
+    PartRow p;
+    p.b = r < n_rows ? find_batch(joff, B, r) : -1;
+    p.i = p.j = p.k = 0; p.bucket = 0;
+    if (p.b >= 0) {
+        p.i = ijk[3 * r]; p.j = ijk[3 * r + 1]; p.k = ijk[3 * r + 2];
+        p.bucket = leaf_hash(p.b, p.i >> 3, p.j >> 3, p.k >> 3) & bucket_mask;
+    }
+    return p;
+}
+
+// rows per (bucket, workgroup): hist[bucket * n_wg + wg]
+__global__ void __launch_bounds__(kPartThreads)
+k_bucket_count(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff, int B,
+               uint32_t bucket_mask, uint32_t* __restrict__ hist) {
+    __shared__ uint32_t cnt[kMaxBuckets];
+    for (uint32_t e = threadIdx.x; e <= bucket_mask; e += kPartThreads) cnt[e] = 0;
+    __syncthreads();
+    const int64_t r0 = (int64_t)blockIdx.x * kPartChunk + threadIdx.x;
+#pragma unroll
+    for (int q = 0; q < kPartRowsPerThread; ++q) {
+        const PartRow p = load_part_row(ijk, n_rows, joff, B, r0 + q * kPartThreads, bucket_mask);
+        if (p.b >= 0) atomicAdd(&cnt[p.bucket], 1u);
+    }
+    __syncthreads();
+    for (uint32_t e = threadIdx.x; e <= bucket_mask; e += kPartThreads) hist[(size_t)e * gridDim.x + blockIdx.x] = cnt[e];
+}
+
+// one wave per bucket: exclusive prefix over the workgroups' counts (in place) and the bucket total
+__global__ void __launch_bounds__(256) k_bucket_scan(uint32_t* __restrict__ hist, int n_wg, int n_buckets,
+                                                     uint32_t* __restrict__ totals) {
+    const int bucket = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6), lane = threadIdx.x & 63;
+    if (bucket >= n_buckets) return;
+    uint32_t* row = hist + (size_t)bucket * n_wg;
+    uint32_t carry = 0;
+    for (int base = 0; base < n_wg; base += 64) {
+        const int e = base + lane;
+        const uint32_t v = e < n_wg ? row[e] : 0u;
+        uint32_t incl = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(incl, d);
+            if (lane >= d) incl += o;
+        }
+        if (e < n_wg) row[e] = carry + incl - v;
+        carry += __shfl(incl, 63);
+    }
+    if (lane == 0) totals[bucket] = carry;
+}
+
+// scatter the rows into their buckets as (i, j, k, grid) records; the records of one workgroup
+// are ordered by bucket in LDS first so that each bucket receives one contiguous run
+__global__ void __launch_bounds__(kPartThreads)
+k_bucket_scatter(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff, int B,
+                 uint32_t bucket_mask, const uint32_t* __restrict__ hist, const uint32_t* __restrict__ totals,
+                 uint32_t* __restrict__ bucket_start, int4* __restrict__ records) {
+    extern __shared__ __align__(16) unsigned char part_lds[];
+    int4* rec = reinterpret_cast<int4*>(part_lds);                          // [kPartChunk]
+    uint32_t* dest = reinterpret_cast<uint32_t*>(rec + kPartChunk);         // [kPartChunk]
+    uint32_t* cnt = dest + kPartChunk;                                      // [kMaxBuckets] rows of this workgroup
+    uint32_t* lstart = cnt + kMaxBuckets;                                   // [kMaxBuckets] first LDS slot
+    uint32_t* gbase = lstart + kMaxBuckets;                                 // [kMaxBuckets] first global record
+    const uint32_t n_buckets = bucket_mask + 1;
+    const int tid = threadIdx.x;
+    // bucket starts = exclusive scan of the totals (every workgroup repeats it; the first one publishes it)
+    {
+        uint32_t v[2], sum = 0;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) { const uint32_t e = tid * 2 + q; v[q] = e < n_buckets ? totals[e] : 0u; sum += v[q]; }
+        uint32_t total;
+        uint32_t run = block_exclusive_scan(sum, &total);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const uint32_t e = tid * 2 + q;
+            if (e < n_buckets) {
+                gbase[e] = run + hist[(size_t)e * gridDim.x + blockIdx.x];
+                if (blockIdx.x == 0) bucket_start[e] = run;
+            }
+            run += v[q];
+        }
+        if (blockIdx.x == 0 && tid == 0) bucket_start[n_buckets] = total;
+    }
+    for (uint32_t e = tid; e < n_buckets; e += kPartThreads) cnt[e] = 0;
+    __syncthreads();
+    PartRow p[kPartRowsPerThread];
+    uint32_t rank[kPartRowsPerThread];
+    const int64_t r0 = (int64_t)blockIdx.x * kPartChunk + tid;
+#pragma unroll
+    for (int q = 0; q < kPartRowsPerThread; ++q) {
+        p[q] = load_part_row(ijk, n_rows, joff, B, r0 + q * kPartThreads, bucket_mask);
+        rank[q] = p[q].b >= 0 ? atomicAdd(&cnt[p[q].bucket], 1u) : 0u;
+    }
+    __syncthreads();
+    // first LDS slot of every bucket = exclusive scan of this workgroup's counts
+    {
+        uint32_t v[2], sum = 0;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) { const uint32_t e = tid * 2 + q; v[q] = e < n_buckets ? cnt[e] : 0u; sum += v[q]; }
+        uint32_t total;
+        uint32_t run = block_exclusive_scan(sum, &total);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const uint32_t e = tid * 2 + q;
+            if (e < n_buckets) lstart[e] = run;
+            run += v[q];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kPartRowsPerThread; ++q) {
+        if (p[q].b < 0) continue;
+        const uint32_t s = lstart[p[q].bucket] + rank[q];
+        rec[s] = make_int4(p[q].i, p[q].j, p[q].k, p[q].b);
+        dest[s] = gbase[p[q].bucket] + rank[q];
+    }
+    __syncthreads();
+    // number of valid rows of this workgroup = last bucket's start + count
+    const uint32_t n_local = lstart[bucket_mask] + cnt[bucket_mask];
+    for (uint32_t s = tid; s < n_local; s += kPartThreads) records[dest[s]] = rec[s];
+}
+
+// one workgroup per bucket: the bucket's distinct leaves and their masks, built in LDS
+__global__ void __launch_bounds__(256)
+k_bucket_leaves(const int4* __restrict__ records, const uint32_t* __restrict__ bucket_start, LeafList L, GridHeader* hdr) {
+    __shared__ int32_t rep[kBucketSlots];                 // representative record + 1 (0 = empty)
+    __shared__ unsigned long long mask[kBucketSlots * 8];
+    __shared__ uint32_t wave_sums[4];
+    __shared__ int32_t list_base;
+    const int tid = threadIdx.x;
+    for (int e = tid; e < kBucketSlots; e += 256) rep[e] = 0;
+    for (int e = tid; e < kBucketSlots * 8; e += 256) mask[e] = 0ull;
+    __syncthreads();
+    const uint32_t begin = bucket_start[blockIdx.x], end = bucket_start[blockIdx.x + 1];
+    bool full = false;
+    for (uint32_t r = begin + tid; r < end; r += 256) {
+        const int4 v = records[r];
+        const int li = v.x >> 3, lj = v.y >> 3, lk = v.z >> 3;
+        uint32_t h = (leaf_hash(v.w, li, lj, lk) >> 12) & (kBucketSlots - 1);   // other bits than the bucket's
+        bool found = false;
+        for (int probe = 0; probe < kBucketSlots; ++probe) {
+            int32_t s = rep[h];
+            if (s == 0) {
+                const int32_t old = atomicCAS(&rep[h], 0, (int32_t)(r - begin) + 1);
+                if (old == 0) { found = true; break; }
+                s = old;
+            }
+            const int4 o = records[begin + (uint32_t)(s - 1)];
+            if ((o.x >> 3) == li && (o.y >> 3) == lj && (o.z >> 3) == lk && o.w == v.w) { found = true; break; }
+            h = (h + 1) & (kBucketSlots - 1);
+        }
+        if (found) atomicOr(&mask[h * 8 + (v.x & 7)], 1ull << (((v.y & 7) << 3) | (v.z & 7)));
+        else full = true;
+    }
+    if (full) atomicOr(&hdr->overflow, 64);   // more leaves than the table holds: the build falls back to the direct path
+    __syncthreads();
+    // append the bucket's leaves to the global list
+    constexpr int kPer = kBucketSlots / 256;
+    uint32_t mine = 0;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) mine += rep[tid * kPer + q] != 0;
+    uint32_t incl = mine;
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) wave_sums[wave] = incl;
+    __syncthreads();
+    uint32_t before = incl - mine;
+    for (int w = 0; w < wave; ++w) before += wave_sums[w];
+    if (tid == 255) {
+        const uint32_t total = before + mine;
+        list_base = total ? atomicAdd(&hdr->n_leaf_raw, (int)total) : 0;
+    }
+    __syncthreads();
+    int pos = list_base + (int)before;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+        const int slot = tid * kPer + q;
+        const int32_t s = rep[slot];
+        if (s == 0) continue;
+        if (pos < L.cap) {
+            const int4 v = records[begin + (uint32_t)(s - 1)];
+            L.key[pos] = make_int4(v.x >> 3, v.y >> 3, v.z >> 3, v.w);
+            L.mask_idx[pos] = pos;
+#pragma unroll
+            for (int w = 0; w < 8; ++w) L.mask[(size_t)pos * 8 + w] = mask[slot * 8 + w];
+        } else {
+            atomicOr(&hdr->overflow, 4);
+        }
+        ++pos;
+    }
+}
+
+// key of distinct leaf `idx`, or false past the end
+__device__ __forceinline__ bool leaf_at(const LeafList& L, const GridHeader* hdr, int64_t idx, int4* key) {
+    const int n = min(hdr->n_leaf_raw, L.cap);
+    if (idx >= n) return false;
+    *key = L.key[idx];
+    return true;
+}
+
+// ---------------------------------------------------------------------------------- root tiles
+// Distinct (grid, tile) pairs of the leaves go into a small open-addressing table whose slots
+// hold a representative leaf (+1; 0 = empty).
+__global__ void k_find_tiles(LeafList L, int32_t* __restrict__ tile_slots, int32_t* __restrict__ rep_leaves,
+                             GridHeader* hdr) {
+    if (hdr->overflow) return;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int4 key;
+    if (!leaf_at(L, hdr, idx, &key)) return;
+    const int b = key.w, ti = key.x >> 9, tj = key.y >> 9, tk = key.z >> 9;   // leaf coordinate >> 9 = voxel >> 12
+    // lanes that share the first active lane's tile let that lane insert for them
+    const uint64_t active = __ballot(1);
+    const int leader = __ffsll((long long)active) - 1;
+    const int lb = __shfl(b, leader), li = __shfl(ti, leader), lj = __shfl(tj, leader), lk = __shfl(tk, leader);
+    const int lane = threadIdx.x & 63;
+    if (lane != leader && lb == b && li == ti && lj == tj && lk == tk) return;
+    uint32_t h = mix32(mix32(mix32(mix32(0x811C9DC5u, (uint32_t)b), (uint32_t)ti), (uint32_t)tj), (uint32_t)tk);
+    h &= (kTileHashSlots - 1);
+    for (int probe = 0; probe < kTileHashSlots; ++probe) {
+        int32_t s = tile_slots[h];
+        if (s == 0) {
+            if (hdr->n_tiles_raw > kMaxTiles) break;  // over the limit: reported by the ranking kernel
+            const int32_t old = atomicCAS(&tile_slots[h], 0, (int32_t)idx + 1);
+            if (old == 0) {
+                const int pos = atomicAdd(&hdr->n_tiles_raw, 1);
+                if (pos < kMaxTiles) rep_leaves[pos] = (int32_t)idx;
+                break;
+            }
+            s = old;
+        }
+        const int4 o = L.key[s - 1];
+        if (o.w == b && (o.x >> 9) == ti && (o.y >> 9) == tj && (o.z >> 9) == tk) break;
+        h = (h + 1) & (kTileHashSlots - 1);
+    }
+}
+
+// Rank every tile among all tiles by (grid, signed tile i, j, k): its rank is its upper-node id
+// (the run index M of Sec. 3.3 step 5).  O(T^2) comparisons; T is tiny for real scenes.
+__global__ void k_rank_tiles(LeafList L, const int32_t* __restrict__ rep_leaves, GridPtrs g) {
+    if (g.hdr->overflow) return;
+    const int raw = g.hdr->n_tiles_raw;
+    const int T = raw < kMaxTiles ? raw : kMaxTiles;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t == 0) {
+        int ov = 0;
+        if (raw > kMaxTiles) ov |= 8;
+        if (T > g.cap_upper) ov |= 1;
+        g.hdr->n_upper = T;
+        if (ov) atomicOr(&g.hdr->overflow, ov);
+    }
+    if (t >= T || T > g.cap_upper) return;
+    const int4 me = L.key[rep_leaves[t]];
+    const uint64_t key = tile_key(me.x << 3, me.y << 3, me.z << 3);
+    int rank = 0;
+    for (int o = 0; o < T; ++o) {
+        const int4 ot = L.key[rep_leaves[o]];
+        const uint64_t ko = tile_key(ot.x << 3, ot.y << 3, ot.z << 3);
+        rank += (ot.w < me.w) || (ot.w == me.w && ko < key);
+    }
+    g.root_key[rank] = key;
+    g.root_batch[rank] = me.w;
+}
+
+// ---------------------------------------------------------------------------------- leaves -> tree
+// One thread per distinct leaf.
+// LEVEL 0: lower-node bit in the upper node's child mask   (step 11.2)
+// LEVEL 1: leaf bit in the lower node's child mask         (step 11.3)
+// LEVEL 2: the leaf's final id is known: move its mask into the leaf record
+template <int LEVEL>
+__global__ void k_insert(LeafList L, GridPtrs g) {
+    if (g.hdr->overflow) return;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int4 key;
+    if (!leaf_at(L, g.hdr, idx, &key)) return;
+    const int b = key.w;
+    const int i = key.x << 3, j = key.y << 3, k = key.z << 3;   // the leaf's origin
+    const int u = find_upper(g.root_key, g.root_batch, g.hdr->n_upper, b, tile_key(i, j, k));
+    if (u < 0) return;
+    if (LEVEL == 0) {
+        const int off = upper_off(i, j, k);
+        uint64_t* word = g.upper_mask + (size_t)u * kUpperWords + (off >> 6);
+        const uint64_t bit = 1ull << (off & 63);
+        if (!(*word & bit)) atomicOr((unsigned long long*)word, (unsigned long long)bit);  // stale reads only cost an atomic
+        return;
+    }
+    const int l = child_of(g.upper_mask + (size_t)u * kUpperWords, g.upper_prefix + (size_t)u * kUpperWords,
+                           upper_off(i, j, k));
+    if (l < 0) return;
+    if (LEVEL == 1) {
+        const int off = lower_off(i, j, k);
+        uint64_t* word = g.lower_mask + (size_t)l * kLowerWords + (off >> 6);
+        atomicOr((unsigned long long*)word, 1ull << (off & 63));
+        return;
+    }
+    const int f = child_of(g.lower_mask + (size_t)l * kLowerWords, g.lower_prefix + (size_t)l * kLowerWords,
+                           lower_off(i, j, k));
+    if (f < 0) return;
+    fx_leaf* lf = &g.leaf[f];
+    const uint64_t* src = L.mask + (size_t)L.mask_idx[idx] * 8;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) lf->mask[w] = src[w];
+    lf->origin[0] = i;
+    lf->origin[1] = j;
+    lf->origin[2] = k;
+    lf->batch = b;
+}
+
+// ---------------------------------------------------------------------------------- popcount scans
 // which level's masks a scan runs over
 struct LevelScan {
     const uint64_t* words;
@@ -507,8 +716,10 @@ static fx_status scan_level(const fx_grid* g, LevelScan s, int cap_nodes, uint32
 
 // One attempt with the given node capacities.  On FX_OK, (*out)->hdr.overflow tells whether a
 // capacity was too small (the counts found so far are valid up to the overflowing level).
+constexpr int64_t kPartitionMinRows = 65536;   // below this the direct path's few kernels win
+
 static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64_t* d_joff, int32_t B,
-                               int cap_upper, int cap_lower, int cap_leaf, hipStream_t st, fx_grid** out) {
+                               int cap_upper, int cap_lower, int cap_leaf, bool direct, hipStream_t st, fx_grid** out) {
     FX_HT("(outside)");
     fx_grid* g = new (std::nothrow) fx_grid();
     if (!g) { set_error("host allocation failed"); return FX_ENOMEM; }
@@ -520,28 +731,51 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     layout(g);
     g->h_vox_base = (int64_t*)calloc((size_t)B + 1, sizeof(int64_t));
 
-    // scratch: [tile table | leaf table slots | leaf table masks] cleared, then
-    //          [tile representative rows | leaf list | scan block sums] not cleared
+    // Leaf list capacity and the way to it.  Scratch layout:
+    //   cleared:      [leaf masks | tile table | direct path: leaf table slots]
+    //   not cleared:  [leaf keys | mask indices | tile representatives | scan block sums |
+    //                  partitioned path: bucket records, histogram, totals, bucket starts]
     const int64_t max_items = std::max<int64_t>((int64_t)g->cap_lower * kLowerWords / kWordChunk,
                                                 std::max<int64_t>((int64_t)g->cap_upper * kUpperWords / kWordChunk,
                                                                   (int64_t)g->cap_leaf / kLeafChunk)) + 2;
-    size_t n_slots = 1024;
-    while (n_slots < 2 * (size_t)g->cap_leaf) n_slots <<= 1;
-    const size_t clear_bytes = sizeof(int32_t) * kTileHashSlots + (sizeof(int32_t) + 8 * sizeof(uint64_t)) * n_slots;
-    const size_t scratch_bytes = clear_bytes + sizeof(int32_t) * kMaxTiles + sizeof(int32_t) * (size_t)g->cap_leaf +
-                                 sizeof(uint32_t) * (size_t)max_items;
+    const bool partition = !direct && n_rows >= kPartitionMinRows;
+    size_t n_slots = 0;                       // direct path: table slots, masks indexed by slot
+    if (!partition) { n_slots = 1024; while (n_slots < 2 * (size_t)g->cap_leaf) n_slots <<= 1; }
+    const size_t n_masks = partition ? (size_t)g->cap_leaf : n_slots;
+    int n_buckets = 64;
+    while (n_buckets < kMaxBuckets && (int64_t)n_buckets * 1024 < n_rows) n_buckets <<= 1;
+    const int n_part_wg = (int)((n_rows + kPartChunk - 1) / kPartChunk);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const size_t o_mask = take(sizeof(uint64_t) * 8 * n_masks);
+    const size_t o_tslot = take(sizeof(int32_t) * kTileHashSlots);
+    const size_t o_slots = take(sizeof(int32_t) * n_slots);
+    const size_t clear_bytes = off;
+    const size_t o_key = take(sizeof(int4) * (size_t)g->cap_leaf);
+    const size_t o_midx = take(sizeof(int32_t) * (size_t)g->cap_leaf);
+    const size_t o_rep = take(sizeof(int32_t) * kMaxTiles);
+    const size_t o_bsum = take(sizeof(uint32_t) * (size_t)max_items);
+    const size_t o_rec = take(partition ? sizeof(int4) * (size_t)n_rows : 0);
+    const size_t o_hist = take(partition ? sizeof(uint32_t) * (size_t)n_buckets * n_part_wg : 0);
+    const size_t o_tot = take(partition ? sizeof(uint32_t) * n_buckets : 0);
+    const size_t o_bst = take(partition ? sizeof(uint32_t) * (n_buckets + 1) : 0);
     void* scratch = nullptr;
-    rc = dev_alloc(&scratch, scratch_bytes, st);
+    rc = dev_alloc(&scratch, off, st);
     if (rc != FX_OK) { fx_grid_destroy(g); return rc; }
-    LeafHash H;
-    H.mask = (uint64_t*)scratch;
-    int32_t* d_tile_slots = (int32_t*)(H.mask + 8 * n_slots);
-    H.slots = d_tile_slots + kTileHashSlots;
-    int32_t* d_rep = H.slots + n_slots;
-    H.list = d_rep + kMaxTiles;
-    uint32_t* d_block_sums = (uint32_t*)(H.list + g->cap_leaf);
-    H.slot_mask = (uint32_t)(n_slots - 1);
-    H.cap_leaf = g->cap_leaf;
+    char* sp = (char*)scratch;
+    LeafList L;
+    L.mask = (uint64_t*)(sp + o_mask);
+    L.key = (int4*)(sp + o_key);
+    L.mask_idx = (int32_t*)(sp + o_midx);
+    L.cap = g->cap_leaf;
+    int32_t* d_tile_slots = (int32_t*)(sp + o_tslot);
+    int32_t* d_slots = (int32_t*)(sp + o_slots);
+    int32_t* d_rep = (int32_t*)(sp + o_rep);
+    uint32_t* d_block_sums = (uint32_t*)(sp + o_bsum);
+    int4* d_records = (int4*)(sp + o_rec);
+    uint32_t* d_hist = (uint32_t*)(sp + o_hist);
+    uint32_t* d_totals = (uint32_t*)(sp + o_tot);
+    uint32_t* d_bucket_start = (uint32_t*)(sp + o_bst);
 
     FX_HT("grid: allocs");
     auto fail = [&](fx_status s) { dev_free(scratch, st); fx_grid_destroy(g); return s; };
@@ -551,25 +785,44 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     {
         ProfScope ps(kProfMemset, st);
         FX_TRY_OR_FAIL(hipMemsetAsync(g->buf, 0, g->buf_bytes, st));
-        FX_TRY_OR_FAIL(hipMemsetAsync(scratch, 0, clear_bytes, st));
+        // the partitioned path writes every mask it lists, so only the tile table needs clearing there
+        if (partition) FX_TRY_OR_FAIL(hipMemsetAsync(d_tile_slots, 0, sizeof(int32_t) * kTileHashSlots, st));
+        else FX_TRY_OR_FAIL(hipMemsetAsync(scratch, 0, clear_bytes, st));
     }
     FX_HT("grid: memsets");
     const GridPtrs q = ptrs_of(g);
     if (n_rows > 0 && B > 0) {
-        const unsigned nb_rows = (unsigned)((n_rows + 255) / 256);
         const unsigned nb_leaf = (unsigned)((g->cap_leaf + 255) / 256);
-        { ProfScope ps(kProfVoxelsToLeaves, st); k_voxels_to_leaves<<<nb_rows, 256, 0, st>>>(d_ijk, n_rows, d_joff, B, H, g->d_hdr); }
-        { ProfScope ps(kProfFindTiles, st); k_find_tiles<<<nb_leaf, 256, 0, st>>>(d_ijk, d_joff, B, H, d_tile_slots, d_rep, g->d_hdr); }
-        { ProfScope ps(kProfRankTiles, st); k_rank_tiles<<<kMaxTiles / 256, 256, 0, st>>>(d_ijk, d_joff, B, d_rep, q); }
-        { ProfScope ps(kProfInsertUpper, st); k_insert<0><<<nb_leaf, 256, 0, st>>>(d_ijk, d_joff, H, q); }
+        if (partition) {
+            const uint32_t bucket_mask = (uint32_t)n_buckets - 1;
+            const size_t lds = (sizeof(int4) + sizeof(uint32_t)) * kPartChunk + 3 * sizeof(uint32_t) * kMaxBuckets;
+            FX_TRY_OR_FAIL(hipFuncSetAttribute((const void*)k_bucket_scatter, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               (int)lds));
+            { ProfScope ps(kProfBucketCount, st);
+              k_bucket_count<<<n_part_wg, kPartThreads, 0, st>>>(d_ijk, n_rows, d_joff, B, bucket_mask, d_hist); }
+            { ProfScope ps(kProfBucketScan, st);
+              k_bucket_scan<<<(n_buckets * 64 + 255) / 256, 256, 0, st>>>(d_hist, n_part_wg, n_buckets, d_totals); }
+            { ProfScope ps(kProfBucketScatter, st);
+              k_bucket_scatter<<<n_part_wg, kPartThreads, lds, st>>>(d_ijk, n_rows, d_joff, B, bucket_mask, d_hist, d_totals,
+                                                                     d_bucket_start, d_records); }
+            { ProfScope ps(kProfBucketLeaves, st);
+              k_bucket_leaves<<<n_buckets, 256, 0, st>>>(d_records, d_bucket_start, L, g->d_hdr); }
+        } else {
+            const unsigned nb_rows = (unsigned)((n_rows + 255) / 256);
+            ProfScope ps(kProfVoxelsToLeaves, st);
+            k_voxels_to_leaves<<<nb_rows, 256, 0, st>>>(d_ijk, n_rows, d_joff, B, d_slots, (uint32_t)(n_slots - 1), L, g->d_hdr);
+        }
+        { ProfScope ps(kProfFindTiles, st); k_find_tiles<<<nb_leaf, 256, 0, st>>>(L, d_tile_slots, d_rep, g->d_hdr); }
+        { ProfScope ps(kProfRankTiles, st); k_rank_tiles<<<kMaxTiles / 256, 256, 0, st>>>(L, d_rep, q); }
+        { ProfScope ps(kProfInsertUpper, st); k_insert<0><<<nb_leaf, 256, 0, st>>>(L, q); }
         LevelScan su{g->d_upper_mask, g->d_upper_prefix, &g->d_hdr->n_upper, kUpperWords, &g->d_hdr->n_lower,
                      g->cap_lower, 2};
         { ProfScope ps(kProfScanUpper, st); if (scan_level(g, su, g->cap_upper, d_block_sums, st) != FX_OK) return fail(FX_EDEVICE); }
-        { ProfScope ps(kProfInsertLower, st); k_insert<1><<<nb_leaf, 256, 0, st>>>(d_ijk, d_joff, H, q); }
+        { ProfScope ps(kProfInsertLower, st); k_insert<1><<<nb_leaf, 256, 0, st>>>(L, q); }
         LevelScan sl{g->d_lower_mask, g->d_lower_prefix, &g->d_hdr->n_lower, kLowerWords, &g->d_hdr->n_leaf,
                      g->cap_leaf, 4};
         { ProfScope ps(kProfScanLower, st); if (scan_level(g, sl, g->cap_lower, d_block_sums, st) != FX_OK) return fail(FX_EDEVICE); }
-        { ProfScope ps(kProfInsertLeaf, st); k_insert<2><<<nb_leaf, 256, 0, st>>>(d_ijk, d_joff, H, q); }
+        { ProfScope ps(kProfInsertLeaf, st); k_insert<2><<<nb_leaf, 256, 0, st>>>(L, q); }
         const int lb = std::max(1, (g->cap_leaf + kLeafChunk - 1) / kLeafChunk);
         {
         ProfScope ps(kProfScanLeaf, st);
@@ -613,9 +866,11 @@ fx_status build_index_grid_device_joff(const int32_t* d_ijk, int64_t n_rows, con
     int cap_upper = B + 8;
     int cap_lower = (int)std::min<int64_t>(std::max<int64_t>(n_rows, 1), 64 * (int64_t)std::max(B, 1) + n_rows / 256);
     int cap_leaf = (int)std::min<int64_t>(std::max<int64_t>(n_rows, 1), 1024 + n_rows / 8);
-    for (int attempt = 0; attempt < 8; ++attempt) {
+    const char* force = getenv("FVDB_HOTPATH_GRID_DIRECT");
+    bool direct = force && force[0] == '1';
+    for (int attempt = 0; attempt < 9; ++attempt) {
         fx_grid* g = nullptr;
-        FX_TRY(build_attempt(d_ijk, n_rows, d_joff, B, cap_upper, cap_lower, cap_leaf, st, &g));
+        FX_TRY(build_attempt(d_ijk, n_rows, d_joff, B, cap_upper, cap_lower, cap_leaf, direct, st, &g));
         const int ov = g->hdr.overflow;
         if (!ov) { *out = g; return FX_OK; }
         if (ov & 8) {
@@ -628,13 +883,14 @@ fx_status build_index_grid_device_joff(const int32_t* d_ijk, int64_t n_rows, con
             set_error("more than 2^31-1 active voxels");
             return FX_ERANGE;
         }
+        if (ov & 64) direct = true;   // a bucket held more leaves than its LDS table
         if (ov & 1) cap_upper = g->hdr.n_upper;
         if (ov & 2) { cap_upper = g->hdr.n_upper; cap_lower = g->hdr.n_lower; }
         if (ov & 4) {
             // The voxel pass counts every distinct leaf it can put in its table (twice the
             // capacity); only when the table itself filled up is the count a lower bound, and
             // the capacity grows geometrically instead (at most one leaf per input row exists).
-            if (ov & 32) cap_leaf = (int)std::min<int64_t>(std::max<int64_t>(n_rows, 1), 4 * (int64_t)cap_leaf);
+            if ((ov & 32) || (ov & 64)) cap_leaf = (int)std::min<int64_t>(std::max<int64_t>(n_rows, 1), 4 * (int64_t)cap_leaf);
             else cap_leaf = g->hdr.n_leaf_raw;
         }
         fx_grid_destroy(g);

@@ -40,6 +40,28 @@ def test_sparse_points_overflow_the_first_capacity_guess():
     H.check_grid(g, og)
 
 
+def test_large_inputs_take_the_bucket_path_and_agree_with_the_direct_path(monkeypatch):
+    # above 65536 rows the build scatters the rows into buckets first; the same input through the
+    # direct path (one global table) must give the same bits, and both must match the oracle
+    grids = [_cloud(31, 60000, -60, 60), np.zeros((0, 3), np.int32), _cloud(32, 50000, 4000, 4200),
+             _cloud(33, 30000, -9000, -8800)]
+    ijk, jo = G.make_jagged(grids)
+    g, og = H.both_grids(ijk, jo)
+    H.check_grid(g, og)
+    monkeypatch.setenv("FVDB_HOTPATH_GRID_DIRECT", "1")
+    g2, _ = H.both_grids(ijk, jo)
+    H.check_grid(g2, og)
+    assert g.leaf_table().tobytes() == g2.leaf_table().tobytes()
+
+
+def test_sparse_large_input_overflows_the_bucket_tables():
+    # one voxel per leaf and about a thousand rows per bucket: some bucket holds more leaves than
+    # its LDS table, so the build repeats through the direct path (and with a larger leaf capacity)
+    pts = _cloud(41, 500000, -40000, 40000)
+    g, og = H.both_grids(pts, np.array([[0, pts.shape[0]]]))
+    H.check_grid(g, og)
+
+
 def test_empty_batch_and_empty_input():
     g, og = H.both_grids(np.zeros((0, 3), np.int32), np.zeros((0, 2), np.int64))
     assert g.num_voxels == 0 and g.counts() == (0, 0, 0)
