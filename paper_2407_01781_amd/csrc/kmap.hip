@@ -87,13 +87,20 @@ __device__ __forceinline__ int lookup_entry(const NbLeafLds& lds, int oi, int oj
 // Neighbour-leaf table: for every output leaf, the ids of the <= 27 input leaves its stencil
 // footprint can touch (-1: none).  One thread per (leaf, slot): a million independent tree
 // descents run at full occupancy here instead of inside the latency-bound tile builder.
+// The thread of slot 0 also notes, for every tile of kTileT consecutive outputs that starts inside
+// its leaf, that the tile's first voxel lies in this leaf.
 template <int K>
-__global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int32_t* __restrict__ nbr) {
+__global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int64_t n_out, int32_t* __restrict__ nbr,
+                                 int32_t* __restrict__ tile_first_leaf) {
     constexpr int D0 = delta_min(K);
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (int64_t)tout.n_leaf * 27) return;
     const int f = (int)(e / 27), slot = (int)(e - (int64_t)f * 27);
     const fx_leaf* lf = tout.leaf + f;
+    if (slot == 0) {
+        const int64_t begin = lf->offset, end = f + 1 < tout.n_leaf ? tout.leaf[f + 1].offset : n_out;
+        for (int64_t t = (begin + kTileT - 1) / kTileT; t * kTileT < end; ++t) tile_first_leaf[t] = f;
+    }
     const int oi = lf->origin[0], oj = lf->origin[1], ok = lf->origin[2];
     const int bi = (stride * oi + D0) >> 3, bj = (stride * oj + D0) >> 3, bk = (stride * ok + D0) >> 3;
     const int hi_i = (stride * (oi + 7) + D0 + K - 1) >> 3, hi_j = (stride * (oj + 7) + D0 + K - 1) >> 3,
@@ -179,7 +186,9 @@ __device__ unsigned long long g_kmap_timing[4096 * 8];
 constexpr int kPackThreads = kTileT;          // one thread per output slot
 constexpr int kPackWaves = kPackThreads / 64;
 constexpr int kHaloHashSlots = 2048;
-constexpr int kLdsLeafRows = 160;            // leaves of a tile whose neighbour rows are kept in LDS
+constexpr int kLdsLeafRows = 56;             // leaves of a tile whose neighbour rows are kept in LDS
+constexpr int kRecHashSlots = 512;           // de-duplication of the neighbour leaves of those rows
+constexpr int kMaxRecs = 160;                // distinct neighbour-leaf records (80 bytes each) kept in LDS
 
 struct PackScratch {                          // live after the lookup phase
     uint64_t key[kTileT];                     // (mask << 16 | slot), sorted by mask
@@ -198,7 +207,12 @@ struct PackLds {
     union {
         struct {                              // lookup phase
             int32_t leaf_off[kTileT];         // first index of every leaf of the tile
-            int32_t nbr_rows[kLdsLeafRows * 27];  // neighbour-leaf ids of the tile's first leaves
+            // neighbours of the tile's first leaves: >= 0 record in `rec`, -1 none, <= -2 leaf id -2-v (not staged)
+            int32_t nbr_rows[kLdsLeafRows * 27];
+            int32_t rec_hash[kRecHashSlots];  // leaf id or -1
+            uint16_t slot_rec[kRecHashSlots]; // hash slot -> record, 0xFFFF: not staged
+            int32_t rec_id[kMaxRecs];
+            uint64_t rec[kMaxRecs * 10];      // Listing 1's 80 bytes: mOffset, mPrefixSum, mBitMask[8]
         } look;
         PackScratch s;
     } u;
@@ -206,8 +220,9 @@ struct PackLds {
     uint32_t wave_mask[kTileWaves];
     uint32_t wave_block0[kTileWaves];
     uint32_t wave_sums[kPackWaves];
-    int32_t n_halo, n_blocks, n_pair_blocks, overflow, f_lo, n_leaves;
+    int32_t n_halo, n_blocks, n_pair_blocks, overflow, f_lo, n_leaves, n_rec;
 };
+static_assert(sizeof(PackLds) <= 80 * 1024, "two tile builders per compute unit");
 
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int j) {
     const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, j);
@@ -296,8 +311,8 @@ __device__ __forceinline__ int select64(uint64_t m, int r) {
 // tile's own index range is the window; otherwise the tile is "direct".
 template <int K, bool SUBM>
 __global__ void __launch_bounds__(kPackThreads)
-k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict__ leaf_nbr, int64_t n_out,
-              TileHeader* __restrict__ tile_hdr,
+k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict__ leaf_nbr,
+              const int32_t* __restrict__ tile_first_leaf, int64_t n_out, TileHeader* __restrict__ tile_hdr,
               uint16_t* __restrict__ tile_perm, int32_t* __restrict__ tile_rows, int row_stride,
               uint16_t* __restrict__ tile_blocks, int block_stride, unsigned long long* __restrict__ stats) {
     constexpr int K3 = K * K * K;
@@ -312,20 +327,15 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     FX_KSTAMP(0);
     // ---- which output leaves overlap [o0, o0 + n_valid)
     if (tid == 0) {
-        int lo = 0, hi = tout.n_leaf;  // last leaf with offset <= o0
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (tout.leaf[mid].offset <= o0) lo = mid; else hi = mid;
-        }
-        int a = lo, b = tout.n_leaf;   // last leaf with offset < o0 + n_valid
-        while (b - a > 1) {
-            const int mid = (a + b) >> 1;
-            if (tout.leaf[mid].offset < o0 + n_valid) a = mid; else b = mid;
-        }
+        // leaves from the one holding the tile's first voxel to the one holding the next tile's first
+        // voxel (which may start exactly at the tile's end: one leaf too many does no harm)
+        const int lo = tile_first_leaf[tile];
+        const int a = (tile + 1) * kTileT < n_out ? tile_first_leaf[tile + 1] : tout.n_leaf - 1;
         L.f_lo = lo;
         L.n_leaves = a + 1 - lo;
-        L.n_halo = 0; L.n_blocks = 0; L.n_pair_blocks = 0; L.overflow = 0;
+        L.n_halo = 0; L.n_blocks = 0; L.n_pair_blocks = 0; L.overflow = 0; L.n_rec = 0;
     }
+    for (int e = tid; e < kRecHashSlots; e += kPackThreads) { L.u.look.rec_hash[e] = -1; L.u.look.slot_rec[e] = 0xFFFF; }
     __syncthreads();
 
     // ---- lookups: one thread per output voxel.  The thread finds its leaf (binary search over the
@@ -335,10 +345,55 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     {
         const int f_lo = L.f_lo, n_leaves = L.n_leaves;
         for (int li = tid; li < n_leaves; li += kPackThreads) L.u.look.leaf_off[li] = (int32_t)tout.leaf[f_lo + li].offset;
+        // The 80-byte records (Listing 1) of the distinct neighbour leaves are staged in LDS, so the
+        // 27 lookups of a voxel chase no pointer through global memory: (1) de-duplicate the
+        // neighbour ids of the tile's leaves in a hash, (2) number the distinct ones, (3) fetch
+        // their records with independent loads and rewrite the neighbour rows as record numbers.
         {
-            const int n_rows_lds = min(n_leaves, kLdsLeafRows) * 27;
+            constexpr int kCandPerThread = (kLdsLeafRows * 27 + kPackThreads - 1) / kPackThreads;
+            const int n_cand = min(n_leaves, kLdsLeafRows) * 27;
             const int32_t* src = leaf_nbr + (int64_t)f_lo * 27;
-            for (int e = tid; e < n_rows_lds; e += kPackThreads) L.u.look.nbr_rows[e] = src[e];
+            int32_t cand_id[kCandPerThread];
+            int cand_slot[kCandPerThread];
+#pragma unroll
+            for (int q = 0; q < kCandPerThread; ++q) {
+                const int e = tid + q * kPackThreads;
+                cand_id[q] = e < n_cand ? src[e] : -1;
+                cand_slot[q] = -1;
+                if (cand_id[q] < 0) continue;
+                uint32_t h = ((uint32_t)cand_id[q] * 0x9E3779B1u) >> 23;   // 9 bits
+                for (int probe = 0; probe < kRecHashSlots; ++probe) {
+                    const int32_t cur = ((volatile int32_t*)L.u.look.rec_hash)[h];
+                    if (cur == cand_id[q]) { cand_slot[q] = (int)h; break; }
+                    if (cur < 0) {
+                        const int32_t old = atomicCAS(&L.u.look.rec_hash[h], -1, cand_id[q]);
+                        if (old < 0 || old == cand_id[q]) { cand_slot[q] = (int)h; break; }
+                    }
+                    h = (h + 1) & (kRecHashSlots - 1);
+                }
+            }
+            __syncthreads();
+            if (tid < kRecHashSlots && L.u.look.rec_hash[tid] >= 0) {
+                const int r = atomicAdd(&L.n_rec, 1);
+                if (r < kMaxRecs) { L.u.look.slot_rec[tid] = (uint16_t)r; L.u.look.rec_id[r] = L.u.look.rec_hash[tid]; }
+            }
+            __syncthreads();
+            const int n_rec = min(L.n_rec, kMaxRecs);
+            for (int e = tid; e < n_rec * 10; e += kPackThreads) {
+                const int r = e / 10, w = e - r * 10;
+                L.u.look.rec[e] = reinterpret_cast<const uint64_t*>(tin.leaf + L.u.look.rec_id[r])[w];
+            }
+#pragma unroll
+            for (int q = 0; q < kCandPerThread; ++q) {
+                const int e = tid + q * kPackThreads;
+                if (e >= n_cand) continue;
+                int32_t v = -1;
+                if (cand_id[q] >= 0) {
+                    const uint16_t r = cand_slot[q] >= 0 ? L.u.look.slot_rec[cand_slot[q]] : (uint16_t)0xFFFF;
+                    v = r != 0xFFFF ? (int32_t)r : -2 - cand_id[q];
+                }
+                L.u.look.nbr_rows[e] = v;
+            }
         }
         __syncthreads();
         int32_t* my_nb = L.nb + tid * K3;
@@ -375,15 +430,19 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
                 const int qj = stride * pj + D0 + (kappa / K) % K;
                 const int qk = stride * pk + D0 + kappa % K;
                 const int slot = (((qi >> 3) - bi) * 3 + ((qj >> 3) - bj)) * 3 + ((qk >> 3) - bk);
-                const int id = row_in_lds ? L.u.look.nbr_rows[lo * 27 + slot] : nbr_row[slot];
+                const int v = row_in_lds ? L.u.look.nbr_rows[lo * 27 + slot] : -2 - nbr_row[slot];   // -2 - (-1) = -1
                 int res = -1;
-                if (id >= 0) {
-                    const fx_leaf* nl = tin.leaf + id;
+                if (v != -1) {
                     const int n2 = qi & 7;
-                    // the three loads are independent: one memory round trip per offset
-                    const uint64_t w = nl->mask[n2];
-                    const uint64_t npre = nl->prefix;
-                    const int32_t noff = (int32_t)nl->offset;
+                    uint64_t w, npre;
+                    int32_t noff;
+                    if (v >= 0) {                   // staged record
+                        const uint64_t* rec = L.u.look.rec + v * 10;
+                        w = rec[2 + n2]; npre = rec[1]; noff = (int32_t)rec[0];
+                    } else {                        // three independent loads: one memory round trip
+                        const fx_leaf* nl = tin.leaf + (-2 - v);
+                        w = nl->mask[n2]; npre = nl->prefix; noff = (int32_t)nl->offset;
+                    }
                     const uint64_t qb = 1ull << (((qj & 7) << 3) | (qk & 7));
                     const int sum = n2 ? (int)((npre >> (9 * (n2 - 1))) & 511) : 0;
                     if (w & qb) res = noff + sum + __popcll(w & (qb - 1));
@@ -694,6 +753,7 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     const size_t o_tr = take(tiled ? sizeof(int32_t) * (size_t)km->row_stride * nt : 0);
     const size_t o_tb = take(tiled ? sizeof(uint16_t) * kIdBlockElems * (size_t)km->block_stride * nt : 0);
     const size_t o_ln = take(tiled ? sizeof(int32_t) * 27 * (size_t)std::max(gout->hdr.n_leaf, 1) : 0);
+    const size_t o_tf = take(tiled ? sizeof(int32_t) * (nt + 1) : 0);
     FX_HT("kmap: host setup");
     fx_status rc = dev_alloc(&km->d_alloc, off, st);
     FX_HT("kmap: alloc");
@@ -705,6 +765,7 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     km->d_tile_rows = (int32_t*)(p + o_tr);
     km->d_tile_blocks = (uint16_t*)(p + o_tb);
     int32_t* d_leaf_nbr = (int32_t*)(p + o_ln);
+    int32_t* d_tile_first = (int32_t*)(p + o_tf);
 
     hipError_t e = hipMemsetAsync(km->d_stats, 0, sizeof(int64_t) * (size_t)(4 + km->K3), st);
     if (e == hipSuccess && km->n_tiles > 0) {
@@ -716,9 +777,9 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
             ProfScope ps(kProfLeafNeighbors, st);
             const int64_t ne = (int64_t)gout->hdr.n_leaf * 27;
             const unsigned nbk = (unsigned)((ne + 255) / 256);
-            if (K == 1) k_leaf_neighbors<1><<<nbk, 256, 0, st>>>(tin, tout, stride, d_leaf_nbr);
-            else if (K == 2) k_leaf_neighbors<2><<<nbk, 256, 0, st>>>(tin, tout, stride, d_leaf_nbr);
-            else k_leaf_neighbors<3><<<nbk, 256, 0, st>>>(tin, tout, stride, d_leaf_nbr);
+            if (K == 1) k_leaf_neighbors<1><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
+            else if (K == 2) k_leaf_neighbors<2><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
+            else k_leaf_neighbors<3><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
         }
         ProfScope ps(kProfBuildTiles, st);
 #define FX_TILES(KV, SUBMV)                                                                                    \
@@ -726,7 +787,8 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
         e = hipFuncSetAttribute((const void*)k_build_tiles<KV, SUBMV>,                                         \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                         \
         if (e == hipSuccess)                                                                                   \
-            k_build_tiles<KV, SUBMV><<<ntl, kPackThreads, lds, st>>>(tin, tout, stride, d_leaf_nbr, km->n_out, \
+            k_build_tiles<KV, SUBMV><<<ntl, kPackThreads, lds, st>>>(tin, tout, stride, d_leaf_nbr, d_tile_first, \
+                                                                     km->n_out,                                \
                                                                      km->d_tile_hdr, km->d_tile_perm,          \
                                                                      km->d_tile_rows, km->row_stride,          \
                                                                      km->d_tile_blocks, km->block_stride,      \
