@@ -43,7 +43,7 @@ fx_status host_staging(void** p, size_t bytes, int area = 0);
 // of hipEvents on the launch stream; fx_profile_read sums the elapsed times per slot.
 enum ProfSlot {
     kProfBucketCount = 0, kProfBucketScan, kProfBucketScatter, kProfBucketLeaves, kProfVoxelsToLeaves, kProfFindTiles, kProfRankTiles, kProfInsertUpper, kProfScanUpper, kProfInsertLower, kProfScanLower,
-    kProfInsertLeaf, kProfScanLeaf, kProfVoxBase, kProfGridIjk, kProfNbmap, kProfLeafNeighbors, kProfBuildTiles,
+    kProfInsertLeaf, kProfScanLeaf, kProfGridIjk, kProfNbmap, kProfLeafNeighbors, kProfBuildTiles,
     kProfPackWeights, kProfConvMfma, kProfConvScalar, kProfMemset, kProfSlotCount
 };
 bool prof_enabled();

@@ -365,10 +365,9 @@ k_bucket_leaves(const int4* __restrict__ records, const uint32_t* __restrict__ b
 
 // key of distinct leaf `idx`, or false past the end
 __device__ __forceinline__ bool leaf_at(const LeafList& L, const GridHeader* hdr, int64_t idx, int4* key) {
-    const int n = min(hdr->n_leaf_raw, L.cap);
-    if (idx >= n) return false;
-    *key = L.key[idx];
-    return true;
+    if (idx >= L.cap) return false;
+    *key = L.key[idx];            // fetched together with the count, not after it (entries past the count are unused)
+    return idx < hdr->n_leaf_raw;
 }
 
 // ---------------------------------------------------------------------------------- root tiles
@@ -453,7 +452,10 @@ __global__ void k_insert(LeafList L, GridPtrs g) {
         const int off = upper_off(i, j, k);
         uint64_t* word = g.upper_mask + (size_t)u * kUpperWords + (off >> 6);
         const uint64_t bit = 1ull << (off & 63);
-        if (!(*word & bit)) atomicOr((unsigned long long*)word, (unsigned long long)bit);  // stale reads only cost an atomic
+        // thousands of leaves share each of these bits: look before the atomic, with a device-coherent
+        // read (a stale one would send every leaf into the same-address atomic queue)
+        const uint64_t seen = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!(seen & bit)) atomicOr((unsigned long long*)word, (unsigned long long)bit);
         return;
     }
     const int l = child_of(g.upper_mask + (size_t)u * kUpperWords, g.upper_prefix + (size_t)u * kUpperWords,
@@ -523,49 +525,70 @@ __global__ void __launch_bounds__(kScanThreads) k_scan_words_local(LevelScan s, 
     }
 }
 
-// phase B: one block turns the block totals into block bases (in place) and publishes the total
-__global__ void __launch_bounds__(kScanThreads) k_scan_block_sums(const int32_t* n_nodes, int items_per_node,
-                                                                   int chunk, uint32_t* __restrict__ block_sums,
-                                                                   GridHeader* hdr, int32_t* n_children,
-                                                                   int64_t* n_children64, int64_t child_cap,
-                                                                   int32_t overflow_bit) {
-    if (hdr->overflow) return;
-    const int64_t n_items = (int64_t)(*n_nodes) * items_per_node;
-    const int n_blocks = (int)((n_items + chunk - 1) / chunk);
-    uint32_t carry = 0;
-    for (int base = 0; base < n_blocks; base += kScanThreads) {
-        const int idx = base + threadIdx.x;
-        const uint32_t v = idx < n_blocks ? block_sums[idx] : 0u;
-        uint32_t total;
-        const uint32_t ex = block_exclusive_scan(v, &total);
-        if (idx < n_blocks) block_sums[idx] = carry + ex;
-        carry += total;
+// sums of the first `mine` block totals and of all `n_blocks` of them (every thread gets both)
+__device__ __forceinline__ void block_sums_before(const uint32_t* __restrict__ block_sums, int mine, int n_blocks,
+                                                  uint64_t* before, uint64_t* all) {
+    __shared__ unsigned long long acc[2];
+    if (threadIdx.x < 2) acc[threadIdx.x] = 0ull;
+    __syncthreads();
+    unsigned long long sb = 0, sa = 0;
+    for (int i = threadIdx.x; i < n_blocks; i += blockDim.x) {
+        const uint32_t v = block_sums[i];
+        sa += v;
+        if (i < mine) sb += v;
     }
-    if (threadIdx.x == 0) {
-        if (n_children) *n_children = (int32_t)carry;
-        if (n_children64) *n_children64 = (int64_t)carry;
-        if ((int64_t)carry > child_cap) atomicOr(&hdr->overflow, overflow_bit);
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+        sb += (unsigned long long)__shfl_xor((long long)sb, d);
+        sa += (unsigned long long)__shfl_xor((long long)sa, d);
     }
+    if ((threadIdx.x & 63) == 0) { atomicAdd(&acc[0], sb); atomicAdd(&acc[1], sa); }
+    __syncthreads();
+    *before = acc[0];
+    *all = acc[1];
 }
 
-// phase C: add the block bases
+// phase B: every block adds the totals of the blocks before it; block 0 publishes the grand total
 __global__ void __launch_bounds__(kScanThreads) k_scan_words_apply(LevelScan s, GridHeader* hdr,
                                                                     const uint32_t* __restrict__ block_sums) {
     if (hdr->overflow) return;
     const int64_t n_words = (int64_t)(*s.n_nodes) * s.words_per_node;
     const int64_t base = (int64_t)blockIdx.x * kWordChunk;
-    if (base >= n_words || blockIdx.x == 0) return;
-    const uint32_t add = block_sums[blockIdx.x];
+    if (base >= n_words) return;
+    const int n_blocks = (int)((n_words + kWordChunk - 1) / kWordChunk);
+    uint64_t before, all;
+    block_sums_before(block_sums, (int)blockIdx.x, n_blocks, &before, &all);
+    if (blockIdx.x == 0) {
+        if (threadIdx.x == 0) {
+            *s.n_children = (int32_t)(all < (uint64_t)INT32_MAX ? all : (uint64_t)INT32_MAX);
+            if ((int64_t)all > s.child_cap) atomicOr(&hdr->overflow, s.overflow_bit);
+        }
+        return;
+    }
+    const uint32_t add = (uint32_t)before;
     const int64_t w0 = base + (int64_t)threadIdx.x * kWordsPerThread;
 #pragma unroll
     for (int q = 0; q < kWordsPerThread; ++q)
         if (w0 + q < n_words) s.prefix[w0 + q] += add;
 }
 
+// First voxel index of every grid of the batch (leaves are ordered by grid): the thread that owns
+// the first leaf of a grid writes the entries of that grid and of the empty grids before it; the
+// owner of the last leaf writes the entries after it.  (The buffer starts zeroed: no leaves, all 0.)
+__device__ __forceinline__ void note_vox_base(const fx_leaf* __restrict__ leaf, int64_t l, int64_t n_leaf, int64_t offset,
+                                              int64_t n_voxels, int64_t* __restrict__ vox_base, int B) {
+    const int bcur = leaf[l].batch;
+    const int bprev = l ? leaf[l - 1].batch : -1;
+    for (int b = bprev + 1; b <= bcur; ++b) vox_base[b] = offset;
+    if (l == n_leaf - 1)
+        for (int b = bcur + 1; b <= B; ++b) vox_base[b] = n_voxels;
+}
+
 // Leaf level: mOffset = exclusive scan of the leaves' active-voxel counts; mPrefixSum = the
 // seven 9-bit inclusive word prefixes of Listing 1.
 __global__ void __launch_bounds__(kScanThreads) k_scan_leaves_local(fx_leaf* __restrict__ leaf, GridHeader* hdr,
-                                                                     uint32_t* __restrict__ block_sums, int single) {
+                                                                     uint32_t* __restrict__ block_sums, int single,
+                                                                     int64_t* __restrict__ vox_base, int B) {
     if (hdr->overflow) return;
     const int64_t n_leaf = hdr->n_leaf;
     const int64_t base = (int64_t)blockIdx.x * kLeafChunk;
@@ -593,7 +616,10 @@ __global__ void __launch_bounds__(kScanThreads) k_scan_leaves_local(fx_leaf* __r
     uint32_t run = block_exclusive_scan(sum, &total);
 #pragma unroll
     for (int q = 0; q < kLeavesPerThread; ++q) {
-        if (l0 + q < n_leaf) leaf[l0 + q].offset = (int64_t)run;
+        if (l0 + q < n_leaf) {
+            leaf[l0 + q].offset = (int64_t)run;
+            if (single) note_vox_base(leaf, l0 + q, n_leaf, (int64_t)run, (int64_t)total, vox_base, B);
+        }
         run += cnt[q];
     }
     if (threadIdx.x == 0) {
@@ -603,30 +629,27 @@ __global__ void __launch_bounds__(kScanThreads) k_scan_leaves_local(fx_leaf* __r
 }
 
 __global__ void __launch_bounds__(kScanThreads) k_scan_leaves_apply(fx_leaf* __restrict__ leaf, GridHeader* hdr,
-                                                                     const uint32_t* __restrict__ block_sums) {
+                                                                     const uint32_t* __restrict__ block_sums,
+                                                                     int64_t* __restrict__ vox_base, int B) {
     if (hdr->overflow) return;
     const int64_t n_leaf = hdr->n_leaf;
     const int64_t base = (int64_t)blockIdx.x * kLeafChunk;
-    if (base >= n_leaf || blockIdx.x == 0) return;
-    const int64_t add = block_sums[blockIdx.x];
+    if (base >= n_leaf) return;
+    const int n_blocks = (int)((n_leaf + kLeafChunk - 1) / kLeafChunk);
+    uint64_t before, all;
+    block_sums_before(block_sums, (int)blockIdx.x, n_blocks, &before, &all);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        hdr->n_voxels = (int64_t)all;
+        if (all > (uint64_t)INT32_MAX) atomicOr(&hdr->overflow, 16);
+    }
     const int64_t l0 = base + (int64_t)threadIdx.x * kLeavesPerThread;
 #pragma unroll
     for (int q = 0; q < kLeavesPerThread; ++q)
-        if (l0 + q < n_leaf) leaf[l0 + q].offset += add;
-}
-
-// first voxel index of every grid of the batch (leaves are ordered by grid)
-__global__ void k_vox_base(GridPtrs g) {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b > g.B) return;
-    if (g.hdr->overflow) { g.vox_base[b] = 0; return; }
-    const int n_leaf = g.hdr->n_leaf;
-    int lo = 0, hi = n_leaf;  // first leaf with batch >= b
-    while (lo < hi) {
-        int mid = (lo + hi) >> 1;
-        if (g.leaf[mid].batch < b) lo = mid + 1; else hi = mid;
-    }
-    g.vox_base[b] = lo < n_leaf ? g.leaf[lo].offset : g.hdr->n_voxels;
+        if (l0 + q < n_leaf) {
+            const int64_t off = leaf[l0 + q].offset + (int64_t)before;
+            leaf[l0 + q].offset = off;
+            note_vox_base(leaf, l0 + q, n_leaf, off, (int64_t)all, vox_base, B);
+        }
 }
 
 // ---------------------------------------------------------------------------------- queries
@@ -706,8 +729,6 @@ static fx_status scan_level(const fx_grid* g, LevelScan s, int cap_nodes, uint32
         k_scan_words_local<<<1, kScanThreads, 0, st>>>(s, g->d_hdr, d_block_sums, 1);
     } else {
         k_scan_words_local<<<n_blocks, kScanThreads, 0, st>>>(s, g->d_hdr, d_block_sums, 0);
-        k_scan_block_sums<<<1, kScanThreads, 0, st>>>(s.n_nodes, s.words_per_node, kWordChunk, d_block_sums,
-                                                      g->d_hdr, s.n_children, nullptr, s.child_cap, s.overflow_bit);
         k_scan_words_apply<<<n_blocks, kScanThreads, 0, st>>>(s, g->d_hdr, d_block_sums);
     }
     FX_HIP_TRY(hipGetLastError());
@@ -827,15 +848,12 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
         {
         ProfScope ps(kProfScanLeaf, st);
         if (lb == 1) {
-            k_scan_leaves_local<<<1, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums, 1);
+            k_scan_leaves_local<<<1, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums, 1, g->d_vox_base, B);
         } else {
-            k_scan_leaves_local<<<lb, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums, 0);
-            k_scan_block_sums<<<1, kScanThreads, 0, st>>>(&g->d_hdr->n_leaf, 1, kLeafChunk, d_block_sums, g->d_hdr,
-                                                          nullptr, &g->d_hdr->n_voxels, INT32_MAX, 16);
-            k_scan_leaves_apply<<<lb, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums);
+            k_scan_leaves_local<<<lb, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums, 0, g->d_vox_base, B);
+            k_scan_leaves_apply<<<lb, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums, g->d_vox_base, B);
         }
         }
-        { ProfScope ps(kProfVoxBase, st); k_vox_base<<<(B + 1 + 255) / 256, 256, 0, st>>>(q); }
         FX_TRY_OR_FAIL(hipGetLastError());
     }
     FX_HT("grid: kernel launches");
