@@ -188,10 +188,10 @@ constexpr int kPackWaves = kPackThreads / 64;
 constexpr int kHaloHashSlots = 2048;
 constexpr int kLdsLeafRows = 56;             // leaves of a tile whose neighbour rows are kept in LDS
 constexpr int kRecHashSlots = 512;           // de-duplication of the neighbour leaves of those rows
-constexpr int kMaxRecs = 160;                // distinct neighbour-leaf records (80 bytes each) kept in LDS
+constexpr int kMaxRecs = 128;                // distinct neighbour-leaf records kept in LDS
 
 struct PackScratch {                          // live after the lookup phase
-    uint64_t key[kTileT];                     // (mask << 16 | slot), sorted by mask
+    uint32_t key[kTileT];                     // slot of every position of the mask-sorted order
     int32_t hash[kHaloHashSlots];             // open addressing over halo rows
     int32_t halo[kMaxHalo];                   // distinct halo rows in insertion order
     uint32_t slot_mask[kTileT];
@@ -212,7 +212,8 @@ struct PackLds {
             int32_t rec_hash[kRecHashSlots];  // leaf id or -1
             uint16_t slot_rec[kRecHashSlots]; // hash slot -> record, 0xFFFF: not staged
             int32_t rec_id[kMaxRecs];
-            uint64_t rec[kMaxRecs * 10];      // Listing 1's 80 bytes: mOffset, mPrefixSum, mBitMask[8]
+            uint64_t rec_mask[kMaxRecs * 8];  // mBitMask of Listing 1
+            int32_t rec_base[kMaxRecs * 8];   // per mask word: mOffset + the prefix-sum field that precedes it
         } look;
         PackScratch s;
     } u;
@@ -231,18 +232,18 @@ __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int j) {
 }
 
 // bitonic sort of one key per thread over the whole block (ascending by thread id)
-__device__ __forceinline__ uint64_t block_sort_keys(uint64_t v, uint64_t* lds) {
+__device__ __forceinline__ uint32_t block_sort_keys32(uint32_t v, uint32_t* lds) {
     const int tid = threadIdx.x;
     for (int k = 2; k <= kPackThreads; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
-            uint64_t o;
+            uint32_t o;
             if (j >= 64) {
                 lds[tid] = v;
                 __syncthreads();
                 o = lds[tid ^ j];
                 __syncthreads();
             } else {
-                o = shfl_xor_u64(v, j);
+                o = (uint32_t)__shfl_xor((int)v, j);
             }
             const bool up = ((tid & k) == 0), lower = ((tid & j) == 0);
             const bool take_min = (lower == up);
@@ -379,9 +380,11 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
             }
             __syncthreads();
             const int n_rec = min(L.n_rec, kMaxRecs);
-            for (int e = tid; e < n_rec * 10; e += kPackThreads) {
-                const int r = e / 10, w = e - r * 10;
-                L.u.look.rec[e] = reinterpret_cast<const uint64_t*>(tin.leaf + L.u.look.rec_id[r])[w];
+            for (int e = tid; e < n_rec * 8; e += kPackThreads) {
+                const int r = e >> 3, w = e & 7;
+                const fx_leaf* nl = tin.leaf + L.u.look.rec_id[r];
+                L.u.look.rec_mask[e] = nl->mask[w];
+                L.u.look.rec_base[e] = (int32_t)nl->offset + (w ? (int32_t)((nl->prefix >> (9 * (w - 1))) & 511) : 0);
             }
 #pragma unroll
             for (int q = 0; q < kCandPerThread; ++q) {
@@ -421,33 +424,43 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
                       bk = (stride * lf->origin[2] + D0) >> 3;
             const int32_t* nbr_row = leaf_nbr + (int64_t)f * 27;
             const bool row_in_lds = lo < kLdsLeafRows;
-            // kept as a rolled loop: the fully unrolled form of this divergent body gave wrong entries
+            // kept as rolled loops: the fully unrolled form of this divergent body gave wrong entries
             // for the offsets (-1,0,0), (0,-1,0), (0,0,-1) on gfx950 (cause not established; the
             // parity tests against the oracle catch it)
+            const int32_t* lds_row = L.u.look.nbr_rows + lo * 27;
+            int kappa = 0;
 #pragma unroll 1
-            for (int kappa = 0; kappa < K3; ++kappa) {
-                const int qi = stride * pi + D0 + kappa / (K * K);
-                const int qj = stride * pj + D0 + (kappa / K) % K;
-                const int qk = stride * pk + D0 + kappa % K;
-                const int slot = (((qi >> 3) - bi) * 3 + ((qj >> 3) - bj)) * 3 + ((qk >> 3) - bk);
-                const int v = row_in_lds ? L.u.look.nbr_rows[lo * 27 + slot] : -2 - nbr_row[slot];   // -2 - (-1) = -1
-                int res = -1;
-                if (v != -1) {
-                    const int n2 = qi & 7;
-                    uint64_t w, npre;
-                    int32_t noff;
-                    if (v >= 0) {                   // staged record
-                        const uint64_t* rec = L.u.look.rec + v * 10;
-                        w = rec[2 + n2]; npre = rec[1]; noff = (int32_t)rec[0];
-                    } else {                        // three independent loads: one memory round trip
-                        const fx_leaf* nl = tin.leaf + (-2 - v);
-                        w = nl->mask[n2]; npre = nl->prefix; noff = (int32_t)nl->offset;
+            for (int a = 0; a < K; ++a) {
+                const int qi = stride * pi + D0 + a;
+                const int si = ((qi >> 3) - bi) * 9, n2 = qi & 7;
+#pragma unroll 1
+                for (int b2 = 0; b2 < K; ++b2) {
+                    const int qj = stride * pj + D0 + b2;
+                    const int sij = si + ((qj >> 3) - bj) * 3, bj8 = (qj & 7) << 3;
+#pragma unroll 1
+                    for (int c = 0; c < K; ++c, ++kappa) {
+                        const int qk = stride * pk + D0 + c;
+                        const int slot = sij + ((qk >> 3) - bk);
+                        const int v = row_in_lds ? lds_row[slot] : -2 - nbr_row[slot];   // -2 - (-1) = -1
+                        int res = -1;
+                        if (v != -1) {
+                            uint64_t w;
+                            int32_t base;
+                            if (v >= 0) {                   // staged record
+                                w = L.u.look.rec_mask[v * 8 + n2];
+                                base = L.u.look.rec_base[v * 8 + n2];
+                            } else {                        // three independent loads: one memory round trip
+                                const fx_leaf* nl = tin.leaf + (-2 - v);
+                                w = nl->mask[n2];
+                                const uint64_t npre = nl->prefix;
+                                base = (int32_t)nl->offset + (n2 ? (int32_t)((npre >> (9 * (n2 - 1))) & 511) : 0);
+                            }
+                            const uint64_t qb = 1ull << (bj8 | (qk & 7));
+                            if (w & qb) res = base + __popcll(w & (qb - 1));
+                        }
+                        my_nb[kappa] = res;
                     }
-                    const uint64_t qb = 1ull << (((qj & 7) << 3) | (qk & 7));
-                    const int sum = n2 ? (int)((npre >> (9 * (n2 - 1))) & 511) : 0;
-                    if (w & qb) res = noff + sum + __popcll(w & (qb - 1));
                 }
-                my_nb[kappa] = res;
             }
         } else {
 #pragma unroll
@@ -494,9 +507,14 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
 
     FX_KSTAMP(2);
     // ---- order outputs by mask; order halo rows by index; per-slot list base (direct tiles)
-    const uint64_t sorted = block_sort_keys(((uint64_t)mask << 16) | (uint64_t)tid, S.key);
+    // The sort key keeps 23 of the 27 mask bits (the four corner taps of the lowest i-plane weigh
+    // least in the order and are dropped) so that key and slot fit 32 bits; S.key then holds the
+    // slot of every sorted position.
+    const uint32_t low9 = mask & 511u;
+    const uint32_t key23 = ((mask >> 9) << 5) | ((low9 >> 1) & 1u) | (((low9 >> 3) & 7u) << 1) | (((low9 >> 7) & 1u) << 4);
+    const uint32_t sorted = block_sort_keys32((key23 << 9) | (uint32_t)tid, S.key);
     __syncthreads();
-    S.key[tid] = sorted;
+    S.key[tid] = sorted & 511u;
     __syncthreads();
     FX_KSTAMP(3);
     int32_t* my_rows = tile_rows + tile * (int64_t)row_stride;
@@ -521,7 +539,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     }
     if (tid < kGroupsPerTile) {
         uint32_t gm = 0;
-        for (int n = 0; n < kGroup; ++n) gm |= (uint32_t)(S.key[tid * kGroup + n] >> 16);
+        for (int n = 0; n < kGroup; ++n) gm |= S.slot_mask[S.key[tid * kGroup + n]];
         L.group_mask[tid] = gm;
     }
     __syncthreads();
@@ -560,7 +578,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     }
     if (tid < kGroupsPerTile) H->group_mask[tid] = L.group_mask[tid];
     if (tid < kTileWaves) { H->wave_mask[tid] = L.wave_mask[tid]; H->wave_block0[tid] = L.wave_block0[tid]; }
-    tile_perm[tile * kTileT + tid] = (uint16_t)(sorted & 0xFFFF);
+    tile_perm[tile * kTileT + tid] = (uint16_t)(sorted & 511u);
     if (direct) {
         uint32_t pos = S.slot_base[tid];
         for (int kappa = 0; kappa < K3; ++kappa) {
