@@ -202,6 +202,8 @@ struct PackScratch {                          // live after the lookup phase
     uint16_t slot_rank[kHaloHashSlots];       // hash slot -> rank of its row among the halo rows
 };
 
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+
 struct PackLds {
     int32_t nb[kTileT * kMaxK3Tiled];         // the tile's map entries [slot][kappa]
     union {
@@ -343,6 +345,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     // tile's leaf offsets), its position inside the leaf (select on the leaf mask), and evaluates
     // Listing 1 for its K^3 neighbours through the neighbour-leaf table; the few leaf records a
     // tile touches stay in the L1 cache.
+    uint32_t mask = 0, hmask = 0;     // taps of this thread's voxel; those whose row lies outside the window
     {
         const int f_lo = L.f_lo, n_leaves = L.n_leaves;
         for (int li = tid; li < n_leaves; li += kPackThreads) L.u.look.leaf_off[li] = (int32_t)tout.leaf[f_lo + li].offset;
@@ -401,6 +404,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
         __syncthreads();
         int32_t* my_nb = L.nb + tid * K3;
         if (tid < n_valid) {
+            const int32_t w_lo = SUBM ? (int32_t)o0 : 0, w_n = SUBM ? n_valid : 0;
             constexpr int D0 = delta_min(K);
             const int32_t o = (int32_t)(o0 + tid);
             int lo = 0, hi = n_leaves;   // last leaf of the tile with offset <= o
@@ -458,6 +462,13 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
                             const uint64_t qb = 1ull << (bj8 | (qk & 7));
                             if (w & qb) res = base + __popcll(w & (qb - 1));
                         }
+                        // entry encoding from here on: -1 none; -2 - id: row win_lo + id of the window;
+                        // >= 0: a row outside the window, not yet entered in the halo table
+                        if (res >= 0) {
+                            mask |= 1u << kappa;
+                            if (res >= w_lo && res < w_lo + w_n) res = -2 - (res - w_lo);
+                            else hmask |= 1u << kappa;
+                        }
                         my_nb[kappa] = res;
                     }
                 }
@@ -476,29 +487,28 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     __syncthreads();
     const int32_t win_lo = SUBM ? (int32_t)o0 : 0;
     const int32_t win_n = SUBM ? n_valid : 0;
-    uint32_t mask = 0;
-    for (int kappa = 0; kappa < K3; ++kappa) {
+    // rows outside the window go into the halo table; an entry that is in becomes -1024 - (table slot)
+    for (uint32_t hm = SUBM ? hmask : 0u; hm; hm &= hm - 1) {
+        const int kappa = __ffs(hm) - 1;
         const int32_t r = L.nb[tid * K3 + kappa];
-        if (r < 0) continue;
-        mask |= 1u << kappa;
-        if (!SUBM) continue;
-        if (r >= win_lo && r < win_lo + win_n) continue;
         uint32_t h = ((uint32_t)r * 0x9E3779B1u) >> 21;  // 11 bits
+        bool in = false;
         for (;;) {
             const int32_t cur = ((volatile int32_t*)S.hash)[h];
-            if (cur == r) break;
+            if (cur == r) { in = true; break; }
             if (cur < 0) {
                 if (((volatile int32_t*)&L.overflow)[0]) break;
                 const int32_t old = atomicCAS(&S.hash[h], -1, r);
                 if (old < 0) {
                     const int pos = atomicAdd(&L.n_halo, 1);
-                    if (pos < kMaxHalo) { S.halo[pos] = r; S.halo_slot[pos] = (uint16_t)h; } else L.overflow = 1;
+                    if (pos < kMaxHalo) { S.halo[pos] = r; S.halo_slot[pos] = (uint16_t)h; in = true; } else L.overflow = 1;
                     break;
                 }
-                if (old == r) break;
+                if (old == r) { in = true; break; }
             }
             h = (h + 1) & (kHaloHashSlots - 1);
         }
+        if (in) L.nb[tid * K3 + kappa] = -1024 - (int32_t)h;
     }
     S.slot_mask[tid] = mask;
     __syncthreads();
@@ -582,43 +592,49 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     if (direct) {
         uint32_t pos = S.slot_base[tid];
         for (int kappa = 0; kappa < K3; ++kappa) {
-            const int32_t r = L.nb[tid * K3 + kappa];
-            if (r >= 0) my_rows[pos++] = r;
+            const int32_t v = L.nb[tid * K3 + kappa];
+            if (v == -1) continue;
+            my_rows[pos++] = v >= 0 ? v : (v <= -1024 ? S.hash[-1024 - v] : win_lo + (-2 - v));
         }
     }
 
     FX_KSTAMP(6);
-    // ---- id blocks: the threads of a group walk the offsets of the group's wave
+    // ---- id blocks: thread (wave w, voxel column n, quarter q) fills the 8-byte entries
+    // [voxel n][4 group slots] of every fourth block of wave w, so that a block is written as 32
+    // consecutive 8-byte stores
     {
-        const int g = tid / kGroup, sub = tid % kGroup;
-        const int w = (g >> kDealShift) & (kTileWaves - 1);
-        const int gi = ((g >> (kDealShift + 2)) << kDealShift) | (g & ((1 << kDealShift) - 1));
-        const int slot = (int)(S.key[g * kGroup + sub] & 0xFFFF);
-        const uint32_t smask = S.slot_mask[slot];
-        const uint32_t sbase = direct ? S.slot_base[slot] : 0u;
+        const int w = tid >> 7, q = (tid >> 5) & 3, n = tid & 31;
+        int slot[kGroupsPerWave];
+        uint32_t smask[kGroupsPerWave], sbase[kGroupsPerWave];
+#pragma unroll
+        for (int gi = 0; gi < kGroupsPerWave; ++gi) {
+            slot[gi] = (int)S.key[tile_group_of(w, gi) * kGroup + n];
+            smask[gi] = S.slot_mask[slot[gi]];
+            sbase[gi] = direct ? S.slot_base[slot[gi]] : 0u;
+        }
         uint32_t wm = L.wave_mask[w];
         size_t blk = (size_t)tile * block_stride + L.wave_block0[w];
-        while (wm) {
+        for (int bi = 0; wm; ++bi, ++blk, wm &= wm - 1) {
+            if ((bi & 3) != q) continue;
             const int kappa = __ffs(wm) - 1;
-            wm &= wm - 1;
-            uint16_t id = kNoRow;
-            if ((smask >> kappa) & 1u) {
-                if (direct) {
-                    id = (uint16_t)(sbase + __popc(smask & ((1u << kappa) - 1u)));
-                } else {
-                    const int32_t r = L.nb[slot * K3 + kappa];
-                    if (r >= win_lo && r < win_lo + win_n) {
-                        id = (uint16_t)(r - win_lo);
+            uint32_t ids[kGroupsPerWave];
+#pragma unroll
+            for (int gi = 0; gi < kGroupsPerWave; ++gi) {
+                uint32_t id = kNoRow;
+                if ((smask[gi] >> kappa) & 1u) {
+                    if (direct) {
+                        id = sbase[gi] + __popc(smask[gi] & ((1u << kappa) - 1u));
                     } else {
-                        uint32_t hh = ((uint32_t)r * 0x9E3779B1u) >> 21;
-                        while (S.hash[hh] != r) hh = (hh + 1) & (kHaloHashSlots - 1);
-                        id = (uint16_t)(win_n + S.slot_rank[hh]);
+                        const int32_t v = L.nb[slot[gi] * K3 + kappa];
+                        id = v <= -1024 ? (uint32_t)win_n + S.slot_rank[-1024 - v] : (uint32_t)(-2 - v);
                     }
                 }
+                if (lds_codes) id = lds_row_code(id == kNoRow ? (uint32_t)kRowCap : id);
+                ids[gi] = id & 0xFFFFu;
             }
-            if (lds_codes) id = (uint16_t)lds_row_code(id == kNoRow ? (uint32_t)kRowCap : (uint32_t)id);
-            tile_blocks[blk * kIdBlockElems + sub * kGroupsPerWave + gi] = id;
-            ++blk;
+            static_assert(kGroupsPerWave == 4, "one 8-byte entry per voxel column");
+            *reinterpret_cast<u32x2_t*>(tile_blocks + blk * kIdBlockElems + n * kGroupsPerWave) =
+                u32x2_t{ids[0] | (ids[1] << 16), ids[2] | (ids[3] << 16)};
         }
     }
     FX_KSTAMP(7);
