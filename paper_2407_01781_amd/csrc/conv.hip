@@ -352,12 +352,18 @@ __device__ __forceinline__ int first_offset(uint32_t mask) { return mask ? __ffs
 // producers' barriers), then write the tile's outputs back (lane (n, h) holds channels
 // slice*64 + 32h .. +31 of output slot g*32 + n).  `phase` counts chunks since kernel start and
 // selects the LDS half; `mb` selects the half that holds this tile's id blocks.
+// The weight pipeline (wa, wb and their tags) runs across chunks and, in the LDS-only variant,
+// across items: the last steps of an item already fetch the first weights of the next one (MN
+// is its slot), ahead of the write-back stores -- loads and stores retire in order, and weights
+// requested after the stores would have to wait for them.
 template <typename T, bool OUT_F32, bool GENERAL>
-__device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, const Item& I, int phase,
+__device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, const MetaSlot& MN, const Item& I, int phase,
                                              int mb, int nchunk, int nslice, int wave, int lane,
                                              const int32_t* __restrict__ tile_rows, int row_stride,
                                              const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp, int C_in,
-                                             int C_out, void* __restrict__ out, unsigned long long (&tm)[4]) {
+                                             int C_out, void* __restrict__ out, typename Elem<T>::vec8 (&wa)[4],
+                                             typename Elem<T>::vec8 (&wb)[4], int& wa_at, int& wb_at,
+                                             unsigned long long (&tm)[4]) {
     typedef typename Elem<T>::vec8 vec8;
     constexpr int NG = kGroupsPerWave;
     const int n = lane & 31, h = lane >> 5;
@@ -377,19 +383,22 @@ __device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, cons
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[gi][mt][v] = 0.f;
 
-    // The weight pipeline runs across the chunks of one item; it restarts with every item (the
-    // two code variants of this function do not share registers well enough to hand it over).
-    vec8 wa[4], wb[4];
-    int wa_at = -1, wb_at = -1;
     int local[NG];
     for (int c = 0; c < nchunk; ++c) {
         // where this wave's weights come from after this chunk
         int w_after0, w_after1;
         {
-            const int nc = c + 1 < nchunk ? c + 1 : c;   // after the last chunk the fetches are not used
-            w_after0 = w_frag(nslice, w_kappa_stride, I.slice, nc, first_offset(wave_mask));
-            const uint32_t more = wave_mask & (wave_mask - 1);
-            w_after1 = more ? w_frag(nslice, w_kappa_stride, I.slice, nc, first_offset(more)) : w_after0;
+            int nsl = I.slice, nc = c + 1;
+            uint32_t nmask = wave_mask;
+            if (nc == nchunk) {      // the next item (if it is not one for this variant, the fetches go unused)
+                const int64_t nwork = slot_work(MN);
+                nc = 0;
+                nsl = nwork >= 0 ? (int)(nwork % nslice) : I.slice;
+                nmask = nwork >= 0 ? (uint32_t)uni((int)MN.hdr.wave_mask[wave]) : 0u;
+            }
+            w_after0 = w_frag(nslice, w_kappa_stride, nsl, nc, first_offset(nmask));
+            const uint32_t more = nmask & (nmask - 1);
+            w_after1 = more ? w_frag(nslice, w_kappa_stride, nsl, nc, first_offset(more)) : w_after0;
         }
         if (wave_mask) {
             FX_T0();
@@ -434,6 +443,25 @@ __device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, cons
         }
     }
     FX_TACC(tm[2]);
+}
+
+// Items whose rows are not all staged in LDS take this path: a real call, so that its registers
+// are allocated apart from the main loop's.
+template <typename T, bool OUT_F32>
+__device__ __noinline__ void consume_item_general(int slot, int phase, int mb, int nchunk, int nslice, int wave, int lane,
+                                                  const int32_t* __restrict__ tile_rows, int row_stride,
+                                                  const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp,
+                                                  int C_in, int C_out, void* __restrict__ out) {
+    typedef typename Elem<T>::vec8 vec8;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    ConvLds& L = *reinterpret_cast<ConvLds*>(lds_raw);
+    const MetaSlot& M = L.meta[slot];
+    const Item I = item_of(M, slot_work(M), nslice);
+    vec8 wa[4], wb[4];
+    int wa_at = -1, wb_at = -1;
+    unsigned long long tm[4] = {0, 0, 0, 0};
+    consume_item<T, OUT_F32, true>(L, M, L.meta[(slot + 1) % kMetaSlots], I, phase, mb, nchunk, nslice, wave, lane, tile_rows,
+                                   row_stride, feat, wp, C_in, C_out, out, wa, wb, wa_at, wb_at, tm);
 }
 
 // Persistent workgroups, one per compute unit.  Work items (tile of 512 consecutive outputs x
@@ -544,19 +572,37 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
         const unsigned long long t_start = __builtin_readcyclecounter();
 #endif
         __syncthreads();
+        vec8 wa[4], wb[4];
+        int wa_at, wb_at;
+        {   // weights of the first two offsets of the first item
+            const int w_kappa_stride = nchunk * nslice * 4 * 64;
+            const uint32_t m0 = (uint32_t)uni((int)L.meta[0].hdr.wave_mask[wave]);
+            const uint32_t m1 = m0 & (m0 - 1);
+            wa_at = w_frag(nslice, w_kappa_stride, (int)(first % nslice), 0, first_offset(m0));
+            wb_at = m1 ? w_frag(nslice, w_kappa_stride, (int)(first % nslice), 0, first_offset(m1)) : wa_at;
+            const vec8* w0 = reinterpret_cast<const vec8*>(wp) + lane;
+#pragma unroll
+            for (int f = 0; f < 4; ++f) { wa[f] = (w0 + wa_at)[f * 64]; wb[f] = (w0 + wb_at)[f * 64]; }
+        }
         __syncthreads();
         int phase = 0, n_items = 0;
         for (int item_no = 0;; ++item_no, phase += nchunk) {
-            const MetaSlot& M = L.meta[item_no % kMetaSlots];
+            const int slot = item_no % kMetaSlots;
+            const MetaSlot& M = L.meta[slot];
             const int64_t work = slot_work(M);
             if (work < 0) break;
             const Item cur = item_of(M, work, nslice);
-            if (cur.general)
-                consume_item<T, OUT_F32, true>(L, M, cur, phase, item_no & 1, nchunk, nslice, wave, lane, tile_rows,
-                                               row_stride, feat, wp, C_in, C_out, out, tm);
-            else
-                consume_item<T, OUT_F32, false>(L, M, cur, phase, item_no & 1, nchunk, nslice, wave, lane, tile_rows,
-                                                row_stride, feat, wp, C_in, C_out, out, tm);
+            if (cur.general) {
+                consume_item_general<T, OUT_F32>(slot, phase, item_no & 1, nchunk, nslice, wave, lane, tile_rows, row_stride,
+                                                 feat, wp, C_in, C_out, out);
+                wa_at = wb_at = -1;       // nothing is handed over a call
+#pragma unroll
+                for (int f = 0; f < 4; ++f) { wa[f] = vec8{}; wb[f] = vec8{}; }
+            } else {
+                consume_item<T, OUT_F32, false>(L, M, L.meta[(item_no + 1) % kMetaSlots], cur, phase, item_no & 1, nchunk, nslice,
+                                                wave, lane, tile_rows, row_stride, feat, wp, C_in, C_out, out, wa, wb, wa_at,
+                                                wb_at, tm);
+            }
             ++n_items;
         }
 #ifdef FX_CONV_TIMING
