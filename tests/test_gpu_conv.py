@@ -102,19 +102,23 @@ def test_dense_block_uses_rows_beyond_the_lds_budget():
     H.conv_tolerance_check(y.float().cpu().numpy(), O.conv(og, og, 3, 1, feat, wt), "bf16", 27, 64)
 
 
-def test_full_size_lidar_bf16_sampled_rows():
-    """Config 3 at full size in the benchmark's launch configuration; the oracle computes a
-    sample of output rows one by one (a few thousand rows spread over the grid)."""
-    w = G.workload("lidar1m")
+@pytest.mark.parametrize("name", ["lidar1m", "indoor4", "lidar1m_down", "sheets4"])
+def test_full_size_configs_sampled_rows(name):
+    """Configs 3, 2, 4 and 5 at full size in the benchmark's launch configuration; the oracle
+    computes a sample of output rows one by one (a few thousand rows spread over the grid, the
+    first and the last rows included)."""
+    w = G.workload(name)
     ijk, jo = w.jagged_ijk()
     g, og = H.both_grids(ijk, jo)
-    km = fx.build_kernel_map(g, 3, 1)
+    km = fx.build_kernel_map(g, w.kernel_size, w.stride)
+    ogo = O.output_grid(og, w.kernel_size, w.stride)
+    assert km.n_out == ogo.num_voxels
     feat, wt = w.feats_weights()
-    y = fx.sparse_conv_fwd(km, H.to_device_storage(feat, "bf16"), H.to_device_storage(wt, "bf16"))
+    y = fx.sparse_conv_fwd(km, H.to_device_storage(feat, w.dtype), H.to_device_storage(wt, w.dtype))
     y = y.float().cpu().numpy()
-    n = og.num_voxels
+    n = ogo.num_voxels
     starts = list(range(0, n - 300, n // 12)) + [n - 300]
     f64, w64 = feat.astype(np.float64), wt.astype(np.float64)
     for s in starts:
-        ref = O.conv(og, og, 3, 1, f64, w64, s, s + 300)
-        H.conv_tolerance_check(y[s:s + 300], ref[s:s + 300], "bf16", 27, 64)
+        ref = O.conv(og, ogo, w.kernel_size, w.stride, f64, w64, s, s + 300)
+        H.conv_tolerance_check(y[s:s + 300], ref[s:s + 300], w.dtype, w.k3, w.c_in)

@@ -72,12 +72,19 @@ def test_unsupported_kernel_stride_is_reported():
     assert e.value.status == -2
 
 
-def test_full_size_lidar_map_sampled_rows_and_invariants():
-    w = G.workload("lidar1m")
+@pytest.mark.parametrize("name,pairs", [("lidar1m", 7983738), ("indoor4", None), ("lidar1m_down", 986880),
+                                        ("sheets4", 1625841)])
+def test_full_size_maps_match_oracle(name, pairs):
+    """Every entry of the map at the benchmark's sizes (the oracle needs a few seconds)."""
+    w = G.workload(name)
     ijk, jo = w.jagged_ijk()
     g, og = H.both_grids(ijk, jo)
-    km = fx.build_kernel_map(g, 3, 1)
+    km = fx.build_kernel_map(g, w.kernel_size, w.stride)
+    ogo = O.output_grid(og, w.kernel_size, w.stride)
     got = km.dense().cpu().numpy()
-    ref = O.kernel_map(og, og, 3, 1)                      # ~2 s on the host
+    ref = O.kernel_map(og, ogo, w.kernel_size, w.stride)
     assert np.array_equal(got, ref)
-    assert km.info()[0] == 7983738
+    n_pairs, per = km.info()
+    assert n_pairs == int((ref >= 0).sum()) and np.array_equal(per, (ref >= 0).sum(0))
+    if pairs is not None:
+        assert n_pairs == pairs
