@@ -380,16 +380,26 @@ __global__ void k_find_tiles(LeafList L, int32_t* __restrict__ tile_slots, int32
     int4 key;
     if (!leaf_at(L, hdr, idx, &key)) return;
     const int b = key.w, ti = key.x >> 9, tj = key.y >> 9, tk = key.z >> 9;   // leaf coordinate >> 9 = voxel >> 12
-    // lanes that share the first active lane's tile let that lane insert for them
-    const uint64_t active = __ballot(1);
-    const int leader = __ffsll((long long)active) - 1;
-    const int lb = __shfl(b, leader), li = __shfl(ti, leader), lj = __shfl(tj, leader), lk = __shfl(tk, leader);
-    const int lane = threadIdx.x & 63;
-    if (lane != leader && lb == b && li == ti && lj == tj && lk == tk) return;
+    // one lane per distinct tile of the wave inserts (accesses to one address from all over the
+    // device queue up at memory): repeatedly, the first lane still waiting becomes the speaker for
+    // all lanes with its tile
+    {
+        const int lane = threadIdx.x & 63;
+        bool waiting = true, speaker = false;
+        for (int round = 0; round < 64; ++round) {
+            const uint64_t pending = __ballot(waiting);
+            if (!pending) break;
+            const int leader = __ffsll((long long)pending) - 1;
+            const int lb = __shfl(b, leader), li = __shfl(ti, leader), lj = __shfl(tj, leader), lk = __shfl(tk, leader);
+            if (waiting && lb == b && li == ti && lj == tj && lk == tk) { waiting = false; speaker = (lane == leader); }
+        }
+        if (!speaker) return;
+    }
     uint32_t h = mix32(mix32(mix32(mix32(0x811C9DC5u, (uint32_t)b), (uint32_t)ti), (uint32_t)tj), (uint32_t)tk);
     h &= (kTileHashSlots - 1);
     for (int probe = 0; probe < kTileHashSlots; ++probe) {
-        int32_t s = tile_slots[h];
+        // device-coherent read: once a tile is in, nobody else reaches the compare-and-swap
+        int32_t s = __hip_atomic_load(&tile_slots[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (s == 0) {
             if (hdr->n_tiles_raw > kMaxTiles) break;  // over the limit: reported by the ranking kernel
             const int32_t old = atomicCAS(&tile_slots[h], 0, (int32_t)idx + 1);
@@ -452,10 +462,9 @@ __global__ void k_insert(LeafList L, GridPtrs g) {
         const int off = upper_off(i, j, k);
         uint64_t* word = g.upper_mask + (size_t)u * kUpperWords + (off >> 6);
         const uint64_t bit = 1ull << (off & 63);
-        // thousands of leaves share each of these bits: look before the atomic, with a device-coherent
-        // read (a stale one would send every leaf into the same-address atomic queue)
-        const uint64_t seen = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (!(seen & bit)) atomicOr((unsigned long long*)word, (unsigned long long)bit);
+        // thousands of leaves share each of these bits: look before the atomic (a stale read only
+        // costs a redundant one)
+        if (!(*word & bit)) atomicOr((unsigned long long*)word, (unsigned long long)bit);
         return;
     }
     const int l = child_of(g.upper_mask + (size_t)u * kUpperWords, g.upper_prefix + (size_t)u * kUpperWords,
