@@ -290,19 +290,20 @@ k_bucket_scatter(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t*
 }
 
 // one workgroup per bucket: the bucket's distinct leaves and their masks, built in LDS
-__global__ void __launch_bounds__(256)
+constexpr int kBucketThreads = 1024;
+__global__ void __launch_bounds__(kBucketThreads)
 k_bucket_leaves(const int4* __restrict__ records, const uint32_t* __restrict__ bucket_start, LeafList L, GridHeader* hdr) {
     __shared__ int32_t rep[kBucketSlots];                 // representative record + 1 (0 = empty)
-    __shared__ unsigned long long mask[kBucketSlots * 8];
-    __shared__ uint32_t wave_sums[4];
+    __shared__ __align__(16) unsigned long long mask[kBucketSlots * 8];
     __shared__ int32_t list_base;
+    static_assert(kBucketSlots == kBucketThreads, "one table slot per thread in the listing step");
     const int tid = threadIdx.x;
-    for (int e = tid; e < kBucketSlots; e += 256) rep[e] = 0;
-    for (int e = tid; e < kBucketSlots * 8; e += 256) mask[e] = 0ull;
+    rep[tid] = 0;
+    for (int e = tid; e < kBucketSlots * 4; e += kBucketThreads) reinterpret_cast<ulonglong2*>(mask)[e] = make_ulonglong2(0ull, 0ull);
     __syncthreads();
     const uint32_t begin = bucket_start[blockIdx.x], end = bucket_start[blockIdx.x + 1];
     bool full = false;
-    for (uint32_t r = begin + tid; r < end; r += 256) {
+    for (uint32_t r = begin + tid; r < end; r += kBucketThreads) {
         const int4 v = records[r];
         const int li = v.x >> 3, lj = v.y >> 3, lk = v.z >> 3;
         uint32_t h = (leaf_hash(v.w, li, lj, lk) >> 12) & (kBucketSlots - 1);   // other bits than the bucket's
@@ -323,43 +324,23 @@ k_bucket_leaves(const int4* __restrict__ records, const uint32_t* __restrict__ b
     }
     if (full) atomicOr(&hdr->overflow, 64);   // more leaves than the table holds: the build falls back to the direct path
     __syncthreads();
-    // append the bucket's leaves to the global list
-    constexpr int kPer = kBucketSlots / 256;
-    uint32_t mine = 0;
-#pragma unroll
-    for (int q = 0; q < kPer; ++q) mine += rep[tid * kPer + q] != 0;
-    uint32_t incl = mine;
-    const int lane = tid & 63, wave = tid >> 6;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(incl, d);
-        if (lane >= d) incl += o;
-    }
-    if (lane == 63) wave_sums[wave] = incl;
+    // append the bucket's leaves to the global list (thread = table slot)
+    const int32_t s = rep[tid];
+    uint32_t total;
+    const uint32_t before = block_exclusive_scan(s != 0 ? 1u : 0u, &total);
+    if (tid == 0) list_base = total ? atomicAdd(&hdr->n_leaf_raw, (int)total) : 0;
     __syncthreads();
-    uint32_t before = incl - mine;
-    for (int w = 0; w < wave; ++w) before += wave_sums[w];
-    if (tid == 255) {
-        const uint32_t total = before + mine;
-        list_base = total ? atomicAdd(&hdr->n_leaf_raw, (int)total) : 0;
-    }
-    __syncthreads();
-    int pos = list_base + (int)before;
+    if (s == 0) return;
+    const int pos = list_base + (int)before;
+    if (pos < L.cap) {
+        const int4 v = records[begin + (uint32_t)(s - 1)];
+        L.key[pos] = make_int4(v.x >> 3, v.y >> 3, v.z >> 3, v.w);
+        L.mask_idx[pos] = pos;
 #pragma unroll
-    for (int q = 0; q < kPer; ++q) {
-        const int slot = tid * kPer + q;
-        const int32_t s = rep[slot];
-        if (s == 0) continue;
-        if (pos < L.cap) {
-            const int4 v = records[begin + (uint32_t)(s - 1)];
-            L.key[pos] = make_int4(v.x >> 3, v.y >> 3, v.z >> 3, v.w);
-            L.mask_idx[pos] = pos;
-#pragma unroll
-            for (int w = 0; w < 8; ++w) L.mask[(size_t)pos * 8 + w] = mask[slot * 8 + w];
-        } else {
-            atomicOr(&hdr->overflow, 4);
-        }
-        ++pos;
+        for (int w = 0; w < 8; w += 2)
+            *reinterpret_cast<ulonglong2*>(&L.mask[(size_t)pos * 8 + w]) = *reinterpret_cast<const ulonglong2*>(&mask[tid * 8 + w]);
+    } else {
+        atomicOr(&hdr->overflow, 4);
     }
 }
 
@@ -836,7 +817,7 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
               k_bucket_scatter<<<n_part_wg, kPartThreads, lds, st>>>(d_ijk, n_rows, d_joff, B, bucket_mask, d_hist, d_totals,
                                                                      d_bucket_start, d_records); }
             { ProfScope ps(kProfBucketLeaves, st);
-              k_bucket_leaves<<<n_buckets, 256, 0, st>>>(d_records, d_bucket_start, L, g->d_hdr); }
+              k_bucket_leaves<<<n_buckets, kBucketThreads, 0, st>>>(d_records, d_bucket_start, L, g->d_hdr); }
         } else {
             const unsigned nb_rows = (unsigned)((n_rows + 255) / 256);
             ProfScope ps(kProfVoxelsToLeaves, st);
