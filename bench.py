@@ -189,9 +189,9 @@ def main():
     torch.cuda.synchronize()
     t_conv_b2b = e0.elapsed_time(e1) / 20
 
-    dom = "k_conv_mfma" if "k_conv_mfma" in kern_ms else "k_conv_scalar"
+    dom = next(k for k in ("k_conv_mfma", "k_conv_gather", "k_conv_scalar") if k in kern_ms)
     dom_ms = kern_ms[dom]
-    if dom == "k_conv_mfma":
+    if dom != "k_conv_scalar":
         peak = MFMA_PEAK_TFLOPS[w.dtype]
         roof = {"kernel": dom, "bound": "mfma", "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": peak,
                 "unit": "TFLOP/s"}

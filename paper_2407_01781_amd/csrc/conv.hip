@@ -614,6 +614,130 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
     }
 }
 
+// ---------------------------------------------------------------------------------- gather kernel
+// For maps whose input rows are used (almost) once -- strided maps, where staging rows in LDS buys no
+// reuse.  One wave owns one column block (32 outputs) x one 64-channel output slice for all
+// offsets: it first resolves the block's (offset, voxel) -> input row table into LDS with independent
+// loads, then walks the offsets, reading each lane's 16-byte B fragments straight from the feature
+// rows (one step ahead) and the packed weights from L2.  No barriers, ~110 registers, so several
+// waves per SIMD hide the gather latency.
+constexpr int kGatherWaves = 4;
+
+template <typename T, bool OUT_F32>
+__global__ void __launch_bounds__(64 * kGatherWaves)
+k_conv_gather(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
+              const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
+              int block_stride, int64_t n_items, const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp,
+              int C_in, int C_out, void* __restrict__ out) {
+    typedef typename Elem<T>::vec8 vec8;
+    __shared__ int32_t row_of[kGatherWaves][kMaxK3Tiled][kGroup];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t item = (int64_t)blockIdx.x * kGatherWaves + wave;
+    if (item >= n_items) return;
+    const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
+    const int slice = (int)(item % nslice);
+    const int64_t tg = item / nslice;
+    const int g = (int)(tg % kGroupsPerTile);
+    const int64_t tile = tg / kGroupsPerTile;
+    const TileHeader* H = tile_hdr + tile;
+    const int w = (g >> kDealShift) & (kTileWaves - 1);
+    const int gi = ((g >> (kDealShift + 2)) << kDealShift) | (g & ((1 << kDealShift) - 1));
+    const uint32_t gm = (uint32_t)uni((int)H->group_mask[g]);
+    const uint32_t wm = (uint32_t)uni((int)H->wave_mask[w]);
+    const int n = lane & 31, h = lane >> 5;
+    const int n_valid = uni(H->n_out);
+
+    // (offset, voxel) -> global input row (-1: none); lane (n, h) resolves every second offset
+    {
+        const int flags = uni(H->flags), win_lo = uni(H->win_lo), win_n = uni(H->win_n);
+        const size_t blk0 = (size_t)tile * block_stride + (uint32_t)uni((int)H->wave_block0[w]);
+        const int32_t* rows = tile_rows + tile * (int64_t)row_stride;
+        int rank = 0;
+        for (uint32_t m = gm; m; m &= m - 1, ++rank) {
+            if ((rank & 1) != h) continue;
+            const int kappa = __ffs(m) - 1;
+            const size_t blk = blk0 + __popc(wm & ((1u << kappa) - 1u));
+            uint32_t id = tile_blocks[blk * kIdBlockElems + n * kGroupsPerWave + gi];
+            if (flags & kTileLdsOffsets) id = (id / kRowBytes == (uint32_t)kRowCap) ? kNoRow : id / kRowBytes;
+            int32_t r = -1;
+            if (id != kNoRow) r = id < (uint32_t)win_n ? win_lo + (int32_t)id : rows[id - (uint32_t)win_n];
+            row_of[wave][rank][n] = r;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // a wave's LDS accesses are processed in order
+    __builtin_amdgcn_wave_barrier();
+
+    f32x16 acc[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
+
+    const int w_kappa_stride = nchunk * nslice * 4 * 64;
+    const vec8* wl = reinterpret_cast<const vec8*>(wp) + lane;
+    const int n_k = __popc(gm);
+    const int n_steps = n_k * nchunk;            // step = (offset rank, chunk), chunk fastest
+    vec8 zero;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) zero[e] = 0;
+    auto fetch = [&](vec8 (&b)[2], vec8 (&wf)[4], int step, uint32_t& rest, int& kappa) {
+        const int rank = step / nchunk, c = step - rank * nchunk;
+        if (c == 0) { kappa = __ffs(rest) - 1; rest &= rest - 1; }
+        const int32_t r = row_of[wave][rank][n];
+        b[0] = zero; b[1] = zero;
+        if (r >= 0) {
+            const uint16_t* src = feat + (int64_t)r * C_in + c * kCinChunk + h * 8;
+            b[0] = *reinterpret_cast<const vec8*>(src);
+            b[1] = *reinterpret_cast<const vec8*>(src + 16);
+        }
+        const vec8* ws = wl + w_frag(nslice, w_kappa_stride, slice, c, kappa);
+#pragma unroll
+        for (int f = 0; f < 4; ++f) wf[f] = ws[f * 64];
+    };
+    vec8 ba[2], bb[2], wa[4], wb[4];
+    uint32_t rest = gm;
+    int kappa = 0;
+    if (n_steps > 0) fetch(ba, wa, 0, rest, kappa);
+    for (int step = 0; step < n_steps; step += 2) {
+        if (step + 1 < n_steps) fetch(bb, wb, step + 1, rest, kappa);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wa[mt * 2 + ks], ba[ks], acc[mt]);
+        if (step + 1 >= n_steps) break;
+        if (step + 2 < n_steps) fetch(ba, wa, step + 2, rest, kappa);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wb[mt * 2 + ks], bb[ks], acc[mt]);
+    }
+
+    const int local = tile_perm[tile * kTileT + g * kGroup + n];
+    if (local >= n_valid) return;
+    const int64_t o = tile * kTileT + local;
+    const int64_t col = (int64_t)slice * kCoutSlice + 32 * h;
+    if (OUT_F32) {
+        float* dst = reinterpret_cast<float*>(out) + o * C_out + col;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4)
+                *reinterpret_cast<f32x4*>(dst + 16 * mt + 4 * v4) =
+                    f32x4{acc[mt][4 * v4], acc[mt][4 * v4 + 1], acc[mt][4 * v4 + 2], acc[mt][4 * v4 + 3]};
+    } else {
+        uint16_t* dst = reinterpret_cast<uint16_t*>(out) + o * C_out + col;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int v8 = 0; v8 < 2; ++v8) {
+                u32x4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pk[e] = Elem<T>::pack2(acc[mt][8 * v8 + 2 * e], acc[mt][8 * v8 + 2 * e + 1]);
+                *reinterpret_cast<u32x4*>(dst + 16 * mt + 8 * v8) = pk;
+            }
+    }
+}
+
 // ---------------------------------------------------------------------------------- scalar path
 // One thread per (output voxel, output channel); fp32 FMA in offset-then-channel order.  Used
 // for fp32 data (true fp32 products) and for channel counts the MFMA tiling does not cover.
@@ -672,6 +796,18 @@ static hipError_t launch_mfma(const fx_kmap* km, const void* feat, const void* w
     return hipGetLastError();
 }
 
+template <typename T, bool OUT_F32>
+static hipError_t launch_gather(const fx_kmap* km, const void* feat, const void* wp, int C_in, int C_out, void* out,
+                                hipStream_t st) {
+    const int64_t n_items = km->n_tiles * (int64_t)kGroupsPerTile * (C_out / kCoutSlice);
+    const unsigned grid = (unsigned)((n_items + kGatherWaves - 1) / kGatherWaves);
+    k_conv_gather<T, OUT_F32><<<grid, 64 * kGatherWaves, 0, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,
+                                                                 km->row_stride, km->d_tile_blocks, km->block_stride,
+                                                                 n_items, (const uint16_t*)feat, (const uint16_t*)wp,
+                                                                 C_in, C_out, out);
+    return hipGetLastError();
+}
+
 }  // namespace fx
 
 using namespace fx;
@@ -711,7 +847,18 @@ extern "C" fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, f
                 (const uint16_t*)d_w, wp, km->K3, C_in, C_out, counters);
         }
         hipError_t e = hipGetLastError();
-        if (e == hipSuccess) {
+        // strided maps use every input row once: the gather kernel; others: the LDS-staged kernel
+        const char* fg = getenv("FVDB_HOTPATH_CONV_GATHER");
+        const bool gather = fg ? fg[0] == '1' : km->stride != 1;
+        if (e == hipSuccess && gather) {
+            ProfScope ps(kProfConvGather, st);
+            if (in_dt == FX_BF16)
+                e = out_f32 ? launch_gather<__bf16, true>(km, d_feat, wp, C_in, C_out, d_out, st)
+                            : launch_gather<__bf16, false>(km, d_feat, wp, C_in, C_out, d_out, st);
+            else
+                e = out_f32 ? launch_gather<_Float16, true>(km, d_feat, wp, C_in, C_out, d_out, st)
+                            : launch_gather<_Float16, false>(km, d_feat, wp, C_in, C_out, d_out, st);
+        } else if (e == hipSuccess) {
             ProfScope ps(kProfConvMfma, st);
             if (in_dt == FX_BF16)
                 e = out_f32 ? launch_mfma<__bf16, true>(km, d_feat, wp, counters, C_in, C_out, d_out, st)

@@ -36,6 +36,16 @@ def test_mfma_path_small_workloads(name, out_f32):
     H.conv_tolerance_check(y, ref, dt, k3, c_in)
 
 
+@pytest.mark.parametrize("name", ["lidar_small", "lidar_small_down", "sheets_small", "indoor_small"])
+@pytest.mark.parametrize("gather", ["0", "1"])
+def test_both_mfma_kernels_serve_every_map(name, gather, monkeypatch):
+    # by default strided maps take the gather kernel and the others the LDS-staged kernel; each kernel
+    # must also be right on the other kind of map
+    monkeypatch.setenv("FVDB_HOTPATH_CONV_GATHER", gather)
+    y, ref, dt, k3, c_in = _run(G.workload(name))
+    H.conv_tolerance_check(y, ref, dt, k3, c_in)
+
+
 def test_mfma_path_deep_channels():
     y, ref, dt, k3, c_in = _run(G.workload("sheets_small"))
     H.conv_tolerance_check(y, ref, dt, k3, c_in)
