@@ -196,16 +196,17 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
     const int n_steps = (n_off + 2) / 3 * 3;
     const u32x2* idp = reinterpret_cast<const u32x2*>(lds_blocks) + (size_t)wave_block0 * kGroup + n;
     uint32_t rest = wave_mask;            // offsets not yet fetched; 31 (which no group has) once exhausted
-    auto pop_kappa = [&]() {
-        if (!rest) return 31;
-        const int k = __ffs(rest) - 1;
+    auto pop_kappa = [&]() {               // branch-free: 31 once the mask is exhausted
+        const int k = __builtin_ctz(rest | 0x80000000u);
         rest &= rest - 1;
         return k;
     };
-    // wave-uniform offset of the weights that step t multiplies (t may lie past this call's end)
+    // wave-uniform offset of the weights that step t multiplies (t may lie past this call's end);
+    // written with masks so that it stays a handful of scalar instructions without branches
     auto w_offset = [&](int t, int k) {
-        if (t < n_off) return w_base + k * w_kappa_stride;
-        return t == n_steps + 1 ? w_after1 : w_after0;
+        const int in = -(int)(t < n_off), last = -(int)(t == n_steps + 1);
+        const int past = (w_after1 & last) | (w_after0 & ~last);
+        return ((w_base + k * w_kappa_stride) & in) | (past & ~in);
     };
     auto fetch_w = [&](vec8 (&w)[4], int off) {   // [mtile*2 + kstep]; uniform base + 32-bit lane offset
         const unsigned char* ws = reinterpret_cast<const unsigned char*>(wbase0 + off);
@@ -249,6 +250,10 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
     if (wb_at != w_offset(1, q1)) fetch_w(wb, w_offset(1, q1));
     wa_at = w_after0;
     wb_at = w_after1;
+    // Both sets were requested at least two steps ago (or, rarely, just now).  Waiting for them here
+    // costs nothing in the common case and tells the compiler so: without it the loop's wait counts
+    // are computed for the rare case and every step also waits for the weights of the next one.
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), other counters untouched
     u32x2 idn = idp[min(1, n_off - 1) * kGroup];   // ids of step 1
     {
         const u32x2 id0 = idp[0];
