@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="lidar1m", choices=sorted(WORKLOAD_DESC))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-rows", type=int, default=300000)
+    ap.add_argument("--cpu-sample-rows", type=int, default=1000000)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain elementwise copy kernel of known size (256 MiB read + 256 MiB "
                          "written), the yardstick for the FETCH_SIZE / WRITE_SIZE counters")
