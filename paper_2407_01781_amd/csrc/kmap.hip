@@ -214,8 +214,8 @@ struct PackLds {
             int32_t rec_hash[kRecHashSlots];  // leaf id or -1
             uint16_t slot_rec[kRecHashSlots]; // hash slot -> record, 0xFFFF: not staged
             int32_t rec_id[kMaxRecs];
-            uint64_t rec_mask[kMaxRecs * 8];  // mBitMask of Listing 1
-            int32_t rec_base[kMaxRecs * 8];   // per mask word: mOffset + the prefix-sum field that precedes it
+            uint64_t rec_mask[(kMaxRecs + 1) * 8];  // mBitMask of Listing 1; record kMaxRecs stays all zero
+            int32_t rec_base[(kMaxRecs + 1) * 8];   // per mask word: mOffset + the prefix-sum field that precedes it
         } look;
         PackScratch s;
     } u;
@@ -339,6 +339,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
         L.n_halo = 0; L.n_blocks = 0; L.n_pair_blocks = 0; L.overflow = 0; L.n_rec = 0;
     }
     for (int e = tid; e < kRecHashSlots; e += kPackThreads) { L.u.look.rec_hash[e] = -1; L.u.look.slot_rec[e] = 0xFFFF; }
+    if (tid < 8) { L.u.look.rec_mask[kMaxRecs * 8 + tid] = 0; L.u.look.rec_base[kMaxRecs * 8 + tid] = 0; }
     __syncthreads();
 
     // ---- lookups: one thread per output voxel.  The thread finds its leaf (binary search over the
@@ -445,30 +446,31 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
                     for (int c = 0; c < K; ++c, ++kappa) {
                         const int qk = stride * pk + D0 + c;
                         const int slot = sij + ((qk >> 3) - bk);
+                        // The common case runs without a branch: a missing neighbour leaf reads the all-zero
+                        // record kMaxRecs, whose mask has no bit to find.
                         const int v = row_in_lds ? lds_row[slot] : -2 - nbr_row[slot];   // -2 - (-1) = -1
-                        int res = -1;
-                        if (v != -1) {
-                            uint64_t w;
-                            int32_t base;
-                            if (v >= 0) {                   // staged record
-                                w = L.u.look.rec_mask[v * 8 + n2];
-                                base = L.u.look.rec_base[v * 8 + n2];
-                            } else {                        // three independent loads: one memory round trip
-                                const fx_leaf* nl = tin.leaf + (-2 - v);
-                                w = nl->mask[n2];
-                                const uint64_t npre = nl->prefix;
-                                base = (int32_t)nl->offset + (n2 ? (int32_t)((npre >> (9 * (n2 - 1))) & 511) : 0);
-                            }
-                            const uint64_t qb = 1ull << (bj8 | (qk & 7));
-                            if (w & qb) res = base + __popcll(w & (qb - 1));
+                        const int rec = v >= 0 ? v : kMaxRecs;
+                        uint64_t w = L.u.look.rec_mask[rec * 8 + n2];
+                        int32_t base = L.u.look.rec_base[rec * 8 + n2];
+                        if (__builtin_expect(v <= -2, 0)) {   // record not staged: three independent global loads
+                            const fx_leaf* nl = tin.leaf + (-2 - v);
+                            w = nl->mask[n2];
+                            const uint64_t npre = nl->prefix;
+                            base = (int32_t)nl->offset + (n2 ? (int32_t)((npre >> (9 * (n2 - 1))) & 511) : 0);
                         }
+                        const int bit6 = bj8 | (qk & 7);
+                        const uint32_t wlo = (uint32_t)w, whi = (uint32_t)(w >> 32);
+                        // bits below bit6, per half: all of the low half once bit6 >= 32
+                        const uint32_t mlo = bit6 >= 32 ? 0xFFFFFFFFu : ((1u << bit6) - 1u);
+                        const uint32_t mhi = bit6 >= 32 ? ((1u << (bit6 - 32)) - 1u) : 0u;
+                        const bool present = (((bit6 >= 32 ? whi : wlo) >> (bit6 & 31)) & 1u) != 0;
+                        const int idx = base + __popc(wlo & mlo) + __popc(whi & mhi);
                         // entry encoding from here on: -1 none; -2 - id: row win_lo + id of the window;
                         // >= 0: a row outside the window, not yet entered in the halo table
-                        if (res >= 0) {
-                            mask |= 1u << kappa;
-                            if (res >= w_lo && res < w_lo + w_n) res = -2 - (res - w_lo);
-                            else hmask |= 1u << kappa;
-                        }
+                        const bool in_win = (uint32_t)(idx - w_lo) < (uint32_t)w_n;
+                        const int res = present ? (in_win ? -2 - (idx - w_lo) : idx) : -1;
+                        mask |= (uint32_t)present << kappa;
+                        hmask |= (uint32_t)(present && !in_win) << kappa;
                         my_nb[kappa] = res;
                     }
                 }
