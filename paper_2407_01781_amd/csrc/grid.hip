@@ -182,8 +182,10 @@ __device__ __forceinline__ PartRow load_part_row(const int32_t* __restrict__ ijk
 // rows per (bucket, workgroup): hist[bucket * n_wg + wg]
 __global__ void __launch_bounds__(kPartThreads)
 k_bucket_count(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff, int B,
-               uint32_t bucket_mask, uint32_t* __restrict__ hist) {
+               uint32_t bucket_mask, uint32_t* __restrict__ hist, int32_t* __restrict__ tile_slots) {
     __shared__ uint32_t cnt[kMaxBuckets];
+    // first launch of the build: also clears the root-tile table (used three launches later)
+    for (int e = blockIdx.x * kPartThreads + threadIdx.x; e < kTileHashSlots; e += gridDim.x * kPartThreads) tile_slots[e] = 0;
     for (uint32_t e = threadIdx.x; e <= bucket_mask; e += kPartThreads) cnt[e] = 0;
     __syncthreads();
     const int64_t r0 = (int64_t)blockIdx.x * kPartChunk + threadIdx.x;
@@ -796,9 +798,8 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     {
         ProfScope ps(kProfMemset, st);
         FX_TRY_OR_FAIL(hipMemsetAsync(g->buf, 0, g->buf_bytes, st));
-        // the partitioned path writes every mask it lists, so only the tile table needs clearing there
-        if (partition) FX_TRY_OR_FAIL(hipMemsetAsync(d_tile_slots, 0, sizeof(int32_t) * kTileHashSlots, st));
-        else FX_TRY_OR_FAIL(hipMemsetAsync(scratch, 0, clear_bytes, st));
+        // the partitioned path writes every mask it lists and clears the tile table in its first kernel
+        if (!partition) FX_TRY_OR_FAIL(hipMemsetAsync(scratch, 0, clear_bytes, st));
     }
     FX_HT("grid: memsets");
     const GridPtrs q = ptrs_of(g);
@@ -810,7 +811,7 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
             FX_TRY_OR_FAIL(hipFuncSetAttribute((const void*)k_bucket_scatter, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                (int)lds));
             { ProfScope ps(kProfBucketCount, st);
-              k_bucket_count<<<n_part_wg, kPartThreads, 0, st>>>(d_ijk, n_rows, d_joff, B, bucket_mask, d_hist); }
+              k_bucket_count<<<n_part_wg, kPartThreads, 0, st>>>(d_ijk, n_rows, d_joff, B, bucket_mask, d_hist, d_tile_slots); }
             { ProfScope ps(kProfBucketScan, st);
               k_bucket_scan<<<(n_buckets * 64 + 255) / 256, 256, 0, st>>>(d_hist, n_part_wg, n_buckets, d_totals); }
             { ProfScope ps(kProfBucketScatter, st);

@@ -91,12 +91,14 @@ __device__ __forceinline__ int lookup_entry(const NbLeafLds& lds, int oi, int oj
 // its leaf, that the tile's first voxel lies in this leaf.
 template <int K>
 __global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int64_t n_out, int32_t* __restrict__ nbr,
-                                 int32_t* __restrict__ tile_first_leaf) {
+                                 int32_t* __restrict__ tile_first_leaf, unsigned long long* __restrict__ stats) {
     constexpr int D0 = delta_min(K);
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (int64_t)tout.n_leaf * 27) return;
     const int f = (int)(e / 27), slot = (int)(e - (int64_t)f * 27);
     const fx_leaf* lf = tout.leaf + f;
+    if (e == 0)                          // the build's statistics (this is its first launch)
+        for (int q = 0; q < 4 + K * K * K; ++q) stats[q] = 0ull;
     if (slot == 0) {
         const int64_t begin = lf->offset, end = f + 1 < tout.n_leaf ? tout.leaf[f + 1].offset : n_out;
         for (int64_t t = (begin + kTileT - 1) / kTileT; t * kTileT < end; ++t) tile_first_leaf[t] = f;
@@ -803,7 +805,8 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     int32_t* d_leaf_nbr = (int32_t*)(p + o_ln);
     int32_t* d_tile_first = (int32_t*)(p + o_tf);
 
-    hipError_t e = hipMemsetAsync(km->d_stats, 0, sizeof(int64_t) * (size_t)(4 + km->K3), st);
+    hipError_t e = hipSuccess;
+    if (km->n_tiles == 0) e = hipMemsetAsync(km->d_stats, 0, sizeof(int64_t) * (size_t)(4 + km->K3), st);
     if (e == hipSuccess && km->n_tiles > 0) {
         unsigned long long* stats = (unsigned long long*)km->d_stats;
         const size_t lds = sizeof(PackLds);
@@ -813,9 +816,9 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
             ProfScope ps(kProfLeafNeighbors, st);
             const int64_t ne = (int64_t)gout->hdr.n_leaf * 27;
             const unsigned nbk = (unsigned)((ne + 255) / 256);
-            if (K == 1) k_leaf_neighbors<1><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
-            else if (K == 2) k_leaf_neighbors<2><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
-            else k_leaf_neighbors<3><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
+            if (K == 1) k_leaf_neighbors<1><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, stats);
+            else if (K == 2) k_leaf_neighbors<2><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, stats);
+            else k_leaf_neighbors<3><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, stats);
         }
         ProfScope ps(kProfBuildTiles, st);
 #define FX_TILES(KV, SUBMV)                                                                                    \
