@@ -94,7 +94,7 @@ def main():
         pmc_summary(args.pmc_summary)
         return
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by grid of the batch; see DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU (the path would shard by grid of the batch, one grid per GPU, with no exchange in the forward pass); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
 

@@ -644,6 +644,20 @@ __global__ void __launch_bounds__(kScanThreads) k_scan_leaves_apply(fx_leaf* __r
         }
 }
 
+// The build's one read-back (Sec. 3.3 step 10): counts and per-grid voxel bases, written by the
+// device straight into pinned host memory -- one tiny launch instead of two copy-engine transfers.
+// The last word written is a ticket the host polls for, which returns sooner than a stream wait.
+__global__ void k_publish(const GridHeader* __restrict__ hdr, const int64_t* __restrict__ vox_base, int B,
+                          unsigned char* __restrict__ host, int32_t* __restrict__ host_ticket, int32_t ticket) {
+    const int t = threadIdx.x;
+    constexpr int kHdrWords = (int)(sizeof(GridHeader) / sizeof(int32_t));
+    if (t < kHdrWords) reinterpret_cast<int32_t*>(host)[t] = reinterpret_cast<const int32_t*>(hdr)[t];
+    for (int b = t; b <= B; b += blockDim.x) reinterpret_cast<int64_t*>(host + sizeof(GridHeader))[b] = vox_base[b];
+    __threadfence_system();
+    __syncthreads();
+    if (t == 0) __hip_atomic_store(host_ticket, ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 // ---------------------------------------------------------------------------------- queries
 // one wave per leaf: lane = bit of the current mask word (ballot-free: every lane tests its bit)
 __global__ void k_grid_ijk(TreeView t, int32_t* __restrict__ ijk_out, int32_t* __restrict__ jidx_out, int shift) {
@@ -852,12 +866,27 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     const size_t hdr_bytes = sizeof(GridHeader);
     const size_t vb_bytes = sizeof(int64_t) * ((size_t)B + 1);
     void* stage = nullptr;
-    rc = host_staging(&stage, hdr_bytes + vb_bytes);
+    const size_t ticket_off = align_up(hdr_bytes + vb_bytes, 64);
+    rc = host_staging(&stage, ticket_off + 64);
     if (rc != FX_OK) return fail(rc);
-    FX_TRY_OR_FAIL(hipMemcpyAsync(stage, g->d_hdr, hdr_bytes, hipMemcpyDeviceToHost, st));
-    FX_TRY_OR_FAIL(hipMemcpyAsync((char*)stage + hdr_bytes, g->d_vox_base, vb_bytes, hipMemcpyDeviceToHost, st));
+    static thread_local int32_t next_ticket = 0;
+    const int32_t ticket = ++next_ticket == 0 ? ++next_ticket : next_ticket;   // never 0
+    volatile int32_t* h_ticket = reinterpret_cast<volatile int32_t*>((char*)stage + ticket_off);
+    *h_ticket = 0;
+    k_publish<<<1, 256, 0, st>>>(g->d_hdr, g->d_vox_base, B, (unsigned char*)stage, (int32_t*)h_ticket, ticket);
+    FX_TRY_OR_FAIL(hipGetLastError());
     FX_HT("grid: d2h enqueue");
-    FX_TRY_OR_FAIL(hipStreamSynchronize(st));
+    {
+        // poll the ticket for a while (a few hundred microseconds at most for the sizes where latency
+        // matters), then fall back to waiting for the stream, which also reports any device error
+        bool seen = false;
+        for (int spin = 0; spin < 200000 && !seen; ++spin) {
+            seen = (*h_ticket == ticket);
+            if (!seen) __builtin_ia32_pause();
+        }
+        if (!seen) FX_TRY_OR_FAIL(hipStreamSynchronize(st));
+        std::atomic_thread_fence(std::memory_order_acquire);
+    }
     FX_HT("grid: sync");
     memcpy(&g->hdr, stage, hdr_bytes);
     memcpy(g->h_vox_base, (char*)stage + hdr_bytes, vb_bytes);
