@@ -355,40 +355,35 @@ __device__ __forceinline__ bool leaf_at(const LeafList& L, const GridHeader* hdr
 
 // ---------------------------------------------------------------------------------- root tiles
 // Distinct (grid, tile) pairs of the leaves go into a small open-addressing table whose slots
-// hold a representative leaf (+1; 0 = empty).
-__global__ void k_find_tiles(LeafList L, int32_t* __restrict__ tile_slots, int32_t* __restrict__ rep_leaves,
-                             GridHeader* hdr) {
-    if (hdr->overflow) return;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int4 key;
-    if (!leaf_at(L, hdr, idx, &key)) return;
+// hold a representative leaf (+1; 0 = empty).  Called by all lanes of a wave together (`has`:
+// this lane holds leaf `idx` with key `key`).
+__device__ __forceinline__ void find_tile_item(const LeafList& L, GridHeader* hdr, int idx, bool has, const int4& key,
+                                               int32_t* __restrict__ tile_slots, int32_t* __restrict__ rep_leaves) {
     const int b = key.w, ti = key.x >> 9, tj = key.y >> 9, tk = key.z >> 9;   // leaf coordinate >> 9 = voxel >> 12
     // one lane per distinct tile of the wave inserts (accesses to one address from all over the
     // device queue up at memory): repeatedly, the first lane still waiting becomes the speaker for
     // all lanes with its tile
-    {
-        const int lane = threadIdx.x & 63;
-        bool waiting = true, speaker = false;
-        for (int round = 0; round < 64; ++round) {
-            const uint64_t pending = __ballot(waiting);
-            if (!pending) break;
-            const int leader = __ffsll((long long)pending) - 1;
-            const int lb = __shfl(b, leader), li = __shfl(ti, leader), lj = __shfl(tj, leader), lk = __shfl(tk, leader);
-            if (waiting && lb == b && li == ti && lj == tj && lk == tk) { waiting = false; speaker = (lane == leader); }
-        }
-        if (!speaker) return;
+    const int lane = threadIdx.x & 63;
+    bool waiting = has, speaker = false;
+    for (int round = 0; round < 64; ++round) {
+        const uint64_t pending = __ballot(waiting);
+        if (!pending) break;
+        const int leader = __ffsll((long long)pending) - 1;
+        const int lb = __shfl(b, leader), li = __shfl(ti, leader), lj = __shfl(tj, leader), lk = __shfl(tk, leader);
+        if (waiting && lb == b && li == ti && lj == tj && lk == tk) { waiting = false; speaker = (lane == leader); }
     }
+    if (!speaker) return;
     uint32_t h = mix32(mix32(mix32(mix32(0x811C9DC5u, (uint32_t)b), (uint32_t)ti), (uint32_t)tj), (uint32_t)tk);
     h &= (kTileHashSlots - 1);
     for (int probe = 0; probe < kTileHashSlots; ++probe) {
         // device-coherent read: once a tile is in, nobody else reaches the compare-and-swap
         int32_t s = __hip_atomic_load(&tile_slots[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (s == 0) {
-            if (hdr->n_tiles_raw > kMaxTiles) break;  // over the limit: reported by the ranking kernel
-            const int32_t old = atomicCAS(&tile_slots[h], 0, (int32_t)idx + 1);
+            if (hdr->n_tiles_raw > kMaxTiles) break;  // over the limit: reported by the ranking step
+            const int32_t old = atomicCAS(&tile_slots[h], 0, idx + 1);
             if (old == 0) {
                 const int pos = atomicAdd(&hdr->n_tiles_raw, 1);
-                if (pos < kMaxTiles) rep_leaves[pos] = (int32_t)idx;
+                if (pos < kMaxTiles) rep_leaves[pos] = idx;
                 break;
             }
             s = old;
@@ -399,13 +394,22 @@ __global__ void k_find_tiles(LeafList L, int32_t* __restrict__ tile_slots, int32
     }
 }
 
+__global__ void k_find_tiles(LeafList L, int32_t* __restrict__ tile_slots, int32_t* __restrict__ rep_leaves,
+                             GridHeader* hdr) {
+    if (hdr->overflow) return;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int4 key = make_int4(0, 0, 0, 0);
+    const bool has = leaf_at(L, hdr, idx, &key);
+    find_tile_item(L, hdr, (int)idx, has, key, tile_slots, rep_leaves);
+}
+
 // Rank every tile among all tiles by (grid, signed tile i, j, k): its rank is its upper-node id
 // (the run index M of Sec. 3.3 step 5).  O(T^2) comparisons; T is tiny for real scenes.
-__global__ void k_rank_tiles(LeafList L, const int32_t* __restrict__ rep_leaves, GridPtrs g) {
-    if (g.hdr->overflow) return;
+// `t` = global thread number of the launch.
+__device__ __forceinline__ void rank_tile_item(const LeafList& L, const int32_t* __restrict__ rep_leaves, const GridPtrs& g,
+                                               int t, int t_stride) {
     const int raw = g.hdr->n_tiles_raw;
     const int T = raw < kMaxTiles ? raw : kMaxTiles;
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t == 0) {
         int ov = 0;
         if (raw > kMaxTiles) ov |= 8;
@@ -413,17 +417,24 @@ __global__ void k_rank_tiles(LeafList L, const int32_t* __restrict__ rep_leaves,
         g.hdr->n_upper = T;
         if (ov) atomicOr(&g.hdr->overflow, ov);
     }
-    if (t >= T || T > g.cap_upper) return;
-    const int4 me = L.key[rep_leaves[t]];
-    const uint64_t key = tile_key(me.x << 3, me.y << 3, me.z << 3);
-    int rank = 0;
-    for (int o = 0; o < T; ++o) {
-        const int4 ot = L.key[rep_leaves[o]];
-        const uint64_t ko = tile_key(ot.x << 3, ot.y << 3, ot.z << 3);
-        rank += (ot.w < me.w) || (ot.w == me.w && ko < key);
+    if (T > g.cap_upper) return;
+    for (; t < T; t += t_stride) {
+        const int4 me = L.key[rep_leaves[t]];
+        const uint64_t key = tile_key(me.x << 3, me.y << 3, me.z << 3);
+        int rank = 0;
+        for (int o = 0; o < T; ++o) {
+            const int4 ot = L.key[rep_leaves[o]];
+            const uint64_t ko = tile_key(ot.x << 3, ot.y << 3, ot.z << 3);
+            rank += (ot.w < me.w) || (ot.w == me.w && ko < key);
+        }
+        g.root_key[rank] = key;
+        g.root_batch[rank] = me.w;
     }
-    g.root_key[rank] = key;
-    g.root_batch[rank] = me.w;
+}
+
+__global__ void k_rank_tiles(LeafList L, const int32_t* __restrict__ rep_leaves, GridPtrs g) {
+    if (g.hdr->overflow) return;
+    rank_tile_item(L, rep_leaves, g, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
 }
 
 // ---------------------------------------------------------------------------------- leaves -> tree
@@ -432,11 +443,7 @@ __global__ void k_rank_tiles(LeafList L, const int32_t* __restrict__ rep_leaves,
 // LEVEL 1: leaf bit in the lower node's child mask         (step 11.3)
 // LEVEL 2: the leaf's final id is known: move its mask into the leaf record
 template <int LEVEL>
-__global__ void k_insert(LeafList L, GridPtrs g) {
-    if (g.hdr->overflow) return;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int4 key;
-    if (!leaf_at(L, g.hdr, idx, &key)) return;
+__device__ __forceinline__ void insert_item(const LeafList& L, const GridPtrs& g, int idx, const int4& key) {
     const int b = key.w;
     const int i = key.x << 3, j = key.y << 3, k = key.z << 3;   // the leaf's origin
     const int u = find_upper(g.root_key, g.root_batch, g.hdr->n_upper, b, tile_key(i, j, k));
@@ -452,7 +459,7 @@ __global__ void k_insert(LeafList L, GridPtrs g) {
     }
     const int l = child_of(g.upper_mask + (size_t)u * kUpperWords, g.upper_prefix + (size_t)u * kUpperWords,
                            upper_off(i, j, k));
-    if (l < 0) return;
+    if (l < 0 || l >= g.cap_lower) return;
     if (LEVEL == 1) {
         const int off = lower_off(i, j, k);
         uint64_t* word = g.lower_mask + (size_t)l * kLowerWords + (off >> 6);
@@ -461,7 +468,7 @@ __global__ void k_insert(LeafList L, GridPtrs g) {
     }
     const int f = child_of(g.lower_mask + (size_t)l * kLowerWords, g.lower_prefix + (size_t)l * kLowerWords,
                            lower_off(i, j, k));
-    if (f < 0) return;
+    if (f < 0 || f >= g.cap_leaf) return;
     fx_leaf* lf = &g.leaf[f];
     const uint64_t* src = L.mask + (size_t)L.mask_idx[idx] * 8;
 #pragma unroll
@@ -470,6 +477,15 @@ __global__ void k_insert(LeafList L, GridPtrs g) {
     lf->origin[1] = j;
     lf->origin[2] = k;
     lf->batch = b;
+}
+
+template <int LEVEL>
+__global__ void k_insert(LeafList L, GridPtrs g) {
+    if (g.hdr->overflow) return;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int4 key;
+    if (!leaf_at(L, g.hdr, idx, &key)) return;
+    insert_item<LEVEL>(L, g, (int)idx, key);
 }
 
 // ---------------------------------------------------------------------------------- popcount scans
@@ -538,6 +554,7 @@ __device__ __forceinline__ void block_sums_before(const uint32_t* __restrict__ b
     __syncthreads();
     *before = acc[0];
     *all = acc[1];
+    __syncthreads();   // the next call may clear the sums
 }
 
 // phase B: every block adds the totals of the blocks before it; block 0 publishes the grand total
