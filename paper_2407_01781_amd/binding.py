@@ -69,6 +69,7 @@ def _load():
     L.fx_kmap_destroy.argtypes = [vp]
     L.fx_sparse_conv_fwd.restype = C.c_int
     L.fx_sparse_conv_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
+    L.fx_release_cached_memory.restype = None
     L.fx_profile_enable.argtypes = [C.c_int]
     L.fx_profile_slot_count.restype = C.c_int
     L.fx_profile_slot_name.restype = C.c_char_p
@@ -215,6 +216,11 @@ class KernelMap:
         out = torch.empty((self.n_out, self.k3), dtype=torch.int32, device="cuda")
         _check(lib.fx_kmap_dense(self._h, _ptr(out), _stream()))
         return out
+
+
+def release_cached_memory() -> None:
+    """Return the device blocks the library keeps for reuse to the driver (waits for the device)."""
+    lib.fx_release_cached_memory()
 
 
 def build_kernel_map(g_in: IndexGrid, kernel_size: int, stride: int) -> KernelMap:

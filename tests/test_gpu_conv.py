@@ -58,6 +58,24 @@ def test_channel_shapes_mfma_and_scalar(dtype, c_in, c_out):
     H.conv_tolerance_check(y, ref, dt, k3, ci)
 
 
+@pytest.mark.parametrize("K,dtype,c_in,c_out", [(1, "bf16", 64, 64), (1, "f16", 32, 128), (5, "bf16", 16, 16),
+                                               (5, "f32", 8, 8)])
+def test_pointwise_and_5x5x5_kernels(K, dtype, c_in, c_out):
+    # K = 1 runs the tiled MFMA path with a single offset (a per-voxel GEMM); K = 5 (125 offsets)
+    # keeps a dense map and takes the scalar path
+    pts = np.random.default_rng(3).integers(-20, 40, size=(6000, 3)).astype(np.int32)
+    g, og = H.both_grids(pts, np.array([[0, 2500], [2500, 6000]], np.int64))
+    km = fx.build_kernel_map(g, K, 1)
+    feat, wt = G.features_and_weights(17, og.num_voxels, c_in, c_out, K ** 3, dtype)
+    y = fx.sparse_conv_fwd(km, H.to_device_storage(feat, dtype), H.to_device_storage(wt, dtype))
+    ref = O.conv(og, og, K, 1, feat, wt)
+    H.conv_tolerance_check(y.float().cpu().numpy(), ref, dtype, K ** 3, c_in)
+    if K == 1:
+        # K = 1 is out = in . W[0] (closed form, independent of the map code)
+        closed = feat.astype(np.float64) @ wt[0].astype(np.float64)
+        H.conv_tolerance_check(y.float().cpu().numpy(), closed, dtype, 1, c_in)
+
+
 def test_identity_tap_is_bit_exact_in_bf16():
     w = G.workload("lidar_small")
     ijk, jo = w.jagged_ijk()

@@ -6,6 +6,7 @@ import pytest
 import torch
 
 import gpu_common as H
+import paper_2407_01781_amd.binding as B
 from oracle import cpu_oracle as O
 from workloads import generators as G
 
@@ -127,3 +128,16 @@ def test_full_size_grid_properties_and_sampled_indices(name):
     ijk, jo = w.jagged_ijk()
     g, og = H.both_grids(ijk, jo)
     H.check_grid(g, og)
+
+
+def test_released_device_blocks_are_reused_and_can_be_returned():
+    # steady-state calls take their device memory from the library's cache of released blocks;
+    # returning the cache to the driver must leave later calls working
+    pts = _cloud(51, 30000, 0, 200)
+    jo = np.array([[0, pts.shape[0]]])
+    g1, og = H.both_grids(pts, jo)
+    t1 = g1.leaf_table().tobytes()
+    del g1
+    B.release_cached_memory()
+    g2, _ = H.both_grids(pts, jo)
+    assert g2.leaf_table().tobytes() == t1 == og.leaf_table().tobytes()
