@@ -14,7 +14,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfvdb_hotpath.so")
+LIB_PATH = os.environ.get("FVDB_HOTPATH_LIB") or os.path.join(_HERE, "libfvdb_hotpath.so")   # override: a development build
 
 FX_OK = 0
 DTYPES = {"f32": 0, "f16": 1, "bf16": 2}

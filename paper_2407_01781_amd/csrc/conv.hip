@@ -168,6 +168,11 @@ __device__ __forceinline__ Item item_of(const MetaSlot& M, int64_t work, int nsl
     return I;
 }
 
+// word e of a lane's id entry (a scalar when a wave has two groups, a vector otherwise)
+__device__ __forceinline__ uint32_t id_word(uint32_t v, int) { return v; }
+template <typename V>
+__device__ __forceinline__ uint32_t id_word(const V& v, int e) { return v[e]; }
+
 // Loop over the stencil offsets a wave needs for one 32-channel chunk.  Software pipeline per
 // offset step i: the weights of step i+2, the B fragments of step i+1 and the ids of step i+2
 // are fetched while the MFMAs of step i are issued (2 m-tiles x 2 k-steps per present column
@@ -194,7 +199,8 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
     constexpr int NG = kGroupsPerWave;
     const int n_off = __popc(wave_mask);
     const int n_steps = (n_off + 2) / 3 * 3;
-    const u32x2* idp = reinterpret_cast<const u32x2*>(lds_blocks) + (size_t)wave_block0 * kGroup + n;
+    typedef __attribute__((ext_vector_type(NG / 2))) uint32_t IdVec;    // a lane's ids of one block: NG x u16
+    const IdVec* idp = reinterpret_cast<const IdVec*>(lds_blocks) + (size_t)wave_block0 * kGroup + n;
     uint32_t rest = wave_mask;            // offsets not yet fetched; 31 (which no group has) once exhausted
     auto pop_kappa = [&]() {               // branch-free: 31 once the mask is exhausted
         const int k = __builtin_ctz(rest | 0x80000000u);
@@ -215,14 +221,14 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
     };
     const uint32_t hsel = (uint32_t)h << 4;
     // B fragments (16 channels x 32 voxels, two k-steps) of column block gi for offset kappa
-    auto fetch_b = [&](vec8 (&bf)[2], const u32x2& ids, int gi, int kappa) {
+    auto fetch_b = [&](vec8 (&bf)[2], const IdVec& ids, int gi, int kappa) {
         // In the LDS-only variant the reads are issued for every group: an absent group's ids all
         // point at the zero row (one broadcast address).  With the reads unconditional every path
         // issues the same number of LDS instructions and the compiler waits for exactly the
         // fragments it needs; behind uniform branches it assumed the worst and drained the freshly
         // issued prefetch before every multiply.
         if (GENERAL && !((gmask[gi] >> kappa) & 1u)) return;
-        const uint32_t id = (ids[gi >> 1] >> (16 * (gi & 1))) & 0xFFFFu;
+        const uint32_t id = (id_word(ids, gi >> 1) >> (16 * (gi & 1))) & 0xFFFFu;
         if (GENERAL) {
             const bool staged = id < (uint32_t)n_staged;
             const int row = staged ? (int)id : kRowCap;
@@ -254,9 +260,9 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
     // costs nothing in the common case and tells the compiler so: without it the loop's wait counts
     // are computed for the rare case and every step also waits for the weights of the next one.
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), other counters untouched
-    u32x2 idn = idp[min(1, n_off - 1) * kGroup];   // ids of step 1
+    IdVec idn = idp[min(1, n_off - 1) * kGroup];   // ids of step 1
     {
-        const u32x2 id0 = idp[0];
+        const IdVec id0 = idp[0];
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi) fetch_b(bf[gi], id0, gi, q0);
     }
@@ -264,7 +270,7 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
     // multiply the current offset and fetch the group's fragments for the next one
     auto step = [&](const vec8 (&wcur)[4], vec8 (&wload)[4]) {
         fetch_w(wload, w_offset(it + 2, q2));
-        const u32x2 ids_next = idn;
+        const IdVec ids_next = idn;
         idn = idp[min(it + 2, n_off - 1) * kGroup];
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi) {
@@ -645,8 +651,7 @@ k_conv_gather(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restric
     const int g = (int)(tg % kGroupsPerTile);
     const int64_t tile = tg / kGroupsPerTile;
     const TileHeader* H = tile_hdr + tile;
-    const int w = (g >> kDealShift) & (kTileWaves - 1);
-    const int gi = ((g >> (kDealShift + 2)) << kDealShift) | (g & ((1 << kDealShift) - 1));
+    const int w = tile_wave_of(g), gi = tile_slot_of(g);
     const uint32_t gm = (uint32_t)uni((int)H->group_mask[g]);
     const uint32_t wm = (uint32_t)uni((int)H->wave_mask[w]);
     const int n = lane & 31, h = lane >> 5;

@@ -29,7 +29,12 @@ namespace fx {
 constexpr int kTileT = 512;                 // outputs per tile
 constexpr int kGroup = 32;                  // outputs per MFMA column block (32x32x16 MFMA)
 constexpr int kGroupsPerTile = kTileT / kGroup;
-constexpr int kTileWaves = 4;               // waves of the convolution workgroup
+#ifndef FX_TILE_WAVES
+#define FX_TILE_WAVES 4
+#endif
+constexpr int kTileWaves = FX_TILE_WAVES;   // consumer waves of the convolution workgroup (4 or 8)
+constexpr int kTileWavesLog2 = kTileWaves == 8 ? 3 : 2;
+static_assert(kTileWaves == (1 << kTileWavesLog2), "4 or 8 consumer waves");
 constexpr int kGroupsPerWave = kGroupsPerTile / kTileWaves;
 constexpr int kDealShift = 0;               // runs of 2^kDealShift adjacent groups go to the same wave
 constexpr int kMaxK3Tiled = 27;             // offsets supported by the tiled form
@@ -45,11 +50,16 @@ constexpr int kCinChunk = 32;               // input channels staged in LDS at a
 constexpr int kRowBytes = kCinChunk * 2;
 constexpr int kRowCap = 792;                // LDS rows per tile
 __host__ __device__ constexpr uint32_t lds_row_code(uint32_t row) { return row * kRowBytes | (((row >> 2) & 3u) << 4); }
-constexpr int kIdBlockElems = kGroup * kGroupsPerWave;   // 128 ids = 256 bytes
+constexpr int kIdBlockElems = kGroup * kGroupsPerWave;   // ids of one block (2 bytes each)
 
 // group (in mask-sorted order) that wave `w` handles in its slot `gi`
 __host__ __device__ constexpr int tile_group_of(int w, int gi) {
-    return ((gi >> kDealShift) << (kDealShift + 2)) | (w << kDealShift) | (gi & ((1 << kDealShift) - 1));
+    return ((gi >> kDealShift) << (kDealShift + kTileWavesLog2)) | (w << kDealShift) | (gi & ((1 << kDealShift) - 1));
+}
+// and back: the wave and the wave's slot of group g
+__host__ __device__ constexpr int tile_wave_of(int g) { return (g >> kDealShift) & (kTileWaves - 1); }
+__host__ __device__ constexpr int tile_slot_of(int g) {
+    return ((g >> (kDealShift + kTileWavesLog2)) << kDealShift) | (g & ((1 << kDealShift) - 1));
 }
 
 struct TileHeader {

@@ -603,11 +603,13 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     }
 
     FX_KSTAMP(6);
-    // ---- id blocks: thread (wave w, voxel column n, quarter q) fills the 8-byte entries
-    // [voxel n][4 group slots] of every fourth block of wave w, so that a block is written as 32
-    // consecutive 8-byte stores
+    // ---- id blocks: thread (wave w, voxel column n, share q) fills the entries [voxel n][group
+    // slots] of every kQuarters-th block of wave w, so that a block is written as 32 consecutive
+    // entries
     {
-        const int w = tid >> 7, q = (tid >> 5) & 3, n = tid & 31;
+        constexpr int kQuarters = kPackThreads / (kTileWaves * kGroup);      // threads per (wave, voxel column)
+        constexpr int kEntryWords = kGroupsPerWave / 2;                     // 32-bit words per entry
+        const int w = tid / (kQuarters * kGroup), q = (tid / kGroup) % kQuarters, n = tid % kGroup;
         int slot[kGroupsPerWave];
         uint32_t smask[kGroupsPerWave], sbase[kGroupsPerWave];
 #pragma unroll
@@ -619,7 +621,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
         uint32_t wm = L.wave_mask[w];
         size_t blk = (size_t)tile * block_stride + L.wave_block0[w];
         for (int bi = 0; wm; ++bi, ++blk, wm &= wm - 1) {
-            if ((bi & 3) != q) continue;
+            if ((bi % kQuarters) != q) continue;
             const int kappa = __ffs(wm) - 1;
             uint32_t ids[kGroupsPerWave];
 #pragma unroll
@@ -636,9 +638,9 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
                 if (lds_codes) id = lds_row_code(id == kNoRow ? (uint32_t)kRowCap : id);
                 ids[gi] = id & 0xFFFFu;
             }
-            static_assert(kGroupsPerWave == 4, "one 8-byte entry per voxel column");
-            *reinterpret_cast<u32x2_t*>(tile_blocks + blk * kIdBlockElems + n * kGroupsPerWave) =
-                u32x2_t{ids[0] | (ids[1] << 16), ids[2] | (ids[3] << 16)};
+            uint32_t* dst = reinterpret_cast<uint32_t*>(tile_blocks + blk * kIdBlockElems + n * kGroupsPerWave);
+#pragma unroll
+            for (int e = 0; e < kEntryWords; ++e) dst[e] = ids[2 * e] | (ids[2 * e + 1] << 16);
         }
     }
     FX_KSTAMP(7);
@@ -661,8 +663,7 @@ k_tiles_to_dense(const TileHeader* __restrict__ tile_hdr, const uint16_t* __rest
     const TileHeader* H = tile_hdr + tile;
     const int n_valid = H->n_out;
     const int g = threadIdx.x / kGroup, sub = threadIdx.x % kGroup;   // blockDim.x == kTileT: one thread per slot
-    const int w = (g >> kDealShift) & (kTileWaves - 1);
-    const int gi = ((g >> (kDealShift + 2)) << kDealShift) | (g & ((1 << kDealShift) - 1));
+    const int w = tile_wave_of(g), gi = tile_slot_of(g);
     const int local = tile_perm[tile * kTileT + g * kGroup + sub];
     uint32_t wm = H->wave_mask[w];
     size_t blk = (size_t)tile * block_stride + H->wave_block0[w];
