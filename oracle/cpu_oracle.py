@@ -46,6 +46,10 @@ def lib():
         L.fo_kernel_map.argtypes = [vp, vp, C.c_int, C.c_int, vp]
         L.fo_conv.restype = i64
         L.fo_conv.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp, i64, i64]
+        L.fo_conv_bwd_data.restype = i64
+        L.fo_conv_bwd_data.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp]
+        L.fo_conv_bwd_weight.restype = i64
+        L.fo_conv_bwd_weight.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp, i64, i64]
         _lib = L
     return _lib
 
@@ -152,4 +156,36 @@ def conv(gin: OracleGrid, gout: OracleGrid, kernel_size: int, stride: int, feat:
                       o_begin, o_end)
     if r < 0:
         raise ValueError("bad conv arguments")
+    return out
+
+
+def conv_bwd_data(gin: OracleGrid, gout: OracleGrid, kernel_size: int, stride: int, grad_out: np.ndarray,
+                  w: np.ndarray) -> np.ndarray:
+    """Gradient with respect to the input features, [N_in, C_in] float64 (O4)."""
+    grad_out = np.ascontiguousarray(grad_out, dtype=np.float64)
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    k3, c_in, c_out = w.shape
+    assert k3 == kernel_size ** 3 and grad_out.shape == (gout.num_voxels, c_out)
+    out = np.zeros((gin.num_voxels, c_in), dtype=np.float64)
+    r = lib().fo_conv_bwd_data(gin._h, gout._h, kernel_size, stride, _p(grad_out), _p(w), c_in, c_out, _p(out))
+    if r < 0:
+        raise ValueError("bad conv_bwd_data arguments")
+    return out
+
+
+def conv_bwd_weight(gin: OracleGrid, gout: OracleGrid, kernel_size: int, stride: int, feat: np.ndarray,
+                    grad_out: np.ndarray, o_begin: int = 0, o_end: Optional[int] = None) -> np.ndarray:
+    """Gradient with respect to the weights, [K^3, C_in, C_out] float64 (O4); only the outputs
+    in [o_begin, o_end) contribute."""
+    feat = np.ascontiguousarray(feat, dtype=np.float64)
+    grad_out = np.ascontiguousarray(grad_out, dtype=np.float64)
+    c_in, c_out = feat.shape[1], grad_out.shape[1]
+    assert feat.shape[0] == gin.num_voxels and grad_out.shape[0] == gout.num_voxels
+    if o_end is None:
+        o_end = gout.num_voxels
+    out = np.zeros((kernel_size ** 3, c_in, c_out), dtype=np.float64)
+    r = lib().fo_conv_bwd_weight(gin._h, gout._h, kernel_size, stride, _p(feat), _p(grad_out), c_in, c_out,
+                                 _p(out), o_begin, o_end)
+    if r < 0:
+        raise ValueError("bad conv_bwd_weight arguments")
     return out

@@ -33,6 +33,15 @@
  *      accumulated in double, looping voxel -> offset -> C_in -> C_out, neighbours
  *      found through this file's own hash map (not through O2's output).
  *
+ *  O4  backward pass -- Sec. 3.6 / 3.6.2 call the operators differentiable and Sec. 4.1.3
+ *      speaks of the gradient with respect to the filter coefficients; no formula is
+ *      printed, so the oracle is the derivative of O3's formula written out.  With
+ *      L any scalar function of out and gout = dL/dout:
+ *          gin[i,:]      = sum over pairs (o,kappa) with nb(o,kappa) = i of  W[kappa] . gout[o,:]
+ *          gw[kappa,:,:] = sum over outputs o with an active input of  in[nb(o,kappa),:]^T gout[o,:]
+ *      both accumulated in double by walking the same voxel -> offset loop as O3 and
+ *      adding each pair's contribution where it belongs.
+ *
  * Readings taken where the paper is silent (all listed in the design notes):
  *   - exported indices are 0-based rows of jdata, -1 means inactive (the paper's
  *     in-tree index 0 is its background value);
@@ -46,7 +55,9 @@
  *
  * Pins: tests/test_oracle_*.py (closed forms of Listings 1-2, dense special cases,
  * counting identities of Sec. 3.3, brute-force neighbour search, dense masked 3-D
- * correlation, K=1 per-voxel GEMM, identity-weight and all-ones exact cases).
+ * correlation, K=1 per-voxel GEMM, identity-weight and all-ones exact cases; for O4 the
+ * gradients a library's autograd gives for the dense masked correlation, the adjoint
+ * identities against O3, and central differences of O3).
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -313,6 +324,71 @@ int64_t fo_conv(const fo_grid *gin, const fo_grid *gout, int K, int stride,
                         const double xv = x[ci];
                         const double *wr = wk + (int64_t)ci * C_out;
                         for (int co = 0; co < C_out; ++co) y[co] += xv * wr[co];
+                    }
+                }
+    }
+    return pairs;
+}
+
+/* ------------------------------------------------------------------ O4 */
+/* gout [N_out, C_out], w [K^3, C_in, C_out], gin [N_in, C_in] (overwritten); all double.
+ * Returns the active pairs, or -1 on bad args. */
+int64_t fo_conv_bwd_data(const fo_grid *gin_grid, const fo_grid *gout_grid, int K, int stride,
+                         const double *gout, const double *w, int C_in, int C_out, double *gin) {
+    if (K < 1 || stride < 1 || gin_grid->B != gout_grid->B) return -1;
+    const int d0 = fo_delta_min(K);
+    int64_t pairs = 0;
+    for (int64_t e = 0; e < gin_grid->N * (int64_t)C_in; ++e) gin[e] = 0.0;
+    for (int64_t o = 0; o < gout_grid->N; ++o) {
+        const fo_vox *p = &gout_grid->vox[o];
+        const double *gy = gout + o * (int64_t)C_out;
+        for (int a = 0; a < K; ++a)
+            for (int b = 0; b < K; ++b)
+                for (int c = 0; c < K; ++c) {
+                    int64_t in = fo_find(gin_grid, p->b, stride * p->i + d0 + a, stride * p->j + d0 + b,
+                                         stride * p->k + d0 + c);
+                    if (in < 0) continue;
+                    ++pairs;
+                    double *gx = gin + in * (int64_t)C_in;
+                    const double *wk = w + (int64_t)((a * K + b) * K + c) * C_in * C_out;
+                    for (int ci = 0; ci < C_in; ++ci) {
+                        const double *wr = wk + (int64_t)ci * C_out;
+                        double s = 0.0;
+                        for (int co = 0; co < C_out; ++co) s += wr[co] * gy[co];
+                        gx[ci] += s;
+                    }
+                }
+    }
+    return pairs;
+}
+
+/* feat [N_in, C_in], gout [N_out, C_out], gw [K^3, C_in, C_out] (overwritten); all double.
+ * Only outputs o_begin..o_end-1 contribute.  Returns their active pairs, or -1 on bad args. */
+int64_t fo_conv_bwd_weight(const fo_grid *gin_grid, const fo_grid *gout_grid, int K, int stride,
+                           const double *feat, const double *gout, int C_in, int C_out, double *gw,
+                           int64_t o_begin, int64_t o_end) {
+    if (K < 1 || stride < 1 || gin_grid->B != gout_grid->B) return -1;
+    const int d0 = fo_delta_min(K);
+    int64_t pairs = 0;
+    for (int64_t e = 0; e < (int64_t)K * K * K * C_in * C_out; ++e) gw[e] = 0.0;
+    if (o_begin < 0) o_begin = 0;
+    if (o_end > gout_grid->N) o_end = gout_grid->N;
+    for (int64_t o = o_begin; o < o_end; ++o) {
+        const fo_vox *p = &gout_grid->vox[o];
+        const double *gy = gout + o * (int64_t)C_out;
+        for (int a = 0; a < K; ++a)
+            for (int b = 0; b < K; ++b)
+                for (int c = 0; c < K; ++c) {
+                    int64_t in = fo_find(gin_grid, p->b, stride * p->i + d0 + a, stride * p->j + d0 + b,
+                                         stride * p->k + d0 + c);
+                    if (in < 0) continue;
+                    ++pairs;
+                    const double *x = feat + in * (int64_t)C_in;
+                    double *gk = gw + (int64_t)((a * K + b) * K + c) * C_in * C_out;
+                    for (int ci = 0; ci < C_in; ++ci) {
+                        const double xv = x[ci];
+                        double *gr = gk + (int64_t)ci * C_out;
+                        for (int co = 0; co < C_out; ++co) gr[co] += xv * gy[co];
                     }
                 }
     }
