@@ -166,6 +166,38 @@ fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, fx_dtype in_
                              int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Sparse convolution backward (Sec. 3.6 / 3.6.2: the operators are differentiable; Sec. 4.1.3
+ * names the gradient with respect to the filter coefficients).  The paper prints no formula;
+ * these are the derivatives of the forward sum above.  With gout = dL/dout:
+ *
+ *   fx_sparse_conv_bwd_data:    gin[i,:] = sum over pairs (o,kappa) with map(o,kappa) = i of
+ *                                          W[kappa] . gout[o,:]
+ *   fx_sparse_conv_bwd_weight:  gw[kappa,:,:] = sum over o with map(o,kappa) >= 0 of
+ *                                          feat[map(o,kappa),:]^T  gout[o,:]
+ *
+ *   d_gout  device [N_out, C_out] row-major, dtype dt
+ *   d_w     device [K^3, C_in, C_out], dtype dt          (bwd_data)
+ *   d_feat  device [N_in, C_in], dtype dt                (bwd_weight)
+ *   d_gin   device [N_in, C_in], dtype out_dt (= dt or FX_F32); every row is written
+ *   d_gw    device [K^3, C_in, C_out], dtype out_dt (= dt or FX_F32); every element is written
+ * Products are exact and accumulated in fp32, one rounding (RNE) to out_dt at the end.  The
+ * weight gradient is summed in a fixed order (per-workgroup partial sums over contiguous tile
+ * ranges, then one ordered reduction): repeated calls give identical bits.
+ * bwd_data on a stride-1 map is the forward kernel run on the same map with the offsets
+ * mirrored and W[kappa] transposed (the map of a submanifold convolution is symmetric); on a
+ * K = stride map every input has exactly one pair and its row is written once.
+ * MFMA paths: FX_F16 / FX_BF16 with C_in % 64 == 0 and C_out % 64 == 0 (bwd_data: C_in % 64 == 0
+ * and C_out % 32 == 0; bwd_weight: C_in % 32 == 0 and C_out % 64 == 0) on tiled maps; everything
+ * else takes scalar kernels.  In the MFMA weight-gradient kernel operands are transposed by a
+ * multiplication with the identity, so a non-finite value in feat or gout makes the whole
+ * 32-channel block of gw that it touches NaN rather than only its own row or column.
+ */
+fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_gout, fx_dtype dt, const void* d_w,
+                                  int32_t C_in, int32_t C_out, void* d_gin, fx_dtype out_dt, void* stream);
+fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_feat, const void* d_gout, fx_dtype dt,
+                                    int32_t C_in, int32_t C_out, void* d_gw, fx_dtype out_dt, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Measurement support (the paper's protocol, Sec. 4.1: per-operator times).  While enabled,
  * every kernel launch of the library is bracketed by hipEvents on its launch stream;
  * fx_profile_read waits for the recorded events and returns the summed time and launch count

@@ -44,7 +44,8 @@ fx_status host_staging(void** p, size_t bytes, int area = 0);
 enum ProfSlot {
     kProfBucketCount = 0, kProfBucketScan, kProfBucketScatter, kProfBucketLeaves, kProfVoxelsToLeaves, kProfFindTiles, kProfRankTiles, kProfInsertUpper, kProfScanUpper, kProfInsertLower, kProfScanLower,
     kProfInsertLeaf, kProfScanLeaf, kProfGridIjk, kProfNbmap, kProfLeafNeighbors, kProfBuildTiles,
-    kProfPackWeights, kProfConvMfma, kProfConvGather, kProfConvScalar, kProfMemset, kProfSlotCount
+    kProfPackWeights, kProfConvMfma, kProfConvGather, kProfConvScalar, kProfMemset,
+    kProfDgradStrided, kProfWgrad, kProfWgradReduce, kProfSlotCount
 };
 bool prof_enabled();
 void prof_begin(int slot, hipStream_t s);

@@ -12,70 +12,9 @@
 // B = gathered features (16 input channels x 32 voxels), D = 32 channels x 32 voxels; the
 // weight rows are permuted so that each lane ends up with 32 consecutive output channels of
 // one voxel.
-#include "kmap.h"
-
-#include <hip/hip_bf16.h>
-#include <hip/hip_fp16.h>
-
-#include <algorithm>
+#include "conv_common.h"
 
 namespace fx {
-
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-
-constexpr int kCoutSlice = 64;      // output channels per wave
-constexpr int kProducerWaves = 4;
-constexpr int kConvThreads = 64 * (kTileWaves + kProducerWaves);
-constexpr int kMaxIdBlocks = kTileWaves * kMaxK3Tiled;
-
-// ---------------------------------------------------------------------------------- element types
-template <typename T> struct Elem;
-template <> struct Elem<__bf16> {
-    typedef bf16x8 vec8;
-    static __device__ __forceinline__ f32x16 mfma(vec8 a, vec8 b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ float to_float(uint16_t bits) { return __uint_as_float((uint32_t)bits << 16); }
-    static __device__ __forceinline__ uint16_t from_float(float f) {  // round to nearest even
-        uint32_t u = __float_as_uint(f);
-        if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
-        u += 0x7FFFu + ((u >> 16) & 1u);
-        return (uint16_t)(u >> 16);
-    }
-    static __device__ __forceinline__ uint32_t pack2(float a, float b) {  // two RNE conversions, a in the low half
-        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-        typedef __attribute__((ext_vector_type(2))) float f32x2;
-        const bf16x2 h = __builtin_convertvector(f32x2{a, b}, bf16x2);
-        uint32_t bits;
-        __builtin_memcpy(&bits, &h, 4);
-        return bits;
-    }
-};
-template <> struct Elem<_Float16> {
-    typedef f16x8 vec8;
-    static __device__ __forceinline__ f32x16 mfma(vec8 a, vec8 b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ float to_float(uint16_t bits) {
-        _Float16 h;
-        __builtin_memcpy(&h, &bits, 2);
-        return (float)h;
-    }
-    static __device__ __forceinline__ uint16_t from_float(float f) {
-        _Float16 h = (_Float16)f;  // v_cvt_f16_f32: round to nearest even
-        uint16_t bits;
-        __builtin_memcpy(&bits, &h, 2);
-        return bits;
-    }
-    static __device__ __forceinline__ uint32_t pack2(float a, float b) {
-        return (uint32_t)from_float(a) | ((uint32_t)from_float(b) << 16);
-    }
-};
 
 // ---------------------------------------------------------------------------------- weight packing
 // Wp[kappa][cin chunk][cout slice][mtile 0..1][kstep 0..1][lane 0..63][8]: the 16-byte A-operand
@@ -85,7 +24,7 @@ template <> struct Elem<_Float16> {
 // accumulators are then the 32 consecutive channels 32*h .. 32*h+31 (m-tile t = channels
 // 32*h + 16*t + v).
 __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wp, int K3, int C_in, int C_out,
-                               int32_t* __restrict__ counters) {
+                               int32_t* __restrict__ counters, int mode) {
     if (blockIdx.x == 0 && threadIdx.x < 8) counters[threadIdx.x] = 0;   // the convolution's work-list counters
     const int64_t total = (int64_t)K3 * C_in * C_out;
     const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
@@ -101,8 +40,17 @@ __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restr
         const int m = lane & 31, kq = lane >> 5;
         const int cin = c * kCinChunk + ks * 16 + kq * 8 + el;
         const int cout = s * kCoutSlice + 32 * ((m >> 2) & 1) + 16 * mt + 4 * (m >> 3) + (m & 3);
-        wp[e] = w[((int64_t)kappa * C_in + cin) * C_out + cout];
+        if (mode == kWeightsForward) wp[e] = w[((int64_t)kappa * C_in + cin) * C_out + cout];
+        else wp[e] = w[((int64_t)(mode == kWeightsMirrored ? K3 - 1 - kappa : kappa) * C_out + cout) * C_in + cin];
     }
+}
+
+void launch_pack_weights(const void* d_w, uint16_t* wp, int K3, int C_in, int C_out, int32_t* counters, int mode,
+                         hipStream_t st) {
+    const int64_t total = (int64_t)K3 * C_in * C_out;
+    ProfScope ps(kProfPackWeights, st);
+    k_pack_weights<<<(unsigned)std::min<int64_t>((total + 255) / 256, 4096), 256, 0, st>>>(
+        (const uint16_t*)d_w, wp, K3, C_in, C_out, counters, mode);
 }
 
 #ifdef FX_CONV_TIMING
@@ -116,8 +64,6 @@ __device__ unsigned long long g_conv_timing[1024 * 8];
 #endif
 
 // ---------------------------------------------------------------------------------- MFMA kernel
-constexpr int kRowBufBytes = (kRowCap + 1) * kRowBytes;           // staged rows + the zero row
-constexpr int kBlockBufBytes = kMaxIdBlocks * kIdBlockElems * 2;
 constexpr int kMetaSlots = 3;
 
 // A work item (tile x 64-channel output slice) as the workgroup sees it: its number in the work
@@ -139,7 +85,6 @@ struct ConvLds {
 };
 static_assert(sizeof(ConvLds) <= 160 * 1024, "LDS budget of one compute unit");
 
-__device__ __forceinline__ int lds_row_offset(int row, int p) { return (int)(lds_row_code((uint32_t)row) ^ (uint32_t)(p << 4)); }
 
 // What a wave needs to know about one work item; all fields are wave-uniform.
 struct Item {
@@ -148,8 +93,6 @@ struct Item {
     int win_lo, win_n, n_list, n_blocks, n_valid, n_staged;
     bool general;
 };
-
-__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 __device__ __forceinline__ int64_t slot_work(const MetaSlot& M) {
     const int lo = uni((int)(uint32_t)(M.work & 0xFFFFFFFFll)), hi = uni((int)(M.work >> 32));
@@ -291,8 +234,6 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
         step(wc, wb);
     }
 }
-
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 // Producer side: one wave copies 1 KB slabs (16 rows of 64 bytes, or 4 id blocks) from global
 // memory straight into LDS; lane l of a slab load writes the 16 bytes at slab + 16*l.
@@ -751,16 +692,9 @@ k_conv_gather(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restric
 // ---------------------------------------------------------------------------------- scalar path
 // One thread per (output voxel, output channel); fp32 FMA in offset-then-channel order.  Used
 // for fp32 data (true fp32 products) and for channel counts the MFMA tiling does not cover.
-template <int DT>
-__device__ __forceinline__ float load_as_float(const void* p, int64_t i) {
-    if (DT == FX_F32) return reinterpret_cast<const float*>(p)[i];
-    if (DT == FX_F16) return Elem<_Float16>::to_float(reinterpret_cast<const uint16_t*>(p)[i]);
-    return Elem<__bf16>::to_float(reinterpret_cast<const uint16_t*>(p)[i]);
-}
-
 template <int DT, bool OUT_F32>
 __global__ void k_conv_scalar(const int32_t* __restrict__ nbmap, int64_t n_out, int K3, const void* __restrict__ feat,
-                              const void* __restrict__ w, int C_in, int C_out, void* __restrict__ out) {
+                              const void* __restrict__ w, int C_in, int C_out, void* __restrict__ out, int mode) {
     const int64_t total = n_out * C_out;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
         const int64_t o = e / C_out;
@@ -770,9 +704,12 @@ __global__ void k_conv_scalar(const int32_t* __restrict__ nbmap, int64_t n_out, 
             const int32_t in = nbmap[o * K3 + kappa];
             if (in < 0) continue;
             const int64_t fb = (int64_t)in * C_in;
-            const int64_t wb = (int64_t)kappa * C_in * C_out + co;
+            // forward: W[kappa][ci][co]; mirrored (input gradient on a symmetric map): W[K3-1-kappa][co][ci]
+            const int64_t wb = mode == kWeightsForward ? (int64_t)kappa * C_in * C_out + co
+                                                       : ((int64_t)(mode == kWeightsMirrored ? K3 - 1 - kappa : kappa) * C_out + co) * C_in;
+            const int64_t ws = mode == kWeightsForward ? C_out : 1;
             for (int ci = 0; ci < C_in; ++ci)
-                acc = fmaf(load_as_float<DT>(feat, fb + ci), load_as_float<DT>(w, wb + (int64_t)ci * C_out), acc);
+                acc = fmaf(load_as_float<DT>(feat, fb + ci), load_as_float<DT>(w, wb + (int64_t)ci * ws), acc);
         }
         if (OUT_F32) reinterpret_cast<float*>(out)[e] = acc;
         else if (DT == FX_F16) reinterpret_cast<uint16_t*>(out)[e] = Elem<_Float16>::from_float(acc);
@@ -828,19 +765,8 @@ extern "C" int fx_debug_conv_timing(unsigned long long* h_out, size_t bytes) {
 }
 #endif
 
-extern "C" fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w,
-                                        int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream) {
-    if (!km || !d_w || C_in < 1 || C_out < 1 || (km->n_in > 0 && !d_feat) || (km->n_out > 0 && !d_out)) {
-        set_error("fx_sparse_conv_fwd: null pointer or non-positive channel count");
-        return FX_EINVAL;
-    }
-    if (in_dt != FX_F32 && in_dt != FX_F16 && in_dt != FX_BF16) { set_error("unknown input dtype"); return FX_EINVAL; }
-    if (out_dt != in_dt && out_dt != FX_F32) {
-        set_error("output dtype must equal the input dtype or be fp32");
-        return FX_EUNSUPPORTED;
-    }
-    if (km->n_out == 0) return FX_OK;
-    hipStream_t st = (hipStream_t)stream;
+fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w, int32_t C_in,
+                         int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st, int mode) {
     const bool out_f32 = (out_dt == FX_F32);
     const char* force = getenv("FVDB_HOTPATH_FORCE_SCALAR");
     const bool mfma = in_dt != FX_F32 && km->n_tiles > 0 && C_in % kCinChunk == 0 && C_out % kCoutSlice == 0 &&
@@ -850,12 +776,7 @@ extern "C" fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, f
         const size_t wbytes = sizeof(uint16_t) * (size_t)km->K3 * C_in * C_out;   // a multiple of 64 bytes
         FX_TRY(dev_alloc((void**)&wp, wbytes + 8 * sizeof(int32_t), st));
         int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
-        const int64_t total = (int64_t)km->K3 * C_in * C_out;
-        {
-            ProfScope ps(kProfPackWeights, st);
-            k_pack_weights<<<(unsigned)std::min<int64_t>((total + 255) / 256, 4096), 256, 0, st>>>(
-                (const uint16_t*)d_w, wp, km->K3, C_in, C_out, counters);
-        }
+        launch_pack_weights(d_w, wp, km->K3, C_in, C_out, counters, mode, st);
         hipError_t e = hipGetLastError();
         // strided maps use every input row once: the gather kernel; others: the LDS-staged kernel
         const char* fg = getenv("FVDB_HOTPATH_CONV_GATHER");
@@ -887,9 +808,9 @@ extern "C" fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, f
 #define FX_SCALAR(DT)                                                                                            \
     do {                                                                                                         \
         if (out_f32) k_conv_scalar<DT, true><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_w,    \
-                                                                 C_in, C_out, d_out);                            \
+                                                                 C_in, C_out, d_out, mode);                      \
         else k_conv_scalar<DT, false><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_w, C_in,     \
-                                                          C_out, d_out);                                         \
+                                                          C_out, d_out, mode);                                   \
     } while (0)
     ProfScope ps(kProfConvScalar, st);
     if (in_dt == FX_F32) FX_SCALAR(FX_F32);
@@ -898,4 +819,19 @@ extern "C" fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, f
 #undef FX_SCALAR
     FX_HIP_TRY(hipGetLastError());
     return FX_OK;
+}
+
+extern "C" fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w,
+                                        int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream) {
+    if (!km || !d_w || C_in < 1 || C_out < 1 || (km->n_in > 0 && !d_feat) || (km->n_out > 0 && !d_out)) {
+        set_error("fx_sparse_conv_fwd: null pointer or non-positive channel count");
+        return FX_EINVAL;
+    }
+    if (in_dt != FX_F32 && in_dt != FX_F16 && in_dt != FX_BF16) { set_error("unknown input dtype"); return FX_EINVAL; }
+    if (out_dt != in_dt && out_dt != FX_F32) {
+        set_error("output dtype must equal the input dtype or be fp32");
+        return FX_EUNSUPPORTED;
+    }
+    if (km->n_out == 0) return FX_OK;
+    return conv_apply(km, d_feat, in_dt, d_w, C_in, C_out, d_out, out_dt, (hipStream_t)stream, kWeightsForward);
 }

@@ -1,0 +1,565 @@
+// Backward pass of the sparse convolution (Sec. 3.6 / 3.6.2: differentiable operators; Sec. 4.1.3
+// names the gradient with respect to the filter coefficients).  The paper gives no formula; these
+// are the derivatives of  out[o,:] = sum_kappa feat[map(o,kappa),:] . W[kappa]:
+//
+//   input gradient    gin[i,:]      = sum over pairs (o,kappa) with map(o,kappa) = i of W[kappa] . gout[o,:]
+//   weight gradient   gw[kappa,:,:] = sum over o with map(o,kappa) >= 0 of feat[map(o,kappa),:]^T gout[o,:]
+//
+// Input gradient: a submanifold map is symmetric (map(o,kappa) = i  <=>  map(i,K^3-1-kappa) = o), so
+// the forward kernels run unchanged on gout with the offsets mirrored and every W[kappa] transposed
+// (conv_apply, kWeightsMirrored).  On a K = stride map no two outputs share an input: one wave per
+// column block multiplies the block's gout rows with each W[kappa]^T and stores the product rows
+// straight to the inputs the map names (k_dgrad_strided).
+//
+// Weight gradient: a contraction over voxels, so both MFMA operands must hold 8 consecutive
+// *voxels* per lane while the rows in memory hold consecutive *channels*.  The gout tile is
+// transposed once while it is staged in LDS; the gathered feature rows are transposed on the
+// matrix unit itself (a multiplication with the identity leaves a 32x32 block of them in the
+// accumulator layout, which is exactly the operand layout with voxels along k), see k_wgrad_mfma.
+#include "conv_common.h"
+
+namespace fx {
+
+// ---------------------------------------------------------------------------------- helpers
+// bit pattern of 1.0 in the storage type
+template <typename T> __device__ __forceinline__ uint16_t one_bits();
+template <> __device__ __forceinline__ uint16_t one_bits<__bf16>() { return 0x3F80; }
+template <> __device__ __forceinline__ uint16_t one_bits<_Float16>() { return 0x3C00; }
+
+template <typename T>
+__device__ __forceinline__ typename Elem<T>::vec8 vec8_from_words(u32x4 w) {
+    typename Elem<T>::vec8 v;
+    __builtin_memcpy(&v, &w, 16);
+    return v;
+}
+
+// eight fp32 values that are exactly representable in T -> one operand fragment
+template <typename T>
+__device__ __forceinline__ typename Elem<T>::vec8 pack8(const f32x16& t, int first) {
+    u32x4 w;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = Elem<T>::pack2(t[first + 2 * e], t[first + 2 * e + 1]);
+    return vec8_from_words<T>(w);
+}
+
+// Global input row behind a local row id of a tile (-1: none).
+__device__ __forceinline__ int32_t tile_row_of(uint32_t id, int flags, int win_lo, int win_n,
+                                               const int32_t* __restrict__ rows) {
+    if (flags & kTileLdsOffsets) id = (id / kRowBytes == (uint32_t)kRowCap) ? kNoRow : id / kRowBytes;
+    if (id == kNoRow) return -1;
+    return id < (uint32_t)win_n ? win_lo + (int32_t)id : rows[id - (uint32_t)win_n];
+}
+
+// ---------------------------------------------------------------------------------- input gradient, K = stride
+// One wave per (tile, column block of 32 outputs, 64 produced channels).  The B operand of every
+// offset is the same: the gout rows of the block's outputs (re-read per offset, they stay in L1);
+// the A operand is W[kappa]^T in the packed fragment order.  After the chunks of one offset the
+// accumulators hold gin rows of the 32 inputs map(o, kappa): each lane stores its 32 channels to
+// the row of its voxel and the accumulators start again from zero.
+constexpr int kDgradWaves = 4;
+
+template <typename T, bool OUT_F32>
+__global__ void __launch_bounds__(64 * kDgradWaves)
+k_dgrad_strided(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
+                const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
+                int block_stride, int64_t n_items, const uint16_t* __restrict__ gout, const uint16_t* __restrict__ wp,
+                int C_contract, int C_produce, void* __restrict__ gin) {
+    typedef typename Elem<T>::vec8 vec8;
+    __shared__ int32_t row_of[kDgradWaves][kMaxK3Tiled][kGroup];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t item = (int64_t)blockIdx.x * kDgradWaves + wave;
+    if (item >= n_items) return;
+    const int nchunk = C_contract / kCinChunk, nslice = C_produce / kCoutSlice;
+    const int slice = (int)(item % nslice);
+    const int64_t tg = item / nslice;
+    const int g = (int)(tg % kGroupsPerTile);
+    const int64_t tile = tg / kGroupsPerTile;
+    const TileHeader* H = tile_hdr + tile;
+    const int w = tile_wave_of(g), gi = tile_slot_of(g);
+    const uint32_t gm = (uint32_t)uni((int)H->group_mask[g]);
+    const uint32_t wm = (uint32_t)uni((int)H->wave_mask[w]);
+    const int n = lane & 31, h = lane >> 5;
+    const int n_valid = uni(H->n_out);
+    {
+        const int flags = uni(H->flags), win_lo = uni(H->win_lo), win_n = uni(H->win_n);
+        const size_t blk0 = (size_t)tile * block_stride + (uint32_t)uni((int)H->wave_block0[w]);
+        const int32_t* rows = tile_rows + tile * (int64_t)row_stride;
+        int rank = 0;
+        for (uint32_t m = gm; m; m &= m - 1, ++rank) {
+            if ((rank & 1) != h) continue;
+            const int kappa = __ffs(m) - 1;
+            const size_t blk = blk0 + __popc(wm & ((1u << kappa) - 1u));
+            const uint32_t id = tile_blocks[blk * kIdBlockElems + n * kGroupsPerWave + gi];
+            row_of[wave][rank][n] = tile_row_of(id, flags, win_lo, win_n, rows);
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    const int local = tile_perm[tile * kTileT + g * kGroup + n];
+    const bool valid = local < n_valid;
+    const uint16_t* grow = gout + (tile * kTileT + (valid ? local : 0)) * (int64_t)C_contract + h * 8;
+    const int w_kappa_stride = nchunk * nslice * 4 * 64;
+    const vec8* wl = reinterpret_cast<const vec8*>(wp) + lane;
+    vec8 zero;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) zero[e] = 0;
+
+    int rank = 0;
+    for (uint32_t m = gm; m; m &= m - 1, ++rank) {
+        const int kappa = __ffs(m) - 1;
+        f32x16 acc[2];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
+        for (int c = 0; c < nchunk; ++c) {
+            vec8 b[2] = {zero, zero}, wf[4];
+            if (valid) {
+                b[0] = *reinterpret_cast<const vec8*>(grow + c * kCinChunk);
+                b[1] = *reinterpret_cast<const vec8*>(grow + c * kCinChunk + 16);
+            }
+            const vec8* ws = wl + ((c * nslice + slice) * 4) * 64 + kappa * w_kappa_stride;
+#pragma unroll
+            for (int f = 0; f < 4; ++f) wf[f] = ws[f * 64];
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wf[mt * 2 + ks], b[ks], acc[mt]);
+        }
+        const int32_t r = row_of[wave][rank][n];
+        if (r < 0) continue;
+        const int64_t col = (int64_t)slice * kCoutSlice + 32 * h;
+        if (OUT_F32) {
+            float* dst = reinterpret_cast<float*>(gin) + (int64_t)r * C_produce + col;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4)
+                    *reinterpret_cast<f32x4*>(dst + 16 * mt + 4 * v4) =
+                        f32x4{acc[mt][4 * v4], acc[mt][4 * v4 + 1], acc[mt][4 * v4 + 2], acc[mt][4 * v4 + 3]};
+        } else {
+            uint16_t* dst = reinterpret_cast<uint16_t*>(gin) + (int64_t)r * C_produce + col;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int v8 = 0; v8 < 2; ++v8) {
+                    u32x4 pk;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) pk[e] = Elem<T>::pack2(acc[mt][8 * v8 + 2 * e], acc[mt][8 * v8 + 2 * e + 1]);
+                    *reinterpret_cast<u32x4*>(dst + 16 * mt + 8 * v8) = pk;
+                }
+        }
+    }
+}
+
+// One thread per (pair, input channel) of a K = stride map (each input row has exactly one pair):
+// gin[map(o,kappa), ci] = sum_co W[kappa][ci][co] * gout[o][co], fp32 FMA in channel order.
+template <int DT, bool OUT_F32>
+__global__ void k_dgrad_strided_scalar(const int32_t* __restrict__ nbmap, int64_t n_out, int K3,
+                                       const void* __restrict__ gout, const void* __restrict__ w, int C_in, int C_out,
+                                       void* __restrict__ gin) {
+    const int64_t total = n_out * K3 * C_in;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t pair = e / C_in;
+        const int ci = (int)(e - pair * C_in);
+        const int32_t in = nbmap[pair];
+        if (in < 0) continue;
+        const int64_t o = pair / K3;
+        const int kappa = (int)(pair - o * K3);
+        const int64_t wb = ((int64_t)kappa * C_in + ci) * C_out, gb = o * C_out;
+        float acc = 0.f;
+        for (int co = 0; co < C_out; ++co) acc = fmaf(load_as_float<DT>(w, wb + co), load_as_float<DT>(gout, gb + co), acc);
+        const int64_t dst = (int64_t)in * C_in + ci;
+        if (OUT_F32) reinterpret_cast<float*>(gin)[dst] = acc;
+        else if (DT == FX_F16) reinterpret_cast<uint16_t*>(gin)[dst] = Elem<_Float16>::from_float(acc);
+        else reinterpret_cast<uint16_t*>(gin)[dst] = Elem<__bf16>::from_float(acc);
+    }
+}
+
+// ---------------------------------------------------------------------------------- weight gradient, MFMA
+// A workgroup owns a block of 32 input channels x 64 output channels of every gw[kappa] and a
+// contiguous range of tiles; its 8 waves split the offsets (wave w: kappa = w, w+8, w+16, w+24),
+// so a wave keeps 4 offsets x 2 accumulator tiles (32 ci x 32 co) in registers over the whole
+// range.  Per tile the workgroup stages, single-buffered: the tile's input rows (32 channels,
+// the forward kernel's LDS row layout, so the map's precomputed LDS offsets apply), its id
+// blocks, and the gout rows of its 512 outputs transposed to [channel][slot] (2 bytes per element,
+// row stride padded by 8 bytes so a fragment read of 32 channels spreads over all banks).
+//
+// For one (column block g, offset kappa) a wave:
+//   1. reads the A fragments of the gathered rows exactly as the forward kernel reads its B
+//      fragments (lane (voxel n, half h): channels 8h..8h+7 and 16+8h..16+8h+7 of the row of voxel n);
+//   2. multiplies them with the identity: D[voxel][channel] = feat[voxel][channel], which in the
+//      accumulator layout gives lane (channel, h) the voxels 8b+4h+r (b, r = 0..3) in register 4b+r;
+//   3. rounds those 16 values to the storage type (exact) -- they are the A operand
+//      [channel][voxel] of two k-steps whose k index runs over voxels in the order
+//      (b, r) -> 16*ks + 8*(b&1) + 4h + r;
+//   4. reads the matching B fragments from the transposed gout tile (two 8-byte reads per k-step:
+//      slots 32g + 16ks + 4h .. +3 and +8 .. +11 of channel n) and accumulates
+//      gw[kappa][ci][co] += sum_voxel feat[voxel][ci] * gout[voxel][co].
+// A voxel of the block without that tap reads the zero row and adds nothing; a slot past the end
+// of the last tile has a zero gout column.
+// Partial sums go to part[range][kappa][ci][co] (fp32); k_wgrad_reduce adds the ranges in
+// ascending order, so the result does not depend on scheduling.
+constexpr int kWgWaves = 8;
+constexpr int kWgThreads = 64 * kWgWaves;
+constexpr int kWgCi = kCinChunk;            // 32: the row chunk staged in LDS
+constexpr int kWgCo = 64;
+constexpr int kGtStride = kTileT * 2 + 8;   // bytes per channel of the transposed gout tile
+constexpr int kWgOffsetsPerWave = (kMaxK3Tiled + kWgWaves - 1) / kWgWaves;   // 4
+
+struct WgradLds {
+    unsigned char rows[kRowBufBytes];
+    unsigned char blocks[kBlockBufBytes];
+    unsigned char gt[kWgCo * kGtStride];
+};
+static_assert(sizeof(WgradLds) <= 160 * 1024, "LDS budget of one compute unit");
+static_assert(kTileT == kWgThreads, "one thread stages one output slot");
+static_assert(kGroupsPerWave == 4 && kTileWaves == 4, "id blocks of four column blocks, 8 bytes per voxel");
+
+template <typename T>
+__global__ void __launch_bounds__(kWgThreads, 1)
+k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
+             const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
+             int block_stride, int64_t n_tiles, int n_ranges, const uint16_t* __restrict__ feat,
+             const uint16_t* __restrict__ gout, int C_in, int C_out, int K3, float* __restrict__ part) {
+    typedef typename Elem<T>::vec8 vec8;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    WgradLds& L = *reinterpret_cast<WgradLds*>(lds_raw);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    const int n_cib = C_in / kWgCi, n_cblk = n_cib * (C_out / kWgCo);
+    const int blk = blockIdx.x % n_cblk, range = blockIdx.x / n_cblk;
+    const int cib = blk % n_cib, cob = blk / n_cib;
+    const int64_t t0 = n_tiles * range / n_ranges, t1 = n_tiles * (range + 1) / n_ranges;
+
+    if (tid < kRowBytes / 16) reinterpret_cast<u32x4*>(L.rows + kRowCap * kRowBytes)[tid] = u32x4{0, 0, 0, 0};
+
+    // identity fragments: element e of lane (n, h) in k-step ks is row k = 8h + e, column n of [I16 at columns 16ks..]
+    vec8 ident[2];
+    {
+        u32x4 wds[2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const uint32_t lo = (n == 16 * ks + 8 * h + 2 * e2) ? one_bits<T>() : 0u;
+                const uint32_t hi = (n == 16 * ks + 8 * h + 2 * e2 + 1) ? one_bits<T>() : 0u;
+                wds[ks][e2] = lo | (hi << 16);
+            }
+        ident[0] = vec8_from_words<T>(wds[0]);
+        ident[1] = vec8_from_words<T>(wds[1]);
+    }
+
+    f32x16 acc[kWgOffsetsPerWave][2];
+#pragma unroll
+    for (int j = 0; j < kWgOffsetsPerWave; ++j)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][cb][v] = 0.f;
+
+    const uint32_t hsel = (uint32_t)h << 4;
+    for (int64_t tile = t0; tile < t1; ++tile) {
+        const TileHeader* H = tile_hdr + tile;
+        const int flags = uni(H->flags), win_lo = uni(H->win_lo), win_n = uni(H->win_n), n_list = uni(H->n_list);
+        const int n_blocks = uni(H->n_blocks), n_valid = uni(H->n_out);
+        const int n_staged = (flags & kTileDirect) ? 0 : min(win_n + n_list, kRowCap);
+        const bool general = !(flags & kTileLdsOffsets);
+        const int32_t* my_rows = tile_rows + tile * (int64_t)row_stride;
+        uint32_t wmask[kTileWaves], gmask[kGroupsPerTile];
+        int block0[kTileWaves];
+#pragma unroll
+        for (int fw = 0; fw < kTileWaves; ++fw) {
+            wmask[fw] = (uint32_t)uni((int)H->wave_mask[fw]);
+            block0[fw] = uni((int)H->wave_block0[fw]);
+        }
+#pragma unroll
+        for (int g = 0; g < kGroupsPerTile; ++g) gmask[g] = (uint32_t)uni((int)H->group_mask[g]);
+
+        // ---- stage: input rows (32 channels of this block), id blocks, transposed gout
+        {
+            const int n_slabs = (n_staged + 15) >> 4;
+            const int piece = (lane & 3) ^ ((lane >> 4) & 3);
+            for (int s = wave; s < n_slabs; s += kWgWaves) {
+                const int r = 16 * s + (lane >> 2);
+                if (r < n_staged) {
+                    const int64_t gr = r < win_n ? (int64_t)win_lo + r : (int64_t)my_rows[r - win_n];
+                    const uint16_t* src = feat + gr * C_in + cib * kWgCi + piece * 8;
+                    __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(L.rows + s * 1024), 16, 0, 0);
+                }
+            }
+            const unsigned char* bsrc =
+                reinterpret_cast<const unsigned char*>(tile_blocks + (size_t)tile * block_stride * kIdBlockElems);
+            const int bytes = n_blocks * kIdBlockElems * 2;
+            for (int s = wave; s * 1024 < bytes; s += kWgWaves) {
+                const int off = s * 1024 + lane * 16;
+                if (off < bytes) __builtin_amdgcn_global_load_lds(bsrc + off, (lds_ptr_t)(L.blocks + s * 1024), 16, 0, 0);
+            }
+            const int local = tile_perm[tile * kTileT + tid];
+            const uint16_t* grow = gout + (tile * kTileT + local) * (int64_t)C_out + cob * kWgCo;
+            u32x4 gv[kWgCo / 8];
+#pragma unroll
+            for (int q = 0; q < kWgCo / 8; ++q)
+                gv[q] = local < n_valid ? *reinterpret_cast<const u32x4*>(grow + q * 8) : u32x4{0, 0, 0, 0};
+#pragma unroll
+            for (int q = 0; q < kWgCo / 8; ++q)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    *reinterpret_cast<uint16_t*>(L.gt + (q * 8 + e) * kGtStride + tid * 2) =
+                        (uint16_t)(gv[q][e >> 1] >> (16 * (e & 1)));
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+
+        // ---- multiply
+#pragma unroll
+        for (int j = 0; j < kWgOffsetsPerWave; ++j) {
+            const int kappa = wave + kWgWaves * j;
+            if (kappa >= K3) continue;
+#pragma unroll
+            for (int fw = 0; fw < kTileWaves; ++fw) {
+                const uint32_t wm = wmask[fw];
+                if (!((wm >> kappa) & 1u)) continue;
+                const int b = block0[fw] + __popc(wm & ((1u << kappa) - 1u));
+                const u32x2 ids = *reinterpret_cast<const u32x2*>(L.blocks + ((size_t)b * kGroup + n) * 8);
+#pragma unroll
+                for (int gi = 0; gi < kGroupsPerWave; ++gi) {
+                    const int g = tile_group_of(fw, gi);
+                    if (!((gmask[g] >> kappa) & 1u)) continue;
+                    const uint32_t id = (ids[gi >> 1] >> (16 * (gi & 1))) & 0xFFFFu;
+                    vec8 a0, a1;
+                    if (!general) {
+                        const uint32_t ad = id ^ hsel;
+                        a0 = *reinterpret_cast<const vec8*>(L.rows + ad);
+                        a1 = *reinterpret_cast<const vec8*>(L.rows + (ad ^ 32u));
+                    } else {
+                        const bool staged = id < (uint32_t)n_staged;
+                        const int row = staged ? (int)id : kRowCap;
+                        a0 = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, h));
+                        a1 = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, h + 2));
+                        if (!staged && id != kNoRow) {
+                            const int64_t gr = id < (uint32_t)win_n ? (int64_t)win_lo + id : (int64_t)my_rows[id - win_n];
+                            const uint16_t* src = feat + gr * C_in + cib * kWgCi + h * 8;
+                            a0 = *reinterpret_cast<const vec8*>(src);
+                            a1 = *reinterpret_cast<const vec8*>(src + 16);
+                        }
+                    }
+                    f32x16 t;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) t[v] = 0.f;
+                    t = Elem<T>::mfma(a0, ident[0], t);
+                    t = Elem<T>::mfma(a1, ident[1], t);
+                    const vec8 fT[2] = {pack8<T>(t, 0), pack8<T>(t, 8)};
+#pragma unroll
+                    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks) {
+                            const unsigned char* src = L.gt + (cb * 32 + n) * kGtStride + (g * kGroup + 16 * ks + 4 * h) * 2;
+                            const u32x2 lo = *reinterpret_cast<const u32x2*>(src);
+                            const u32x2 hi = *reinterpret_cast<const u32x2*>(src + 16);
+                            acc[j][cb] = Elem<T>::mfma(fT[ks], vec8_from_words<T>(u32x4{lo[0], lo[1], hi[0], hi[1]}), acc[j][cb]);
+                        }
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- partial sums of this range: lane (co = n, h), register 4b + r  ->  ci = 8b + 4h + r
+#pragma unroll
+    for (int j = 0; j < kWgOffsetsPerWave; ++j) {
+        const int kappa = wave + kWgWaves * j;
+        if (kappa >= K3) continue;
+        float* dst = part + (((int64_t)range * K3 + kappa) * C_in + cib * kWgCi) * C_out + cob * kWgCo + n;
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) dst[(int64_t)(8 * (v >> 2) + 4 * h + (v & 3)) * C_out + cb * 32] = acc[j][cb][v];
+    }
+}
+
+// gw[e] = part[0][e] + part[1][e] + ... in ascending order, rounded once to the output type.
+template <int OUT_DT>
+__global__ void k_wgrad_reduce(const float* __restrict__ part, int n_ranges, int64_t total, void* __restrict__ gw) {
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        float s = 0.f;
+        for (int r = 0; r < n_ranges; ++r) s += part[(int64_t)r * total + e];
+        if (OUT_DT == FX_F32) reinterpret_cast<float*>(gw)[e] = s;
+        else if (OUT_DT == FX_F16) reinterpret_cast<uint16_t*>(gw)[e] = Elem<_Float16>::from_float(s);
+        else reinterpret_cast<uint16_t*>(gw)[e] = Elem<__bf16>::from_float(s);
+    }
+}
+
+// Scalar weight gradient: one thread per element of gw and per range of outputs, fp32 FMA in
+// output order; the ranges are added by k_wgrad_reduce.
+template <int DT>
+__global__ void k_wgrad_scalar(const int32_t* __restrict__ nbmap, int64_t n_out, int K3, const void* __restrict__ feat,
+                               const void* __restrict__ gout, int C_in, int C_out, int n_ranges,
+                               float* __restrict__ part) {
+    const int64_t total = (int64_t)K3 * C_in * C_out;
+    const int range = blockIdx.y;
+    const int64_t o0 = n_out * range / n_ranges, o1 = n_out * (range + 1) / n_ranges;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int kappa = (int)(e / ((int64_t)C_in * C_out));
+        const int rem = (int)(e - (int64_t)kappa * C_in * C_out);
+        const int ci = rem / C_out, co = rem - ci * C_out;
+        float acc = 0.f;
+        for (int64_t o = o0; o < o1; ++o) {
+            const int32_t in = nbmap[o * K3 + kappa];
+            if (in < 0) continue;
+            acc = fmaf(load_as_float<DT>(feat, (int64_t)in * C_in + ci), load_as_float<DT>(gout, o * C_out + co), acc);
+        }
+        part[(int64_t)range * total + e] = acc;
+    }
+}
+
+static int compute_units() {
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
+        if (n_cu <= 0) n_cu = 256;
+    }
+    return n_cu;
+}
+
+static hipError_t launch_reduce(const float* part, int n_ranges, int64_t total, void* gw, fx_dtype out_dt, hipStream_t st) {
+    const unsigned nb = (unsigned)std::min<int64_t>((total + 255) / 256, 1 << 16);
+    ProfScope ps(kProfWgradReduce, st);
+    if (out_dt == FX_F32) k_wgrad_reduce<FX_F32><<<nb, 256, 0, st>>>(part, n_ranges, total, gw);
+    else if (out_dt == FX_F16) k_wgrad_reduce<FX_F16><<<nb, 256, 0, st>>>(part, n_ranges, total, gw);
+    else k_wgrad_reduce<FX_BF16><<<nb, 256, 0, st>>>(part, n_ranges, total, gw);
+    return hipGetLastError();
+}
+
+}  // namespace fx
+
+using namespace fx;
+
+static fx_status check_bwd_types(const char* who, fx_dtype dt, fx_dtype out_dt) {
+    if (dt != FX_F32 && dt != FX_F16 && dt != FX_BF16) { set_error("%s: unknown dtype", who); return FX_EINVAL; }
+    if (out_dt != dt && out_dt != FX_F32) {
+        set_error("%s: output dtype must equal the input dtype or be fp32", who);
+        return FX_EUNSUPPORTED;
+    }
+    return FX_OK;
+}
+
+static bool force_scalar() {
+    const char* force = getenv("FVDB_HOTPATH_FORCE_SCALAR");
+    return force && force[0] == '1';
+}
+
+extern "C" fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_gout, fx_dtype dt, const void* d_w,
+                                             int32_t C_in, int32_t C_out, void* d_gin, fx_dtype out_dt, void* stream) {
+    if (!km || !d_w || C_in < 1 || C_out < 1 || (km->n_out > 0 && !d_gout) || (km->n_in > 0 && !d_gin)) {
+        set_error("fx_sparse_conv_bwd_data: null pointer or non-positive channel count");
+        return FX_EINVAL;
+    }
+    FX_TRY(check_bwd_types("fx_sparse_conv_bwd_data", dt, out_dt));
+    if (km->n_in == 0) return FX_OK;
+    hipStream_t st = (hipStream_t)stream;
+    if (km->stride == 1) {
+        // symmetric map, same grid on both sides: the forward multiply on gout with mirrored offsets
+        // and transposed weights (C_out channels are contracted, C_in produced)
+        return conv_apply(km, d_gout, dt, d_w, C_out, C_in, d_gin, out_dt, st, kWeightsMirrored);
+    }
+    if (km->K != km->stride) { set_error("fx_sparse_conv_bwd_data: unsupported (kernel, stride)"); return FX_EUNSUPPORTED; }
+    const bool out_f32 = out_dt == FX_F32;
+    const bool mfma = dt != FX_F32 && km->n_tiles > 0 && C_out % kCinChunk == 0 && C_in % kCoutSlice == 0 && !force_scalar();
+    if (mfma) {
+        uint16_t* wp = nullptr;
+        const size_t wbytes = sizeof(uint16_t) * (size_t)km->K3 * C_in * C_out;
+        FX_TRY(dev_alloc((void**)&wp, wbytes + 8 * sizeof(int32_t), st));
+        int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
+        launch_pack_weights(d_w, wp, km->K3, C_out, C_in, counters, kWeightsTransposed, st);
+        hipError_t e = hipGetLastError();
+        if (e == hipSuccess) {
+            const int64_t n_items = km->n_tiles * (int64_t)kGroupsPerTile * (C_in / kCoutSlice);
+            const unsigned grid = (unsigned)((n_items + kDgradWaves - 1) / kDgradWaves);
+            ProfScope ps(kProfDgradStrided, st);
+#define FX_DGRAD(T, F32)                                                                                             \
+    k_dgrad_strided<T, F32><<<grid, 64 * kDgradWaves, 0, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,      \
+                                                               km->row_stride, km->d_tile_blocks, km->block_stride,  \
+                                                               n_items, (const uint16_t*)d_gout, wp, C_out, C_in, d_gin)
+            if (dt == FX_BF16) { if (out_f32) FX_DGRAD(__bf16, true); else FX_DGRAD(__bf16, false); }
+            else { if (out_f32) FX_DGRAD(_Float16, true); else FX_DGRAD(_Float16, false); }
+#undef FX_DGRAD
+            e = hipGetLastError();
+        }
+        dev_free(wp, st);
+        if (e != hipSuccess) { set_error("input-gradient launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
+        return FX_OK;
+    }
+    FX_TRY(kmap_ensure_dense(const_cast<fx_kmap*>(km), st));
+    const int64_t total = km->n_out * km->K3 * C_in;
+    const unsigned nb = (unsigned)std::min<int64_t>((total + 255) / 256, 1 << 20);
+    ProfScope ps(kProfDgradStrided, st);
+#define FX_SCALAR(DT)                                                                                                 \
+    do {                                                                                                              \
+        if (out_f32) k_dgrad_strided_scalar<DT, true><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_gout, d_w, \
+                                                                          C_in, C_out, d_gin);                        \
+        else k_dgrad_strided_scalar<DT, false><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_gout, d_w, C_in,  \
+                                                                   C_out, d_gin);                                     \
+    } while (0)
+    if (dt == FX_F32) FX_SCALAR(FX_F32);
+    else if (dt == FX_F16) FX_SCALAR(FX_F16);
+    else FX_SCALAR(FX_BF16);
+#undef FX_SCALAR
+    FX_HIP_TRY(hipGetLastError());
+    return FX_OK;
+}
+
+extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_feat, const void* d_gout, fx_dtype dt,
+                                               int32_t C_in, int32_t C_out, void* d_gw, fx_dtype out_dt, void* stream) {
+    if (!km || !d_gw || C_in < 1 || C_out < 1 || (km->n_in > 0 && !d_feat) || (km->n_out > 0 && !d_gout)) {
+        set_error("fx_sparse_conv_bwd_weight: null pointer or non-positive channel count");
+        return FX_EINVAL;
+    }
+    FX_TRY(check_bwd_types("fx_sparse_conv_bwd_weight", dt, out_dt));
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t total = (int64_t)km->K3 * C_in * C_out;
+    if (km->n_out == 0) {   // no pairs: the gradient is zero
+        FX_HIP_TRY(launch_reduce(nullptr, 0, total, d_gw, out_dt, st));
+        return FX_OK;
+    }
+    const bool mfma = dt != FX_F32 && km->n_tiles > 0 && C_in % kWgCi == 0 && C_out % kWgCo == 0 && !force_scalar();
+    float* part = nullptr;
+    hipError_t e = hipSuccess;
+    int n_ranges = 1;
+    if (mfma) {
+        const int n_cblk = (C_in / kWgCi) * (C_out / kWgCo);
+        n_ranges = (int)std::max<int64_t>(1, std::min<int64_t>(km->n_tiles, compute_units() / n_cblk));
+        FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * n_ranges, st));
+        const size_t lds = sizeof(WgradLds);
+        ProfScope ps(kProfWgrad, st);
+#define FX_WGRAD(T)                                                                                                    \
+    do {                                                                                                               \
+        e = hipFuncSetAttribute((const void*)k_wgrad_mfma<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);   \
+        if (e == hipSuccess)                                                                                           \
+            k_wgrad_mfma<T><<<(unsigned)(n_cblk * n_ranges), kWgThreads, lds, st>>>(                                   \
+                km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows, km->row_stride, km->d_tile_blocks, km->block_stride, \
+                km->n_tiles, n_ranges, (const uint16_t*)d_feat, (const uint16_t*)d_gout, C_in, C_out, km->K3, part);   \
+    } while (0)
+        if (dt == FX_BF16) FX_WGRAD(__bf16); else FX_WGRAD(_Float16);
+#undef FX_WGRAD
+        if (e == hipSuccess) e = hipGetLastError();
+    } else {
+        fx_status rc = kmap_ensure_dense(const_cast<fx_kmap*>(km), st);
+        if (rc != FX_OK) return rc;
+        n_ranges = (int)std::max<int64_t>(1, std::min<int64_t>(64, km->n_out / 256));
+        FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * n_ranges, st));
+        const dim3 grid((unsigned)std::min<int64_t>((total + 255) / 256, 1 << 16), (unsigned)n_ranges);
+        ProfScope ps(kProfWgrad, st);
+        if (dt == FX_F32) k_wgrad_scalar<FX_F32><<<grid, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_gout, C_in, C_out, n_ranges, part);
+        else if (dt == FX_F16) k_wgrad_scalar<FX_F16><<<grid, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_gout, C_in, C_out, n_ranges, part);
+        else k_wgrad_scalar<FX_BF16><<<grid, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_gout, C_in, C_out, n_ranges, part);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = launch_reduce(part, n_ranges, total, d_gw, out_dt, st);
+    dev_free(part, st);
+    if (e != hipSuccess) { set_error("weight-gradient launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
+    return FX_OK;
+}

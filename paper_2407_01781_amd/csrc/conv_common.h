@@ -1,0 +1,101 @@
+// Declarations shared by the forward and backward convolution kernels: element types with
+// their MFMA instruction, vector typedefs, and the host-side pieces of the forward path that
+// the backward pass reuses.
+#pragma once
+#include "kmap.h"
+
+#include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
+
+#include <algorithm>
+
+namespace fx {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int kCoutSlice = 64;      // output channels per wave
+constexpr int kProducerWaves = 4;
+constexpr int kConvThreads = 64 * (kTileWaves + kProducerWaves);
+constexpr int kMaxIdBlocks = kTileWaves * kMaxK3Tiled;
+
+// ---------------------------------------------------------------------------------- element types
+template <typename T> struct Elem;
+template <> struct Elem<__bf16> {
+    typedef bf16x8 vec8;
+    static __device__ __forceinline__ f32x16 mfma(vec8 a, vec8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ float to_float(uint16_t bits) { return __uint_as_float((uint32_t)bits << 16); }
+    static __device__ __forceinline__ uint16_t from_float(float f) {  // round to nearest even
+        uint32_t u = __float_as_uint(f);
+        if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        return (uint16_t)(u >> 16);
+    }
+    static __device__ __forceinline__ uint32_t pack2(float a, float b) {  // two RNE conversions, a in the low half
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+        typedef __attribute__((ext_vector_type(2))) float f32x2;
+        const bf16x2 h = __builtin_convertvector(f32x2{a, b}, bf16x2);
+        uint32_t bits;
+        __builtin_memcpy(&bits, &h, 4);
+        return bits;
+    }
+};
+template <> struct Elem<_Float16> {
+    typedef f16x8 vec8;
+    static __device__ __forceinline__ f32x16 mfma(vec8 a, vec8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ float to_float(uint16_t bits) {
+        _Float16 h;
+        __builtin_memcpy(&h, &bits, 2);
+        return (float)h;
+    }
+    static __device__ __forceinline__ uint16_t from_float(float f) {
+        _Float16 h = (_Float16)f;  // v_cvt_f16_f32: round to nearest even
+        uint16_t bits;
+        __builtin_memcpy(&bits, &h, 2);
+        return bits;
+    }
+    static __device__ __forceinline__ uint32_t pack2(float a, float b) {
+        return (uint32_t)from_float(a) | ((uint32_t)from_float(b) << 16);
+    }
+};
+
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+template <int DT>
+__device__ __forceinline__ float load_as_float(const void* p, int64_t i) {
+    if (DT == FX_F32) return reinterpret_cast<const float*>(p)[i];
+    if (DT == FX_F16) return Elem<_Float16>::to_float(reinterpret_cast<const uint16_t*>(p)[i]);
+    return Elem<__bf16>::to_float(reinterpret_cast<const uint16_t*>(p)[i]);
+}
+
+constexpr int kRowBufBytes = (kRowCap + 1) * kRowBytes;           // staged rows + the zero row
+constexpr int kBlockBufBytes = kMaxIdBlocks * kIdBlockElems * 2;
+__device__ __forceinline__ int lds_row_offset(int row, int p) { return (int)(lds_row_code((uint32_t)row) ^ (uint32_t)(p << 4)); }
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// How the packed A-operand fragments are read from the caller's W[K^3][C_in][C_out]:
+//   kWeightsForward        fragment (kappa, cin, cout) = W[kappa][cin][cout]
+//   kWeightsTransposed     fragment (kappa, a, b)      = W[kappa][b][a]            (roles of the channel
+//                          counts swapped: the multiply contracts over W's output channels)
+//   kWeightsMirrored       fragment (kappa, a, b)      = W[K^3-1-kappa][b][a]      (and offsets mirrored)
+enum WeightMode { kWeightsForward = 0, kWeightsTransposed = 1, kWeightsMirrored = 2 };
+
+// Packs the weights (C_in = contracted channels, C_out = produced channels, in the sense of the
+// mode) and zeroes the eight work-list counters behind them.
+void launch_pack_weights(const void* d_w, uint16_t* wp, int K3, int C_in, int C_out, int32_t* counters, int mode,
+                         hipStream_t st);
+
+// The forward multiply-accumulate over a map with the weights read in the given mode: d_out[o,:]
+// = sum over kappa of d_feat[map(o,kappa),:] . Wmode[kappa], C_in channels in, C_out channels out.
+fx_status conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w, int32_t C_in,
+                     int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st, int mode);
+
+}  // namespace fx

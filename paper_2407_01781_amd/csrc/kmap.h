@@ -105,4 +105,6 @@ struct fx_kmap {
 namespace fx {
 // dense [n_out, K3] table for the scalar convolution path, built on first use (not thread-safe)
 fx_status kmap_ensure_dense(fx_kmap* km, hipStream_t st);
+// host copies of the map's statistics (pairs per offset, tiling figures); synchronises the build stream once
+fx_status kmap_fetch_stats(fx_kmap* km);
 }

@@ -856,7 +856,7 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     return FX_OK;
 }
 
-static fx_status kmap_fetch_stats(fx_kmap* km) {
+fx_status fx::kmap_fetch_stats(fx_kmap* km) {
     if (km->stats_valid) return FX_OK;
     hipStream_t st = km->stream;
     unsigned long long* pairs = (unsigned long long*)(km->d_stats + 4);
