@@ -189,6 +189,22 @@ def main():
     torch.cuda.synchronize()
     t_conv_b2b = e0.elapsed_time(e1) / 20
 
+    # ---- backward pass on the same map (not part of `value`): warm, back to back
+    d_gy = torch.randn(out_buf.shape, device="cuda").to(tdt).contiguous()
+
+    def b2b(fn, reps=10):
+        fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    t_dgrad = b2b(lambda: fx.sparse_conv_bwd_data(km, d_gy, d_w))
+    t_wgrad = b2b(lambda: fx.sparse_conv_bwd_weight(km, d_feat, d_gy))
+
     # ---- the paper's timing protocol (Sec. 4.1: one warm-up, five timed runs, mean of the best
     # four), cold = a 768 MiB scratch buffer is overwritten before every run so that neither the
     # L2s nor the 256 MB last-level cache hold the operands, warm = no flush
@@ -267,6 +283,9 @@ def main():
             "mfma_row_utilisation": (pairs / tstats["mfma_rows_issued"]) if tstats["mfma_rows_issued"] else None,
             "staged_rows_per_output": tstats["staged_rows"] / max(n_out, 1),
         },
+        "backward": {"bwd_data_ms": t_dgrad, "bwd_weight_ms": t_wgrad,
+                     "bwd_data_effective_TFLOPs": flops / (t_dgrad * 1e-3) / 1e12,
+                     "bwd_weight_effective_TFLOPs": flops / (t_wgrad * 1e-3) / 1e12},
         "kernels_ms_per_launch": kern_ms,
         "kernels_ms_per_step": per_step_ms,
         "roofline": roof,
