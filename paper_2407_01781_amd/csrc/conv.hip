@@ -8,10 +8,13 @@
 // a block only if one of the 32 has a neighbour there (missing neighbours read a zero row).
 // Nothing is scattered; the write-back is one sequential range per tile.
 //
-// Operand roles: A = packed weights (32 output channels x 16 input channels per instruction),
-// B = gathered features (16 input channels x 32 voxels), D = 32 channels x 32 voxels; the
-// weight rows are permuted so that each lane ends up with 32 consecutive output channels of
-// one voxel.
+// Operand roles in the tile kernel: A = gathered features (32 voxels x 16 input channels per
+// instruction), B = packed weights (16 input channels x 32 output channels), D = 32 voxels x 32
+// channels with the channels across lanes; the two weight tiles of a 64-channel slice interleave
+// the channels (column n of tile t = channel 2n + t), so lane n holds two adjacent channels of
+// every voxel and the 32 lanes of a half-wave store one whole output row at a time.  The gather
+// kernel for strided maps keeps the roles the other way round (weights as A, 32 consecutive
+// channels of one voxel per lane).
 #include "conv_common.h"
 
 namespace fx {
@@ -23,8 +26,13 @@ namespace fx {
 // 32x32 accumulator layout (lane half h, register v -> row 8*(v/4) + 4*h + v%4) a lane's
 // accumulators are then the 32 consecutive channels 32*h .. 32*h+31 (m-tile t = channels
 // 32*h + 16*t + v).
+//
+// Layout kPackInterleaved serves kernels that take the features as the A operand and the weights
+// as B: column n of n-tile t is output channel 2n + t of the slice, so that lane n of an
+// accumulator row holds two adjacent channels (one per n-tile) and the 32 lanes of a half-wave
+// store one whole output row.
 __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wp, int K3, int C_in, int C_out,
-                               int32_t* __restrict__ counters, int mode) {
+                               int32_t* __restrict__ counters, int mode, int layout) {
     if (blockIdx.x == 0 && threadIdx.x < 8) counters[threadIdx.x] = 0;   // the convolution's work-list counters
     const int64_t total = (int64_t)K3 * C_in * C_out;
     const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
@@ -39,18 +47,61 @@ __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restr
         const int kappa = (int)r;
         const int m = lane & 31, kq = lane >> 5;
         const int cin = c * kCinChunk + ks * 16 + kq * 8 + el;
-        const int cout = s * kCoutSlice + 32 * ((m >> 2) & 1) + 16 * mt + 4 * (m >> 3) + (m & 3);
+        const int cout = layout == kPackInterleaved ? s * kCoutSlice + 2 * m + mt
+                                                    : s * kCoutSlice + 32 * ((m >> 2) & 1) + 16 * mt + 4 * (m >> 3) + (m & 3);
         if (mode == kWeightsForward) wp[e] = w[((int64_t)kappa * C_in + cin) * C_out + cout];
         else wp[e] = w[((int64_t)(mode == kWeightsMirrored ? K3 - 1 - kappa : kappa) * C_out + cout) * C_in + cin];
     }
 }
 
 void launch_pack_weights(const void* d_w, uint16_t* wp, int K3, int C_in, int C_out, int32_t* counters, int mode,
-                         hipStream_t st) {
+                         int layout, hipStream_t st) {
     const int64_t total = (int64_t)K3 * C_in * C_out;
     ProfScope ps(kProfPackWeights, st);
     k_pack_weights<<<(unsigned)std::min<int64_t>((total + 255) / 256, 4096), 256, 0, st>>>(
-        (const uint16_t*)d_w, wp, K3, C_in, C_out, counters, mode);
+        (const uint16_t*)d_w, wp, K3, C_in, C_out, counters, mode, layout);
+}
+
+// Write-back of one column block computed with the features as the A operand: register v of
+// accumulator tile t in lane (n, h) is output channel 2n + t of the slice for the block's slot
+// 8*(v/4) + 4*h + v%4.  perm_g points at the block's 32 entries of the tile permutation in LDS
+// (slot -> local output number).  Each store instruction covers two whole output rows.
+typedef __attribute__((address_space(1))) unsigned char global_byte;
+
+template <typename T, bool OUT_F32, bool FULL>
+__device__ __forceinline__ void store_block_rows_impl(const f32x16 (&acc)[2], const uint16_t* perm_g, global_byte* tile_out,
+                                                      uint32_t row_bytes, uint32_t lane_off, int n_valid, int h) {
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const u32x2 lp = *reinterpret_cast<const u32x2*>(perm_g + 8 * b + 4 * h);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t local = (lp[r >> 1] >> (16 * (r & 1))) & 0xFFFFu;
+            if (!FULL && (int)local >= n_valid) continue;
+            global_byte* dst = tile_out + (uint32_t)(__umul24(local, row_bytes) + lane_off);   // 32-bit offset from a wave-uniform base
+            const int v = 4 * b + r;
+            if (OUT_F32) {
+                typedef __attribute__((ext_vector_type(2))) float f32x2;
+                *reinterpret_cast<__attribute__((address_space(1))) f32x2*>(dst) = f32x2{acc[0][v], acc[1][v]};
+            } else {
+                *reinterpret_cast<__attribute__((address_space(1))) uint32_t*>(dst) = Elem<T>::pack2(acc[0][v], acc[1][v]);
+            }
+        }
+    }
+}
+
+// tile_out: first byte of the tile's first output row at the slice's first channel (wave-uniform).
+template <typename T, bool OUT_F32>
+__device__ __forceinline__ void store_block_rows(const f32x16 (&acc)[2], const uint16_t* perm_g, unsigned char* tile_out,
+                                                 int C_out, int n_valid, int n, int h) {
+    const uint32_t esize = OUT_F32 ? 4u : 2u;
+    const uint32_t row_bytes = (uint32_t)C_out * esize, lane_off = 2u * (uint32_t)n * esize;
+    // keep the base in scalar registers: the stores then take it as their scalar address operand
+    const uint64_t bits = reinterpret_cast<uint64_t>(tile_out);
+    const uint32_t lo = (uint32_t)uni((int)(uint32_t)bits), hi = (uint32_t)uni((int)(uint32_t)(bits >> 32));
+    global_byte* base = (global_byte*)(((uint64_t)hi << 32) | lo);
+    if (n_valid == kTileT) store_block_rows_impl<T, OUT_F32, true>(acc, perm_g, base, row_bytes, lane_off, n_valid, h);
+    else store_block_rows_impl<T, OUT_F32, false>(acc, perm_g, base, row_bytes, lane_off, n_valid, h);
 }
 
 #ifdef FX_CONV_TIMING
@@ -80,7 +131,7 @@ struct MetaSlot {
 struct ConvLds {
     unsigned char rows[2][kRowBufBytes];     // 64-byte rows; 16-byte piece p stored at p ^ ((row >> 2) & 3)
     unsigned char blocks[2][kBlockBufBytes]; // id blocks [block][voxel n][group slot], u16
-    uint16_t perm[2][kTileT];
+    uint16_t perm[3][kTileT];                // a ring of three: the write-back of item i reads its entry while item i+1 multiplies
     MetaSlot meta[kMetaSlots];
 };
 static_assert(sizeof(ConvLds) <= 160 * 1024, "LDS budget of one compute unit");
@@ -221,7 +272,7 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)      // k-step outermost: consecutive MFMAs never share an accumulator
 #pragma unroll
-                    for (int mt = 0; mt < 2; ++mt) acc[gi][mt] = Elem<T>::mfma(wcur[mt * 2 + ks], bf[gi][ks], acc[gi][mt]);
+                    for (int mt = 0; mt < 2; ++mt) acc[gi][mt] = Elem<T>::mfma(bf[gi][ks], wcur[mt * 2 + ks], acc[gi][mt]);
             }
             fetch_b(bf[gi], ids_next, gi, q1);
         }
@@ -249,6 +300,33 @@ __device__ __forceinline__ void produce_rows(unsigned char* lds_rows, const Item
             const int64_t gr = r < I.win_n ? (int64_t)I.win_lo + r : (int64_t)my_rows[r - I.win_n];
             const uint16_t* src = feat + gr * C_in + c * kCinChunk + piece * 8;
             __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(lds_rows + s * 1024), 16, 0, 0);
+        }
+    }
+}
+
+// The same with the global row of every slab a lane serves kept in registers: the rows of a tile
+// are the same for all its chunks, so only the first chunk pays the dependent load of the halo list.
+constexpr int kSlabsPerProducer = ((kRowCap + 15) / 16 + kProducerWaves - 1) / kProducerWaves;
+
+__device__ __forceinline__ void resolve_rows(int32_t (&gr)[kSlabsPerProducer], const Item& I, int pwave, int lane,
+                                             const int32_t* __restrict__ tile_rows, int row_stride) {
+    const int32_t* my_rows = tile_rows + I.tile * (int64_t)row_stride;
+#pragma unroll
+    for (int j = 0; j < kSlabsPerProducer; ++j) {
+        const int r = 16 * (pwave + kProducerWaves * j) + (lane >> 2);
+        gr[j] = -1;
+        if (r < I.n_staged) gr[j] = r < I.win_n ? I.win_lo + r : my_rows[r - I.win_n];
+    }
+}
+
+__device__ __forceinline__ void produce_rows_resolved(unsigned char* lds_rows, const int32_t (&gr)[kSlabsPerProducer],
+                                                      int pwave, int lane, const uint16_t* __restrict__ feat, int C_in, int c) {
+    const int piece = (lane & 3) ^ ((lane >> 4) & 3);
+#pragma unroll
+    for (int j = 0; j < kSlabsPerProducer; ++j) {
+        if (gr[j] >= 0) {
+            const uint16_t* src = feat + (int64_t)gr[j] * C_in + c * kCinChunk + piece * 8;
+            __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(lds_rows + (pwave + kProducerWaves * j) * 1024), 16, 0, 0);
         }
     }
 }
@@ -310,7 +388,7 @@ __device__ __forceinline__ int first_offset(uint32_t mask) { return mask ? __ffs
 // requested after the stores would have to wait for them.
 template <typename T, bool OUT_F32, bool GENERAL>
 __device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, const MetaSlot& MN, const Item& I, int phase,
-                                             int mb, int nchunk, int nslice, int wave, int lane,
+                                             int mb, int pb, int nchunk, int nslice, int wave, int lane,
                                              const int32_t* __restrict__ tile_rows, int row_stride,
                                              const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp, int C_in,
                                              int C_out, void* __restrict__ out, typename Elem<T>::vec8 (&wa)[4],
@@ -335,7 +413,6 @@ __device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, cons
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[gi][mt][v] = 0.f;
 
-    int local[NG];
     for (int c = 0; c < nchunk; ++c) {
         // where this wave's weights come from after this chunk
         int w_after0, w_after1;
@@ -360,47 +437,21 @@ __device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, cons
                                      w_after0, w_after1, n, h, I.n_staged, I.win_lo, I.win_n, my_rows, feat, C_in, c);
             FX_TACC(tm[0]);
         }
-        if (c == nchunk - 1) {   // the permutation's half is recycled right after the barrier when there is one chunk
-#pragma unroll
-            for (int gi = 0; gi < NG; ++gi) local[gi] = L.perm[mb][tile_group_of(wave, gi) * kGroup + n];
-        }
         { FX_T0(); __syncthreads(); FX_TACC(tm[1]); }
     }
     FX_T0();
+    unsigned char* tile_out = reinterpret_cast<unsigned char*>(out) +
+                              ((I.tile * kTileT) * C_out + (int64_t)I.slice * kCoutSlice) * (OUT_F32 ? 4 : 2);
 #pragma unroll
-    for (int gi = 0; gi < NG; ++gi) {
-        if (local[gi] >= I.n_valid) continue;
-        const int64_t o = I.tile * kTileT + local[gi];
-        const int64_t col = (int64_t)I.slice * kCoutSlice + 32 * h;
-        if (OUT_F32) {
-            float* dst = reinterpret_cast<float*>(out) + o * C_out + col;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4)
-                    *reinterpret_cast<f32x4*>(dst + 16 * mt + 4 * v4) =
-                        f32x4{acc[gi][mt][4 * v4], acc[gi][mt][4 * v4 + 1], acc[gi][mt][4 * v4 + 2], acc[gi][mt][4 * v4 + 3]};
-        } else {
-            uint16_t* dst = reinterpret_cast<uint16_t*>(out) + o * C_out + col;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int v8 = 0; v8 < 2; ++v8) {
-                    u32x4 pk;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        pk[e] = Elem<T>::pack2(acc[gi][mt][8 * v8 + 2 * e], acc[gi][mt][8 * v8 + 2 * e + 1]);
-                    *reinterpret_cast<u32x4*>(dst + 16 * mt + 8 * v8) = pk;
-                }
-        }
-    }
+    for (int gi = 0; gi < NG; ++gi)
+        store_block_rows<T, OUT_F32>(acc[gi], L.perm[pb] + tile_group_of(wave, gi) * kGroup, tile_out, C_out, I.n_valid, n, h);
     FX_TACC(tm[2]);
 }
 
 // Items whose rows are not all staged in LDS take this path: a real call, so that its registers
 // are allocated apart from the main loop's.
 template <typename T, bool OUT_F32>
-__device__ __noinline__ void consume_item_general(int slot, int phase, int mb, int nchunk, int nslice, int wave, int lane,
+__device__ __noinline__ void consume_item_general(int slot, int phase, int mb, int pb, int nchunk, int nslice, int wave, int lane,
                                                   const int32_t* __restrict__ tile_rows, int row_stride,
                                                   const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp,
                                                   int C_in, int C_out, void* __restrict__ out) {
@@ -412,7 +463,7 @@ __device__ __noinline__ void consume_item_general(int slot, int phase, int mb, i
     vec8 wa[4], wb[4];
     int wa_at = -1, wb_at = -1;
     unsigned long long tm[4] = {0, 0, 0, 0};
-    consume_item<T, OUT_F32, true>(L, M, L.meta[(slot + 1) % kMetaSlots], I, phase, mb, nchunk, nslice, wave, lane, tile_rows,
+    consume_item<T, OUT_F32, true>(L, M, L.meta[(slot + 1) % kMetaSlots], I, phase, mb, pb, nchunk, nslice, wave, lane, tile_rows,
                                    row_stride, feat, wp, C_in, C_out, out, wa, wb, wa_at, wb_at, tm);
 }
 
@@ -464,10 +515,12 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
+        int32_t gr[kSlabsPerProducer];
         {
             const Item cur = item_of(L.meta[0], first, nslice);
             produce_meta(L.blocks[0], L.perm[0], cur, pwave, lane, tile_perm, tile_blocks, block_stride);
-            produce_rows(L.rows[0], cur, pwave, lane, tile_rows, row_stride, feat, C_in, 0);
+            resolve_rows(gr, cur, pwave, lane, tile_rows, row_stride);
+            produce_rows_resolved(L.rows[0], gr, pwave, lane, feat, C_in, 0);
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
@@ -484,15 +537,16 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
             for (int c = 0; c < nchunk; ++c, ++phase) {
                 const int rb = (phase + 1) & 1;
                 if (c != nchunk - 1) {
-                    produce_rows(L.rows[rb], cur, pwave, lane, tile_rows, row_stride, feat, C_in, c + 1);
+                    produce_rows_resolved(L.rows[rb], gr, pwave, lane, feat, C_in, c + 1);
                 } else {
                     const MetaSlot& MN = L.meta[(item_no + 1) % kMetaSlots];
                     const int64_t nwork = slot_work(MN);
                     if (nwork >= 0) {
                         const Item nxt = item_of(MN, nwork, nslice);
                         const int nb = (item_no + 1) & 1;
-                        produce_meta(L.blocks[nb], L.perm[nb], nxt, pwave, lane, tile_perm, tile_blocks, block_stride);
-                        produce_rows(L.rows[rb], nxt, pwave, lane, tile_rows, row_stride, feat, C_in, 0);
+                        produce_meta(L.blocks[nb], L.perm[(item_no + 1) % 3], nxt, pwave, lane, tile_perm, tile_blocks, block_stride);
+                        resolve_rows(gr, nxt, pwave, lane, tile_rows, row_stride);
+                        produce_rows_resolved(L.rows[rb], gr, pwave, lane, feat, C_in, 0);
                     }
                 }
                 if (pwave == 0 && (phase + 2) % nchunk == 0) {   // an item starts two phases from now
@@ -545,13 +599,13 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
             if (work < 0) break;
             const Item cur = item_of(M, work, nslice);
             if (cur.general) {
-                consume_item_general<T, OUT_F32>(slot, phase, item_no & 1, nchunk, nslice, wave, lane, tile_rows, row_stride,
+                consume_item_general<T, OUT_F32>(slot, phase, item_no & 1, item_no % 3, nchunk, nslice, wave, lane, tile_rows, row_stride,
                                                  feat, wp, C_in, C_out, out);
                 wa_at = wb_at = -1;       // nothing is handed over a call
 #pragma unroll
                 for (int f = 0; f < 4; ++f) { wa[f] = vec8{}; wb[f] = vec8{}; }
             } else {
-                consume_item<T, OUT_F32, false>(L, M, L.meta[(item_no + 1) % kMetaSlots], cur, phase, item_no & 1, nchunk, nslice,
+                consume_item<T, OUT_F32, false>(L, M, L.meta[(item_no + 1) % kMetaSlots], cur, phase, item_no & 1, item_no % 3, nchunk, nslice,
                                                 wave, lane, tile_rows, row_stride, feat, wp, C_in, C_out, out, wa, wb, wa_at,
                                                 wb_at, tm);
             }
@@ -776,11 +830,11 @@ fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, 
         const size_t wbytes = sizeof(uint16_t) * (size_t)km->K3 * C_in * C_out;   // a multiple of 64 bytes
         FX_TRY(dev_alloc((void**)&wp, wbytes + 8 * sizeof(int32_t), st));
         int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
-        launch_pack_weights(d_w, wp, km->K3, C_in, C_out, counters, mode, st);
-        hipError_t e = hipGetLastError();
         // strided maps use every input row once: the gather kernel; others: the LDS-staged kernel
         const char* fg = getenv("FVDB_HOTPATH_CONV_GATHER");
         const bool gather = fg ? fg[0] == '1' : km->stride != 1;
+        launch_pack_weights(d_w, wp, km->K3, C_in, C_out, counters, mode, gather ? kPackRows : kPackInterleaved, st);
+        hipError_t e = hipGetLastError();
         if (e == hipSuccess && gather) {
             ProfScope ps(kProfConvGather, st);
             if (in_dt == FX_BF16)

@@ -474,7 +474,7 @@ extern "C" fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_go
         const size_t wbytes = sizeof(uint16_t) * (size_t)km->K3 * C_in * C_out;
         FX_TRY(dev_alloc((void**)&wp, wbytes + 8 * sizeof(int32_t), st));
         int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
-        launch_pack_weights(d_w, wp, km->K3, C_out, C_in, counters, kWeightsTransposed, st);
+        launch_pack_weights(d_w, wp, km->K3, C_out, C_in, counters, kWeightsTransposed, kPackRows, st);
         hipError_t e = hipGetLastError();
         if (e == hipSuccess) {
             const int64_t n_items = km->n_tiles * (int64_t)kGroupsPerTile * (C_in / kCoutSlice);

@@ -88,10 +88,17 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 //   kWeightsMirrored       fragment (kappa, a, b)      = W[K^3-1-kappa][b][a]      (and offsets mirrored)
 enum WeightMode { kWeightsForward = 0, kWeightsTransposed = 1, kWeightsMirrored = 2 };
 
+// Which produced channel a fragment row / column m of tile t holds (within a slice of 64):
+//   kPackRows          32*((m>>2)&1) + 16*t + 4*(m>>3) + (m&3)   weights as the A operand: a lane's accumulators
+//                                                               are 32 consecutive channels of one voxel
+//   kPackInterleaved   2*m + t                                  weights as the B operand: lane m holds two adjacent
+//                                                               channels of the voxel of each accumulator register
+enum PackLayout { kPackRows = 0, kPackInterleaved = 1 };
+
 // Packs the weights (C_in = contracted channels, C_out = produced channels, in the sense of the
 // mode) and zeroes the eight work-list counters behind them.
 void launch_pack_weights(const void* d_w, uint16_t* wp, int K3, int C_in, int C_out, int32_t* counters, int mode,
-                         hipStream_t st);
+                         int layout, hipStream_t st);
 
 // The forward multiply-accumulate over a map with the weights read in the given mode: d_out[o,:]
 // = sum over kappa of d_feat[map(o,kappa),:] . Wmode[kappa], C_in channels in, C_out channels out.

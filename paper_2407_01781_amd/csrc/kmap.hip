@@ -222,6 +222,7 @@ struct PackLds {
         PackScratch s;
     } u;
     uint32_t group_mask[kGroupsPerTile];
+    uint32_t group_src[kGroupsPerTile];      // column block of the mask-sorted order that takes each final position
     uint32_t wave_mask[kTileWaves];
     uint32_t wave_block0[kTileWaves];
     uint32_t wave_sums[kPackWaves];
@@ -551,11 +552,32 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
         if (direct) S.slot_base[tid] = base;
         n_list = direct ? total : (uint32_t)n_halo;
     }
+    uint32_t my_gm = 0;
     if (tid < kGroupsPerTile) {
-        uint32_t gm = 0;
-        for (int n = 0; n < kGroup; ++n) gm |= S.slot_mask[S.key[tid * kGroup + n]];
-        L.group_mask[tid] = gm;
+        for (int n = 0; n < kGroup; ++n) my_gm |= S.slot_mask[S.key[tid * kGroup + n]];
+        L.group_mask[tid] = my_gm;
     }
+    __syncthreads();
+    // Deal the column blocks to the consumer waves of the convolution by cost (offsets present =
+    // multiplies issued): rank the blocks by cost, heaviest first, and deal the ranks to the waves
+    // in serpentine order (0 1 2 3 3 2 1 0 ...), which evens out the sums.  Position
+    // tile_group_of(w, gi) of the final order takes block group_src[...] of the sorted order.
+    if (tid < kGroupsPerTile) {
+        const int c = __popc(my_gm);
+        int rank = 0;
+        for (int g = 0; g < kGroupsPerTile; ++g) {
+            const int cg = __popc(L.group_mask[g]);
+            rank += (cg > c) || (cg == c && g < tid);
+        }
+        const int gi = rank / kTileWaves, r = rank % kTileWaves;
+        L.group_src[tile_group_of((gi & 1) ? kTileWaves - 1 - r : r, gi)] = (uint32_t)tid;
+    }
+    __syncthreads();
+    const uint32_t dealt = S.key[L.group_src[tid / kGroup] * kGroup + tid % kGroup];   // slot at final position tid
+    if (tid < kGroupsPerTile) my_gm = L.group_mask[L.group_src[tid]];
+    __syncthreads();
+    S.key[tid] = dealt;
+    if (tid < kGroupsPerTile) L.group_mask[tid] = my_gm;
     __syncthreads();
     if (tid == 0) {
         int run = 0, pairs = 0;
@@ -592,7 +614,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     }
     if (tid < kGroupsPerTile) H->group_mask[tid] = L.group_mask[tid];
     if (tid < kTileWaves) { H->wave_mask[tid] = L.wave_mask[tid]; H->wave_block0[tid] = L.wave_block0[tid]; }
-    tile_perm[tile * kTileT + tid] = (uint16_t)(sorted & 511u);
+    tile_perm[tile * kTileT + tid] = (uint16_t)dealt;
     if (direct) {
         uint32_t pos = S.slot_base[tid];
         for (int kappa = 0; kappa < K3; ++kappa) {
