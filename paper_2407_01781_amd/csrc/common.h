@@ -38,6 +38,9 @@ void dev_free(void* p, hipStream_t s);
 // in flight until the caller's next synchronisation on the same stream.
 fx_status host_staging(void** p, size_t bytes, int area = 0);
 
+// compute units of the current device (256 on an MI355X; 256 if the query fails)
+int compute_units();
+
 // ------------------------------------------------------------------ per-kernel timing
 // When enabled (fx_profile_enable), every kernel launch of the library is bracketed by a pair
 // of hipEvents on the launch stream; fx_profile_read sums the elapsed times per slot.

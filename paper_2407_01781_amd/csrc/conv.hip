@@ -31,14 +31,17 @@ namespace fx {
 // as B: column n of n-tile t is output channel 2n + t of the slice, so that lane n of an
 // accumulator row holds two adjacent channels (one per n-tile) and the 32 lanes of a half-wave
 // store one whole output row.
-__global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wp, int K3, int C_in, int C_out,
+template <typename E>   // uint16_t or uint32_t: the bits of one element
+__global__ void k_pack_weights(const E* __restrict__ w, E* __restrict__ wp, int K3, int C_in, int C_out,
                                int32_t* __restrict__ counters, int mode, int layout) {
     if (blockIdx.x == 0 && threadIdx.x < 8) counters[threadIdx.x] = 0;   // the convolution's work-list counters
-    const int64_t total = (int64_t)K3 * C_in * C_out;
-    const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
+    constexpr int EPL = 16 / (int)sizeof(E);     // elements per lane fragment
+    constexpr int kChunk = 4 * EPL;              // input channels per 64-byte row chunk
+    const int nchunk = C_in / kChunk, nslice = (C_out + kCoutSlice - 1) / kCoutSlice;
+    const int64_t total = (int64_t)K3 * C_in * nslice * kCoutSlice;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
         int64_t r = e;
-        const int el = (int)(r & 7); r >>= 3;
+        const int el = (int)(r % EPL); r /= EPL;
         const int lane = (int)(r & 63); r >>= 6;
         const int ks = (int)(r & 1); r >>= 1;
         const int mt = (int)(r & 1); r >>= 1;
@@ -46,20 +49,31 @@ __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restr
         const int c = (int)(r % nchunk); r /= nchunk;
         const int kappa = (int)r;
         const int m = lane & 31, kq = lane >> 5;
-        const int cin = c * kCinChunk + ks * 16 + kq * 8 + el;
+        const int cin = c * kChunk + ks * 2 * EPL + kq * EPL + el;
         const int cout = layout == kPackInterleaved ? s * kCoutSlice + 2 * m + mt
                                                     : s * kCoutSlice + 32 * ((m >> 2) & 1) + 16 * mt + 4 * (m >> 3) + (m & 3);
-        if (mode == kWeightsForward) wp[e] = w[((int64_t)kappa * C_in + cin) * C_out + cout];
-        else wp[e] = w[((int64_t)(mode == kWeightsMirrored ? K3 - 1 - kappa : kappa) * C_out + cout) * C_in + cin];
+        E v = 0;
+        if (cout < C_out) {
+            if (mode == kWeightsForward) v = w[((int64_t)kappa * C_in + cin) * C_out + cout];
+            else v = w[((int64_t)(mode == kWeightsMirrored ? K3 - 1 - kappa : kappa) * C_out + cout) * C_in + cin];
+        }
+        wp[e] = v;
     }
 }
 
-void launch_pack_weights(const void* d_w, uint16_t* wp, int K3, int C_in, int C_out, int32_t* counters, int mode,
-                         int layout, hipStream_t st) {
-    const int64_t total = (int64_t)K3 * C_in * C_out;
+size_t packed_weight_bytes(int K3, int C_in, int C_out, int elem_bytes) {
+    return (size_t)elem_bytes * K3 * C_in * ((C_out + kCoutSlice - 1) / kCoutSlice) * kCoutSlice;
+}
+
+void launch_pack_weights(const void* d_w, void* wp, int K3, int C_in, int C_out, int elem_bytes, int32_t* counters,
+                         int mode, int layout, hipStream_t st) {
+    const int64_t total = (int64_t)(packed_weight_bytes(K3, C_in, C_out, elem_bytes) / elem_bytes);
+    const unsigned nb = (unsigned)std::min<int64_t>((total + 255) / 256, 4096);
     ProfScope ps(kProfPackWeights, st);
-    k_pack_weights<<<(unsigned)std::min<int64_t>((total + 255) / 256, 4096), 256, 0, st>>>(
-        (const uint16_t*)d_w, wp, K3, C_in, C_out, counters, mode, layout);
+    if (elem_bytes == 2)
+        k_pack_weights<uint16_t><<<nb, 256, 0, st>>>((const uint16_t*)d_w, (uint16_t*)wp, K3, C_in, C_out, counters, mode, layout);
+    else
+        k_pack_weights<uint32_t><<<nb, 256, 0, st>>>((const uint32_t*)d_w, (uint32_t*)wp, K3, C_in, C_out, counters, mode, layout);
 }
 
 // Write-back of one column block computed with the features as the A operand: register v of
@@ -70,14 +84,14 @@ typedef __attribute__((address_space(1))) unsigned char global_byte;
 
 template <typename T, bool OUT_F32, bool FULL>
 __device__ __forceinline__ void store_block_rows_impl(const f32x16 (&acc)[2], const uint16_t* perm_g, global_byte* tile_out,
-                                                      uint32_t row_bytes, uint32_t lane_off, int n_valid, int h) {
+                                                      uint32_t row_bytes, uint32_t lane_off, int n_valid, bool lane_ok, int h) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         const u32x2 lp = *reinterpret_cast<const u32x2*>(perm_g + 8 * b + 4 * h);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const uint32_t local = (lp[r >> 1] >> (16 * (r & 1))) & 0xFFFFu;
-            if (!FULL && (int)local >= n_valid) continue;
+            if (!FULL && ((int)local >= n_valid || !lane_ok)) continue;
             global_byte* dst = tile_out + (uint32_t)(__umul24(local, row_bytes) + lane_off);   // 32-bit offset from a wave-uniform base
             const int v = 4 * b + r;
             if (OUT_F32) {
@@ -90,18 +104,21 @@ __device__ __forceinline__ void store_block_rows_impl(const f32x16 (&acc)[2], co
     }
 }
 
-// tile_out: first byte of the tile's first output row at the slice's first channel (wave-uniform).
+// tile_out: first byte of the tile's first output row at the slice's first channel (wave-uniform);
+// cols: channels of the slice that exist (64, or fewer in the last slice of a padded channel count).
 template <typename T, bool OUT_F32>
 __device__ __forceinline__ void store_block_rows(const f32x16 (&acc)[2], const uint16_t* perm_g, unsigned char* tile_out,
-                                                 int C_out, int n_valid, int n, int h) {
+                                                 int C_out, int cols, int n_valid, int n, int h) {
     const uint32_t esize = OUT_F32 ? 4u : 2u;
     const uint32_t row_bytes = (uint32_t)C_out * esize, lane_off = 2u * (uint32_t)n * esize;
     // keep the base in scalar registers: the stores then take it as their scalar address operand
     const uint64_t bits = reinterpret_cast<uint64_t>(tile_out);
     const uint32_t lo = (uint32_t)uni((int)(uint32_t)bits), hi = (uint32_t)uni((int)(uint32_t)(bits >> 32));
     global_byte* base = (global_byte*)(((uint64_t)hi << 32) | lo);
-    if (n_valid == kTileT) store_block_rows_impl<T, OUT_F32, true>(acc, perm_g, base, row_bytes, lane_off, n_valid, h);
-    else store_block_rows_impl<T, OUT_F32, false>(acc, perm_g, base, row_bytes, lane_off, n_valid, h);
+    if (n_valid == kTileT && cols == kCoutSlice)
+        store_block_rows_impl<T, OUT_F32, true>(acc, perm_g, base, row_bytes, lane_off, n_valid, true, h);
+    else
+        store_block_rows_impl<T, OUT_F32, false>(acc, perm_g, base, row_bytes, lane_off, n_valid, 2 * n < cols, h);
 }
 
 #ifdef FX_CONV_TIMING
@@ -187,8 +204,8 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
                                              uint32_t lane_off, int w_base, int w_kappa_stride, typename Elem<T>::vec8 (&wa)[4],
                                              typename Elem<T>::vec8 (&wb)[4], int& wa_at, int& wb_at, int w_after0,
                                              int w_after1, int n, int h, int n_staged, int win_lo, int win_n,
-                                             const int32_t* __restrict__ my_rows, const uint16_t* __restrict__ feat,
-                                             int C_in, int c) {
+                                             const int32_t* __restrict__ my_rows, const unsigned char* __restrict__ feat,
+                                             int64_t pitch, int c) {
     typedef typename Elem<T>::vec8 vec8;
     constexpr int NG = kGroupsPerWave;
     const int n_off = __popc(wave_mask);
@@ -232,9 +249,9 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
             if (__any(from_global)) {
                 if (from_global) {
                     const int64_t gr = id < (uint32_t)win_n ? (int64_t)win_lo + id : (int64_t)my_rows[id - win_n];
-                    const uint16_t* src = feat + gr * C_in + c * kCinChunk + h * 8;
+                    const unsigned char* src = feat + gr * pitch + c * kRowBytes + h * 16;
                     bf[0] = *reinterpret_cast<const vec8*>(src);
-                    bf[1] = *reinterpret_cast<const vec8*>(src + 16);
+                    bf[1] = *reinterpret_cast<const vec8*>(src + 32);
                 }
             }
         } else {   // id = lds_row_code(row): 16-byte piece p of the row sits at id ^ (p << 4); pieces h and h + 2
@@ -272,7 +289,7 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)      // k-step outermost: consecutive MFMAs never share an accumulator
 #pragma unroll
-                    for (int mt = 0; mt < 2; ++mt) acc[gi][mt] = Elem<T>::mfma(bf[gi][ks], wcur[mt * 2 + ks], acc[gi][mt]);
+                    for (int mt = 0; mt < 2; ++mt) acc[gi][mt] = Elem<T>::mma(bf[gi][ks], wcur[mt * 2 + ks], acc[gi][mt]);
             }
             fetch_b(bf[gi], ids_next, gi, q1);
         }
@@ -290,7 +307,7 @@ __device__ __forceinline__ void offsets_loop(const unsigned char* lds_rows, cons
 // memory straight into LDS; lane l of a slab load writes the 16 bytes at slab + 16*l.
 __device__ __forceinline__ void produce_rows(unsigned char* lds_rows, const Item& I, int pwave, int lane,
                                              const int32_t* __restrict__ tile_rows, int row_stride,
-                                             const uint16_t* __restrict__ feat, int C_in, int c) {
+                                             const unsigned char* __restrict__ feat, int64_t pitch, int c) {
     const int32_t* my_rows = tile_rows + I.tile * (int64_t)row_stride;
     const int n_slabs = (I.n_staged + 15) >> 4;
     const int piece = (lane & 3) ^ ((lane >> 4) & 3);   // stored position lane&3 holds piece (lane&3) ^ ((row >> 2) & 3)
@@ -298,7 +315,7 @@ __device__ __forceinline__ void produce_rows(unsigned char* lds_rows, const Item
         const int r = 16 * s + (lane >> 2);
         if (r < I.n_staged) {
             const int64_t gr = r < I.win_n ? (int64_t)I.win_lo + r : (int64_t)my_rows[r - I.win_n];
-            const uint16_t* src = feat + gr * C_in + c * kCinChunk + piece * 8;
+            const unsigned char* src = feat + gr * pitch + c * kRowBytes + piece * 16;
             __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(lds_rows + s * 1024), 16, 0, 0);
         }
     }
@@ -320,12 +337,13 @@ __device__ __forceinline__ void resolve_rows(int32_t (&gr)[kSlabsPerProducer], c
 }
 
 __device__ __forceinline__ void produce_rows_resolved(unsigned char* lds_rows, const int32_t (&gr)[kSlabsPerProducer],
-                                                      int pwave, int lane, const uint16_t* __restrict__ feat, int C_in, int c) {
+                                                      int pwave, int lane, const unsigned char* __restrict__ feat,
+                                                      int64_t pitch, int c) {
     const int piece = (lane & 3) ^ ((lane >> 4) & 3);
 #pragma unroll
     for (int j = 0; j < kSlabsPerProducer; ++j) {
         if (gr[j] >= 0) {
-            const uint16_t* src = feat + (int64_t)gr[j] * C_in + c * kCinChunk + piece * 8;
+            const unsigned char* src = feat + (int64_t)gr[j] * pitch + c * kRowBytes + piece * 16;
             __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(lds_rows + (pwave + kProducerWaves * j) * 1024), 16, 0, 0);
         }
     }
@@ -390,8 +408,8 @@ template <typename T, bool OUT_F32, bool GENERAL>
 __device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, const MetaSlot& MN, const Item& I, int phase,
                                              int mb, int pb, int nchunk, int nslice, int wave, int lane,
                                              const int32_t* __restrict__ tile_rows, int row_stride,
-                                             const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp, int C_in,
-                                             int C_out, void* __restrict__ out, typename Elem<T>::vec8 (&wa)[4],
+                                             const unsigned char* __restrict__ feat, const unsigned char* __restrict__ wp,
+                                             int64_t pitch, int C_out, void* __restrict__ out, typename Elem<T>::vec8 (&wa)[4],
                                              typename Elem<T>::vec8 (&wb)[4], int& wa_at, int& wb_at,
                                              unsigned long long (&tm)[4]) {
     typedef typename Elem<T>::vec8 vec8;
@@ -434,7 +452,7 @@ __device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, cons
             offsets_loop<T, GENERAL>(L.rows[(phase + c) & 1], L.blocks[mb], acc, gmask, wave_mask, wave_block0,
                                      reinterpret_cast<const vec8*>(wp), (uint32_t)lane * 16u,
                                      w_frag(nslice, w_kappa_stride, I.slice, c, 0), w_kappa_stride, wa, wb, wa_at, wb_at,
-                                     w_after0, w_after1, n, h, I.n_staged, I.win_lo, I.win_n, my_rows, feat, C_in, c);
+                                     w_after0, w_after1, n, h, I.n_staged, I.win_lo, I.win_n, my_rows, feat, pitch, c);
             FX_TACC(tm[0]);
         }
         { FX_T0(); __syncthreads(); FX_TACC(tm[1]); }
@@ -444,7 +462,8 @@ __device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, cons
                               ((I.tile * kTileT) * C_out + (int64_t)I.slice * kCoutSlice) * (OUT_F32 ? 4 : 2);
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi)
-        store_block_rows<T, OUT_F32>(acc[gi], L.perm[pb] + tile_group_of(wave, gi) * kGroup, tile_out, C_out, I.n_valid, n, h);
+        store_block_rows<T, OUT_F32>(acc[gi], L.perm[pb] + tile_group_of(wave, gi) * kGroup, tile_out, C_out,
+                                     min(kCoutSlice, C_out - I.slice * kCoutSlice), I.n_valid, n, h);
     FX_TACC(tm[2]);
 }
 
@@ -453,8 +472,8 @@ __device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, cons
 template <typename T, bool OUT_F32>
 __device__ __noinline__ void consume_item_general(int slot, int phase, int mb, int pb, int nchunk, int nslice, int wave, int lane,
                                                   const int32_t* __restrict__ tile_rows, int row_stride,
-                                                  const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp,
-                                                  int C_in, int C_out, void* __restrict__ out) {
+                                                  const unsigned char* __restrict__ feat, const unsigned char* __restrict__ wp,
+                                                  int64_t pitch, int C_out, void* __restrict__ out) {
     typedef typename Elem<T>::vec8 vec8;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     ConvLds& L = *reinterpret_cast<ConvLds*>(lds_raw);
@@ -464,7 +483,7 @@ __device__ __noinline__ void consume_item_general(int slot, int phase, int mb, i
     int wa_at = -1, wb_at = -1;
     unsigned long long tm[4] = {0, 0, 0, 0};
     consume_item<T, OUT_F32, true>(L, M, L.meta[(slot + 1) % kMetaSlots], I, phase, mb, pb, nchunk, nslice, wave, lane, tile_rows,
-                                   row_stride, feat, wp, C_in, C_out, out, wa, wb, wa_at, wb_at, tm);
+                                   row_stride, feat, wp, pitch, C_out, out, wa, wb, wa_at, wb_at, tm);
 }
 
 // Persistent workgroups, one per compute unit.  Work items (tile of 512 consecutive outputs x
@@ -485,13 +504,14 @@ __global__ void __launch_bounds__(kConvThreads, 1)
 k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
             const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
             int block_stride, int64_t n_work, int per_xcd, int32_t* __restrict__ counters,
-            const uint16_t* __restrict__ feat, const uint16_t* __restrict__ wp, int C_in, int C_out,
+            const unsigned char* __restrict__ feat, const unsigned char* __restrict__ wp, int C_in, int C_out,
             void* __restrict__ out) {
     typedef typename Elem<T>::vec8 vec8;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     ConvLds& L = *reinterpret_cast<ConvLds*>(lds_raw);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
+    const int64_t pitch = (int64_t)C_in * Elem<T>::kBytes;                      // bytes per feature row
+    const int nchunk = (int)(pitch / kRowBytes), nslice = (C_out + kCoutSlice - 1) / kCoutSlice;
 
     // workgroup b runs on XCD b % 8 (round-robin dispatch)
     const int xcd = blockIdx.x & 7, in_xcd = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
@@ -520,7 +540,7 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
             const Item cur = item_of(L.meta[0], first, nslice);
             produce_meta(L.blocks[0], L.perm[0], cur, pwave, lane, tile_perm, tile_blocks, block_stride);
             resolve_rows(gr, cur, pwave, lane, tile_rows, row_stride);
-            produce_rows_resolved(L.rows[0], gr, pwave, lane, feat, C_in, 0);
+            produce_rows_resolved(L.rows[0], gr, pwave, lane, feat, pitch, 0);
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
@@ -537,7 +557,7 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
             for (int c = 0; c < nchunk; ++c, ++phase) {
                 const int rb = (phase + 1) & 1;
                 if (c != nchunk - 1) {
-                    produce_rows_resolved(L.rows[rb], gr, pwave, lane, feat, C_in, c + 1);
+                    produce_rows_resolved(L.rows[rb], gr, pwave, lane, feat, pitch, c + 1);
                 } else {
                     const MetaSlot& MN = L.meta[(item_no + 1) % kMetaSlots];
                     const int64_t nwork = slot_work(MN);
@@ -546,7 +566,7 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
                         const int nb = (item_no + 1) & 1;
                         produce_meta(L.blocks[nb], L.perm[(item_no + 1) % 3], nxt, pwave, lane, tile_perm, tile_blocks, block_stride);
                         resolve_rows(gr, nxt, pwave, lane, tile_rows, row_stride);
-                        produce_rows_resolved(L.rows[rb], gr, pwave, lane, feat, C_in, 0);
+                        produce_rows_resolved(L.rows[rb], gr, pwave, lane, feat, pitch, 0);
                     }
                 }
                 if (pwave == 0 && (phase + 2) % nchunk == 0) {   // an item starts two phases from now
@@ -600,13 +620,13 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
             const Item cur = item_of(M, work, nslice);
             if (cur.general) {
                 consume_item_general<T, OUT_F32>(slot, phase, item_no & 1, item_no % 3, nchunk, nslice, wave, lane, tile_rows, row_stride,
-                                                 feat, wp, C_in, C_out, out);
+                                                 feat, wp, pitch, C_out, out);
                 wa_at = wb_at = -1;       // nothing is handed over a call
 #pragma unroll
                 for (int f = 0; f < 4; ++f) { wa[f] = vec8{}; wb[f] = vec8{}; }
             } else {
                 consume_item<T, OUT_F32, false>(L, M, L.meta[(item_no + 1) % kMetaSlots], cur, phase, item_no & 1, item_no % 3, nchunk, nslice,
-                                                wave, lane, tile_rows, row_stride, feat, wp, C_in, C_out, out, wa, wb, wa_at,
+                                                wave, lane, tile_rows, row_stride, feat, wp, pitch, C_out, out, wa, wb, wa_at,
                                                 wb_at, tm);
             }
             ++n_items;
@@ -771,6 +791,60 @@ __global__ void k_conv_scalar(const int32_t* __restrict__ nbmap, int64_t n_out, 
     }
 }
 
+// The same sum with four output channels per thread and four input channels per load (channel
+// counts that are multiples of 4): one 16-byte feature load and four 16-byte
+// weight loads feed 16 multiply-adds, a sixth of the loads of the kernel above.  The sum over the
+// input channels of one offset keeps the order ci = 0, 1, 2, ... of the one-channel kernel.
+template <int DT, bool OUT_F32>
+__global__ void k_conv_scalar4(const int32_t* __restrict__ nbmap, int64_t n_out, int K3, const void* __restrict__ feat,
+                               const void* __restrict__ w, int C_in, int C_out, void* __restrict__ out, int mode) {
+    const int q_out = C_out / 4;
+    const int64_t total = n_out * q_out;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t o = e / q_out;
+        const int co = (int)(e - o * q_out) * 4;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int kappa = 0; kappa < K3; ++kappa) {
+            const int32_t in = nbmap[o * K3 + kappa];
+            if (in < 0) continue;
+            const int64_t fb = (int64_t)in * C_in;
+            if (mode == kWeightsForward) {
+                const int64_t wb = (int64_t)kappa * C_in * C_out + co;
+                for (int ci = 0; ci < C_in; ci += 4) {
+                    const f32x4 x = load4_as_float<DT>(feat, fb + ci);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const f32x4 wr = load4_as_float<DT>(w, wb + (int64_t)(ci + j) * C_out);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[v] = fmaf(x[j], wr[v], acc[v]);
+                    }
+                }
+            } else {   // W[kappa'][co][ci]: the four contracted channels of a produced channel are adjacent
+                const int64_t wb = ((int64_t)(mode == kWeightsMirrored ? K3 - 1 - kappa : kappa) * C_out + co) * C_in;
+                for (int ci = 0; ci < C_in; ci += 4) {
+                    const f32x4 x = load4_as_float<DT>(feat, fb + ci);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const f32x4 wr = load4_as_float<DT>(w, wb + (int64_t)v * C_in + ci);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[v] = fmaf(x[j], wr[j], acc[v]);
+                    }
+                }
+            }
+        }
+        const int64_t at = o * C_out + co;
+        if (OUT_F32) {
+            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + at) = acc;
+        } else if (DT == FX_F16) {
+            *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + at) =
+                u32x2{Elem<_Float16>::pack2(acc[0], acc[1]), Elem<_Float16>::pack2(acc[2], acc[3])};
+        } else {
+            *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + at) =
+                u32x2{Elem<__bf16>::pack2(acc[0], acc[1]), Elem<__bf16>::pack2(acc[2], acc[3])};
+        }
+    }
+}
+
 template <typename T, bool OUT_F32>
 static hipError_t launch_mfma(const fx_kmap* km, const void* feat, const void* wp, int32_t* counters, int C_in, int C_out,
                               void* out, hipStream_t st) {
@@ -778,22 +852,16 @@ static hipError_t launch_mfma(const fx_kmap* km, const void* feat, const void* w
     hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<T, OUT_F32>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
-        if (n_cu <= 0) n_cu = 256;
-    }
-    const int64_t n_work = km->n_tiles * (int64_t)(C_out / kCoutSlice);
+    const int n_cu = compute_units();
+    const int64_t n_work = km->n_tiles * (int64_t)((C_out + kCoutSlice - 1) / kCoutSlice);
     const int per_xcd = (int)((n_work + 7) / 8);
     // one workgroup per compute unit, a multiple of 8 (one share per XCD), no more than the work needs
     int grid = std::max(8, (n_cu / 8) * 8);
     grid = (int)std::min<int64_t>(grid, (int64_t)8 * per_xcd);
     k_conv_mfma<T, OUT_F32><<<grid, kConvThreads, lds, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,
                                                              km->row_stride, km->d_tile_blocks, km->block_stride, n_work,
-                                                             per_xcd, counters, (const uint16_t*)feat,
-                                                             (const uint16_t*)wp, C_in, C_out, out);
+                                                             per_xcd, counters, (const unsigned char*)feat,
+                                                             (const unsigned char*)wp, C_in, C_out, out);
     return hipGetLastError();
 }
 
@@ -823,17 +891,26 @@ fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, 
                          int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st, int mode) {
     const bool out_f32 = (out_dt == FX_F32);
     const char* force = getenv("FVDB_HOTPATH_FORCE_SCALAR");
-    const bool mfma = in_dt != FX_F32 && km->n_tiles > 0 && C_in % kCinChunk == 0 && C_out % kCoutSlice == 0 &&
+    const int esize = in_dt == FX_F32 ? 4 : 2;
+    // The tile kernel takes input rows in 64-byte chunks (32 channels of a 16-bit type, 16 of fp32) and
+    // pads the produced channels to 64 with zero weights; the gather kernel for strided maps needs whole
+    // 64-channel slices of a 16-bit type.  Everything else is left to the scalar kernel.
+    // fp32 multiplies at 1/16 of the 16-bit rate on the matrix units, so a grid of few tiles (one
+    // workgroup each) is served faster by the scalar kernel spread over the whole chip
+    const int64_t n_items = km->n_tiles * (int64_t)((C_out + kCoutSlice - 1) / kCoutSlice);
+    const char* ft = getenv("FVDB_HOTPATH_FP32_TILES");      // "1": fp32 takes the tile kernel at any size (tests)
+    const bool mfma = km->n_tiles > 0 && ((int64_t)C_in * esize) % kRowBytes == 0 && C_out % 2 == 0 &&
+                      (in_dt != FX_F32 || n_items >= compute_units() / 2 || (ft && ft[0] == '1')) &&
                       !(force && force[0] == '1');
     if (mfma) {
-        uint16_t* wp = nullptr;
-        const size_t wbytes = sizeof(uint16_t) * (size_t)km->K3 * C_in * C_out;   // a multiple of 64 bytes
-        FX_TRY(dev_alloc((void**)&wp, wbytes + 8 * sizeof(int32_t), st));
+        void* wp = nullptr;
+        const size_t wbytes = packed_weight_bytes(km->K3, C_in, C_out, esize);   // a multiple of 64 bytes
+        FX_TRY(dev_alloc(&wp, wbytes + 8 * sizeof(int32_t), st));
         int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
         // strided maps use every input row once: the gather kernel; others: the LDS-staged kernel
         const char* fg = getenv("FVDB_HOTPATH_CONV_GATHER");
-        const bool gather = fg ? fg[0] == '1' : km->stride != 1;
-        launch_pack_weights(d_w, wp, km->K3, C_in, C_out, counters, mode, gather ? kPackRows : kPackInterleaved, st);
+        const bool gather = (fg ? fg[0] == '1' : km->stride != 1) && in_dt != FX_F32 && C_out % kCoutSlice == 0;
+        launch_pack_weights(d_w, wp, km->K3, C_in, C_out, esize, counters, mode, gather ? kPackRows : kPackInterleaved, st);
         hipError_t e = hipGetLastError();
         if (e == hipSuccess && gather) {
             ProfScope ps(kProfConvGather, st);
@@ -845,7 +922,9 @@ fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, 
                             : launch_gather<_Float16, false>(km, d_feat, wp, C_in, C_out, d_out, st);
         } else if (e == hipSuccess) {
             ProfScope ps(kProfConvMfma, st);
-            if (in_dt == FX_BF16)
+            if (in_dt == FX_F32)
+                e = launch_mfma<float, true>(km, d_feat, wp, counters, C_in, C_out, d_out, st);
+            else if (in_dt == FX_BF16)
                 e = out_f32 ? launch_mfma<__bf16, true>(km, d_feat, wp, counters, C_in, C_out, d_out, st)
                             : launch_mfma<__bf16, false>(km, d_feat, wp, counters, C_in, C_out, d_out, st);
             else
@@ -857,12 +936,17 @@ fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, 
         return FX_OK;
     }
     FX_TRY(kmap_ensure_dense(const_cast<fx_kmap*>(km), st));
-    const int64_t total = km->n_out * C_out;
+    const bool four = C_in % 4 == 0 && C_out % 4 == 0;
+    const int64_t total = km->n_out * (four ? C_out / 4 : C_out);
     const unsigned nb = (unsigned)std::min<int64_t>((total + 255) / 256, 1 << 20);
 #define FX_SCALAR(DT)                                                                                            \
     do {                                                                                                         \
-        if (out_f32) k_conv_scalar<DT, true><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_w,    \
-                                                                 C_in, C_out, d_out, mode);                      \
+        if (four && out_f32) k_conv_scalar4<DT, true><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, \
+                                                                          d_w, C_in, C_out, d_out, mode);        \
+        else if (four) k_conv_scalar4<DT, false><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_w, \
+                                                                     C_in, C_out, d_out, mode);                  \
+        else if (out_f32) k_conv_scalar<DT, true><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_w, \
+                                                                      C_in, C_out, d_out, mode);                 \
         else k_conv_scalar<DT, false><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_w, C_in,     \
                                                           C_out, d_out, mode);                                   \
     } while (0)

@@ -414,17 +414,6 @@ __global__ void k_wgrad_scalar(const int32_t* __restrict__ nbmap, int64_t n_out,
     }
 }
 
-static int compute_units() {
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
-        if (n_cu <= 0) n_cu = 256;
-    }
-    return n_cu;
-}
-
 static hipError_t launch_reduce(const float* part, int n_ranges, int64_t total, void* gw, fx_dtype out_dt, hipStream_t st) {
     const unsigned nb = (unsigned)std::min<int64_t>((total + 255) / 256, 1 << 16);
     ProfScope ps(kProfWgradReduce, st);
@@ -474,7 +463,7 @@ extern "C" fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_go
         const size_t wbytes = sizeof(uint16_t) * (size_t)km->K3 * C_in * C_out;
         FX_TRY(dev_alloc((void**)&wp, wbytes + 8 * sizeof(int32_t), st));
         int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
-        launch_pack_weights(d_w, wp, km->K3, C_out, C_in, counters, kWeightsTransposed, kPackRows, st);
+        launch_pack_weights(d_w, wp, km->K3, C_out, C_in, 2, counters, kWeightsTransposed, kPackRows, st);
         hipError_t e = hipGetLastError();
         if (e == hipSuccess) {
             const int64_t n_items = km->n_tiles * (int64_t)kGroupsPerTile * (C_in / kCoutSlice);

@@ -24,9 +24,14 @@ constexpr int kConvThreads = 64 * (kTileWaves + kProducerWaves);
 constexpr int kMaxIdBlocks = kTileWaves * kMaxK3Tiled;
 
 // ---------------------------------------------------------------------------------- element types
+// vec8 is the 16-byte operand fragment of a lane (8 values of a 16-bit type, 4 of fp32); mma
+// multiplies one fragment pair into a 32x32 accumulator tile (one instruction with k = 16 for the
+// 16-bit types, four with k = 2 for fp32, whose products are true fp32 products).
 template <typename T> struct Elem;
 template <> struct Elem<__bf16> {
     typedef bf16x8 vec8;
+    static constexpr int kBytes = 2;
+    static __device__ __forceinline__ f32x16 mma(vec8 a, vec8 b, f32x16 c) { return mfma(a, b, c); }
     static __device__ __forceinline__ f32x16 mfma(vec8 a, vec8 b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
     }
@@ -48,6 +53,8 @@ template <> struct Elem<__bf16> {
 };
 template <> struct Elem<_Float16> {
     typedef f16x8 vec8;
+    static constexpr int kBytes = 2;
+    static __device__ __forceinline__ f32x16 mma(vec8 a, vec8 b, f32x16 c) { return mfma(a, b, c); }
     static __device__ __forceinline__ f32x16 mfma(vec8 a, vec8 b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
     }
@@ -67,6 +74,17 @@ template <> struct Elem<_Float16> {
     }
 };
 
+template <> struct Elem<float> {
+    typedef f32x4 vec8;
+    static constexpr int kBytes = 4;
+    static __device__ __forceinline__ f32x16 mma(vec8 a, vec8 b, f32x16 c) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], b[e], c, 0, 0, 0);
+        return c;
+    }
+    static __device__ __forceinline__ uint32_t pack2(float a, float) { return __float_as_uint(a); }   // never stored narrow
+};
+
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 template <int DT>
@@ -74,6 +92,20 @@ __device__ __forceinline__ float load_as_float(const void* p, int64_t i) {
     if (DT == FX_F32) return reinterpret_cast<const float*>(p)[i];
     if (DT == FX_F16) return Elem<_Float16>::to_float(reinterpret_cast<const uint16_t*>(p)[i]);
     return Elem<__bf16>::to_float(reinterpret_cast<const uint16_t*>(p)[i]);
+}
+
+// four consecutive elements starting at element i (i a multiple of 4, p suitably aligned)
+template <int DT>
+__device__ __forceinline__ f32x4 load4_as_float(const void* p, int64_t i) {
+    if (DT == FX_F32) return *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(p) + i);
+    const u32x2 b = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint16_t*>(p) + i);
+    f32x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint16_t h = (uint16_t)(b[e >> 1] >> (16 * (e & 1)));
+        r[e] = DT == FX_F16 ? Elem<_Float16>::to_float(h) : Elem<__bf16>::to_float(h);
+    }
+    return r;
 }
 
 constexpr int kRowBufBytes = (kRowCap + 1) * kRowBytes;           // staged rows + the zero row
@@ -97,8 +129,11 @@ enum PackLayout { kPackRows = 0, kPackInterleaved = 1 };
 
 // Packs the weights (C_in = contracted channels, C_out = produced channels, in the sense of the
 // mode) and zeroes the eight work-list counters behind them.
-void launch_pack_weights(const void* d_w, uint16_t* wp, int K3, int C_in, int C_out, int32_t* counters, int mode,
-                         int layout, hipStream_t st);
+// elem_bytes 2 or 4; a row of the packed array covers 64 bytes of input channels (32 or 16 of them)
+// and the produced channels are padded with zeros to a multiple of 64.  Returns the bytes packed.
+size_t packed_weight_bytes(int K3, int C_in, int C_out, int elem_bytes);
+void launch_pack_weights(const void* d_w, void* wp, int K3, int C_in, int C_out, int elem_bytes, int32_t* counters,
+                         int mode, int layout, hipStream_t st);
 
 // The forward multiply-accumulate over a map with the weights read in the given mode: d_out[o,:]
 // = sum over kappa of d_feat[map(o,kappa),:] . Wmode[kappa], C_in channels in, C_out channels out.

@@ -195,6 +195,17 @@ extern "C" void fx_debug_host_timing_dump(int reset) {
 }
 #endif
 
+int compute_units() {
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
+        if (n_cu <= 0) n_cu = 256;
+    }
+    return n_cu;
+}
+
 // ---------------------------------------------------------------------------------- profiler
 struct ProfRec { int slot; hipEvent_t a, b; };
 static std::atomic<bool> g_prof_on{false};

@@ -58,6 +58,18 @@ def test_channel_shapes_mfma_and_scalar(dtype, c_in, c_out):
     H.conv_tolerance_check(y, ref, dt, k3, ci)
 
 
+@pytest.mark.parametrize("dtype,c_in,c_out", [("bf16", 32, 40), ("f16", 64, 34), ("bf16", 96, 2), ("f32", 16, 16),
+                                             ("f32", 32, 96), ("f32", 48, 6), ("f32", 64, 64)])
+@pytest.mark.parametrize("name", ["sheets_small", "lidar_small_down"])
+def test_tile_kernel_with_fp32_rows_and_padded_output_channels(name, dtype, c_in, c_out, monkeypatch):
+    # input rows in whole 64-byte chunks (32 channels of a 16-bit type, 16 of fp32) and an even number
+    # of output channels run on the matrix units; fp32 keeps true fp32 products (the fp32 bar applies).
+    # Small fp32 grids go to the scalar kernel by default; the switch sends them to the tile kernel.
+    monkeypatch.setenv("FVDB_HOTPATH_FP32_TILES", "1")
+    y, ref, dt, k3, ci = _run(G.workload(name), c_in=c_in, c_out=c_out, dtype=dtype)
+    H.conv_tolerance_check(y, ref, dt, k3, ci)
+
+
 @pytest.mark.parametrize("K,dtype,c_in,c_out", [(1, "bf16", 64, 64), (1, "f16", 32, 128), (5, "bf16", 16, 16),
                                                (5, "f32", 8, 8)])
 def test_pointwise_and_5x5x5_kernels(K, dtype, c_in, c_out):
@@ -74,6 +86,28 @@ def test_pointwise_and_5x5x5_kernels(K, dtype, c_in, c_out):
         # K = 1 is out = in . W[0] (closed form, independent of the map code)
         closed = feat.astype(np.float64) @ wt[0].astype(np.float64)
         H.conv_tolerance_check(y.float().cpu().numpy(), closed, dtype, 1, c_in)
+
+
+@pytest.mark.parametrize("tiles", ["0", "1"])
+def test_fp32_scalar_and_tile_kernels_on_config1(tiles, monkeypatch):
+    monkeypatch.setenv("FVDB_HOTPATH_FP32_TILES", tiles)
+    y, ref, dt, k3, c_in = _run(G.workload("sphere64"))
+    H.conv_tolerance_check(y, ref, dt, k3, c_in)
+
+
+def test_fp32_full_size_takes_the_tile_kernel():
+    """Config 3's grid with fp32 features, 32 -> 32 channels: large enough for the fp32 matrix path
+    by default; sampled output rows against the oracle at the fp32 bar."""
+    w = G.workload("lidar1m")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 3, 1)
+    feat, wt = G.features_and_weights(31, og.num_voxels, 32, 32, 27, "f32")
+    y = fx.sparse_conv_fwd(km, H.to_device_storage(feat, "f32"), H.to_device_storage(wt, "f32")).cpu().numpy()
+    n = og.num_voxels
+    for s in (0, n // 2, n - 300):
+        ref = O.conv(og, og, 3, 1, feat.astype(np.float64), wt.astype(np.float64), s, s + 300)
+        H.conv_tolerance_check(y[s:s + 300], ref[s:s + 300], "f32", 27, 32)
 
 
 def test_identity_tap_is_bit_exact_in_bf16():
