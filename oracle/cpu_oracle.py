@@ -50,6 +50,14 @@ def lib():
         L.fo_conv_bwd_data.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp]
         L.fo_conv_bwd_weight.restype = i64
         L.fo_conv_bwd_weight.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp, i64, i64]
+        L.fo_conv_transpose.restype = i64
+        L.fo_conv_transpose.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp]
+        L.fo_pool2.restype = i64
+        L.fo_pool2.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp]
+        L.fo_upsample2.restype = i64
+        L.fo_upsample2.argtypes = [vp, vp, vp, C.c_int, vp]
+        L.fo_grid_subdivide2.restype = vp
+        L.fo_grid_subdivide2.argtypes = [vp]
         _lib = L
     return _lib
 
@@ -122,6 +130,10 @@ class OracleGrid:
     def coarsen2(self) -> "OracleGrid":
         return OracleGrid(None, None, _handle=lib().fo_grid_coarsen2(self._h))
 
+    def subdivide2(self) -> "OracleGrid":
+        """All 8 children of every voxel (O5)."""
+        return OracleGrid(None, None, _handle=lib().fo_grid_subdivide2(self._h))
+
 
 def output_grid(gin: OracleGrid, kernel_size: int, stride: int) -> OracleGrid:
     if stride == 1:
@@ -188,4 +200,38 @@ def conv_bwd_weight(gin: OracleGrid, gout: OracleGrid, kernel_size: int, stride:
                                  _p(out), o_begin, o_end)
     if r < 0:
         raise ValueError("bad conv_bwd_weight arguments")
+    return out
+
+
+def conv_transpose(gin: OracleGrid, gout: OracleGrid, kernel_size: int, stride: int, z: np.ndarray,
+                   w: np.ndarray) -> np.ndarray:
+    """Transposed convolution over the map of a convolution gin -> gout (O5): z [N_out, C_in] lives
+    on gout, the result [N_in, C_out] on gin; w [K^3, C_in, C_out]."""
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    k3, c_in, c_out = w.shape
+    assert k3 == kernel_size ** 3 and z.shape == (gout.num_voxels, c_in)
+    out = np.zeros((gin.num_voxels, c_out), dtype=np.float64)
+    if lib().fo_conv_transpose(gin._h, gout._h, kernel_size, stride, _p(z), _p(w), c_in, c_out, _p(out)) < 0:
+        raise ValueError("bad conv_transpose arguments")
+    return out
+
+
+def pool2(fine: OracleGrid, coarse: OracleGrid, mode: str, z: np.ndarray) -> np.ndarray:
+    """Max ("max") or mean ("avg") over the active children of every coarse voxel (O5)."""
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    assert z.shape[0] == fine.num_voxels
+    out = np.zeros((coarse.num_voxels, z.shape[1]), dtype=np.float64)
+    if lib().fo_pool2(fine._h, coarse._h, {"max": 0, "avg": 1}[mode], _p(z), z.shape[1], _p(out)) < 0:
+        raise ValueError("bad pool2 arguments")
+    return out
+
+
+def upsample2(fine: OracleGrid, coarse: OracleGrid, z: np.ndarray) -> np.ndarray:
+    """Nearest-neighbour upsampling: every fine voxel takes the row of its parent floor(ijk/2) (O5)."""
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    assert z.shape[0] == coarse.num_voxels
+    out = np.zeros((fine.num_voxels, z.shape[1]), dtype=np.float64)
+    if lib().fo_upsample2(fine._h, coarse._h, _p(z), z.shape[1], _p(out)) < 0:
+        raise ValueError("bad upsample2 arguments")
     return out

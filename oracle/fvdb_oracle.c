@@ -42,6 +42,24 @@
  *      both accumulated in double by walking the same voxel -> offset loop as O3 and
  *      adding each pair's contribution where it belongs.
  *
+ *  O5  transposed convolution, pooling, upsampling -- Sec. 3.6.2 lists, beside the
+ *      convolution, average and max pooling on a GridBatch / JaggedTensor pair and an
+ *      operator that upsamples a grid and its features by subdivision and nearest-
+ *      neighbour sampling; Sec. 4.1.4's encoder-decoder network goes back up to the fine
+ *      resolution.  No formula is printed.  With nb(o,kappa) the map of a convolution
+ *      from a fine grid (inputs i) to a coarser one (outputs o):
+ *          transposed convolution  out[i,:] = sum over pairs (o,kappa) with nb(o,kappa) = i
+ *                                             of  z[o,:] . W[kappa]        (z lives on the outputs o;
+ *                                             the adjoint of O3 in the features for the weights
+ *                                             W[kappa]^T, i.e. O4's input gradient with W read as
+ *                                             [c_in, c_out] of the new direction)
+ *          pooling, factor 2       out[o,c] = max / mean over the active children i of o (the
+ *                                             voxels with floor(ijk_i / 2) = ijk_o) of z[i,c]
+ *          upsampling, factor 2    fine grid = all 8 children 2*ijk + {0,1}^3 of every coarse voxel
+ *                                  (fo_grid_subdivide2), or any given fine grid; out[i,:] = z[parent(i),:],
+ *                                  zero where the parent is not active
+ *      All are written as plain loops over voxels with this file's hash map.
+ *
  * Readings taken where the paper is silent (all listed in the design notes):
  *   - exported indices are 0-based rows of jdata, -1 means inactive (the paper's
  *     in-tree index 0 is its background value);
@@ -50,6 +68,8 @@
  *   - weights W[kappa][c_in][c_out]; cross-correlation, no flip, no bias;
  *   - stride 1: output voxel set = input set; stride 2: output set = distinct
  *     floor(ijk/2) (arithmetic shift), indexed by O1 applied to those coordinates;
+ *   - average pooling divides by the number of ACTIVE children, not by 8 (inactive voxels
+ *     carry no value in an IndexGrid; a dense average would mix in the background);
  *   - prefix field w (bits 9w..9w+8, w = 0..6) of mPrefixSum = popcount of mask
  *     words 0..w, as the prose under Listing 1 states.
  *
@@ -393,4 +413,93 @@ int64_t fo_conv_bwd_weight(const fo_grid *gin_grid, const fo_grid *gout_grid, in
                 }
     }
     return pairs;
+}
+
+/* ------------------------------------------------------------------ O5 */
+/* z [N_out, C_in] on the outputs of the map (gin_grid, gout_grid, K, stride), w [K^3, C_in, C_out],
+ * out [N_in, C_out] (overwritten); all double.  Returns the active pairs, or -1 on bad args. */
+int64_t fo_conv_transpose(const fo_grid *gin_grid, const fo_grid *gout_grid, int K, int stride,
+                          const double *z, const double *w, int C_in, int C_out, double *out) {
+    if (K < 1 || stride < 1 || gin_grid->B != gout_grid->B) return -1;
+    const int d0 = fo_delta_min(K);
+    int64_t pairs = 0;
+    for (int64_t e = 0; e < gin_grid->N * (int64_t)C_out; ++e) out[e] = 0.0;
+    for (int64_t o = 0; o < gout_grid->N; ++o) {
+        const fo_vox *p = &gout_grid->vox[o];
+        const double *x = z + o * (int64_t)C_in;
+        for (int a = 0; a < K; ++a)
+            for (int b = 0; b < K; ++b)
+                for (int c = 0; c < K; ++c) {
+                    int64_t in = fo_find(gin_grid, p->b, stride * p->i + d0 + a, stride * p->j + d0 + b,
+                                         stride * p->k + d0 + c);
+                    if (in < 0) continue;
+                    ++pairs;
+                    double *y = out + in * (int64_t)C_out;
+                    const double *wk = w + (int64_t)((a * K + b) * K + c) * C_in * C_out;
+                    for (int ci = 0; ci < C_in; ++ci) {
+                        const double xv = x[ci];
+                        const double *wr = wk + (int64_t)ci * C_out;
+                        for (int co = 0; co < C_out; ++co) y[co] += xv * wr[co];
+                    }
+                }
+    }
+    return pairs;
+}
+
+/* z [N_fine, C] -> out [N_coarse, C] (overwritten); mode 0 = max, 1 = mean over the active children.
+ * Returns the number of (coarse voxel, child) pairs, or -1 on bad args. */
+int64_t fo_pool2(const fo_grid *fine, const fo_grid *coarse, int mode, const double *z, int C, double *out) {
+    if (fine->B != coarse->B || (mode != 0 && mode != 1)) return -1;
+    int64_t pairs = 0;
+    for (int64_t o = 0; o < coarse->N; ++o) {
+        const fo_vox *p = &coarse->vox[o];
+        double *y = out + o * (int64_t)C;
+        int n = 0;
+        for (int a = 0; a < 2; ++a)
+            for (int b = 0; b < 2; ++b)
+                for (int c = 0; c < 2; ++c) {
+                    int64_t in = fo_find(fine, p->b, 2 * p->i + a, 2 * p->j + b, 2 * p->k + c);
+                    if (in < 0) continue;
+                    const double *x = z + in * (int64_t)C;
+                    for (int ch = 0; ch < C; ++ch) {
+                        if (n == 0) y[ch] = x[ch];
+                        else if (mode == 0) y[ch] = x[ch] > y[ch] ? x[ch] : y[ch];
+                        else y[ch] += x[ch];
+                    }
+                    ++n;
+                }
+        if (n == 0) for (int ch = 0; ch < C; ++ch) y[ch] = 0.0;
+        if (mode == 1 && n > 1) for (int ch = 0; ch < C; ++ch) y[ch] /= (double)n;
+        pairs += n;
+    }
+    return pairs;
+}
+
+/* z [N_coarse, C] -> out [N_fine, C] (overwritten): every fine voxel takes its parent's row. */
+int64_t fo_upsample2(const fo_grid *fine, const fo_grid *coarse, const double *z, int C, double *out) {
+    if (fine->B != coarse->B) return -1;
+    int64_t found = 0;
+    for (int64_t i = 0; i < fine->N; ++i) {
+        const fo_vox *p = &fine->vox[i];
+        int64_t o = fo_find(coarse, p->b, p->i >> 1, p->j >> 1, p->k >> 1);
+        double *y = out + i * (int64_t)C;
+        for (int ch = 0; ch < C; ++ch) y[ch] = o >= 0 ? z[o * (int64_t)C + ch] : 0.0;
+        found += o >= 0;
+    }
+    return found;
+}
+
+/* the grid of all 8 children of every voxel */
+fo_grid *fo_grid_subdivide2(const fo_grid *g) {
+    int32_t *c = (int32_t *)malloc(sizeof(int32_t) * 3 * 8 * (size_t)(g->N > 0 ? g->N : 1));
+    int64_t *jo = (int64_t *)malloc(sizeof(int64_t) * 2 * (size_t)(g->B > 0 ? g->B : 1));
+    for (int64_t s = 0; s < g->N; ++s)
+        for (int d = 0; d < 8; ++d) {
+            int32_t *q = c + 3 * (8 * s + d);
+            q[0] = 2 * g->vox[s].i + ((d >> 2) & 1); q[1] = 2 * g->vox[s].j + ((d >> 1) & 1); q[2] = 2 * g->vox[s].k + (d & 1);
+        }
+    for (int32_t b = 0; b < g->B; ++b) { jo[2 * b] = 8 * g->base[b]; jo[2 * b + 1] = 8 * g->base[b + 1]; }
+    fo_grid *o = fo_grid_create(c, jo, g->B);
+    free(c); free(jo);
+    return o;
 }
