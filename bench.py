@@ -205,6 +205,32 @@ def main():
     t_dgrad = b2b(lambda: fx.sparse_conv_bwd_data(km, d_gy, d_w))
     t_wgrad = b2b(lambda: fx.sparse_conv_bwd_weight(km, d_feat, d_gy))
 
+    # ---- the other operators of an encoder-decoder network on the same grid (not part of `value`):
+    # factor-2 max pooling, nearest upsampling and the 2x2x2 stride-2 transposed convolution
+    # (2*C -> C channels), warm, back to back, on the (2,2) kernel map of the input grid
+    km2 = km if (w.kernel_size, w.stride) == (2, 2) else fx.build_kernel_map(g, 2, 2)
+    n_c, c = km2.n_out, w.c_in
+    d_fine = d_feat
+    pooled = fx.pool2(km2, d_fine, "max")
+    t_pool = b2b(lambda: fx.pool2(km2, d_fine, "max"))
+    t_up = b2b(lambda: fx.upsample2(km2, pooled))
+    move_bytes = (n_in + n_c) * c * elem + n_c * 8 * 4            # both sides' rows once + the dense (2,2) map
+    ops = {"n_coarse": n_c, "channels": c,
+           "max_pool_ms": t_pool, "max_pool_GBs": move_bytes / (t_pool * 1e-3) / 1e9,
+           "upsample_ms": t_up, "upsample_GBs": move_bytes / (t_up * 1e-3) / 1e9,
+           "algorithmic_bytes": move_bytes, "hbm_peak_GBs": HBM_PEAK_GBS}
+    ops["max_pool_frac"] = ops["max_pool_GBs"] / HBM_PEAK_GBS
+    ops["upsample_frac"] = ops["upsample_GBs"] / HBM_PEAK_GBS
+    if w.dtype != "f32":
+        d_coarse = torch.randn((n_c, 2 * c), device="cuda").to(tdt).contiguous()
+        d_wt = (torch.randn((8, 2 * c, c), device="cuda") * (1.0 / (8 * 2 * c)) ** 0.5).to(tdt).contiguous()
+        t_tc = b2b(lambda: fx.sparse_conv_transpose_fwd(km2, d_coarse, d_wt))
+        ops["conv_transpose_ms"] = t_tc
+        ops["conv_transpose_effective_TFLOPs"] = 2.0 * n_in * 2 * c * c / (t_tc * 1e-3) / 1e12
+        tc_bytes = (n_c * 2 * c + n_in * c) * elem
+        ops["conv_transpose_GBs"] = tc_bytes / (t_tc * 1e-3) / 1e9
+    del pooled
+
     # ---- the paper's timing protocol (Sec. 4.1: one warm-up, five timed runs, mean of the best
     # four), cold = a 768 MiB scratch buffer is overwritten before every run so that neither the
     # L2s nor the 256 MB last-level cache hold the operands, warm = no flush
@@ -286,6 +312,7 @@ def main():
         "backward": {"bwd_data_ms": t_dgrad, "bwd_weight_ms": t_wgrad,
                      "bwd_data_effective_TFLOPs": flops / (t_dgrad * 1e-3) / 1e12,
                      "bwd_weight_effective_TFLOPs": flops / (t_wgrad * 1e-3) / 1e12},
+        "encoder_decoder_ops": ops,
         "kernels_ms_per_launch": kern_ms,
         "kernels_ms_per_step": per_step_ms,
         "roofline": roof,

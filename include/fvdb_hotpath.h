@@ -106,6 +106,12 @@ fx_status fx_grid_leaf_table(const fx_grid* g, fx_leaf* h_out, size_t bytes, voi
  * coarsening of Sec. 3.6.2 "Grid Construction Operators").  Synchronises `stream`. */
 fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** out);
 
+/* The subdivided grid of Sec. 3.6.2 ("upsamples a GridBatch ... via subdivision"): active set =
+ * all eight children 2*ijk + {0,1}^3 of every active voxel, per grid of the batch.  The kernel map
+ * fx_build_kernel_map(*out, 2, 2) then has g as its output grid (same voxels, same order).
+ * FX_ERANGE beyond 2^31-1 voxels.  Synchronises `stream`. */
+fx_status fx_grid_subdivide2(const fx_grid* g, void* stream, fx_grid** out);
+
 void fx_grid_retain(fx_grid* g);
 void fx_grid_destroy(fx_grid* g);
 
@@ -196,6 +202,38 @@ fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_gout, fx_dtyp
                                   int32_t C_in, int32_t C_out, void* d_gin, fx_dtype out_dt, void* stream);
 fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_feat, const void* d_gout, fx_dtype dt,
                                     int32_t C_in, int32_t C_out, void* d_gw, fx_dtype out_dt, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Transposed convolution, pooling, upsampling (Sec. 3.6.2: "average and max pooling operators on a
+ * GridBatch and JaggedTensor pair as well as an upsampling operator which upsamples ... via
+ * subdivision and nearest neighbor sampling"; the decoder half of the network of Sec. 4.1.4).  The
+ * paper prints no formulas; with km the kernel map of a convolution from grid g_in (inputs i) to
+ * g_out (outputs o):
+ *
+ *   fx_sparse_conv_transpose_fwd   out[i,:] = sum over pairs (o,kappa) with map(o,kappa) = i of
+ *                                             feat[o,:] . W[kappa]
+ *        d_feat [N_out, C_in] lives on g_out, d_out [N_in, C_out] on g_in, d_w [K^3, C_in, C_out];
+ *        supported maps: K = stride (one pair per input, every row of d_out is written) and stride 1
+ *        (symmetric map: the forward kernels over the mirrored offsets).  Types, accumulation and
+ *        rounding as fx_sparse_conv_fwd; MFMA path for K = stride: FX_F16 / FX_BF16, C_in % 32 == 0,
+ *        C_out % 64 == 0.
+ *   fx_pool2       km must be a (2,2) map.  out[o,c] = max (FX_POOL_MAX) or mean (FX_POOL_AVG) over the
+ *                  ACTIVE children i = map(o,kappa) of feat[i,c]; the mean is the fp32 sum in offset
+ *                  order divided by the number of active children (not by 8), rounded once to dt.
+ *        d_feat [N_in, C], d_out [N_out, C], both dtype dt.
+ *   fx_upsample2   km must be a (2,2) map.  out[i,:] = feat[o,:] for the pair with map(o,kappa) = i
+ *                  (nearest neighbour: every fine voxel copies its parent's row, bit for bit).
+ *        d_feat [N_out, C], d_out [N_in, C], both dtype dt.  To upsample onto all children of a grid
+ *        g: fine = fx_grid_subdivide2(g), km = fx_build_kernel_map(fine, 2, 2).
+ * All device pointers are borrowed for the stream-ordered work; outputs are caller-allocated.
+ */
+typedef enum { FX_POOL_MAX = 0, FX_POOL_AVG = 1 } fx_pool_mode;
+
+fx_status fx_sparse_conv_transpose_fwd(const fx_kmap* km, const void* d_feat, fx_dtype dt, const void* d_w,
+                                       int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream);
+fx_status fx_pool2(const fx_kmap* km, int32_t mode, const void* d_feat, fx_dtype dt, int32_t C, void* d_out,
+                   void* stream);
+fx_status fx_upsample2(const fx_kmap* km, const void* d_feat, fx_dtype dt, int32_t C, void* d_out, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Measurement support (the paper's protocol, Sec. 4.1: per-operator times).  While enabled,

@@ -73,6 +73,14 @@ def _load():
     L.fx_sparse_conv_bwd_data.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
     L.fx_sparse_conv_bwd_weight.restype = C.c_int
     L.fx_sparse_conv_bwd_weight.argtypes = [vp, vp, vp, C.c_int, i32, i32, vp, C.c_int, vp]
+    L.fx_grid_subdivide2.restype = C.c_int
+    L.fx_grid_subdivide2.argtypes = [vp, vp, C.POINTER(vp)]
+    L.fx_sparse_conv_transpose_fwd.restype = C.c_int
+    L.fx_sparse_conv_transpose_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
+    L.fx_pool2.restype = C.c_int
+    L.fx_pool2.argtypes = [vp, i32, vp, C.c_int, i32, vp, vp]
+    L.fx_upsample2.restype = C.c_int
+    L.fx_upsample2.argtypes = [vp, vp, C.c_int, i32, vp, vp]
     L.fx_release_cached_memory.restype = None
     L.fx_profile_enable.argtypes = [C.c_int]
     L.fx_profile_slot_count.restype = C.c_int
@@ -171,6 +179,12 @@ class IndexGrid:
     def coarsen2(self) -> "IndexGrid":
         h = C.c_void_p()
         _check(lib.fx_grid_coarsen2(self._h, _stream(), C.byref(h)))
+        return IndexGrid(h.value)
+
+    def subdivide2(self) -> "IndexGrid":
+        """The grid of all eight children of every voxel."""
+        h = C.c_void_p()
+        _check(lib.fx_grid_subdivide2(self._h, _stream(), C.byref(h)))
         return IndexGrid(h.value)
 
 
@@ -276,3 +290,36 @@ def sparse_conv_bwd_weight(kmap: KernelMap, feat: torch.Tensor, grad_out: torch.
     _check(lib.fx_sparse_conv_bwd_weight(kmap._h, _ptr(feat), _ptr(grad_out), _TORCH_DT[feat.dtype], c_in, c_out,
                                          _ptr(gw), _TORCH_DT[out_dtype], _stream()))
     return gw
+
+
+def sparse_conv_transpose_fwd(kmap: KernelMap, feat: torch.Tensor, weights: torch.Tensor,
+                              out_dtype: Optional[torch.dtype] = None) -> torch.Tensor:
+    """feat [N_out, C_in] on the map's output grid, weights [K^3, C_in, C_out] -> [N_in, C_out] on its input grid."""
+    assert feat.is_cuda and weights.is_cuda and feat.is_contiguous() and weights.is_contiguous()
+    assert feat.dtype == weights.dtype and feat.dtype in _TORCH_DT
+    k3, c_in, c_out = weights.shape
+    assert k3 == kmap.k3 and feat.shape == (kmap.n_out, c_in)
+    out_dtype = out_dtype or feat.dtype
+    out = torch.empty((kmap.g_in.num_voxels, c_out), dtype=out_dtype, device="cuda")
+    _check(lib.fx_sparse_conv_transpose_fwd(kmap._h, _ptr(feat), _TORCH_DT[feat.dtype], _ptr(weights), c_in, c_out,
+                                            _ptr(out), _TORCH_DT[out_dtype], _stream()))
+    return out
+
+
+def pool2(kmap: KernelMap, feat: torch.Tensor, mode: str = "max") -> torch.Tensor:
+    """Max / mean over the active children; kmap is a (2,2) map, feat [N_in, C] -> [N_out, C]."""
+    assert feat.is_cuda and feat.is_contiguous() and feat.dtype in _TORCH_DT
+    assert feat.shape[0] == kmap.g_in.num_voxels
+    out = torch.empty((kmap.n_out, feat.shape[1]), dtype=feat.dtype, device="cuda")
+    _check(lib.fx_pool2(kmap._h, {"max": 0, "avg": 1}[mode], _ptr(feat), _TORCH_DT[feat.dtype], feat.shape[1],
+                        _ptr(out), _stream()))
+    return out
+
+
+def upsample2(kmap: KernelMap, feat: torch.Tensor) -> torch.Tensor:
+    """Nearest-neighbour upsampling; kmap is a (2,2) map, feat [N_out, C] -> [N_in, C]."""
+    assert feat.is_cuda and feat.is_contiguous() and feat.dtype in _TORCH_DT
+    assert feat.shape[0] == kmap.n_out
+    out = torch.empty((kmap.g_in.num_voxels, feat.shape[1]), dtype=feat.dtype, device="cuda")
+    _check(lib.fx_upsample2(kmap._h, _ptr(feat), _TORCH_DT[feat.dtype], feat.shape[1], _ptr(out), _stream()))
+    return out

@@ -54,8 +54,9 @@ __global__ void k_pack_weights(const E* __restrict__ w, E* __restrict__ wp, int 
                                                     : s * kCoutSlice + 32 * ((m >> 2) & 1) + 16 * mt + 4 * (m >> 3) + (m & 3);
         E v = 0;
         if (cout < C_out) {
-            if (mode == kWeightsForward) v = w[((int64_t)kappa * C_in + cin) * C_out + cout];
-            else v = w[((int64_t)(mode == kWeightsMirrored ? K3 - 1 - kappa : kappa) * C_out + cout) * C_in + cin];
+            const int64_t kw = (mode & kWeightsFlipped) ? K3 - 1 - kappa : kappa;
+            if (mode & kWeightsTransposed) v = w[(kw * C_out + cout) * C_in + cin];
+            else v = w[(kw * C_in + cin) * C_out + cout];
         }
         wp[e] = v;
     }
@@ -778,10 +779,10 @@ __global__ void k_conv_scalar(const int32_t* __restrict__ nbmap, int64_t n_out, 
             const int32_t in = nbmap[o * K3 + kappa];
             if (in < 0) continue;
             const int64_t fb = (int64_t)in * C_in;
-            // forward: W[kappa][ci][co]; mirrored (input gradient on a symmetric map): W[K3-1-kappa][co][ci]
-            const int64_t wb = mode == kWeightsForward ? (int64_t)kappa * C_in * C_out + co
-                                                       : ((int64_t)(mode == kWeightsMirrored ? K3 - 1 - kappa : kappa) * C_out + co) * C_in;
-            const int64_t ws = mode == kWeightsForward ? C_out : 1;
+            // plain: W[kw][ci][co]; transposed (e.g. the input gradient on a symmetric map): W[kw][co][ci]
+            const int64_t kw = (mode & kWeightsFlipped) ? K3 - 1 - kappa : kappa;
+            const int64_t wb = (mode & kWeightsTransposed) ? (kw * C_out + co) * C_in : kw * C_in * C_out + co;
+            const int64_t ws = (mode & kWeightsTransposed) ? 1 : C_out;
             for (int ci = 0; ci < C_in; ++ci)
                 acc = fmaf(load_as_float<DT>(feat, fb + ci), load_as_float<DT>(w, wb + (int64_t)ci * ws), acc);
         }
@@ -808,8 +809,9 @@ __global__ void k_conv_scalar4(const int32_t* __restrict__ nbmap, int64_t n_out,
             const int32_t in = nbmap[o * K3 + kappa];
             if (in < 0) continue;
             const int64_t fb = (int64_t)in * C_in;
-            if (mode == kWeightsForward) {
-                const int64_t wb = (int64_t)kappa * C_in * C_out + co;
+            const int64_t kw = (mode & kWeightsFlipped) ? K3 - 1 - kappa : kappa;
+            if (!(mode & kWeightsTransposed)) {
+                const int64_t wb = kw * C_in * C_out + co;
                 for (int ci = 0; ci < C_in; ci += 4) {
                     const f32x4 x = load4_as_float<DT>(feat, fb + ci);
 #pragma unroll
@@ -819,8 +821,8 @@ __global__ void k_conv_scalar4(const int32_t* __restrict__ nbmap, int64_t n_out,
                         for (int v = 0; v < 4; ++v) acc[v] = fmaf(x[j], wr[v], acc[v]);
                     }
                 }
-            } else {   // W[kappa'][co][ci]: the four contracted channels of a produced channel are adjacent
-                const int64_t wb = ((int64_t)(mode == kWeightsMirrored ? K3 - 1 - kappa : kappa) * C_out + co) * C_in;
+            } else {   // W[kw][co][ci]: the four contracted channels of a produced channel are adjacent
+                const int64_t wb = (kw * C_out + co) * C_in;
                 for (int ci = 0; ci < C_in; ci += 4) {
                     const f32x4 x = load4_as_float<DT>(feat, fb + ci);
 #pragma unroll

@@ -177,6 +177,30 @@ __global__ void k_dgrad_strided_scalar(const int32_t* __restrict__ nbmap, int64_
     }
 }
 
+// The same product with the weights read forward, W[kappa][contracted][produced] (transposed
+// convolution): one thread per (pair, produced channel).
+template <int DT, bool OUT_F32>
+__global__ void k_conv_transpose_scalar(const int32_t* __restrict__ nbmap, int64_t n_out, int K3, const void* __restrict__ z,
+                                        const void* __restrict__ w, int C_in, int C_out, void* __restrict__ out) {
+    const int64_t total = n_out * K3 * C_out;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t pair = e / C_out;
+        const int co = (int)(e - pair * C_out);
+        const int32_t in = nbmap[pair];
+        if (in < 0) continue;
+        const int64_t o = pair / K3;
+        const int kappa = (int)(pair - o * K3);
+        const int64_t wb = (int64_t)kappa * C_in * C_out + co, zb = o * C_in;
+        float acc = 0.f;
+        for (int ci = 0; ci < C_in; ++ci)
+            acc = fmaf(load_as_float<DT>(z, zb + ci), load_as_float<DT>(w, wb + (int64_t)ci * C_out), acc);
+        const int64_t dst = (int64_t)in * C_out + co;
+        if (OUT_F32) reinterpret_cast<float*>(out)[dst] = acc;
+        else if (DT == FX_F16) reinterpret_cast<uint16_t*>(out)[dst] = Elem<_Float16>::from_float(acc);
+        else reinterpret_cast<uint16_t*>(out)[dst] = Elem<__bf16>::from_float(acc);
+    }
+}
+
 // ---------------------------------------------------------------------------------- weight gradient, MFMA
 // A workgroup owns a block of 32 input channels x 64 output channels of every gw[kappa] and a
 // contiguous range of tiles; its 8 waves split the offsets (wave w: kappa = w, w+8, w+16, w+24),
@@ -423,6 +447,68 @@ static hipError_t launch_reduce(const float* part, int n_ranges, int64_t total, 
     return hipGetLastError();
 }
 
+// dst[map(o,kappa), :] = W'[kappa] applied to src[o, :] for every pair of a K = stride map (each input
+// row has exactly one pair, so every row of dst is written once).  C_contract channels of src are
+// contracted, C_produce channels produced; mode kWeightsTransposed reads W[kappa][produced][contracted]
+// (the input gradient), kWeightsForward reads W[kappa][contracted][produced] (transposed convolution).
+fx_status strided_pair_product(const fx_kmap* km, const void* d_src, fx_dtype dt, const void* d_w, int32_t C_contract,
+                               int32_t C_produce, void* d_dst, fx_dtype out_dt, hipStream_t st, int mode) {
+    const bool out_f32 = out_dt == FX_F32;
+    const char* force = getenv("FVDB_HOTPATH_FORCE_SCALAR");
+    const bool mfma = dt != FX_F32 && km->n_tiles > 0 && C_contract % kCinChunk == 0 && C_produce % kCoutSlice == 0 &&
+                      !(force && force[0] == '1');
+    if (mfma) {
+        void* wp = nullptr;
+        const size_t wbytes = packed_weight_bytes(km->K3, C_contract, C_produce, 2);
+        FX_TRY(dev_alloc(&wp, wbytes + 8 * sizeof(int32_t), st));
+        int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
+        launch_pack_weights(d_w, wp, km->K3, C_contract, C_produce, 2, counters, mode, kPackRows, st);
+        hipError_t e = hipGetLastError();
+        if (e == hipSuccess) {
+            const int64_t n_items = km->n_tiles * (int64_t)kGroupsPerTile * (C_produce / kCoutSlice);
+            const unsigned grid = (unsigned)((n_items + kDgradWaves - 1) / kDgradWaves);
+            ProfScope ps(kProfDgradStrided, st);
+#define FX_DGRAD(T, F32)                                                                                             \
+    k_dgrad_strided<T, F32><<<grid, 64 * kDgradWaves, 0, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,      \
+                                                               km->row_stride, km->d_tile_blocks, km->block_stride,  \
+                                                               n_items, (const uint16_t*)d_src, (const uint16_t*)wp, \
+                                                               C_contract, C_produce, d_dst)
+            if (dt == FX_BF16) { if (out_f32) FX_DGRAD(__bf16, true); else FX_DGRAD(__bf16, false); }
+            else { if (out_f32) FX_DGRAD(_Float16, true); else FX_DGRAD(_Float16, false); }
+#undef FX_DGRAD
+            e = hipGetLastError();
+        }
+        dev_free(wp, st);
+        if (e != hipSuccess) { set_error("strided pair product launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
+        return FX_OK;
+    }
+    FX_TRY(kmap_ensure_dense(const_cast<fx_kmap*>(km), st));
+    const int64_t total = km->n_out * km->K3 * C_produce;
+    const unsigned nb = (unsigned)std::max<int64_t>(1, std::min<int64_t>((total + 255) / 256, 1 << 20));
+    ProfScope ps(kProfDgradStrided, st);
+    // k_dgrad_strided_scalar takes W[kappa][produced][contracted], k_conv_transpose_scalar W[kappa][contracted][produced]
+#define FX_SCALAR(DT)                                                                                                    \
+    do {                                                                                                                 \
+        if (mode == kWeightsTransposed) {                                                                                \
+            if (out_f32) k_dgrad_strided_scalar<DT, true><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_src, d_w, \
+                                                                              C_produce, C_contract, d_dst);             \
+            else k_dgrad_strided_scalar<DT, false><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_src, d_w,        \
+                                                                       C_produce, C_contract, d_dst);                    \
+        } else {                                                                                                         \
+            if (out_f32) k_conv_transpose_scalar<DT, true><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_src, d_w, \
+                                                                               C_contract, C_produce, d_dst);            \
+            else k_conv_transpose_scalar<DT, false><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_src, d_w,       \
+                                                                        C_contract, C_produce, d_dst);                   \
+        }                                                                                                                \
+    } while (0)
+    if (dt == FX_F32) FX_SCALAR(FX_F32);
+    else if (dt == FX_F16) FX_SCALAR(FX_F16);
+    else FX_SCALAR(FX_BF16);
+#undef FX_SCALAR
+    FX_HIP_TRY(hipGetLastError());
+    return FX_OK;
+}
+
 }  // namespace fx
 
 using namespace fx;
@@ -456,49 +542,7 @@ extern "C" fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_go
         return conv_apply(km, d_gout, dt, d_w, C_out, C_in, d_gin, out_dt, st, kWeightsMirrored);
     }
     if (km->K != km->stride) { set_error("fx_sparse_conv_bwd_data: unsupported (kernel, stride)"); return FX_EUNSUPPORTED; }
-    const bool out_f32 = out_dt == FX_F32;
-    const bool mfma = dt != FX_F32 && km->n_tiles > 0 && C_out % kCinChunk == 0 && C_in % kCoutSlice == 0 && !force_scalar();
-    if (mfma) {
-        uint16_t* wp = nullptr;
-        const size_t wbytes = sizeof(uint16_t) * (size_t)km->K3 * C_in * C_out;
-        FX_TRY(dev_alloc((void**)&wp, wbytes + 8 * sizeof(int32_t), st));
-        int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
-        launch_pack_weights(d_w, wp, km->K3, C_out, C_in, 2, counters, kWeightsTransposed, kPackRows, st);
-        hipError_t e = hipGetLastError();
-        if (e == hipSuccess) {
-            const int64_t n_items = km->n_tiles * (int64_t)kGroupsPerTile * (C_in / kCoutSlice);
-            const unsigned grid = (unsigned)((n_items + kDgradWaves - 1) / kDgradWaves);
-            ProfScope ps(kProfDgradStrided, st);
-#define FX_DGRAD(T, F32)                                                                                             \
-    k_dgrad_strided<T, F32><<<grid, 64 * kDgradWaves, 0, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,      \
-                                                               km->row_stride, km->d_tile_blocks, km->block_stride,  \
-                                                               n_items, (const uint16_t*)d_gout, wp, C_out, C_in, d_gin)
-            if (dt == FX_BF16) { if (out_f32) FX_DGRAD(__bf16, true); else FX_DGRAD(__bf16, false); }
-            else { if (out_f32) FX_DGRAD(_Float16, true); else FX_DGRAD(_Float16, false); }
-#undef FX_DGRAD
-            e = hipGetLastError();
-        }
-        dev_free(wp, st);
-        if (e != hipSuccess) { set_error("input-gradient launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
-        return FX_OK;
-    }
-    FX_TRY(kmap_ensure_dense(const_cast<fx_kmap*>(km), st));
-    const int64_t total = km->n_out * km->K3 * C_in;
-    const unsigned nb = (unsigned)std::min<int64_t>((total + 255) / 256, 1 << 20);
-    ProfScope ps(kProfDgradStrided, st);
-#define FX_SCALAR(DT)                                                                                                 \
-    do {                                                                                                              \
-        if (out_f32) k_dgrad_strided_scalar<DT, true><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_gout, d_w, \
-                                                                          C_in, C_out, d_gin);                        \
-        else k_dgrad_strided_scalar<DT, false><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_gout, d_w, C_in,  \
-                                                                   C_out, d_gin);                                     \
-    } while (0)
-    if (dt == FX_F32) FX_SCALAR(FX_F32);
-    else if (dt == FX_F16) FX_SCALAR(FX_F16);
-    else FX_SCALAR(FX_BF16);
-#undef FX_SCALAR
-    FX_HIP_TRY(hipGetLastError());
-    return FX_OK;
+    return strided_pair_product(km, d_gout, dt, d_w, C_out, C_in, d_gin, out_dt, st, kWeightsTransposed);
 }
 
 extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_feat, const void* d_gout, fx_dtype dt,

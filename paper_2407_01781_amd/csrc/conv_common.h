@@ -113,12 +113,13 @@ constexpr int kBlockBufBytes = kMaxIdBlocks * kIdBlockElems * 2;
 __device__ __forceinline__ int lds_row_offset(int row, int p) { return (int)(lds_row_code((uint32_t)row) ^ (uint32_t)(p << 4)); }
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-// How the packed A-operand fragments are read from the caller's W[K^3][C_in][C_out]:
+// How the packed operand fragments are read from the caller's W[K^3][C_in][C_out] (two flags):
 //   kWeightsForward        fragment (kappa, cin, cout) = W[kappa][cin][cout]
 //   kWeightsTransposed     fragment (kappa, a, b)      = W[kappa][b][a]            (roles of the channel
 //                          counts swapped: the multiply contracts over W's output channels)
-//   kWeightsMirrored       fragment (kappa, a, b)      = W[K^3-1-kappa][b][a]      (and offsets mirrored)
-enum WeightMode { kWeightsForward = 0, kWeightsTransposed = 1, kWeightsMirrored = 2 };
+//   kWeightsFlipped        fragment (kappa, cin, cout) = W[K^3-1-kappa][cin][cout] (offsets mirrored)
+//   kWeightsMirrored       fragment (kappa, a, b)      = W[K^3-1-kappa][b][a]      (both)
+enum WeightMode { kWeightsForward = 0, kWeightsTransposed = 1, kWeightsFlipped = 2, kWeightsMirrored = 3 };
 
 // Which produced channel a fragment row / column m of tile t holds (within a slice of 64):
 //   kPackRows          32*((m>>2)&1) + 16*t + 4*(m>>3) + (m&3)   weights as the A operand: a lane's accumulators
@@ -139,5 +140,9 @@ void launch_pack_weights(const void* d_w, void* wp, int K3, int C_in, int C_out,
 // = sum over kappa of d_feat[map(o,kappa),:] . Wmode[kappa], C_in channels in, C_out channels out.
 fx_status conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w, int32_t C_in,
                      int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st, int mode);
+
+// dst[map(o,kappa), :] for every pair of a K = stride map; see conv_bwd.hip
+fx_status strided_pair_product(const fx_kmap* km, const void* d_src, fx_dtype dt, const void* d_w, int32_t C_contract,
+                               int32_t C_produce, void* d_dst, fx_dtype out_dt, hipStream_t st, int mode);
 
 }  // namespace fx

@@ -697,6 +697,29 @@ __global__ void k_grid_ijk(TreeView t, int32_t* __restrict__ ijk_out, int32_t* _
     }
 }
 
+// the eight children 2*ijk + {0,1}^3 of every active voxel, as rows 8*o .. 8*o+7 (child d = 4*di + 2*dj + dk)
+__global__ void k_grid_children(TreeView t, int32_t* __restrict__ ijk_out) {
+    const int f = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    if (f >= t.n_leaf) return;
+    const int lane = threadIdx.x & 63;
+    const fx_leaf* lf = t.leaf + f;
+    const uint64_t lt = (1ull << lane) - 1;
+    int64_t run = lf->offset;
+    for (int w = 0; w < 8; ++w) {
+        const uint64_t m = lf->mask[w];
+        if ((m >> lane) & 1) {
+            const int64_t o = run + __popcll(m & lt);
+            const int i = 2 * (lf->origin[0] + w), j = 2 * (lf->origin[1] + (lane >> 3)), k = 2 * (lf->origin[2] + (lane & 7));
+#pragma unroll
+            for (int d = 0; d < 8; ++d) {
+                int32_t* q = ijk_out + 3 * (8 * o + d);
+                q[0] = i + ((d >> 2) & 1); q[1] = j + ((d >> 1) & 1); q[2] = k + (d & 1);
+            }
+        }
+        run += __popcll(m);
+    }
+}
+
 __global__ void k_ijk_to_index(TreeView t, const int32_t* __restrict__ ijk, const int32_t* __restrict__ jidx,
                                int64_t n, int32_t* __restrict__ out) {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1073,6 +1096,39 @@ extern "C" fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** 
     }
     fx_grid* o = nullptr;
     rc = build_index_grid_device_joff(d_c, n, d_joff, g->B, st, &o);
+    cleanup();
+    if (rc != FX_OK) return rc;
+    *out = o;
+    return FX_OK;
+}
+
+extern "C" fx_status fx_grid_subdivide2(const fx_grid* g, void* stream, fx_grid** out) {
+    if (!g || !out) { set_error("fx_grid_subdivide2: null pointer"); return FX_EINVAL; }
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t n = g->hdr.n_voxels;
+    if (8 * n > 0x7FFFFFFFll) { set_error("fx_grid_subdivide2: more than 2^31-1 voxels"); return FX_ERANGE; }
+    int32_t* d_c = nullptr;
+    int64_t* d_joff = nullptr;
+    FX_TRY(dev_alloc((void**)&d_c, sizeof(int32_t) * 3 * 8 * (size_t)std::max<int64_t>(n, 1), st));
+    fx_status rc = dev_alloc((void**)&d_joff, sizeof(int64_t) * 2 * (size_t)std::max(g->B, 1), st);
+    if (rc != FX_OK) { dev_free(d_c, st); return rc; }
+    auto cleanup = [&]() { dev_free(d_c, st); dev_free(d_joff, st); };
+    if (g->hdr.n_leaf > 0) {
+        const int64_t threads = (int64_t)g->hdr.n_leaf * 64;
+        ProfScope ps(kProfGridIjk, st);
+        k_grid_children<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(g->view(), d_c);
+    }
+    if (g->B > 0) {
+        void* stage = nullptr;
+        rc = host_staging(&stage, sizeof(int64_t) * 2 * (size_t)g->B, 1);
+        if (rc != FX_OK) { cleanup(); return rc; }
+        int64_t* hj = (int64_t*)stage;
+        for (int b = 0; b < g->B; ++b) { hj[2 * b] = 8 * g->h_vox_base[b]; hj[2 * b + 1] = 8 * g->h_vox_base[b + 1]; }
+        hipError_t e = hipMemcpyAsync(d_joff, stage, sizeof(int64_t) * 2 * (size_t)g->B, hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) { cleanup(); set_error("joffsets upload failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
+    }
+    fx_grid* o = nullptr;
+    rc = build_index_grid_device_joff(d_c, 8 * n, d_joff, g->B, st, &o);
     cleanup();
     if (rc != FX_OK) return rc;
     *out = o;

@@ -1,0 +1,222 @@
+// Transposed convolution, factor-2 pooling and nearest-neighbour upsampling (Sec. 3.6.2: beside the
+// convolution the framework offers average and max pooling on a grid / feature pair and an
+// operator that upsamples by subdivision and nearest-neighbour sampling; Sec. 4.1.4's network goes
+// back up to the fine resolution).  The paper gives no formulas; with map(o,kappa) the kernel map
+// of a K = stride = 2 convolution from a fine grid (inputs i) to its coarse grid (outputs o):
+//
+//   pooling        out[o,c] = max, or mean, over the ACTIVE children i = map(o,kappa) of z[i,c]
+//   upsampling     out[i,:] = z[o,:] for the one pair (o,kappa) with map(o,kappa) = i
+//   transposed     out[i,:] = sum over pairs (o,kappa) with map(o,kappa) = i of z[o,:] . W[kappa]
+//   convolution    (one pair per input when K = stride; on a submanifold map the sum runs over the
+//                   mirrored offsets, which is the forward kernel with the offsets flipped)
+//
+// Pooling and upsampling move every feature row once: they are bandwidth-bound, one thread per
+// 16 bytes of a row, rows of the coarse side visited in order (coalesced), rows of the fine side
+// reached through the dense [N_out, 8] form of the map.
+#include "conv_common.h"
+
+namespace fx {
+
+template <int DT>
+__device__ __forceinline__ void load_vec(const void* p, int64_t byte_off, float (&v)[8]) {
+    const u32x4 b = *reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(p) + byte_off);
+    if (DT == FX_F32) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = __uint_as_float(b[e]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint16_t h = (uint16_t)(b[e >> 1] >> (16 * (e & 1)));
+            v[e] = DT == FX_F16 ? Elem<_Float16>::to_float(h) : Elem<__bf16>::to_float(h);
+        }
+    }
+}
+
+template <int DT>
+__device__ __forceinline__ void store_vec(void* p, int64_t byte_off, const float (&v)[8]) {
+    u32x4 b;
+    if (DT == FX_F32) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) b[e] = __float_as_uint(v[e]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            b[e] = DT == FX_F16 ? Elem<_Float16>::pack2(v[2 * e], v[2 * e + 1]) : Elem<__bf16>::pack2(v[2 * e], v[2 * e + 1]);
+    }
+    *reinterpret_cast<u32x4*>(reinterpret_cast<unsigned char*>(p) + byte_off) = b;
+}
+
+// One thread per (coarse voxel, 16-byte piece of its row).  The children are visited in offset
+// order; the mean is the fp32 sum in that order divided by the number of active children and
+// rounded once (RNE) to the storage type; the maximum is exact in every type.
+template <int DT, bool AVG>
+__global__ void __launch_bounds__(256)
+k_pool2(const int32_t* __restrict__ nbmap, int64_t n_out, int vec_per_row, const void* __restrict__ z, void* __restrict__ out) {
+    constexpr int NE = DT == FX_F32 ? 4 : 8;
+    const int64_t total = n_out * vec_per_row;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t o = t / vec_per_row;
+        const int q = (int)(t - o * vec_per_row);
+        float acc[8];
+        int n = 0;
+#pragma unroll
+        for (int kappa = 0; kappa < 8; ++kappa) {
+            const int32_t in = nbmap[o * 8 + kappa];
+            if (in < 0) continue;
+            float v[8];
+            load_vec<DT>(z, ((int64_t)in * vec_per_row + q) * 16, v);
+#pragma unroll
+            for (int e = 0; e < NE; ++e) acc[e] = n == 0 ? v[e] : (AVG ? acc[e] + v[e] : (v[e] > acc[e] ? v[e] : acc[e]));
+            ++n;
+        }
+        if (n == 0) {
+#pragma unroll
+            for (int e = 0; e < NE; ++e) acc[e] = 0.f;
+        }
+        if (AVG && n > 1) {
+            const float fn = (float)n;
+#pragma unroll
+            for (int e = 0; e < NE; ++e) acc[e] = acc[e] / fn;
+        }
+        store_vec<DT>(out, t * 16, acc);
+    }
+}
+
+// One thread per (coarse voxel, child slot, 16-byte piece): copies the parent's piece to the child.
+__global__ void __launch_bounds__(256)
+k_upsample2(const int32_t* __restrict__ nbmap, int64_t n_out, int vec_per_row, const void* __restrict__ z, void* __restrict__ out) {
+    const int64_t total = n_out * 8 * vec_per_row;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t pair = t / vec_per_row;
+        const int q = (int)(t - pair * vec_per_row);
+        const int32_t in = nbmap[pair];
+        if (in < 0) continue;
+        const int64_t o = pair >> 3;
+        reinterpret_cast<u32x4*>(out)[(int64_t)in * vec_per_row + q] = reinterpret_cast<const u32x4*>(z)[o * vec_per_row + q];
+    }
+}
+
+// element-wise fallbacks for rows that are not a multiple of 16 bytes
+template <int DT, bool AVG>
+__global__ void k_pool2_elem(const int32_t* __restrict__ nbmap, int64_t n_out, int C, const void* __restrict__ z,
+                             void* __restrict__ out) {
+    const int64_t total = n_out * C;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t o = t / C;
+        const int c = (int)(t - o * C);
+        float acc = 0.f;
+        int n = 0;
+        for (int kappa = 0; kappa < 8; ++kappa) {
+            const int32_t in = nbmap[o * 8 + kappa];
+            if (in < 0) continue;
+            const float v = load_as_float<DT>(z, (int64_t)in * C + c);
+            acc = n == 0 ? v : (AVG ? acc + v : (v > acc ? v : acc));
+            ++n;
+        }
+        if (AVG && n > 1) acc = acc / (float)n;
+        if (DT == FX_F32) reinterpret_cast<float*>(out)[t] = acc;
+        else if (DT == FX_F16) reinterpret_cast<uint16_t*>(out)[t] = Elem<_Float16>::from_float(acc);
+        else reinterpret_cast<uint16_t*>(out)[t] = Elem<__bf16>::from_float(acc);
+    }
+}
+
+template <typename E>
+__global__ void k_upsample2_elem(const int32_t* __restrict__ nbmap, int64_t n_out, int C, const E* __restrict__ z,
+                                 E* __restrict__ out) {
+    const int64_t total = n_out * 8 * C;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t pair = t / C;
+        const int32_t in = nbmap[pair];
+        if (in < 0) continue;
+        const int c = (int)(t - pair * C);
+        out[(int64_t)in * C + c] = z[(pair >> 3) * C + c];
+    }
+}
+
+static unsigned blocks_for(int64_t total) { return (unsigned)std::max<int64_t>(1, std::min<int64_t>((total + 255) / 256, 1 << 20)); }
+
+}  // namespace fx
+
+using namespace fx;
+
+static fx_status check_pair_map(const char* who, const fx_kmap* km) {
+    if (!km) { set_error("%s: null kernel map", who); return FX_EINVAL; }
+    if (km->K != 2 || km->stride != 2) { set_error("%s: needs the kernel map of a 2x2x2 stride-2 convolution", who); return FX_EUNSUPPORTED; }
+    return FX_OK;
+}
+
+extern "C" fx_status fx_pool2(const fx_kmap* km, int32_t mode, const void* d_feat, fx_dtype dt, int32_t C, void* d_out,
+                              void* stream) {
+    FX_TRY(check_pair_map("fx_pool2", km));
+    if ((mode != FX_POOL_MAX && mode != FX_POOL_AVG) || C < 1 || (dt != FX_F32 && dt != FX_F16 && dt != FX_BF16) ||
+        (km->n_in > 0 && !d_feat) || (km->n_out > 0 && !d_out)) {
+        set_error("fx_pool2: bad mode, dtype, channel count or null pointer");
+        return FX_EINVAL;
+    }
+    if (km->n_out == 0) return FX_OK;
+    hipStream_t st = (hipStream_t)stream;
+    FX_TRY(kmap_ensure_dense(const_cast<fx_kmap*>(km), st));
+    const int esize = dt == FX_F32 ? 4 : 2;
+    const bool avg = mode == FX_POOL_AVG;
+    ProfScope ps(kProfPool, st);
+    if (((int64_t)C * esize) % 16 == 0) {
+        const int vpr = C * esize / 16;
+        const unsigned nb = blocks_for(km->n_out * vpr);
+#define FX_POOL(DT) do { if (avg) k_pool2<DT, true><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, vpr, d_feat, d_out); \
+                         else k_pool2<DT, false><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, vpr, d_feat, d_out); } while (0)
+        if (dt == FX_F32) FX_POOL(FX_F32); else if (dt == FX_F16) FX_POOL(FX_F16); else FX_POOL(FX_BF16);
+#undef FX_POOL
+    } else {
+        const unsigned nb = blocks_for(km->n_out * C);
+#define FX_POOL(DT) do { if (avg) k_pool2_elem<DT, true><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, C, d_feat, d_out); \
+                         else k_pool2_elem<DT, false><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, C, d_feat, d_out); } while (0)
+        if (dt == FX_F32) FX_POOL(FX_F32); else if (dt == FX_F16) FX_POOL(FX_F16); else FX_POOL(FX_BF16);
+#undef FX_POOL
+    }
+    FX_HIP_TRY(hipGetLastError());
+    return FX_OK;
+}
+
+extern "C" fx_status fx_upsample2(const fx_kmap* km, const void* d_feat, fx_dtype dt, int32_t C, void* d_out, void* stream) {
+    FX_TRY(check_pair_map("fx_upsample2", km));
+    if (C < 1 || (dt != FX_F32 && dt != FX_F16 && dt != FX_BF16) || (km->n_out > 0 && !d_feat) || (km->n_in > 0 && !d_out)) {
+        set_error("fx_upsample2: bad dtype, channel count or null pointer");
+        return FX_EINVAL;
+    }
+    if (km->n_out == 0) return FX_OK;
+    hipStream_t st = (hipStream_t)stream;
+    FX_TRY(kmap_ensure_dense(const_cast<fx_kmap*>(km), st));
+    const int esize = dt == FX_F32 ? 4 : 2;
+    ProfScope ps(kProfUpsample, st);
+    if (((int64_t)C * esize) % 16 == 0) {
+        const int vpr = C * esize / 16;
+        k_upsample2<<<blocks_for(km->n_out * 8 * vpr), 256, 0, st>>>(km->d_nbmap, km->n_out, vpr, d_feat, d_out);
+    } else if (esize == 4) {
+        k_upsample2_elem<uint32_t><<<blocks_for(km->n_out * 8 * C), 256, 0, st>>>(km->d_nbmap, km->n_out, C, (const uint32_t*)d_feat, (uint32_t*)d_out);
+    } else {
+        k_upsample2_elem<uint16_t><<<blocks_for(km->n_out * 8 * C), 256, 0, st>>>(km->d_nbmap, km->n_out, C, (const uint16_t*)d_feat, (uint16_t*)d_out);
+    }
+    FX_HIP_TRY(hipGetLastError());
+    return FX_OK;
+}
+
+extern "C" fx_status fx_sparse_conv_transpose_fwd(const fx_kmap* km, const void* d_feat, fx_dtype dt, const void* d_w,
+                                                  int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream) {
+    if (!km || !d_w || C_in < 1 || C_out < 1 || (km->n_out > 0 && !d_feat) || (km->n_in > 0 && !d_out)) {
+        set_error("fx_sparse_conv_transpose_fwd: null pointer or non-positive channel count");
+        return FX_EINVAL;
+    }
+    if (dt != FX_F32 && dt != FX_F16 && dt != FX_BF16) { set_error("fx_sparse_conv_transpose_fwd: unknown dtype"); return FX_EINVAL; }
+    if (out_dt != dt && out_dt != FX_F32) {
+        set_error("fx_sparse_conv_transpose_fwd: output dtype must equal the input dtype or be fp32");
+        return FX_EUNSUPPORTED;
+    }
+    if (km->n_in == 0) return FX_OK;
+    hipStream_t st = (hipStream_t)stream;
+    if (km->stride == 1)   // symmetric map: the forward multiply over the mirrored offsets
+        return conv_apply(km, d_feat, dt, d_w, C_in, C_out, d_out, out_dt, st, kWeightsFlipped);
+    if (km->K != km->stride) { set_error("fx_sparse_conv_transpose_fwd: unsupported (kernel, stride)"); return FX_EUNSUPPORTED; }
+    // one pair per input voxel: the input-gradient kernel of the strided map with the weights read
+    // forward (C_in contracted, C_out produced)
+    return strided_pair_product(km, d_feat, dt, d_w, C_in, C_out, d_out, out_dt, st, kWeightsForward);
+}

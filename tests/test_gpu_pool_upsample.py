@@ -1,0 +1,152 @@
+"""GPU parity: transposed convolution, factor-2 pooling, nearest-neighbour upsampling and
+subdivision against the oracle.
+
+Bars: grids bit-exact (leaf tables); max pooling and upsampling move values unchanged, so they are
+compared bit for bit in every type; average pooling sums at most 8 values in fp32 and rounds once:
+|y - ref| <= 2^-22 * (sum of |children|) for fp32 and one rounding of the storage type on top of
+that for fp16 / bf16 (2^-10 / 2^-7 relative); transposed convolution: the forward bars with the
+number of contracted channels (fp32: max-abs <= 1e-4*sqrt(K^3*C_in); 16-bit: per-row 2e-2)."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_common as H
+import paper_2407_01781_amd as fx
+from oracle import cpu_oracle as O
+from workloads import generators as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair_map(name, dup=0.01):
+    w = G.workload(name)
+    ijk, jo = w.jagged_ijk(dup_fraction=dup)
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 2, 2)
+    ogc = og.coarsen2()
+    assert km.n_out == ogc.num_voxels
+    return km, og, ogc
+
+
+def _feat(seed, n, c, dtype):
+    return G.round_to_dtype(np.random.default_rng(seed).standard_normal((n, c)).astype(np.float32), dtype)
+
+
+@pytest.mark.parametrize("name", ["lidar_small", "sheets_small"])
+@pytest.mark.parametrize("dtype,c", [("bf16", 64), ("f16", 24), ("f32", 32), ("f32", 3), ("bf16", 5)])
+def test_pooling(name, dtype, c):
+    km, og, ogc = _pair_map(name)
+    z = _feat(41, og.num_voxels, c, dtype)
+    d_z = H.to_device_storage(z, dtype)
+    mx = fx.pool2(km, d_z, "max").float().cpu().numpy()
+    assert np.array_equal(mx, O.pool2(og, ogc, "max", z).astype(np.float32))
+    av = fx.pool2(km, d_z, "avg").float().cpu().numpy().astype(np.float64)
+    ref = O.pool2(og, ogc, "avg", z)
+    mag = O.pool2(og, ogc, "avg", np.abs(z)) * 8            # >= sum of |children|
+    rnd = {"f32": 0.0, "f16": 2.0 ** -10, "bf16": 2.0 ** -7}[dtype]
+    assert (np.abs(av - ref) <= 2.0 ** -22 * mag + rnd * np.abs(ref) + 1e-30).all()
+
+
+@pytest.mark.parametrize("name", ["lidar_small", "sheets_small"])
+@pytest.mark.parametrize("dtype,c", [("bf16", 64), ("f32", 16), ("f16", 7)])
+def test_upsampling_on_the_map_of_a_fine_grid(name, dtype, c):
+    km, og, ogc = _pair_map(name)
+    z = _feat(43, ogc.num_voxels, c, dtype)
+    up = fx.upsample2(km, H.to_device_storage(z, dtype)).float().cpu().numpy()
+    assert np.array_equal(up, O.upsample2(og, ogc, z).astype(np.float32))
+
+
+def test_subdivision_and_upsampling_onto_all_children():
+    w = G.workload("sheets_small")
+    ijk, jo = w.jagged_ijk(dup_fraction=0.01)
+    g, og = H.both_grids(ijk, jo)
+    fine, ofine = g.subdivide2(), og.subdivide2()
+    H.check_grid(fine, ofine)
+    assert fine.num_voxels == 8 * g.num_voxels
+    km = fx.build_kernel_map(fine, 2, 2)
+    # the coarse grid of the subdivided grid is the original grid, voxel for voxel
+    assert km.g_out.leaf_table().tobytes() == og.leaf_table().tobytes()
+    z = _feat(47, og.num_voxels, 32, "bf16")
+    d_z = H.to_device_storage(z, "bf16")
+    up = fx.upsample2(km, d_z)
+    assert np.array_equal(up.float().cpu().numpy(), O.upsample2(ofine, og, z).astype(np.float32))
+    # pooling undoes it exactly
+    assert torch.equal(fx.pool2(km, up, "max"), d_z) and torch.equal(fx.pool2(km, up, "avg"), d_z)
+
+
+@pytest.mark.parametrize("name", ["lidar_small_down", "sheets_small"])
+@pytest.mark.parametrize("dtype,c_in,c_out", [("bf16", 128, 64), ("f16", 32, 64), ("bf16", 64, 192), ("f32", 16, 8),
+                                             ("bf16", 48, 40)])
+def test_transposed_convolution_on_strided_maps(name, dtype, c_in, c_out):
+    km, og, ogc = _pair_map(name)
+    z = _feat(51, ogc.num_voxels, c_in, dtype)
+    _, wt = G.features_and_weights(52, 1, c_in, c_out, 8, dtype)
+    y = fx.sparse_conv_transpose_fwd(km, H.to_device_storage(z, dtype), H.to_device_storage(wt, dtype))
+    ref = O.conv_transpose(og, ogc, 2, 2, z, wt)
+    H.conv_tolerance_check(y.float().cpu().numpy(), ref, dtype, 8, c_in)
+
+
+@pytest.mark.parametrize("dtype,c_in,c_out", [("bf16", 64, 64), ("f32", 8, 12)])
+def test_transposed_convolution_on_a_submanifold_map(dtype, c_in, c_out):
+    w = G.workload("lidar_small")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 3, 1)
+    z = _feat(53, og.num_voxels, c_in, dtype)
+    _, wt = G.features_and_weights(54, 1, c_in, c_out, 27, dtype)
+    y = fx.sparse_conv_transpose_fwd(km, H.to_device_storage(z, dtype), H.to_device_storage(wt, dtype))
+    H.conv_tolerance_check(y.float().cpu().numpy(), O.conv_transpose(og, og, 3, 1, z, wt), dtype, 27, c_in)
+
+
+def test_scalar_path_of_the_transposed_convolution(monkeypatch):
+    monkeypatch.setenv("FVDB_HOTPATH_FORCE_SCALAR", "1")
+    km, og, ogc = _pair_map("lidar_small_down")
+    z = _feat(55, ogc.num_voxels, 64, "bf16")
+    _, wt = G.features_and_weights(56, 1, 64, 64, 8, "bf16")
+    y = fx.sparse_conv_transpose_fwd(km, H.to_device_storage(z, "bf16"), H.to_device_storage(wt, "bf16"))
+    H.conv_tolerance_check(y.float().cpu().numpy(), O.conv_transpose(og, ogc, 2, 2, z, wt), "bf16", 8, 64)
+
+
+def test_wrong_map_and_empty_grid():
+    w = G.workload("lidar_small")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km3 = fx.build_kernel_map(g, 3, 1)
+    z = torch.zeros((g.num_voxels, 8), dtype=torch.float32, device="cuda")
+    with pytest.raises(fx.FxError):
+        fx.pool2(km3, z)
+    with pytest.raises(fx.FxError):
+        fx.upsample2(km3, z)
+    ge, _ = H.both_grids(np.zeros((0, 3), np.int32), np.array([[0, 0]], np.int64))
+    kme = fx.build_kernel_map(ge, 2, 2)
+    e = torch.zeros((0, 8), dtype=torch.float32, device="cuda")
+    assert fx.pool2(kme, e).shape == (0, 8) and fx.upsample2(kme, e).shape == (0, 8)
+    assert ge.subdivide2().num_voxels == 0
+
+
+def test_full_size_config4_grid():
+    """The 1M-voxel grid of config 4 and its coarse grid: pooling and upsampling bit for bit on whole
+    arrays (the oracle does these in seconds); transposed convolution 128 -> 64 on sampled rows."""
+    w = G.workload("lidar1m_down")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 2, 2)
+    ogc = og.coarsen2()
+    z = _feat(61, og.num_voxels, 64, "bf16")
+    d_z = H.to_device_storage(z, "bf16")
+    pooled = fx.pool2(km, d_z, "max")
+    ref_pool = O.pool2(og, ogc, "max", z)
+    assert np.array_equal(pooled.float().cpu().numpy(), ref_pool.astype(np.float32))
+    up = fx.upsample2(km, pooled).float().cpu().numpy()
+    assert np.array_equal(up, O.upsample2(og, ogc, ref_pool).astype(np.float32))
+    zc = _feat(62, ogc.num_voxels, 128, "bf16")
+    _, wt = G.features_and_weights(63, 1, 128, 64, 8, "bf16")
+    y = fx.sparse_conv_transpose_fwd(km, H.to_device_storage(zc, "bf16"), H.to_device_storage(wt, "bf16")).float().cpu().numpy()
+    # rows of the fine grid whose parents are the first / last 200 coarse voxels
+    nb = O.kernel_map(og, ogc, 2, 2)
+    for sl in (slice(0, 200), slice(ogc.num_voxels - 200, ogc.num_voxels)):
+        zs = np.zeros_like(zc)
+        zs[sl] = zc[sl]
+        ref = O.conv_transpose(og, ogc, 2, 2, zs, wt)
+        rows = nb[sl][nb[sl] >= 0]
+        H.conv_tolerance_check(y[rows], ref[rows], "bf16", 8, 128)
