@@ -570,7 +570,10 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
             rank += (cg > c) || (cg == c && g < tid);
         }
         const int gi = rank / kTileWaves, r = rank % kTileWaves;
-        L.group_src[tile_group_of((gi & 1) ? kTileWaves - 1 - r : r, gi)] = (uint32_t)tid;
+        // (tiles without staged rows go to the one-wave-per-block gather kernels, which gain nothing
+        // from the deal and run the mask-sorted order slightly faster: they keep it)
+        if (direct) L.group_src[tid] = (uint32_t)tid;
+        else L.group_src[tile_group_of((gi & 1) ? kTileWaves - 1 - r : r, gi)] = (uint32_t)tid;
     }
     __syncthreads();
     const uint32_t dealt = S.key[L.group_src[tid / kGroup] * kGroup + tid % kGroup];   // slot at final position tid
