@@ -764,6 +764,159 @@ k_conv_gather(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restric
     }
 }
 
+// ---------------------------------------------------------------------------------- gather kernel, weights in LDS
+// k_conv_gather issues six vector loads per four multiplies, four of them for the weights, and
+// is bound by the load path of the compute unit (one wave-wide 16-byte load occupies it for at
+// least 16 cycles).  When the packed weights of one 64-channel output slice fit in LDS next to
+// the row tables (K^3 * C_in * 128 bytes; 64 KB for a 2x2x2 kernel with 64 input channels), a
+// persistent workgroup of 16 waves copies them there once, and each wave then walks column
+// blocks of that slice exactly as k_conv_gather does, with its A fragments read from LDS: two
+// vector loads per four multiplies.  Workgroup b serves slice b % nslice.
+constexpr int kGatherLdsWaves = 16;
+
+template <typename T, bool OUT_F32>
+__global__ void __launch_bounds__(64 * kGatherLdsWaves, 1)
+k_conv_gather_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
+                   const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
+                   int block_stride, int64_t n_blocks_total, int K3, const uint16_t* __restrict__ feat,
+                   const uint16_t* __restrict__ wp, int C_in, int C_out, void* __restrict__ out) {
+    typedef typename Elem<T>::vec8 vec8;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
+    const int slice = blockIdx.x % nslice;
+    const int wg = blockIdx.x / nslice, n_wg = gridDim.x / nslice;      // the launch makes gridDim a multiple of nslice
+    unsigned char* wlds = lds_raw;                                       // [kappa][chunk][4 fragments][64 lanes][16 bytes]
+    const int w_bytes = K3 * nchunk * 4096;
+    int32_t* row_of = reinterpret_cast<int32_t*>(lds_raw + w_bytes) + wave * 2 * K3 * kGroup;   // two tables [rank][voxel]
+
+    for (int sl = wave; sl * 1024 < w_bytes; sl += kGatherLdsWaves) {   // 1 KB = one fragment of all lanes
+        const int kc = sl >> 2, f = sl & 3;                              // (kappa * nchunk + chunk), fragment
+        const unsigned char* src = reinterpret_cast<const unsigned char*>(wp) + ((size_t)(kc * nslice + slice) * 4 + f) * 1024 + lane * 16;
+        __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(wlds + sl * 1024), 16, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    const int n = lane & 31, h = lane >> 5;
+    vec8 zero;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) zero[e] = 0;
+    // (offset rank, voxel) -> global input row of column block tg, into table `tab`; lane (n, h)
+    // resolves every second offset.  Returns the block's offset mask.
+    auto resolve = [&](int64_t tg, int32_t* tab) -> uint32_t {
+        const int g = (int)(tg % kGroupsPerTile);
+        const int64_t tile = tg / kGroupsPerTile;
+        const TileHeader* H = tile_hdr + tile;
+        const int w = tile_wave_of(g), gi = tile_slot_of(g);
+        const uint32_t gm = (uint32_t)uni((int)H->group_mask[g]);
+        const uint32_t wm = (uint32_t)uni((int)H->wave_mask[w]);
+        const int flags = uni(H->flags), win_lo = uni(H->win_lo), win_n = uni(H->win_n);
+        const size_t blk0 = (size_t)tile * block_stride + (uint32_t)uni((int)H->wave_block0[w]);
+        const int32_t* rows = tile_rows + tile * (int64_t)row_stride;
+        int rank = 0;
+#pragma unroll 1
+        for (uint32_t m = gm; m; m &= m - 1, ++rank) {
+            if ((rank & 1) != h) continue;
+            const int kappa = __ffs(m) - 1;
+            const size_t blk = blk0 + __popc(wm & ((1u << kappa) - 1u));
+            uint32_t id = tile_blocks[blk * kIdBlockElems + n * kGroupsPerWave + gi];
+            if (flags & kTileLdsOffsets) id = (id / kRowBytes == (uint32_t)kRowCap) ? kNoRow : id / kRowBytes;
+            int32_t r = -1;
+            if (id != kNoRow) r = id < (uint32_t)win_n ? win_lo + (int32_t)id : rows[id - (uint32_t)win_n];
+            tab[rank * kGroup + n] = r;
+        }
+        return gm;
+    };
+    // Two row tables per wave: the next block's table is resolved (two dependent global loads) while
+    // the current block multiplies.
+    const int64_t tg_stride = (int64_t)n_wg * kGatherLdsWaves;
+    int64_t tg = (int64_t)wg * kGatherLdsWaves + wave;
+    int cur = 0;
+    uint32_t gm_next = tg < n_blocks_total ? resolve(tg, row_of) : 0u;
+#pragma unroll 1
+    for (; tg < n_blocks_total; tg += tg_stride, cur ^= 1) {
+        const int g = (int)(tg % kGroupsPerTile);
+        const int64_t tile = tg / kGroupsPerTile;
+        const int n_valid = uni(tile_hdr[tile].n_out);
+        const uint32_t gm = gm_next;
+        const int32_t* tab = row_of + cur * K3 * kGroup;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // a wave's LDS accesses are processed in order
+        __builtin_amdgcn_wave_barrier();
+        if (tg + tg_stride < n_blocks_total) gm_next = resolve(tg + tg_stride, row_of + (cur ^ 1) * K3 * kGroup);
+
+        f32x16 acc[2];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
+        const int n_steps = __popc(gm) * nchunk;        // step = (offset rank, chunk), chunk fastest
+        // B fragments of step `step` into b; returns where the step's A fragments start in LDS
+        // fetches come in step order: (offset rank, chunk) advance with them
+        int f_rank = -1, f_c = nchunk - 1;
+        auto fetch = [&](vec8 (&b)[2], int step, uint32_t& rest, int& kappa) {
+            if (++f_c == nchunk) { f_c = 0; ++f_rank; kappa = __ffs(rest | 0x80000000u) - 1; rest &= rest - 1; }
+            const int32_t r = step < n_steps ? tab[f_rank * kGroup + n] : -1;
+            b[0] = zero; b[1] = zero;
+            if (r >= 0) {
+                const uint16_t* src = feat + (int64_t)r * C_in + f_c * kCinChunk + h * 8;
+                b[0] = *reinterpret_cast<const vec8*>(src);
+                b[1] = *reinterpret_cast<const vec8*>(src + 16);
+            }
+            return (kappa * nchunk + f_c) * 4096 + lane * 16;
+        };
+        auto multiply = [&](const vec8 (&b)[2], int w_at) {
+            vec8 wf[4];
+#pragma unroll
+            for (int f = 0; f < 4; ++f) wf[f] = *reinterpret_cast<const vec8*>(wlds + w_at + f * 1024);
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wf[mt * 2 + ks], b[ks], acc[mt]);
+        };
+        // the gather of the next step is in flight while one multiplies (two fragment sets; a deeper
+        // ring at three waves per SIMD measured slower: 85 us against 79 at config 4)
+        vec8 ba[2], bb[2];
+        uint32_t rest = gm;
+        int kappa = 0, wa_at = 0, wb_at = 0;
+        if (n_steps > 0) wa_at = fetch(ba, 0, rest, kappa);
+#pragma unroll 1
+        for (int step = 0; step < n_steps; step += 2) {
+            if (step + 1 < n_steps) wb_at = fetch(bb, step + 1, rest, kappa);
+            multiply(ba, wa_at);
+            if (step + 1 >= n_steps) break;
+            if (step + 2 < n_steps) wa_at = fetch(ba, step + 2, rest, kappa);
+            multiply(bb, wb_at);
+        }
+
+        const int local = tile_perm[tile * kTileT + g * kGroup + n];
+        if (local < n_valid) {
+            const int64_t o = tile * kTileT + local;
+            const int64_t col = (int64_t)slice * kCoutSlice + 32 * h;
+            if (OUT_F32) {
+                float* dst = reinterpret_cast<float*>(out) + o * C_out + col;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; ++v4)
+                        *reinterpret_cast<f32x4*>(dst + 16 * mt + 4 * v4) =
+                            f32x4{acc[mt][4 * v4], acc[mt][4 * v4 + 1], acc[mt][4 * v4 + 2], acc[mt][4 * v4 + 3]};
+            } else {
+                uint16_t* dst = reinterpret_cast<uint16_t*>(out) + o * C_out + col;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int v8 = 0; v8 < 2; ++v8) {
+                        u32x4 pk;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) pk[e] = Elem<T>::pack2(acc[mt][8 * v8 + 2 * e], acc[mt][8 * v8 + 2 * e + 1]);
+                        *reinterpret_cast<u32x4*>(dst + 16 * mt + 8 * v8) = pk;
+                    }
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------- scalar path
 // One thread per (output voxel, output channel); fp32 FMA in offset-then-channel order.  Used
 // for fp32 data (true fp32 products) and for channel counts the MFMA tiling does not cover.
@@ -870,6 +1023,22 @@ static hipError_t launch_mfma(const fx_kmap* km, const void* feat, const void* w
 template <typename T, bool OUT_F32>
 static hipError_t launch_gather(const fx_kmap* km, const void* feat, const void* wp, int C_in, int C_out, void* out,
                                 hipStream_t st) {
+    const int nslice = C_out / kCoutSlice;
+    const size_t lds = (size_t)km->K3 * (C_in / kCinChunk) * 4096 + (size_t)kGatherLdsWaves * 2 * km->K3 * kGroup * sizeof(int32_t);
+    const char* fl = getenv("FVDB_HOTPATH_GATHER_LDS");     // "0": never keep the weights in LDS (tests)
+    if (lds <= 160 * 1024 && !(fl && fl[0] == '0')) {
+        hipError_t e = hipFuncSetAttribute((const void*)k_conv_gather_ldsw<T, OUT_F32>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        const int64_t n_blocks_total = km->n_tiles * (int64_t)kGroupsPerTile;
+        // one workgroup per compute unit, a multiple of the slice count, no more than there is work for
+        int64_t grid = std::max(nslice, compute_units() / nslice * nslice);
+        grid = std::min<int64_t>(grid, (n_blocks_total + kGatherLdsWaves - 1) / kGatherLdsWaves * nslice);
+        k_conv_gather_ldsw<T, OUT_F32><<<(unsigned)grid, 64 * kGatherLdsWaves, lds, st>>>(
+            km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows, km->row_stride, km->d_tile_blocks, km->block_stride,
+            n_blocks_total, km->K3, (const uint16_t*)feat, (const uint16_t*)wp, C_in, C_out, out);
+        return hipGetLastError();
+    }
     const int64_t n_items = km->n_tiles * (int64_t)kGroupsPerTile * (C_out / kCoutSlice);
     const unsigned grid = (unsigned)((n_items + kGatherWaves - 1) / kGatherWaves);
     k_conv_gather<T, OUT_F32><<<grid, 64 * kGatherWaves, 0, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,

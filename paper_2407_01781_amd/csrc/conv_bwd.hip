@@ -203,9 +203,10 @@ __global__ void k_conv_transpose_scalar(const int32_t* __restrict__ nbmap, int64
 
 // ---------------------------------------------------------------------------------- weight gradient, MFMA
 // A workgroup owns a block of 32 input channels x 64 output channels of every gw[kappa] and a
-// contiguous range of tiles; its 8 waves split the offsets (wave w: kappa = w, w+8, w+16, w+24),
-// so a wave keeps 4 offsets x 2 accumulator tiles (32 ci x 32 co) in registers over the whole
-// range.  Per tile the workgroup stages, single-buffered: the tile's input rows (32 channels,
+// contiguous range of tiles; its 16 waves split the offsets (wave w: kappa = w, w+16), so a wave
+// keeps 2 offsets x 2 accumulator tiles (32 ci x 32 co) in registers over the whole range, and four
+// waves per SIMD hide each other's LDS and matrix latencies (the per-block chain read -> identity
+// product -> rounding -> products is not software-pipelined).  Per tile the workgroup stages, single-buffered: the tile's input rows (32 channels,
 // the forward kernel's LDS row layout, so the map's precomputed LDS offsets apply), its id
 // blocks, and the gout rows of its 512 outputs transposed to [channel][slot] (2 bytes per element,
 // row stride padded by 8 bytes so a fragment read of 32 channels spreads over all banks).
@@ -225,7 +226,7 @@ __global__ void k_conv_transpose_scalar(const int32_t* __restrict__ nbmap, int64
 // of the last tile has a zero gout column.
 // Partial sums go to part[range][kappa][ci][co] (fp32); k_wgrad_reduce adds the ranges in
 // ascending order, so the result does not depend on scheduling.
-constexpr int kWgWaves = 8;
+constexpr int kWgWaves = 16;
 constexpr int kWgThreads = 64 * kWgWaves;
 constexpr int kWgCi = kCinChunk;            // 32: the row chunk staged in LDS
 constexpr int kWgCo = 64;
@@ -238,7 +239,7 @@ struct WgradLds {
     unsigned char gt[kWgCo * kGtStride];
 };
 static_assert(sizeof(WgradLds) <= 160 * 1024, "LDS budget of one compute unit");
-static_assert(kTileT == kWgThreads, "one thread stages one output slot");
+static_assert(kWgThreads % kTileT == 0 && (kWgCo / 8) % (kWgThreads / kTileT) == 0, "threads per output slot when staging gout");
 static_assert(kGroupsPerWave == 4 && kTileWaves == 4, "id blocks of four column blocks, 8 bytes per voxel");
 
 template <typename T>
@@ -253,7 +254,14 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, h = lane >> 5;
     const int n_cib = C_in / kWgCi, n_cblk = n_cib * (C_out / kWgCo);
-    const int blk = blockIdx.x % n_cblk, range = blockIdx.x / n_cblk;
+    // Workgroup b runs on XCD b % 8.  The channel blocks of one tile range read the same gout tiles and
+    // id blocks: with the number of ranges a multiple of 8 they get block indices 8 apart, so they share
+    // an XCD and its L2 and run side by side.
+    int blk = blockIdx.x % n_cblk, range = blockIdx.x / n_cblk;
+    if (n_ranges % 8 == 0) {
+        blk = (blockIdx.x >> 3) % n_cblk;
+        range = (int)(blockIdx.x / (8 * n_cblk)) * 8 + (blockIdx.x & 7);
+    }
     const int cib = blk % n_cib, cob = blk / n_cib;
     const int64_t t0 = n_tiles * range / n_ranges, t1 = n_tiles * (range + 1) / n_ranges;
 
@@ -284,6 +292,26 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
             for (int v = 0; v < 16; ++v) acc[j][cb][v] = 0.f;
 
     const uint32_t hsel = (uint32_t)h << 4;
+    // kSlotThreads threads stage one output slot, each kPieces 16-byte pieces of its gout row
+    constexpr int kSlotThreads = kWgThreads / kTileT, kPieces = kWgCo / 8 / kSlotThreads;
+    constexpr int kWgSlabs = ((kRowCap + 15) / 16 + kWgWaves - 1) / kWgWaves;   // 1 KB row slabs per wave
+    const int slot = tid % kTileT, part_of_row = tid / kTileT;
+    int32_t nx_gr[kWgSlabs];
+    int nx_local = 0;
+    auto resolve = [&](int64_t t) {
+        const TileHeader* Ht = tile_hdr + t;
+        const int fl = uni(Ht->flags), wl = uni(Ht->win_lo), wn = uni(Ht->win_n), nl = uni(Ht->n_list);
+        const int ns = (fl & kTileDirect) ? 0 : min(wn + nl, kRowCap);
+        const int32_t* rows_t = tile_rows + t * (int64_t)row_stride;
+#pragma unroll
+        for (int j = 0; j < kWgSlabs; ++j) {
+            const int r = 16 * (wave + kWgWaves * j) + (lane >> 2);
+            nx_gr[j] = -1;
+            if (r < ns) nx_gr[j] = r < wn ? wl + r : rows_t[r - wn];
+        }
+        nx_local = tile_perm[t * kTileT + slot];
+    };
+    if (t0 < t1) resolve(t0);
     for (int64_t tile = t0; tile < t1; ++tile) {
         const TileHeader* H = tile_hdr + tile;
         const int flags = uni(H->flags), win_lo = uni(H->win_lo), win_n = uni(H->win_n), n_list = uni(H->n_list);
@@ -301,16 +329,20 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
 #pragma unroll
         for (int g = 0; g < kGroupsPerTile; ++g) gmask[g] = (uint32_t)uni((int)H->group_mask[g]);
 
-        // ---- stage: input rows (32 channels of this block), id blocks, transposed gout
+        // ---- stage: input rows (32 channels of this block), id blocks, transposed gout.  The global
+        // row of every slab piece and the output row of the thread's slot were resolved while the
+        // previous tile was staged, so all of this tile's loads leave at once.
         {
-            const int n_slabs = (n_staged + 15) >> 4;
             const int piece = (lane & 3) ^ ((lane >> 4) & 3);
-            for (int s = wave; s < n_slabs; s += kWgWaves) {
-                const int r = 16 * s + (lane >> 2);
-                if (r < n_staged) {
-                    const int64_t gr = r < win_n ? (int64_t)win_lo + r : (int64_t)my_rows[r - win_n];
-                    const uint16_t* src = feat + gr * C_in + cib * kWgCi + piece * 8;
-                    __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(L.rows + s * 1024), 16, 0, 0);
+            int32_t gr[kWgSlabs];
+#pragma unroll
+            for (int j = 0; j < kWgSlabs; ++j) gr[j] = nx_gr[j];
+            const int local = nx_local;
+#pragma unroll
+            for (int j = 0; j < kWgSlabs; ++j) {
+                if (gr[j] >= 0) {
+                    const uint16_t* src = feat + (int64_t)gr[j] * C_in + cib * kWgCi + piece * 8;
+                    __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(L.rows + (wave + kWgWaves * j) * 1024), 16, 0, 0);
                 }
             }
             const unsigned char* bsrc =
@@ -320,18 +352,29 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
                 const int off = s * 1024 + lane * 16;
                 if (off < bytes) __builtin_amdgcn_global_load_lds(bsrc + off, (lds_ptr_t)(L.blocks + s * 1024), 16, 0, 0);
             }
-            const int local = tile_perm[tile * kTileT + tid];
-            const uint16_t* grow = gout + (tile * kTileT + local) * (int64_t)C_out + cob * kWgCo;
-            u32x4 gv[kWgCo / 8];
+            const uint16_t* grow = gout + (tile * kTileT + local) * (int64_t)C_out + cob * kWgCo + part_of_row * kPieces * 8;
+            u32x4 gv[kPieces];
 #pragma unroll
-            for (int q = 0; q < kWgCo / 8; ++q)
+            for (int q = 0; q < kPieces; ++q)
                 gv[q] = local < n_valid ? *reinterpret_cast<const u32x4*>(grow + q * 8) : u32x4{0, 0, 0, 0};
+            if (tile + 1 < t1) resolve(tile + 1);
+            // Transposed store, two slots per 4-byte word: a thread pair (slots 2p, 2p+1) exchanges words
+            // across lanes; the even thread then writes the channels of the low halves (channel 2j of
+            // word j), the odd thread those of the high halves (channel 2j+1), each as the word
+            // (value of slot 2p) | (value of slot 2p+1) << 16 at gt[channel][slot 2p].
+            const int odd = tid & 1;
 #pragma unroll
-            for (int q = 0; q < kWgCo / 8; ++q)
+            for (int q = 0; q < kPieces; ++q)
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    *reinterpret_cast<uint16_t*>(L.gt + (q * 8 + e) * kGtStride + tid * 2) =
-                        (uint16_t)(gv[q][e >> 1] >> (16 * (e & 1)));
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t mine = gv[q][j];
+                    const uint32_t other = (uint32_t)__shfl_xor((int)mine, 1);
+                    const uint32_t lo_slot = odd ? other : mine, hi_slot = odd ? mine : other;   // words of slots 2p, 2p+1
+                    const uint32_t word = odd ? ((lo_slot >> 16) | (hi_slot & 0xFFFF0000u))
+                                              : ((lo_slot & 0xFFFFu) | (hi_slot << 16));
+                    const int ch = (part_of_row * kPieces + q) * 8 + 2 * j + odd;
+                    *reinterpret_cast<uint32_t*>(L.gt + ch * kGtStride + (slot & ~1) * 2) = word;
+                }
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
@@ -403,10 +446,37 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
     }
 }
 
-// gw[e] = part[0][e] + part[1][e] + ... in ascending order, rounded once to the output type.
+// gw[e] = part[0][e] + part[1][e] + ... in ascending order, rounded once to the output type.  One
+// thread per four consecutive elements when the element count is a multiple of 4 (both channel counts
+// even), one per element otherwise.
 template <int OUT_DT>
 __global__ void k_wgrad_reduce(const float* __restrict__ part, int n_ranges, int64_t total, void* __restrict__ gw) {
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t n4 = (total & 3) ? 0 : total / 4;    // the vector path needs every range 16-byte aligned
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < n4; q += (int64_t)gridDim.x * blockDim.x) {
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+        int r = 0;
+        for (; r + 4 <= n_ranges; r += 4) {   // four loads in flight, added in ascending order
+            const f32x4 a = *reinterpret_cast<const f32x4*>(part + (int64_t)r * total + 4 * q);
+            const f32x4 b = *reinterpret_cast<const f32x4*>(part + (int64_t)(r + 1) * total + 4 * q);
+            const f32x4 c = *reinterpret_cast<const f32x4*>(part + (int64_t)(r + 2) * total + 4 * q);
+            const f32x4 d = *reinterpret_cast<const f32x4*>(part + (int64_t)(r + 3) * total + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] = (((s[e] + a[e]) + b[e]) + c[e]) + d[e];
+        }
+        for (; r < n_ranges; ++r) {
+            const f32x4 a = *reinterpret_cast<const f32x4*>(part + (int64_t)r * total + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] += a[e];
+        }
+        if (OUT_DT == FX_F32) *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(gw) + 4 * q) = s;
+        else if (OUT_DT == FX_F16)
+            *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(gw) + 4 * q) =
+                u32x2{Elem<_Float16>::pack2(s[0], s[1]), Elem<_Float16>::pack2(s[2], s[3])};
+        else
+            *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(gw) + 4 * q) =
+                u32x2{Elem<__bf16>::pack2(s[0], s[1]), Elem<__bf16>::pack2(s[2], s[3])};
+    }
+    for (int64_t e = 4 * n4 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
         float s = 0.f;
         for (int r = 0; r < n_ranges; ++r) s += part[(int64_t)r * total + e];
         if (OUT_DT == FX_F32) reinterpret_cast<float*>(gw)[e] = s;
@@ -439,7 +509,7 @@ __global__ void k_wgrad_scalar(const int32_t* __restrict__ nbmap, int64_t n_out,
 }
 
 static hipError_t launch_reduce(const float* part, int n_ranges, int64_t total, void* gw, fx_dtype out_dt, hipStream_t st) {
-    const unsigned nb = (unsigned)std::min<int64_t>((total + 255) / 256, 1 << 16);
+    const unsigned nb = (unsigned)std::max<int64_t>(1, std::min<int64_t>((total / 4 + 255) / 256, 1 << 16));
     ProfScope ps(kProfWgradReduce, st);
     if (out_dt == FX_F32) k_wgrad_reduce<FX_F32><<<nb, 256, 0, st>>>(part, n_ranges, total, gw);
     else if (out_dt == FX_F16) k_wgrad_reduce<FX_F16><<<nb, 256, 0, st>>>(part, n_ranges, total, gw);
@@ -565,6 +635,7 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
     if (mfma) {
         const int n_cblk = (C_in / kWgCi) * (C_out / kWgCo);
         n_ranges = (int)std::max<int64_t>(1, std::min<int64_t>(km->n_tiles, compute_units() / n_cblk));
+        if (n_ranges > 8) n_ranges -= n_ranges % 8;   // see the block-to-XCD mapping in the kernel
         FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * n_ranges, st));
         const size_t lds = sizeof(WgradLds);
         ProfScope ps(kProfWgrad, st);

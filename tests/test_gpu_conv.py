@@ -46,6 +46,18 @@ def test_both_mfma_kernels_serve_every_map(name, gather, monkeypatch):
     H.conv_tolerance_check(y, ref, dt, k3, c_in)
 
 
+@pytest.mark.parametrize("lds_weights", ["0", "1"])
+def test_gather_kernel_with_and_without_weights_in_lds(lds_weights, monkeypatch):
+    # strided maps: by default the packed weights of a slice sit in LDS when they fit; the switch
+    # sends the same map to the kernel that fetches them per step
+    monkeypatch.setenv("FVDB_HOTPATH_GATHER_LDS", lds_weights)
+    for name, c_in, c_out in (("lidar_small_down", 64, 128), ("lidar_small_down", 32, 64), ("sheets_small", 32, 64)):
+        if name == "sheets_small":
+            monkeypatch.setenv("FVDB_HOTPATH_CONV_GATHER", "1")      # K = 3: 27 x 32 channels no longer fit, falls back
+        y, ref, dt, k3, ci = _run(G.workload(name), c_in=c_in, c_out=c_out, dtype="bf16")
+        H.conv_tolerance_check(y, ref, dt, k3, ci)
+
+
 def test_mfma_path_deep_channels():
     y, ref, dt, k3, c_in = _run(G.workload("sheets_small"))
     H.conv_tolerance_check(y, ref, dt, k3, c_in)
