@@ -153,6 +153,129 @@ k_dgrad_strided(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restr
     }
 }
 
+// The same product with the packed weights of one produced slice kept in LDS and the block's B
+// fragments kept in registers for all offsets (at most kDgradMaxChunks 32-channel chunks): the
+// offset loop then issues no vector loads at all.  Persistent workgroups of 16 waves; workgroup b
+// serves produced slice b % nslice and walks column blocks with a stride.
+constexpr int kDgradLdsWaves = 16;
+constexpr int kDgradMaxChunks = 4;
+
+template <typename T, bool OUT_F32>
+__global__ void __launch_bounds__(64 * kDgradLdsWaves, 1)
+k_dgrad_strided_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
+                     const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
+                     int block_stride, int64_t n_blocks_total, int K3, const uint16_t* __restrict__ gout,
+                     const uint16_t* __restrict__ wp, int C_contract, int C_produce, void* __restrict__ gin) {
+    typedef typename Elem<T>::vec8 vec8;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nchunk = C_contract / kCinChunk, nslice = C_produce / kCoutSlice;
+    const int slice = blockIdx.x % nslice;
+    const int wg = blockIdx.x / nslice, n_wg = gridDim.x / nslice;
+    unsigned char* wlds = lds_raw;                                       // [kappa][chunk][4 fragments][64 lanes][16 bytes]
+    const int w_bytes = K3 * nchunk * 4096;
+    int32_t* row_of = reinterpret_cast<int32_t*>(lds_raw + w_bytes) + wave * K3 * kGroup;   // [rank][voxel]
+    for (int sl = wave; sl * 1024 < w_bytes; sl += kDgradLdsWaves) {
+        const int kc = sl >> 2, f = sl & 3;
+        const unsigned char* src = reinterpret_cast<const unsigned char*>(wp) + ((size_t)(kc * nslice + slice) * 4 + f) * 1024 + lane * 16;
+        __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(wlds + sl * 1024), 16, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    const int n = lane & 31, h = lane >> 5;
+    vec8 zero;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) zero[e] = 0;
+#pragma unroll 1
+    for (int64_t tg = (int64_t)wg * kDgradLdsWaves + wave; tg < n_blocks_total; tg += (int64_t)n_wg * kDgradLdsWaves) {
+        const int g = (int)(tg % kGroupsPerTile);
+        const int64_t tile = tg / kGroupsPerTile;
+        const TileHeader* H = tile_hdr + tile;
+        const int w = tile_wave_of(g), gi = tile_slot_of(g);
+        const uint32_t gm = (uint32_t)uni((int)H->group_mask[g]);
+        const uint32_t wm = (uint32_t)uni((int)H->wave_mask[w]);
+        const int n_valid = uni(H->n_out);
+        {
+            const int flags = uni(H->flags), win_lo = uni(H->win_lo), win_n = uni(H->win_n);
+            const size_t blk0 = (size_t)tile * block_stride + (uint32_t)uni((int)H->wave_block0[w]);
+            const int32_t* rows = tile_rows + tile * (int64_t)row_stride;
+            int rank = 0;
+#pragma unroll 1
+            for (uint32_t m = gm; m; m &= m - 1, ++rank) {
+                if ((rank & 1) != h) continue;
+                const int kappa = __ffs(m) - 1;
+                const size_t blk = blk0 + __popc(wm & ((1u << kappa) - 1u));
+                const uint32_t id = tile_blocks[blk * kIdBlockElems + n * kGroupsPerWave + gi];
+                row_of[rank * kGroup + n] = tile_row_of(id, flags, win_lo, win_n, rows);
+            }
+        }
+        // the block's rows of the contracted side, all chunks, for every offset
+        const int local = tile_perm[tile * kTileT + g * kGroup + n];
+        const bool valid = local < n_valid;
+        const uint16_t* grow = gout + (tile * kTileT + (valid ? local : 0)) * (int64_t)C_contract + h * 8;
+        vec8 b[kDgradMaxChunks][2];
+#pragma unroll
+        for (int c = 0; c < kDgradMaxChunks; ++c) {
+            b[c][0] = zero; b[c][1] = zero;
+            if (valid && c < nchunk) {
+                b[c][0] = *reinterpret_cast<const vec8*>(grow + c * kCinChunk);
+                b[c][1] = *reinterpret_cast<const vec8*>(grow + c * kCinChunk + 16);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        int rank = 0;
+#pragma unroll 1
+        for (uint32_t m = gm; m; m &= m - 1, ++rank) {
+            const int kappa = __ffs(m) - 1;
+            f32x16 acc[2];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
+#pragma unroll
+            for (int c = 0; c < kDgradMaxChunks; ++c) {
+                if (c < nchunk) {
+                    const unsigned char* ws = wlds + (kappa * nchunk + c) * 4096 + lane * 16;
+                    vec8 wf[4];
+#pragma unroll
+                    for (int f = 0; f < 4; ++f) wf[f] = *reinterpret_cast<const vec8*>(ws + f * 1024);
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                        for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wf[mt * 2 + ks], b[c][ks], acc[mt]);
+                }
+            }
+            const int32_t r = row_of[rank * kGroup + n];
+            if (r < 0) continue;
+            const int64_t col = (int64_t)slice * kCoutSlice + 32 * h;
+            if (OUT_F32) {
+                float* dst = reinterpret_cast<float*>(gin) + (int64_t)r * C_produce + col;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; ++v4)
+                        *reinterpret_cast<f32x4*>(dst + 16 * mt + 4 * v4) =
+                            f32x4{acc[mt][4 * v4], acc[mt][4 * v4 + 1], acc[mt][4 * v4 + 2], acc[mt][4 * v4 + 3]};
+            } else {
+                uint16_t* dst = reinterpret_cast<uint16_t*>(gin) + (int64_t)r * C_produce + col;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int v8 = 0; v8 < 2; ++v8) {
+                        u32x4 pk;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) pk[e] = Elem<T>::pack2(acc[mt][8 * v8 + 2 * e], acc[mt][8 * v8 + 2 * e + 1]);
+                        *reinterpret_cast<u32x4*>(dst + 16 * mt + 8 * v8) = pk;
+                    }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();     // the row table is rewritten for the next block
+    }
+}
+
 // One thread per (pair, input channel) of a K = stride map (each input row has exactly one pair):
 // gin[map(o,kappa), ci] = sum_co W[kappa][ci][co] * gout[o][co], fp32 FMA in channel order.
 template <int DT, bool OUT_F32>
@@ -534,7 +657,29 @@ fx_status strided_pair_product(const fx_kmap* km, const void* d_src, fx_dtype dt
         int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
         launch_pack_weights(d_w, wp, km->K3, C_contract, C_produce, 2, counters, mode, kPackRows, st);
         hipError_t e = hipGetLastError();
-        if (e == hipSuccess) {
+        const int nslice = C_produce / kCoutSlice, nchunk = C_contract / kCinChunk;
+        const size_t lds = (size_t)km->K3 * nchunk * 4096 + (size_t)kDgradLdsWaves * km->K3 * kGroup * sizeof(int32_t);
+        const char* fl = getenv("FVDB_HOTPATH_GATHER_LDS");     // "0": never keep the weights in LDS (tests)
+        const bool lds_weights = lds <= 160 * 1024 && nchunk <= kDgradMaxChunks && !(fl && fl[0] == '0');
+        if (e == hipSuccess && lds_weights) {
+            const int64_t n_blocks_total = km->n_tiles * (int64_t)kGroupsPerTile;
+            int64_t grid = std::max(nslice, compute_units() / nslice * nslice);
+            grid = std::min<int64_t>(grid, (n_blocks_total + kDgradLdsWaves - 1) / kDgradLdsWaves * nslice);
+            ProfScope ps(kProfDgradStrided, st);
+#define FX_DGRAD(T, F32)                                                                                              \
+    do {                                                                                                              \
+        e = hipFuncSetAttribute((const void*)k_dgrad_strided_ldsw<T, F32>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                (int)lds);                                                                            \
+        if (e == hipSuccess)                                                                                          \
+            k_dgrad_strided_ldsw<T, F32><<<(unsigned)grid, 64 * kDgradLdsWaves, lds, st>>>(                            \
+                km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows, km->row_stride, km->d_tile_blocks, km->block_stride, \
+                n_blocks_total, km->K3, (const uint16_t*)d_src, (const uint16_t*)wp, C_contract, C_produce, d_dst);    \
+    } while (0)
+            if (dt == FX_BF16) { if (out_f32) FX_DGRAD(__bf16, true); else FX_DGRAD(__bf16, false); }
+            else { if (out_f32) FX_DGRAD(_Float16, true); else FX_DGRAD(_Float16, false); }
+#undef FX_DGRAD
+            if (e == hipSuccess) e = hipGetLastError();
+        } else if (e == hipSuccess) {
             const int64_t n_items = km->n_tiles * (int64_t)kGroupsPerTile * (C_produce / kCoutSlice);
             const unsigned grid = (unsigned)((n_items + kDgradWaves - 1) / kDgradWaves);
             ProfScope ps(kProfDgradStrided, st);
