@@ -120,11 +120,13 @@ void fx_grid_destroy(fx_grid* g);
  * by that offset, found through the tree's index lookup; scenario 3 (a)-(c): blocks of
  * consecutive output indices with per-offset packed pairs).
  *
- *   kernel_size K, stride s: supported (K,s) = (1,1), (3,1), (5,1), (2,2).
+ *   kernel_size K, stride s: supported (K,s) = (1,1), (3,1), (5,1), (2,2), (3,2).
  *   Offsets: K odd -> delta in {-(K-1)/2..(K-1)/2}^3; K even -> {0..K-1}^3;
  *            kappa = (di-dmin)*K*K + (dj-dmin)*K + (dk-dmin)   (i slowest).
  *   Output grid: s == 1 -> g_in itself (submanifold; *g_out = g_in with one more reference);
- *                s == 2 -> fx_grid_coarsen2(g_in).
+ *                s == 2 -> fx_grid_coarsen2(g_in) for K = 2 and for K = 3 alike (the paper leaves the
+ *                          output set of a strided 3x3x3 convolution open; this reading keeps the
+ *                          coarse grid of the 2x2x2 case, and output p reads the inputs 2p + {-1,0,1}^3).
  *   map(o,kappa) = index in g_in of voxel  s*p_o + delta_kappa  (same grid of the batch), or -1.
  * Both handles must be destroyed by the caller.  Synchronises `stream` when s == 2.
  */

@@ -785,7 +785,7 @@ extern "C" void fx_kmap_destroy(fx_kmap* km) {
 extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t stride, void* stream, fx_grid** g_out,
                                          fx_kmap** out) {
     if (!g_in || !g_out || !out) { set_error("fx_build_kernel_map: null pointer"); return FX_EINVAL; }
-    const bool ok = (stride == 1 && (K == 1 || K == 3 || K == 5)) || (stride == 2 && K == 2);
+    const bool ok = (stride == 1 && (K == 1 || K == 3 || K == 5)) || (stride == 2 && (K == 2 || K == 3));
     if (!ok) {
         set_error("fx_build_kernel_map: (kernel_size, stride) = (%d, %d) is not supported", K, stride);
         return (K >= 1 && stride >= 1) ? FX_EUNSUPPORTED : FX_EINVAL;
@@ -861,7 +861,8 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     } while (0)
         if (K == 1) FX_TILES(1, true);
         else if (K == 2) FX_TILES(2, false);
-        else FX_TILES(3, true);
+        else if (stride == 1) FX_TILES(3, true);
+        else FX_TILES(3, false);      // 3x3x3 stride 2: windows overlap, still no input row inside the tile's own range
 #undef FX_TILES
         if (e == hipSuccess) e = hipGetLastError();
     }

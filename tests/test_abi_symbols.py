@@ -51,6 +51,14 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.fx_build_kernel_map(None, 3, 1, None, None, None) == -1
     assert lib.fx_sparse_conv_fwd(None, None, 0, None, 4, 4, None, 0, None) == -1
     assert lib.fx_kmap_info(None, None, None, None, None) == -1
+    # backward pass, transposed convolution, pooling, upsampling, subdivision: null handles / pointers
+    assert lib.fx_sparse_conv_bwd_data(None, None, 0, None, 4, 4, None, 0, None) == -1
+    assert lib.fx_sparse_conv_bwd_weight(None, None, None, 0, 4, 4, None, 0, None) == -1
+    assert lib.fx_sparse_conv_transpose_fwd(None, None, 0, None, 4, 4, None, 0, None) == -1
+    assert lib.fx_pool2(None, 0, None, 0, 4, None, None) == -1
+    assert lib.fx_upsample2(None, None, 0, 4, None, None) == -1
+    assert lib.fx_grid_subdivide2(None, None, None) == -1
+    assert b"fx_grid_subdivide2" in lib.fx_last_error()
 
 
 def test_leaf_record_is_96_bytes_with_an_80_byte_payload():

@@ -122,6 +122,31 @@ def test_fp32_full_size_takes_the_tile_kernel():
         H.conv_tolerance_check(y[s:s + 300], ref[s:s + 300], "f32", 27, 32)
 
 
+@pytest.mark.parametrize("dtype,c_in,c_out", [("bf16", 64, 128), ("f16", 32, 64), ("f32", 16, 8), ("bf16", 24, 10)])
+def test_3x3x3_stride_2(dtype, c_in, c_out):
+    # output grid = the coarse grid of the 2x2x2 case, output p reads 2p + {-1,0,1}^3; the windows of
+    # neighbouring outputs overlap, so an input row is used by up to 8 outputs
+    w = G.workload("lidar_small")
+    ijk, jo = w.jagged_ijk(dup_fraction=0.01)
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 3, 2)
+    ogc = og.coarsen2()
+    feat, wt = G.features_and_weights(71, og.num_voxels, c_in, c_out, 27, dtype)
+    d_x, d_w = H.to_device_storage(feat, dtype), H.to_device_storage(wt, dtype)
+    y = fx.sparse_conv_fwd(km, d_x, d_w)
+    H.conv_tolerance_check(y.float().cpu().numpy(), O.conv(og, ogc, 3, 2, feat, wt), dtype, 27, c_in)
+    # weight gradient on the same map; the input gradient of this map needs a scatter-add and is not provided
+    gy = G.round_to_dtype(np.random.default_rng(72).standard_normal((ogc.num_voxels, c_out)).astype(np.float32), dtype)
+    gw = fx.sparse_conv_bwd_weight(km, d_x, H.to_device_storage(gy, dtype), out_dtype=torch.float32).cpu().numpy()
+    ref = O.conv_bwd_weight(og, ogc, 3, 2, feat, gy)
+    num = np.sqrt(((gw - ref) ** 2).sum(axis=(1, 2)))
+    den = np.maximum(np.sqrt((ref ** 2).sum(axis=(1, 2))), 1e-3 * np.sqrt(c_in * c_out))
+    assert (num / den).max() <= (1e-4 if dtype == "f32" else 2e-3)
+    with pytest.raises(fx.FxError) as e:
+        fx.sparse_conv_bwd_data(km, H.to_device_storage(gy, dtype), d_w)
+    assert e.value.status == -2
+
+
 def test_identity_tap_is_bit_exact_in_bf16():
     w = G.workload("lidar_small")
     ijk, jo = w.jagged_ijk()

@@ -32,7 +32,8 @@ def _check_map(g, og, K, s):
 
 @pytest.mark.parametrize("name,K,s", [("sphere64", 3, 1), ("sheets_small", 3, 1), ("lidar_small", 3, 1),
                                       ("indoor_small", 3, 1), ("lidar_small", 2, 2), ("sheets_small", 1, 1),
-                                      ("sphere64", 5, 1), ("sheets_small", 2, 2)])
+                                      ("sphere64", 5, 1), ("sheets_small", 2, 2), ("sheets_small", 3, 2),
+                                      ("lidar_small", 3, 2)])
 def test_workload_maps_match_oracle(name, K, s):
     w = G.workload(name)
     ijk, jo = w.jagged_ijk(dup_fraction=0.01)
@@ -40,7 +41,7 @@ def test_workload_maps_match_oracle(name, K, s):
     _check_map(g, og, K, s)
 
 
-@pytest.mark.parametrize("K,s", [(3, 1), (2, 2)])
+@pytest.mark.parametrize("K,s", [(3, 1), (2, 2), (3, 2)])
 def test_negative_coordinates_and_tile_borders(K, s):
     grids = [_cloud(1, 4000, -20, 20), _cloud(2, 4000, 4080, 4112), np.zeros((0, 3), np.int32),
              _cloud(3, 300, -4100, -4090)]
@@ -67,9 +68,10 @@ def test_empty_grid_map():
 
 def test_unsupported_kernel_stride_is_reported():
     g, _ = H.both_grids(_cloud(5, 100, 0, 10), np.array([[0, 100]], np.int64))
-    with pytest.raises(fx.FxError) as e:
-        fx.build_kernel_map(g, 3, 2)
-    assert e.value.status == -2
+    for K, s in ((3, 3), (2, 1), (5, 2)):
+        with pytest.raises(fx.FxError) as e:
+            fx.build_kernel_map(g, K, s)
+        assert e.value.status == -2
 
 
 @pytest.mark.parametrize("name,pairs", [("lidar1m", 7983738), ("indoor4", None), ("lidar1m_down", 986880),

@@ -37,7 +37,7 @@ def _dense_autograd(coords_in, feat, coords_out, w, gout, K, s):
     return x.grad.numpy(), wt.grad.numpy()
 
 
-@pytest.mark.parametrize("K,s,c_in,c_out", [(3, 1, 5, 7), (2, 2, 6, 3), (1, 1, 4, 4), (5, 1, 2, 3)])
+@pytest.mark.parametrize("K,s,c_in,c_out", [(3, 1, 5, 7), (2, 2, 6, 3), (1, 1, 4, 4), (5, 1, 2, 3), (3, 2, 4, 5)])
 def test_matches_autograd_of_dense_masked_correlation(K, s, c_in, c_out):
     pts = np.unique(_cloud(131, 600, -7, 8), axis=0)
     gin = O.OracleGrid(pts, np.array([[0, pts.shape[0]]]))

@@ -30,7 +30,7 @@ def _brute_nbmap(coords_in, jidx_in, coords_out, jidx_out, K, s):
     return out
 
 
-@pytest.mark.parametrize("K,s", [(3, 1), (1, 1), (2, 2), (5, 1)])
+@pytest.mark.parametrize("K,s", [(3, 1), (1, 1), (2, 2), (5, 1), (3, 2)])
 def test_against_brute_force(K, s):
     grids = [_cloud(1, 120, -5, 6), _cloud(2, 90, 4090, 4102), np.zeros((0, 3), np.int32)]
     ijk, jo = G.make_jagged(grids)
