@@ -106,7 +106,7 @@ fx_status fx_grid_leaf_table(const fx_grid* g, fx_leaf* h_out, size_t bytes, voi
  * coarsening of Sec. 3.6.2 "Grid Construction Operators").  Synchronises `stream`. */
 fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** out);
 
-/* The subdivided grid of Sec. 3.6.2 ("upsamples a GridBatch ... via subdivision"): active set =
+/* The subdivided grid of Sec. 3.6.2 (the grid that upsampling produces): active set =
  * all eight children 2*ijk + {0,1}^3 of every active voxel, per grid of the batch.  The kernel map
  * fx_build_kernel_map(*out, 2, 2) then has g as its output grid (same voxels, same order).
  * FX_ERANGE beyond 2^31-1 voxels.  Synchronises `stream`. */
@@ -206,9 +206,9 @@ fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_feat, const
                                     int32_t C_in, int32_t C_out, void* d_gw, fx_dtype out_dt, void* stream);
 
 /* ---------------------------------------------------------------------------------------
- * Transposed convolution, pooling, upsampling (Sec. 3.6.2: "average and max pooling operators on a
- * GridBatch and JaggedTensor pair as well as an upsampling operator which upsamples ... via
- * subdivision and nearest neighbor sampling"; the decoder half of the network of Sec. 4.1.4).  The
+ * Transposed convolution, pooling, upsampling (Sec. 3.6.2 lists max and average pooling of a grid and
+ * its features, and upsampling by subdivision with nearest-neighbour sampling; Sec. 4.1.4's network
+ * needs them and the transposed convolution in its decoder half).  The
  * paper prints no formulas; with km the kernel map of a convolution from grid g_in (inputs i) to
  * g_out (outputs o):
  *
@@ -236,6 +236,29 @@ fx_status fx_sparse_conv_transpose_fwd(const fx_kmap* km, const void* d_feat, fx
 fx_status fx_pool2(const fx_kmap* km, int32_t mode, const void* d_feat, fx_dtype dt, int32_t C, void* d_out,
                    void* stream);
 fx_status fx_upsample2(const fx_kmap* km, const void* d_feat, fx_dtype dt, int32_t C, void* d_out, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Low-depth 3x3x3 submanifold convolution straight from the grid, without a kernel map (Sec. 3.5
+ * scenario 1, the "Leaf" operator: the 10^3 window of input rows around each 8^3 leaf is densified
+ * in on-chip memory, the gather offsets come from the tree itself, and each leaf's outputs are
+ * written as one contiguous range).  Same result as fx_sparse_conv_fwd on the (3,1) map of g:
+ *     out[o,:] = sum over the 27 offsets kappa whose neighbour i of voxel o is active of
+ *                feat[i,:] . W[kappa]
+ *
+ *   g       the grid; inputs and outputs both live on it (N = its voxel count)
+ *   d_feat  device [N, C_in]  fp32 row-major, 16-byte aligned
+ *   d_w     device [27, C_in, C_out] fp32 row-major, kappa = (di+1)*9 + (dj+1)*3 + (dk+1)
+ *   d_out   device [N, C_out] fp32 row-major, 16-byte aligned; every row is written
+ * fp32 products accumulated in fp32 on the matrix units (sum order differs from
+ * fx_sparse_conv_fwd; same tolerance).  Supported: dt = out_dt = FX_F32, C_in in {4, 8, 12, 16},
+ * C_out in {16, 32}; anything else returns FX_EUNSUPPORTED (build a kernel map and call
+ * fx_sparse_conv_fwd).  Unlike the paper's kernel, (16-voxel tile, offset) pairs without any
+ * active neighbour are skipped: at fp32 this operator is bound by arithmetic on gfx950, not by memory.
+ * Meant for leaf occupancy above ~20 %; on very sparse grids the kernel-map path is faster.
+ * Does not synchronise; pointers are borrowed for the stream-ordered work.
+ */
+fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_feat, fx_dtype dt, const void* d_w,
+                                  int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Measurement support (the paper's protocol, Sec. 4.1: per-operator times).  While enabled,

@@ -75,6 +75,8 @@ def _load():
     L.fx_sparse_conv_bwd_weight.argtypes = [vp, vp, vp, C.c_int, i32, i32, vp, C.c_int, vp]
     L.fx_grid_subdivide2.restype = C.c_int
     L.fx_grid_subdivide2.argtypes = [vp, vp, C.POINTER(vp)]
+    L.fx_sparse_conv_leaf_fwd.restype = C.c_int
+    L.fx_sparse_conv_leaf_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
     L.fx_sparse_conv_transpose_fwd.restype = C.c_int
     L.fx_sparse_conv_transpose_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
     L.fx_pool2.restype = C.c_int
@@ -303,6 +305,19 @@ def sparse_conv_transpose_fwd(kmap: KernelMap, feat: torch.Tensor, weights: torc
     out = torch.empty((kmap.g_in.num_voxels, c_out), dtype=out_dtype, device="cuda")
     _check(lib.fx_sparse_conv_transpose_fwd(kmap._h, _ptr(feat), _TORCH_DT[feat.dtype], _ptr(weights), c_in, c_out,
                                             _ptr(out), _TORCH_DT[out_dtype], _stream()))
+    return out
+
+
+def sparse_conv_leaf_fwd(grid: IndexGrid, feat: torch.Tensor, weights: torch.Tensor) -> torch.Tensor:
+    """3x3x3 submanifold convolution at low depth straight from the grid (no kernel map):
+    feat [N, C_in] fp32, weights [27, C_in, C_out] fp32 -> [N, C_out] fp32."""
+    assert feat.is_cuda and weights.is_cuda and feat.is_contiguous() and weights.is_contiguous()
+    assert feat.dtype == weights.dtype and feat.dtype in _TORCH_DT
+    k3, c_in, c_out = weights.shape
+    assert k3 == 27 and feat.shape == (grid.num_voxels, c_in)
+    out = torch.empty((grid.num_voxels, c_out), dtype=feat.dtype, device="cuda")
+    _check(lib.fx_sparse_conv_leaf_fwd(grid._h, _ptr(feat), _TORCH_DT[feat.dtype], _ptr(weights), c_in, c_out,
+                                       _ptr(out), _TORCH_DT[feat.dtype], _stream()))
     return out
 
 

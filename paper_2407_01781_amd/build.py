@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfvdb_hotpath.so")
-SOURCES = ["lib.hip", "grid.hip", "kmap.hip", "conv.hip", "conv_bwd.hip", "pool.hip"]
+SOURCES = ["lib.hip", "grid.hip", "kmap.hip", "conv.hip", "conv_bwd.hip", "pool.hip", "conv_leaf.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

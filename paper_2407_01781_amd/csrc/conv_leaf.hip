@@ -1,0 +1,396 @@
+// Low-depth 3x3x3 submanifold convolution computed leaf by leaf, straight from the tree, with no
+// kernel map (Sec. 3.5 scenario 1, "Leaf": local densification of the 10^3 window around an 8^3
+// leaf in on-chip memory, gather offsets taken from the tree's own metadata, sequential
+// write-back of the leaf's outputs).
+//
+// What is kept from the paper's design: one workgroup per leaf; the window of input rows
+// densified in LDS (inactive cells hold zeros) so that the 27 taps become fixed address
+// offsets; the leaf's outputs leave as one contiguous range.  What differs, and why: the
+// paper's kernel multiplies all 512 cells of the leaf by all 27 taps because on its hardware a
+// dense 8 -> 16 convolution at fp32 is bound by memory.  On gfx950 it is not: 6912 flop per
+// 96 bytes is 72 flop/byte against a ridge of 157.3 TFLOP/s / 8 TB/s = 20 flop/byte, so wasted
+// multiplies cost time.  This kernel therefore packs the leaf's ACTIVE voxels into column tiles
+// of 16 and skips every (tile, tap) in which no voxel of the tile has an active neighbour.
+// The contraction runs on v_mfma_f32_16x16x4_f32 (gfx950 has no TF32-class format): output
+// channels are the rows, voxels the columns, so a lane ends up holding four adjacent channels
+// of one voxel and a tile of 16 output rows leaves as one 16-byte store per lane.
+#include <algorithm>
+
+#include "common.h"
+#include "conv_common.h"
+#include "tree_device.h"
+
+namespace fx {
+namespace {
+
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+constexpr int kLeafWaves = 4;                // one wave per SIMD, so that workgroups pack evenly onto a compute unit
+constexpr int kLeafThreads = 64 * kLeafWaves;
+constexpr int kWinCells = 1000;              // 10 x 10 x 10 cells: the leaf plus a one-voxel halo
+constexpr int kVoxTile = 16;                 // active voxels per MFMA column tile
+
+struct LeafLds {
+    uint64_t mask[27][8];                    // records of the 27 leaves around (and including) this one
+    uint64_t prefix[27];
+    int32_t offset[27];                      // first index of the leaf; masks are zero when the leaf is absent
+    uint32_t act_row[100];                   // per (x, y) of the window: bit z = cell (x, y, z) is active
+    uint16_t cell_of_rank[512];              // window cell of the leaf's r-th active voxel
+    uint32_t tile_taps[512 / kVoxTile];      // per column tile: bit kappa = some voxel has that neighbour
+    int32_t next_tile;                       // column tiles handed out so far
+    int32_t range[2];                        // this workgroup's leaves [range[0], range[1])
+};
+
+__device__ __forceinline__ int window_cell(int x, int y, int z) { return (x * 10 + y) * 10 + z; }
+
+// index of the voxel at leaf-local (lx,ly,lz) of staged record `slot`, or -1 (Listing 1)
+__device__ __forceinline__ int staged_value(const LeafLds& L, int slot, int lx, int ly, int lz) {
+    const uint64_t w = L.mask[slot][lx];
+    const uint64_t bit = 1ull << ((ly << 3) | lz);
+    if (!(w & bit)) return -1;
+    const uint64_t pre = lx ? (L.prefix[slot] >> (9 * (lx - 1))) & 511 : 0;
+    return L.offset[slot] + (int)pre + __popcll(w & (bit - 1));
+}
+
+// J consecutive floats from LDS (p is J*4-byte aligned for J = 1, 2, 4)
+template <int J> struct Floats { float v[J]; };
+template <int J>
+__device__ __forceinline__ Floats<J> lds_floats(const float* p) {
+    Floats<J> r;
+    if (J == 2) {
+        const f32x2 t = *reinterpret_cast<const f32x2*>(p);
+        r.v[0] = t[0]; r.v[1] = t[1];
+    } else if (J == 4) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(p);
+#pragma unroll
+        for (int j = 0; j < J; ++j) r.v[j] = t[j];
+    } else {
+#pragma unroll
+        for (int j = 0; j < J; ++j) r.v[j] = p[j];
+    }
+    return r;
+}
+
+#ifdef FX_LEAF_TIMING
+// development aid: per-workgroup cycle totals of the phases, read back with fx_debug_leaf_timing
+__device__ unsigned long long g_leaf_timing[1024 * 8];
+#define FX_LT(slot)                                                              \
+    do {                                                                         \
+        if (lane == 0 && wave == 0) {            \
+            const unsigned long long _n = __builtin_readcyclecounter();          \
+            if (blockIdx.x < 1024) g_leaf_timing[blockIdx.x * 8 + (slot)] += _n - _tl; \
+            _tl = _n;                                                            \
+        }                                                                        \
+    } while (0)
+#else
+#define FX_LT(slot) do { } while (0)
+#endif
+
+// Records of the 27 leaves around (and including) leaf f into LDS: one tree descent per lane.
+__device__ __forceinline__ void stage_records(const TreeView& t, LeafLds& L, int f, int lane) {
+    if (lane >= 27) return;
+    const fx_leaf* lf = t.leaf + f;
+    const int a = lane / 9, b = (lane / 3) % 3, c = lane % 3;
+    const int id = lane == 13 ? f
+                              : find_leaf(t, lf->batch, lf->origin[0] + 8 * (a - 1), lf->origin[1] + 8 * (b - 1),
+                                          lf->origin[2] + 8 * (c - 1));
+    if (id >= 0) {
+        const fx_leaf* nl = t.leaf + id;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) L.mask[lane][x] = nl->mask[x];
+        L.prefix[lane] = nl->prefix;
+        L.offset[lane] = (int32_t)nl->offset;
+    } else {
+#pragma unroll
+        for (int x = 0; x < 8; ++x) L.mask[lane][x] = 0;
+        L.prefix[lane] = 0;
+        L.offset[lane] = -1;
+    }
+}
+
+// Leaves are dealt to the persistent workgroups as contiguous ranges of equal estimated cost: a
+// leaf costs kLeafFixedCost (staging, densifying 1000 cells) plus one unit per active voxel, so the
+// cost of leaves [0, f) is kLeafFixedCost * f + offset of leaf f, which grows with f.  Returns the
+// first leaf whose prefix cost reaches `target` (wave-wide 64-ary search; every lane gets the result).
+constexpr int64_t kLeafFixedCost = 220;
+__device__ __forceinline__ int first_leaf_at_cost(const TreeView& t, int64_t first_index, int64_t target, int lane) {
+    int lo = 0, hi = t.n_leaf;               // answer in [lo, hi]; prefix cost of leaf n_leaf counts as infinite
+    while (hi - lo > 0) {
+        const int span = hi - lo;
+        const int step = (span + 63) / 64;
+        const int f = lo + lane * step;      // probes lo, lo + step, ...
+        bool below = false;                  // prefix cost of f < target
+        if (f < hi) below = kLeafFixedCost * f + (t.leaf[f].offset - first_index) < target;
+        const int n_below = __popcll(__ballot(below));     // probes are ascending in cost: a prefix of them is below
+        if (n_below == 0) { hi = lo; break; }
+        const int last_below = lo + (n_below - 1) * step;
+        lo = last_below + 1;
+        hi = min(hi, last_below + step);
+    }
+    return lo;
+}
+
+// window-cell distance of tap kappa
+__device__ __forceinline__ int tap_delta(int kappa) { return (kappa / 9) * 100 + ((kappa / 3) % 3) * 10 + kappa % 3 - 111; }
+
+// J = C_in / 4 MFMA k-steps per tap, NT = C_out / 16 row tiles, WREG: every lane keeps its share of
+// the weights (27 * J * NT values) in registers instead of LDS.
+// Workgroups are persistent: each keeps the weights and takes leaves blockIdx.x, blockIdx.x +
+// gridDim.x, ...  All four waves densify; in the multiply phase the waves claim column tiles from a
+// counter in LDS, and the last wave first walks the tree for the NEXT leaf's 27 records (they are not
+// read during the multiply, so one copy of them is enough) and joins the others afterwards.  The
+// multiply is bound by the matrix pipes, which all workgroups of a compute unit share; the other
+// phases of one workgroup overlap with the multiplies of the others.
+// Lane l of a wave works on voxel column v = l % 16 and k-quarter q = l / 16: it holds the J
+// input channels J*q .. J*q + J-1 of its voxel's neighbour (k-step j contracts channels {J*q + j})
+// and, per row tile, the same channels of output channel 16*nt + v of the weights.
+template <int J, int NT, bool WREG>
+__global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const float* __restrict__ feat,
+                                                            const float* __restrict__ w, float* __restrict__ out,
+                                                            int64_t n_voxels) {
+    constexpr int C_in = 4 * J, C_out = 16 * NT;
+    extern __shared__ __align__(16) unsigned char smem[];
+    LeafLds& L = *reinterpret_cast<LeafLds*>(smem);
+    float* win = reinterpret_cast<float*>(smem + ((sizeof(LeafLds) + 15) & ~size_t(15)));   // [cell][C_in]
+    float* wl = win + kWinCells * C_in;                                  // [kappa][q][cout][j], unless WREG
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int v = lane & 15, q = lane >> 4;
+
+    float wr[WREG ? 27 : 1][NT][J];
+    if (WREG) {
+#pragma unroll
+        for (int kappa = 0; kappa < 27; ++kappa)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int j = 0; j < J; ++j)
+                    wr[WREG ? kappa : 0][nt][j] = w[(kappa * C_in + J * q + j) * C_out + 16 * nt + v];
+    } else {
+        for (int e = tid; e < 27 * C_in * C_out; e += kLeafThreads) {
+            const int cout = e % C_out, ci = (e / C_out) % C_in, kappa = e / (C_out * C_in);
+            wl[((kappa * 4 + ci / J) * C_out + cout) * J + ci % J] = w[e];
+        }
+    }
+    if (wave < 2) {
+        const int64_t first_index = t.leaf[0].offset;
+        const int64_t total = kLeafFixedCost * t.n_leaf + n_voxels;
+        const int b = blockIdx.x + wave;
+        const int f = b >= (int)gridDim.x ? t.n_leaf
+                                          : first_leaf_at_cost(t, first_index, total * b / (int64_t)gridDim.x, lane);
+        if (lane == 0) L.range[wave] = f;
+    }
+    __syncthreads();
+    const int f_begin = L.range[0], f_end = L.range[1];
+    if (wave == kLeafWaves - 1 && f_begin < f_end) stage_records(t, L, f_begin, lane);
+    __syncthreads();
+
+#ifdef FX_LEAF_TIMING
+    unsigned long long _tl = __builtin_readcyclecounter();
+    const unsigned long long _w0 = wall_clock64();
+#endif
+    for (int f = f_begin; f < f_end; ++f) {
+        // ---- densify: row of every window cell, its channels into LDS (zeros where inactive)
+        {
+            if (tid < 512 / kVoxTile) L.tile_taps[tid] = 0;
+            if (tid == 64) L.next_tile = 0;
+            if (tid >= 128 && tid < 228) {       // activity bits of window row (x, y): z = 0 and 9 from the leaves beside
+                int xy = tid - 128;
+                asm volatile("" : "+v"(xy));
+                const int x = xy / 10, y = xy % 10;
+                const int s9 = ((x + 7) >> 3) * 9 + ((y + 7) >> 3) * 3, lx = (x - 1) & 7, sh = ((y - 1) & 7) * 8;
+                L.act_row[xy] = (uint32_t)((L.mask[s9][lx] >> (sh + 7)) & 1) | (uint32_t)((L.mask[s9 + 1][lx] >> sh) & 0xff) << 1 |
+                                (uint32_t)((L.mask[s9 + 2][lx] >> sh) & 1) << 9;
+            }
+            // loads of all passes are issued before the first is stored: an inactive cell reads row 0 and drops it
+            f32x4 val[(kWinCells + kLeafThreads - 1) / kLeafThreads][J];
+            bool on[(kWinCells + kLeafThreads - 1) / kLeafThreads];
+#pragma unroll
+            for (int it = 0; it < (kWinCells + kLeafThreads - 1) / kLeafThreads; ++it) {
+                int cell = min(tid + it * kLeafThreads, kWinCells - 1);
+                asm volatile("" : "+v"(cell));      // recompute the cell's addresses per leaf: registers are scarce
+                const int x = cell / 100, y = (cell / 10) % 10, z = cell % 10;
+                const int slot = ((x + 7) >> 3) * 9 + ((y + 7) >> 3) * 3 + ((z + 7) >> 3);
+                const int row = staged_value(L, slot, (x - 1) & 7, (y - 1) & 7, (z - 1) & 7);
+                on[it] = row >= 0;
+                const f32x4* src = reinterpret_cast<const f32x4*>(feat + (int64_t)max(row, 0) * C_in);
+#pragma unroll
+                for (int c4 = 0; c4 < J; ++c4) val[it][c4] = src[c4];
+            }
+#pragma unroll
+            for (int it = 0; it < (kWinCells + kLeafThreads - 1) / kLeafThreads; ++it) {
+                const int cell = tid + it * kLeafThreads;
+                if (cell < kWinCells) {
+                    f32x4* dst = reinterpret_cast<f32x4*>(win + cell * C_in);
+#pragma unroll
+                    for (int c4 = 0; c4 < J; ++c4) dst[c4] = on[it] ? val[it][c4] : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+        }
+        if (wave == 0) FX_LT(0);             // densify (wave 0's own work)
+        __syncthreads();
+        if (wave == 0) FX_LT(1);             // wait for the others
+
+        // ---- the leaf's active voxels in index order, and which taps each column tile needs
+        const int n_act = (int)((L.prefix[13] >> 54) & 511) + __popcll(L.mask[13][7]);
+        const int64_t base = L.offset[13];
+        {
+#pragma unroll
+            for (int it = 0; it < 512 / kLeafThreads; ++it) {
+                int m = tid + it * kLeafThreads;
+                asm volatile("" : "+v"(m));
+                const int lx = m >> 6, ly = (m >> 3) & 7, lz = m & 7;
+                const int row = staged_value(L, 13, lx, ly, lz);
+                if (row >= 0) {
+                    const int r = row - (int)base;
+                    const int cell = window_cell(lx + 1, ly + 1, lz + 1);
+                    L.cell_of_rank[r] = (uint16_t)cell;
+                    uint32_t taps = 0;       // three taps (dz = -1, 0, 1) per window row: bits lz .. lz + 2 of it
+#pragma unroll
+                    for (int ab = 0; ab < 9; ++ab)
+                        taps |= ((L.act_row[(lx + ab / 3) * 10 + ly + ab % 3] >> lz) & 7u) << (3 * ab);
+                    atomicOr(&L.tile_taps[r / kVoxTile], taps);
+                }
+            }
+        }
+        __syncthreads();
+        if (wave == 0) FX_LT(2);             // masks phase incl. barrier
+
+        if (wave == kLeafWaves - 1 && f + 1 < f_end) stage_records(t, L, f + 1, lane);
+        {
+            // ---- multiply: per column tile of 16 active voxels, the taps that tile needs.  The window
+            // rows of nine taps are fetched together (any cell of the window may be read), then the
+            // multiplies of the taps the tile needs are issued.
+            const int n_tiles = (n_act + kVoxTile - 1) / kVoxTile;
+            int claimed = uni(lane == 0 ? atomicAdd(&L.next_tile, 1) : 0);
+            while (claimed < n_tiles) {
+                const int tile = claimed;
+                claimed = uni(lane == 0 ? atomicAdd(&L.next_tile, 1) : 0);     // in flight during this tile's multiplies
+                const int r = tile * kVoxTile + v;
+                const int cell = L.cell_of_rank[min(r, n_act - 1)];
+                const float* fp = win + cell * C_in + J * q;
+                const float* wp = wl + (q * C_out + v) * J;
+                f32x4 acc[NT];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                const uint32_t taps = (uint32_t)uni((int)L.tile_taps[tile]);
+#pragma unroll
+                for (int a = 0; a < 3; ++a) {
+                    __builtin_amdgcn_sched_barrier(0);       // keeps the fetches of one plane of taps together
+                    Floats<J> x[9];
+#pragma unroll
+                    for (int bc = 0; bc < 9; ++bc) x[bc] = lds_floats<J>(fp + tap_delta(a * 9 + bc) * C_in);
+#pragma unroll
+                    for (int bc = 0; bc < 9; ++bc) {
+                        const int kappa = a * 9 + bc;
+                        if (taps & (1u << kappa)) {
+#pragma unroll
+                            for (int nt = 0; nt < NT; ++nt) {
+                                Floats<J> wv;
+                                if (WREG) {
+#pragma unroll
+                                    for (int j = 0; j < J; ++j) wv.v[j] = wr[WREG ? kappa : 0][nt][j];
+                                } else {
+                                    wv = lds_floats<J>(wp + (kappa * 4 * C_out + 16 * nt) * J);
+                                }
+#pragma unroll
+                                for (int j = 0; j < J; ++j)
+                                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.v[j], x[bc].v[j], acc[nt], 0, 0, 0);
+                            }
+                        }
+                    }
+                }
+                if (r < n_act) {
+                    float* o = out + (base + r) * C_out + 4 * q;
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) *reinterpret_cast<f32x4*>(o + 16 * nt) = acc[nt];
+                }
+            }
+            if (wave == 0) FX_LT(3);         // multiply (wave 0's tiles)
+        }
+        __syncthreads();
+        if (wave == 0) FX_LT(4);             // wait at the end of the leaf
+    }
+#ifdef FX_LEAF_TIMING
+    if (tid == 0 && blockIdx.x < 1024) {
+        g_leaf_timing[blockIdx.x * 8 + 7] = wall_clock64() - _w0;   // 100 MHz ticks
+        g_leaf_timing[blockIdx.x * 8 + 5] = _w0;
+    }
+#endif
+}
+
+constexpr bool leaf_weights_in_registers(int J, int NT) { return 27 * J * NT <= 64; }
+
+size_t leaf_lds_bytes(int J, int NT) {
+    const int C_in = 4 * J, C_out = 16 * NT;
+    return ((sizeof(LeafLds) + 15) & ~size_t(15)) +
+           sizeof(float) * ((size_t)kWinCells * C_in + (leaf_weights_in_registers(J, NT) ? 0 : (size_t)27 * C_in * C_out));
+}
+
+template <int J, int NT>
+fx_status launch_leaf(const fx_grid* g, const float* feat, const float* w, float* out, hipStream_t st) {
+    constexpr bool WREG = leaf_weights_in_registers(J, NT);
+    const size_t lds = leaf_lds_bytes(J, NT);
+    static int per_cu = 0;                    // resident workgroups per compute unit (registers, LDS, wave slots)
+    if (per_cu == 0) {
+        FX_HIP_TRY(hipFuncSetAttribute((const void*)k_conv_leaf<J, NT, WREG>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds));
+        int n = 0;
+        FX_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_conv_leaf<J, NT, WREG>, kLeafThreads, lds));
+        per_cu = std::max(1, n);
+    }
+    const unsigned n_wg = (unsigned)std::min<int64_t>(g->hdr.n_leaf, (int64_t)per_cu * compute_units());
+    ProfScope ps(kProfConvLeaf, st);
+    k_conv_leaf<J, NT, WREG><<<n_wg, kLeafThreads, lds, st>>>(g->view(), feat, w, out, g->hdr.n_voxels);
+    FX_HIP_TRY(hipGetLastError());
+    return FX_OK;
+}
+
+}  // namespace
+}  // namespace fx
+
+using namespace fx;
+
+#ifdef FX_LEAF_TIMING
+extern "C" int fx_debug_leaf_timing(unsigned long long* h_out, size_t bytes, int reset) {
+    if (reset) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_leaf_timing)) != hipSuccess) return -1;
+        return (int)hipMemset(p, 0, sizeof(unsigned long long) * 1024 * 8);
+    }
+    return (int)hipMemcpyFromSymbol(h_out, HIP_SYMBOL(g_leaf_timing), bytes);
+}
+#endif
+
+extern "C" fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_feat, fx_dtype dt, const void* d_w,
+                                             int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream) {
+    if (!g || !d_w || C_in < 1 || C_out < 1 || (g->hdr.n_voxels > 0 && (!d_feat || !d_out))) {
+        set_error("fx_sparse_conv_leaf_fwd: null pointer or non-positive channel count");
+        return FX_EINVAL;
+    }
+    if (dt != FX_F32 && dt != FX_F16 && dt != FX_BF16) { set_error("unknown input dtype"); return FX_EINVAL; }
+    if (dt != FX_F32 || out_dt != FX_F32) {
+        set_error("fx_sparse_conv_leaf_fwd: fp32 in, fp32 out only");
+        return FX_EUNSUPPORTED;
+    }
+    if (C_in % 4 || C_in > 16 || C_out % 16 || C_out > 32) {
+        set_error("fx_sparse_conv_leaf_fwd: needs C_in in {4,8,12,16} and C_out in {16,32} (got %d -> %d); "
+                  "use fx_build_kernel_map + fx_sparse_conv_fwd", C_in, C_out);
+        return FX_EUNSUPPORTED;
+    }
+    if (g->hdr.n_voxels == 0) return FX_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const float* feat = (const float*)d_feat;
+    const float* w = (const float*)d_w;
+    float* out = (float*)d_out;
+#define FX_LEAF(JV)                                                                          \
+    case JV:                                                                                 \
+        return C_out == 16 ? launch_leaf<JV, 1>(g, feat, w, out, st) : launch_leaf<JV, 2>(g, feat, w, out, st)
+    switch (C_in / 4) {
+        FX_LEAF(1);
+        FX_LEAF(2);
+        FX_LEAF(3);
+        FX_LEAF(4);
+    }
+#undef FX_LEAF
+    return FX_EINVAL;
+}

@@ -1,0 +1,97 @@
+"""GPU parity: the map-free low-depth convolution (Sec. 3.5 scenario 1) against the oracle's
+3x3x3 submanifold convolution, at the fp32 bar; and against the kernel-map path."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_common as H
+import paper_2407_01781_amd as fx
+from oracle import cpu_oracle as O
+from workloads import generators as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _leaf_vs_oracle(grids, c_in, c_out, seed, dup=0.01):
+    ijk, jo = G.make_jagged([G.shuffle_and_duplicate(g, seed + b, dup) for b, g in enumerate(grids)])
+    g, og = H.both_grids(ijk, jo)
+    feat, wt = G.features_and_weights(seed, og.num_voxels, c_in, c_out, 27, "f32")
+    y = fx.sparse_conv_leaf_fwd(g, H.to_device_storage(feat, "f32"), H.to_device_storage(wt, "f32"))
+    ref = O.conv(og, og, 3, 1, feat, wt)
+    assert y.shape == ref.shape
+    H.conv_tolerance_check(y.cpu().numpy(), ref, "f32", 27, c_in)
+    return g, feat, wt, y
+
+
+@pytest.mark.parametrize("c_in,c_out", [(8, 16), (4, 16), (12, 32), (16, 32), (16, 16), (8, 32)])
+def test_volumetric_bodies_all_channel_shapes(c_in, c_out):
+    w = G.workload("volume_small")
+    _leaf_vs_oracle(w.grids, c_in, c_out, w.feat_seed)
+
+
+@pytest.mark.parametrize("name", ["lidar_small", "sheets_small", "indoor_small", "sphere64"])
+def test_sparse_and_surface_grids(name):
+    # leaves with a handful of voxels, ragged last tiles, batches of several grids
+    w = G.workload(name)
+    _leaf_vs_oracle(w.grids, 8, 16, w.feat_seed)
+
+
+def test_dense_block_across_node_boundaries():
+    # a dense 20^3 block that straddles the origin, a lower-node boundary (128) and a root-tile
+    # boundary (4096): full leaves (512 voxels, 32 full tiles) and neighbours in other nodes
+    a = np.arange(-10, 10)
+    blk = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3)
+    grids = [np.concatenate([blk, blk + np.array([128, 128, 4096])]).astype(np.int32)]
+    _leaf_vs_oracle(grids, 8, 16, 71)
+
+
+def test_isolated_voxels_and_single_voxel_grid():
+    rng = np.random.default_rng(5)
+    far = (rng.integers(-2000, 2000, size=(300, 3)) * 16).astype(np.int32)     # no two share a neighbourhood
+    one = np.array([[7, 0, -1]], dtype=np.int32)
+    _leaf_vs_oracle([far, one], 8, 16, 72, dup=0.0)
+
+
+def test_empty_grid_and_empty_batch_member():
+    w = G.workload("volume_small")
+    g, og = H.both_grids(*G.make_jagged([np.zeros((0, 3), np.int32)]))
+    y = fx.sparse_conv_leaf_fwd(g, torch.zeros((0, 8), device="cuda"), torch.zeros((27, 8, 16), device="cuda"))
+    assert y.shape == (0, 16)
+    _leaf_vs_oracle([w.grids[0], np.zeros((0, 3), np.int32), w.grids[1]], 8, 16, 73)
+
+
+def test_agrees_with_the_kernel_map_path():
+    w = G.workload("volume_small")
+    g, feat, wt, y = _leaf_vs_oracle(w.grids, 8, 16, w.feat_seed)
+    km = fx.build_kernel_map(g, 3, 1)
+    y2 = fx.sparse_conv_fwd(km, H.to_device_storage(feat, "f32"), H.to_device_storage(wt, "f32"))
+    tol = 1e-4 * np.sqrt(27 * 8)
+    assert float((y - y2).abs().max()) <= tol
+
+
+def test_unsupported_shapes_are_refused():
+    w = G.workload("volume_small")
+    ijk, jo = w.jagged_ijk()
+    g, _ = H.both_grids(ijk, jo)
+    n = g.num_voxels
+    for c_in, c_out, dt in ((8, 24, torch.float32), (20, 16, torch.float32), (6, 16, torch.float32),
+                            (8, 16, torch.bfloat16)):
+        with pytest.raises(fx.FxError):
+            fx.sparse_conv_leaf_fwd(g, torch.zeros((n, c_in), device="cuda", dtype=dt),
+                                    torch.zeros((27, c_in, c_out), device="cuda", dtype=dt))
+
+
+def test_full_size_volume_sampled_rows():
+    # the bench configuration: ~1M voxels at > 50 % leaf occupancy; the oracle computes a sample of output rows
+    w = G.workload("volume1m")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    feat, wt = w.feats_weights()
+    y = fx.sparse_conv_leaf_fwd(g, H.to_device_storage(feat, "f32"), H.to_device_storage(wt, "f32")).cpu().numpy()
+    n = og.num_voxels
+    starts = list(range(0, n - 300, n // 12)) + [n - 300]
+    f64, w64 = feat.astype(np.float64), wt.astype(np.float64)
+    for s0 in starts:
+        ref = O.conv(og, og, 3, 1, f64, w64, s0, s0 + 300)
+        H.conv_tolerance_check(y[s0:s0 + 300], ref[s0:s0 + 300], "f32", 27, w.c_in)
+    assert np.isfinite(y).all()

@@ -148,6 +148,26 @@ def random_walk_sheets(seed: int, extent: int = 128, n_sheets: int = 3) -> np.nd
     return _unique_rows(np.concatenate(parts, axis=0))
 
 
+def volumetric_bodies(seed: int, extent: int = 192, n_bodies: int = 7, origin: int = 0) -> np.ndarray:
+    """Solid balls and thick spherical shells (4-8 voxels thick) at random places in extent^3:
+    the densest of the three sparsity classes of Sec. 4.1.3 (rasterised volumes, leaf occupancy
+    above 40 %).  ``origin`` shifts the whole scene (negative origins put bodies
+    across the coordinate planes)."""
+    rng = np.random.default_rng(seed)
+    a = np.arange(extent, dtype=np.float64) + 0.5
+    m = np.zeros((extent, extent, extent), dtype=bool)
+    for b in range(n_bodies):
+        r = float(rng.uniform(0.12, 0.22) * extent)
+        c = rng.uniform(r + 1, extent - r - 1, size=3)
+        d2 = ((a - c[0]) ** 2)[:, None, None] + ((a - c[1]) ** 2)[None, :, None] + ((a - c[2]) ** 2)[None, None, :]
+        if b % 2 == 0:
+            m |= d2 <= r * r
+        else:
+            t = float(rng.uniform(4.0, 8.0))
+            m |= (d2 <= r * r) & (d2 >= (r - t) ** 2)
+    return (np.argwhere(m) + origin).astype(np.int32)
+
+
 def gaussian_points(seed: int, n: int, sigma: float = 64.0) -> np.ndarray:
     """Integer coordinates of points drawn from an isotropic normal distribution.
 
@@ -289,6 +309,12 @@ def workload(name: str) -> Workload:
     if name == "sheets_small":
         return Workload(name, [random_walk_sheets(5100 + g, extent=48, n_sheets=2) for g in range(2)],
                         3, 1, 256, 256, "bf16", 5200, 5201)
+    # ---- the volumetric class (Sec. 4.1.3 c) at low depth (Sec. 3.5 scenario 1: 8 -> 16, fp32) ----
+    if name == "volume1m":
+        return Workload(name, [volumetric_bodies(6000, extent=224, n_bodies=8)], 3, 1, 8, 16, "f32", 6100, 6101)
+    if name == "volume_small":
+        return Workload(name, [volumetric_bodies(6001 + g, extent=40, n_bodies=3, origin=-13 * g) for g in range(2)],
+                        3, 1, 8, 16, "f32", 6200, 6201)
     raise KeyError(name)
 
 
