@@ -56,6 +56,8 @@ def lib():
         L.fo_pool2.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp]
         L.fo_upsample2.restype = i64
         L.fo_upsample2.argtypes = [vp, vp, vp, C.c_int, vp]
+        L.fo_points_to_ijk.restype = i64
+        L.fo_points_to_ijk.argtypes = [vp, i64, vp, vp, vp]
         L.fo_grid_subdivide2.restype = vp
         L.fo_grid_subdivide2.argtypes = [vp]
         _lib = L
@@ -235,3 +237,13 @@ def upsample2(fine: OracleGrid, coarse: OracleGrid, z: np.ndarray) -> np.ndarray
     if lib().fo_upsample2(fine._h, coarse._h, _p(z), z.shape[1], _p(out)) < 0:
         raise ValueError("bad upsample2 arguments")
     return out
+
+
+def points_to_ijk(xyz: np.ndarray, origin, voxel_size) -> Tuple[np.ndarray, int]:
+    """Voxel coordinates of points (O6): ijk [n,3] int32 and the number of invalid points."""
+    xyz = np.ascontiguousarray(xyz, dtype=np.float32)
+    o = np.ascontiguousarray(origin, dtype=np.float32).reshape(3)
+    s = np.ascontiguousarray(voxel_size, dtype=np.float32).reshape(3)
+    out = np.zeros((xyz.shape[0], 3), dtype=np.int32)
+    bad = lib().fo_points_to_ijk(_p(xyz), xyz.shape[0], _p(o), _p(s), _p(out))
+    return out, int(bad)

@@ -60,6 +60,15 @@
  *                                  zero where the parent is not active
  *      All are written as plain loops over voxels with this file's hash map.
  *
+ *  O6  voxel coordinates of points -- Sec. 3.6.2 and Sec. 4.1.1: a grid can be built from
+ *      xyz point coordinates as well as from ijk.  No formula is printed; the reading taken:
+ *      voxel (i,j,k) is the half-open cell [origin + i*s, origin + (i+1)*s) per axis, so
+ *          ijk = floor((xyz - origin) / voxel_size)
+ *      evaluated in IEEE single precision (one rounded subtraction, one rounded division,
+ *      floorf), the precision of the input; a point is invalid if the quotient is not finite
+ *      or its floor lies outside [-2^30, 2^30).  The grid of a point cloud is O1 applied to
+ *      these coordinates.
+ *
  * Readings taken where the paper is silent (all listed in the design notes):
  *   - exported indices are 0-based rows of jdata, -1 means inactive (the paper's
  *     in-tree index 0 is its background value);
@@ -77,8 +86,10 @@
  * counting identities of Sec. 3.3, brute-force neighbour search, dense masked 3-D
  * correlation, K=1 per-voxel GEMM, identity-weight and all-ones exact cases; for O4 the
  * gradients a library's autograd gives for the dense masked correlation, the adjoint
- * identities against O3, and central differences of O3).
+ * identities against O3, and central differences of O3; for O6 exact dyadic cases, points on
+ * cell faces, and containment of every point in its cell checked in exact rational arithmetic).
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -502,4 +513,25 @@ fo_grid *fo_grid_subdivide2(const fo_grid *g) {
     fo_grid *o = fo_grid_create(c, jo, g->B);
     free(c); free(jo);
     return o;
+}
+
+/* O6: xyz [n,3] float -> ijk [n,3] int32 (rows of invalid points are set to 0,0,0); returns the
+ * number of invalid points. */
+int64_t fo_points_to_ijk(const float *xyz, int64_t n, const float origin[3], const float voxel_size[3],
+                         int32_t *ijk) {
+    int64_t invalid = 0;
+    for (int64_t p = 0; p < n; ++p) {
+        int ok = 1;
+        int32_t c[3];
+        for (int a = 0; a < 3; ++a) {
+            volatile float d = xyz[3 * p + a] - origin[a];   /* volatile: each step rounded to float */
+            volatile float t = d / voxel_size[a];
+            float fl = floorf(t);
+            if (!isfinite(fl) || fl < -1073741824.0f || fl >= 1073741824.0f) { ok = 0; c[a] = 0; }
+            else c[a] = (int32_t)fl;
+        }
+        if (!ok) { c[0] = c[1] = c[2] = 0; ++invalid; }
+        ijk[3 * p] = c[0]; ijk[3 * p + 1] = c[1]; ijk[3 * p + 2] = c[2];
+    }
+    return invalid;
 }

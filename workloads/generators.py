@@ -178,6 +178,13 @@ def gaussian_points(seed: int, n: int, sigma: float = 64.0) -> np.ndarray:
     return np.floor(p).astype(np.int32)
 
 
+def gaussian_point_cloud(seed: int, n: int, sigma: float = 1.0) -> np.ndarray:
+    """xyz [n,3] float32 drawn from an isotropic normal distribution: the input of the paper's
+    grid-construction benchmark (Sec. 4.1.1) before it is turned into voxel coordinates."""
+    rng = np.random.default_rng(seed)
+    return rng.normal(0.0, sigma, size=(n, 3)).astype(np.float32)
+
+
 # ----------------------------------------------------------------------------------
 # batches, features, weights
 # ----------------------------------------------------------------------------------
