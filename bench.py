@@ -260,6 +260,22 @@ def main():
                      "kernel_map_path_ms": {"kernel_map": t_kmv, "conv": t_cv}}
         del kmv, gv, v_feat
 
+    # ---- grid build from xyz points (Sec. 4.1.1's benchmark input: normally distributed points), 10 M points,
+    # sigma = 100 voxels (not part of `value`)
+    points_build = None
+    if not args.no_low_depth:
+        n_pts = 10_000_000
+        d_xyz = torch.from_numpy(G.gaussian_point_cloud(7000, n_pts, 1.0)).cuda()
+        pjo = np.array([[0, n_pts]], dtype=np.int64)
+        gp = fx.build_index_grid_from_points(d_xyz, pjo, (0.0, 0.0, 0.0), (0.01, 0.01, 0.01))
+        t_pts = b2b(lambda: fx.build_index_grid_from_points(d_xyz, pjo, (0.0, 0.0, 0.0), (0.01, 0.01, 0.01)), reps=5)
+        points_build = {"n_points": n_pts, "n_voxels": gp.num_voxels, "n_leaves": gp.counts()[0], "ms": t_pts,
+                        "Mpoints_per_s": n_pts / (t_pts * 1e-3) / 1e6,
+                        "algorithmic_bytes": 12 * n_pts + 96 * gp.counts()[0],
+                        "GBs": (12 * n_pts + 96 * gp.counts()[0]) / (t_pts * 1e-3) / 1e9}
+        points_build["frac_of_hbm_peak"] = points_build["GBs"] / HBM_PEAK_GBS
+        del gp, d_xyz
+
     # ---- the paper's timing protocol (Sec. 4.1: one warm-up, five timed runs, mean of the best
     # four), cold = a 768 MiB scratch buffer is overwritten before every run so that neither the
     # L2s nor the 256 MB last-level cache hold the operands, warm = no flush
@@ -343,6 +359,7 @@ def main():
                      "bwd_weight_effective_TFLOPs": flops / (t_wgrad * 1e-3) / 1e12},
         "encoder_decoder_ops": ops,
         "low_depth": low_depth,
+        "grid_from_points": points_build,
         "kernels_ms_per_launch": kern_ms,
         "kernels_ms_per_step": per_step_ms,
         "roofline": roof,

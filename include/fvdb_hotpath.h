@@ -84,6 +84,25 @@ void fx_release_cached_memory(void);
 fx_status fx_build_index_grid(const int32_t* d_ijk, int64_t n_rows, const int64_t* h_joffsets,
                               int32_t B, void* stream, fx_grid** out);
 
+/* The same grid from point coordinates (Sec. 3.6.2: grids are also built from point clouds; Sec. 4.1.1
+ * times the build from ijk or xyz lists).  The paper prints no formula; here voxel (i,j,k) is the
+ * half-open cell [origin + i*s, origin + (i+1)*s) per axis:
+ *     ijk = floor((xyz - origin) / voxel_size)
+ * evaluated in IEEE single precision (rounded subtraction, rounded division, floor), then
+ * fx_build_index_grid on those coordinates (a caller who wants voxel centres at integer
+ * coordinates passes origin - voxel_size / 2).
+ *
+ *   d_xyz         device [n_rows,3] float32, row-major
+ *   h_joffsets, B as fx_build_index_grid
+ *   h_origin      host [3] float32, finite
+ *   h_voxel_size  host [3] float32, finite and > 0
+ * FX_ERANGE if any coordinate is not finite or its cell lies outside [-2^30, 2^30) (no grid is
+ * returned).  Allocates n_rows * 12 bytes of temporary device memory; synchronises `stream`.
+ */
+fx_status fx_build_index_grid_from_points(const float* d_xyz, int64_t n_rows, const int64_t* h_joffsets,
+                                          int32_t B, const float* h_origin, const float* h_voxel_size,
+                                          void* stream, fx_grid** out);
+
 /* Sizes of a grid: total active voxels, batch size, per-grid voxel ranges [B,2] (host, may
  * be NULL) and node counts {leaf, lower, upper} (host, may be NULL). */
 fx_status fx_grid_info(const fx_grid* g, int64_t* n_voxels, int32_t* B,

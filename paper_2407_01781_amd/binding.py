@@ -44,6 +44,8 @@ def _load():
     L.fx_init.restype = C.c_int
     L.fx_build_index_grid.restype = C.c_int
     L.fx_build_index_grid.argtypes = [vp, i64, vp, i32, vp, C.POINTER(vp)]
+    L.fx_build_index_grid_from_points.restype = C.c_int
+    L.fx_build_index_grid_from_points.argtypes = [vp, i64, vp, i32, vp, vp, vp, C.POINTER(vp)]
     L.fx_grid_info.restype = C.c_int
     L.fx_grid_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), vp, vp]
     L.fx_grid_ijk.restype = C.c_int
@@ -197,6 +199,20 @@ def build_index_grid(ijk: torch.Tensor, joffsets) -> IndexGrid:
     h = C.c_void_p()
     _check(lib.fx_build_index_grid(_ptr(ijk), ijk.shape[0], jo.ctypes.data_as(C.c_void_p), jo.shape[0],
                                    _stream(), C.byref(h)))
+    return IndexGrid(h.value)
+
+
+def build_index_grid_from_points(xyz: torch.Tensor, joffsets, origin=(0.0, 0.0, 0.0),
+                                 voxel_size=(1.0, 1.0, 1.0)) -> IndexGrid:
+    """xyz: CUDA float32 [n_rows,3]; voxel (i,j,k) is the cell [origin + i*s, origin + (i+1)*s)."""
+    assert xyz.is_cuda and xyz.dtype == torch.float32 and xyz.is_contiguous()
+    jo = np.ascontiguousarray(np.asarray(joffsets, dtype=np.int64).reshape(-1, 2))
+    o = np.ascontiguousarray(np.broadcast_to(np.asarray(origin, dtype=np.float32), (3,)))
+    s = np.ascontiguousarray(np.broadcast_to(np.asarray(voxel_size, dtype=np.float32), (3,)))
+    h = C.c_void_p()
+    _check(lib.fx_build_index_grid_from_points(_ptr(xyz), xyz.shape[0], jo.ctypes.data_as(C.c_void_p), jo.shape[0],
+                                               o.ctypes.data_as(C.c_void_p), s.ctypes.data_as(C.c_void_p),
+                                               _stream(), C.byref(h)))
     return IndexGrid(h.value)
 
 

@@ -48,7 +48,7 @@ enum ProfSlot {
     kProfBucketCount = 0, kProfBucketScan, kProfBucketScatter, kProfBucketLeaves, kProfVoxelsToLeaves, kProfFindTiles, kProfRankTiles, kProfInsertUpper, kProfScanUpper, kProfInsertLower, kProfScanLower,
     kProfInsertLeaf, kProfScanLeaf, kProfGridIjk, kProfNbmap, kProfLeafNeighbors, kProfBuildTiles,
     kProfPackWeights, kProfConvMfma, kProfConvGather, kProfConvScalar, kProfMemset,
-    kProfDgradStrided, kProfWgrad, kProfWgradReduce, kProfPool, kProfUpsample, kProfConvLeaf, kProfSlotCount
+    kProfDgradStrided, kProfWgrad, kProfWgradReduce, kProfPool, kProfUpsample, kProfConvLeaf, kProfPointsToIjk, kProfSlotCount
 };
 bool prof_enabled();
 void prof_begin(int slot, hipStream_t s);

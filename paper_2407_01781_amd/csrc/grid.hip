@@ -8,6 +8,8 @@
 // parent order).  Only the few root tiles are ranked by comparison.  One streaming pass over
 // ijk collects the distinct leaves and their voxel masks in a hash table; the levels above are
 // built from those leaves (tens of thousands) instead of from the voxels (millions).
+#include <cmath>
+
 #include "common.h"
 #include "tree_device.h"
 
@@ -1067,6 +1069,68 @@ extern "C" fx_status fx_grid_leaf_table(const fx_grid* g, fx_leaf* h_out, size_t
     if (!need) return FX_OK;
     FX_HIP_TRY(hipMemcpyAsync(h_out, g->d_leaf, need, hipMemcpyDeviceToHost, (hipStream_t)stream));
     FX_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    return FX_OK;
+}
+
+// Voxel coordinates of points (Sec. 3.6.2: grids from point clouds): element e = 3 * point + axis.
+// Subtraction and division are the correctly rounded single-precision ones (no reciprocal, no
+// contraction), so that the cell of a point near a face is the same on every implementation.
+__global__ void k_points_to_ijk(const float* __restrict__ xyz, int64_t n3, float ox, float oy, float oz, float sx,
+                                float sy, float sz, int32_t* __restrict__ ijk, int32_t* __restrict__ n_bad) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n3) return;
+    const int axis = (int)(e % 3);
+    const float o = axis == 0 ? ox : axis == 1 ? oy : oz;
+    const float s = axis == 0 ? sx : axis == 1 ? sy : sz;
+    const float t = floorf(__fdiv_rn(__fsub_rn(xyz[e], o), s));
+    const bool ok = isfinite(t) && t >= -1073741824.0f && t < 1073741824.0f;
+    ijk[e] = ok ? (int32_t)t : 0;
+    if (!ok) atomicAdd(n_bad, 1);
+}
+
+extern "C" fx_status fx_build_index_grid_from_points(const float* d_xyz, int64_t n_rows, const int64_t* h_joffsets,
+                                                     int32_t B, const float* h_origin, const float* h_voxel_size,
+                                                     void* stream, fx_grid** out) {
+    if (!out || !h_origin || !h_voxel_size || n_rows < 0 || (n_rows > 0 && !d_xyz)) {
+        set_error("fx_build_index_grid_from_points: null pointer or negative size");
+        return FX_EINVAL;
+    }
+    for (int a = 0; a < 3; ++a)
+        if (!(h_voxel_size[a] > 0.f) || !std::isfinite(h_voxel_size[a]) || !std::isfinite(h_origin[a])) {
+            set_error("fx_build_index_grid_from_points: voxel sizes must be positive and finite, the origin finite");
+            return FX_EINVAL;
+        }
+    if (n_rows > (int64_t)INT32_MAX) { set_error("more than 2^31-1 input rows"); return FX_ERANGE; }
+    hipStream_t st = (hipStream_t)stream;
+    int32_t* d_ijk = nullptr;
+    // the counter of invalid points sits behind the coordinates, in the same allocation
+    const size_t ijk_bytes = (sizeof(int32_t) * 3 * (size_t)std::max<int64_t>(n_rows, 1) + 15) & ~size_t(15);
+    FX_TRY(dev_alloc((void**)&d_ijk, ijk_bytes + 16, st));
+    int32_t* d_bad = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(d_ijk) + ijk_bytes);
+    hipError_t e = hipMemsetAsync(d_bad, 0, sizeof(int32_t), st);
+    if (e == hipSuccess && n_rows > 0) {
+        ProfScope ps(kProfPointsToIjk, st);
+        const int64_t n3 = 3 * n_rows;
+        k_points_to_ijk<<<(unsigned)((n3 + 255) / 256), 256, 0, st>>>(d_xyz, n3, h_origin[0], h_origin[1], h_origin[2],
+                                                                    h_voxel_size[0], h_voxel_size[1], h_voxel_size[2],
+                                                                    d_ijk, d_bad);
+        e = hipGetLastError();
+    }
+    if (e != hipSuccess) { dev_free(d_ijk, st); set_error("point quantisation failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
+    fx_grid* g = nullptr;
+    fx_status rc = fx_build_index_grid(d_ijk, n_rows, h_joffsets, B, stream, &g);    // synchronises the stream
+    int32_t bad = 0;
+    if (rc == FX_OK) {
+        e = hipMemcpy(&bad, d_bad, sizeof(int32_t), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) { rc = FX_EDEVICE; set_error("read-back failed: %s", hipGetErrorString(e)); }
+    }
+    dev_free(d_ijk, st);
+    if (rc == FX_OK && bad > 0) {
+        set_error("%d point coordinates are not finite or fall outside [-2^30, 2^30) voxels", bad);
+        rc = FX_ERANGE;
+    }
+    if (rc != FX_OK) { if (g) fx_grid_destroy(g); return rc; }
+    *out = g;
     return FX_OK;
 }
 

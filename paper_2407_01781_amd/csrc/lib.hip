@@ -256,7 +256,7 @@ static const char* kProfNames[kProfSlotCount] = {
     "k_bucket_count", "k_bucket_scan", "k_bucket_scatter", "k_bucket_leaves", "k_voxels_to_leaves", "k_find_tiles", "k_rank_tiles", "k_insert<0>", "scan_upper", "k_insert<1>", "scan_lower", "k_insert<2>",
     "scan_leaves", "k_grid_ijk", "k_nbmap", "k_leaf_neighbors", "k_build_tiles", "k_pack_weights",
     "k_conv_mfma", "k_conv_gather",
-    "k_conv_scalar", "memset", "k_dgrad_strided", "k_wgrad", "k_wgrad_reduce", "k_pool2", "k_upsample2", "k_conv_leaf"};
+    "k_conv_scalar", "memset", "k_dgrad_strided", "k_wgrad", "k_wgrad_reduce", "k_pool2", "k_upsample2", "k_conv_leaf", "k_points_to_ijk"};
 
 }  // namespace fx
 
