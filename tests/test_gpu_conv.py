@@ -201,7 +201,7 @@ def test_dense_block_uses_rows_beyond_the_lds_budget():
     H.conv_tolerance_check(y.float().cpu().numpy(), O.conv(og, og, 3, 1, feat, wt), "bf16", 27, 64)
 
 
-@pytest.mark.parametrize("name", ["lidar1m", "indoor4", "lidar1m_down", "sheets4"])
+@pytest.mark.parametrize("name", ["lidar1m", "indoor4", "lidar1m_down", "sheets4", "volume1m_c64", "dense96"])
 def test_full_size_configs_sampled_rows(name):
     """Configs 3, 2, 4 and 5 at full size in the benchmark's launch configuration; the oracle
     computes a sample of output rows one by one (a few thousand rows spread over the grid, the

@@ -75,7 +75,7 @@ def test_unsupported_kernel_stride_is_reported():
 
 
 @pytest.mark.parametrize("name,pairs", [("lidar1m", 7983738), ("indoor4", None), ("lidar1m_down", 986880),
-                                        ("sheets4", 1625841)])
+                                        ("sheets4", 1625841), ("volume1m_c64", 26144783), ("dense96", None)])
 def test_full_size_maps_match_oracle(name, pairs):
     """Every entry of the map at the benchmark's sizes (the oracle needs a few seconds)."""
     w = G.workload(name)

@@ -319,6 +319,13 @@ def workload(name: str) -> Workload:
     # ---- the volumetric class (Sec. 4.1.3 c) at low depth (Sec. 3.5 scenario 1: 8 -> 16, fp32) ----
     if name == "volume1m":
         return Workload(name, [volumetric_bodies(6000, extent=224, n_bodies=8)], 3, 1, 8, 16, "f32", 6100, 6101)
+    # the same volumetric grid and a fully dense block at the depth of the benchmark's middle layers
+    if name == "volume1m_c64":
+        return Workload(name, [volumetric_bodies(6000, extent=224, n_bodies=8)], 3, 1, 64, 64, "bf16", 6300, 6101)
+    if name == "dense96":
+        a = np.arange(-48, 48, dtype=np.int32)
+        blk = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3)
+        return Workload(name, [blk], 3, 1, 64, 64, "bf16", 6400, 6401)
     if name == "volume_small":
         return Workload(name, [volumetric_bodies(6001 + g, extent=40, n_bodies=3, origin=-13 * g) for g in range(2)],
                         3, 1, 8, 16, "f32", 6200, 6201)
