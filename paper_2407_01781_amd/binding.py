@@ -324,16 +324,18 @@ def sparse_conv_transpose_fwd(kmap: KernelMap, feat: torch.Tensor, weights: torc
     return out
 
 
-def sparse_conv_leaf_fwd(grid: IndexGrid, feat: torch.Tensor, weights: torch.Tensor) -> torch.Tensor:
-    """3x3x3 submanifold convolution at low depth straight from the grid (no kernel map):
-    feat [N, C_in] fp32, weights [27, C_in, C_out] fp32 -> [N, C_out] fp32."""
+def sparse_conv_leaf_fwd(grid: IndexGrid, feat: torch.Tensor, weights: torch.Tensor,
+                         out_dtype: Optional[torch.dtype] = None) -> torch.Tensor:
+    """3x3x3 submanifold convolution straight from the grid (no kernel map): feat [N, C_in],
+    weights [27, C_in, C_out] -> [N, C_out]; fp32 at low depth, f16 / bf16 at C_in % 32 == 0, C_out % 64 == 0."""
     assert feat.is_cuda and weights.is_cuda and feat.is_contiguous() and weights.is_contiguous()
     assert feat.dtype == weights.dtype and feat.dtype in _TORCH_DT
     k3, c_in, c_out = weights.shape
     assert k3 == 27 and feat.shape == (grid.num_voxels, c_in)
-    out = torch.empty((grid.num_voxels, c_out), dtype=feat.dtype, device="cuda")
+    out_dtype = out_dtype or feat.dtype
+    out = torch.empty((grid.num_voxels, c_out), dtype=out_dtype, device="cuda")
     _check(lib.fx_sparse_conv_leaf_fwd(grid._h, _ptr(feat), _TORCH_DT[feat.dtype], _ptr(weights), c_in, c_out,
-                                       _ptr(out), _TORCH_DT[feat.dtype], _stream()))
+                                       _ptr(out), _TORCH_DT[out_dtype], _stream()))
     return out
 
 

@@ -44,7 +44,8 @@ struct LeafLds {
 __device__ __forceinline__ int window_cell(int x, int y, int z) { return (x * 10 + y) * 10 + z; }
 
 // index of the voxel at leaf-local (lx,ly,lz) of staged record `slot`, or -1 (Listing 1)
-__device__ __forceinline__ int staged_value(const LeafLds& L, int slot, int lx, int ly, int lz) {
+template <typename LDS>
+__device__ __forceinline__ int staged_value(const LDS& L, int slot, int lx, int ly, int lz) {
     const uint64_t w = L.mask[slot][lx];
     const uint64_t bit = 1ull << ((ly << 3) | lz);
     if (!(w & bit)) return -1;
@@ -87,7 +88,8 @@ __device__ unsigned long long g_leaf_timing[1024 * 8];
 #endif
 
 // Records of the 27 leaves around (and including) leaf f into LDS: one tree descent per lane.
-__device__ __forceinline__ void stage_records(const TreeView& t, LeafLds& L, int f, int lane) {
+template <typename LDS>
+__device__ __forceinline__ void stage_records(const TreeView& t, LDS& L, int f, int lane) {
     if (lane >= 27) return;
     const fx_leaf* lf = t.leaf + f;
     const int a = lane / 9, b = (lane / 3) % 3, c = lane % 3;
@@ -113,6 +115,7 @@ __device__ __forceinline__ void stage_records(const TreeView& t, LeafLds& L, int
 // cost of leaves [0, f) is kLeafFixedCost * f + offset of leaf f, which grows with f.  Returns the
 // first leaf whose prefix cost reaches `target` (wave-wide 64-ary search; every lane gets the result).
 constexpr int64_t kLeafFixedCost = 220;
+template <int64_t FIXED>
 __device__ __forceinline__ int first_leaf_at_cost(const TreeView& t, int64_t first_index, int64_t target, int lane) {
     int lo = 0, hi = t.n_leaf;               // answer in [lo, hi]; prefix cost of leaf n_leaf counts as infinite
     while (hi - lo > 0) {
@@ -120,7 +123,7 @@ __device__ __forceinline__ int first_leaf_at_cost(const TreeView& t, int64_t fir
         const int step = (span + 63) / 64;
         const int f = lo + lane * step;      // probes lo, lo + step, ...
         bool below = false;                  // prefix cost of f < target
-        if (f < hi) below = kLeafFixedCost * f + (t.leaf[f].offset - first_index) < target;
+        if (f < hi) below = FIXED * f + (t.leaf[f].offset - first_index) < target;
         const int n_below = __popcll(__ballot(below));     // probes are ascending in cost: a prefix of them is below
         if (n_below == 0) { hi = lo; break; }
         const int last_below = lo + (n_below - 1) * step;
@@ -176,7 +179,7 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
         const int64_t total = kLeafFixedCost * t.n_leaf + n_voxels;
         const int b = blockIdx.x + wave;
         const int f = b >= (int)gridDim.x ? t.n_leaf
-                                          : first_leaf_at_cost(t, first_index, total * b / (int64_t)gridDim.x, lane);
+                                          : first_leaf_at_cost<kLeafFixedCost>(t, first_index, total * b / (int64_t)gridDim.x, lane);
         if (lane == 0) L.range[wave] = f;
     }
     __syncthreads();
@@ -318,6 +321,237 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
 #endif
 }
 
+// ---------------------------------------------------------------------------------- 16-bit types, depth >= 32
+// The same leaf window for f16 / bf16 at C_in % 32 == 0, C_out % 64 == 0: the regime of locally dense
+// grids at moderate depth (Sec. 3.5 scenario 2 serves it with dense 4x2x2 bricks; here the window stays
+// the leaf's, the columns are the leaf's ACTIVE voxels in tiles of 32, and taps a tile does not need
+// are skipped).  The window holds one 32-channel chunk of every cell (64-byte rows, 16-byte pieces
+// XOR-swizzled by (row >> 2) & 3 like the tile kernel's rows); a tap is an address offset, so neither
+// row lists nor id blocks exist and a full leaf with all its neighbours needs 64 KB where the
+// kernel-map tiles of a dense region exceed their LDS budget.  Each wave owns up to four column tiles
+// (128 voxels x 64 output channels in 128 accumulator registers), fetches a tap's packed weights
+// once for all of them (same packing as the tile kernel: features A, weights B, channels
+// interleaved so that a half-wave stores whole output rows) and prefetches the next tap's.
+constexpr int kLeaf16Threads = 256;
+constexpr int kLeaf16Waves = kLeaf16Threads / 64;
+constexpr int kLeaf16Groups = 4;             // column tiles of 32 voxels per wave: 4 waves x 4 x 32 = 512
+constexpr int64_t kLeaf16FixedCost = 48;     // staging of a leaf in units of one active voxel's multiplies
+
+struct Leaf16Lds {
+    uint64_t mask[27][8];
+    uint64_t prefix[27];
+    int32_t offset[27];
+    uint32_t act_row[100];
+    int32_t cell_row[kWinCells];             // input row of each window cell, -1 = inactive
+    uint16_t cell_of_rank[512];
+    uint32_t tile_taps[16];                  // per column tile of 32 voxels
+    int32_t range[2];
+    unsigned char win[kWinCells * 64] __attribute__((aligned(16)));
+};
+
+__device__ __forceinline__ uint32_t win_piece_offset(int row, int piece) {
+    return (uint32_t)row * 64u + (uint32_t)((piece ^ ((row >> 2) & 3)) << 4);
+}
+
+template <typename T, bool OUT_F32>
+__global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, const unsigned char* __restrict__ feat,
+                                                                  const unsigned char* __restrict__ wp,
+                                                                  unsigned char* __restrict__ out, int C_in, int C_out,
+                                                                  int64_t n_voxels) {
+    typedef typename Elem<T>::vec8 vec8;
+    extern __shared__ __align__(16) unsigned char smem[];
+    Leaf16Lds& L = *reinterpret_cast<Leaf16Lds*>(smem);
+    const int tid0 = threadIdx.x, wave = tid0 >> 6;
+    const int nchunk = C_in / 32, nslice = C_out / 64;
+    const int64_t pitch = (int64_t)C_in * 2;
+
+    if (wave < 2) {
+        const int lane = tid0 & 63;
+        const int64_t first_index = t.leaf[0].offset;
+        const int64_t total = kLeaf16FixedCost * t.n_leaf + n_voxels;
+        const int b = blockIdx.x + wave;
+        const int f = b >= (int)gridDim.x ? t.n_leaf
+                                          : first_leaf_at_cost<kLeaf16FixedCost>(t, first_index, total * b / (int64_t)gridDim.x, lane);
+        if (lane == 0) L.range[wave] = f;
+    }
+    __syncthreads();
+    const int f_begin = uni(L.range[0]), f_end = uni(L.range[1]);
+
+    for (int f = f_begin; f < f_end; ++f) {
+        // everything a thread derives from its number is recomputed per leaf (registers are needed
+        // for the accumulators, not for loop-invariant addresses)
+        int tid = tid0;
+        asm volatile("" : "+v"(tid));
+        const int lane = tid & 63, n = lane & 31, h = lane >> 5;
+        // ---- the leaf's 27 records, then per cell its input row; activity bits per window row
+        if (wave == 0) stage_records(t, L, f, lane);
+        __syncthreads();
+        if (tid < 16) L.tile_taps[tid] = 0;
+        if (tid >= 128 && tid < 228) {
+            const int xy = tid - 128;
+            const int x = xy / 10, y = xy % 10;
+            const int s9 = ((x + 7) >> 3) * 9 + ((y + 7) >> 3) * 3, lx = (x - 1) & 7, sh = ((y - 1) & 7) * 8;
+            L.act_row[xy] = (uint32_t)((L.mask[s9][lx] >> (sh + 7)) & 1) | (uint32_t)((L.mask[s9 + 1][lx] >> sh) & 0xff) << 1 |
+                            (uint32_t)((L.mask[s9 + 2][lx] >> sh) & 1) << 9;
+        }
+        for (int cell = tid; cell < kWinCells; cell += kLeaf16Threads) {
+            const int x = cell / 100, y = (cell / 10) % 10, z = cell % 10;
+            const int slot = ((x + 7) >> 3) * 9 + ((y + 7) >> 3) * 3 + ((z + 7) >> 3);
+            L.cell_row[cell] = staged_value(L, slot, (x - 1) & 7, (y - 1) & 7, (z - 1) & 7);
+        }
+        __syncthreads();
+        const int n_act = uni((int)((L.prefix[13] >> 54) & 511) + __popcll(L.mask[13][7]));
+        const int64_t base = uni(L.offset[13]);
+        for (int m = tid; m < 512; m += kLeaf16Threads) {
+            const int lx = m >> 6, ly = (m >> 3) & 7, lz = m & 7;
+            const int row = L.cell_row[window_cell(lx + 1, ly + 1, lz + 1)];
+            if (row >= 0) {
+                const int r = row - (int)base;
+                L.cell_of_rank[r] = (uint16_t)window_cell(lx + 1, ly + 1, lz + 1);
+                uint32_t taps = 0;
+#pragma unroll
+                for (int ab = 0; ab < 9; ++ab)
+                    taps |= ((L.act_row[(lx + ab / 3) * 10 + ly + ab % 3] >> lz) & 7u) << (3 * ab);
+                atomicOr(&L.tile_taps[r >> 5], taps);
+            }
+        }
+        __syncthreads();
+
+        // this wave's column tiles: tile gi * 4 + wave, voxel n of it in lanes n and n + 32
+        const int n_tiles = (n_act + 31) >> 5;
+        uint32_t gtaps[kLeaf16Groups];
+        uint32_t gcell[kLeaf16Groups];          // byte offset of the voxel's own window row
+        uint32_t wtaps = 0;
+#pragma unroll
+        for (int gi = 0; gi < kLeaf16Groups; ++gi) {
+            const int tile = gi * kLeaf16Waves + wave;
+            gtaps[gi] = (uint32_t)uni((int)(tile < n_tiles ? L.tile_taps[tile] : 0u));
+            wtaps |= gtaps[gi];
+            gcell[gi] = L.cell_of_rank[min(tile * 32 + n, n_act - 1)];
+        }
+
+        for (int s = 0; s < nslice; ++s) {
+            f32x16 acc[kLeaf16Groups][2];
+#pragma unroll
+            for (int gi = 0; gi < kLeaf16Groups; ++gi)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[gi][mt][v] = 0.f;
+            for (int c = 0; c < nchunk; ++c) {
+                // ---- densify chunk c: 1000 cells x 4 pieces of 16 bytes, four loads in flight per thread
+                __syncthreads();                 // the previous multiply has finished with the window
+#pragma unroll 1
+                for (int e0 = tid; e0 < kWinCells * 4; e0 += kLeaf16Threads * 4) {
+                    u32x4 val[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int e = min(e0 + u * kLeaf16Threads, kWinCells * 4 - 1);
+                        const int row = L.cell_row[e >> 2];
+                        val[u] = *reinterpret_cast<const u32x4*>(feat + (int64_t)max(row, 0) * pitch + c * 64 + (e & 3) * 16);
+                        if (row < 0) val[u] = u32x4{0, 0, 0, 0};
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int e = e0 + u * kLeaf16Threads;
+                        if (e < kWinCells * 4) *reinterpret_cast<u32x4*>(L.win + win_piece_offset(e >> 2, e & 3)) = val[u];
+                    }
+                }
+                __syncthreads();
+
+                // ---- multiply: the taps this wave's tiles need; the next tap's weights are in flight
+                const unsigned char* wq = wp + ((int64_t)c * nslice + s) * 4096 + lane * 16;
+                const int64_t wstep = (int64_t)nchunk * nslice * 4096;
+                uint32_t taps = (uint32_t)uni((int)wtaps);
+                if (taps) {
+                    int kappa = __builtin_ctz(taps);
+                    taps &= taps - 1;
+                    vec8 wc[4];
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) wc[q4] = *reinterpret_cast<const vec8*>(wq + kappa * wstep + q4 * 1024);
+                    while (true) {
+                        const bool more = taps != 0;
+                        const int kn = more ? __builtin_ctz(taps) : kappa;
+                        taps &= taps - 1;
+                        vec8 wn[4];
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) wn[q4] = *reinterpret_cast<const vec8*>(wq + kn * wstep + q4 * 1024);
+                        const int d = tap_delta(kappa);
+                        vec8 bf[kLeaf16Groups][2];
+#pragma unroll
+                        for (int gi = 0; gi < kLeaf16Groups; ++gi) {
+                            const int row = (int)gcell[gi] + d;
+                            const uint32_t a0 = win_piece_offset(row, h);
+                            bf[gi][0] = *reinterpret_cast<const vec8*>(L.win + a0);
+                            bf[gi][1] = *reinterpret_cast<const vec8*>(L.win + (a0 ^ 32u));
+                        }
+#pragma unroll
+                        for (int gi = 0; gi < kLeaf16Groups; ++gi) {
+                            if ((gtaps[gi] >> kappa) & 1u) {
+#pragma unroll
+                                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                                    for (int mt = 0; mt < 2; ++mt)
+                                        acc[gi][mt] = Elem<T>::mma(bf[gi][ks], wc[mt * 2 + ks], acc[gi][mt]);
+                            }
+                        }
+                        if (!more) break;
+                        kappa = kn;
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) wc[q4] = wn[q4];
+                    }
+                }
+            }
+            // ---- write-back: register v of tile mt in lane (n, h) is channel 64 s + 2 n + mt of the
+            // tile's voxel 8 (v / 4) + 4 h + v % 4; the leaf's outputs are consecutive rows
+            const uint32_t esize = OUT_F32 ? 4u : 2u;
+            int lane_w = lane;
+            asm volatile("" : "+v"(lane_w));      // offsets and bounds of the stores are computed here, per slice
+            const int n_w = lane_w & 31, h_w = lane_w >> 5;
+            const uint32_t row_bytes = (uint32_t)C_out * esize, lane_off = 2u * (uint32_t)n_w * esize;
+            // wave-uniform 64-bit base, 32-bit lane offsets: the stores take the base as their scalar operand
+            const uint64_t bits = reinterpret_cast<uint64_t>(out) + (uint64_t)((base * C_out + 64 * s) * (int64_t)esize);
+            typedef __attribute__((address_space(1))) unsigned char gbyte;
+            gbyte* ob = (gbyte*)(((uint64_t)(uint32_t)uni((int)(uint32_t)(bits >> 32)) << 32) | (uint32_t)uni((int)(uint32_t)bits));
+#pragma unroll
+            for (int gi = 0; gi < kLeaf16Groups; ++gi) {
+                const int tile = gi * kLeaf16Waves + wave;
+                if (tile >= n_tiles) continue;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = tile * 32 + 8 * (v >> 2) + 4 * h_w + (v & 3);
+                    if (r >= n_act) continue;
+                    gbyte* dst = ob + ((uint32_t)r * row_bytes + lane_off);
+                    if (OUT_F32) *reinterpret_cast<__attribute__((address_space(1))) f32x2*>(dst) = f32x2{acc[gi][0][v], acc[gi][1][v]};
+                    else *reinterpret_cast<__attribute__((address_space(1))) uint32_t*>(dst) = Elem<T>::pack2(acc[gi][0][v], acc[gi][1][v]);
+                }
+            }
+        }
+        __syncthreads();                         // records and lists are rewritten for the next leaf
+    }
+}
+
+template <typename T, bool OUT_F32>
+fx_status launch_leaf16(const fx_grid* g, const void* feat, const void* wpacked, void* out, int C_in, int C_out,
+                        hipStream_t st) {
+    const size_t lds = sizeof(Leaf16Lds);
+    static int per_cu = 0;
+    if (per_cu == 0) {
+        FX_HIP_TRY(hipFuncSetAttribute((const void*)k_conv_leaf16<T, OUT_F32>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds));
+        int nb = 0;
+        FX_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_conv_leaf16<T, OUT_F32>, kLeaf16Threads, lds));
+        per_cu = std::max(1, nb);
+    }
+    const unsigned n_wg = (unsigned)std::min<int64_t>(g->hdr.n_leaf, (int64_t)per_cu * compute_units());
+    ProfScope ps(kProfConvLeaf, st);
+    k_conv_leaf16<T, OUT_F32><<<n_wg, kLeaf16Threads, lds, st>>>(g->view(), (const unsigned char*)feat,
+                                                                 (const unsigned char*)wpacked, (unsigned char*)out, C_in,
+                                                                 C_out, g->hdr.n_voxels);
+    FX_HIP_TRY(hipGetLastError());
+    return FX_OK;
+}
+
 constexpr bool leaf_weights_in_registers(int J, int NT) { return 27 * J * NT <= 64; }
 
 size_t leaf_lds_bytes(int J, int NT) {
@@ -368,9 +602,32 @@ extern "C" fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_fea
         return FX_EINVAL;
     }
     if (dt != FX_F32 && dt != FX_F16 && dt != FX_BF16) { set_error("unknown input dtype"); return FX_EINVAL; }
-    if (dt != FX_F32 || out_dt != FX_F32) {
-        set_error("fx_sparse_conv_leaf_fwd: fp32 in, fp32 out only");
+    if (out_dt != dt && out_dt != FX_F32) {
+        set_error("output dtype must equal the input dtype or be fp32");
         return FX_EUNSUPPORTED;
+    }
+    if (dt != FX_F32) {
+        if (C_in % 32 || C_out % 64) {
+            set_error("fx_sparse_conv_leaf_fwd: 16-bit types need C_in %% 32 == 0 and C_out %% 64 == 0 (got %d -> %d); "
+                      "use fx_build_kernel_map + fx_sparse_conv_fwd", C_in, C_out);
+            return FX_EUNSUPPORTED;
+        }
+        if (g->hdr.n_voxels == 0) return FX_OK;
+        hipStream_t st16 = (hipStream_t)stream;
+        void* wpk = nullptr;
+        const size_t wbytes = packed_weight_bytes(27, C_in, C_out, 2);
+        FX_TRY(dev_alloc(&wpk, wbytes + 8 * sizeof(int32_t), st16));
+        launch_pack_weights(d_w, wpk, 27, C_in, C_out, 2, reinterpret_cast<int32_t*>((char*)wpk + wbytes), kWeightsForward,
+                            kPackInterleaved, st16);
+        fx_status rc;
+        if (dt == FX_BF16)
+            rc = out_dt == FX_F32 ? launch_leaf16<__bf16, true>(g, d_feat, wpk, d_out, C_in, C_out, st16)
+                                  : launch_leaf16<__bf16, false>(g, d_feat, wpk, d_out, C_in, C_out, st16);
+        else
+            rc = out_dt == FX_F32 ? launch_leaf16<_Float16, true>(g, d_feat, wpk, d_out, C_in, C_out, st16)
+                                  : launch_leaf16<_Float16, false>(g, d_feat, wpk, d_out, C_in, C_out, st16);
+        dev_free(wpk, st16);
+        return rc;
     }
     if (C_in % 4 || C_in > 16 || C_out % 16 || C_out > 32) {
         set_error("fx_sparse_conv_leaf_fwd: needs C_in in {4,8,12,16} and C_out in {16,32} (got %d -> %d); "

@@ -12,14 +12,16 @@ from workloads import generators as G
 pytestmark = pytest.mark.gpu
 
 
-def _leaf_vs_oracle(grids, c_in, c_out, seed, dup=0.01):
+def _leaf_vs_oracle(grids, c_in, c_out, seed, dup=0.01, dtype="f32", out_f32=False):
     ijk, jo = G.make_jagged([G.shuffle_and_duplicate(g, seed + b, dup) for b, g in enumerate(grids)])
     g, og = H.both_grids(ijk, jo)
-    feat, wt = G.features_and_weights(seed, og.num_voxels, c_in, c_out, 27, "f32")
-    y = fx.sparse_conv_leaf_fwd(g, H.to_device_storage(feat, "f32"), H.to_device_storage(wt, "f32"))
+    feat, wt = G.features_and_weights(seed, og.num_voxels, c_in, c_out, 27, dtype)
+    y = fx.sparse_conv_leaf_fwd(g, H.to_device_storage(feat, dtype), H.to_device_storage(wt, dtype),
+                                out_dtype=torch.float32 if out_f32 else None)
     ref = O.conv(og, og, 3, 1, feat, wt)
     assert y.shape == ref.shape
-    H.conv_tolerance_check(y.cpu().numpy(), ref, "f32", 27, c_in)
+    assert y.dtype == (torch.float32 if out_f32 else H.TORCH_DT[dtype])
+    H.conv_tolerance_check(y.float().cpu().numpy(), ref, dtype, 27, c_in)
     return g, feat, wt, y
 
 
@@ -27,6 +29,44 @@ def _leaf_vs_oracle(grids, c_in, c_out, seed, dup=0.01):
 def test_volumetric_bodies_all_channel_shapes(c_in, c_out):
     w = G.workload("volume_small")
     _leaf_vs_oracle(w.grids, c_in, c_out, w.feat_seed)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("c_in,c_out,out_f32", [(32, 64, False), (64, 64, True), (64, 128, False), (96, 64, False)])
+def test_sixteen_bit_window_kernel_on_volumetric_bodies(dtype, c_in, c_out, out_f32):
+    w = G.workload("volume_small")
+    _leaf_vs_oracle(w.grids, c_in, c_out, w.feat_seed, dtype=dtype, out_f32=out_f32)
+
+
+@pytest.mark.parametrize("name", ["lidar_small", "sheets_small", "indoor_small"])
+def test_sixteen_bit_window_kernel_on_sparse_grids(name):
+    w = G.workload(name)
+    _leaf_vs_oracle(w.grids, 64, 64, w.feat_seed, dtype="bf16")
+
+
+def test_sixteen_bit_window_kernel_on_dense_block_and_isolated_voxels():
+    a = np.arange(-10, 10)
+    blk = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3)
+    rng = np.random.default_rng(6)
+    far = (rng.integers(-2000, 2000, size=(200, 3)) * 16).astype(np.int32)
+    _leaf_vs_oracle([np.concatenate([blk, blk + np.array([128, 128, 4096])]).astype(np.int32), far], 32, 64, 74,
+                    dtype="f16")
+
+
+@pytest.mark.parametrize("name", ["volume1m_c64", "dense96"])
+def test_sixteen_bit_window_kernel_full_size_sampled_rows(name):
+    w = G.workload(name)
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    feat, wt = w.feats_weights()
+    y = fx.sparse_conv_leaf_fwd(g, H.to_device_storage(feat, w.dtype), H.to_device_storage(wt, w.dtype)).float().cpu().numpy()
+    n = og.num_voxels
+    starts = list(range(0, n - 300, n // 12)) + [n - 300]
+    f64, w64 = feat.astype(np.float64), wt.astype(np.float64)
+    for s0 in starts:
+        ref = O.conv(og, og, 3, 1, f64, w64, s0, s0 + 300)
+        H.conv_tolerance_check(y[s0:s0 + 300], ref[s0:s0 + 300], w.dtype, 27, w.c_in)
+    assert np.isfinite(y).all()
 
 
 @pytest.mark.parametrize("name", ["lidar_small", "sheets_small", "indoor_small", "sphere64"])
@@ -75,7 +115,7 @@ def test_unsupported_shapes_are_refused():
     g, _ = H.both_grids(ijk, jo)
     n = g.num_voxels
     for c_in, c_out, dt in ((8, 24, torch.float32), (20, 16, torch.float32), (6, 16, torch.float32),
-                            (8, 16, torch.bfloat16)):
+                            (8, 16, torch.bfloat16), (32, 32, torch.bfloat16), (48, 64, torch.float16)):
         with pytest.raises(fx.FxError):
             fx.sparse_conv_leaf_fwd(g, torch.zeros((n, c_in), device="cuda", dtype=dt),
                                     torch.zeros((27, c_in, c_out), device="cuda", dtype=dt))
