@@ -337,6 +337,9 @@ constexpr int kLeaf16Waves = kLeaf16Threads / 64;
 constexpr int kLeaf16Groups = 4;             // column tiles of 32 voxels per wave: 4 waves x 4 x 32 = 512
 constexpr int64_t kLeaf16FixedCost = 48;     // staging of a leaf in units of one active voxel's multiplies
 
+constexpr int kWinSlabs = (kWinCells + 15) / 16;     // direct-to-LDS loads fill 16 rows (1 KB) per wave instruction
+typedef __attribute__((address_space(3))) void* leaf_lds_ptr;
+
 struct Leaf16Lds {
     uint64_t mask[27][8];
     uint64_t prefix[27];
@@ -346,7 +349,7 @@ struct Leaf16Lds {
     uint16_t cell_of_rank[512];
     uint32_t tile_taps[16];                  // per column tile of 32 voxels
     int32_t range[2];
-    unsigned char win[kWinCells * 64] __attribute__((aligned(16)));
+    unsigned char win[kWinSlabs * 1024] __attribute__((aligned(16)));   // 64-byte rows, in slabs of 16
 };
 
 __device__ __forceinline__ uint32_t win_piece_offset(int row, int piece) {
@@ -357,7 +360,7 @@ template <typename T, bool OUT_F32>
 __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, const unsigned char* __restrict__ feat,
                                                                   const unsigned char* __restrict__ wp,
                                                                   unsigned char* __restrict__ out, int C_in, int C_out,
-                                                                  int64_t n_voxels) {
+                                                                  int64_t n_voxels, const unsigned char* __restrict__ zero_row) {
     typedef typename Elem<T>::vec8 vec8;
     extern __shared__ __align__(16) unsigned char smem[];
     Leaf16Lds& L = *reinterpret_cast<Leaf16Lds*>(smem);
@@ -377,6 +380,10 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
     __syncthreads();
     const int f_begin = uni(L.range[0]), f_end = uni(L.range[1]);
 
+#ifdef FX_LEAF_TIMING
+    unsigned long long _tl = __builtin_readcyclecounter();
+    const unsigned long long _w0 = wall_clock64();
+#endif
     for (int f = f_begin; f < f_end; ++f) {
         // everything a thread derives from its number is recomputed per leaf (registers are needed
         // for the accumulators, not for loop-invariant addresses)
@@ -417,6 +424,7 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
         }
         __syncthreads();
 
+        if (wave == 0) FX_LT(0);                 // leaf prologue: records, cell rows, lists
         // this wave's column tiles: tile gi * 4 + wave, voxel n of it in lanes n and n + 32
         const int n_tiles = (n_act + 31) >> 5;
         uint32_t gtaps[kLeaf16Groups];
@@ -439,43 +447,52 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc[gi][mt][v] = 0.f;
             for (int c = 0; c < nchunk; ++c) {
-                // ---- densify chunk c: 1000 cells x 4 pieces of 16 bytes, four loads in flight per thread
+                // ---- densify chunk c: direct-to-LDS loads, one 1 KB slab of 16 rows per wave instruction; lane l
+                // of a slab writes the 16 bytes at slab + 16 l, i.e. stored piece l & 3 of row l / 4, which is
+                // piece (l & 3) ^ ((row >> 2) & 3) of the cell's chunk; inactive cells load from a zero row
+                if (wave == 0) FX_LT(5);
                 __syncthreads();                 // the previous multiply has finished with the window
-#pragma unroll 1
-                for (int e0 = tid; e0 < kWinCells * 4; e0 += kLeaf16Threads * 4) {
-                    u32x4 val[4];
+                if (wave == 0) FX_LT(1);         // wait before densify
+                {
+                    const int piece = (lane & 3) ^ ((lane >> 4) & 3);
+                    // all row numbers first: a read of LDS after an asynchronous write to LDS has been issued
+                    // would wait for that write
+                    constexpr int kSlabsPerWave = (kWinSlabs + kLeaf16Waves - 1) / kLeaf16Waves;
+                    int rows[kSlabsPerWave];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int e = min(e0 + u * kLeaf16Threads, kWinCells * 4 - 1);
-                        const int row = L.cell_row[e >> 2];
-                        val[u] = *reinterpret_cast<const u32x4*>(feat + (int64_t)max(row, 0) * pitch + c * 64 + (e & 3) * 16);
-                        if (row < 0) val[u] = u32x4{0, 0, 0, 0};
+                    for (int j = 0; j < kSlabsPerWave; ++j) {
+                        const int cell = 16 * (wave + j * kLeaf16Waves) + (lane >> 2);
+                        rows[j] = cell < kWinCells ? L.cell_row[cell] : -1;
                     }
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int e = e0 + u * kLeaf16Threads;
-                        if (e < kWinCells * 4) *reinterpret_cast<u32x4*>(L.win + win_piece_offset(e >> 2, e & 3)) = val[u];
+                    for (int j = 0; j < kSlabsPerWave; ++j) {
+                        const int sl = wave + j * kLeaf16Waves;
+                        if (sl < kWinSlabs) {
+                            const unsigned char* src = rows[j] >= 0 ? feat + (int64_t)rows[j] * pitch + c * 64 + piece * 16
+                                                                    : zero_row + piece * 16;
+                            __builtin_amdgcn_global_load_lds(src, (leaf_lds_ptr)(L.win + sl * 1024), 16, 0, 0);
+                        }
                     }
+                    __builtin_amdgcn_s_waitcnt(0);
                 }
+                if (wave == 0) FX_LT(2);         // densify own loads
                 __syncthreads();
+                if (wave == 0) FX_LT(3);         // wait after densify
 
                 // ---- multiply: the taps this wave's tiles need; the next tap's weights are in flight
                 const unsigned char* wq = wp + ((int64_t)c * nslice + s) * 4096 + lane * 16;
                 const int64_t wstep = (int64_t)nchunk * nslice * 4096;
                 uint32_t taps = (uint32_t)uni((int)wtaps);
                 if (taps) {
-                    int kappa = __builtin_ctz(taps);
-                    taps &= taps - 1;
-                    vec8 wc[4];
+                    // one tap: request the weights of the tap after it into the other register set, fetch the
+                    // four tiles' fragments of this tap from the window, multiply.  Two register sets take turns
+                    // (the loop is unrolled by two), so a set is first touched a whole tap after its request.
+                    auto fetch_w = [&](vec8 (&wset)[4], int k) {
 #pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) wc[q4] = *reinterpret_cast<const vec8*>(wq + kappa * wstep + q4 * 1024);
-                    while (true) {
-                        const bool more = taps != 0;
-                        const int kn = more ? __builtin_ctz(taps) : kappa;
-                        taps &= taps - 1;
-                        vec8 wn[4];
-#pragma unroll
-                        for (int q4 = 0; q4 < 4; ++q4) wn[q4] = *reinterpret_cast<const vec8*>(wq + kn * wstep + q4 * 1024);
+                        for (int q4 = 0; q4 < 4; ++q4) wset[q4] = *reinterpret_cast<const vec8*>(wq + k * wstep + q4 * 1024);
+                    };
+                    auto tap = [&](const vec8 (&wcur)[4], vec8 (&wnext)[4], int kappa, int knext) {
+                        fetch_w(wnext, knext);
                         const int d = tap_delta(kappa);
                         vec8 bf[kLeaf16Groups][2];
 #pragma unroll
@@ -492,16 +509,25 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
                                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                                     for (int mt = 0; mt < 2; ++mt)
-                                        acc[gi][mt] = Elem<T>::mma(bf[gi][ks], wc[mt * 2 + ks], acc[gi][mt]);
+                                        acc[gi][mt] = Elem<T>::mma(bf[gi][ks], wcur[mt * 2 + ks], acc[gi][mt]);
                             }
                         }
-                        if (!more) break;
-                        kappa = kn;
-#pragma unroll
-                        for (int q4 = 0; q4 < 4; ++q4) wc[q4] = wn[q4];
+                    };
+                    auto pop = [&]() { const int k = taps ? __builtin_ctz(taps) : -1; taps &= taps - 1; return k; };
+                    vec8 wa[4], wb[4];
+                    int k0 = pop(), k1 = pop();
+                    fetch_w(wa, k0);
+                    while (true) {
+                        tap(wa, wb, k0, k1 >= 0 ? k1 : k0);
+                        if (k1 < 0) break;
+                        k0 = pop();
+                        tap(wb, wa, k1, k0 >= 0 ? k0 : k1);
+                        if (k0 < 0) break;
+                        k1 = pop();
                     }
                 }
             }
+            if (wave == 0) FX_LT(4);             // multiply (last chunk)
             // ---- write-back: register v of tile mt in lane (n, h) is channel 64 s + 2 n + mt of the
             // tile's voxel 8 (v / 4) + 4 h + v % 4; the leaf's outputs are consecutive rows
             const uint32_t esize = OUT_F32 ? 4u : 2u;
@@ -527,13 +553,17 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
                 }
             }
         }
+        if (wave == 0) FX_LT(6);                 // write-back
         __syncthreads();                         // records and lists are rewritten for the next leaf
     }
+#ifdef FX_LEAF_TIMING
+    if (tid0 == 0 && blockIdx.x < 1024) g_leaf_timing[blockIdx.x * 8 + 7] = wall_clock64() - _w0;
+#endif
 }
 
 template <typename T, bool OUT_F32>
 fx_status launch_leaf16(const fx_grid* g, const void* feat, const void* wpacked, void* out, int C_in, int C_out,
-                        hipStream_t st) {
+                        const void* zero_row, hipStream_t st) {
     const size_t lds = sizeof(Leaf16Lds);
     static int per_cu = 0;
     if (per_cu == 0) {
@@ -547,7 +577,7 @@ fx_status launch_leaf16(const fx_grid* g, const void* feat, const void* wpacked,
     ProfScope ps(kProfConvLeaf, st);
     k_conv_leaf16<T, OUT_F32><<<n_wg, kLeaf16Threads, lds, st>>>(g->view(), (const unsigned char*)feat,
                                                                  (const unsigned char*)wpacked, (unsigned char*)out, C_in,
-                                                                 C_out, g->hdr.n_voxels);
+                                                                 C_out, g->hdr.n_voxels, (const unsigned char*)zero_row);
     FX_HIP_TRY(hipGetLastError());
     return FX_OK;
 }
@@ -616,16 +646,23 @@ extern "C" fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_fea
         hipStream_t st16 = (hipStream_t)stream;
         void* wpk = nullptr;
         const size_t wbytes = packed_weight_bytes(27, C_in, C_out, 2);
-        FX_TRY(dev_alloc(&wpk, wbytes + 8 * sizeof(int32_t), st16));
+        // behind the packed weights: 32 bytes the packing kernel clears, then a 64-byte row of zeros
+        FX_TRY(dev_alloc(&wpk, wbytes + 96, st16));
+        const void* zero_row = (const char*)wpk + wbytes + 32;
+        if (hipMemsetAsync((char*)wpk + wbytes, 0, 96, st16) != hipSuccess) {
+            dev_free(wpk, st16);
+            set_error("fx_sparse_conv_leaf_fwd: memset failed");
+            return FX_EDEVICE;
+        }
         launch_pack_weights(d_w, wpk, 27, C_in, C_out, 2, reinterpret_cast<int32_t*>((char*)wpk + wbytes), kWeightsForward,
                             kPackInterleaved, st16);
         fx_status rc;
         if (dt == FX_BF16)
-            rc = out_dt == FX_F32 ? launch_leaf16<__bf16, true>(g, d_feat, wpk, d_out, C_in, C_out, st16)
-                                  : launch_leaf16<__bf16, false>(g, d_feat, wpk, d_out, C_in, C_out, st16);
+            rc = out_dt == FX_F32 ? launch_leaf16<__bf16, true>(g, d_feat, wpk, d_out, C_in, C_out, zero_row, st16)
+                                  : launch_leaf16<__bf16, false>(g, d_feat, wpk, d_out, C_in, C_out, zero_row, st16);
         else
-            rc = out_dt == FX_F32 ? launch_leaf16<_Float16, true>(g, d_feat, wpk, d_out, C_in, C_out, st16)
-                                  : launch_leaf16<_Float16, false>(g, d_feat, wpk, d_out, C_in, C_out, st16);
+            rc = out_dt == FX_F32 ? launch_leaf16<_Float16, true>(g, d_feat, wpk, d_out, C_in, C_out, zero_row, st16)
+                                  : launch_leaf16<_Float16, false>(g, d_feat, wpk, d_out, C_in, C_out, zero_row, st16);
         dev_free(wpk, st16);
         return rc;
     }
