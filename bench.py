@@ -262,7 +262,17 @@ def main():
                      "algorithmic_bytes": v_bytes, "GBs": v_bytes / (t_leaf * 1e-3) / 1e9,
                      "frac_of_hbm_peak": v_bytes / (t_leaf * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "kernel_map_path_ms": {"kernel_map": t_kmv, "conv": t_cv}}
-        del kmv, gv, v_feat
+        # the same grid at 64 -> 64 bf16: the leaf-window kernel for 16-bit types against the kernel-map path
+        h_feat = torch.randn((nv, 64), device="cuda").to(torch.bfloat16)
+        h_w = (torch.randn((27, 64, 64), device="cuda") * (1.0 / (27 * 64)) ** 0.5).to(torch.bfloat16)
+        t_l16 = b2b(lambda: fx.sparse_conv_leaf_fwd(gv, h_feat, h_w), reps=5)
+        t_c16 = b2b(lambda: fx.sparse_conv_fwd(kmv, h_feat, h_w), reps=5)
+        h_flops = 2.0 * v_pairs * 64 * 64
+        low_depth["leaf_window_bf16_64"] = {
+            "leaf_conv_ms": t_l16, "leaf_conv_effective_TFLOPs": h_flops / (t_l16 * 1e-3) / 1e12,
+            "frac_of_bf16_mfma_peak": h_flops / (t_l16 * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS["bf16"],
+            "kernel_map_path_ms": {"kernel_map": t_kmv, "conv": t_c16}}
+        del kmv, gv, v_feat, h_feat
 
     # ---- grid build from xyz points (Sec. 4.1.1's benchmark input: normally distributed points), 10 M points,
     # sigma = 100 voxels (not part of `value`)

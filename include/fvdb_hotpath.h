@@ -257,23 +257,27 @@ fx_status fx_pool2(const fx_kmap* km, int32_t mode, const void* d_feat, fx_dtype
 fx_status fx_upsample2(const fx_kmap* km, const void* d_feat, fx_dtype dt, int32_t C, void* d_out, void* stream);
 
 /* ---------------------------------------------------------------------------------------
- * Low-depth 3x3x3 submanifold convolution straight from the grid, without a kernel map (Sec. 3.5
- * scenario 1, the "Leaf" operator: the 10^3 window of input rows around each 8^3 leaf is densified
- * in on-chip memory, the gather offsets come from the tree itself, and each leaf's outputs are
- * written as one contiguous range).  Same result as fx_sparse_conv_fwd on the (3,1) map of g:
+ * 3x3x3 submanifold convolution straight from the grid, without a kernel map (Sec. 3.5 scenario 1,
+ * the "Leaf" operator: the 10^3 window of input rows around each 8^3 leaf is densified in on-chip
+ * memory, the gather offsets come from the tree itself, and each leaf's outputs are written as one
+ * contiguous range; the same window serves the locally dense, deeper regime that scenario 2 targets).
+ * Same result as fx_sparse_conv_fwd on the (3,1) map of g:
  *     out[o,:] = sum over the 27 offsets kappa whose neighbour i of voxel o is active of
  *                feat[i,:] . W[kappa]
  *
  *   g       the grid; inputs and outputs both live on it (N = its voxel count)
- *   d_feat  device [N, C_in]  fp32 row-major, 16-byte aligned
- *   d_w     device [27, C_in, C_out] fp32 row-major, kappa = (di+1)*9 + (dj+1)*3 + (dk+1)
- *   d_out   device [N, C_out] fp32 row-major, 16-byte aligned; every row is written
- * fp32 products accumulated in fp32 on the matrix units (sum order differs from
- * fx_sparse_conv_fwd; same tolerance).  Supported: dt = out_dt = FX_F32, C_in in {4, 8, 12, 16},
- * C_out in {16, 32}; anything else returns FX_EUNSUPPORTED (build a kernel map and call
- * fx_sparse_conv_fwd).  Unlike the paper's kernel, (16-voxel tile, offset) pairs without any
- * active neighbour are skipped: at fp32 this operator is bound by arithmetic on gfx950, not by memory.
- * Meant for leaf occupancy above ~20 %; on very sparse grids the kernel-map path is faster.
+ *   d_feat  device [N, C_in]  row-major, dtype dt, 16-byte aligned
+ *   d_w     device [27, C_in, C_out] row-major, dtype dt, kappa = (di+1)*9 + (dj+1)*3 + (dk+1)
+ *   d_out   device [N, C_out] row-major, dtype out_dt (= dt or FX_F32), 16-byte aligned; every row is written
+ * Supported shapes:
+ *   FX_F32            C_in in {4, 8, 12, 16}, C_out in {16, 32}, out_dt = FX_F32 (true fp32 products on the
+ *                     matrix units, fp32 sums; order differs from fx_sparse_conv_fwd, same tolerance)
+ *   FX_F16 / FX_BF16  C_in % 32 == 0, C_out % 64 == 0 (exact products, fp32 sums, one RNE rounding to out_dt);
+ *                     allocates the packed weights (27 * C_in * C_out * 2 bytes) for the call
+ * anything else returns FX_EUNSUPPORTED (build a kernel map and call fx_sparse_conv_fwd).  Unlike the
+ * paper's kernel, (column tile, offset) pairs without any active neighbour are skipped: at these shapes
+ * the operator is bound by arithmetic on gfx950, not by memory.  Meant for leaf occupancy above ~20 %
+ * (volumetric and dense grids); on sparse grids the kernel-map path is several times faster.
  * Does not synchronise; pointers are borrowed for the stream-ordered work.
  */
 fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_feat, fx_dtype dt, const void* d_w,
