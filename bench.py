@@ -61,7 +61,7 @@ def pmc_summary(directory):
     acc = collections.defaultdict(lambda: collections.defaultdict(list))
     for f in files:
         for row in csv.DictReader(open(f)):
-            name = row["Kernel_Name"].split("(")[0]
+            name = row["Kernel_Name"].replace("(anonymous namespace)::", "").split("(")[0]
             acc[name][row["Counter_Name"]].append(float(row["Counter_Value"]))
     for name in sorted(acc):
         for ctr, v in sorted(acc[name].items()):
