@@ -283,6 +283,18 @@ fx_status fx_upsample2(const fx_kmap* km, const void* d_feat, fx_dtype dt, int32
 fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_feat, fx_dtype dt, const void* d_w,
                                   int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream);
 
+/* Input gradient of the convolution above (Sec. 3.6: the operators are differentiable), again without a
+ * kernel map:  gin[i,:] = sum over pairs (o,kappa) with neighbour(o,kappa) = i of  W[kappa] . gout[o,:].
+ * The map of a submanifold convolution is symmetric, so this is the forward kernel on gout with the
+ * offsets reflected (kappa -> 26 - kappa) and every W[kappa] transposed; same result as
+ * fx_sparse_conv_bwd_data on the (3,1) map of g.
+ *   d_gout [N, C_out] dtype dt, d_w [27, C_in, C_out] (the forward layout), d_gin [N, C_in] dtype out_dt.
+ * Supported shapes: the forward's with the roles of C_in and C_out exchanged (fp32: C_out in
+ * {4, 8, 12, 16}, C_in in {16, 32}; FX_F16 / FX_BF16: C_out % 32 == 0, C_in % 64 == 0); others
+ * FX_EUNSUPPORTED.  The weight gradient has no map-free form here: fx_sparse_conv_bwd_weight on a kernel map. */
+fx_status fx_sparse_conv_leaf_bwd_data(const fx_grid* g, const void* d_gout, fx_dtype dt, const void* d_w,
+                                       int32_t C_in, int32_t C_out, void* d_gin, fx_dtype out_dt, void* stream);
+
 /* ---------------------------------------------------------------------------------------
  * Measurement support (the paper's protocol, Sec. 4.1: per-operator times).  While enabled,
  * every kernel launch of the library is bracketed by hipEvents on its launch stream;

@@ -79,6 +79,8 @@ def _load():
     L.fx_grid_subdivide2.argtypes = [vp, vp, C.POINTER(vp)]
     L.fx_sparse_conv_leaf_fwd.restype = C.c_int
     L.fx_sparse_conv_leaf_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
+    L.fx_sparse_conv_leaf_bwd_data.restype = C.c_int
+    L.fx_sparse_conv_leaf_bwd_data.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
     L.fx_sparse_conv_transpose_fwd.restype = C.c_int
     L.fx_sparse_conv_transpose_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
     L.fx_pool2.restype = C.c_int
@@ -337,6 +339,20 @@ def sparse_conv_leaf_fwd(grid: IndexGrid, feat: torch.Tensor, weights: torch.Ten
     _check(lib.fx_sparse_conv_leaf_fwd(grid._h, _ptr(feat), _TORCH_DT[feat.dtype], _ptr(weights), c_in, c_out,
                                        _ptr(out), _TORCH_DT[out_dtype], _stream()))
     return out
+
+
+def sparse_conv_leaf_bwd_data(grid: IndexGrid, grad_out: torch.Tensor, weights: torch.Tensor,
+                              out_dtype: Optional[torch.dtype] = None) -> torch.Tensor:
+    """Input gradient of sparse_conv_leaf_fwd: grad_out [N, C_out], weights [27, C_in, C_out] -> [N, C_in]."""
+    assert grad_out.is_cuda and weights.is_cuda and grad_out.is_contiguous() and weights.is_contiguous()
+    assert grad_out.dtype == weights.dtype and grad_out.dtype in _TORCH_DT
+    k3, c_in, c_out = weights.shape
+    assert k3 == 27 and grad_out.shape == (grid.num_voxels, c_out)
+    out_dtype = out_dtype or grad_out.dtype
+    gin = torch.empty((grid.num_voxels, c_in), dtype=out_dtype, device="cuda")
+    _check(lib.fx_sparse_conv_leaf_bwd_data(grid._h, _ptr(grad_out), _TORCH_DT[grad_out.dtype], _ptr(weights), c_in, c_out,
+                                            _ptr(gin), _TORCH_DT[out_dtype], _stream()))
+    return gin
 
 
 def pool2(kmap: KernelMap, feat: torch.Tensor, mode: str = "max") -> torch.Tensor:

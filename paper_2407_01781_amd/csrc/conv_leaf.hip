@@ -136,6 +136,13 @@ __device__ __forceinline__ int first_leaf_at_cost(const TreeView& t, int64_t fir
 // window-cell distance of tap kappa
 __device__ __forceinline__ int tap_delta(int kappa) { return (kappa / 9) * 100 + ((kappa / 3) % 3) * 10 + kappa % 3 - 111; }
 
+// Element of the caller's weights that multiplies contracted channel c into produced channel p at tap
+// kappa.  Forward: W[kappa][c][p].  Mirrored (the input gradient on the symmetric submanifold map): the
+// caller's array is W[27][p-count][c-count] and the tap is reflected: W[26 - kappa][p][c].
+__device__ __forceinline__ int leaf_weight_index(int kappa, int c, int p, int n_contract, int n_produce, int mirrored) {
+    return mirrored ? ((26 - kappa) * n_produce + p) * n_contract + c : (kappa * n_contract + c) * n_produce + p;
+}
+
 // J = C_in / 4 MFMA k-steps per tap, NT = C_out / 16 row tiles, WREG: every lane keeps its share of
 // the weights (27 * J * NT values) in registers instead of LDS.
 // Workgroups are persistent: each keeps the weights and takes leaves blockIdx.x, blockIdx.x +
@@ -150,7 +157,7 @@ __device__ __forceinline__ int tap_delta(int kappa) { return (kappa / 9) * 100 +
 template <int J, int NT, bool WREG>
 __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const float* __restrict__ feat,
                                                             const float* __restrict__ w, float* __restrict__ out,
-                                                            int64_t n_voxels) {
+                                                            int64_t n_voxels, int mirrored) {
     constexpr int C_in = 4 * J, C_out = 16 * NT;
     extern __shared__ __align__(16) unsigned char smem[];
     LeafLds& L = *reinterpret_cast<LeafLds*>(smem);
@@ -167,11 +174,11 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                 for (int j = 0; j < J; ++j)
-                    wr[WREG ? kappa : 0][nt][j] = w[(kappa * C_in + J * q + j) * C_out + 16 * nt + v];
+                    wr[WREG ? kappa : 0][nt][j] = w[leaf_weight_index(kappa, J * q + j, 16 * nt + v, C_in, C_out, mirrored)];
     } else {
         for (int e = tid; e < 27 * C_in * C_out; e += kLeafThreads) {
             const int cout = e % C_out, ci = (e / C_out) % C_in, kappa = e / (C_out * C_in);
-            wl[((kappa * 4 + ci / J) * C_out + cout) * J + ci % J] = w[e];
+            wl[((kappa * 4 + ci / J) * C_out + cout) * J + ci % J] = w[leaf_weight_index(kappa, ci, cout, C_in, C_out, mirrored)];
         }
     }
     if (wave < 2) {
@@ -591,7 +598,7 @@ size_t leaf_lds_bytes(int J, int NT) {
 }
 
 template <int J, int NT>
-fx_status launch_leaf(const fx_grid* g, const float* feat, const float* w, float* out, hipStream_t st) {
+fx_status launch_leaf(const fx_grid* g, const float* feat, const float* w, float* out, int mirrored, hipStream_t st) {
     constexpr bool WREG = leaf_weights_in_registers(J, NT);
     const size_t lds = leaf_lds_bytes(J, NT);
     static int per_cu = 0;                    // resident workgroups per compute unit (registers, LDS, wave slots)
@@ -604,7 +611,7 @@ fx_status launch_leaf(const fx_grid* g, const float* feat, const float* w, float
     }
     const unsigned n_wg = (unsigned)std::min<int64_t>(g->hdr.n_leaf, (int64_t)per_cu * compute_units());
     ProfScope ps(kProfConvLeaf, st);
-    k_conv_leaf<J, NT, WREG><<<n_wg, kLeafThreads, lds, st>>>(g->view(), feat, w, out, g->hdr.n_voxels);
+    k_conv_leaf<J, NT, WREG><<<n_wg, kLeafThreads, lds, st>>>(g->view(), feat, w, out, g->hdr.n_voxels, mirrored);
     FX_HIP_TRY(hipGetLastError());
     return FX_OK;
 }
@@ -625,10 +632,12 @@ extern "C" int fx_debug_leaf_timing(unsigned long long* h_out, size_t bytes, int
 }
 #endif
 
-extern "C" fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_feat, fx_dtype dt, const void* d_w,
-                                             int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream) {
-    if (!g || !d_w || C_in < 1 || C_out < 1 || (g->hdr.n_voxels > 0 && (!d_feat || !d_out))) {
-        set_error("fx_sparse_conv_leaf_fwd: null pointer or non-positive channel count");
+// The leaf-window convolution of `src` [N, C_contract] into `dst` [N, C_produce]; `mode` says how the
+// caller's weights are read (kWeightsForward, or kWeightsMirrored for the input gradient).
+static fx_status leaf_apply(const char* who, const fx_grid* g, const void* d_src, fx_dtype dt, const void* d_w,
+                            int32_t C_contract, int32_t C_produce, void* d_dst, fx_dtype out_dt, hipStream_t st, int mode) {
+    if (!g || !d_w || C_contract < 1 || C_produce < 1 || (g->hdr.n_voxels > 0 && (!d_src || !d_dst))) {
+        set_error("%s: null pointer or non-positive channel count", who);
         return FX_EINVAL;
     }
     if (dt != FX_F32 && dt != FX_F16 && dt != FX_BF16) { set_error("unknown input dtype"); return FX_EINVAL; }
@@ -637,49 +646,48 @@ extern "C" fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_fea
         return FX_EUNSUPPORTED;
     }
     if (dt != FX_F32) {
-        if (C_in % 32 || C_out % 64) {
-            set_error("fx_sparse_conv_leaf_fwd: 16-bit types need C_in %% 32 == 0 and C_out %% 64 == 0 (got %d -> %d); "
-                      "use fx_build_kernel_map + fx_sparse_conv_fwd", C_in, C_out);
+        if (C_contract % 32 || C_produce % 64) {
+            set_error("%s: 16-bit types need a multiple of 32 contracted and of 64 produced channels (got %d -> %d); "
+                      "use the kernel-map path", who, C_contract, C_produce);
             return FX_EUNSUPPORTED;
         }
         if (g->hdr.n_voxels == 0) return FX_OK;
-        hipStream_t st16 = (hipStream_t)stream;
         void* wpk = nullptr;
-        const size_t wbytes = packed_weight_bytes(27, C_in, C_out, 2);
+        const size_t wbytes = packed_weight_bytes(27, C_contract, C_produce, 2);
         // behind the packed weights: 32 bytes the packing kernel clears, then a 64-byte row of zeros
-        FX_TRY(dev_alloc(&wpk, wbytes + 96, st16));
+        FX_TRY(dev_alloc(&wpk, wbytes + 96, st));
         const void* zero_row = (const char*)wpk + wbytes + 32;
-        if (hipMemsetAsync((char*)wpk + wbytes, 0, 96, st16) != hipSuccess) {
-            dev_free(wpk, st16);
-            set_error("fx_sparse_conv_leaf_fwd: memset failed");
+        if (hipMemsetAsync((char*)wpk + wbytes, 0, 96, st) != hipSuccess) {
+            dev_free(wpk, st);
+            set_error("%s: memset failed", who);
             return FX_EDEVICE;
         }
-        launch_pack_weights(d_w, wpk, 27, C_in, C_out, 2, reinterpret_cast<int32_t*>((char*)wpk + wbytes), kWeightsForward,
-                            kPackInterleaved, st16);
+        launch_pack_weights(d_w, wpk, 27, C_contract, C_produce, 2, reinterpret_cast<int32_t*>((char*)wpk + wbytes), mode,
+                            kPackInterleaved, st);
         fx_status rc;
         if (dt == FX_BF16)
-            rc = out_dt == FX_F32 ? launch_leaf16<__bf16, true>(g, d_feat, wpk, d_out, C_in, C_out, zero_row, st16)
-                                  : launch_leaf16<__bf16, false>(g, d_feat, wpk, d_out, C_in, C_out, zero_row, st16);
+            rc = out_dt == FX_F32 ? launch_leaf16<__bf16, true>(g, d_src, wpk, d_dst, C_contract, C_produce, zero_row, st)
+                                  : launch_leaf16<__bf16, false>(g, d_src, wpk, d_dst, C_contract, C_produce, zero_row, st);
         else
-            rc = out_dt == FX_F32 ? launch_leaf16<_Float16, true>(g, d_feat, wpk, d_out, C_in, C_out, zero_row, st16)
-                                  : launch_leaf16<_Float16, false>(g, d_feat, wpk, d_out, C_in, C_out, zero_row, st16);
-        dev_free(wpk, st16);
+            rc = out_dt == FX_F32 ? launch_leaf16<_Float16, true>(g, d_src, wpk, d_dst, C_contract, C_produce, zero_row, st)
+                                  : launch_leaf16<_Float16, false>(g, d_src, wpk, d_dst, C_contract, C_produce, zero_row, st);
+        dev_free(wpk, st);
         return rc;
     }
-    if (C_in % 4 || C_in > 16 || C_out % 16 || C_out > 32) {
-        set_error("fx_sparse_conv_leaf_fwd: needs C_in in {4,8,12,16} and C_out in {16,32} (got %d -> %d); "
-                  "use fx_build_kernel_map + fx_sparse_conv_fwd", C_in, C_out);
+    if (C_contract % 4 || C_contract > 16 || C_produce % 16 || C_produce > 32) {
+        set_error("%s: fp32 needs 4, 8, 12 or 16 contracted and 16 or 32 produced channels (got %d -> %d); "
+                  "use the kernel-map path", who, C_contract, C_produce);
         return FX_EUNSUPPORTED;
     }
     if (g->hdr.n_voxels == 0) return FX_OK;
-    hipStream_t st = (hipStream_t)stream;
-    const float* feat = (const float*)d_feat;
+    const float* src = (const float*)d_src;
     const float* w = (const float*)d_w;
-    float* out = (float*)d_out;
-#define FX_LEAF(JV)                                                                          \
-    case JV:                                                                                 \
-        return C_out == 16 ? launch_leaf<JV, 1>(g, feat, w, out, st) : launch_leaf<JV, 2>(g, feat, w, out, st)
-    switch (C_in / 4) {
+    float* dst = (float*)d_dst;
+    const int mirrored = mode == kWeightsMirrored;
+#define FX_LEAF(JV)                                                                                  \
+    case JV:                                                                                         \
+        return C_produce == 16 ? launch_leaf<JV, 1>(g, src, w, dst, mirrored, st) : launch_leaf<JV, 2>(g, src, w, dst, mirrored, st)
+    switch (C_contract / 4) {
         FX_LEAF(1);
         FX_LEAF(2);
         FX_LEAF(3);
@@ -687,4 +695,16 @@ extern "C" fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_fea
     }
 #undef FX_LEAF
     return FX_EINVAL;
+}
+
+extern "C" fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_feat, fx_dtype dt, const void* d_w,
+                                             int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream) {
+    return leaf_apply("fx_sparse_conv_leaf_fwd", g, d_feat, dt, d_w, C_in, C_out, d_out, out_dt, (hipStream_t)stream,
+                      kWeightsForward);
+}
+
+extern "C" fx_status fx_sparse_conv_leaf_bwd_data(const fx_grid* g, const void* d_gout, fx_dtype dt, const void* d_w,
+                                                  int32_t C_in, int32_t C_out, void* d_gin, fx_dtype out_dt, void* stream) {
+    return leaf_apply("fx_sparse_conv_leaf_bwd_data", g, d_gout, dt, d_w, C_out, C_in, d_gin, out_dt, (hipStream_t)stream,
+                      kWeightsMirrored);
 }

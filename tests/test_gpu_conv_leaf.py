@@ -135,3 +135,56 @@ def test_full_size_volume_sampled_rows():
         ref = O.conv(og, og, 3, 1, f64, w64, s0, s0 + 300)
         H.conv_tolerance_check(y[s0:s0 + 300], ref[s0:s0 + 300], "f32", 27, w.c_in)
     assert np.isfinite(y).all()
+
+
+# ---------------------------------------------------------------- input gradient without a kernel map
+def _leaf_bwd_vs_oracle(grids, c_in, c_out, seed, dtype, out_f32=False):
+    ijk, jo = G.make_jagged([G.shuffle_and_duplicate(g, seed + b, 0.01) for b, g in enumerate(grids)])
+    g, og = H.both_grids(ijk, jo)
+    _, wt = G.features_and_weights(seed, og.num_voxels, c_in, c_out, 27, dtype)
+    gy = G.round_to_dtype(np.random.default_rng(seed + 99).standard_normal((og.num_voxels, c_out)).astype(np.float32), dtype)
+    gin = fx.sparse_conv_leaf_bwd_data(g, H.to_device_storage(gy, dtype), H.to_device_storage(wt, dtype),
+                                       out_dtype=torch.float32 if out_f32 else None)
+    ref = O.conv_bwd_data(og, og, 3, 1, gy, wt)
+    assert gin.shape == ref.shape
+    # the forward bars with the contracted channel count (here C_out); the rows of the weights W[kappa] . gout
+    # have the scale of gout times sqrt(C_out / (27 C_in)) per tap, which the relative bar absorbs
+    H.conv_tolerance_check(gin.float().cpu().numpy(), ref, dtype, 27, c_out)
+    return g, gy, wt, gin
+
+
+@pytest.mark.parametrize("c_in,c_out", [(16, 8), (32, 16), (16, 4), (32, 12)])
+def test_input_gradient_fp32(c_in, c_out):
+    w = G.workload("volume_small")
+    _leaf_bwd_vs_oracle(w.grids, c_in, c_out, w.feat_seed, "f32")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("c_in,c_out,out_f32", [(64, 32, False), (64, 64, True), (128, 64, False)])
+def test_input_gradient_sixteen_bit(dtype, c_in, c_out, out_f32):
+    w = G.workload("volume_small")
+    _leaf_bwd_vs_oracle(w.grids, c_in, c_out, w.feat_seed, dtype, out_f32)
+
+
+def test_input_gradient_on_sparse_grid_and_against_the_kernel_map_path():
+    w = G.workload("lidar_small")
+    g, gy, wt, gin = _leaf_bwd_vs_oracle(w.grids, 64, 64, w.feat_seed, "bf16")
+    km = fx.build_kernel_map(g, 3, 1)
+    gin2 = fx.sparse_conv_bwd_data(km, H.to_device_storage(gy, "bf16"), H.to_device_storage(wt, "bf16"))
+    d = (gin.float() - gin2.float()).norm(dim=1) / gin2.float().norm(dim=1).clamp_min(1e-3)
+    assert float(d.max()) <= 2e-2
+
+
+def test_input_gradient_is_the_adjoint_of_the_forward():
+    # <leaf_fwd(x; W), g> = <x, leaf_bwd_data(g; W)> in fp32 (both sides computed by the library)
+    w = G.workload("volume_small")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    n = og.num_voxels
+    gen = torch.Generator(device="cpu").manual_seed(5)
+    x = torch.randn((n, 16), generator=gen).cuda()       # 16 -> 16: a shape both directions support
+    gy = torch.randn((n, 16), generator=gen).cuda()
+    wt = (torch.randn((27, 16, 16), generator=gen) * 0.1).cuda()
+    lhs = (fx.sparse_conv_leaf_fwd(g, x, wt).double() * gy.double()).sum()
+    rhs = (x.double() * fx.sparse_conv_leaf_bwd_data(g, gy, wt).double()).sum()
+    assert abs(float(lhs - rhs)) <= 1e-4 * abs(float(lhs)) + 1e-3
