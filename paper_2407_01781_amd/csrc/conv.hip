@@ -1107,18 +1107,25 @@ fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, 
         return FX_OK;
     }
     FX_TRY(kmap_ensure_dense(const_cast<fx_kmap*>(km), st));
+    return conv_scalar_on_table(km->d_nbmap, km->n_out, km->K3, d_feat, in_dt, d_w, C_in, C_out, d_out, out_dt, st, mode);
+}
+
+fx_status fx::conv_scalar_on_table(const int32_t* d_table, int64_t n_rows, int K3, const void* d_feat, fx_dtype in_dt,
+                                   const void* d_w, int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st,
+                                   int mode) {
+    const bool out_f32 = (out_dt == FX_F32);
     const bool four = C_in % 4 == 0 && C_out % 4 == 0;
-    const int64_t total = km->n_out * (four ? C_out / 4 : C_out);
-    const unsigned nb = (unsigned)std::min<int64_t>((total + 255) / 256, 1 << 20);
+    const int64_t total = n_rows * (four ? C_out / 4 : C_out);
+    const unsigned nb = (unsigned)std::max<int64_t>(1, std::min<int64_t>((total + 255) / 256, 1 << 20));
 #define FX_SCALAR(DT)                                                                                            \
     do {                                                                                                         \
-        if (four && out_f32) k_conv_scalar4<DT, true><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, \
+        if (four && out_f32) k_conv_scalar4<DT, true><<<nb, 256, 0, st>>>(d_table, n_rows, K3, d_feat,           \
                                                                           d_w, C_in, C_out, d_out, mode);        \
-        else if (four) k_conv_scalar4<DT, false><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_w, \
+        else if (four) k_conv_scalar4<DT, false><<<nb, 256, 0, st>>>(d_table, n_rows, K3, d_feat, d_w,           \
                                                                      C_in, C_out, d_out, mode);                  \
-        else if (out_f32) k_conv_scalar<DT, true><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_w, \
+        else if (out_f32) k_conv_scalar<DT, true><<<nb, 256, 0, st>>>(d_table, n_rows, K3, d_feat, d_w,          \
                                                                       C_in, C_out, d_out, mode);                 \
-        else k_conv_scalar<DT, false><<<nb, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_w, C_in,     \
+        else k_conv_scalar<DT, false><<<nb, 256, 0, st>>>(d_table, n_rows, K3, d_feat, d_w, C_in,                \
                                                           C_out, d_out, mode);                                   \
     } while (0)
     ProfScope ps(kProfConvScalar, st);

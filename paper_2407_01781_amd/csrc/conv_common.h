@@ -140,6 +140,12 @@ void launch_pack_weights(const void* d_w, void* wp, int K3, int C_in, int C_out,
 // = sum over kappa of d_feat[map(o,kappa),:] . Wmode[kappa], C_in channels in, C_out channels out.
 fx_status conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w, int32_t C_in,
                      int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st, int mode);
+// The same sum through a dense table [n_rows, K3] of source rows (-1: none), one thread per output element
+// (or per four): out[r,:] = sum over kappa with table[r][kappa] >= 0 of src[table[r][kappa],:] . W'[kappa], W' read
+// from the caller's weights as `mode` says.  Serves maps without a tiled form and the inverse table.
+fx_status conv_scalar_on_table(const int32_t* d_table, int64_t n_rows, int K3, const void* d_feat, fx_dtype in_dt,
+                               const void* d_w, int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st,
+                               int mode);
 
 // dst[map(o,kappa), :] for every pair of a K = stride map; see conv_bwd.hip
 fx_status strided_pair_product(const fx_kmap* km, const void* d_src, fx_dtype dt, const void* d_w, int32_t C_contract,

@@ -761,6 +761,36 @@ fx_status kmap_ensure_dense(fx_kmap* km, hipStream_t st) {
     return FX_OK;
 }
 
+__global__ void k_invert_nbmap(const int32_t* __restrict__ nbmap, int64_t n_out, int K3, int32_t* __restrict__ inv) {
+    const int64_t total = n_out * K3;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t in = nbmap[e];
+        if (in >= 0) inv[(int64_t)in * K3 + (e % K3)] = (int32_t)(e / K3);
+    }
+}
+
+fx_status kmap_ensure_inverse_dense(fx_kmap* km, hipStream_t st) {
+    if (km->d_inv_nbmap || km->n_in == 0) return FX_OK;
+    FX_TRY(kmap_ensure_dense(km, st));
+    void* p = nullptr;
+    const int64_t n = km->n_in * km->K3;
+    FX_TRY(dev_alloc(&p, sizeof(int32_t) * (size_t)n, st));
+    k_fill_i32<<<(unsigned)std::min<int64_t>((n + 255) / 256, 1 << 16), 256, 0, st>>>((int32_t*)p, n, -1);
+    if (km->n_out > 0) {
+        const int64_t total = km->n_out * km->K3;
+        k_invert_nbmap<<<(unsigned)std::min<int64_t>((total + 255) / 256, 1 << 16), 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3,
+                                                                                                  (int32_t*)p);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        dev_free(p, st);
+        set_error("inverse kernel-map build failed: %s", hipGetErrorString(e));
+        return FX_EDEVICE;
+    }
+    km->d_inv_nbmap = (int32_t*)p;
+    return FX_OK;
+}
+
 }  // namespace fx
 
 using namespace fx;
@@ -776,6 +806,7 @@ extern "C" void fx_kmap_destroy(fx_kmap* km) {
     if (km->refs.fetch_sub(1) != 1) return;
     if (km->d_alloc) dev_free(km->d_alloc, km->stream);
     if (km->d_nbmap) dev_free(km->d_nbmap, km->stream);
+    if (km->d_inv_nbmap) dev_free(km->d_inv_nbmap, km->stream);
     if (km->gin) fx_grid_destroy(km->gin);
     if (km->gout) fx_grid_destroy(km->gout);
     free(km->h_pairs);

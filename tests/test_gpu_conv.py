@@ -135,16 +135,21 @@ def test_3x3x3_stride_2(dtype, c_in, c_out):
     d_x, d_w = H.to_device_storage(feat, dtype), H.to_device_storage(wt, dtype)
     y = fx.sparse_conv_fwd(km, d_x, d_w)
     H.conv_tolerance_check(y.float().cpu().numpy(), O.conv(og, ogc, 3, 2, feat, wt), dtype, 27, c_in)
-    # weight gradient on the same map; the input gradient of this map needs a scatter-add and is not provided
+    # weight gradient on the same map
     gy = G.round_to_dtype(np.random.default_rng(72).standard_normal((ogc.num_voxels, c_out)).astype(np.float32), dtype)
     gw = fx.sparse_conv_bwd_weight(km, d_x, H.to_device_storage(gy, dtype), out_dtype=torch.float32).cpu().numpy()
     ref = O.conv_bwd_weight(og, ogc, 3, 2, feat, gy)
     num = np.sqrt(((gw - ref) ** 2).sum(axis=(1, 2)))
     den = np.maximum(np.sqrt((ref ** 2).sum(axis=(1, 2))), 1e-3 * np.sqrt(c_in * c_out))
     assert (num / den).max() <= (1e-4 if dtype == "f32" else 2e-3)
-    with pytest.raises(fx.FxError) as e:
-        fx.sparse_conv_bwd_data(km, H.to_device_storage(gy, dtype), d_w)
-    assert e.value.status == -2
+    # input gradient and transposed convolution: an input is shared by up to 8 outputs, both gather
+    # through the inverse table of the map
+    gx = fx.sparse_conv_bwd_data(km, H.to_device_storage(gy, dtype), d_w).float().cpu().numpy()
+    H.conv_tolerance_check(gx, O.conv_bwd_data(og, ogc, 3, 2, gy, wt), dtype, 27, c_out)
+    _, wt_t = G.features_and_weights(73, 1, c_out, c_in, 27, dtype)          # [27, c_out, c_in]: coarse c_out -> fine c_in
+    up = fx.sparse_conv_transpose_fwd(km, H.to_device_storage(gy, dtype), H.to_device_storage(wt_t, dtype))
+    assert up.shape == (og.num_voxels, c_in)
+    H.conv_tolerance_check(up.float().cpu().numpy(), O.conv_transpose(og, ogc, 3, 2, gy, wt_t), dtype, 27, c_out)
 
 
 def test_identity_tap_is_bit_exact_in_bf16():

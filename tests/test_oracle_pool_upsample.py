@@ -21,27 +21,31 @@ def _densify(coords, feat, lo, shape):
     return d
 
 
+@pytest.mark.parametrize("K", [2, 3])
 @pytest.mark.parametrize("c_in,c_out", [(3, 5), (4, 2)])
-def test_transposed_convolution_matches_dense_conv_transpose3d(c_in, c_out):
+def test_transposed_convolution_matches_dense_conv_transpose3d(c_in, c_out, K):
     pts = _cloud(201, 500, -8, 9)
     fine = O.OracleGrid(pts, np.array([[0, pts.shape[0]]]))
     coarse = fine.coarsen2()
     rng = np.random.default_rng(202)
     z = rng.standard_normal((coarse.num_voxels, c_in))
-    w = rng.standard_normal((8, c_in, c_out))
+    w = rng.standard_normal((K ** 3, c_in, c_out))
     cc, fc = coarse.ijk()[0], fine.ijk()[0]
     lo = cc.min(0)
     shape = cc.max(0) - lo + 1
     dense = torch.from_numpy(_densify(cc, z, lo, shape))[None]
     # torch's weight layout for conv_transpose3d is [C_in, C_out, kD, kH, kW]
-    kern = torch.from_numpy(w.reshape(2, 2, 2, c_in, c_out)).permute(3, 4, 0, 1, 2).contiguous()
-    y = torch.nn.functional.conv_transpose3d(dense, kern, stride=2)[0].numpy()      # fine box starting at 2*lo
+    kern = torch.from_numpy(w.reshape(K, K, K, c_in, c_out)).permute(3, 4, 0, 1, 2).contiguous()
+    # fine box starting at 2*lo; for K = 3 the offsets are -1, 0, 1: padding 1 shifts the taps, output_padding 1
+    # keeps the last fine row of the box
+    y = torch.nn.functional.conv_transpose3d(dense, kern, stride=2, padding=K // 2 if K == 3 else 0,
+                                             output_padding=1 if K == 3 else 0)[0].numpy()
     q = fc - 2 * lo
     ref = y[:, q[:, 0], q[:, 1], q[:, 2]].T
-    assert np.allclose(O.conv_transpose(fine, coarse, 2, 2, z, w), ref, rtol=1e-12, atol=1e-12)
+    assert np.allclose(O.conv_transpose(fine, coarse, K, 2, z, w), ref, rtol=1e-12, atol=1e-12)
 
 
-@pytest.mark.parametrize("K,s", [(2, 2), (3, 1)])
+@pytest.mark.parametrize("K,s", [(2, 2), (3, 1), (3, 2)])
 def test_transposed_convolution_is_the_adjoint_of_the_forward_oracle(K, s):
     """<conv(x; W), z> = <x, conv_transpose(z; W^T)> with W^T[kappa] = W[kappa] transposed."""
     w_ = G.workload("sheets_small")
