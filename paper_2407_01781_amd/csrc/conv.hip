@@ -1062,6 +1062,21 @@ fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, 
                          int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st, int mode) {
     const bool out_f32 = (out_dt == FX_F32);
     const char* force = getenv("FVDB_HOTPATH_FORCE_SCALAR");
+    // Locally dense grids (Sec. 3.5 scenarios 1-2): on a 3x3x3 stride-1 map the leaf-window kernels compute the same
+    // sum from the grid alone and are faster once the leaves are full enough -- the tiles of such a map need more
+    // rows than the tile kernel's LDS holds -- and, at fp32 depths that the tile kernel does not take, almost
+    // everywhere.  FVDB_HOTPATH_LEAF_DISPATCH=0 keeps the kernel-map kernels, =1 takes the leaf kernels whenever
+    // they serve the shape.
+    if (km->K == 3 && km->stride == 1 && (mode == kWeightsForward || mode == kWeightsMirrored) &&
+        leaf_shape_supported(in_dt, C_in, C_out) && !(force && force[0] == '1')) {
+        const char* ld = getenv("FVDB_HOTPATH_LEAF_DISPATCH");
+        const double occupancy = (double)km->n_in / (512.0 * (double)std::max<int64_t>(1, km->gin->hdr.n_leaf));
+        const bool scalar_otherwise = in_dt == FX_F32 && C_in % 16 != 0;
+        const bool take = ld ? ld[0] == '1' : occupancy >= (scalar_otherwise ? 0.08 : 0.40);
+        if (take && !(ld && ld[0] == '0'))
+            return leaf_apply("sparse convolution (leaf-window kernels)", km->gin, d_feat, in_dt, d_w, C_in, C_out, d_out, out_dt,
+                              st, mode);
+    }
     const int esize = in_dt == FX_F32 ? 4 : 2;
     // The tile kernel takes input rows in 64-byte chunks (32 channels of a 16-bit type, 16 of fp32) and
     // pads the produced channels to 64 with zero weights; the gather kernel for strided maps needs whole

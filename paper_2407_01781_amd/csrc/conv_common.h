@@ -140,6 +140,16 @@ void launch_pack_weights(const void* d_w, void* wp, int K3, int C_in, int C_out,
 // = sum over kappa of d_feat[map(o,kappa),:] . Wmode[kappa], C_in channels in, C_out channels out.
 fx_status conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w, int32_t C_in,
                      int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st, int mode);
+// The 3x3x3 stride-1 convolution of `src` [N, C_contract] into `dst` [N, C_produce] straight from the grid, leaf by
+// leaf, without a kernel map (Sec. 3.5 scenario 1); `mode` is kWeightsForward or kWeightsMirrored (input gradient).
+// FX_EUNSUPPORTED for shapes its kernels do not serve.  leaf_shape_supported says so without setting an error.
+fx_status leaf_apply(const char* who, const fx_grid* g, const void* d_src, fx_dtype dt, const void* d_w, int32_t C_contract,
+                     int32_t C_produce, void* d_dst, fx_dtype out_dt, hipStream_t st, int mode);
+inline bool leaf_shape_supported(fx_dtype dt, int C_contract, int C_produce) {
+    if (dt == FX_F32) return C_contract % 4 == 0 && C_contract <= 16 && (C_produce == 16 || C_produce == 32);
+    return C_contract % 32 == 0 && C_produce % 64 == 0;
+}
+
 // The same sum through a dense table [n_rows, K3] of source rows (-1: none), one thread per output element
 // (or per four): out[r,:] = sum over kappa with table[r][kappa] >= 0 of src[table[r][kappa],:] . W'[kappa], W' read
 // from the caller's weights as `mode` says.  Serves maps without a tiled form and the inverse table.

@@ -634,7 +634,7 @@ extern "C" int fx_debug_leaf_timing(unsigned long long* h_out, size_t bytes, int
 
 // The leaf-window convolution of `src` [N, C_contract] into `dst` [N, C_produce]; `mode` says how the
 // caller's weights are read (kWeightsForward, or kWeightsMirrored for the input gradient).
-static fx_status leaf_apply(const char* who, const fx_grid* g, const void* d_src, fx_dtype dt, const void* d_w,
+fx_status fx::leaf_apply(const char* who, const fx_grid* g, const void* d_src, fx_dtype dt, const void* d_w,
                             int32_t C_contract, int32_t C_produce, void* d_dst, fx_dtype out_dt, hipStream_t st, int mode) {
     if (!g || !d_w || C_contract < 1 || C_produce < 1 || (g->hdr.n_voxels > 0 && (!d_src || !d_dst))) {
         set_error("%s: null pointer or non-positive channel count", who);

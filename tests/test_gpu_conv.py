@@ -194,9 +194,10 @@ def test_scalar_and_mfma_paths_agree_with_oracle_on_empty_and_tiny_grids():
     H.conv_tolerance_check(y.float().cpu().numpy(), O.conv(og, og, 3, 1, feat, wt), "bf16", 27, 64)
 
 
-def test_dense_block_uses_rows_beyond_the_lds_budget():
+def test_dense_block_uses_rows_beyond_the_lds_budget(monkeypatch):
     # a dense 24^3 block: every tile is one full leaf whose 10^3 footprint has more distinct
     # input rows than the convolution stages in LDS, so part of them is read from global memory
+    monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", "0")      # this test is about the tile kernel's general variant
     a = np.arange(24, dtype=np.int32)
     pts = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3)
     g, og = H.both_grids(pts, np.array([[0, pts.shape[0]]]))
@@ -206,11 +207,16 @@ def test_dense_block_uses_rows_beyond_the_lds_budget():
     H.conv_tolerance_check(y.float().cpu().numpy(), O.conv(og, og, 3, 1, feat, wt), "bf16", 27, 64)
 
 
-@pytest.mark.parametrize("name", ["lidar1m", "indoor4", "lidar1m_down", "sheets4", "volume1m_c64", "dense96"])
-def test_full_size_configs_sampled_rows(name):
+@pytest.mark.parametrize("name", ["lidar1m", "indoor4", "lidar1m_down", "sheets4", "volume1m_c64", "dense96",
+                                  "volume1m_c64:tiles", "dense96:tiles"])
+def test_full_size_configs_sampled_rows(name, monkeypatch):
     """Configs 3, 2, 4 and 5 at full size in the benchmark's launch configuration; the oracle
     computes a sample of output rows one by one (a few thousand rows spread over the grid, the
-    first and the last rows included)."""
+    first and the last rows included).  The volumetric and the dense grid run twice: through the
+    leaf-window kernels, which the convolution picks for them, and (":tiles") through the tile kernel."""
+    if name.endswith(":tiles"):
+        monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", "0")
+        name = name[:-6]
     w = G.workload(name)
     ijk, jo = w.jagged_ijk()
     g, og = H.both_grids(ijk, jo)

@@ -120,7 +120,8 @@ def test_empty_and_tiny_grids():
     _wgrad_check(gw, O.conv_bwd_weight(og, og, 3, 1, feat, gy), 2e-3)
 
 
-def test_dense_block_with_rows_beyond_the_lds_budget():
+def test_dense_block_with_rows_beyond_the_lds_budget(monkeypatch):
+    monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", "0")      # this test is about the tile kernel's general variant
     a = np.arange(24, dtype=np.int32)
     pts = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3)
     g, og = H.both_grids(pts, np.array([[0, pts.shape[0]]]))

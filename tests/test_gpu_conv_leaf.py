@@ -100,7 +100,8 @@ def test_empty_grid_and_empty_batch_member():
     _leaf_vs_oracle([w.grids[0], np.zeros((0, 3), np.int32), w.grids[1]], 8, 16, 73)
 
 
-def test_agrees_with_the_kernel_map_path():
+def test_agrees_with_the_kernel_map_path(monkeypatch):
+    monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", "0")      # keep fx.sparse_conv_fwd on the kernel-map kernels
     w = G.workload("volume_small")
     g, feat, wt, y = _leaf_vs_oracle(w.grids, 8, 16, w.feat_seed)
     km = fx.build_kernel_map(g, 3, 1)
@@ -166,7 +167,8 @@ def test_input_gradient_sixteen_bit(dtype, c_in, c_out, out_f32):
     _leaf_bwd_vs_oracle(w.grids, c_in, c_out, w.feat_seed, dtype, out_f32)
 
 
-def test_input_gradient_on_sparse_grid_and_against_the_kernel_map_path():
+def test_input_gradient_on_sparse_grid_and_against_the_kernel_map_path(monkeypatch):
+    monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", "0")
     w = G.workload("lidar_small")
     g, gy, wt, gin = _leaf_bwd_vs_oracle(w.grids, 64, 64, w.feat_seed, "bf16")
     km = fx.build_kernel_map(g, 3, 1)
@@ -188,3 +190,46 @@ def test_input_gradient_is_the_adjoint_of_the_forward():
     lhs = (fx.sparse_conv_leaf_fwd(g, x, wt).double() * gy.double()).sum()
     rhs = (x.double() * fx.sparse_conv_leaf_bwd_data(g, gy, wt).double()).sum()
     assert abs(float(lhs - rhs)) <= 1e-4 * abs(float(lhs)) + 1e-3
+
+
+# ---------------------------------------------------------------- dispatch from the kernel-map entry points
+@pytest.mark.parametrize("switch,expect_leaf", [(None, True), ("0", False), ("1", True)])
+def test_kernel_map_entry_points_take_the_leaf_kernels_on_dense_grids(switch, expect_leaf, monkeypatch):
+    # a dense block: by default fx.sparse_conv_fwd / bwd_data on its (3,1) map run the leaf-window kernels; the
+    # switch keeps the tile kernels.  Both must meet the oracle; which kernel ran is read from the profile slots.
+    if switch is None:
+        monkeypatch.delenv("FVDB_HOTPATH_LEAF_DISPATCH", raising=False)
+    else:
+        monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", switch)
+    a = np.arange(-12, 12, dtype=np.int32)
+    blk = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3)
+    g, og = H.both_grids(blk, np.array([[0, blk.shape[0]]]))
+    km = fx.build_kernel_map(g, 3, 1)
+    feat, wt = G.features_and_weights(81, og.num_voxels, 64, 64, 27, "bf16")
+    gy = G.round_to_dtype(np.random.default_rng(82).standard_normal((og.num_voxels, 64)).astype(np.float32), "bf16")
+    fx.profile_enable(True)
+    fx.profile_reset()
+    y = fx.sparse_conv_fwd(km, H.to_device_storage(feat, "bf16"), H.to_device_storage(wt, "bf16"))
+    gx = fx.sparse_conv_bwd_data(km, H.to_device_storage(gy, "bf16"), H.to_device_storage(wt, "bf16"))
+    torch.cuda.synchronize()
+    slots = fx.profile_read()
+    fx.profile_enable(False)
+    assert ("k_conv_leaf" in slots) == expect_leaf and ("k_conv_mfma" in slots) == (not expect_leaf)
+    H.conv_tolerance_check(y.float().cpu().numpy(), O.conv(og, og, 3, 1, feat, wt), "bf16", 27, 64)
+    H.conv_tolerance_check(gx.float().cpu().numpy(), O.conv_bwd_data(og, og, 3, 1, gy, wt), "bf16", 27, 64)
+
+
+def test_sparse_grids_stay_on_the_kernel_map_kernels(monkeypatch):
+    monkeypatch.delenv("FVDB_HOTPATH_LEAF_DISPATCH", raising=False)
+    w = G.workload("lidar_small")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 3, 1)
+    feat, wt = w.feats_weights()
+    fx.profile_enable(True)
+    fx.profile_reset()
+    fx.sparse_conv_fwd(km, H.to_device_storage(feat, w.dtype), H.to_device_storage(wt, w.dtype))
+    torch.cuda.synchronize()
+    slots = fx.profile_read()
+    fx.profile_enable(False)
+    assert "k_conv_mfma" in slots and "k_conv_leaf" not in slots
