@@ -32,6 +32,7 @@ WORKLOAD_DESC = {
     "lidar1m": "config 3: LiDAR-like 2048x2048x64 grid (~1M voxels), 3x3x3 submanifold, 64->64 bf16",
     "lidar1m_down": "config 4: config-3 grid, 2x2x2 stride 2, 64->128 bf16 (coarse grid + map + conv)",
     "sheets4": "config 5: 4 random-walk sheet grids in 128^3, 3x3x3 submanifold, 256->256 bf16",
+    "lidar1m_down3": "config-3 grid, 3x3x3 stride 2, 64->128 bf16 (coarse grid + map + conv)",
     "volume1m": "volumetric class: solid balls and thick shells in 224^3 (~1M voxels, leaf occupancy 53 %), "
                 "3x3x3 submanifold, 8->16 fp32",
     "volume1m_c64": "volumetric class: the volume1m grid, 3x3x3 submanifold, 64->64 bf16",

@@ -213,8 +213,8 @@ fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, fx_dtype in_
  * bwd_data on a stride-1 map is the forward kernel run on the same map with the offsets
  * mirrored and W[kappa] transposed (the map of a submanifold convolution is symmetric); on a
  * K = stride map every input has exactly one pair and its row is written once; on the 3x3x3 stride-2
- * map an input is shared by up to 8 outputs and the sum is gathered per input through the inverse table
- * of the map (built on first use, 4 * 27 bytes per input; scalar fp32 FMA kernel, no atomics, fixed order).
+ * map an input is shared by up to 8 outputs and the sum is gathered per input through the inverse map
+ * (a tiled map of its own, built on the first such call and kept with km; no atomics, fixed order).
  * MFMA paths: FX_F16 / FX_BF16 with C_in % 64 == 0 and C_out % 64 == 0 (bwd_data: C_in % 64 == 0
  * and C_out % 32 == 0; bwd_weight: C_in % 32 == 0 and C_out % 64 == 0) on tiled maps; everything
  * else takes scalar kernels.  In the MFMA weight-gradient kernel operands are transposed by a
@@ -238,7 +238,7 @@ fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_feat, const
  *        d_feat [N_out, C_in] lives on g_out, d_out [N_in, C_out] on g_in, d_w [K^3, C_in, C_out];
  *        supported maps: K = stride (one pair per input, every row of d_out is written), stride 1
  *        (symmetric map: the forward kernels over the mirrored offsets) and 3x3x3 stride 2 (gathered per
- *        input through the inverse table of the map, scalar kernel).  Types, accumulation and
+ *        input through the inverse map, built on first use).  Types, accumulation and
  *        rounding as fx_sparse_conv_fwd; MFMA path for K = stride: FX_F16 / FX_BF16, C_in % 32 == 0,
  *        C_out % 64 == 0.
  *   fx_pool2       km must be a (2,2) map.  out[o,c] = max (FX_POOL_MAX) or mean (FX_POOL_AVG) over the

@@ -757,11 +757,11 @@ extern "C" fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_go
         return conv_apply(km, d_gout, dt, d_w, C_out, C_in, d_gin, out_dt, st, kWeightsMirrored);
     }
     if (km->K != km->stride) {
-        // 3x3x3 stride 2: an input is shared by up to 8 outputs.  Gather through the inverse table: gin[i,:] =
-        // sum over kappa with inv(i, kappa) = o of W[kappa] . gout[o,:], the scalar kernel with W[kappa] transposed
-        FX_TRY(kmap_ensure_inverse_dense(const_cast<fx_kmap*>(km), st));
-        return conv_scalar_on_table(km->d_inv_nbmap, km->n_in, km->K3, d_gout, dt, d_w, C_out, C_in, d_gin, out_dt, st,
-                                    kWeightsTransposed);
+        // 3x3x3 stride 2: an input is shared by up to 8 outputs.  Gather per input through the inverse map
+        // (a tiled map of its own, built on first use): gin[i,:] = sum over kappa with inv(i, kappa) = o of
+        // W[kappa] . gout[o,:], i.e. the forward kernels of strided maps with W[kappa] transposed
+        FX_TRY(kmap_ensure_inverse(const_cast<fx_kmap*>(km), st));
+        return conv_apply(km->inverse, d_gout, dt, d_w, C_out, C_in, d_gin, out_dt, st, kWeightsTransposed);
     }
     return strided_pair_product(km, d_gout, dt, d_w, C_out, C_in, d_gin, out_dt, st, kWeightsTransposed);
 }

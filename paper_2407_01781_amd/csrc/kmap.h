@@ -86,7 +86,8 @@ struct fx_kmap {
     int32_t K = 0, stride = 0, K3 = 0;
     int64_t n_in = 0, n_out = 0;
     int32_t* d_nbmap = nullptr;             // dense [n_out, K3]; only when the map is not tiled
-    int32_t* d_inv_nbmap = nullptr;         // dense [n_in, K3]: output whose offset kappa lands on the input (-1: none); built on demand
+    fx_kmap* inverse = nullptr;             // 3x3x3 stride 2: the inverse as a tiled map (produced rows = this map's inputs); built on demand
+    bool is_inverse = false;
     // tiled form
     int64_t n_tiles = 0;
     fx::TileHeader* d_tile_hdr = nullptr;   // [n_tiles]
@@ -106,10 +107,9 @@ struct fx_kmap {
 namespace fx {
 // dense [n_out, K3] table for the scalar convolution path, built on first use (not thread-safe)
 fx_status kmap_ensure_dense(fx_kmap* km, hipStream_t st);
-// dense inverse table [n_in, K3] (inv[i][kappa] = o with map(o, kappa) = i, else -1; unique because offset kappa
-// of one output names one coordinate), built on first use (not thread-safe): the input gradient and the
-// transposed convolution of maps whose inputs are shared by several outputs gather through it
-fx_status kmap_ensure_inverse_dense(fx_kmap* km, hipStream_t st);
+// the inverse of a 3x3x3 stride-2 map in tiled form (km->inverse), built on first use (not thread-safe)
+fx_status kmap_ensure_inverse(fx_kmap* km, hipStream_t st);
+fx_status build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool inverse, hipStream_t st, fx_kmap** out);
 // host copies of the map's statistics (pairs per offset, tiling figures); synchronises the build stream once
 fx_status kmap_fetch_stats(fx_kmap* km);
 }

@@ -89,7 +89,11 @@ __device__ __forceinline__ int lookup_entry(const NbLeafLds& lds, int oi, int oj
 // descents run at full occupancy here instead of inside the latency-bound tile builder.
 // The thread of slot 0 also notes, for every tile of kTileT consecutive outputs that starts inside
 // its leaf, that the tile's first voxel lies in this leaf.
-template <int K>
+// INV: the table of the INVERSE of a 3x3x3 stride-2 map.  The "outputs" are then the fine voxels p and their
+// "neighbours" the coarse voxels (p - delta) / 2 for the offsets delta in {-1,0,1}^3 with p - delta even on
+// every axis (exactly the pairs (coarse o, offset delta) of the forward map with 2 o + delta = p); tin is
+// the coarse grid.  A fine leaf at origin 8t touches coarse coordinates 4t-1 .. 4t+4: two leaves per axis.
+template <int K, bool INV = false>
 __global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int64_t n_out, int32_t* __restrict__ nbr,
                                  int32_t* __restrict__ tile_first_leaf, unsigned long long* __restrict__ stats) {
     constexpr int D0 = delta_min(K);
@@ -104,9 +108,11 @@ __global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int64_
         for (int64_t t = (begin + kTileT - 1) / kTileT; t * kTileT < end; ++t) tile_first_leaf[t] = f;
     }
     const int oi = lf->origin[0], oj = lf->origin[1], ok = lf->origin[2];
-    const int bi = (stride * oi + D0) >> 3, bj = (stride * oj + D0) >> 3, bk = (stride * ok + D0) >> 3;
-    const int hi_i = (stride * (oi + 7) + D0 + K - 1) >> 3, hi_j = (stride * (oj + 7) + D0 + K - 1) >> 3,
-              hi_k = (stride * (ok + 7) + D0 + K - 1) >> 3;
+    const int bi = INV ? ((oi - 1) >> 1) >> 3 : (stride * oi + D0) >> 3, bj = INV ? ((oj - 1) >> 1) >> 3 : (stride * oj + D0) >> 3,
+              bk = INV ? ((ok - 1) >> 1) >> 3 : (stride * ok + D0) >> 3;
+    const int hi_i = INV ? ((oi + 8) >> 1) >> 3 : (stride * (oi + 7) + D0 + K - 1) >> 3,
+              hi_j = INV ? ((oj + 8) >> 1) >> 3 : (stride * (oj + 7) + D0 + K - 1) >> 3,
+              hi_k = INV ? ((ok + 8) >> 1) >> 3 : (stride * (ok + 7) + D0 + K - 1) >> 3;
     const int a = slot / 9, c = (slot / 3) % 3, d = slot % 3;
     int id = -1;
     if (bi + a <= hi_i && bj + c <= hi_j && bk + d <= hi_k)
@@ -315,7 +321,7 @@ __device__ __forceinline__ int select64(uint64_t m, int r) {
 // One workgroup per tile of kTileT consecutive outputs: lookups (one thread per voxel, straight
 // into LDS), mask sort, row de-duplication, block emission.  SUBM: input grid == output grid, so the
 // tile's own index range is the window; otherwise the tile is "direct".
-template <int K, bool SUBM>
+template <int K, bool SUBM, bool INV = false>
 __global__ void __launch_bounds__(kPackThreads)
 k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict__ leaf_nbr,
               const int32_t* __restrict__ tile_first_leaf, int64_t n_out, TileHeader* __restrict__ tile_hdr,
@@ -428,8 +434,11 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
             }
             const int bit = select64(lf->mask[wn], r - before);
             const int pi = lf->origin[0] + wn, pj = lf->origin[1] + (bit >> 3), pk = lf->origin[2] + (bit & 7);
-            const int bi = (stride * lf->origin[0] + D0) >> 3, bj = (stride * lf->origin[1] + D0) >> 3,
-                      bk = (stride * lf->origin[2] + D0) >> 3;
+            // INV (inverse of the 3x3x3 stride-2 map): offset (a,b,c) of fine voxel p names the coarse voxel
+            // (p - delta) / 2, delta = (a,b,c) - 1, and only when p - delta is even on every axis
+            const int bi = INV ? ((lf->origin[0] - 1) >> 1) >> 3 : (stride * lf->origin[0] + D0) >> 3,
+                      bj = INV ? ((lf->origin[1] - 1) >> 1) >> 3 : (stride * lf->origin[1] + D0) >> 3,
+                      bk = INV ? ((lf->origin[2] - 1) >> 1) >> 3 : (stride * lf->origin[2] + D0) >> 3;
             const int32_t* nbr_row = leaf_nbr + (int64_t)f * 27;
             const bool row_in_lds = lo < kLdsLeafRows;
             // kept as rolled loops: the fully unrolled form of this divergent body gave wrong entries
@@ -439,15 +448,21 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
             int kappa = 0;
 #pragma unroll 1
             for (int a = 0; a < K; ++a) {
-                const int qi = stride * pi + D0 + a;
+                const int qi_full = INV ? pi + 1 - a : stride * pi + D0 + a;
+                const bool even_i = INV ? !(qi_full & 1) : true;
+                const int qi = INV ? qi_full >> 1 : qi_full;
                 const int si = ((qi >> 3) - bi) * 9, n2 = qi & 7;
 #pragma unroll 1
                 for (int b2 = 0; b2 < K; ++b2) {
-                    const int qj = stride * pj + D0 + b2;
+                    const int qj_full = INV ? pj + 1 - b2 : stride * pj + D0 + b2;
+                    const bool even_ij = INV ? even_i && !(qj_full & 1) : true;
+                    const int qj = INV ? qj_full >> 1 : qj_full;
                     const int sij = si + ((qj >> 3) - bj) * 3, bj8 = (qj & 7) << 3;
 #pragma unroll 1
                     for (int c = 0; c < K; ++c, ++kappa) {
-                        const int qk = stride * pk + D0 + c;
+                        const int qk_full = INV ? pk + 1 - c : stride * pk + D0 + c;
+                        const bool even_ijk = INV ? even_ij && !(qk_full & 1) : true;
+                        const int qk = INV ? qk_full >> 1 : qk_full;
                         const int slot = sij + ((qk >> 3) - bk);
                         // The common case runs without a branch: a missing neighbour leaf reads the all-zero
                         // record kMaxRecs, whose mask has no bit to find.
@@ -466,7 +481,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
                         // bits below bit6, per half: all of the low half once bit6 >= 32
                         const uint32_t mlo = bit6 >= 32 ? 0xFFFFFFFFu : ((1u << bit6) - 1u);
                         const uint32_t mhi = bit6 >= 32 ? ((1u << (bit6 - 32)) - 1u) : 0u;
-                        const bool present = (((bit6 >= 32 ? whi : wlo) >> (bit6 & 31)) & 1u) != 0;
+                        const bool present = even_ijk && (((bit6 >= 32 ? whi : wlo) >> (bit6 & 31)) & 1u) != 0;
                         const int idx = base + __popc(wlo & mlo) + __popc(whi & mhi);
                         // entry encoding from here on: -1 none; -2 - id: row win_lo + id of the window;
                         // >= 0: a row outside the window, not yet entered in the halo table
@@ -734,6 +749,15 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // dense [n_out, K3] table computed by the leaf-centric lookup kernel
 static hipError_t launch_nbmap(const fx_kmap* km, int32_t* d_nbmap, hipStream_t st) {
     if (km->gout->hdr.n_leaf == 0) return hipSuccess;
+    if (km->is_inverse) {        // the lookup rule of an inverse map lives in the tile builder only: decode its tiles
+        const int64_t total = km->n_out * km->K3;
+        const unsigned nbf = (unsigned)std::min<int64_t>((total + 256 * 8 - 1) / (256 * 8), 8192);
+        k_fill_i32<<<nbf, 256, 0, st>>>(d_nbmap, total, -1);
+        k_tiles_to_dense<<<(unsigned)km->n_tiles, kTileT, 0, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,
+                                                                  km->row_stride, km->d_tile_blocks, km->block_stride,
+                                                                  km->K3, d_nbmap, nullptr);
+        return hipGetLastError();
+    }
     const unsigned nb = (unsigned)((km->gout->hdr.n_leaf + kNbWavesPerBlock - 1) / kNbWavesPerBlock);
     const TreeView tin = km->gin->view(), tout = km->gout->view();
     ProfScope ps(kProfNbmap, st);
@@ -761,36 +785,6 @@ fx_status kmap_ensure_dense(fx_kmap* km, hipStream_t st) {
     return FX_OK;
 }
 
-__global__ void k_invert_nbmap(const int32_t* __restrict__ nbmap, int64_t n_out, int K3, int32_t* __restrict__ inv) {
-    const int64_t total = n_out * K3;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
-        const int32_t in = nbmap[e];
-        if (in >= 0) inv[(int64_t)in * K3 + (e % K3)] = (int32_t)(e / K3);
-    }
-}
-
-fx_status kmap_ensure_inverse_dense(fx_kmap* km, hipStream_t st) {
-    if (km->d_inv_nbmap || km->n_in == 0) return FX_OK;
-    FX_TRY(kmap_ensure_dense(km, st));
-    void* p = nullptr;
-    const int64_t n = km->n_in * km->K3;
-    FX_TRY(dev_alloc(&p, sizeof(int32_t) * (size_t)n, st));
-    k_fill_i32<<<(unsigned)std::min<int64_t>((n + 255) / 256, 1 << 16), 256, 0, st>>>((int32_t*)p, n, -1);
-    if (km->n_out > 0) {
-        const int64_t total = km->n_out * km->K3;
-        k_invert_nbmap<<<(unsigned)std::min<int64_t>((total + 255) / 256, 1 << 16), 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3,
-                                                                                                  (int32_t*)p);
-    }
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) {
-        dev_free(p, st);
-        set_error("inverse kernel-map build failed: %s", hipGetErrorString(e));
-        return FX_EDEVICE;
-    }
-    km->d_inv_nbmap = (int32_t*)p;
-    return FX_OK;
-}
-
 }  // namespace fx
 
 using namespace fx;
@@ -806,7 +800,7 @@ extern "C" void fx_kmap_destroy(fx_kmap* km) {
     if (km->refs.fetch_sub(1) != 1) return;
     if (km->d_alloc) dev_free(km->d_alloc, km->stream);
     if (km->d_nbmap) dev_free(km->d_nbmap, km->stream);
-    if (km->d_inv_nbmap) dev_free(km->d_inv_nbmap, km->stream);
+    if (km->inverse) fx_kmap_destroy(km->inverse);
     if (km->gin) fx_grid_destroy(km->gin);
     if (km->gout) fx_grid_destroy(km->gout);
     free(km->h_pairs);
@@ -826,11 +820,21 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     FX_HT("(outside)");
     if (stride == 1) { gout = g_in; fx_grid_retain(gout); }
     else FX_TRY(fx_grid_coarsen2(g_in, stream, &gout));
+    fx_kmap* km = nullptr;
+    FX_TRY(build_map(g_in, gout, K, stride, false, st, &km));     // takes over the reference to gout
+    *g_out = gout;
+    fx_grid_retain(gout);
+    *out = km;
+    return FX_OK;
+}
 
+// The map from the voxels of `gout` (the rows that are produced) to the voxels of `g_in` (the rows that are
+// looked up).  Takes over the caller's reference to gout and retains g_in.  inverse: see k_leaf_neighbors.
+fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool inverse, hipStream_t st, fx_kmap** out) {
     fx_kmap* km = new (std::nothrow) fx_kmap();
     if (!km) { fx_grid_destroy(gout); set_error("host allocation failed"); return FX_ENOMEM; }
     km->stream = st; km->gin = g_in; fx_grid_retain(g_in); km->gout = gout;
-    km->K = K; km->stride = stride; km->K3 = K * K * K;
+    km->K = K; km->stride = stride; km->K3 = K * K * K; km->is_inverse = inverse;
     km->n_in = g_in->hdr.n_voxels; km->n_out = gout->hdr.n_voxels;
     km->h_pairs = (int64_t*)calloc((size_t)km->K3, sizeof(int64_t));
     const bool tiled = km->K3 <= kMaxK3Tiled;
@@ -875,10 +879,11 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
             const unsigned nbk = (unsigned)((ne + 255) / 256);
             if (K == 1) k_leaf_neighbors<1><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, stats);
             else if (K == 2) k_leaf_neighbors<2><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, stats);
+            else if (inverse) k_leaf_neighbors<3, true><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, stats);
             else k_leaf_neighbors<3><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, stats);
         }
         ProfScope ps(kProfBuildTiles, st);
-#define FX_TILES(KV, SUBMV)                                                                                    \
+#define FX_TILES(KV, SUBMV...)                                                                                 \
     do {                                                                                                       \
         e = hipFuncSetAttribute((const void*)k_build_tiles<KV, SUBMV>,                                         \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                         \
@@ -893,6 +898,7 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
         if (K == 1) FX_TILES(1, true);
         else if (K == 2) FX_TILES(2, false);
         else if (stride == 1) FX_TILES(3, true);
+        else if (inverse) FX_TILES(3, false, true);
         else FX_TILES(3, false);      // 3x3x3 stride 2: windows overlap, still no input row inside the tile's own range
 #undef FX_TILES
         if (e == hipSuccess) e = hipGetLastError();
@@ -907,10 +913,17 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
         rc = kmap_ensure_dense(km, st);
         if (rc != FX_OK) { fx_kmap_destroy(km); return rc; }
     }
-    *g_out = gout;
-    fx_grid_retain(gout);
     *out = km;
     return FX_OK;
+}
+
+// The inverse of a 3x3x3 stride-2 map as a tiled map of its own: produced rows = the fine voxels, looked-up
+// rows = the coarse voxels, offset kappa of a fine voxel = the coarse voxel whose offset kappa lands on it.
+fx_status fx::kmap_ensure_inverse(fx_kmap* km, hipStream_t st) {
+    if (km->inverse) return FX_OK;
+    if (km->K != 3 || km->stride != 2 || km->is_inverse) { set_error("no inverse map for this (kernel, stride)"); return FX_EUNSUPPORTED; }
+    fx_grid_retain(km->gin);                  // build_map takes over one reference to the grid of the produced rows
+    return build_map(km->gout, km->gin, 3, 2, true, st, &km->inverse);
 }
 
 fx_status fx::kmap_fetch_stats(fx_kmap* km) {

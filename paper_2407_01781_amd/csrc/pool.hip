@@ -216,11 +216,10 @@ extern "C" fx_status fx_sparse_conv_transpose_fwd(const fx_kmap* km, const void*
     if (km->stride == 1)   // symmetric map: the forward multiply over the mirrored offsets
         return conv_apply(km, d_feat, dt, d_w, C_in, C_out, d_out, out_dt, st, kWeightsFlipped);
     if (km->K != km->stride) {
-        // 3x3x3 stride 2: inputs are shared by up to 8 outputs; gather through the inverse table with the
-        // weights read forward
-        FX_TRY(kmap_ensure_inverse_dense(const_cast<fx_kmap*>(km), st));
-        return conv_scalar_on_table(km->d_inv_nbmap, km->n_in, km->K3, d_feat, dt, d_w, C_in, C_out, d_out, out_dt, st,
-                                    kWeightsForward);
+        // 3x3x3 stride 2: inputs are shared by up to 8 outputs; the forward kernels of strided maps over the
+        // inverse map, weights as given
+        FX_TRY(kmap_ensure_inverse(const_cast<fx_kmap*>(km), st));
+        return conv_apply(km->inverse, d_feat, dt, d_w, C_in, C_out, d_out, out_dt, st, kWeightsForward);
     }
     // one pair per input voxel: the input-gradient kernel of the strided map with the weights read
     // forward (C_in contracted, C_out produced)

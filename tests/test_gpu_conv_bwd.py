@@ -135,7 +135,7 @@ def test_dense_block_with_rows_beyond_the_lds_budget(monkeypatch):
     H.conv_tolerance_check(gx, O.conv_bwd_data(og, og, 3, 1, gy, wt), "bf16", 27, 64)
 
 
-@pytest.mark.parametrize("name", ["lidar1m", "lidar1m_down"])
+@pytest.mark.parametrize("name", ["lidar1m", "lidar1m_down", "lidar1m_down3"])
 def test_full_size_adjoint_identity(name):
     """At full size the oracle's whole backward pass takes too long; instead the three bilinear
     forms that the pinned oracle satisfies exactly, <conv(x;W), g> = <x, bwd_data(g;W)> =

@@ -300,6 +300,8 @@ def workload(name: str) -> Workload:
         return Workload(name, [lidar_like(3000)], 3, 1, 64, 64, "bf16", 3100, 3101)
     if name == "lidar1m_down":      # config 4
         return Workload(name, [lidar_like(3000)], 2, 2, 64, 128, "bf16", 4100, 3101)
+    if name == "lidar1m_down3":     # the config-3 grid through a 3x3x3 stride-2 layer
+        return Workload(name, [lidar_like(3000)], 3, 2, 64, 128, "bf16", 4300, 3101)
     if name == "sheets4":           # config 5
         return Workload(name, [random_walk_sheets(5000 + g) for g in range(4)], 3, 1, 256, 256,
                         "bf16", 5100, 5101)
