@@ -273,7 +273,7 @@ fx_status fx_upsample2(const fx_kmap* km, const void* d_feat, fx_dtype dt, int32
  *   d_w     device [27, C_in, C_out] row-major, dtype dt, kappa = (di+1)*9 + (dj+1)*3 + (dk+1)
  *   d_out   device [N, C_out] row-major, dtype out_dt (= dt or FX_F32), 16-byte aligned; every row is written
  * Supported shapes:
- *   FX_F32            C_in in {4, 8, 12, 16}, C_out in {16, 32}, out_dt = FX_F32 (true fp32 products on the
+ *   FX_F32            C_in in {4, 8, 12, 16}, C_out a multiple of 4 up to 32, out_dt = FX_F32 (true fp32 products on the
  *                     matrix units, fp32 sums; order differs from fx_sparse_conv_fwd, same tolerance)
  *   FX_F16 / FX_BF16  C_in % 32 == 0, C_out % 64 == 0 (exact products, fp32 sums, one RNE rounding to out_dt);
  *                     allocates the packed weights (27 * C_in * C_out * 2 bytes) for the call
@@ -293,7 +293,7 @@ fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_feat, fx_dtype
  * fx_sparse_conv_bwd_data on the (3,1) map of g.
  *   d_gout [N, C_out] dtype dt, d_w [27, C_in, C_out] (the forward layout), d_gin [N, C_in] dtype out_dt.
  * Supported shapes: the forward's with the roles of C_in and C_out exchanged (fp32: C_out in
- * {4, 8, 12, 16}, C_in in {16, 32}; FX_F16 / FX_BF16: C_out % 32 == 0, C_in % 64 == 0); others
+ * {4, 8, 12, 16}, C_in a multiple of 4 up to 32; FX_F16 / FX_BF16: C_out % 32 == 0, C_in % 64 == 0); others
  * FX_EUNSUPPORTED.  The weight gradient has no map-free form here: fx_sparse_conv_bwd_weight on a kernel map. */
 fx_status fx_sparse_conv_leaf_bwd_data(const fx_grid* g, const void* d_gout, fx_dtype dt, const void* d_w,
                                        int32_t C_in, int32_t C_out, void* d_gin, fx_dtype out_dt, void* stream);

@@ -146,7 +146,7 @@ fx_status conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, cons
 fx_status leaf_apply(const char* who, const fx_grid* g, const void* d_src, fx_dtype dt, const void* d_w, int32_t C_contract,
                      int32_t C_produce, void* d_dst, fx_dtype out_dt, hipStream_t st, int mode);
 inline bool leaf_shape_supported(fx_dtype dt, int C_contract, int C_produce) {
-    if (dt == FX_F32) return C_contract % 4 == 0 && C_contract <= 16 && (C_produce == 16 || C_produce == 32);
+    if (dt == FX_F32) return C_contract % 4 == 0 && C_contract <= 16 && C_produce % 4 == 0 && C_produce <= 32;
     return C_contract % 32 == 0 && C_produce % 64 == 0;
 }
 

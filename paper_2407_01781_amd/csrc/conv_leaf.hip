@@ -143,7 +143,8 @@ __device__ __forceinline__ int leaf_weight_index(int kappa, int c, int p, int n_
     return mirrored ? ((26 - kappa) * n_produce + p) * n_contract + c : (kappa * n_contract + c) * n_produce + p;
 }
 
-// J = C_in / 4 MFMA k-steps per tap, NT = C_out / 16 row tiles, WREG: every lane keeps its share of
+// J = C_in / 4 MFMA k-steps per tap, NT row tiles of 16 produced channels (n_produce <= 16 NT of them exist,
+// a multiple of 4: the others multiply zero weights and are not stored), WREG: every lane keeps its share of
 // the weights (27 * J * NT values) in registers instead of LDS.
 // Workgroups are persistent: each keeps the weights and takes leaves blockIdx.x, blockIdx.x +
 // gridDim.x, ...  All four waves densify; in the multiply phase the waves claim column tiles from a
@@ -157,7 +158,7 @@ __device__ __forceinline__ int leaf_weight_index(int kappa, int c, int p, int n_
 template <int J, int NT, bool WREG>
 __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const float* __restrict__ feat,
                                                             const float* __restrict__ w, float* __restrict__ out,
-                                                            int64_t n_voxels, int mirrored) {
+                                                            int64_t n_voxels, int mirrored, int n_produce) {
     constexpr int C_in = 4 * J, C_out = 16 * NT;
     extern __shared__ __align__(16) unsigned char smem[];
     LeafLds& L = *reinterpret_cast<LeafLds*>(smem);
@@ -174,11 +175,13 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                 for (int j = 0; j < J; ++j)
-                    wr[WREG ? kappa : 0][nt][j] = w[leaf_weight_index(kappa, J * q + j, 16 * nt + v, C_in, C_out, mirrored)];
+                    wr[WREG ? kappa : 0][nt][j] =
+                        16 * nt + v < n_produce ? w[leaf_weight_index(kappa, J * q + j, 16 * nt + v, C_in, n_produce, mirrored)] : 0.f;
     } else {
         for (int e = tid; e < 27 * C_in * C_out; e += kLeafThreads) {
             const int cout = e % C_out, ci = (e / C_out) % C_in, kappa = e / (C_out * C_in);
-            wl[((kappa * 4 + ci / J) * C_out + cout) * J + ci % J] = w[leaf_weight_index(kappa, ci, cout, C_in, C_out, mirrored)];
+            wl[((kappa * 4 + ci / J) * C_out + cout) * J + ci % J] =
+                cout < n_produce ? w[leaf_weight_index(kappa, ci, cout, C_in, n_produce, mirrored)] : 0.f;
         }
     }
     if (wave < 2) {
@@ -310,9 +313,10 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
                     }
                 }
                 if (r < n_act) {
-                    float* o = out + (base + r) * C_out + 4 * q;
+                    float* o = out + (base + r) * n_produce + 4 * q;      // n_produce is a multiple of 4
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) *reinterpret_cast<f32x4*>(o + 16 * nt) = acc[nt];
+                    for (int nt = 0; nt < NT; ++nt)
+                        if (16 * nt + 4 * q < n_produce) *reinterpret_cast<f32x4*>(o + 16 * nt) = acc[nt];
                 }
             }
             if (wave == 0) FX_LT(3);         // multiply (wave 0's tiles)
@@ -598,7 +602,8 @@ size_t leaf_lds_bytes(int J, int NT) {
 }
 
 template <int J, int NT>
-fx_status launch_leaf(const fx_grid* g, const float* feat, const float* w, float* out, int mirrored, hipStream_t st) {
+fx_status launch_leaf(const fx_grid* g, const float* feat, const float* w, float* out, int mirrored, int n_produce,
+                      hipStream_t st) {
     constexpr bool WREG = leaf_weights_in_registers(J, NT);
     const size_t lds = leaf_lds_bytes(J, NT);
     static int per_cu = 0;                    // resident workgroups per compute unit (registers, LDS, wave slots)
@@ -611,7 +616,7 @@ fx_status launch_leaf(const fx_grid* g, const float* feat, const float* w, float
     }
     const unsigned n_wg = (unsigned)std::min<int64_t>(g->hdr.n_leaf, (int64_t)per_cu * compute_units());
     ProfScope ps(kProfConvLeaf, st);
-    k_conv_leaf<J, NT, WREG><<<n_wg, kLeafThreads, lds, st>>>(g->view(), feat, w, out, g->hdr.n_voxels, mirrored);
+    k_conv_leaf<J, NT, WREG><<<n_wg, kLeafThreads, lds, st>>>(g->view(), feat, w, out, g->hdr.n_voxels, mirrored, n_produce);
     FX_HIP_TRY(hipGetLastError());
     return FX_OK;
 }
@@ -674,8 +679,8 @@ fx_status fx::leaf_apply(const char* who, const fx_grid* g, const void* d_src, f
         dev_free(wpk, st);
         return rc;
     }
-    if (C_contract % 4 || C_contract > 16 || C_produce % 16 || C_produce > 32) {
-        set_error("%s: fp32 needs 4, 8, 12 or 16 contracted and 16 or 32 produced channels (got %d -> %d); "
+    if (!leaf_shape_supported(dt, C_contract, C_produce)) {
+        set_error("%s: fp32 needs 4, 8, 12 or 16 contracted and a multiple of 4 up to 32 produced channels (got %d -> %d); "
                   "use the kernel-map path", who, C_contract, C_produce);
         return FX_EUNSUPPORTED;
     }
@@ -686,7 +691,8 @@ fx_status fx::leaf_apply(const char* who, const fx_grid* g, const void* d_src, f
     const int mirrored = mode == kWeightsMirrored;
 #define FX_LEAF(JV)                                                                                  \
     case JV:                                                                                         \
-        return C_produce == 16 ? launch_leaf<JV, 1>(g, src, w, dst, mirrored, st) : launch_leaf<JV, 2>(g, src, w, dst, mirrored, st)
+        return C_produce <= 16 ? launch_leaf<JV, 1>(g, src, w, dst, mirrored, C_produce, st)                \
+                               : launch_leaf<JV, 2>(g, src, w, dst, mirrored, C_produce, st)
     switch (C_contract / 4) {
         FX_LEAF(1);
         FX_LEAF(2);

@@ -25,7 +25,8 @@ def _leaf_vs_oracle(grids, c_in, c_out, seed, dup=0.01, dtype="f32", out_f32=Fal
     return g, feat, wt, y
 
 
-@pytest.mark.parametrize("c_in,c_out", [(8, 16), (4, 16), (12, 32), (16, 32), (16, 16), (8, 32)])
+@pytest.mark.parametrize("c_in,c_out", [(8, 16), (4, 16), (12, 32), (16, 32), (16, 16), (8, 32), (16, 8), (8, 4), (12, 24),
+                                        (4, 28)])
 def test_volumetric_bodies_all_channel_shapes(c_in, c_out):
     w = G.workload("volume_small")
     _leaf_vs_oracle(w.grids, c_in, c_out, w.feat_seed)
@@ -115,7 +116,7 @@ def test_unsupported_shapes_are_refused():
     ijk, jo = w.jagged_ijk()
     g, _ = H.both_grids(ijk, jo)
     n = g.num_voxels
-    for c_in, c_out, dt in ((8, 24, torch.float32), (20, 16, torch.float32), (6, 16, torch.float32),
+    for c_in, c_out, dt in ((8, 36, torch.float32), (20, 16, torch.float32), (6, 16, torch.float32), (8, 18, torch.float32),
                             (8, 16, torch.bfloat16), (32, 32, torch.bfloat16), (48, 64, torch.float16)):
         with pytest.raises(fx.FxError):
             fx.sparse_conv_leaf_fwd(g, torch.zeros((n, c_in), device="cuda", dtype=dt),
@@ -154,7 +155,7 @@ def _leaf_bwd_vs_oracle(grids, c_in, c_out, seed, dtype, out_f32=False):
     return g, gy, wt, gin
 
 
-@pytest.mark.parametrize("c_in,c_out", [(16, 8), (32, 16), (16, 4), (32, 12)])
+@pytest.mark.parametrize("c_in,c_out", [(16, 8), (32, 16), (16, 4), (32, 12), (8, 16), (4, 8), (20, 12)])
 def test_input_gradient_fp32(c_in, c_out):
     w = G.workload("volume_small")
     _leaf_bwd_vs_oracle(w.grids, c_in, c_out, w.feat_seed, "f32")
@@ -184,9 +185,9 @@ def test_input_gradient_is_the_adjoint_of_the_forward():
     g, og = H.both_grids(ijk, jo)
     n = og.num_voxels
     gen = torch.Generator(device="cpu").manual_seed(5)
-    x = torch.randn((n, 16), generator=gen).cuda()       # 16 -> 16: a shape both directions support
+    x = torch.randn((n, 8), generator=gen).cuda()
     gy = torch.randn((n, 16), generator=gen).cuda()
-    wt = (torch.randn((27, 16, 16), generator=gen) * 0.1).cuda()
+    wt = (torch.randn((27, 8, 16), generator=gen) * 0.1).cuda()
     lhs = (fx.sparse_conv_leaf_fwd(g, x, wt).double() * gy.double()).sum()
     rhs = (x.double() * fx.sparse_conv_leaf_bwd_data(g, gy, wt).double()).sum()
     assert abs(float(lhs - rhs)) <= 1e-4 * abs(float(lhs)) + 1e-3
