@@ -622,12 +622,45 @@ __global__ void k_wgrad_scalar(const int32_t* __restrict__ nbmap, int64_t n_out,
         const int rem = (int)(e - (int64_t)kappa * C_in * C_out);
         const int ci = rem / C_out, co = rem - ci * C_out;
         float acc = 0.f;
-        for (int64_t o = o0; o < o1; ++o) {
+        int64_t o = o0;
+        for (; o + 8 <= o1; o += 8) {      // eight map entries, then eight row pairs in flight; added in output order
+            int32_t in[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) in[u] = nbmap[(o + u) * K3 + kappa];
+            float f[8], g[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                f[u] = load_as_float<DT>(feat, (int64_t)max(in[u], 0) * C_in + ci);
+                g[u] = load_as_float<DT>(gout, (o + u) * C_out + co);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc = in[u] >= 0 ? fmaf(f[u], g[u], acc) : acc;
+        }
+        for (; o < o1; ++o) {
             const int32_t in = nbmap[o * K3 + kappa];
             if (in < 0) continue;
             acc = fmaf(load_as_float<DT>(feat, (int64_t)in * C_in + ci), load_as_float<DT>(gout, o * C_out + co), acc);
         }
         part[(int64_t)range * total + e] = acc;
+    }
+}
+
+// First level of a two-level ordered reduction: group blockIdx.y adds its `group` consecutive ranges in
+// ascending order into part2[group index]; the final reduction then adds the groups in order.  The
+// bracketing is fixed by (n_ranges, group), so repeated calls still give identical bits.
+__global__ void k_wgrad_reduce_groups(const float* __restrict__ part, int n_ranges, int64_t total, int group,
+                                      float* __restrict__ part2) {
+    const int r0 = blockIdx.y * group, r1 = min(n_ranges, r0 + group);
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        float s = 0.f;
+        int r = r0;
+        for (; r + 4 <= r1; r += 4) {
+            const float a = part[(int64_t)r * total + e], b = part[(int64_t)(r + 1) * total + e],
+                        c = part[(int64_t)(r + 2) * total + e], d = part[(int64_t)(r + 3) * total + e];
+            s = (((s + a) + b) + c) + d;
+        }
+        for (; r < r1; ++r) s += part[(int64_t)r * total + e];
+        part2[(int64_t)blockIdx.y * total + e] = s;
     }
 }
 
@@ -804,7 +837,10 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
     } else {
         fx_status rc = kmap_ensure_dense(const_cast<fx_kmap*>(km), st);
         if (rc != FX_OK) return rc;
-        n_ranges = (int)std::max<int64_t>(1, std::min<int64_t>(64, km->n_out / 256));
+        // one thread per (element of gw, range of outputs): small weight tensors (low depth) get many short
+        // ranges so that the chip is full -- up to 64 MB of partial sums -- and a two-level ordered reduction
+        const int64_t cap = std::max<int64_t>(64, std::min<int64_t>(4096, ((int64_t)64 << 20) / (total * 4)));
+        n_ranges = (int)std::max<int64_t>(1, std::min<int64_t>(cap, km->n_out / 256));
         FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * n_ranges, st));
         const dim3 grid((unsigned)std::min<int64_t>((total + 255) / 256, 1 << 16), (unsigned)n_ranges);
         ProfScope ps(kProfWgrad, st);
@@ -813,7 +849,21 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
         else k_wgrad_scalar<FX_BF16><<<grid, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_gout, C_in, C_out, n_ranges, part);
         e = hipGetLastError();
     }
-    if (e == hipSuccess) e = launch_reduce(part, n_ranges, total, d_gw, out_dt, st);
+    float* part2 = nullptr;
+    constexpr int kReduceGroup = 64;
+    if (e == hipSuccess && n_ranges > 2 * kReduceGroup) {
+        const int n_groups = (n_ranges + kReduceGroup - 1) / kReduceGroup;
+        fx_status rc2 = dev_alloc((void**)&part2, sizeof(float) * (size_t)total * n_groups, st);
+        if (rc2 != FX_OK) { dev_free(part, st); return rc2; }
+        const dim3 grid((unsigned)std::min<int64_t>((total + 255) / 256, 1 << 16), (unsigned)n_groups);
+        ProfScope ps(kProfWgradReduce, st);
+        k_wgrad_reduce_groups<<<grid, 256, 0, st>>>(part, n_ranges, total, kReduceGroup, part2);
+        e = hipGetLastError();
+        if (e == hipSuccess) e = launch_reduce(part2, n_groups, total, d_gw, out_dt, st);
+        dev_free(part2, st);
+    } else if (e == hipSuccess) {
+        e = launch_reduce(part, n_ranges, total, d_gw, out_dt, st);
+    }
     dev_free(part, st);
     if (e != hipSuccess) { set_error("weight-gradient launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
     return FX_OK;
