@@ -56,6 +56,10 @@ def lib():
         L.fo_pool2.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp]
         L.fo_upsample2.restype = i64
         L.fo_upsample2.argtypes = [vp, vp, vp, C.c_int, vp]
+        L.fo_pool2_bwd.restype = i64
+        L.fo_pool2_bwd.argtypes = [vp, vp, C.c_int, vp, vp, C.c_int, vp]
+        L.fo_upsample2_bwd.restype = i64
+        L.fo_upsample2_bwd.argtypes = [vp, vp, vp, C.c_int, vp]
         L.fo_points_to_ijk.restype = i64
         L.fo_points_to_ijk.argtypes = [vp, i64, vp, vp, vp]
         L.fo_grid_subdivide2.restype = vp
@@ -247,3 +251,26 @@ def points_to_ijk(xyz: np.ndarray, origin, voxel_size) -> Tuple[np.ndarray, int]
     out = np.zeros((xyz.shape[0], 3), dtype=np.int32)
     bad = lib().fo_points_to_ijk(_p(xyz), xyz.shape[0], _p(o), _p(s), _p(out))
     return out, int(bad)
+
+
+def pool2_bwd(fine: OracleGrid, coarse: OracleGrid, mode: str, grad_out: np.ndarray,
+              z: Optional[np.ndarray] = None) -> np.ndarray:
+    """Gradient of pool2 with respect to its input: grad_out [N_coarse, C] -> [N_fine, C] (O5);
+    max pooling needs the forward input z."""
+    g = np.ascontiguousarray(grad_out, dtype=np.float64)
+    assert g.shape[0] == coarse.num_voxels
+    zz = None if z is None else np.ascontiguousarray(z, dtype=np.float64)
+    out = np.zeros((fine.num_voxels, g.shape[1]), dtype=np.float64)
+    if lib().fo_pool2_bwd(fine._h, coarse._h, {"max": 0, "avg": 1}[mode], _p(zz), _p(g), g.shape[1], _p(out)) < 0:
+        raise ValueError("bad pool2_bwd arguments")
+    return out
+
+
+def upsample2_bwd(fine: OracleGrid, coarse: OracleGrid, grad_out: np.ndarray) -> np.ndarray:
+    """Gradient of upsample2: grad_out [N_fine, C] -> [N_coarse, C], the sum over the children (O5)."""
+    g = np.ascontiguousarray(grad_out, dtype=np.float64)
+    assert g.shape[0] == fine.num_voxels
+    out = np.zeros((coarse.num_voxels, g.shape[1]), dtype=np.float64)
+    if lib().fo_upsample2_bwd(fine._h, coarse._h, _p(g), g.shape[1], _p(out)) < 0:
+        raise ValueError("bad upsample2_bwd arguments")
+    return out

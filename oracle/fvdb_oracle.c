@@ -59,6 +59,12 @@
  *                                  (fo_grid_subdivide2), or any given fine grid; out[i,:] = z[parent(i),:],
  *                                  zero where the parent is not active
  *      All are written as plain loops over voxels with this file's hash map.
+ *      Their gradients (Sec. 3.6: the operators are differentiable) are the derivatives of those sums:
+ *          mean pooling   gin[i,c] = gout[o,c] / n(o)      o the parent of i, n(o) its active children
+ *          max pooling    gin[i,c] = gout[o,c] for the child i that attains the maximum of channel c --
+ *                         the first one in offset order when several are equal, the one the forward
+ *                         pass keeps -- and 0 for the others
+ *          upsampling     gin[o,c] = sum over the active children i of o of gout[i,c]
  *
  *  O6  voxel coordinates of points -- Sec. 3.6.2 and Sec. 4.1.1: a grid can be built from
  *      xyz point coordinates as well as from ijk.  No formula is printed; the reading taken:
@@ -534,4 +540,57 @@ int64_t fo_points_to_ijk(const float *xyz, int64_t n, const float origin[3], con
         ijk[3 * p] = c[0]; ijk[3 * p + 1] = c[1]; ijk[3 * p + 2] = c[2];
     }
     return invalid;
+}
+
+/* O5, gradients.  mode 0 max (needs the forward input z), 1 mean.  gout [N_coarse, C] -> gin [N_fine, C]
+ * (overwritten; every fine voxel has exactly one parent in the coarse grid of a factor-2 pooling). */
+int64_t fo_pool2_bwd(const fo_grid *fine, const fo_grid *coarse, int mode, const double *z, const double *gout, int C,
+                     double *gin) {
+    if (fine->B != coarse->B || (mode != 0 && mode != 1) || (mode == 0 && !z)) return -1;
+    for (int64_t e = 0; e < fine->N * (int64_t)C; ++e) gin[e] = 0.0;
+    int64_t pairs = 0;
+    for (int64_t o = 0; o < coarse->N; ++o) {
+        const fo_vox *p = &coarse->vox[o];
+        int64_t child[8];
+        int n = 0;
+        for (int a = 0; a < 2; ++a)
+            for (int b = 0; b < 2; ++b)
+                for (int c = 0; c < 2; ++c) {
+                    int64_t in = fo_find(fine, p->b, 2 * p->i + a, 2 * p->j + b, 2 * p->k + c);
+                    if (in >= 0) child[n++] = in;            /* offset order */
+                }
+        for (int ch = 0; ch < C; ++ch) {
+            const double g = gout[o * (int64_t)C + ch];
+            if (mode == 1) {
+                for (int q = 0; q < n; ++q) gin[child[q] * (int64_t)C + ch] = g / (double)n;
+            } else if (n > 0) {
+                int best = 0;
+                for (int q = 1; q < n; ++q)
+                    if (z[child[q] * (int64_t)C + ch] > z[child[best] * (int64_t)C + ch]) best = q;
+                gin[child[best] * (int64_t)C + ch] = g;
+            }
+        }
+        pairs += n;
+    }
+    return pairs;
+}
+
+/* gout [N_fine, C] -> gin [N_coarse, C] (overwritten): the sum over the active children. */
+int64_t fo_upsample2_bwd(const fo_grid *fine, const fo_grid *coarse, const double *gout, int C, double *gin) {
+    if (fine->B != coarse->B) return -1;
+    int64_t pairs = 0;
+    for (int64_t o = 0; o < coarse->N; ++o) {
+        const fo_vox *p = &coarse->vox[o];
+        double *y = gin + o * (int64_t)C;
+        for (int ch = 0; ch < C; ++ch) y[ch] = 0.0;
+        for (int a = 0; a < 2; ++a)
+            for (int b = 0; b < 2; ++b)
+                for (int c = 0; c < 2; ++c) {
+                    int64_t in = fo_find(fine, p->b, 2 * p->i + a, 2 * p->j + b, 2 * p->k + c);
+                    if (in < 0) continue;
+                    for (int ch = 0; ch < C; ++ch) y[ch] += gout[in * (int64_t)C + ch];
+                    ++pairs;
+                }
+    }
+    return pairs;
 }

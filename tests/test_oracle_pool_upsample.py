@@ -137,3 +137,77 @@ def test_upsampling_matches_dense_repeat_and_subdivision_has_all_children():
     up2 = O.upsample2(g2, coarse, z)
     orphan = g2.lookup(np.array([[1000, 1000, 1000]], np.int32), np.zeros(1, np.int32))[0]
     assert not up2[orphan].any() and np.abs(up2).sum() > 0
+
+
+# ---------------------------------------------------------------- gradients of pooling and upsampling
+def _fine_coarse(seed, n=900, lo=-9, hi=10):
+    pts = _cloud(seed, n, lo, hi)
+    fine = O.OracleGrid(pts, np.array([[0, pts.shape[0]]]))
+    return fine, fine.coarsen2()
+
+
+def test_pooling_gradients_match_autograd_of_the_dense_pooling():
+    fine, coarse = _fine_coarse(241)
+    rng = np.random.default_rng(242)
+    z = rng.standard_normal((fine.num_voxels, 3))
+    g = rng.standard_normal((coarse.num_voxels, 3))
+    fc, cc = fine.ijk()[0], coarse.ijk()[0]
+    lo = 2 * cc.min(0)
+    shape = 2 * (cc.max(0) - cc.min(0) + 1)
+    p, q = fc - lo, cc - cc.min(0)
+    # max: a library's autograd through max_pool3d of the densified box (inactive sites at -inf never win;
+    # random values have no ties)
+    d = torch.full((3,) + tuple(int(s) for s in shape), -np.inf, dtype=torch.float64)
+    d[:, p[:, 0], p[:, 1], p[:, 2]] = torch.from_numpy(z.T)
+    d.requires_grad_(True)
+    y = torch.nn.functional.max_pool3d(d[None], 2)[0]
+    (y[:, q[:, 0], q[:, 1], q[:, 2]] * torch.from_numpy(g.T)).sum().backward()
+    ref = d.grad[:, p[:, 0], p[:, 1], p[:, 2]].numpy().T
+    assert np.array_equal(O.pool2_bwd(fine, coarse, "max", g, z), ref)
+    # mean: autograd through block sums divided by the (constant) number of active children
+    dz = torch.zeros((3,) + tuple(int(s) for s in shape), dtype=torch.float64)
+    dz[:, p[:, 0], p[:, 1], p[:, 2]] = torch.from_numpy(z.T)
+    dz.requires_grad_(True)
+    occ = torch.from_numpy(_densify(fc, np.ones((fine.num_voxels, 1)), lo, shape))
+    blk = lambda a: a.reshape(a.shape[0], shape[0] // 2, 2, shape[1] // 2, 2, shape[2] // 2, 2).sum(dim=(2, 4, 6))
+    ym = blk(dz) / torch.clamp(blk(occ), min=1)
+    (ym[:, q[:, 0], q[:, 1], q[:, 2]] * torch.from_numpy(g.T)).sum().backward()
+    refm = dz.grad[:, p[:, 0], p[:, 1], p[:, 2]].numpy().T
+    assert np.allclose(O.pool2_bwd(fine, coarse, "avg", g), refm, rtol=1e-13, atol=1e-13)
+
+
+def test_gradients_are_the_adjoints_of_the_pinned_forward_operators():
+    fine, coarse = _fine_coarse(251)
+    rng = np.random.default_rng(252)
+    z = rng.standard_normal((fine.num_voxels, 4))
+    g = rng.standard_normal((coarse.num_voxels, 4))
+    gf = rng.standard_normal((fine.num_voxels, 4))
+    # mean pooling and upsampling are linear: <op(z), g> = <z, op_bwd(g)>
+    assert np.isclose((O.pool2(fine, coarse, "avg", z) * g).sum(), (z * O.pool2_bwd(fine, coarse, "avg", g)).sum(), rtol=1e-11)
+    assert np.isclose((O.upsample2(fine, coarse, g) * gf).sum(), (g * O.upsample2_bwd(fine, coarse, gf)).sum(), rtol=1e-11)
+    # max pooling is piecewise linear: pool(z) = <selection, z>, and the gradient is that selection applied to g
+    gm = O.pool2_bwd(fine, coarse, "max", g, z)
+    assert np.isclose((O.pool2(fine, coarse, "max", z) * g).sum(), (z * gm).sum(), rtol=1e-11)
+    # every coarse voxel hands each channel's gradient to exactly one child
+    assert np.allclose(O.upsample2_bwd(fine, coarse, gm), g, rtol=0, atol=0)
+    # upsampling then its gradient counts the children: upsample2_bwd(upsample2(g)) = n(o) * g
+    n_children = O.upsample2_bwd(fine, coarse, np.ones((fine.num_voxels, 1)))
+    assert np.allclose(O.upsample2_bwd(fine, coarse, O.upsample2(fine, coarse, g)), n_children * g, rtol=1e-13)
+
+
+def test_max_pooling_gradient_with_ties_goes_to_the_first_child_in_offset_order():
+    a = np.arange(2, dtype=np.int32)
+    pts = np.stack(np.meshgrid(a, a, a, indexing="ij"), -1).reshape(-1, 3).astype(np.int32)
+    fine = O.OracleGrid(pts, np.array([[0, 8]]))
+    coarse = fine.coarsen2()
+    idx = fine.lookup(pts)                   # offset order kappa = 4a + 2b + c is the order of pts
+    z = np.zeros((8, 2))
+    z[idx[[2, 5, 7]], 0] = 3.0               # three equal maxima in channel 0: the first (kappa = 2) wins
+    z[idx, 1] = np.array([1, 9, 2, 9, 0, 0, 0, 0])      # channel 1: kappa = 1 and 3 tie
+    g = np.array([[10.0, -4.0]])
+    gin = O.pool2_bwd(fine, coarse, "max", g, z)
+    exp = np.zeros((8, 2))
+    exp[idx[2], 0] = 10.0
+    exp[idx[1], 1] = -4.0
+    assert np.array_equal(gin, exp)
+    assert np.array_equal(O.pool2_bwd(fine, coarse, "avg", g), np.tile(g / 8.0, (8, 1)))
