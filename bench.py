@@ -226,6 +226,13 @@ def main():
            "max_pool_ms": t_pool, "max_pool_GBs": move_bytes / (t_pool * 1e-3) / 1e9,
            "upsample_ms": t_up, "upsample_GBs": move_bytes / (t_up * 1e-3) / 1e9,
            "algorithmic_bytes": move_bytes, "hbm_peak_GBs": HBM_PEAK_GBS}
+    g_coarse = torch.randn(pooled.shape, device="cuda").to(tdt).contiguous()
+    t_pool_b = b2b(lambda: fx.pool2_bwd(km2, g_coarse, "max", d_fine))
+    t_up_b = b2b(lambda: fx.upsample2_bwd(km2, d_fine))
+    ops["max_pool_bwd_ms"] = t_pool_b                      # reads the fine input and the coarse gradient, writes the fine gradient
+    ops["max_pool_bwd_GBs"] = (move_bytes + n_in * c * elem) / (t_pool_b * 1e-3) / 1e9
+    ops["upsample_bwd_ms"] = t_up_b
+    ops["upsample_bwd_GBs"] = move_bytes / (t_up_b * 1e-3) / 1e9
     ops["max_pool_frac"] = ops["max_pool_GBs"] / HBM_PEAK_GBS
     ops["upsample_frac"] = ops["upsample_GBs"] / HBM_PEAK_GBS
     if w.dtype != "f32":

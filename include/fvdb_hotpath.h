@@ -259,6 +259,20 @@ fx_status fx_pool2(const fx_kmap* km, int32_t mode, const void* d_feat, fx_dtype
                    void* stream);
 fx_status fx_upsample2(const fx_kmap* km, const void* d_feat, fx_dtype dt, int32_t C, void* d_out, void* stream);
 
+/* Gradients of fx_pool2 and fx_upsample2 (Sec. 3.6: the operators are differentiable); km a (2,2) map,
+ * i its inputs (fine voxels), o its outputs (coarse voxels), n(o) the number of active children of o:
+ *   fx_pool2_bwd      FX_POOL_AVG: gin[i,c] = gout[o,c] / n(o) for the parent o of i (fp32 division, one
+ *                     rounding to dt); d_feat is not read and may be NULL.
+ *                     FX_POOL_MAX: gin[i,c] = gout[o,c] if i is the child whose feat[i,c] is the maximum --
+ *                     the first in offset order among equals, the one fx_pool2 keeps -- else 0 (exact);
+ *                     d_feat is the input of the forward call.
+ *        d_feat [N_in, C], d_gout [N_out, C], d_gin [N_in, C], all dtype dt; every row of d_gin is written.
+ *   fx_upsample2_bwd  gin[o,c] = sum over the active children i of o of gout[i,c] (fp32 sum in offset order,
+ *                     one rounding to dt).  d_gout [N_in, C], d_gin [N_out, C]. */
+fx_status fx_pool2_bwd(const fx_kmap* km, int32_t mode, const void* d_feat, const void* d_gout, fx_dtype dt, int32_t C,
+                       void* d_gin, void* stream);
+fx_status fx_upsample2_bwd(const fx_kmap* km, const void* d_gout, fx_dtype dt, int32_t C, void* d_gin, void* stream);
+
 /* ---------------------------------------------------------------------------------------
  * 3x3x3 submanifold convolution straight from the grid, without a kernel map (Sec. 3.5 scenario 1,
  * the "Leaf" operator: the 10^3 window of input rows around each 8^3 leaf is densified in on-chip

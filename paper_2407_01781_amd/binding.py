@@ -85,6 +85,10 @@ def _load():
     L.fx_sparse_conv_transpose_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
     L.fx_pool2.restype = C.c_int
     L.fx_pool2.argtypes = [vp, i32, vp, C.c_int, i32, vp, vp]
+    L.fx_pool2_bwd.restype = C.c_int
+    L.fx_pool2_bwd.argtypes = [vp, C.c_int, vp, vp, C.c_int, i32, vp, vp]
+    L.fx_upsample2_bwd.restype = C.c_int
+    L.fx_upsample2_bwd.argtypes = [vp, vp, C.c_int, i32, vp, vp]
     L.fx_upsample2.restype = C.c_int
     L.fx_upsample2.argtypes = [vp, vp, C.c_int, i32, vp, vp]
     L.fx_release_cached_memory.restype = None
@@ -372,3 +376,24 @@ def upsample2(kmap: KernelMap, feat: torch.Tensor) -> torch.Tensor:
     out = torch.empty((kmap.g_in.num_voxels, feat.shape[1]), dtype=feat.dtype, device="cuda")
     _check(lib.fx_upsample2(kmap._h, _ptr(feat), _TORCH_DT[feat.dtype], feat.shape[1], _ptr(out), _stream()))
     return out
+
+
+def pool2_bwd(kmap: KernelMap, grad_out: torch.Tensor, mode: str = "max", feat: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Gradient of pool2: grad_out [N_out, C] -> [N_in, C]; max pooling needs the forward input feat [N_in, C]."""
+    assert grad_out.is_cuda and grad_out.is_contiguous() and grad_out.dtype in _TORCH_DT and grad_out.shape[0] == kmap.n_out
+    if mode == "max":
+        assert feat is not None and feat.is_cuda and feat.is_contiguous() and feat.dtype == grad_out.dtype
+        assert feat.shape == (kmap.g_in.num_voxels, grad_out.shape[1])
+    gin = torch.empty((kmap.g_in.num_voxels, grad_out.shape[1]), dtype=grad_out.dtype, device="cuda")
+    _check(lib.fx_pool2_bwd(kmap._h, {"max": 0, "avg": 1}[mode], _ptr(feat) if mode == "max" else None, _ptr(grad_out),
+                            _TORCH_DT[grad_out.dtype], grad_out.shape[1], _ptr(gin), _stream()))
+    return gin
+
+
+def upsample2_bwd(kmap: KernelMap, grad_out: torch.Tensor) -> torch.Tensor:
+    """Gradient of upsample2: grad_out [N_in, C] on the fine grid -> [N_out, C], the sum over the children."""
+    assert grad_out.is_cuda and grad_out.is_contiguous() and grad_out.dtype in _TORCH_DT
+    assert grad_out.shape[0] == kmap.g_in.num_voxels
+    gin = torch.empty((kmap.n_out, grad_out.shape[1]), dtype=grad_out.dtype, device="cuda")
+    _check(lib.fx_upsample2_bwd(kmap._h, _ptr(grad_out), _TORCH_DT[grad_out.dtype], grad_out.shape[1], _ptr(gin), _stream()))
+    return gin

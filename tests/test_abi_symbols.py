@@ -57,6 +57,8 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.fx_sparse_conv_transpose_fwd(None, None, 0, None, 4, 4, None, 0, None) == -1
     assert lib.fx_pool2(None, 0, None, 0, 4, None, None) == -1
     assert lib.fx_upsample2(None, None, 0, 4, None, None) == -1
+    assert lib.fx_pool2_bwd(None, 0, None, None, 0, 4, None, None) == -1
+    assert lib.fx_upsample2_bwd(None, None, 0, 4, None, None) == -1
     assert lib.fx_grid_subdivide2(None, None, None) == -1
     assert b"fx_grid_subdivide2" in lib.fx_last_error()
     assert lib.fx_sparse_conv_leaf_fwd(None, None, 0, None, 8, 16, None, 0, None) == -1

@@ -150,3 +150,59 @@ def test_full_size_config4_grid():
         ref = O.conv_transpose(og, ogc, 2, 2, zs, wt)
         rows = nb[sl][nb[sl] >= 0]
         H.conv_tolerance_check(y[rows], ref[rows], "bf16", 8, 128)
+
+
+# ---------------------------------------------------------------- gradients
+@pytest.mark.parametrize("name", ["lidar_small", "sheets_small"])
+@pytest.mark.parametrize("dtype,c", [("bf16", 64), ("f16", 24), ("f32", 32), ("f32", 3), ("bf16", 5)])
+def test_pooling_gradients(name, dtype, c):
+    # max: a selection of the parent's gradient, bit for bit (ties included: the values are rounded to the
+    # storage type, so equal children occur).  mean: one fp32 division and one rounding of the storage type.
+    km, og, ogc = _pair_map(name)
+    z = _feat(51, og.num_voxels, c, dtype)
+    if dtype != "f32":
+        z = np.round(z * 2) / 2                      # coarse values: many exact ties between siblings
+    g = _feat(52, ogc.num_voxels, c, dtype)
+    d_z, d_g = H.to_device_storage(z, dtype), H.to_device_storage(g, dtype)
+    gm = fx.pool2_bwd(km, d_g, "max", d_z).float().cpu().numpy()
+    assert np.array_equal(gm, O.pool2_bwd(og, ogc, "max", g, z).astype(np.float32))
+    ga = fx.pool2_bwd(km, d_g, "avg").float().cpu().numpy().astype(np.float64)
+    ref = O.pool2_bwd(og, ogc, "avg", g)
+    rnd = {"f32": 2.0 ** -23, "f16": 2.0 ** -10, "bf16": 2.0 ** -7}[dtype]
+    tiny = 2.0 ** -24 if dtype == "f16" else 1e-30          # fp16 quotients below 2^-14 are subnormal: absolute spacing 2^-24
+    assert (np.abs(ga - ref) <= rnd * np.abs(ref) + tiny).all()
+
+
+@pytest.mark.parametrize("name", ["lidar_small", "sheets_small"])
+@pytest.mark.parametrize("dtype,c", [("bf16", 64), ("f32", 16), ("f16", 7)])
+def test_upsampling_gradient(name, dtype, c):
+    km, og, ogc = _pair_map(name)
+    g = _feat(53, og.num_voxels, c, dtype)
+    gin = fx.upsample2_bwd(km, H.to_device_storage(g, dtype)).float().cpu().numpy().astype(np.float64)
+    ref = O.upsample2_bwd(og, ogc, g)
+    mag = O.upsample2_bwd(og, ogc, np.abs(g))
+    rnd = {"f32": 0.0, "f16": 2.0 ** -10, "bf16": 2.0 ** -7}[dtype]
+    assert (np.abs(gin - ref) <= 2.0 ** -22 * mag + rnd * np.abs(ref) + 1e-30).all()
+
+
+def test_gradients_on_empty_grid_and_full_size_identities():
+    g0, _ = H.both_grids(np.zeros((0, 3), np.int32), np.zeros((0, 2), np.int64))
+    km0 = fx.build_kernel_map(g0, 2, 2)
+    assert fx.pool2_bwd(km0, torch.zeros((0, 8), device="cuda"), "avg").shape == (0, 8)
+    assert fx.upsample2_bwd(km0, torch.zeros((0, 8), device="cuda")).shape == (0, 8)
+    # full size (the benchmark's grid): identities that hold exactly -- every parent hands each channel of
+    # its gradient to exactly one child under max pooling, and upsampling then summing counts the children
+    w = G.workload("lidar1m")
+    ijk, jo = w.jagged_ijk()
+    g = fx.build_index_grid(torch.from_numpy(ijk).cuda(), jo)
+    km = fx.build_kernel_map(g, 2, 2)
+    gen = torch.Generator(device="cpu").manual_seed(3)
+    z = torch.randn((g.num_voxels, 64), generator=gen).to(torch.bfloat16).cuda()
+    go = torch.randn((km.n_out, 64), generator=gen).to(torch.bfloat16).cuda()
+    gm = fx.pool2_bwd(km, go, "max", z)
+    assert torch.equal(fx.upsample2_bwd(km, gm), go)                       # one nonzero per (parent, channel): the sum is exact
+    ones = torch.ones((g.num_voxels, 8), dtype=torch.float32, device="cuda")
+    count = fx.upsample2_bwd(km, ones)                                     # children per coarse voxel, exact in fp32
+    assert float(count[:, 0].sum()) == g.num_voxels and float(count.min()) >= 1 and float(count.max()) <= 8
+    ga = fx.pool2_bwd(km, torch.ones((km.n_out, 8), dtype=torch.float32, device="cuda"), "avg")
+    assert torch.equal(ga, fx.upsample2(km, 1.0 / count))
