@@ -155,11 +155,12 @@ __device__ __forceinline__ int leaf_weight_index(int kappa, int c, int p, int n_
 // Lane l of a wave works on voxel column v = l % 16 and k-quarter q = l / 16: it holds the J
 // input channels J*q .. J*q + J-1 of its voxel's neighbour (k-step j contracts channels {J*q + j})
 // and, per row tile, the same channels of output channel 16*nt + v of the weights.
-template <int J, int NT, bool WREG>
+template <int J, int NT, bool WREG, bool FULLP>     // FULLP: all 16 NT produced channels exist
 __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const float* __restrict__ feat,
                                                             const float* __restrict__ w, float* __restrict__ out,
-                                                            int64_t n_voxels, int mirrored, int n_produce) {
+                                                            int64_t n_voxels, int mirrored, int n_produce_arg) {
     constexpr int C_in = 4 * J, C_out = 16 * NT;
+    const int n_produce = FULLP ? C_out : n_produce_arg;
     extern __shared__ __align__(16) unsigned char smem[];
     LeafLds& L = *reinterpret_cast<LeafLds*>(smem);
     float* win = reinterpret_cast<float*>(smem + ((sizeof(LeafLds) + 15) & ~size_t(15)));   // [cell][C_in]
@@ -176,12 +177,12 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
 #pragma unroll
                 for (int j = 0; j < J; ++j)
                     wr[WREG ? kappa : 0][nt][j] =
-                        16 * nt + v < n_produce ? w[leaf_weight_index(kappa, J * q + j, 16 * nt + v, C_in, n_produce, mirrored)] : 0.f;
+                        FULLP || 16 * nt + v < n_produce ? w[leaf_weight_index(kappa, J * q + j, 16 * nt + v, C_in, n_produce, mirrored)] : 0.f;
     } else {
         for (int e = tid; e < 27 * C_in * C_out; e += kLeafThreads) {
             const int cout = e % C_out, ci = (e / C_out) % C_in, kappa = e / (C_out * C_in);
             wl[((kappa * 4 + ci / J) * C_out + cout) * J + ci % J] =
-                cout < n_produce ? w[leaf_weight_index(kappa, ci, cout, C_in, n_produce, mirrored)] : 0.f;
+                FULLP || cout < n_produce ? w[leaf_weight_index(kappa, ci, cout, C_in, n_produce, mirrored)] : 0.f;
         }
     }
     if (wave < 2) {
@@ -316,7 +317,7 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
                     float* o = out + (base + r) * n_produce + 4 * q;      // n_produce is a multiple of 4
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
-                        if (16 * nt + 4 * q < n_produce) *reinterpret_cast<f32x4*>(o + 16 * nt) = acc[nt];
+                        if (FULLP || 16 * nt + 4 * q < n_produce) *reinterpret_cast<f32x4*>(o + 16 * nt) = acc[nt];
                 }
             }
             if (wave == 0) FX_LT(3);         // multiply (wave 0's tiles)
@@ -601,24 +602,31 @@ size_t leaf_lds_bytes(int J, int NT) {
            sizeof(float) * ((size_t)kWinCells * C_in + (leaf_weights_in_registers(J, NT) ? 0 : (size_t)27 * C_in * C_out));
 }
 
-template <int J, int NT>
-fx_status launch_leaf(const fx_grid* g, const float* feat, const float* w, float* out, int mirrored, int n_produce,
-                      hipStream_t st) {
+template <int J, int NT, bool FULLP>
+fx_status launch_leaf_full(const fx_grid* g, const float* feat, const float* w, float* out, int mirrored, int n_produce,
+                           hipStream_t st) {
     constexpr bool WREG = leaf_weights_in_registers(J, NT);
     const size_t lds = leaf_lds_bytes(J, NT);
     static int per_cu = 0;                    // resident workgroups per compute unit (registers, LDS, wave slots)
     if (per_cu == 0) {
-        FX_HIP_TRY(hipFuncSetAttribute((const void*)k_conv_leaf<J, NT, WREG>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        FX_HIP_TRY(hipFuncSetAttribute((const void*)k_conv_leaf<J, NT, WREG, FULLP>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)lds));
         int n = 0;
-        FX_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_conv_leaf<J, NT, WREG>, kLeafThreads, lds));
+        FX_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_conv_leaf<J, NT, WREG, FULLP>, kLeafThreads, lds));
         per_cu = std::max(1, n);
     }
     const unsigned n_wg = (unsigned)std::min<int64_t>(g->hdr.n_leaf, (int64_t)per_cu * compute_units());
     ProfScope ps(kProfConvLeaf, st);
-    k_conv_leaf<J, NT, WREG><<<n_wg, kLeafThreads, lds, st>>>(g->view(), feat, w, out, g->hdr.n_voxels, mirrored, n_produce);
+    k_conv_leaf<J, NT, WREG, FULLP><<<n_wg, kLeafThreads, lds, st>>>(g->view(), feat, w, out, g->hdr.n_voxels, mirrored, n_produce);
     FX_HIP_TRY(hipGetLastError());
     return FX_OK;
+}
+
+template <int J, int NT>
+fx_status launch_leaf(const fx_grid* g, const float* feat, const float* w, float* out, int mirrored, int n_produce,
+                      hipStream_t st) {
+    return n_produce == 16 * NT ? launch_leaf_full<J, NT, true>(g, feat, w, out, mirrored, n_produce, st)
+                                : launch_leaf_full<J, NT, false>(g, feat, w, out, mirrored, n_produce, st);
 }
 
 }  // namespace
