@@ -107,6 +107,68 @@ __device__ __forceinline__ void store_block_rows_impl(const f32x16 (&acc)[2], co
 
 // tile_out: first byte of the tile's first output row at the slice's first channel (wave-uniform);
 // cols: channels of the slice that exist (64, or fewer in the last slice of a padded channel count).
+// The same with the weights held in LDS as fp32 in forward order W'[kappa][ci][co] (read through `mode` once per
+// workgroup): at low depth the weight reads are most of the kernel's loads, and all lanes of a wave that work
+// on the same four produced channels read the same 16 bytes, which LDS serves as a broadcast.  Few, fat
+// workgroups walk the outputs so that the copy of the weights is paid a few thousand times, not per 256 outputs.
+// QV: groups of four produced channels per thread.  1 is what runs: with 4 (one thread per voxel and 16 channels)
+// the 64 lanes of a wave walk 64 different map rows and input rows, and the kernel took twice as long.
+template <int DT, bool OUT_F32, int QV>
+__global__ void __launch_bounds__(256)
+k_conv_scalar4_ldsw(const int32_t* __restrict__ nbmap, int64_t n_out, int K3, const void* __restrict__ feat,
+                    const void* __restrict__ w, int C_in, int C_out, void* __restrict__ out, int mode) {
+    extern __shared__ __align__(16) unsigned char lds_w_raw[];
+    float* wl = reinterpret_cast<float*>(lds_w_raw);
+    const int n_w = K3 * C_in * C_out;
+    for (int e = threadIdx.x; e < n_w; e += blockDim.x) {
+        const int co = e % C_out, ci = (e / C_out) % C_in, kappa = e / (C_out * C_in);
+        const int64_t kw = (mode & kWeightsFlipped) ? K3 - 1 - kappa : kappa;
+        const int64_t src = (mode & kWeightsTransposed) ? (kw * C_out + co) * C_in + ci : (kw * C_in + ci) * C_out + co;
+        wl[e] = load_as_float<DT>(w, src);
+    }
+    __syncthreads();
+    const int q_out = C_out / (4 * QV);
+    const int64_t total = n_out * q_out;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t o = e / q_out;
+        const int co = (int)(e - o * q_out) * 4 * QV;
+        f32x4 acc[QV];
+#pragma unroll
+        for (int g = 0; g < QV; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int kappa = 0; kappa < K3; ++kappa) {
+            const int32_t in = nbmap[o * K3 + kappa];
+            if (in < 0) continue;
+            const int64_t fb = (int64_t)in * C_in;
+            const float* wk = wl + kappa * C_in * C_out + co;
+            for (int ci = 0; ci < C_in; ci += 4) {
+                const f32x4 x = load4_as_float<DT>(feat, fb + ci);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                    for (int g = 0; g < QV; ++g) {
+                        const f32x4 wr = *reinterpret_cast<const f32x4*>(wk + (ci + j) * C_out + 4 * g);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[g][v] = fmaf(x[j], wr[v], acc[g][v]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < QV; ++g) {
+            const int64_t at = o * C_out + co + 4 * g;
+            if (OUT_F32) {
+                *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + at) = acc[g];
+            } else if (DT == FX_F16) {
+                *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + at) =
+                    u32x2{Elem<_Float16>::pack2(acc[g][0], acc[g][1]), Elem<_Float16>::pack2(acc[g][2], acc[g][3])};
+            } else {
+                *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + at) =
+                    u32x2{Elem<__bf16>::pack2(acc[g][0], acc[g][1]), Elem<__bf16>::pack2(acc[g][2], acc[g][3])};
+            }
+        }
+    }
+}
+
 template <typename T, bool OUT_F32>
 __device__ __forceinline__ void store_block_rows(const f32x16 (&acc)[2], const uint16_t* perm_g, unsigned char* tile_out,
                                                  int C_out, int cols, int n_valid, int n, int h) {
@@ -1131,10 +1193,18 @@ fx_status fx::conv_scalar_on_table(const int32_t* d_table, int64_t n_rows, int K
     const bool out_f32 = (out_dt == FX_F32);
     const bool four = C_in % 4 == 0 && C_out % 4 == 0;
     const int64_t total = n_rows * (four ? C_out / 4 : C_out);
-    const unsigned nb = (unsigned)std::max<int64_t>(1, std::min<int64_t>((total + 255) / 256, 1 << 20));
+    const size_t w_lds = sizeof(float) * (size_t)K3 * C_in * C_out;
+    const char* wl_env = getenv("FVDB_HOTPATH_SCALAR_LDS");          // "0": weights from L1 (tests run both)
+    const bool lds_w = four && w_lds <= 32 * 1024 && total >= 8 * 1024 && !(wl_env && wl_env[0] == '0');
+    const unsigned nb = lds_w ? (unsigned)std::max<int64_t>(1, std::min<int64_t>((total + 255) / 256, (int64_t)compute_units() * 8))
+                              : (unsigned)std::max<int64_t>(1, std::min<int64_t>((total + 255) / 256, 1 << 20));
 #define FX_SCALAR(DT)                                                                                            \
     do {                                                                                                         \
-        if (four && out_f32) k_conv_scalar4<DT, true><<<nb, 256, 0, st>>>(d_table, n_rows, K3, d_feat,           \
+        if (lds_w && out_f32) k_conv_scalar4_ldsw<DT, true, 1><<<nb, 256, w_lds, st>>>(d_table, n_rows, K3, d_feat, \
+                                                                                       d_w, C_in, C_out, d_out, mode); \
+        else if (lds_w) k_conv_scalar4_ldsw<DT, false, 1><<<nb, 256, w_lds, st>>>(d_table, n_rows, K3, d_feat, d_w, \
+                                                                                  C_in, C_out, d_out, mode);     \
+        else if (four && out_f32) k_conv_scalar4<DT, true><<<nb, 256, 0, st>>>(d_table, n_rows, K3, d_feat,      \
                                                                           d_w, C_in, C_out, d_out, mode);        \
         else if (four) k_conv_scalar4<DT, false><<<nb, 256, 0, st>>>(d_table, n_rows, K3, d_feat, d_w,           \
                                                                      C_in, C_out, d_out, mode);                  \

@@ -152,6 +152,17 @@ def test_3x3x3_stride_2(dtype, c_in, c_out):
     H.conv_tolerance_check(up.float().cpu().numpy(), O.conv_transpose(og, ogc, 3, 2, gy, wt_t), dtype, 27, c_out)
 
 
+@pytest.mark.parametrize("lds_weights", ["0", "1"])
+@pytest.mark.parametrize("dtype,c_in,c_out", [("f32", 8, 16), ("bf16", 8, 16), ("f16", 4, 32), ("f32", 12, 8)])
+def test_low_depth_scalar_kernel_with_and_without_weights_in_lds(dtype, c_in, c_out, lds_weights, monkeypatch):
+    # depths the matrix kernels do not take on a sparse grid: the scalar kernel, weights in LDS by default
+    monkeypatch.setenv("FVDB_HOTPATH_SCALAR_LDS", lds_weights)
+    monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", "0")
+    for name in ("lidar_small", "lidar_small_down"):
+        y, ref, dt, k3, ci = _run(G.workload(name), c_in=c_in, c_out=c_out, dtype=dtype)
+        H.conv_tolerance_check(y, ref, dt, k3, ci)
+
+
 def test_identity_tap_is_bit_exact_in_bf16():
     w = G.workload("lidar_small")
     ijk, jo = w.jagged_ijk()
