@@ -171,3 +171,29 @@ def test_full_size_adjoint_identity(name):
         for s in (0, n // 3, n - 300):
             ref = O.conv(og, og, w.kernel_size, 1, gy.astype(np.float64), wm.astype(np.float64), s, s + 300)
             H.conv_tolerance_check(gxs[s:s + 300], ref[s:s + 300], w.dtype, w.k3, w.c_out)
+
+
+def test_3x3x3_stride_2_backward_edge_cases():
+    # empty grid, a batch with an empty member, a single voxel with negative coordinates: the inverse map is
+    # built on the first backward call of each map
+    for grids in ([np.zeros((0, 3), np.int32)],
+                  [G.workload("lidar_small").grids[0][:3000], np.zeros((0, 3), np.int32), np.array([[-1, -2, -3]], np.int32)],
+                  [np.array([[7, 0, -1]], np.int32)]):
+        ijk, jo = G.make_jagged(grids)
+        g, og = H.both_grids(ijk, jo)
+        km = fx.build_kernel_map(g, 3, 2)
+        ogc = og.coarsen2()
+        assert km.n_out == ogc.num_voxels
+        _, wt = G.features_and_weights(5, 1, 32, 64, 27, "bf16")
+        gy = G.round_to_dtype(np.random.default_rng(6).standard_normal((ogc.num_voxels, 64)).astype(np.float32), "bf16")
+        gx = fx.sparse_conv_bwd_data(km, H.to_device_storage(gy, "bf16"), H.to_device_storage(wt, "bf16"))
+        assert gx.shape == (og.num_voxels, 32)
+        if og.num_voxels:
+            H.conv_tolerance_check(gx.float().cpu().numpy(), O.conv_bwd_data(og, ogc, 3, 2, gy, wt), "bf16", 27, 64)
+        _, wt_t = G.features_and_weights(7, 1, 64, 32, 27, "bf16")
+        up = fx.sparse_conv_transpose_fwd(km, H.to_device_storage(gy, "bf16"), H.to_device_storage(wt_t, "bf16"))
+        assert up.shape == (og.num_voxels, 32)
+        if og.num_voxels:
+            H.conv_tolerance_check(up.float().cpu().numpy(), O.conv_transpose(og, ogc, 3, 2, gy, wt_t), "bf16", 27, 64)
+        # the forward map is untouched by the inverse that now hangs on it
+        assert np.array_equal(km.dense().cpu().numpy(), O.kernel_map(og, ogc, 3, 2))
