@@ -347,7 +347,6 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
 constexpr int kLeaf16Threads = 256;
 constexpr int kLeaf16Waves = kLeaf16Threads / 64;
 constexpr int kLeaf16Groups = 4;             // column tiles of 32 voxels per wave: 4 waves x 4 x 32 = 512
-constexpr int64_t kLeaf16FixedCost = 48;     // staging of a leaf in units of one active voxel's multiplies
 
 constexpr int kWinSlabs = (kWinCells + 15) / 16;     // direct-to-LDS loads fill 16 rows (1 KB) per wave instruction
 typedef __attribute__((address_space(3))) void* leaf_lds_ptr;
@@ -372,7 +371,8 @@ template <typename T, bool OUT_F32>
 __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, const unsigned char* __restrict__ feat,
                                                                   const unsigned char* __restrict__ wp,
                                                                   unsigned char* __restrict__ out, int C_in, int C_out,
-                                                                  int64_t n_voxels, const unsigned char* __restrict__ zero_row) {
+                                                                  int32_t* __restrict__ work_counter,
+                                                                  const unsigned char* __restrict__ zero_row) {
     typedef typename Elem<T>::vec8 vec8;
     extern __shared__ __align__(16) unsigned char smem[];
     Leaf16Lds& L = *reinterpret_cast<Leaf16Lds*>(smem);
@@ -380,23 +380,21 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
     const int nchunk = C_in / 32, nslice = C_out / 64;
     const int64_t pitch = (int64_t)C_in * 2;
 
-    if (wave < 2) {
-        const int lane = tid0 & 63;
-        const int64_t first_index = t.leaf[0].offset;
-        const int64_t total = kLeaf16FixedCost * t.n_leaf + n_voxels;
-        const int b = blockIdx.x + wave;
-        const int f = b >= (int)gridDim.x ? t.n_leaf
-                                          : first_leaf_at_cost<kLeaf16FixedCost>(t, first_index, total * b / (int64_t)gridDim.x, lane);
-        if (lane == 0) L.range[wave] = f;
-    }
+    // Leaves are claimed one at a time from a counter in global memory, in index order: workgroups that run
+    // together then work on neighbouring leaves (whose windows overlap, so their rows meet in L2), and the
+    // tail is one leaf long.  The next claim is made while the current leaf is processed.
+    if (tid0 == 0) L.range[0] = atomicAdd(work_counter, 1);
     __syncthreads();
-    const int f_begin = uni(L.range[0]), f_end = uni(L.range[1]);
+    int f = uni(L.range[0]);
+    int parity = 0;
 
 #ifdef FX_LEAF_TIMING
     unsigned long long _tl = __builtin_readcyclecounter();
     const unsigned long long _w0 = wall_clock64();
 #endif
-    for (int f = f_begin; f < f_end; ++f) {
+    while (f < t.n_leaf) {
+        parity ^= 1;
+        if (tid0 == 64) L.range[parity] = atomicAdd(work_counter, 1);    // by the second wave (the first walks the tree); read after this leaf's barriers
         // everything a thread derives from its number is recomputed per leaf (registers are needed
         // for the accumulators, not for loop-invariant addresses)
         int tid = tid0;
@@ -567,6 +565,7 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
         }
         if (wave == 0) FX_LT(6);                 // write-back
         __syncthreads();                         // records and lists are rewritten for the next leaf
+        f = uni(L.range[parity]);
     }
 #ifdef FX_LEAF_TIMING
     if (tid0 == 0 && blockIdx.x < 1024) g_leaf_timing[blockIdx.x * 8 + 7] = wall_clock64() - _w0;
@@ -575,7 +574,7 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
 
 template <typename T, bool OUT_F32>
 fx_status launch_leaf16(const fx_grid* g, const void* feat, const void* wpacked, void* out, int C_in, int C_out,
-                        const void* zero_row, hipStream_t st) {
+                        void* work_counter, const void* zero_row, hipStream_t st) {
     const size_t lds = sizeof(Leaf16Lds);
     static int per_cu = 0;
     if (per_cu == 0) {
@@ -589,7 +588,7 @@ fx_status launch_leaf16(const fx_grid* g, const void* feat, const void* wpacked,
     ProfScope ps(kProfConvLeaf, st);
     k_conv_leaf16<T, OUT_F32><<<n_wg, kLeaf16Threads, lds, st>>>(g->view(), (const unsigned char*)feat,
                                                                  (const unsigned char*)wpacked, (unsigned char*)out, C_in,
-                                                                 C_out, g->hdr.n_voxels, (const unsigned char*)zero_row);
+                                                                 C_out, (int32_t*)work_counter, (const unsigned char*)zero_row);
     FX_HIP_TRY(hipGetLastError());
     return FX_OK;
 }
@@ -667,7 +666,8 @@ fx_status fx::leaf_apply(const char* who, const fx_grid* g, const void* d_src, f
         if (g->hdr.n_voxels == 0) return FX_OK;
         void* wpk = nullptr;
         const size_t wbytes = packed_weight_bytes(27, C_contract, C_produce, 2);
-        // behind the packed weights: 32 bytes the packing kernel clears, then a 64-byte row of zeros
+        // behind the packed weights: 32 bytes that the memset and the packing kernel clear (the first four are the
+        // leaf kernel's work counter), then a 64-byte row of zeros
         FX_TRY(dev_alloc(&wpk, wbytes + 96, st));
         const void* zero_row = (const char*)wpk + wbytes + 32;
         if (hipMemsetAsync((char*)wpk + wbytes, 0, 96, st) != hipSuccess) {
@@ -679,11 +679,11 @@ fx_status fx::leaf_apply(const char* who, const fx_grid* g, const void* d_src, f
                             kPackInterleaved, st);
         fx_status rc;
         if (dt == FX_BF16)
-            rc = out_dt == FX_F32 ? launch_leaf16<__bf16, true>(g, d_src, wpk, d_dst, C_contract, C_produce, zero_row, st)
-                                  : launch_leaf16<__bf16, false>(g, d_src, wpk, d_dst, C_contract, C_produce, zero_row, st);
+            rc = out_dt == FX_F32 ? launch_leaf16<__bf16, true>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, st)
+                                  : launch_leaf16<__bf16, false>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, st);
         else
-            rc = out_dt == FX_F32 ? launch_leaf16<_Float16, true>(g, d_src, wpk, d_dst, C_contract, C_produce, zero_row, st)
-                                  : launch_leaf16<_Float16, false>(g, d_src, wpk, d_dst, C_contract, C_produce, zero_row, st);
+            rc = out_dt == FX_F32 ? launch_leaf16<_Float16, true>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, st)
+                                  : launch_leaf16<_Float16, false>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, st);
         dev_free(wpk, st);
         return rc;
     }
