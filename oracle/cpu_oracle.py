@@ -64,6 +64,8 @@ def lib():
         L.fo_points_to_ijk.argtypes = [vp, i64, vp, vp, vp]
         L.fo_grid_subdivide2.restype = vp
         L.fo_grid_subdivide2.argtypes = [vp]
+        L.fo_grid_pad.restype = vp
+        L.fo_grid_pad.argtypes = [vp, C.c_int]
         _lib = L
     return _lib
 
@@ -139,6 +141,13 @@ class OracleGrid:
     def subdivide2(self) -> "OracleGrid":
         """All 8 children of every voxel (O5)."""
         return OracleGrid(None, None, _handle=lib().fo_grid_subdivide2(self._h))
+
+    def pad(self, r: int = 1) -> "OracleGrid":
+        """Every voxel within Chebyshev distance r of an active one (O7)."""
+        h = lib().fo_grid_pad(self._h, int(r))
+        if not h:
+            raise ValueError("pad needs r >= 0")
+        return OracleGrid(None, None, _handle=h)
 
 
 def output_grid(gin: OracleGrid, kernel_size: int, stride: int) -> OracleGrid:

@@ -66,6 +66,14 @@
  *                         pass keeps -- and 0 for the others
  *          upsampling     gin[o,c] = sum over the active children i of o of gout[i,c]
  *
+ *  O7  padded grid -- Sec. 3.6.2 lists padding beside coarsening and subdivision among the ways to
+ *      make a grid from another; Sec. 3.3 names morphological dilation as the case that changes
+ *      topology.  No formula is printed; the reading taken: padding by r >= 0 voxels activates
+ *      every voxel within Chebyshev distance r of an active one, per grid of the batch,
+ *          S' = { p + d : p in S, d in {-r..r}^3 }
+ *      (r = 1: the voxels a 3x3x3 stencil centred on them reaches S from -- the output set of a
+ *      convolution that is not restricted to the input's voxels).  Written as that union.
+ *
  *  O6  voxel coordinates of points -- Sec. 3.6.2 and Sec. 4.1.1: a grid can be built from
  *      xyz point coordinates as well as from ijk.  No formula is printed; the reading taken:
  *      voxel (i,j,k) is the half-open cell [origin + i*s, origin + (i+1)*s) per axis, so
@@ -516,6 +524,26 @@ fo_grid *fo_grid_subdivide2(const fo_grid *g) {
             q[0] = 2 * g->vox[s].i + ((d >> 2) & 1); q[1] = 2 * g->vox[s].j + ((d >> 1) & 1); q[2] = 2 * g->vox[s].k + (d & 1);
         }
     for (int32_t b = 0; b < g->B; ++b) { jo[2 * b] = 8 * g->base[b]; jo[2 * b + 1] = 8 * g->base[b + 1]; }
+    fo_grid *o = fo_grid_create(c, jo, g->B);
+    free(c); free(jo);
+    return o;
+}
+
+/* O7: the grid of all voxels within Chebyshev distance r of an active voxel; NULL if r < 0 */
+fo_grid *fo_grid_pad(const fo_grid *g, int r) {
+    if (r < 0) return NULL;
+    const int64_t w = 2 * (int64_t)r + 1, w3 = w * w * w;
+    int32_t *c = (int32_t *)malloc(sizeof(int32_t) * 3 * (size_t)(g->N > 0 ? g->N * w3 : 1));
+    int64_t *jo = (int64_t *)malloc(sizeof(int64_t) * 2 * (size_t)(g->B > 0 ? g->B : 1));
+    int64_t n = 0;
+    for (int64_t s = 0; s < g->N; ++s)
+        for (int a = -r; a <= r; ++a)
+            for (int b = -r; b <= r; ++b)
+                for (int d = -r; d <= r; ++d) {
+                    c[3 * n] = g->vox[s].i + a; c[3 * n + 1] = g->vox[s].j + b; c[3 * n + 2] = g->vox[s].k + d;
+                    ++n;
+                }
+    for (int32_t b = 0; b < g->B; ++b) { jo[2 * b] = w3 * g->base[b]; jo[2 * b + 1] = w3 * g->base[b + 1]; }
     fo_grid *o = fo_grid_create(c, jo, g->B);
     free(c); free(jo);
     return o;
