@@ -131,6 +131,14 @@ fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** out);
  * FX_ERANGE beyond 2^31-1 voxels.  Synchronises `stream`. */
 fx_status fx_grid_subdivide2(const fx_grid* g, void* stream, fx_grid** out);
 
+/* The padded grid of Sec. 3.6.2 (a grid made from another by padding; the dilation that Sec. 3.3 names as
+ * the case that changes topology): active set = every voxel within Chebyshev distance r of an active one,
+ * { p + d : p active, d in {-r..r}^3 }, per grid of the batch.  r = 0 gives a copy; r = 1 is the set of sites
+ * a 3x3x3 stencil reaches the grid from.  0 <= r <= 8 (FX_EINVAL below, FX_EUNSUPPORTED above);
+ * FX_ERANGE if (2r+1)^3 * voxels exceeds 2^31-1 or a voxel lies within r of the int32 coordinate limits.
+ * The caller owns *out.  Synchronises `stream`. */
+fx_status fx_grid_pad(const fx_grid* g, int32_t r, void* stream, fx_grid** out);
+
 void fx_grid_retain(fx_grid* g);
 void fx_grid_destroy(fx_grid* g);
 
@@ -151,6 +159,19 @@ void fx_grid_destroy(fx_grid* g);
  */
 fx_status fx_build_kernel_map(fx_grid* g_in, int32_t kernel_size, int32_t stride, void* stream,
                               fx_grid** g_out, fx_kmap** out);
+
+/* The stride-1 map onto a caller-given output grid: map(o,kappa) = index in g_in of voxel p_o + delta_kappa
+ * for the voxels p_o of g_out (same offsets and kappa order as above).  With g_out = fx_grid_pad(g_in, 1) and
+ * K = 3 this is the map of a convolution that is not restricted to the input's voxels: every (input, offset)
+ * pair occurs once, so no product of the dense cross-correlation is dropped (Sec. 3.5 describes the operator
+ * for any pair of input and output index spaces; Sec. 3.6.2 makes the output grid by padding).
+ *   K in {1, 3, 5}; the grids must hold the same number of batch members (FX_EINVAL otherwise); g_out may be
+ *   g_in itself (the submanifold map of fx_build_kernel_map).  The map keeps references to both grids.
+ * All operators that take a stride-1 map accept it: fx_sparse_conv_fwd, fx_sparse_conv_bwd_data,
+ * fx_sparse_conv_bwd_weight, fx_sparse_conv_transpose_fwd.  Between two different grids the tiles hold one row
+ * per pair (no staging of shared rows), and the input gradient and the transposed convolution run over the
+ * map from g_in's voxels into g_out, built on their first call and kept with the map. */
+fx_status fx_build_kernel_map_onto(fx_grid* g_in, fx_grid* g_out, int32_t kernel_size, void* stream, fx_kmap** out);
 
 /* n_out, K^3, number of active (output, offset) pairs and pairs per offset (host [K^3], may
  * be NULL).  Synchronises the stream the map was built on. */

@@ -58,6 +58,8 @@ def _load():
     L.fx_grid_coarsen2.argtypes = [vp, vp, C.POINTER(vp)]
     L.fx_grid_retain.argtypes = [vp]
     L.fx_grid_destroy.argtypes = [vp]
+    L.fx_build_kernel_map_onto.restype = C.c_int
+    L.fx_build_kernel_map_onto.argtypes = [vp, vp, i32, vp, C.POINTER(vp)]
     L.fx_build_kernel_map.restype = C.c_int
     L.fx_build_kernel_map.argtypes = [vp, i32, i32, vp, C.POINTER(vp), C.POINTER(vp)]
     L.fx_kmap_info.restype = C.c_int
@@ -77,6 +79,8 @@ def _load():
     L.fx_sparse_conv_bwd_weight.argtypes = [vp, vp, vp, C.c_int, i32, i32, vp, C.c_int, vp]
     L.fx_grid_subdivide2.restype = C.c_int
     L.fx_grid_subdivide2.argtypes = [vp, vp, C.POINTER(vp)]
+    L.fx_grid_pad.restype = C.c_int
+    L.fx_grid_pad.argtypes = [vp, C.c_int32, vp, C.POINTER(vp)]
     L.fx_sparse_conv_leaf_fwd.restype = C.c_int
     L.fx_sparse_conv_leaf_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
     L.fx_sparse_conv_leaf_bwd_data.restype = C.c_int
@@ -197,6 +201,12 @@ class IndexGrid:
         _check(lib.fx_grid_subdivide2(self._h, _stream(), C.byref(h)))
         return IndexGrid(h.value)
 
+    def pad(self, r: int = 1) -> "IndexGrid":
+        """The grid of all voxels within Chebyshev distance r of an active one."""
+        h = C.c_void_p()
+        _check(lib.fx_grid_pad(self._h, int(r), _stream(), C.byref(h)))
+        return IndexGrid(h.value)
+
 
 def build_index_grid(ijk: torch.Tensor, joffsets) -> IndexGrid:
     """ijk: CUDA int32 [n_rows,3]; joffsets: host int64 [B,2]."""
@@ -270,6 +280,13 @@ def build_kernel_map(g_in: IndexGrid, kernel_size: int, stride: int) -> KernelMa
     _check(lib.fx_build_kernel_map(g_in._h, kernel_size, stride, _stream(), C.byref(hg), C.byref(hk)))
     g_out = IndexGrid(hg.value)
     return KernelMap(hk.value, g_in, g_out, kernel_size, stride)
+
+
+def build_kernel_map_onto(g_in: IndexGrid, g_out: IndexGrid, kernel_size: int) -> KernelMap:
+    """Stride-1 map from the voxels of g_out (any grid of the same batch size) into g_in."""
+    hk = C.c_void_p()
+    _check(lib.fx_build_kernel_map_onto(g_in._h, g_out._h, kernel_size, _stream(), C.byref(hk)))
+    return KernelMap(hk.value, g_in, g_out, kernel_size, 1)
 
 
 def sparse_conv_fwd(kmap: KernelMap, feat: torch.Tensor, weights: torch.Tensor,

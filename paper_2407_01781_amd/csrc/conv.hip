@@ -1129,7 +1129,7 @@ fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, 
     // rows than the tile kernel's LDS holds -- and, at fp32 depths that the tile kernel does not take, almost
     // everywhere.  FVDB_HOTPATH_LEAF_DISPATCH=0 keeps the kernel-map kernels, =1 takes the leaf kernels whenever
     // they serve the shape.
-    if (km->K == 3 && km->stride == 1 && (mode == kWeightsForward || mode == kWeightsMirrored) &&
+    if (km->K == 3 && km->stride == 1 && km->gin == km->gout && (mode == kWeightsForward || mode == kWeightsMirrored) &&
         leaf_shape_supported(in_dt, C_in, C_out) && !(force && force[0] == '1')) {
         const char* ld = getenv("FVDB_HOTPATH_LEAF_DISPATCH");
         const double occupancy = (double)km->n_in / (512.0 * (double)std::max<int64_t>(1, km->gin->hdr.n_leaf));
@@ -1155,9 +1155,10 @@ fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, 
         const size_t wbytes = packed_weight_bytes(km->K3, C_in, C_out, esize);   // a multiple of 64 bytes
         FX_TRY(dev_alloc(&wp, wbytes + 8 * sizeof(int32_t), st));
         int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
-        // strided maps use every input row once: the gather kernel; others: the LDS-staged kernel
+        // maps whose tiles list one row per pair (strided; stride 1 back from a larger grid): the gather kernel;
+        // others: the LDS-staged kernel
         const char* fg = getenv("FVDB_HOTPATH_CONV_GATHER");
-        const bool gather = (fg ? fg[0] == '1' : km->stride != 1) && in_dt != FX_F32 && C_out % kCoutSlice == 0;
+        const bool gather = (fg ? fg[0] == '1' : !map_shares_rows(km)) && in_dt != FX_F32 && C_out % kCoutSlice == 0;
         launch_pack_weights(d_w, wp, km->K3, C_in, C_out, esize, counters, mode, gather ? kPackRows : kPackInterleaved, st);
         hipError_t e = hipGetLastError();
         if (e == hipSuccess && gather) {

@@ -786,8 +786,14 @@ extern "C" fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_go
     hipStream_t st = (hipStream_t)stream;
     if (km->stride == 1) {
         // symmetric map, same grid on both sides: the forward multiply on gout with mirrored offsets
-        // and transposed weights (C_out channels are contracted, C_in produced)
-        return conv_apply(km, d_gout, dt, d_w, C_out, C_in, d_gin, out_dt, st, kWeightsMirrored);
+        // and transposed weights (C_out channels are contracted, C_in produced); between two grids the
+        // same over the map the other way round
+        const fx_kmap* back = km;
+        if (km->gin != km->gout) {
+            FX_TRY(kmap_ensure_inverse(const_cast<fx_kmap*>(km), st));
+            back = km->inverse;
+        }
+        return conv_apply(back, d_gout, dt, d_w, C_out, C_in, d_gin, out_dt, st, kWeightsMirrored);
     }
     if (km->K != km->stride) {
         // 3x3x3 stride 2: an input is shared by up to 8 outputs.  Gather per input through the inverse map

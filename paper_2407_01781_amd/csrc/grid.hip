@@ -722,6 +722,37 @@ __global__ void k_grid_children(TreeView t, int32_t* __restrict__ ijk_out) {
     }
 }
 
+// the (2r+1)^3 voxels p + {-r..r}^3 around every active voxel p, as rows w3*o .. w3*o + w3 - 1 (offset-major as
+// in a kernel map: i slowest); coordinates that leave the int32 range are counted in *bad and written as p
+__global__ void k_grid_padded(TreeView t, int r, int32_t* __restrict__ ijk_out, int32_t* __restrict__ bad) {
+    const int f = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    if (f >= t.n_leaf) return;
+    const int lane = threadIdx.x & 63;
+    const fx_leaf* lf = t.leaf + f;
+    const uint64_t lt = (1ull << lane) - 1;
+    const int w1 = 2 * r + 1;
+    const int64_t w3 = (int64_t)w1 * w1 * w1;
+    int64_t run = lf->offset;
+    for (int w = 0; w < 8; ++w) {
+        const uint64_t m = lf->mask[w];
+        if ((m >> lane) & 1) {
+            const int64_t o = run + __popcll(m & lt);
+            const int64_t i = lf->origin[0] + w, j = lf->origin[1] + (lane >> 3), k = lf->origin[2] + (lane & 7);
+            const bool ok = i - r >= INT32_MIN && i + r <= INT32_MAX && j - r >= INT32_MIN && j + r <= INT32_MAX &&
+                            k - r >= INT32_MIN && k + r <= INT32_MAX;
+            if (!ok) atomicAdd(bad, 1);
+            int32_t* q = ijk_out + 3 * (w3 * o);
+            for (int a = -r; a <= r; ++a)
+                for (int b = -r; b <= r; ++b)
+                    for (int c = -r; c <= r; ++c) {
+                        q[0] = (int32_t)(ok ? i + a : i); q[1] = (int32_t)(ok ? j + b : j); q[2] = (int32_t)(ok ? k + c : k);
+                        q += 3;
+                    }
+        }
+        run += __popcll(m);
+    }
+}
+
 __global__ void k_ijk_to_index(TreeView t, const int32_t* __restrict__ ijk, const int32_t* __restrict__ jidx,
                                int64_t n, int32_t* __restrict__ out) {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1195,6 +1226,57 @@ extern "C" fx_status fx_grid_subdivide2(const fx_grid* g, void* stream, fx_grid*
     rc = build_index_grid_device_joff(d_c, 8 * n, d_joff, g->B, st, &o);
     cleanup();
     if (rc != FX_OK) return rc;
+    *out = o;
+    return FX_OK;
+}
+
+extern "C" fx_status fx_grid_pad(const fx_grid* g, int32_t r, void* stream, fx_grid** out) {
+    if (!g || !out) { set_error("fx_grid_pad: null pointer"); return FX_EINVAL; }
+    if (r < 0) { set_error("fx_grid_pad: negative padding %d", r); return FX_EINVAL; }
+    if (r > 8) { set_error("fx_grid_pad: padding %d is above the supported 8 voxels", r); return FX_EUNSUPPORTED; }
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t n = g->hdr.n_voxels;
+    const int64_t w3 = (int64_t)(2 * r + 1) * (2 * r + 1) * (2 * r + 1);
+    if (w3 * n > 0x7FFFFFFFll) { set_error("fx_grid_pad: more than 2^31-1 candidate voxels"); return FX_ERANGE; }
+    int32_t* d_c = nullptr;
+    int64_t* d_joff = nullptr;
+    // the counter of coordinates that leave the int32 range sits behind the candidates, in the same allocation
+    const size_t c_bytes = (sizeof(int32_t) * 3 * (size_t)std::max<int64_t>(w3 * n, 1) + 15) & ~size_t(15);
+    FX_TRY(dev_alloc((void**)&d_c, c_bytes + 16, st));
+    int32_t* d_bad = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(d_c) + c_bytes);
+    fx_status rc = dev_alloc((void**)&d_joff, sizeof(int64_t) * 2 * (size_t)std::max(g->B, 1), st);
+    if (rc != FX_OK) { dev_free(d_c, st); return rc; }
+    auto cleanup = [&]() { dev_free(d_c, st); dev_free(d_joff, st); };
+    hipError_t e = hipMemsetAsync(d_bad, 0, sizeof(int32_t), st);
+    if (e == hipSuccess && g->hdr.n_leaf > 0) {
+        const int64_t threads = (int64_t)g->hdr.n_leaf * 64;
+        ProfScope ps(kProfGridIjk, st);
+        k_grid_padded<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(g->view(), r, d_c, d_bad);
+        e = hipGetLastError();
+    }
+    if (e != hipSuccess) { cleanup(); set_error("fx_grid_pad: launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
+    if (g->B > 0) {
+        void* stage = nullptr;
+        rc = host_staging(&stage, sizeof(int64_t) * 2 * (size_t)g->B, 1);
+        if (rc != FX_OK) { cleanup(); return rc; }
+        int64_t* hj = (int64_t*)stage;
+        for (int b = 0; b < g->B; ++b) { hj[2 * b] = w3 * g->h_vox_base[b]; hj[2 * b + 1] = w3 * g->h_vox_base[b + 1]; }
+        e = hipMemcpyAsync(d_joff, stage, sizeof(int64_t) * 2 * (size_t)g->B, hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) { cleanup(); set_error("joffsets upload failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
+    }
+    fx_grid* o = nullptr;
+    rc = build_index_grid_device_joff(d_c, w3 * n, d_joff, g->B, st, &o);     // synchronises the stream
+    int32_t bad = 0;
+    if (rc == FX_OK) {
+        e = hipMemcpy(&bad, d_bad, sizeof(int32_t), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) { rc = FX_EDEVICE; set_error("read-back failed: %s", hipGetErrorString(e)); }
+    }
+    cleanup();
+    if (rc == FX_OK && bad > 0) {
+        set_error("fx_grid_pad: %d voxels lie within %d of the int32 coordinate limits", bad, r);
+        rc = FX_ERANGE;
+    }
+    if (rc != FX_OK) { if (o) fx_grid_destroy(o); return rc; }
     *out = o;
     return FX_OK;
 }

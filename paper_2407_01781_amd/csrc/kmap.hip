@@ -320,8 +320,10 @@ __device__ __forceinline__ int select64(uint64_t m, int r) {
 
 // One workgroup per tile of kTileT consecutive outputs: lookups (one thread per voxel, straight
 // into LDS), mask sort, row de-duplication, block emission.  SUBM: input grid == output grid, so the
-// tile's own index range is the window; otherwise the tile is "direct".
-template <int K, bool SUBM, bool INV = false>
+// tile's own index range is the window; otherwise there is no window.  DEDUP: rows outside the window are
+// de-duplicated in the halo table (a stride-1 map between two grids: no window, all rows in the table);
+// without it the tile is "direct".
+template <int K, bool SUBM, bool INV = false, bool DEDUP = SUBM>
 __global__ void __launch_bounds__(kPackThreads)
 k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict__ leaf_nbr,
               const int32_t* __restrict__ tile_first_leaf, int64_t n_out, TileHeader* __restrict__ tile_hdr,
@@ -508,7 +510,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     const int32_t win_lo = SUBM ? (int32_t)o0 : 0;
     const int32_t win_n = SUBM ? n_valid : 0;
     // rows outside the window go into the halo table; an entry that is in becomes -1024 - (table slot)
-    for (uint32_t hm = SUBM ? hmask : 0u; hm; hm &= hm - 1) {
+    for (uint32_t hm = DEDUP ? hmask : 0u; hm; hm &= hm - 1) {
         const int kappa = __ffs(hm) - 1;
         const int32_t r = L.nb[tid * K3 + kappa];
         uint32_t h = ((uint32_t)r * 0x9E3779B1u) >> 21;  // 11 bits
@@ -532,7 +534,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     }
     S.slot_mask[tid] = mask;
     __syncthreads();
-    const bool direct = !SUBM || L.overflow != 0;
+    const bool direct = !DEDUP || L.overflow != 0;
     const int n_halo = direct ? 0 : L.n_halo;
 
     FX_KSTAMP(2);
@@ -828,6 +830,20 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     return FX_OK;
 }
 
+extern "C" fx_status fx_build_kernel_map_onto(fx_grid* g_in, fx_grid* g_out, int32_t K, void* stream, fx_kmap** out) {
+    if (!g_in || !g_out || !out) { set_error("fx_build_kernel_map_onto: null pointer"); return FX_EINVAL; }
+    if (K != 1 && K != 3 && K != 5) {
+        set_error("fx_build_kernel_map_onto: kernel size %d is not supported (stride 1: 1, 3, 5)", K);
+        return K >= 1 ? FX_EUNSUPPORTED : FX_EINVAL;
+    }
+    if (g_in->B != g_out->B) {
+        set_error("fx_build_kernel_map_onto: the grids hold %d and %d batch members", g_in->B, g_out->B);
+        return FX_EINVAL;
+    }
+    fx_grid_retain(g_out);
+    return build_map(g_in, g_out, K, 1, false, (hipStream_t)stream, out);    // takes over that reference
+}
+
 // The map from the voxels of `gout` (the rows that are produced) to the voxels of `g_in` (the rows that are
 // looked up).  Takes over the caller's reference to gout and retains g_in.  inverse: see k_leaf_neighbors.
 fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool inverse, hipStream_t st, fx_kmap** out) {
@@ -895,9 +911,16 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
                                                                      km->d_tile_blocks, km->block_stride,      \
                                                                      stats);                                   \
     } while (0)
-        if (K == 1) FX_TILES(1, true);
+        const bool same_grid = g_in == gout;      // a stride-1 map onto another grid has no window of its own rows
+        if (K == 1 && same_grid) FX_TILES(1, true);
+        else if (K == 1) FX_TILES(1, false);
         else if (K == 2) FX_TILES(2, false);
-        else if (stride == 1) FX_TILES(3, true);
+        else if (stride == 1 && same_grid) FX_TILES(3, true);
+        // between two grids: when the outputs outnumber the inputs 2:1 (a padded output grid), a tile's outputs share
+        // few input rows and all of them go through the halo table; otherwise (the map back) a tile reaches more
+        // rows than the table holds and keeps one row per pair
+        else if (stride == 1 && map_shares_rows(km)) FX_TILES(3, false, false, true);
+        else if (stride == 1) FX_TILES(3, false);
         else if (inverse) FX_TILES(3, false, true);
         else FX_TILES(3, false);      // 3x3x3 stride 2: windows overlap, still no input row inside the tile's own range
 #undef FX_TILES
@@ -919,11 +942,14 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
 
 // The inverse of a 3x3x3 stride-2 map as a tiled map of its own: produced rows = the fine voxels, looked-up
 // rows = the coarse voxels, offset kappa of a fine voxel = the coarse voxel whose offset kappa lands on it.
+// The inverse of a stride-1 map between two different grids is the ordinary stride-1 map the other way round
+// with the offsets mirrored (input p is linked to output p - delta), so its users mirror the weights.
 fx_status fx::kmap_ensure_inverse(fx_kmap* km, hipStream_t st) {
     if (km->inverse) return FX_OK;
-    if (km->K != 3 || km->stride != 2 || km->is_inverse) { set_error("no inverse map for this (kernel, stride)"); return FX_EUNSUPPORTED; }
+    const bool strided3 = km->K == 3 && km->stride == 2, onto = km->stride == 1 && km->gin != km->gout;
+    if (!(strided3 || onto) || km->is_inverse) { set_error("no inverse map for this (kernel, stride)"); return FX_EUNSUPPORTED; }
     fx_grid_retain(km->gin);                  // build_map takes over one reference to the grid of the produced rows
-    return build_map(km->gout, km->gin, 3, 2, true, st, &km->inverse);
+    return build_map(km->gout, km->gin, km->K, km->stride, strided3, st, &km->inverse);
 }
 
 fx_status fx::kmap_fetch_stats(fx_kmap* km) {

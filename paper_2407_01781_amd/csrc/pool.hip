@@ -307,8 +307,14 @@ extern "C" fx_status fx_sparse_conv_transpose_fwd(const fx_kmap* km, const void*
     }
     if (km->n_in == 0) return FX_OK;
     hipStream_t st = (hipStream_t)stream;
-    if (km->stride == 1)   // symmetric map: the forward multiply over the mirrored offsets
-        return conv_apply(km, d_feat, dt, d_w, C_in, C_out, d_out, out_dt, st, kWeightsFlipped);
+    if (km->stride == 1) {  // symmetric map: the forward multiply over the mirrored offsets (between two grids: of the map back)
+        const fx_kmap* back = km;
+        if (km->gin != km->gout) {
+            FX_TRY(kmap_ensure_inverse(const_cast<fx_kmap*>(km), st));
+            back = km->inverse;
+        }
+        return conv_apply(back, d_feat, dt, d_w, C_in, C_out, d_out, out_dt, st, kWeightsFlipped);
+    }
     if (km->K != km->stride) {
         // 3x3x3 stride 2: inputs are shared by up to 8 outputs; the forward kernels of strided maps over the
         // inverse map, weights as given
