@@ -300,6 +300,27 @@ def main():
         points_build["frac_of_hbm_peak"] = points_build["GBs"] / HBM_PEAK_GBS
         del gp, d_xyz
 
+    # ---- convolution onto the padded grid (Sec. 3.6.2: a grid made by padding; the output set of a 3x3x3 convolution
+    # that is not restricted to the input's voxels): grid padding, the map onto it, forward and both gradients at
+    # the workload's channels (not part of `value`)
+    padded_output = None
+    if not args.no_low_depth and (w.kernel_size, w.stride) == (3, 1):
+        gpad = g.pad(1)
+        t_pad = b2b(lambda: g.pad(1), reps=3)
+        kmp = fx.build_kernel_map_onto(g, gpad, 3)
+        t_kmp = b2b(lambda: fx.build_kernel_map_onto(g, gpad, 3), reps=3)
+        p_pairs = kmp.info()[0]
+        d_gyp = torch.randn((gpad.num_voxels, w.c_out), device="cuda").to(tdt).contiguous()
+        t_pf = b2b(lambda: fx.sparse_conv_fwd(kmp, d_feat, d_w), reps=5)
+        t_pd = b2b(lambda: fx.sparse_conv_bwd_data(kmp, d_gyp, d_w), reps=5)
+        t_pw = b2b(lambda: fx.sparse_conv_bwd_weight(kmp, d_feat, d_gyp), reps=5)
+        p_flops = 2.0 * p_pairs * w.c_in * w.c_out
+        padded_output = {"n_voxels_padded": gpad.num_voxels, "n_leaves_padded": gpad.counts()[0], "active_pairs": p_pairs,
+                         "grid_pad_ms": t_pad, "kernel_map_onto_ms": t_kmp, "conv_ms": t_pf,
+                         "conv_effective_TFLOPs": p_flops / (t_pf * 1e-3) / 1e12,
+                         "bwd_data_ms": t_pd, "bwd_weight_ms": t_pw}
+        del kmp, gpad, d_gyp
+
     # ---- the paper's timing protocol (Sec. 4.1: one warm-up, five timed runs, mean of the best
     # four), cold = a 768 MiB scratch buffer is overwritten before every run so that neither the
     # L2s nor the 256 MB last-level cache hold the operands, warm = no flush
@@ -384,6 +405,7 @@ def main():
         "encoder_decoder_ops": ops,
         "low_depth": low_depth,
         "grid_from_points": points_build,
+        "padded_output": padded_output,
         "kernels_ms_per_launch": kern_ms,
         "kernels_ms_per_step": per_step_ms,
         "roofline": roof,
