@@ -329,9 +329,23 @@ fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_feat, fx_dtype
  *   d_gout [N, C_out] dtype dt, d_w [27, C_in, C_out] (the forward layout), d_gin [N, C_in] dtype out_dt.
  * Supported shapes: the forward's with the roles of C_in and C_out exchanged (fp32: C_out in
  * {4, 8, 12, 16}, C_in a multiple of 4 up to 32; FX_F16 / FX_BF16: C_out % 32 == 0, C_in % 64 == 0); others
- * FX_EUNSUPPORTED.  The weight gradient has no map-free form here: fx_sparse_conv_bwd_weight on a kernel map. */
+ * FX_EUNSUPPORTED. */
 fx_status fx_sparse_conv_leaf_bwd_data(const fx_grid* g, const void* d_gout, fx_dtype dt, const void* d_w,
                                        int32_t C_in, int32_t C_out, void* d_gin, fx_dtype out_dt, void* stream);
+
+/* Weight gradient of the same convolution without a kernel map (fp32, low depth):
+ *     gw[kappa,:,:] = sum over voxels o whose neighbour i at offset kappa is active of  feat[i,:]^T gout[o,:]
+ * with the voxels as the contracted dimension of the matrix instructions, straight from the leaf window; same
+ * result as fx_sparse_conv_bwd_weight on the (3,1) map of g.
+ *   d_feat [N, C_in] and d_gout [N, C_out] device, dtype dt, 16-byte aligned; d_gw [27, C_in, C_out] device,
+ *   dtype out_dt; every element is written (zeros for an empty grid).
+ * Supported: dt = FX_F32 with C_in in {4, 8} and C_out a multiple of 4 up to 32, or C_in in {12, 16} and C_out a
+ * multiple of 4 up to 16; out_dt = FX_F32 (or dt); others FX_EUNSUPPORTED.  True fp32 products, fp32 sums in a
+ * fixed order (leaves in fixed ranges per workgroup, the workgroups' partial sums added in index order): repeated
+ * calls give identical bits.  Allocates the partial sums (one [27, C_in, C_out] fp32 block per workgroup, at
+ * most a few thousand) for the call.  Does not synchronise. */
+fx_status fx_sparse_conv_leaf_bwd_weight(const fx_grid* g, const void* d_feat, const void* d_gout, fx_dtype dt,
+                                         int32_t C_in, int32_t C_out, void* d_gw, fx_dtype out_dt, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Measurement support (the paper's protocol, Sec. 4.1: per-operator times).  While enabled,

@@ -83,6 +83,8 @@ def _load():
     L.fx_grid_pad.argtypes = [vp, C.c_int32, vp, C.POINTER(vp)]
     L.fx_sparse_conv_leaf_fwd.restype = C.c_int
     L.fx_sparse_conv_leaf_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
+    L.fx_sparse_conv_leaf_bwd_weight.restype = C.c_int
+    L.fx_sparse_conv_leaf_bwd_weight.argtypes = [vp, vp, vp, C.c_int, i32, i32, vp, C.c_int, vp]
     L.fx_sparse_conv_leaf_bwd_data.restype = C.c_int
     L.fx_sparse_conv_leaf_bwd_data.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
     L.fx_sparse_conv_transpose_fwd.restype = C.c_int
@@ -374,6 +376,20 @@ def sparse_conv_leaf_bwd_data(grid: IndexGrid, grad_out: torch.Tensor, weights: 
     _check(lib.fx_sparse_conv_leaf_bwd_data(grid._h, _ptr(grad_out), _TORCH_DT[grad_out.dtype], _ptr(weights), c_in, c_out,
                                             _ptr(gin), _TORCH_DT[out_dtype], _stream()))
     return gin
+
+
+def sparse_conv_leaf_bwd_weight(grid: IndexGrid, feat: torch.Tensor, grad_out: torch.Tensor,
+                                out_dtype: Optional[torch.dtype] = None) -> torch.Tensor:
+    """Weight gradient of sparse_conv_leaf_fwd: feat [N, C_in], grad_out [N, C_out] -> [27, C_in, C_out]."""
+    assert feat.is_cuda and grad_out.is_cuda and feat.is_contiguous() and grad_out.is_contiguous()
+    assert feat.dtype == grad_out.dtype and feat.dtype in _TORCH_DT
+    assert feat.shape[0] == grid.num_voxels and grad_out.shape[0] == grid.num_voxels
+    c_in, c_out = feat.shape[1], grad_out.shape[1]
+    out_dtype = out_dtype or feat.dtype
+    gw = torch.empty((27, c_in, c_out), dtype=out_dtype, device="cuda")
+    _check(lib.fx_sparse_conv_leaf_bwd_weight(grid._h, _ptr(feat), _ptr(grad_out), _TORCH_DT[feat.dtype], c_in, c_out,
+                                              _ptr(gw), _TORCH_DT[out_dtype], _stream()))
+    return gw
 
 
 def pool2(kmap: KernelMap, feat: torch.Tensor, mode: str = "max") -> torch.Tensor:

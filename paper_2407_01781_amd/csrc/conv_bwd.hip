@@ -805,6 +805,30 @@ extern "C" fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_go
     return strided_pair_product(km, d_gout, dt, d_w, C_out, C_in, d_gin, out_dt, st, kWeightsTransposed);
 }
 
+// Adds the ranges of part[n_ranges][total] in ascending order into gw; above 128 ranges in two levels (groups of
+// 64, then the groups), so that the first level runs at full occupancy.  The bracketing depends on n_ranges only.
+fx_status fx::wgrad_reduce_ranges(const float* part, int n_ranges, int64_t total, void* gw, fx_dtype out_dt, hipStream_t st) {
+    constexpr int kReduceGroup = 64;
+    hipError_t e;
+    if (n_ranges > 2 * kReduceGroup) {
+        float* part2 = nullptr;
+        const int n_groups = (n_ranges + kReduceGroup - 1) / kReduceGroup;
+        FX_TRY(dev_alloc((void**)&part2, sizeof(float) * (size_t)total * n_groups, st));
+        const dim3 grid((unsigned)std::min<int64_t>((total + 255) / 256, 1 << 16), (unsigned)n_groups);
+        {
+            ProfScope ps(kProfWgradReduce, st);
+            k_wgrad_reduce_groups<<<grid, 256, 0, st>>>(part, n_ranges, total, kReduceGroup, part2);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = launch_reduce(part2, n_groups, total, gw, out_dt, st);
+        dev_free(part2, st);
+    } else {
+        e = launch_reduce(part, n_ranges, total, gw, out_dt, st);
+    }
+    if (e != hipSuccess) { set_error("weight-gradient reduction failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
+    return FX_OK;
+}
+
 extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_feat, const void* d_gout, fx_dtype dt,
                                                int32_t C_in, int32_t C_out, void* d_gw, fx_dtype out_dt, void* stream) {
     if (!km || !d_gw || C_in < 1 || C_out < 1 || (km->n_in > 0 && !d_feat) || (km->n_out > 0 && !d_gout)) {
@@ -817,6 +841,15 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
     if (km->n_out == 0) {   // no pairs: the gradient is zero
         FX_HIP_TRY(launch_reduce(nullptr, 0, total, d_gw, out_dt, st));
         return FX_OK;
+    }
+    // fp32 at low depth on a 3x3x3 submanifold map: the leaf-window kernel sums on the matrix units straight from
+    // the grid, where everything below would take the scalar kernel (FVDB_HOTPATH_LEAF_DISPATCH=0 keeps that one)
+    if (km->K == 3 && km->stride == 1 && km->gin == km->gout && leaf_wgrad_shape_supported(dt, C_in, C_out) &&
+        !force_scalar()) {
+        const char* ld = getenv("FVDB_HOTPATH_LEAF_DISPATCH");
+        if (!(ld && ld[0] == '0'))
+            return leaf_wgrad("sparse convolution weight gradient (leaf-window kernel)", km->gin, d_feat, d_gout, dt, C_in,
+                              C_out, d_gw, out_dt, st);
     }
     const bool mfma = dt != FX_F32 && km->n_tiles > 0 && C_in % kWgCi == 0 && C_out % kWgCo == 0 && !force_scalar();
     float* part = nullptr;
@@ -855,22 +888,9 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
         else k_wgrad_scalar<FX_BF16><<<grid, 256, 0, st>>>(km->d_nbmap, km->n_out, km->K3, d_feat, d_gout, C_in, C_out, n_ranges, part);
         e = hipGetLastError();
     }
-    float* part2 = nullptr;
-    constexpr int kReduceGroup = 64;
-    if (e == hipSuccess && n_ranges > 2 * kReduceGroup) {
-        const int n_groups = (n_ranges + kReduceGroup - 1) / kReduceGroup;
-        fx_status rc2 = dev_alloc((void**)&part2, sizeof(float) * (size_t)total * n_groups, st);
-        if (rc2 != FX_OK) { dev_free(part, st); return rc2; }
-        const dim3 grid((unsigned)std::min<int64_t>((total + 255) / 256, 1 << 16), (unsigned)n_groups);
-        ProfScope ps(kProfWgradReduce, st);
-        k_wgrad_reduce_groups<<<grid, 256, 0, st>>>(part, n_ranges, total, kReduceGroup, part2);
-        e = hipGetLastError();
-        if (e == hipSuccess) e = launch_reduce(part2, n_groups, total, d_gw, out_dt, st);
-        dev_free(part2, st);
-    } else if (e == hipSuccess) {
-        e = launch_reduce(part, n_ranges, total, d_gw, out_dt, st);
-    }
+    fx_status rc_red = FX_OK;
+    if (e == hipSuccess) rc_red = wgrad_reduce_ranges(part, n_ranges, total, d_gw, out_dt, st);
     dev_free(part, st);
     if (e != hipSuccess) { set_error("weight-gradient launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
-    return FX_OK;
+    return rc_red;
 }

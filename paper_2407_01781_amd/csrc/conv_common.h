@@ -150,6 +150,17 @@ inline bool leaf_shape_supported(fx_dtype dt, int C_contract, int C_produce) {
     return C_contract % 32 == 0 && C_produce % 64 == 0;
 }
 
+// Weight gradient of the 3x3x3 submanifold convolution from the leaf window (fp32, low depth), and the ordered
+// reduction of per-range partial sums part[n_ranges][total] into gw that all weight-gradient kernels end with
+// (n_ranges = 0: gw = 0).
+fx_status leaf_wgrad(const char* who, const fx_grid* g, const void* d_feat, const void* d_gout, fx_dtype dt, int32_t C_in,
+                     int32_t C_out, void* d_gw, fx_dtype out_dt, hipStream_t st);
+inline bool leaf_wgrad_shape_supported(fx_dtype dt, int C_in, int C_out) {
+    if (dt != FX_F32 || C_out < 4 || C_out % 4) return false;
+    return ((C_in == 4 || C_in == 8) && C_out <= 32) || ((C_in == 12 || C_in == 16) && C_out <= 16);
+}
+fx_status wgrad_reduce_ranges(const float* part, int n_ranges, int64_t total, void* gw, fx_dtype out_dt, hipStream_t st);
+
 // The same sum through a dense table [n_rows, K3] of source rows (-1: none), one thread per output element
 // (or per four): out[r,:] = sum over kappa with table[r][kappa] >= 0 of src[table[r][kappa],:] . W'[kappa], W' read
 // from the caller's weights as `mode` says.  Serves maps without a tiled form and the inverse table.

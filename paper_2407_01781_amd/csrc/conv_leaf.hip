@@ -333,6 +333,199 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
 #endif
 }
 
+// ---------------------------------------------------------------------------------- weight gradient, fp32, low depth
+// gw[kappa][ci][co] = sum over active voxels o with an active neighbour at tap kappa of
+// feat[nb(o,kappa)][ci] * gout[o][co] (the derivative of the forward sum in the weights), from the same leaf
+// window: the voxels are the contracted dimension of v_mfma_f32_16x16x4_f32, four per instruction.  Lane
+// (v = l % 16, q = l / 16) supplies, for the q-th voxel of a quad, one window value as A (row v) and one gout
+// value as B (column v = output channel).  The 16 rows hold 16 / C_in taps side by side (C_in = 8: two taps,
+// C_in = 4: four), so the 27 taps take ceil(27 / taps-per-instruction) multiplies per quad and as many
+// accumulator tiles, which a wave keeps in registers over all its leaves.  An inactive neighbour is a zero
+// window cell and adds nothing.  Quads are dealt to the four waves round-robin and leaves to workgroups in
+// fixed ranges; the waves' sums are added in wave order, the workgroups' partial sums in index order by the
+// ordered reduction that the other weight-gradient kernels use: repeated calls give identical bits.
+template <int C_IN> struct WgLeafShape {
+    static constexpr int kTapsPer = C_IN <= 4 ? 4 : (C_IN <= 8 ? 2 : 1);
+    static constexpr int kGroups = (27 + kTapsPer - 1) / kTapsPer;
+    // waves per SIMD the register budget is set for: the accumulators take 4 * kGroups * NT registers
+    static constexpr int waves_per_simd(int NT) { return 4 * kGroups * NT <= 32 ? 4 : (4 * kGroups * NT <= 64 ? 3 : 2); }
+};
+
+template <int C_IN, int NT>
+__global__ __launch_bounds__(kLeafThreads, WgLeafShape<C_IN>::waves_per_simd(NT)) void k_wgrad_leaf(TreeView t, const float* __restrict__ feat,
+                                                             const float* __restrict__ gout, int C_out, int64_t n_voxels,
+                                                             float* __restrict__ part) {
+    constexpr int J = C_IN / 4, TPI = WgLeafShape<C_IN>::kTapsPer, NG = WgLeafShape<C_IN>::kGroups;
+    extern __shared__ __align__(16) unsigned char smem[];
+    LeafLds& L = *reinterpret_cast<LeafLds*>(smem);
+    float* win = reinterpret_cast<float*>(smem + ((sizeof(LeafLds) + 15) & ~size_t(15)));   // [cell][C_IN]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int v = lane & 15, q = lane >> 4;
+    const int sub = v / C_IN, ci = v % C_IN;                 // the lane's tap within a group, its input channel
+    const bool row_ok = v < TPI * C_IN;                      // C_IN = 12: rows 12..15 stay zero
+
+    f32x4 acc[NG][NT];
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[g][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (wave < 2) {
+        const int64_t first_index = t.leaf[0].offset;
+        const int64_t total = kLeafFixedCost * t.n_leaf + n_voxels;
+        const int b = blockIdx.x + wave;
+        const int f = b >= (int)gridDim.x ? t.n_leaf
+                                          : first_leaf_at_cost<kLeafFixedCost>(t, first_index, total * b / (int64_t)gridDim.x, lane);
+        if (lane == 0) L.range[wave] = f;
+    }
+    __syncthreads();
+    const int f_begin = L.range[0], f_end = L.range[1];
+    if (wave == kLeafWaves - 1 && f_begin < f_end) stage_records(t, L, f_begin, lane);
+    __syncthreads();
+
+    for (int f = f_begin; f < f_end; ++f) {
+        // ---- densify: as in k_conv_leaf
+        {
+            f32x4 val[(kWinCells + kLeafThreads - 1) / kLeafThreads][J];
+            bool on[(kWinCells + kLeafThreads - 1) / kLeafThreads];
+#pragma unroll
+            for (int it = 0; it < (kWinCells + kLeafThreads - 1) / kLeafThreads; ++it) {
+                int cell = min(tid + it * kLeafThreads, kWinCells - 1);
+                asm volatile("" : "+v"(cell));
+                const int x = cell / 100, y = (cell / 10) % 10, z = cell % 10;
+                const int slot = ((x + 7) >> 3) * 9 + ((y + 7) >> 3) * 3 + ((z + 7) >> 3);
+                const int row = staged_value(L, slot, (x - 1) & 7, (y - 1) & 7, (z - 1) & 7);
+                on[it] = row >= 0;
+                const f32x4* src = reinterpret_cast<const f32x4*>(feat + (int64_t)max(row, 0) * C_IN);
+#pragma unroll
+                for (int c4 = 0; c4 < J; ++c4) val[it][c4] = src[c4];
+            }
+#pragma unroll
+            for (int it = 0; it < (kWinCells + kLeafThreads - 1) / kLeafThreads; ++it) {
+                const int cell = tid + it * kLeafThreads;
+                if (cell < kWinCells) {
+                    f32x4* dst = reinterpret_cast<f32x4*>(win + cell * C_IN);
+#pragma unroll
+                    for (int c4 = 0; c4 < J; ++c4) dst[c4] = on[it] ? val[it][c4] : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+            // the leaf's active voxels in index order (reads the centre record only)
+#pragma unroll
+            for (int it = 0; it < 512 / kLeafThreads; ++it) {
+                int m = tid + it * kLeafThreads;
+                asm volatile("" : "+v"(m));
+                const int lx = m >> 6, ly = (m >> 3) & 7, lz = m & 7;
+                const int row = staged_value(L, 13, lx, ly, lz);
+                if (row >= 0) L.cell_of_rank[row - L.offset[13]] = (uint16_t)window_cell(lx + 1, ly + 1, lz + 1);
+            }
+        }
+        const int n_act = uni((int)((L.prefix[13] >> 54) & 511) + __popcll(L.mask[13][7]));
+        const int64_t base = uni(L.offset[13]);
+        __syncthreads();
+
+        if (wave == kLeafWaves - 1 && f + 1 < f_end) stage_records(t, L, f + 1, lane);
+        {
+            const int n_quads = (n_act + 3) >> 2;
+            const float* gp = gout + base * C_out + v;
+            // the next quad's cell and gout values are requested before the current quad's multiplies
+            int cell_n = 0;
+            float b_n[NT];
+            auto fetch = [&](int qd) {
+                const int r = qd * 4 + q;
+                cell_n = L.cell_of_rank[min(r, n_act - 1)];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    b_n[nt] = (r < n_act && 16 * nt + v < C_out) ? gp[(int64_t)r * C_out + 16 * nt] : 0.f;
+            };
+            if (wave < n_quads) fetch(wave);
+            for (int qd = wave; qd < n_quads; qd += kLeafWaves) {
+                const float* fp = win + cell_n * C_IN + ci;
+                float b[NT];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) b[nt] = b_n[nt];
+                if (qd + kLeafWaves < n_quads) fetch(qd + kLeafWaves);
+#pragma unroll
+                for (int g = 0; g < NG; ++g) {
+                    const int kappa = g * TPI + sub;                   // < 27 + TPI
+                    const bool ok = row_ok && kappa < 27;
+                    const float a = ok ? fp[tap_delta(min(kappa, 26)) * C_IN] : 0.f;
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[g][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[nt], acc[g][nt], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();                 // the window and the records are rewritten for the next leaf
+    }
+
+    // ---- the four waves' sums, added in wave order through LDS (the window is free now)
+    float* red = win;                    // [NG][NT][64 lanes][4]
+    for (int w = 1; w < kLeafWaves; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) *reinterpret_cast<f32x4*>(red + ((g * NT + nt) * 64 + lane) * 4) = acc[g][nt];
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const f32x4 o = *reinterpret_cast<const f32x4*>(red + ((g * NT + nt) * 64 + lane) * 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[g][nt][e] += o[e];
+                }
+        }
+        __syncthreads();
+    }
+    if (wave == 0) {
+        // accumulator register e of lane (v, q) is row 4 q + e (tap sub-slot and input channel), column v
+        float* dst = part + (int64_t)blockIdx.x * 27 * C_IN * C_out;
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int row = 4 * q + e;
+                const int kappa = g * TPI + row / C_IN, c = row % C_IN;
+                if (row < TPI * C_IN && kappa < 27) {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        if (16 * nt + v < C_out) dst[(kappa * C_IN + c) * C_out + 16 * nt + v] = acc[g][nt][e];
+                }
+            }
+    }
+}
+
+template <int C_IN, int NT>
+fx_status launch_wgrad_leaf(const fx_grid* g, const float* feat, const float* gout, int C_out, void* gw, fx_dtype out_dt,
+                            hipStream_t st) {
+    constexpr int NG = WgLeafShape<C_IN>::kGroups;
+    static_assert((size_t)NG * NT * 64 * 4 <= (size_t)kWinCells * C_IN, "the waves' sums are exchanged through the window");
+    const size_t lds = ((sizeof(LeafLds) + 15) & ~size_t(15)) + sizeof(float) * (size_t)kWinCells * C_IN;
+    static int per_cu = 0;
+    if (per_cu == 0) {
+        FX_HIP_TRY(hipFuncSetAttribute((const void*)k_wgrad_leaf<C_IN, NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        int n = 0;
+        FX_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_wgrad_leaf<C_IN, NT>, kLeafThreads, lds));
+        per_cu = std::max(1, n);
+    }
+    const int n_wg = (int)std::min<int64_t>(g->hdr.n_leaf, (int64_t)per_cu * compute_units());
+    const int64_t total = (int64_t)27 * C_IN * C_out;
+    float* part = nullptr;
+    FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * n_wg, st));
+    {
+        ProfScope ps(kProfWgrad, st);
+        k_wgrad_leaf<C_IN, NT><<<n_wg, kLeafThreads, lds, st>>>(g->view(), feat, gout, C_out, g->hdr.n_voxels, part);
+    }
+    fx_status rc = FX_OK;
+    if (hipGetLastError() != hipSuccess) { set_error("leaf-window weight gradient: launch failed"); rc = FX_EDEVICE; }
+    if (rc == FX_OK) rc = wgrad_reduce_ranges(part, n_wg, total, gw, out_dt, st);
+    dev_free(part, st);
+    return rc;
+}
+
 // ---------------------------------------------------------------------------------- 16-bit types, depth >= 32
 // The same leaf window for f16 / bf16 at C_in % 32 == 0, C_out % 64 == 0: the regime of locally dense
 // grids at moderate depth (Sec. 3.5 scenario 2 serves it with dense 4x2x2 bricks; here the window stays
@@ -709,6 +902,40 @@ fx_status fx::leaf_apply(const char* who, const fx_grid* g, const void* d_src, f
     }
 #undef FX_LEAF
     return FX_EINVAL;
+}
+
+fx_status fx::leaf_wgrad(const char* who, const fx_grid* g, const void* d_feat, const void* d_gout, fx_dtype dt, int32_t C_in,
+                         int32_t C_out, void* d_gw, fx_dtype out_dt, hipStream_t st) {
+    if (!g || !d_gw || C_in < 1 || C_out < 1 || (g->hdr.n_voxels > 0 && (!d_feat || !d_gout))) {
+        set_error("%s: null pointer or non-positive channel count", who);
+        return FX_EINVAL;
+    }
+    if (dt != FX_F32 && dt != FX_F16 && dt != FX_BF16) { set_error("unknown input dtype"); return FX_EINVAL; }
+    if (out_dt != dt && out_dt != FX_F32) {
+        set_error("output dtype must equal the input dtype or be fp32");
+        return FX_EUNSUPPORTED;
+    }
+    if (!leaf_wgrad_shape_supported(dt, C_in, C_out)) {
+        set_error("%s: serves fp32 with 4 or 8 input channels and a multiple of 4 up to 32 output channels, or 12 or 16 input "
+                  "and up to 16 output channels (got %d -> %d); use the kernel-map path", who, C_in, C_out);
+        return FX_EUNSUPPORTED;
+    }
+    const float* x = (const float*)d_feat;
+    const float* gy = (const float*)d_gout;
+    if (g->hdr.n_voxels == 0) return wgrad_reduce_ranges(nullptr, 0, (int64_t)27 * C_in * C_out, d_gw, out_dt, st);
+    const bool wide = C_out > 16;
+    switch (C_in) {
+        case 4: return wide ? launch_wgrad_leaf<4, 2>(g, x, gy, C_out, d_gw, out_dt, st) : launch_wgrad_leaf<4, 1>(g, x, gy, C_out, d_gw, out_dt, st);
+        case 8: return wide ? launch_wgrad_leaf<8, 2>(g, x, gy, C_out, d_gw, out_dt, st) : launch_wgrad_leaf<8, 1>(g, x, gy, C_out, d_gw, out_dt, st);
+        case 12: return launch_wgrad_leaf<12, 1>(g, x, gy, C_out, d_gw, out_dt, st);
+        case 16: return launch_wgrad_leaf<16, 1>(g, x, gy, C_out, d_gw, out_dt, st);
+    }
+    return FX_EINVAL;
+}
+
+extern "C" fx_status fx_sparse_conv_leaf_bwd_weight(const fx_grid* g, const void* d_feat, const void* d_gout, fx_dtype dt,
+                                                    int32_t C_in, int32_t C_out, void* d_gw, fx_dtype out_dt, void* stream) {
+    return leaf_wgrad("fx_sparse_conv_leaf_bwd_weight", g, d_feat, d_gout, dt, C_in, C_out, d_gw, out_dt, (hipStream_t)stream);
 }
 
 extern "C" fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_feat, fx_dtype dt, const void* d_w,

@@ -65,6 +65,8 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert b"fx_sparse_conv_leaf_fwd" in lib.fx_last_error()
     assert lib.fx_sparse_conv_leaf_bwd_data(None, None, 0, None, 16, 8, None, 0, None) == -1
     assert b"fx_sparse_conv_leaf_bwd_data" in lib.fx_last_error()
+    assert lib.fx_sparse_conv_leaf_bwd_weight(None, None, None, 0, 8, 16, None, 0, None) == -1
+    assert b"fx_sparse_conv_leaf_bwd_weight" in lib.fx_last_error()
     assert lib.fx_grid_pad(None, 1, None, None) == -1
     assert b"fx_grid_pad" in lib.fx_last_error()
     assert lib.fx_build_kernel_map_onto(None, None, 3, None, None) == -1

@@ -234,3 +234,92 @@ def test_sparse_grids_stay_on_the_kernel_map_kernels(monkeypatch):
     slots = fx.profile_read()
     fx.profile_enable(False)
     assert "k_conv_mfma" in slots and "k_conv_leaf" not in slots
+
+
+# ---------------------------------------------------------------------------------- weight gradient from the leaf window
+def _wgrad_rel(gw, ref):
+    gw = gw.astype(np.float64)
+    num = np.sqrt(((gw - ref) ** 2).sum(axis=(1, 2)))
+    den = np.maximum(np.sqrt((ref ** 2).sum(axis=(1, 2))), 1e-3 * np.sqrt(ref.shape[1] * ref.shape[2]))
+    return (num / den).max()
+
+
+def _leaf_wgrad_vs_oracle(grids, c_in, c_out, seed, dup=0.01):
+    """Per offset, ||gw[kappa] - ref||_F <= 1e-4 ||ref||_F (fp32 data, fp32 sums)."""
+    ijk, jo = G.make_jagged([G.shuffle_and_duplicate(g, seed + b, dup) for b, g in enumerate(grids)])
+    g, og = H.both_grids(ijk, jo)
+    feat, _ = G.features_and_weights(seed, og.num_voxels, c_in, c_out, 27, "f32")
+    gy = np.random.default_rng(seed + 11).standard_normal((og.num_voxels, c_out)).astype(np.float32)
+    gw = fx.sparse_conv_leaf_bwd_weight(g, H.to_device_storage(feat, "f32"), H.to_device_storage(gy, "f32"))
+    assert gw.shape == (27, c_in, c_out) and gw.dtype == torch.float32
+    ref = O.conv_bwd_weight(og, og, 3, 1, feat, gy)
+    assert _wgrad_rel(gw.cpu().numpy(), ref) <= 1e-4
+    return g, og, feat, gy, gw
+
+
+@pytest.mark.parametrize("c_in,c_out", [(8, 16), (4, 16), (4, 32), (8, 32), (12, 16), (16, 16), (8, 12), (16, 4), (4, 4),
+                                        (12, 8), (8, 28)])
+def test_weight_gradient_all_channel_shapes(c_in, c_out):
+    w = G.workload("volume_small")
+    _leaf_wgrad_vs_oracle(w.grids, c_in, c_out, w.feat_seed)
+
+
+@pytest.mark.parametrize("name", ["lidar_small", "sheets_small", "sphere64"])
+def test_weight_gradient_on_sparse_and_surface_grids(name):
+    w = G.workload(name)
+    _leaf_wgrad_vs_oracle(w.grids, 8, 16, w.feat_seed)
+
+
+def test_weight_gradient_edge_cases_and_reproducibility():
+    # a batch with an empty member, isolated voxels (every leaf holds one voxel: only the centre tap sums), a dense
+    # block across node boundaries
+    a = np.arange(-9, 9)
+    blk = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3).astype(np.int32)
+    far = (np.random.default_rng(9).integers(-3000, 3000, size=(300, 3)) * 16).astype(np.int32)
+    g, og, feat, gy, gw = _leaf_wgrad_vs_oracle([blk + np.array([4090, 120, -8], np.int32), np.zeros((0, 3), np.int32), far], 8, 16, 91)
+    again = fx.sparse_conv_leaf_bwd_weight(g, H.to_device_storage(feat, "f32"), H.to_device_storage(gy, "f32"))
+    assert torch.equal(gw, again)                       # fixed summation order: identical bits
+    _, _, _, _, gw1 = _leaf_wgrad_vs_oracle([np.array([[3, -4, 5]], np.int32)], 16, 16, 92, dup=0.0)
+    assert (gw1.cpu().numpy()[np.arange(27) != 13] == 0).all()
+    # empty grid: all zeros
+    e, _ = H.both_grids(np.zeros((0, 3), np.int32), np.array([[0, 0]]))
+    z = fx.sparse_conv_leaf_bwd_weight(e, torch.zeros((0, 8), device="cuda"), torch.zeros((0, 16), device="cuda"))
+    assert z.shape == (27, 8, 16) and (z == 0).all()
+    # shapes the kernel does not serve
+    for c_in, c_out, dt in ((16, 32, torch.float32), (8, 6, torch.float32), (6, 16, torch.float32), (8, 16, torch.bfloat16)):
+        with pytest.raises(fx.FxError):
+            fx.sparse_conv_leaf_bwd_weight(g, torch.zeros((g.num_voxels, c_in), device="cuda", dtype=dt),
+                                           torch.zeros((g.num_voxels, c_out), device="cuda", dtype=dt))
+
+
+@pytest.mark.parametrize("switch", [None, "0"])
+def test_kernel_map_weight_gradient_takes_the_leaf_kernel_at_low_depth(switch, monkeypatch):
+    if switch is None:
+        monkeypatch.delenv("FVDB_HOTPATH_LEAF_DISPATCH", raising=False)
+    else:
+        monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", switch)
+    w = G.workload("volume_small")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 3, 1)
+    feat, _ = G.features_and_weights(5, og.num_voxels, 8, 16, 27, "f32")
+    gy = np.random.default_rng(6).standard_normal((og.num_voxels, 16)).astype(np.float32)
+    d_x, d_gy = H.to_device_storage(feat, "f32"), H.to_device_storage(gy, "f32")
+    fx.profile_enable(True); fx.profile_reset()
+    gw = fx.sparse_conv_bwd_weight(km, d_x, d_gy)
+    torch.cuda.synchronize()
+    fx.profile_enable(False)
+    assert _wgrad_rel(gw.cpu().numpy(), O.conv_bwd_weight(og, og, 3, 1, feat, gy)) <= 1e-4
+    leaf = fx.sparse_conv_leaf_bwd_weight(g, d_x, d_gy)
+    assert torch.equal(gw, leaf) == (switch is None)      # the same kernel, or the scalar one
+
+
+def test_weight_gradient_full_size_volume():
+    """volume1m, 8 -> 16 fp32 (1.03 M voxels, 26 M pairs): the whole gradient against the oracle."""
+    w = G.workload("volume1m")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    feat, _ = G.features_and_weights(w.feat_seed, og.num_voxels, 8, 16, 27, "f32")
+    gy = np.random.default_rng(w.feat_seed + 3).standard_normal((og.num_voxels, 16)).astype(np.float32)
+    gw = fx.sparse_conv_leaf_bwd_weight(g, H.to_device_storage(feat, "f32"), H.to_device_storage(gy, "f32"))
+    assert _wgrad_rel(gw.cpu().numpy(), O.conv_bwd_weight(og, og, 3, 1, feat, gy)) <= 1e-4
