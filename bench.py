@@ -271,6 +271,13 @@ def main():
                      "algorithmic_bytes": v_bytes, "GBs": v_bytes / (t_leaf * 1e-3) / 1e9,
                      "frac_of_hbm_peak": v_bytes / (t_leaf * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "kernel_map_path_ms": {"kernel_map": t_kmv, "conv": t_cv}}
+        # its weight gradient from the same window, against the scalar kernel over the kernel map
+        v_gy = torch.randn((nv, wv.c_out), device="cuda")
+        t_lw = b2b(lambda: fx.sparse_conv_leaf_bwd_weight(gv, v_feat, v_gy))
+        t_sw = b2b(lambda: fx.sparse_conv_bwd_weight(kmv, v_feat, v_gy), reps=3)      # dispatch is off here: the scalar kernel
+        low_depth["leaf_bwd_weight_ms"] = t_lw
+        low_depth["leaf_bwd_weight_effective_TFLOPs"] = v_flops / (t_lw * 1e-3) / 1e12
+        low_depth["kernel_map_path_ms"]["bwd_weight_scalar"] = t_sw
         # the same grid at 64 -> 64 bf16: the leaf-window kernel for 16-bit types against the kernel-map path
         h_feat = torch.randn((nv, 64), device="cuda").to(torch.bfloat16)
         h_w = (torch.randn((27, 64, 64), device="cuda") * (1.0 / (27 * 64)) ** 0.5).to(torch.bfloat16)
