@@ -339,8 +339,8 @@ fx_status fx_sparse_conv_leaf_bwd_data(const fx_grid* g, const void* d_gout, fx_
  * result as fx_sparse_conv_bwd_weight on the (3,1) map of g.
  *   d_feat [N, C_in] and d_gout [N, C_out] device, dtype dt, 16-byte aligned; d_gw [27, C_in, C_out] device,
  *   dtype out_dt; every element is written (zeros for an empty grid).
- * Supported: dt = FX_F32 with C_in in {4, 8} and C_out a multiple of 4 up to 32, or C_in in {12, 16} and C_out a
- * multiple of 4 up to 16; out_dt = FX_F32 (or dt); others FX_EUNSUPPORTED.  True fp32 products, fp32 sums in a
+ * Supported: dt = FX_F32 with C_in in {4, 8, 12, 16} and C_out a multiple of 4 up to 32 (the forward's shapes; C_in
+ * of 12 or 16 with more than 16 output channels takes two launches); out_dt = FX_F32; others FX_EUNSUPPORTED.  True fp32 products, fp32 sums in a
  * fixed order (leaves in fixed ranges per workgroup, the workgroups' partial sums added in index order): repeated
  * calls give identical bits.  Allocates the partial sums (one [27, C_in, C_out] fp32 block per workgroup, at
  * most a few thousand) for the call.  Does not synchronise. */

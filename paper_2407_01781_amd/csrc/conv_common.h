@@ -156,8 +156,7 @@ inline bool leaf_shape_supported(fx_dtype dt, int C_contract, int C_produce) {
 fx_status leaf_wgrad(const char* who, const fx_grid* g, const void* d_feat, const void* d_gout, fx_dtype dt, int32_t C_in,
                      int32_t C_out, void* d_gw, fx_dtype out_dt, hipStream_t st);
 inline bool leaf_wgrad_shape_supported(fx_dtype dt, int C_in, int C_out) {
-    if (dt != FX_F32 || C_out < 4 || C_out % 4) return false;
-    return ((C_in == 4 || C_in == 8) && C_out <= 32) || ((C_in == 12 || C_in == 16) && C_out <= 16);
+    return dt == FX_F32 && (C_in == 4 || C_in == 8 || C_in == 12 || C_in == 16) && C_out >= 4 && C_out % 4 == 0 && C_out <= 32;
 }
 fx_status wgrad_reduce_ranges(const float* part, int n_ranges, int64_t total, void* gw, fx_dtype out_dt, hipStream_t st);
 

@@ -353,8 +353,9 @@ template <int C_IN> struct WgLeafShape {
 
 template <int C_IN, int NT>
 __global__ __launch_bounds__(kLeafThreads, WgLeafShape<C_IN>::waves_per_simd(NT)) void k_wgrad_leaf(TreeView t, const float* __restrict__ feat,
-                                                             const float* __restrict__ gout, int C_out, int64_t n_voxels,
-                                                             float* __restrict__ part) {
+                                                             const float* __restrict__ gout, int C_out, int co_base,
+                                                             int64_t n_voxels, float* __restrict__ part) {
+    // serves the output channels co_base .. co_base + 16 NT - 1 (those below C_out) of gout and of gw
     constexpr int J = C_IN / 4, TPI = WgLeafShape<C_IN>::kTapsPer, NG = WgLeafShape<C_IN>::kGroups;
     extern __shared__ __align__(16) unsigned char smem[];
     LeafLds& L = *reinterpret_cast<LeafLds*>(smem);
@@ -426,7 +427,7 @@ __global__ __launch_bounds__(kLeafThreads, WgLeafShape<C_IN>::waves_per_simd(NT)
         if (wave == kLeafWaves - 1 && f + 1 < f_end) stage_records(t, L, f + 1, lane);
         {
             const int n_quads = (n_act + 3) >> 2;
-            const float* gp = gout + base * C_out + v;
+            const float* gp = gout + base * C_out + co_base + v;
             // the next quad's cell and gout values are requested before the current quad's multiplies
             int cell_n = 0;
             float b_n[NT];
@@ -435,7 +436,7 @@ __global__ __launch_bounds__(kLeafThreads, WgLeafShape<C_IN>::waves_per_simd(NT)
                 cell_n = L.cell_of_rank[min(r, n_act - 1)];
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
-                    b_n[nt] = (r < n_act && 16 * nt + v < C_out) ? gp[(int64_t)r * C_out + 16 * nt] : 0.f;
+                    b_n[nt] = (r < n_act && co_base + 16 * nt + v < C_out) ? gp[(int64_t)r * C_out + 16 * nt] : 0.f;
             };
             if (wave < n_quads) fetch(wave);
             for (int qd = wave; qd < n_quads; qd += kLeafWaves) {
@@ -492,7 +493,7 @@ __global__ __launch_bounds__(kLeafThreads, WgLeafShape<C_IN>::waves_per_simd(NT)
                 if (row < TPI * C_IN && kappa < 27) {
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
-                        if (16 * nt + v < C_out) dst[(kappa * C_IN + c) * C_out + 16 * nt + v] = acc[g][nt][e];
+                        if (co_base + 16 * nt + v < C_out) dst[(kappa * C_IN + c) * C_out + co_base + 16 * nt + v] = acc[g][nt][e];
                 }
             }
     }
@@ -516,8 +517,11 @@ fx_status launch_wgrad_leaf(const fx_grid* g, const float* feat, const float* go
     float* part = nullptr;
     FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * n_wg, st));
     {
+        // wider gradients than one launch's accumulators hold take one launch per 16 NT output channels; the
+        // launches write disjoint columns of the same partial sums
         ProfScope ps(kProfWgrad, st);
-        k_wgrad_leaf<C_IN, NT><<<n_wg, kLeafThreads, lds, st>>>(g->view(), feat, gout, C_out, g->hdr.n_voxels, part);
+        for (int co_base = 0; co_base < C_out; co_base += 16 * NT)
+            k_wgrad_leaf<C_IN, NT><<<n_wg, kLeafThreads, lds, st>>>(g->view(), feat, gout, C_out, co_base, g->hdr.n_voxels, part);
     }
     fx_status rc = FX_OK;
     if (hipGetLastError() != hipSuccess) { set_error("leaf-window weight gradient: launch failed"); rc = FX_EDEVICE; }
@@ -916,8 +920,8 @@ fx_status fx::leaf_wgrad(const char* who, const fx_grid* g, const void* d_feat, 
         return FX_EUNSUPPORTED;
     }
     if (!leaf_wgrad_shape_supported(dt, C_in, C_out)) {
-        set_error("%s: serves fp32 with 4 or 8 input channels and a multiple of 4 up to 32 output channels, or 12 or 16 input "
-                  "and up to 16 output channels (got %d -> %d); use the kernel-map path", who, C_in, C_out);
+        set_error("%s: serves fp32 with 4, 8, 12 or 16 input channels and a multiple of 4 up to 32 output channels "
+                  "(got %d -> %d); use the kernel-map path", who, C_in, C_out);
         return FX_EUNSUPPORTED;
     }
     const float* x = (const float*)d_feat;

@@ -258,7 +258,7 @@ def _leaf_wgrad_vs_oracle(grids, c_in, c_out, seed, dup=0.01):
 
 
 @pytest.mark.parametrize("c_in,c_out", [(8, 16), (4, 16), (4, 32), (8, 32), (12, 16), (16, 16), (8, 12), (16, 4), (4, 4),
-                                        (12, 8), (8, 28)])
+                                        (12, 8), (8, 28), (16, 32), (12, 24), (16, 20)])
 def test_weight_gradient_all_channel_shapes(c_in, c_out):
     w = G.workload("volume_small")
     _leaf_wgrad_vs_oracle(w.grids, c_in, c_out, w.feat_seed)
@@ -286,7 +286,7 @@ def test_weight_gradient_edge_cases_and_reproducibility():
     z = fx.sparse_conv_leaf_bwd_weight(e, torch.zeros((0, 8), device="cuda"), torch.zeros((0, 16), device="cuda"))
     assert z.shape == (27, 8, 16) and (z == 0).all()
     # shapes the kernel does not serve
-    for c_in, c_out, dt in ((16, 32, torch.float32), (8, 6, torch.float32), (6, 16, torch.float32), (8, 16, torch.bfloat16)):
+    for c_in, c_out, dt in ((16, 36, torch.float32), (8, 6, torch.float32), (6, 16, torch.float32), (8, 16, torch.bfloat16)):
         with pytest.raises(fx.FxError):
             fx.sparse_conv_leaf_bwd_weight(g, torch.zeros((g.num_voxels, c_in), device="cuda", dtype=dt),
                                            torch.zeros((g.num_voxels, c_out), device="cuda", dtype=dt))
