@@ -106,8 +106,10 @@ struct fx_kmap {
 
 namespace fx {
 // whether the tiles of a stride-1 map stage shared input rows (the LDS-staged convolution kernel) or list one row
-// per pair (the gather kernels): the submanifold map, and a map onto a grid at least twice the size of its input
+// per pair (the gather kernels): the submanifold map, a map onto a grid at least twice the size of its input, and
+// the inverse of the 3x3x3 stride-2 map
 inline bool map_shares_rows(const fx_kmap* km) {
+    if (km->is_inverse) return true;       // fine voxels looking up their coarse voxels: neighbours share them
     return km->stride == 1 && (km->gin == km->gout || km->n_out >= 2 * km->n_in);
 }
 // dense [n_out, K3] table for the scalar convolution path, built on first use (not thread-safe)

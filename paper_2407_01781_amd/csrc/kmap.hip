@@ -921,7 +921,7 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
         // rows than the table holds and keeps one row per pair
         else if (stride == 1 && map_shares_rows(km)) FX_TILES(3, false, false, true);
         else if (stride == 1) FX_TILES(3, false);
-        else if (inverse) FX_TILES(3, false, true);
+        else if (inverse) FX_TILES(3, false, true, true);      // 512 fine voxels reach a few hundred coarse rows: staged tiles
         else FX_TILES(3, false);      // 3x3x3 stride 2: windows overlap, still no input row inside the tile's own range
 #undef FX_TILES
         if (e == hipSuccess) e = hipGetLastError();
