@@ -47,7 +47,7 @@ def lib():
         L.fo_conv.restype = i64
         L.fo_conv.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp, i64, i64]
         L.fo_conv_bwd_data.restype = i64
-        L.fo_conv_bwd_data.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp]
+        L.fo_conv_bwd_data.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp, i64, i64]
         L.fo_conv_bwd_weight.restype = i64
         L.fo_conv_bwd_weight.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, C.c_int, vp, i64, i64]
         L.fo_conv_transpose.restype = i64
@@ -168,9 +168,19 @@ def kernel_map(gin: OracleGrid, gout: OracleGrid, kernel_size: int, stride: int)
     return out
 
 
+def _row_ranges(o_begin: int, o_end: int, threads: int):
+    """[o_begin, o_end) cut into at most `threads` contiguous ranges of near-equal length."""
+    n = max(0, o_end - o_begin)
+    parts = max(1, min(threads, n))
+    return [(o_begin + n * t // parts, o_begin + n * (t + 1) // parts) for t in range(parts)]
+
+
 def conv(gin: OracleGrid, gout: OracleGrid, kernel_size: int, stride: int, feat: np.ndarray,
-         w: np.ndarray, o_begin: int = 0, o_end: Optional[int] = None) -> np.ndarray:
-    """out [N_out, C_out] float64 (O3); rows outside [o_begin, o_end) are zero."""
+         w: np.ndarray, o_begin: int = 0, o_end: Optional[int] = None, threads: int = 1) -> np.ndarray:
+    """out [N_out, C_out] float64 (O3); rows outside [o_begin, o_end) are zero.
+
+    threads > 1: the same C routine is called on disjoint row ranges from that many host threads (every
+    output row is still one plain sum computed by one call, so the values do not depend on `threads`)."""
     feat = np.ascontiguousarray(feat, dtype=np.float64)
     w = np.ascontiguousarray(w, dtype=np.float64)
     k3, c_in, c_out = w.shape
@@ -179,42 +189,87 @@ def conv(gin: OracleGrid, gout: OracleGrid, kernel_size: int, stride: int, feat:
     if o_end is None:
         o_end = n_out
     out = np.zeros((n_out, c_out), dtype=np.float64)
-    r = lib().fo_conv(gin._h, gout._h, kernel_size, stride, _p(feat), _p(w), c_in, c_out, _p(out),
-                      o_begin, o_end)
-    if r < 0:
+    L = lib()
+
+    def run(rng):
+        return L.fo_conv(gin._h, gout._h, kernel_size, stride, _p(feat), _p(w), c_in, c_out, _p(out), rng[0], rng[1])
+
+    ranges = _row_ranges(max(0, o_begin), min(n_out, o_end), threads)
+    if len(ranges) == 1:
+        rs = [run(ranges[0])]
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(len(ranges)) as ex:       # ctypes releases the interpreter lock during the call
+            rs = list(ex.map(run, ranges))
+    if min(rs) < 0:
         raise ValueError("bad conv arguments")
     return out
 
 
 def conv_bwd_data(gin: OracleGrid, gout: OracleGrid, kernel_size: int, stride: int, grad_out: np.ndarray,
-                  w: np.ndarray) -> np.ndarray:
-    """Gradient with respect to the input features, [N_in, C_in] float64 (O4)."""
+                  w: np.ndarray, threads: int = 1) -> np.ndarray:
+    """Gradient with respect to the input features, [N_in, C_in] float64 (O4).
+
+    threads > 1: the C routine runs on disjoint output ranges in that many host threads, each into its own
+    array, and the arrays are added in range order (float64: the regrouping moves a sum by ~1e-16 relative)."""
     grad_out = np.ascontiguousarray(grad_out, dtype=np.float64)
     w = np.ascontiguousarray(w, dtype=np.float64)
     k3, c_in, c_out = w.shape
     assert k3 == kernel_size ** 3 and grad_out.shape == (gout.num_voxels, c_out)
-    out = np.zeros((gin.num_voxels, c_in), dtype=np.float64)
-    r = lib().fo_conv_bwd_data(gin._h, gout._h, kernel_size, stride, _p(grad_out), _p(w), c_in, c_out, _p(out))
-    if r < 0:
-        raise ValueError("bad conv_bwd_data arguments")
+    L = lib()
+
+    def run(rng):
+        part = np.zeros((gin.num_voxels, c_in), dtype=np.float64)
+        r = L.fo_conv_bwd_data(gin._h, gout._h, kernel_size, stride, _p(grad_out), _p(w), c_in, c_out, _p(part),
+                               rng[0], rng[1])
+        if r < 0:
+            raise ValueError("bad conv_bwd_data arguments")
+        return part
+
+    ranges = _row_ranges(0, gout.num_voxels, threads)
+    if len(ranges) == 1:
+        return run(ranges[0])
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(len(ranges)) as ex:
+        parts = list(ex.map(run, ranges))
+    out = parts[0]
+    for part in parts[1:]:
+        out += part
     return out
 
 
 def conv_bwd_weight(gin: OracleGrid, gout: OracleGrid, kernel_size: int, stride: int, feat: np.ndarray,
-                    grad_out: np.ndarray, o_begin: int = 0, o_end: Optional[int] = None) -> np.ndarray:
+                    grad_out: np.ndarray, o_begin: int = 0, o_end: Optional[int] = None, threads: int = 1) -> np.ndarray:
     """Gradient with respect to the weights, [K^3, C_in, C_out] float64 (O4); only the outputs
-    in [o_begin, o_end) contribute."""
+    in [o_begin, o_end) contribute.
+
+    threads > 1: the C routine runs on disjoint output ranges in that many host threads, each into its own
+    array, and the arrays are added in range order (float64: the regrouping moves the sum by ~1e-16 relative)."""
     feat = np.ascontiguousarray(feat, dtype=np.float64)
     grad_out = np.ascontiguousarray(grad_out, dtype=np.float64)
     c_in, c_out = feat.shape[1], grad_out.shape[1]
     assert feat.shape[0] == gin.num_voxels and grad_out.shape[0] == gout.num_voxels
     if o_end is None:
         o_end = gout.num_voxels
-    out = np.zeros((kernel_size ** 3, c_in, c_out), dtype=np.float64)
-    r = lib().fo_conv_bwd_weight(gin._h, gout._h, kernel_size, stride, _p(feat), _p(grad_out), c_in, c_out,
-                                 _p(out), o_begin, o_end)
-    if r < 0:
-        raise ValueError("bad conv_bwd_weight arguments")
+    L = lib()
+
+    def run(rng):
+        part = np.zeros((kernel_size ** 3, c_in, c_out), dtype=np.float64)
+        r = L.fo_conv_bwd_weight(gin._h, gout._h, kernel_size, stride, _p(feat), _p(grad_out), c_in, c_out,
+                                 _p(part), rng[0], rng[1])
+        if r < 0:
+            raise ValueError("bad conv_bwd_weight arguments")
+        return part
+
+    ranges = _row_ranges(o_begin, o_end, threads)
+    if len(ranges) == 1:
+        return run(ranges[0])
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(len(ranges)) as ex:
+        parts = list(ex.map(run, ranges))
+    out = parts[0]
+    for part in parts[1:]:
+        out += part
     return out
 
 

@@ -377,14 +377,18 @@ int64_t fo_conv(const fo_grid *gin, const fo_grid *gout, int K, int stride,
 
 /* ------------------------------------------------------------------ O4 */
 /* gout [N_out, C_out], w [K^3, C_in, C_out], gin [N_in, C_in] (overwritten); all double.
- * Returns the active pairs, or -1 on bad args. */
+ * Only the outputs in [o_begin, o_end) contribute (the whole gradient is the sum over disjoint
+ * ranges).  Returns the active pairs, or -1 on bad args. */
 int64_t fo_conv_bwd_data(const fo_grid *gin_grid, const fo_grid *gout_grid, int K, int stride,
-                         const double *gout, const double *w, int C_in, int C_out, double *gin) {
+                         const double *gout, const double *w, int C_in, int C_out, double *gin,
+                         int64_t o_begin, int64_t o_end) {
     if (K < 1 || stride < 1 || gin_grid->B != gout_grid->B) return -1;
     const int d0 = fo_delta_min(K);
     int64_t pairs = 0;
     for (int64_t e = 0; e < gin_grid->N * (int64_t)C_in; ++e) gin[e] = 0.0;
-    for (int64_t o = 0; o < gout_grid->N; ++o) {
+    if (o_begin < 0) o_begin = 0;
+    if (o_end > gout_grid->N) o_end = gout_grid->N;
+    for (int64_t o = o_begin; o < o_end; ++o) {
         const fo_vox *p = &gout_grid->vox[o];
         const double *gy = gout + o * (int64_t)C_out;
         for (int a = 0; a < K; ++a)

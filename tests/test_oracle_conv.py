@@ -108,3 +108,21 @@ def test_linearity_and_row_range():
     part = O.conv(g, g, 3, 1, f1, w1, 10, 50)
     full = O.conv(g, g, 3, 1, f1, w1)
     assert np.array_equal(part[10:50], full[10:50]) and not part[:10].any() and not part[50:].any()
+
+
+def test_host_threads_do_not_change_the_values():
+    """The range-parallel harness calls the same routine on disjoint output ranges: forward rows are bit-identical,
+    the gradients (sums over ranges regrouped in float64) agree to 1e-12."""
+    rng = np.random.default_rng(77)
+    pts = rng.integers(-6, 14, size=(3000, 3)).astype(np.int32)
+    og = O.OracleGrid(pts, np.array([[0, 1200], [1200, 3000]], np.int64))
+    n = og.num_voxels
+    feat, wt = rng.standard_normal((n, 5)), rng.standard_normal((27, 5, 7))
+    gy = rng.standard_normal((n, 7))
+    assert np.array_equal(O.conv(og, og, 3, 1, feat, wt), O.conv(og, og, 3, 1, feat, wt, threads=5))
+    a, b = O.conv(og, og, 3, 1, feat, wt, 100, 900), O.conv(og, og, 3, 1, feat, wt, 100, 900, threads=3)
+    assert np.array_equal(a, b) and not a[:100].any() and not a[900:].any()
+    np.testing.assert_allclose(O.conv_bwd_data(og, og, 3, 1, gy, wt, threads=4), O.conv_bwd_data(og, og, 3, 1, gy, wt),
+                               rtol=0, atol=1e-12)
+    np.testing.assert_allclose(O.conv_bwd_weight(og, og, 3, 1, feat, gy, threads=4), O.conv_bwd_weight(og, og, 3, 1, feat, gy),
+                               rtol=0, atol=1e-10)
