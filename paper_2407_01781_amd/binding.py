@@ -308,28 +308,30 @@ def sparse_conv_fwd(kmap: KernelMap, feat: torch.Tensor, weights: torch.Tensor,
 
 
 def sparse_conv_bwd_data(kmap: KernelMap, grad_out: torch.Tensor, weights: torch.Tensor,
-                         out_dtype: Optional[torch.dtype] = None) -> torch.Tensor:
+                         out_dtype: Optional[torch.dtype] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """grad_out [N_out, C_out], weights [K^3, C_in, C_out] -> gradient of the input features [N_in, C_in]."""
     assert grad_out.is_cuda and weights.is_cuda and grad_out.is_contiguous() and weights.is_contiguous()
     assert grad_out.dtype == weights.dtype and grad_out.dtype in _TORCH_DT
     k3, c_in, c_out = weights.shape
     assert k3 == kmap.k3 and grad_out.shape == (kmap.n_out, c_out)
     out_dtype = out_dtype or grad_out.dtype
-    gin = torch.empty((kmap.g_in.num_voxels, c_in), dtype=out_dtype, device="cuda")
+    gin = out if out is not None else torch.empty((kmap.g_in.num_voxels, c_in), dtype=out_dtype, device="cuda")
+    assert gin.is_cuda and gin.is_contiguous() and gin.shape == (kmap.g_in.num_voxels, c_in) and gin.dtype == out_dtype
     _check(lib.fx_sparse_conv_bwd_data(kmap._h, _ptr(grad_out), _TORCH_DT[grad_out.dtype], _ptr(weights), c_in, c_out,
                                        _ptr(gin), _TORCH_DT[out_dtype], _stream()))
     return gin
 
 
 def sparse_conv_bwd_weight(kmap: KernelMap, feat: torch.Tensor, grad_out: torch.Tensor,
-                           out_dtype: Optional[torch.dtype] = None) -> torch.Tensor:
+                           out_dtype: Optional[torch.dtype] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """feat [N_in, C_in], grad_out [N_out, C_out] -> gradient of the weights [K^3, C_in, C_out]."""
     assert feat.is_cuda and grad_out.is_cuda and feat.is_contiguous() and grad_out.is_contiguous()
     assert feat.dtype == grad_out.dtype and feat.dtype in _TORCH_DT
     c_in, c_out = feat.shape[1], grad_out.shape[1]
     assert feat.shape[0] == kmap.g_in.num_voxels and grad_out.shape[0] == kmap.n_out
     out_dtype = out_dtype or feat.dtype
-    gw = torch.empty((kmap.k3, c_in, c_out), dtype=out_dtype, device="cuda")
+    gw = out if out is not None else torch.empty((kmap.k3, c_in, c_out), dtype=out_dtype, device="cuda")
+    assert gw.is_cuda and gw.is_contiguous() and gw.shape == (kmap.k3, c_in, c_out) and gw.dtype == out_dtype
     _check(lib.fx_sparse_conv_bwd_weight(kmap._h, _ptr(feat), _ptr(grad_out), _TORCH_DT[feat.dtype], c_in, c_out,
                                          _ptr(gw), _TORCH_DT[out_dtype], _stream()))
     return gw

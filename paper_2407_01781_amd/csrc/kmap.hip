@@ -342,11 +342,13 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     // ---- which output leaves overlap [o0, o0 + n_valid)
     if (tid == 0) {
         // leaves from the one holding the tile's first voxel to the one holding the next tile's first
-        // voxel (which may start exactly at the tile's end: one leaf too many does no harm)
+        // voxel.  That last leaf may start exactly at the tile's end and hold none of the tile's voxels;
+        // kTileT voxels lie in at most kTileT leaves, so the count is cut there (a tile of kTileT one-voxel
+        // leaves would otherwise list kTileT + 1 and write past leaf_off)
         const int lo = tile_first_leaf[tile];
         const int a = (tile + 1) * kTileT < n_out ? tile_first_leaf[tile + 1] : tout.n_leaf - 1;
         L.f_lo = lo;
-        L.n_leaves = a + 1 - lo;
+        L.n_leaves = min(a + 1 - lo, kTileT);
         L.n_halo = 0; L.n_blocks = 0; L.n_pair_blocks = 0; L.overflow = 0; L.n_rec = 0;
     }
     for (int e = tid; e < kRecHashSlots; e += kPackThreads) { L.u.look.rec_hash[e] = -1; L.u.look.slot_rec[e] = 0xFFFF; }

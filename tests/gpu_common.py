@@ -1,5 +1,7 @@
 """Helpers shared by the GPU parity tests: build the HIP path's objects and the oracle's on
 the same seeded inputs."""
+import os
+
 import numpy as np
 import torch
 
@@ -8,6 +10,19 @@ from oracle import cpu_oracle as O
 from workloads import generators as G
 
 TORCH_DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+ORACLE_THREADS = max(1, min(16, os.cpu_count() or 1))     # host threads the oracle's range-parallel harness may use
+
+
+def nan_filled(shape, dtype) -> torch.Tensor:
+    """An output buffer no element of which can pass a comparison unless the kernel wrote it."""
+    return torch.full(tuple(shape), float("nan"), dtype=dtype, device="cuda")
+
+
+def row_error_report(y: np.ndarray, ref: np.ndarray) -> float:
+    """Largest per-row relative L2 error (the quantity the 16-bit bar bounds), for the test log."""
+    num = np.linalg.norm(y.astype(np.float64) - ref, axis=1)
+    den = np.maximum(np.linalg.norm(ref, axis=1), 1e-3 * np.sqrt(ref.shape[1]))
+    return float((num / den).max()) if y.size else 0.0
 
 
 def to_device_storage(x_f32: np.ndarray, dtype: str) -> torch.Tensor:

@@ -243,3 +243,92 @@ def test_full_size_configs_sampled_rows(name, monkeypatch):
     for s in starts:
         ref = O.conv(og, ogo, w.kernel_size, w.stride, f64, w64, s, s + 300)
         H.conv_tolerance_check(y[s:s + 300], ref[s:s + 300], w.dtype, w.k3, w.c_in)
+
+
+# The 16-bit path's own error model (exact products, fp32 accumulation of <= K^3*C_in terms, one rounding to an
+# 8-bit significand) puts the per-row relative error near 2^-9 = 2e-3 for bf16 outputs and ~1e-6 for fp32 outputs;
+# the asserted bar stays the stated 2e-2, the figure below is printed so that a drift towards it shows in the log.
+def _report(tag, y, ref):
+    print(f"[row-error] {tag}: max per-row relative L2 error {H.row_error_report(y, ref):.3e}", flush=True)
+
+
+@pytest.mark.parametrize("name", ["lidar1m", "lidar1m_down", "sheets4", "indoor4"])
+def test_full_size_every_output_row(name):
+    """Configs 3, 4, 5 and 2 at full size in the benchmark's launch configuration, every output row against the
+    oracle.  The output buffer starts as NaN, so a row that no workgroup wrote fails; a tile claimed twice or
+    skipped by the persistent kernel's work lists cannot hide among sampled rows."""
+    w = G.workload(name)
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, w.kernel_size, w.stride)
+    ogo = O.output_grid(og, w.kernel_size, w.stride)
+    assert km.n_out == ogo.num_voxels
+    feat, wt = w.feats_weights()
+    out = H.nan_filled((km.n_out, w.c_out), H.TORCH_DT[w.dtype])
+    fx.sparse_conv_fwd(km, H.to_device_storage(feat, w.dtype), H.to_device_storage(wt, w.dtype), out=out)
+    y = out.float().cpu().numpy()
+    assert np.isfinite(y).all()
+    ref = O.conv(og, ogo, w.kernel_size, w.stride, feat, wt, threads=H.ORACLE_THREADS)
+    _report(name, y, ref)
+    H.conv_tolerance_check(y, ref, w.dtype, w.k3, w.c_in)
+
+
+@pytest.mark.parametrize("dtype,out_f32", [("bf16", False), ("f16", True)])
+def test_many_work_items_per_workgroup_under_a_full_compare(dtype, out_f32):
+    """196 tiles x 8 output slices = 1568 work items on at most 256 persistent workgroups: every workgroup claims
+    several items through the per-XCD counters, announces them in the LDS ring and hands its weight pipeline from
+    item to item -- all compared row by row, outputs NaN before the call."""
+    w = G.workload("lidar_small")
+    ijk, jo = w.jagged_ijk(dup_fraction=0.01)
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 3, 1)
+    feat, wt = G.features_and_weights(9100, og.num_voxels, 64, 512, 27, dtype)
+    odt = torch.float32 if out_f32 else H.TORCH_DT[dtype]
+    out = H.nan_filled((km.n_out, 512), odt)
+    fx.sparse_conv_fwd(km, H.to_device_storage(feat, dtype), H.to_device_storage(wt, dtype), out_dtype=odt, out=out)
+    y = out.float().cpu().numpy()
+    assert np.isfinite(y).all()
+    ref = O.conv(og, og, 3, 1, feat, wt, threads=H.ORACLE_THREADS)
+    _report(f"lidar_small 64->512 {dtype}", y, ref)
+    H.conv_tolerance_check(y, ref, dtype, 27, 64)
+    # identity tap on the same launch shape: bit-exact rows, so a row written by the wrong item shows
+    wid = np.zeros((27, 64, 512), dtype=np.float32)
+    for s in range(8):
+        wid[(3 * s + 1) % 27, :, 64 * s:64 * s + 64] = np.eye(64)
+    out.fill_(float("nan"))
+    fx.sparse_conv_fwd(km, H.to_device_storage(feat, dtype), H.to_device_storage(wid, dtype), out_dtype=odt, out=out)
+    y = out.float().cpu().numpy()
+    nb = O.kernel_map(og, og, 3, 1)
+    for s in range(8):
+        col = nb[:, (3 * s + 1) % 27]
+        expect = np.where(col[:, None] >= 0, feat[np.maximum(col, 0)], 0.0)
+        assert np.array_equal(y[:, 64 * s:64 * s + 64], expect)
+
+
+def _one_voxel_leaves(n_side=13, seed=4242):
+    """A lattice of leaves with ONE active voxel each (random position inside its leaf): every tile of 512
+    consecutive outputs spans 512 different leaves -- the densest leaf list a tile can have."""
+    rng = np.random.default_rng(seed)
+    a = np.arange(n_side, dtype=np.int32) - n_side // 2
+    leaf = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3) * 8
+    return (leaf + rng.integers(0, 8, size=leaf.shape)).astype(np.int32)
+
+
+@pytest.mark.parametrize("K,stride", [(3, 1), (2, 2), (3, 2), (1, 1)])
+def test_tiles_of_512_one_voxel_leaves(K, stride):
+    """2197 voxels in 2197 leaves (four full tiles and a tail): the map is compared entry by entry and the
+    convolution row by row; slot 511 of a full tile lies in the tile's 512th leaf."""
+    pts = _one_voxel_leaves()
+    g, og = H.both_grids(pts, np.array([[0, pts.shape[0]]], np.int64))
+    assert g.counts()[0] == pts.shape[0] == og.num_voxels
+    km = fx.build_kernel_map(g, K, stride)
+    ogo = O.output_grid(og, K, stride)
+    assert np.array_equal(km.dense().cpu().numpy(), O.kernel_map(og, ogo, K, stride))
+    feat, wt = G.features_and_weights(4243, og.num_voxels, 64, 64, K ** 3, "bf16")
+    out = H.nan_filled((km.n_out, 64), torch.bfloat16)
+    fx.sparse_conv_fwd(km, H.to_device_storage(feat, "bf16"), H.to_device_storage(wt, "bf16"), out=out)
+    H.conv_tolerance_check(out.float().cpu().numpy(), O.conv(og, ogo, K, stride, feat, wt), "bf16", K ** 3, 64)
+    if (K, stride) == (3, 2):           # the inverse map's tiles list leaves of the fine grid the same way
+        gy = G.round_to_dtype(np.random.default_rng(4244).standard_normal((ogo.num_voxels, 64)).astype(np.float32), "bf16")
+        gx = fx.sparse_conv_bwd_data(km, H.to_device_storage(gy, "bf16"), H.to_device_storage(wt, "bf16"))
+        H.conv_tolerance_check(gx.float().cpu().numpy(), O.conv_bwd_data(og, ogo, K, stride, gy, wt), "bf16", 27, 64)

@@ -137,12 +137,12 @@ def test_dense_block_with_rows_beyond_the_lds_budget(monkeypatch):
 
 @pytest.mark.parametrize("name", ["lidar1m", "lidar1m_down", "lidar1m_down3"])
 def test_full_size_adjoint_identity(name):
-    """At full size the oracle's whole backward pass takes too long; instead the three bilinear
-    forms that the pinned oracle satisfies exactly, <conv(x;W), g> = <x, bwd_data(g;W)> =
-    <W, bwd_weight(x,g)>, are evaluated in float64 on the HIP path's fp32 outputs; the weight-gradient
-    contribution of an output range is compared directly, and so are sampled input-gradient rows of
-    the submanifold map (by its symmetry they are the forward oracle on gout with mirrored offsets and
-    transposed weights)."""
+    """A consistency check of the three entry points among themselves at full size, next to the element-by-element
+    comparison with the oracle in test_full_size_every_gradient_element: the bilinear forms that the pinned
+    oracle satisfies exactly, <conv(x;W), g> = <x, bwd_data(g;W)> = <W, bwd_weight(x,g)>, evaluated in float64 on
+    the HIP path's fp32 outputs; the weight-gradient contribution of an output range compared directly, and
+    sampled input-gradient rows of the submanifold map (by its symmetry the forward oracle on gout with
+    mirrored offsets and transposed weights)."""
     w = G.workload(name)
     ijk, jo = w.jagged_ijk()
     g, og = H.both_grids(ijk, jo)
@@ -197,3 +197,52 @@ def test_3x3x3_stride_2_backward_edge_cases():
             H.conv_tolerance_check(up.float().cpu().numpy(), O.conv_transpose(og, ogc, 3, 2, gy, wt_t), "bf16", 27, 64)
         # the forward map is untouched by the inverse that now hangs on it
         assert np.array_equal(km.dense().cpu().numpy(), O.kernel_map(og, ogc, 3, 2))
+
+
+@pytest.mark.parametrize("name", ["lidar1m", "lidar1m_down", "sheets4"])
+def test_full_size_every_gradient_element(name):
+    """Configs 3, 4 and 5 at full size: every row of the input gradient and every element of the weight gradient
+    against the oracle (the weight gradient of config 3 sums ~3e5 products per element in fp32 in the kernel's
+    fixed order).  Outputs are NaN before the calls."""
+    w = G.workload(name)
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, w.kernel_size, w.stride)
+    ogo = O.output_grid(og, w.kernel_size, w.stride)
+    feat, wt = w.feats_weights()
+    gy = G.round_to_dtype(np.random.default_rng(199).standard_normal((ogo.num_voxels, w.c_out)).astype(np.float32), w.dtype)
+    d_x, d_w, d_gy = (H.to_device_storage(a, w.dtype) for a in (feat, wt, gy))
+    gx = H.nan_filled((og.num_voxels, w.c_in), H.TORCH_DT[w.dtype])
+    fx.sparse_conv_bwd_data(km, d_gy, d_w, out=gx)
+    gx = gx.float().cpu().numpy()
+    assert np.isfinite(gx).all()
+    ref_gx = O.conv_bwd_data(og, ogo, w.kernel_size, w.stride, gy, wt, threads=min(4, H.ORACLE_THREADS))
+    print(f"[row-error] {name} input gradient: {H.row_error_report(gx, ref_gx):.3e}", flush=True)
+    H.conv_tolerance_check(gx, ref_gx, w.dtype, w.k3, w.c_out)
+    del ref_gx
+    gw = H.nan_filled((w.k3, w.c_in, w.c_out), torch.float32)
+    fx.sparse_conv_bwd_weight(km, d_x, d_gy, out_dtype=torch.float32, out=gw)
+    gw = gw.cpu().numpy()
+    assert np.isfinite(gw).all()
+    ref_gw = O.conv_bwd_weight(og, ogo, w.kernel_size, w.stride, feat, gy, threads=H.ORACLE_THREADS)
+    print(f"[wgrad-error] {name}: max relative Frobenius error per offset {_wgrad_check(gw, ref_gw, 2e-3):.3e}", flush=True)
+
+
+@pytest.mark.parametrize("c_in,c_out", [(512, 64), (64, 512)])
+def test_many_work_items_per_workgroup_backward(c_in, c_out):
+    """lidar_small (196 tiles) at 512 channels on one side: the input gradient runs 1568 work items on at most 256
+    persistent workgroups (c_in = 512 produced channels), and the weight gradient walks a dozen tiles per
+    workgroup; both compared element by element, outputs NaN before the calls."""
+    w = G.workload("lidar_small")
+    km, og, ogo, feat, wt, gy, dtype, _, _ = _setup(w, c_in=c_in, c_out=c_out)
+    d_x, d_w, d_gy = (H.to_device_storage(a, dtype) for a in (feat, wt, gy))
+    gx = H.nan_filled((og.num_voxels, c_in), torch.bfloat16)
+    fx.sparse_conv_bwd_data(km, d_gy, d_w, out=gx)
+    gx = gx.float().cpu().numpy()
+    assert np.isfinite(gx).all()
+    H.conv_tolerance_check(gx, O.conv_bwd_data(og, ogo, 3, 1, gy, wt, threads=min(4, H.ORACLE_THREADS)), dtype, 27, c_out)
+    gw = H.nan_filled((27, c_in, c_out), torch.float32)
+    fx.sparse_conv_bwd_weight(km, d_x, d_gy, out_dtype=torch.float32, out=gw)
+    gw = gw.cpu().numpy()
+    assert np.isfinite(gw).all()
+    _wgrad_check(gw, O.conv_bwd_weight(og, ogo, 3, 1, feat, gy, threads=H.ORACLE_THREADS), 2e-3)
