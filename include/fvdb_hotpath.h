@@ -56,7 +56,8 @@ typedef struct {
     int32_t  batch;
 } fx_leaf;
 
-/* Library version string and a no-op device check (returns FX_EDEVICE if no HIP device). */
+/* Library version string; fx_init checks that a HIP device is present (FX_EDEVICE otherwise) and does the
+ * per-device set-up of the current device ahead of time (optional: every entry point does its own on first use). */
 const char* fx_version(void);
 fx_status   fx_init(void);
 const char* fx_last_error(void);
@@ -212,6 +213,22 @@ void fx_kmap_destroy(fx_kmap* km);
  */
 fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w,
                              int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream);
+
+/* fx_sparse_conv_fwd for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same result bits; the memory
+ * the kernels need beyond inputs and outputs (the packed weights and eight work-list counters) is a static
+ * device array of FX_NOALLOC_MAX_WEIGHT_BYTES + 256 bytes that each GPU the library runs on holds until the
+ * process ends.  The call allocates and frees nothing, on the device or through any library.
+ *   Serves the matrix-unit kernels only: a tiled map (K^3 <= 27), C_in * sizeof(element) a multiple of 64,
+ *   C_out even; anything else returns FX_EUNSUPPORTED (use fx_sparse_conv_fwd).  Packed weights
+ *   (K^3 * C_in * roundup(C_out, 64) elements) beyond the static buffer return FX_ERANGE; 3x3x3 at 256 -> 256
+ *   channels of a 16-bit type fits.
+ *   All calls on one GPU share that GPU's array: calls that overlap on one GPU (different streams or threads)
+ *   race on it and give undefined outputs; calls on one stream are ordered and safe.  Every call rewrites what
+ *   it reads from the array (weights and counters), so nothing carries over from the previous call. */
+#define FX_NOALLOC_MAX_WEIGHT_BYTES (4u << 20)
+fx_status fx_sparse_conv_fwd_noalloc(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w,
+                                     int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Sparse convolution backward (Sec. 3.6 / 3.6.2: the operators are differentiable; Sec. 4.1.3

@@ -73,6 +73,8 @@ def _load():
     L.fx_kmap_destroy.argtypes = [vp]
     L.fx_sparse_conv_fwd.restype = C.c_int
     L.fx_sparse_conv_fwd.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
+    L.fx_sparse_conv_fwd_noalloc.restype = C.c_int
+    L.fx_sparse_conv_fwd_noalloc.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
     L.fx_sparse_conv_bwd_data.restype = C.c_int
     L.fx_sparse_conv_bwd_data.argtypes = [vp, vp, C.c_int, vp, i32, i32, vp, C.c_int, vp]
     L.fx_sparse_conv_bwd_weight.restype = C.c_int
@@ -304,6 +306,18 @@ def sparse_conv_fwd(kmap: KernelMap, feat: torch.Tensor, weights: torch.Tensor,
     assert out.is_cuda and out.is_contiguous() and out.shape == (kmap.n_out, c_out) and out.dtype == out_dtype
     _check(lib.fx_sparse_conv_fwd(kmap._h, _ptr(feat), _TORCH_DT[feat.dtype], _ptr(weights), c_in, c_out,
                                   _ptr(out), _TORCH_DT[out_dtype], _stream()))
+    return out
+
+
+def sparse_conv_fwd_noalloc(kmap: KernelMap, feat: torch.Tensor, weights: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+    """sparse_conv_fwd through the entry point that allocates nothing; the caller supplies `out` [N_out, C_out]."""
+    assert feat.is_cuda and weights.is_cuda and feat.is_contiguous() and weights.is_contiguous()
+    assert feat.dtype == weights.dtype and feat.dtype in _TORCH_DT
+    k3, c_in, c_out = weights.shape
+    assert k3 == kmap.k3 and feat.shape == (kmap.g_in.num_voxels, c_in)
+    assert out.is_cuda and out.is_contiguous() and out.shape == (kmap.n_out, c_out) and out.dtype in _TORCH_DT
+    _check(lib.fx_sparse_conv_fwd_noalloc(kmap._h, _ptr(feat), _TORCH_DT[feat.dtype], _ptr(weights), c_in, c_out,
+                                          _ptr(out), _TORCH_DT[out.dtype], _stream()))
     return out
 
 

@@ -17,6 +17,8 @@
 // channels of one voxel per lane).
 #include "conv_common.h"
 
+#include <mutex>
+
 namespace fx {
 
 // ---------------------------------------------------------------------------------- weight packing
@@ -1120,6 +1122,58 @@ extern "C" int fx_debug_conv_timing(unsigned long long* h_out, size_t bytes) {
 }
 #endif
 
+
+// Device memory the matrix-unit kernels need beyond inputs and outputs: the packed weights and, behind them, the
+// eight work-list counters of the persistent kernel.
+static size_t conv_scratch_bytes(int K3, int C_in, int C_out, int esize) {
+    return packed_weight_bytes(K3, C_in, C_out, esize) + 8 * sizeof(int32_t);    // the packed part is a multiple of 64 bytes
+}
+
+// The tiled map's convolution on the matrix units with that memory supplied by the caller (`scratch`, at least
+// conv_scratch_bytes, 16-byte aligned): pack the weights (which also clears the counters), then the LDS-staged
+// kernel or, for maps whose tiles list one row per pair, the gather kernel.  Allocates nothing.
+static fx_status conv_tiles_with_scratch(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w, int32_t C_in,
+                                         int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st, int mode, void* scratch) {
+    const bool out_f32 = (out_dt == FX_F32);
+    const int esize = in_dt == FX_F32 ? 4 : 2;
+    void* wp = scratch;
+    const size_t wbytes = packed_weight_bytes(km->K3, C_in, C_out, esize);
+    int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
+    // maps whose tiles list one row per pair (strided; stride 1 back from a larger grid): the gather kernel;
+    // others: the LDS-staged kernel
+    const char* fg = getenv("FVDB_HOTPATH_CONV_GATHER");
+    const bool gather = (fg ? fg[0] == '1' : !map_shares_rows(km)) && in_dt != FX_F32 && C_out % kCoutSlice == 0;
+    launch_pack_weights(d_w, wp, km->K3, C_in, C_out, esize, counters, mode, gather ? kPackRows : kPackInterleaved, st);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && gather) {
+        ProfScope ps(kProfConvGather, st);
+        if (in_dt == FX_BF16)
+            e = out_f32 ? launch_gather<__bf16, true>(km, d_feat, wp, C_in, C_out, d_out, st)
+                        : launch_gather<__bf16, false>(km, d_feat, wp, C_in, C_out, d_out, st);
+        else
+            e = out_f32 ? launch_gather<_Float16, true>(km, d_feat, wp, C_in, C_out, d_out, st)
+                        : launch_gather<_Float16, false>(km, d_feat, wp, C_in, C_out, d_out, st);
+    } else if (e == hipSuccess) {
+        ProfScope ps(kProfConvMfma, st);
+        if (in_dt == FX_F32)
+            e = launch_mfma<float, true>(km, d_feat, wp, counters, C_in, C_out, d_out, st);
+        else if (in_dt == FX_BF16)
+            e = out_f32 ? launch_mfma<__bf16, true>(km, d_feat, wp, counters, C_in, C_out, d_out, st)
+                        : launch_mfma<__bf16, false>(km, d_feat, wp, counters, C_in, C_out, d_out, st);
+        else
+            e = out_f32 ? launch_mfma<_Float16, true>(km, d_feat, wp, counters, C_in, C_out, d_out, st)
+                        : launch_mfma<_Float16, false>(km, d_feat, wp, counters, C_in, C_out, d_out, st);
+    }
+    if (e != hipSuccess) { set_error("convolution launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
+    return FX_OK;
+}
+
+// whether the matrix-unit kernels take this map and shape at all (the size heuristics of conv_apply aside)
+static bool conv_tiles_shape_ok(const fx_kmap* km, fx_dtype in_dt, int C_in, int C_out) {
+    const int esize = in_dt == FX_F32 ? 4 : 2;
+    return km->n_tiles > 0 && ((int64_t)C_in * esize) % kRowBytes == 0 && C_out % 2 == 0;
+}
+
 fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w, int32_t C_in,
                          int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st, int mode) {
     const bool out_f32 = (out_dt == FX_F32);
@@ -1147,42 +1201,15 @@ fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, 
     // workgroup each) is served faster by the scalar kernel spread over the whole chip
     const int64_t n_items = km->n_tiles * (int64_t)((C_out + kCoutSlice - 1) / kCoutSlice);
     const char* ft = getenv("FVDB_HOTPATH_FP32_TILES");      // "1": fp32 takes the tile kernel at any size (tests)
-    const bool mfma = km->n_tiles > 0 && ((int64_t)C_in * esize) % kRowBytes == 0 && C_out % 2 == 0 &&
+    const bool mfma = conv_tiles_shape_ok(km, in_dt, C_in, C_out) &&
                       (in_dt != FX_F32 || n_items >= compute_units() / 2 || (ft && ft[0] == '1')) &&
                       !(force && force[0] == '1');
     if (mfma) {
         void* wp = nullptr;
-        const size_t wbytes = packed_weight_bytes(km->K3, C_in, C_out, esize);   // a multiple of 64 bytes
-        FX_TRY(dev_alloc(&wp, wbytes + 8 * sizeof(int32_t), st));
-        int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
-        // maps whose tiles list one row per pair (strided; stride 1 back from a larger grid): the gather kernel;
-        // others: the LDS-staged kernel
-        const char* fg = getenv("FVDB_HOTPATH_CONV_GATHER");
-        const bool gather = (fg ? fg[0] == '1' : !map_shares_rows(km)) && in_dt != FX_F32 && C_out % kCoutSlice == 0;
-        launch_pack_weights(d_w, wp, km->K3, C_in, C_out, esize, counters, mode, gather ? kPackRows : kPackInterleaved, st);
-        hipError_t e = hipGetLastError();
-        if (e == hipSuccess && gather) {
-            ProfScope ps(kProfConvGather, st);
-            if (in_dt == FX_BF16)
-                e = out_f32 ? launch_gather<__bf16, true>(km, d_feat, wp, C_in, C_out, d_out, st)
-                            : launch_gather<__bf16, false>(km, d_feat, wp, C_in, C_out, d_out, st);
-            else
-                e = out_f32 ? launch_gather<_Float16, true>(km, d_feat, wp, C_in, C_out, d_out, st)
-                            : launch_gather<_Float16, false>(km, d_feat, wp, C_in, C_out, d_out, st);
-        } else if (e == hipSuccess) {
-            ProfScope ps(kProfConvMfma, st);
-            if (in_dt == FX_F32)
-                e = launch_mfma<float, true>(km, d_feat, wp, counters, C_in, C_out, d_out, st);
-            else if (in_dt == FX_BF16)
-                e = out_f32 ? launch_mfma<__bf16, true>(km, d_feat, wp, counters, C_in, C_out, d_out, st)
-                            : launch_mfma<__bf16, false>(km, d_feat, wp, counters, C_in, C_out, d_out, st);
-            else
-                e = out_f32 ? launch_mfma<_Float16, true>(km, d_feat, wp, counters, C_in, C_out, d_out, st)
-                            : launch_mfma<_Float16, false>(km, d_feat, wp, counters, C_in, C_out, d_out, st);
-        }
+        FX_TRY(dev_alloc(&wp, conv_scratch_bytes(km->K3, C_in, C_out, esize), st));
+        const fx_status rc = conv_tiles_with_scratch(km, d_feat, in_dt, d_w, C_in, C_out, d_out, out_dt, st, mode, wp);
         dev_free(wp, st);
-        if (e != hipSuccess) { set_error("convolution launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
-        return FX_OK;
+        return rc;
     }
     FX_TRY(kmap_ensure_dense(const_cast<fx_kmap*>(km), st));
     return conv_scalar_on_table(km->d_nbmap, km->n_out, km->K3, d_feat, in_dt, d_w, C_in, C_out, d_out, out_dt, st, mode);
@@ -1236,4 +1263,65 @@ extern "C" fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, f
     }
     if (km->n_out == 0) return FX_OK;
     return conv_apply(km, d_feat, in_dt, d_w, C_in, C_out, d_out, out_dt, (hipStream_t)stream, kWeightsForward);
+}
+
+// ---------------------------------------------------------------------------------- no allocation
+// fx_sparse_conv_fwd for callers that cannot allocate device memory (under graph capture, in tight serving loops):
+// the packed weights and the work-list counters live in a file-scope device array instead of an allocation.
+// The array's name stands for the symbol in host code; its device address is looked up once per device and only
+// that address is ever handed to kernels.
+namespace {
+constexpr size_t kNoAllocScratchBytes = FX_NOALLOC_MAX_WEIGHT_BYTES + 256;
+__device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];
+std::atomic<bool> g_scratch_ready[kMaxDevices];
+std::mutex g_scratch_mu;
+}  // namespace
+
+// Device address of the scratch array on the current device (looked up on first use per device).
+fx_status fx::conv_noalloc_setup(void** out_ptr) {
+    int dev = 0;
+    FX_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) { set_error("device ordinal %d out of range", dev); return FX_EDEVICE; }
+    if (!g_scratch_ready[dev].load(std::memory_order_acquire)) {
+        std::lock_guard<std::mutex> lock(g_scratch_mu);
+        if (!g_scratch_ready[dev].load(std::memory_order_relaxed)) {
+            void* ptr = nullptr;
+            FX_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+            if (!ptr) { set_error("hipGetSymbolAddress returned a null address"); return FX_EDEVICE; }
+            g_scratch_ptr[dev] = ptr;
+            g_scratch_ready[dev].store(true, std::memory_order_release);
+        }
+    }
+    if (out_ptr) *out_ptr = g_scratch_ptr[dev];
+    return FX_OK;
+}
+
+extern "C" fx_status fx_sparse_conv_fwd_noalloc(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w,
+                                                int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream) {
+    if (!km || !d_w || C_in < 1 || C_out < 1 || (km->n_in > 0 && !d_feat) || (km->n_out > 0 && !d_out)) {
+        set_error("fx_sparse_conv_fwd_noalloc: null pointer or non-positive channel count");
+        return FX_EINVAL;
+    }
+    if (in_dt != FX_F32 && in_dt != FX_F16 && in_dt != FX_BF16) { set_error("unknown input dtype"); return FX_EINVAL; }
+    if (out_dt != in_dt && out_dt != FX_F32) {
+        set_error("output dtype must equal the input dtype or be fp32");
+        return FX_EUNSUPPORTED;
+    }
+    if (km->n_out == 0) return FX_OK;
+    if (!conv_tiles_shape_ok(km, in_dt, C_in, C_out)) {
+        set_error("fx_sparse_conv_fwd_noalloc: only maps and shapes of the matrix-unit kernels (a tiled map, input rows in whole "
+                  "64-byte chunks, an even number of output channels); K = %d, C_in = %d, C_out = %d is not", km->K, C_in, C_out);
+        return FX_EUNSUPPORTED;
+    }
+    const size_t need = conv_scratch_bytes(km->K3, C_in, C_out, in_dt == FX_F32 ? 4 : 2);
+    if (need > kNoAllocScratchBytes) {
+        set_error("fx_sparse_conv_fwd_noalloc: the packed weights need %zu bytes, the static buffer holds %zu "
+                  "(FX_NOALLOC_MAX_WEIGHT_BYTES)", need, kNoAllocScratchBytes);
+        return FX_ERANGE;
+    }
+    void* ptr = nullptr;
+    FX_TRY(conv_noalloc_setup(&ptr));
+    return conv_tiles_with_scratch(km, d_feat, in_dt, d_w, C_in, C_out, d_out, out_dt, (hipStream_t)stream, kWeightsForward, ptr);
 }

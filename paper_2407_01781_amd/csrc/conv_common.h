@@ -140,6 +140,9 @@ void launch_pack_weights(const void* d_w, void* wp, int K3, int C_in, int C_out,
 // = sum over kappa of d_feat[map(o,kappa),:] . Wmode[kappa], C_in channels in, C_out channels out.
 fx_status conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w, int32_t C_in,
                      int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st, int mode);
+// Looks up (once per device) the device address of the static scratch array behind fx_sparse_conv_fwd_noalloc on the
+// current device; fx_init calls it so that the entry point's first call does no set-up work.
+fx_status conv_noalloc_setup(void** out_ptr);
 // The 3x3x3 stride-1 convolution of `src` [N, C_contract] into `dst` [N, C_produce] straight from the grid, leaf by
 // leaf, without a kernel map (Sec. 3.5 scenario 1); `mode` is kWeightsForward or kWeightsMirrored (input gradient).
 // FX_EUNSUPPORTED for shapes its kernels do not serve.  leaf_shape_supported says so without setting an error.

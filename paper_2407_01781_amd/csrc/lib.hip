@@ -1,5 +1,5 @@
 // Library-wide plumbing: error text, device allocation, pinned staging, version.
-#include "common.h"
+#include "conv_common.h"
 
 #include <stdarg.h>
 #include <stdlib.h>
@@ -292,5 +292,5 @@ extern "C" fx_status fx_init(void) {
         fx::set_error("no HIP device: %s", e == hipSuccess ? "device count is 0" : hipGetErrorString(e));
         return FX_EDEVICE;
     }
-    return FX_OK;
+    return fx::conv_noalloc_setup(nullptr);     // the static scratch buffer's address on the current device
 }
