@@ -1,6 +1,7 @@
 // Kernel-map build (Sec. 3.5): neighbour lookup through the tree for every output voxel and
 // stencil offset, and the tiled form the MFMA convolution consumes.
 #include "kmap.h"
+#include "dev_timing.h"
 #include "tree_device.h"
 
 #include <string.h>
@@ -95,14 +96,12 @@ __device__ __forceinline__ int lookup_entry(const NbLeafLds& lds, int oi, int oj
 // the coarse grid.  A fine leaf at origin 8t touches coarse coordinates 4t-1 .. 4t+4: two leaves per axis.
 template <int K, bool INV = false>
 __global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int64_t n_out, int32_t* __restrict__ nbr,
-                                 int32_t* __restrict__ tile_first_leaf, unsigned long long* __restrict__ stats) {
+                                 int32_t* __restrict__ tile_first_leaf) {
     constexpr int D0 = delta_min(K);
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (int64_t)tout.n_leaf * 27) return;
     const int f = (int)(e / 27), slot = (int)(e - (int64_t)f * 27);
     const fx_leaf* lf = tout.leaf + f;
-    if (e == 0)                          // the build's statistics (this is its first launch)
-        for (int q = 0; q < 4 + K * K * K; ++q) stats[q] = 0ull;
     if (slot == 0) {
         const int64_t begin = lf->offset, end = f + 1 < tout.n_leaf ? tout.leaf[f + 1].offset : n_out;
         for (int64_t t = (begin + kTileT - 1) / kTileT; t * kTileT < end; ++t) tile_first_leaf[t] = f;
@@ -182,59 +181,71 @@ k_nbmap(TreeView tin, TreeView tout, int stride, int32_t* __restrict__ nbmap) {
     }
 }
 
-#ifdef FX_KMAP_TIMING
-// development aid: per-workgroup phase timestamps (thread 0), read back with fx_debug_kmap_timing
-__device__ unsigned long long g_kmap_timing[4096 * 8];
-#define FX_KSTAMP(slot) do { if (threadIdx.x == 0 && blockIdx.x < 4096) g_kmap_timing[blockIdx.x * 8 + (slot)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define FX_KSTAMP(slot) do { } while (0)
-#endif
-
 // ---------------------------------------------------------------------------------- tiled form
 constexpr int kPackThreads = kTileT;          // one thread per output slot
 constexpr int kPackWaves = kPackThreads / 64;
 constexpr int kHaloHashSlots = 2048;
 constexpr int kLdsLeafRows = 56;             // leaves of a tile whose neighbour rows are kept in LDS
 constexpr int kRecHashSlots = 512;           // de-duplication of the neighbour leaves of those rows
-constexpr int kMaxRecs = 128;                // distinct neighbour-leaf records kept in LDS
-
-struct PackScratch {                          // live after the lookup phase
-    uint32_t key[kTileT];                     // slot of every position of the mask-sorted order
-    int32_t hash[kHaloHashSlots];             // open addressing over halo rows
-    int32_t halo[kMaxHalo];                   // distinct halo rows in insertion order
-    uint32_t slot_mask[kTileT];
-    union {
-        uint32_t slot_base[kTileT];           // direct tiles: first list entry of each slot
-        uint16_t halo_slot[kMaxHalo];         // other tiles: hash slot of each halo row
-    };
-    uint16_t slot_rank[kHaloHashSlots];       // hash slot -> rank of its row among the halo rows
-};
+constexpr int kMaxRecs = 80;                 // distinct neighbour-leaf records kept in LDS
+// Provisional 16-bit entry codes of the index pass: a window row (< kTileT), kCodeNear | offset of a row in the
+// index neighbourhood of the window, kCodeHalo | hash slot of a row farther away, or none.
+constexpr uint32_t kCodeNone = 0xFFFFu, kCodeHalo = 0x8000u, kCodeNear = 0x4000u;
+// Rows just outside a submanifold tile's own index range (in VDB order nearly all of a tile's outside rows lie within a
+// few thousand indices of it) are marked in a bitmap over [o0 - kNearSpan, o0 + kTileT + kNearSpan): one LDS atomic
+// without a return value per reference, and the bitmap's prefix popcounts are the ascending order.  Only rows
+// beyond that go through the hash.
+constexpr int kNearSpan = 4096;
+constexpr int kNearBits = 2 * kNearSpan + kTileT, kNearWords = kNearBits / 32;
+static_assert(kHaloHashSlots <= 0x4000 && kTileT <= 0x4000 && kNearBits <= 0x4000, "entry codes are 16 bits");
+static_assert(kNearWords <= kTileT, "one thread per bitmap word");
 
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+typedef __attribute__((ext_vector_type(4))) int32_t i32x4_t;
+typedef __attribute__((ext_vector_type(16))) uint32_t u32x16_t;
 
+// LDS of one tile builder.  Regions, who writes and who reads them, phase by phase (every phase boundary below
+// is a __syncthreads()):
+//   staging    writes stage.leaf_off, stage.rec_hash / slot_rec / rec_id, then rec_mask / rec_base / nbr_rows
+//   mask pass  reads  stage.leaf_off, nbr_rows, rec_mask;            writes vox, slot_mask
+//   sort       reads  slot_mask;                                      writes key (scratch, then slot per position)
+//   index pass reads  key, vox, slot_mask, nbr_rows, rec_mask, rec_base;  writes halo.* (or reads slot_base)
+//   halo rank  reads  halo.halo, halo.halo_slot, halo.near_bits;      writes slot_rank (over rec_mask, dead by then), near_prefix
+//   emission   reads  slot_rank, near_bits, near_prefix
+// The three arms of `u` are never live together: stage ends with the mask pass, halo / slot_base begin after
+// the sort.
 struct PackLds {
-    int32_t nb[kTileT * kMaxK3Tiled];         // the tile's map entries [slot][kappa]
-    union {
-        struct {                              // lookup phase
+    uint64_t rec_mask[(kMaxRecs + 1) * 8];    // mBitMask of Listing 1 per staged record; record kMaxRecs stays all zero
+    int32_t rec_base[(kMaxRecs + 1) * 8];     // per mask word: mOffset + the prefix-sum field that precedes it
+    int16_t nbr_rows[kLdsLeafRows * 27];      // neighbours of the tile's first leaves: >= 0 record, -1 none, -2 not staged
+    uint32_t vox[kTileT];                     // per slot: leaf of the tile | word << 9 | bit << 12 | origin parities << 18
+    uint32_t slot_mask[kTileT];               // per slot: taps with an active input
+    uint32_t key[kTileT];                     // sort scratch, then the slot at every position of the final order
+    union alignas(16) {
+        struct {
             int32_t leaf_off[kTileT];         // first index of every leaf of the tile
-            // neighbours of the tile's first leaves: >= 0 record in `rec`, -1 none, <= -2 leaf id -2-v (not staged)
-            int32_t nbr_rows[kLdsLeafRows * 27];
             int32_t rec_hash[kRecHashSlots];  // leaf id or -1
             uint16_t slot_rec[kRecHashSlots]; // hash slot -> record, 0xFFFF: not staged
             int32_t rec_id[kMaxRecs];
-            uint64_t rec_mask[(kMaxRecs + 1) * 8];  // mBitMask of Listing 1; record kMaxRecs stays all zero
-            int32_t rec_base[(kMaxRecs + 1) * 8];   // per mask word: mOffset + the prefix-sum field that precedes it
-        } look;
-        PackScratch s;
+        } stage;
+        struct {
+            int32_t hash[kHaloHashSlots];     // open addressing over the rows outside the window
+            int32_t halo[kMaxHalo];           // the distinct ones in insertion order
+            uint16_t halo_slot[kMaxHalo];     // and their hash slots
+            uint32_t near_bits[kNearWords];   // rows near the window: bit (row - (o0 - kNearSpan))
+            uint32_t near_prefix[kNearWords]; // rows marked in the words before each word
+        } halo;
+        uint32_t slot_base[kTileT];           // direct tiles: first list entry of each column
     } u;
     uint32_t group_mask[kGroupsPerTile];
-    uint32_t group_src[kGroupsPerTile];      // column block of the mask-sorted order that takes each final position
+    uint32_t group_dst[kGroupsPerTile];      // final position (tile_group_of(wave, slot)) of each block of the mask-sorted order
     uint32_t wave_mask[kTileWaves];
     uint32_t wave_block0[kTileWaves];
     uint32_t wave_sums[kPackWaves];
-    int32_t n_halo, n_blocks, n_pair_blocks, overflow, f_lo, n_leaves, n_rec;
+    int32_t n_halo, n_blocks, n_pair_blocks, overflow, n_rec;
 };
-static_assert(sizeof(PackLds) <= 80 * 1024, "two tile builders per compute unit");
+static_assert(sizeof(PackLds) <= 40 * 1024, "four tile builders per compute unit");
+static_assert(sizeof(uint16_t) * kHaloHashSlots <= sizeof(uint64_t) * kMaxRecs * 8, "slot_rank lives in rec_mask");
 
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int j) {
     const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, j);
@@ -262,23 +273,6 @@ __device__ __forceinline__ uint32_t block_sort_keys32(uint32_t v, uint32_t* lds)
         }
     }
     return v;
-}
-
-// in-LDS bitonic sort of P (power of two) int32 values
-__device__ __forceinline__ void lds_bitonic_sort(int32_t* a, int P) {
-    for (int k = 2; k <= P; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = threadIdx.x; t < P; t += blockDim.x) {
-                const int p = t ^ j;
-                if (p > t) {
-                    const int32_t x = a[t], y = a[p];
-                    const bool up = ((t & k) == 0);
-                    if ((x > y) == up) { a[t] = y; a[p] = x; }
-                }
-            }
-            __syncthreads();
-        }
-    }
 }
 
 // exclusive scan of one value per thread over the block
@@ -318,117 +312,202 @@ __device__ __forceinline__ int select64(uint64_t m, int r) {
     return pos;
 }
 
-// One workgroup per tile of kTileT consecutive outputs: lookups (one thread per voxel, straight
-// into LDS), mask sort, row de-duplication, block emission.  SUBM: input grid == output grid, so the
-// tile's own index range is the window; otherwise there is no window.  DEDUP: rows outside the window are
-// de-duplicated in the halo table (a stride-1 map between two grids: no window, all rows in the table);
-// without it the tile is "direct".
+// Where tap (a, b, c) of the voxel at word wn, row j, column k of its leaf looks: the slot 0..26 of the
+// neighbour-leaf table, the mask word n2 and the bit inside it (Listing 1's offset, split), all relative to
+// the voxel's own leaf, whose origin is a multiple of 8 and drops out.  The three axes are independent, so a
+// thread packs, once, one byte per tap coordinate and axis: bits 0-1 the leaf step s (0..2) along the axis, bits
+// 2-4 the coordinate inside that leaf, bit 5 "this tap coordinate exists" (TapAxes); a tap is then three byte
+// extractions with wave-uniform positions.
+//   forward maps   query = stride * p + D0 + (a, b, c); the table's first slot is the leaf of stride * origin + D0
+//   INV            (the inverse of the 3x3x3 stride-2 map) tap (a, b, c) of fine voxel p names the coarse voxel
+//                  (p + 1 - (a, b, c)) / 2 and only when that is even on every axis; the table's first slot is the
+//                  leaf of (origin - 1) / 2, so the parity of origin / 8 (one bit per axis) comes in
+struct TapAxes { uint32_t i, j, k; };
+
+template <int K, bool INV>
+__device__ __forceinline__ uint32_t tap_axis(int stride, int x, int par) {      // x: the voxel's coordinate inside its leaf
+    uint32_t packed = 0;
+#pragma unroll
+    for (int a = 0; a < K; ++a) {
+        int step, in, ok = 1;
+        if (INV) {
+            const int t = x + 1 - a, u = 4 * par + (t >> 1);
+            ok = !(t & 1);
+            step = (u >> 3) + 1 - par;
+            in = u & 7;
+        } else {
+            constexpr int D0 = delta_min(K), S0 = D0 < 0 ? -1 : 0;      // floor(D0 / 8)
+            const int t = stride * x + D0 + a;
+            step = (t >> 3) - S0;
+            in = t & 7;
+        }
+        packed |= (uint32_t)(step | (in << 2) | (ok << 5)) << (8 * a);
+    }
+    return packed;
+}
+
+template <int K, bool INV>
+__device__ __forceinline__ TapAxes tap_axes(int stride, int wn, int j, int k, int par) {
+    return TapAxes{tap_axis<K, INV>(stride, wn, par & 1), tap_axis<K, INV>(stride, j, (par >> 1) & 1),
+                   tap_axis<K, INV>(stride, k, (par >> 2) & 1)};
+}
+
+// tap (a, b, c), wave-uniform: slot of the neighbour-leaf table, mask word, bit, and whether the tap exists
+__device__ __forceinline__ void tap_query(const TapAxes& t, int a, int b, int c, int& slot, int& n2, int& bit6, bool& ok) {
+    const uint32_t qi = (t.i >> (8 * a)) & 0xFFu, qj = (t.j >> (8 * b)) & 0xFFu, qk = (t.k >> (8 * c)) & 0xFFu;
+    slot = (int)((qi & 3u) * 9u + (qj & 3u) * 3u + (qk & 3u));
+    n2 = (int)((qi >> 2) & 7u);
+    bit6 = (int)((((qj >> 2) & 7u) << 3) | ((qk >> 2) & 7u));
+    ok = ((qi & qj & qk) >> 5) & 1u;
+}
+
+// Mask word n2 of the neighbour leaf in slot `slot` of tile-leaf `lo` and the index of that word's first voxel
+// (Listing 1: mOffset + prefix field).  A missing leaf reads the all-zero record; a leaf whose record is not
+// staged (rows beyond kLdsLeafRows, records beyond kMaxRecs) is fetched from the grid.
+__device__ __forceinline__ void neighbour_word(const PackLds& L, const TreeView& tin, const int32_t* __restrict__ nbr_row_global,
+                                               int lo, int slot, int n2, uint64_t& w, int32_t& base) {
+    const int v = lo < kLdsLeafRows ? (int)L.nbr_rows[lo * 27 + slot] : -2;
+    const int rec = v >= 0 ? v : kMaxRecs;
+    w = L.rec_mask[rec * 8 + n2];
+    base = L.rec_base[rec * 8 + n2];
+    if (__builtin_expect(v == -2, 0)) {
+        const int id = nbr_row_global[slot];
+        if (id >= 0) {
+            const fx_leaf* nl = tin.leaf + id;
+            w = nl->mask[n2];
+            const uint64_t npre = nl->prefix;
+            base = (int32_t)nl->offset + (n2 ? (int32_t)((npre >> (9 * (n2 - 1))) & 511) : 0);
+        }
+    }
+}
+
+// a fresh read of an LDS word that other waves update with atomics
+__device__ __forceinline__ int32_t lds_peek(const int32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+__device__ __forceinline__ uint32_t popc_below(uint64_t w, int bit6) {   // set bits of w below position bit6
+    const uint32_t wlo = (uint32_t)w, whi = (uint32_t)(w >> 32);
+    const uint32_t mlo = bit6 >= 32 ? 0xFFFFFFFFu : ((1u << bit6) - 1u);
+    const uint32_t mhi = bit6 >= 32 ? ((1u << (bit6 - 32)) - 1u) : 0u;
+    return (uint32_t)(__popc(wlo & mlo) + __popc(whi & mhi));
+}
+
+// One workgroup per tile of kTileT consecutive outputs.  SUBM: input grid == output grid, so the tile's own
+// index range is the window; otherwise there is no window.  DEDUP: rows outside the window are de-duplicated in
+// the halo table (a stride-1 map between two grids: no window, all rows in the table); without it the tile is
+// "direct".  Phases:
+//   staging     the distinct neighbour leaves of the tile's leaves, their records into LDS
+//   mask pass   thread = output voxel: which of its K^3 taps have an active input (bit tests only; for the 3x3x3
+//               stride-1 stencil three taps per mask-word read)
+//   sort, deal  voxels ordered by tap mask, cut into column blocks, blocks dealt to the convolution's waves
+//   index pass  thread = column of the final order, laid out as the id blocks are (voxel column, wave slot):
+//               Listing 1's prefix + popcount for the taps of the wave's union mask, one uniform step per offset;
+//               rows outside the window enter the halo table; the 16-bit entries stay in registers
+//   halo rank, emission   the halo rows ranked; every thread writes its own entries, a wave 128 consecutive bytes
 template <int K, bool SUBM, bool INV = false, bool DEDUP = SUBM>
-__global__ void __launch_bounds__(kPackThreads)
+__global__ void __launch_bounds__(kPackThreads, 8)
 k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict__ leaf_nbr,
               const int32_t* __restrict__ tile_first_leaf, int64_t n_out, TileHeader* __restrict__ tile_hdr,
               uint16_t* __restrict__ tile_perm, int32_t* __restrict__ tile_rows, int row_stride,
-              uint16_t* __restrict__ tile_blocks, int block_stride, unsigned long long* __restrict__ stats) {
+              uint16_t* __restrict__ tile_blocks, int block_stride) {
     constexpr int K3 = K * K * K;
     static_assert(K3 <= kMaxK3Tiled, "tiled path supports up to 27 offsets");
     extern __shared__ __align__(16) unsigned char lds_raw[];
     PackLds& L = *reinterpret_cast<PackLds*>(lds_raw);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     const int64_t tile = blockIdx.x;
     const int64_t o0 = tile * kTileT;
     const int n_valid = (int)min((int64_t)kTileT, n_out - o0);
 
-    FX_KSTAMP(0);
-    // ---- which output leaves overlap [o0, o0 + n_valid)
-    if (tid == 0) {
-        // leaves from the one holding the tile's first voxel to the one holding the next tile's first
-        // voxel.  That last leaf may start exactly at the tile's end and hold none of the tile's voxels;
-        // kTileT voxels lie in at most kTileT leaves, so the count is cut there (a tile of kTileT one-voxel
-        // leaves would otherwise list kTileT + 1 and write past leaf_off)
-        const int lo = tile_first_leaf[tile];
-        const int a = (tile + 1) * kTileT < n_out ? tile_first_leaf[tile + 1] : tout.n_leaf - 1;
-        L.f_lo = lo;
-        L.n_leaves = min(a + 1 - lo, kTileT);
-        L.n_halo = 0; L.n_blocks = 0; L.n_pair_blocks = 0; L.overflow = 0; L.n_rec = 0;
-    }
-    for (int e = tid; e < kRecHashSlots; e += kPackThreads) { L.u.look.rec_hash[e] = -1; L.u.look.slot_rec[e] = 0xFFFF; }
-    if (tid < 8) { L.u.look.rec_mask[kMaxRecs * 8 + tid] = 0; L.u.look.rec_base[kMaxRecs * 8 + tid] = 0; }
+    FX_STAMP(0);
+    FX_STAMP_HWID(8);
+    // ---- which output leaves overlap [o0, o0 + n_valid): from the one holding the tile's first voxel to the one
+    // holding the next tile's first voxel.  That last leaf may start exactly at the tile's end and hold none of
+    // the tile's voxels; kTileT voxels lie in at most kTileT leaves, so the count is cut there.
+    const int f_lo = tile_first_leaf[tile];
+    const int f_hi = (tile + 1) * kTileT < n_out ? tile_first_leaf[tile + 1] : tout.n_leaf - 1;
+    const int n_leaves = min(f_hi + 1 - f_lo, kTileT);
+    static_assert(sizeof(L.u.stage.leaf_off) / sizeof(int32_t) >= kTileT, "one entry per possible leaf of a tile");
+    if (tid == 0) { L.n_halo = 0; L.n_blocks = 0; L.n_pair_blocks = 0; L.overflow = 0; L.n_rec = 0; }
+    if (tid < kTileWaves) L.wave_mask[tid] = 0;
+    for (int e = tid; e < kRecHashSlots; e += kPackThreads) { L.u.stage.rec_hash[e] = -1; L.u.stage.slot_rec[e] = 0xFFFF; }
+    if (tid < 8) { L.rec_mask[kMaxRecs * 8 + tid] = 0; L.rec_base[kMaxRecs * 8 + tid] = 0; }
+    for (int li = tid; li < n_leaves; li += kPackThreads) L.u.stage.leaf_off[li] = (int32_t)tout.leaf[f_lo + li].offset;
     __syncthreads();
 
-    // ---- lookups: one thread per output voxel.  The thread finds its leaf (binary search over the
-    // tile's leaf offsets), its position inside the leaf (select on the leaf mask), and evaluates
-    // Listing 1 for its K^3 neighbours through the neighbour-leaf table; the few leaf records a
-    // tile touches stay in the L1 cache.
-    uint32_t mask = 0, hmask = 0;     // taps of this thread's voxel; those whose row lies outside the window
+    // ---- staging.  The 80-byte records (Listing 1) of the distinct neighbour leaves go to LDS, so that no
+    // lookup chases a pointer through global memory: (1) de-duplicate the neighbour ids of the tile's leaves in
+    // a hash, (2) number the distinct ones, (3) fetch their records with independent loads and rewrite the
+    // neighbour rows as record numbers.
     {
-        const int f_lo = L.f_lo, n_leaves = L.n_leaves;
-        for (int li = tid; li < n_leaves; li += kPackThreads) L.u.look.leaf_off[li] = (int32_t)tout.leaf[f_lo + li].offset;
-        // The 80-byte records (Listing 1) of the distinct neighbour leaves are staged in LDS, so the
-        // 27 lookups of a voxel chase no pointer through global memory: (1) de-duplicate the
-        // neighbour ids of the tile's leaves in a hash, (2) number the distinct ones, (3) fetch
-        // their records with independent loads and rewrite the neighbour rows as record numbers.
-        {
-            constexpr int kCandPerThread = (kLdsLeafRows * 27 + kPackThreads - 1) / kPackThreads;
-            const int n_cand = min(n_leaves, kLdsLeafRows) * 27;
-            const int32_t* src = leaf_nbr + (int64_t)f_lo * 27;
-            int32_t cand_id[kCandPerThread];
-            int cand_slot[kCandPerThread];
+        constexpr int kCandPerThread = (kLdsLeafRows * 27 + kPackThreads - 1) / kPackThreads;
+        const int n_cand = min(n_leaves, kLdsLeafRows) * 27;
+        const int32_t* src = leaf_nbr + (int64_t)f_lo * 27;
+        int32_t cand_id[kCandPerThread];
+        int cand_slot[kCandPerThread];
 #pragma unroll
-            for (int q = 0; q < kCandPerThread; ++q) {
-                const int e = tid + q * kPackThreads;
-                cand_id[q] = e < n_cand ? src[e] : -1;
-                cand_slot[q] = -1;
-                if (cand_id[q] < 0) continue;
-                uint32_t h = ((uint32_t)cand_id[q] * 0x9E3779B1u) >> 23;   // 9 bits
-                for (int probe = 0; probe < kRecHashSlots; ++probe) {
-                    const int32_t cur = ((volatile int32_t*)L.u.look.rec_hash)[h];
-                    if (cur == cand_id[q]) { cand_slot[q] = (int)h; break; }
-                    if (cur < 0) {
-                        const int32_t old = atomicCAS(&L.u.look.rec_hash[h], -1, cand_id[q]);
-                        if (old < 0 || old == cand_id[q]) { cand_slot[q] = (int)h; break; }
-                    }
-                    h = (h + 1) & (kRecHashSlots - 1);
-                }
-            }
-            __syncthreads();
-            if (tid < kRecHashSlots && L.u.look.rec_hash[tid] >= 0) {
-                const int r = atomicAdd(&L.n_rec, 1);
-                if (r < kMaxRecs) { L.u.look.slot_rec[tid] = (uint16_t)r; L.u.look.rec_id[r] = L.u.look.rec_hash[tid]; }
-            }
-            __syncthreads();
-            const int n_rec = min(L.n_rec, kMaxRecs);
-            for (int e = tid; e < n_rec * 8; e += kPackThreads) {
-                const int r = e >> 3, w = e & 7;
-                const fx_leaf* nl = tin.leaf + L.u.look.rec_id[r];
-                L.u.look.rec_mask[e] = nl->mask[w];
-                L.u.look.rec_base[e] = (int32_t)nl->offset + (w ? (int32_t)((nl->prefix >> (9 * (w - 1))) & 511) : 0);
-            }
+        for (int q = 0; q < kCandPerThread; ++q) {
+            const int e = tid + q * kPackThreads;
+            cand_id[q] = e < n_cand ? src[e] : -1;
+        }
 #pragma unroll
-            for (int q = 0; q < kCandPerThread; ++q) {
-                const int e = tid + q * kPackThreads;
-                if (e >= n_cand) continue;
-                int32_t v = -1;
-                if (cand_id[q] >= 0) {
-                    const uint16_t r = cand_slot[q] >= 0 ? L.u.look.slot_rec[cand_slot[q]] : (uint16_t)0xFFFF;
-                    v = r != 0xFFFF ? (int32_t)r : -2 - cand_id[q];
+        for (int q = 0; q < kCandPerThread; ++q) {
+            cand_slot[q] = -1;
+            if (cand_id[q] < 0) continue;
+            uint32_t h = ((uint32_t)cand_id[q] * 0x9E3779B1u) >> 23;   // 9 bits
+            for (int probe = 0; probe < kRecHashSlots; ++probe) {
+                const int32_t cur = lds_peek(&L.u.stage.rec_hash[h]);
+                if (cur == cand_id[q]) { cand_slot[q] = (int)h; break; }
+                if (cur < 0) {
+                    const int32_t old = atomicCAS(&L.u.stage.rec_hash[h], -1, cand_id[q]);
+                    if (old < 0 || old == cand_id[q]) { cand_slot[q] = (int)h; break; }
                 }
-                L.u.look.nbr_rows[e] = v;
+                h = (h + 1) & (kRecHashSlots - 1);
             }
         }
         __syncthreads();
-        int32_t* my_nb = L.nb + tid * K3;
+        if (tid < kRecHashSlots && L.u.stage.rec_hash[tid] >= 0) {
+            const int r = atomicAdd(&L.n_rec, 1);
+            if (r < kMaxRecs) { L.u.stage.slot_rec[tid] = (uint16_t)r; L.u.stage.rec_id[r] = L.u.stage.rec_hash[tid]; }
+        }
+        __syncthreads();
+        const int n_rec = min(L.n_rec, kMaxRecs);
+        for (int e = tid; e < n_rec * 8; e += kPackThreads) {
+            const int r = e >> 3, w = e & 7;
+            const fx_leaf* nl = tin.leaf + L.u.stage.rec_id[r];
+            L.rec_mask[e] = nl->mask[w];
+            L.rec_base[e] = (int32_t)nl->offset + (w ? (int32_t)((nl->prefix >> (9 * (w - 1))) & 511) : 0);
+        }
+#pragma unroll
+        for (int q = 0; q < kCandPerThread; ++q) {
+            const int e = tid + q * kPackThreads;
+            if (e >= n_cand) continue;
+            int v = -1;
+            if (cand_id[q] >= 0) {
+                const uint16_t r = cand_slot[q] >= 0 ? L.u.stage.slot_rec[cand_slot[q]] : (uint16_t)0xFFFF;
+                v = r != 0xFFFF ? (int)r : -2;
+            }
+            L.nbr_rows[e] = (int16_t)v;
+        }
+    }
+    __syncthreads();
+    FX_STAMP(1);
+
+    // ---- mask pass: thread = output voxel (slot tid).  The thread finds its leaf (binary search over the tile's
+    // leaf offsets) and its position inside the leaf (select on the leaf mask), then tests its taps.
+    uint32_t mask = 0;
+    {
+        uint32_t vox = 0;
         if (tid < n_valid) {
-            const int32_t w_lo = SUBM ? (int32_t)o0 : 0, w_n = SUBM ? n_valid : 0;
-            constexpr int D0 = delta_min(K);
             const int32_t o = (int32_t)(o0 + tid);
             int lo = 0, hi = n_leaves;   // last leaf of the tile with offset <= o
             while (hi - lo > 1) {
                 const int mid = (lo + hi) >> 1;
-                if (L.u.look.leaf_off[mid] <= o) lo = mid; else hi = mid;
+                if (L.u.stage.leaf_off[mid] <= o) lo = mid; else hi = mid;
             }
-            const int f = f_lo + lo;
-            const fx_leaf* lf = tout.leaf + f;
-            int r = o - L.u.look.leaf_off[lo];           // rank of the voxel inside its leaf
+            const fx_leaf* lf = tout.leaf + (f_lo + lo);
+            const int r = o - L.u.stage.leaf_off[lo];           // rank of the voxel inside its leaf
             const uint64_t pre = lf->prefix;
             int wn = 0, before = 0;                 // mask word holding the voxel, active voxels before that word
 #pragma unroll
@@ -437,257 +516,253 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
                 if (fld <= r) { wn = w + 1; before = fld; }
             }
             const int bit = select64(lf->mask[wn], r - before);
-            const int pi = lf->origin[0] + wn, pj = lf->origin[1] + (bit >> 3), pk = lf->origin[2] + (bit & 7);
-            // INV (inverse of the 3x3x3 stride-2 map): offset (a,b,c) of fine voxel p names the coarse voxel
-            // (p - delta) / 2, delta = (a,b,c) - 1, and only when p - delta is even on every axis
-            const int bi = INV ? ((lf->origin[0] - 1) >> 1) >> 3 : (stride * lf->origin[0] + D0) >> 3,
-                      bj = INV ? ((lf->origin[1] - 1) >> 1) >> 3 : (stride * lf->origin[1] + D0) >> 3,
-                      bk = INV ? ((lf->origin[2] - 1) >> 1) >> 3 : (stride * lf->origin[2] + D0) >> 3;
-            const int32_t* nbr_row = leaf_nbr + (int64_t)f * 27;
-            const bool row_in_lds = lo < kLdsLeafRows;
-            // kept as rolled loops: the fully unrolled form of this divergent body gave wrong entries
-            // for the offsets (-1,0,0), (0,-1,0), (0,0,-1) on gfx950 (cause not established; the
-            // parity tests against the oracle catch it)
-            const int32_t* lds_row = L.u.look.nbr_rows + lo * 27;
-            int kappa = 0;
-#pragma unroll 1
-            for (int a = 0; a < K; ++a) {
-                const int qi_full = INV ? pi + 1 - a : stride * pi + D0 + a;
-                const bool even_i = INV ? !(qi_full & 1) : true;
-                const int qi = INV ? qi_full >> 1 : qi_full;
-                const int si = ((qi >> 3) - bi) * 9, n2 = qi & 7;
-#pragma unroll 1
-                for (int b2 = 0; b2 < K; ++b2) {
-                    const int qj_full = INV ? pj + 1 - b2 : stride * pj + D0 + b2;
-                    const bool even_ij = INV ? even_i && !(qj_full & 1) : true;
-                    const int qj = INV ? qj_full >> 1 : qj_full;
-                    const int sij = si + ((qj >> 3) - bj) * 3, bj8 = (qj & 7) << 3;
-#pragma unroll 1
-                    for (int c = 0; c < K; ++c, ++kappa) {
-                        const int qk_full = INV ? pk + 1 - c : stride * pk + D0 + c;
-                        const bool even_ijk = INV ? even_ij && !(qk_full & 1) : true;
-                        const int qk = INV ? qk_full >> 1 : qk_full;
-                        const int slot = sij + ((qk >> 3) - bk);
-                        // The common case runs without a branch: a missing neighbour leaf reads the all-zero
-                        // record kMaxRecs, whose mask has no bit to find.
-                        const int v = row_in_lds ? lds_row[slot] : -2 - nbr_row[slot];   // -2 - (-1) = -1
-                        const int rec = v >= 0 ? v : kMaxRecs;
-                        uint64_t w = L.u.look.rec_mask[rec * 8 + n2];
-                        int32_t base = L.u.look.rec_base[rec * 8 + n2];
-                        if (__builtin_expect(v <= -2, 0)) {   // record not staged: three independent global loads
-                            const fx_leaf* nl = tin.leaf + (-2 - v);
-                            w = nl->mask[n2];
-                            const uint64_t npre = nl->prefix;
-                            base = (int32_t)nl->offset + (n2 ? (int32_t)((npre >> (9 * (n2 - 1))) & 511) : 0);
-                        }
-                        const int bit6 = bj8 | (qk & 7);
-                        const uint32_t wlo = (uint32_t)w, whi = (uint32_t)(w >> 32);
-                        // bits below bit6, per half: all of the low half once bit6 >= 32
-                        const uint32_t mlo = bit6 >= 32 ? 0xFFFFFFFFu : ((1u << bit6) - 1u);
-                        const uint32_t mhi = bit6 >= 32 ? ((1u << (bit6 - 32)) - 1u) : 0u;
-                        const bool present = even_ijk && (((bit6 >= 32 ? whi : wlo) >> (bit6 & 31)) & 1u) != 0;
-                        const int idx = base + __popc(wlo & mlo) + __popc(whi & mhi);
-                        // entry encoding from here on: -1 none; -2 - id: row win_lo + id of the window;
-                        // >= 0: a row outside the window, not yet entered in the halo table
-                        const bool in_win = (uint32_t)(idx - w_lo) < (uint32_t)w_n;
-                        const int res = present ? (in_win ? -2 - (idx - w_lo) : idx) : -1;
-                        mask |= (uint32_t)present << kappa;
-                        hmask |= (uint32_t)(present && !in_win) << kappa;
-                        my_nb[kappa] = res;
+            const int j = bit >> 3, k = bit & 7;
+            int par = 0;
+            if (INV) par = ((lf->origin[0] >> 3) & 1) | (((lf->origin[1] >> 3) & 1) << 1) | (((lf->origin[2] >> 3) & 1) << 2);
+            vox = (uint32_t)lo | ((uint32_t)wn << 9) | ((uint32_t)bit << 12) | ((uint32_t)par << 18);
+            const int32_t* nbr_row = leaf_nbr + (int64_t)(f_lo + lo) * 27;
+            if (K == 3 && !INV && stride == 1) {
+                // The 3x3x3 stencil: the taps (a, b, 0..2) are three adjacent bits of one mask-word row, padded
+                // at the leaf's k faces with the facing bit of the leaf beyond (read only by the voxels at k = 0
+                // and k = 7; the others re-read the row's own word).
+                const int side = k == 0 ? -1 : 1, side_bit = k == 0 ? 7 : 0;
+#pragma unroll
+                for (int a = 0; a < 3; ++a) {
+                    const int ti = wn - 1 + a, si = (ti >> 3) + 1, n2 = ti & 7;
+#pragma unroll
+                    for (int b = 0; b < 3; ++b) {
+                        const int tj = j - 1 + b, sj = (tj >> 3) + 1, jr = (tj & 7) << 3;
+                        const int sc = (si * 3 + sj) * 3 + 1;
+                        uint64_t wc, ws;
+                        int32_t unused;
+                        neighbour_word(L, tin, nbr_row, lo, sc, n2, wc, unused);
+                        neighbour_word(L, tin, nbr_row, lo, sc + side, n2, ws, unused);
+                        const uint32_t row8 = (uint32_t)(wc >> jr) & 0xFFu;
+                        const uint32_t sbit = (uint32_t)(ws >> (jr + side_bit)) & 1u;
+                        const uint32_t row10 = (row8 << 1) | (k == 0 ? sbit : sbit << 9);
+                        mask |= ((row10 >> k) & 7u) << (a * 9 + b * 3);
                     }
                 }
-            }
-        } else {
-#pragma unroll
-            for (int kappa = 0; kappa < K3; ++kappa) my_nb[kappa] = -1;
-        }
-    }
-    __syncthreads();
-
-    FX_KSTAMP(1);
-    // ---- per-slot mask; halo rows into the hash
-    PackScratch& S = L.u.s;
-    for (int e = tid; e < kHaloHashSlots; e += kPackThreads) S.hash[e] = -1;
-    __syncthreads();
-    const int32_t win_lo = SUBM ? (int32_t)o0 : 0;
-    const int32_t win_n = SUBM ? n_valid : 0;
-    // rows outside the window go into the halo table; an entry that is in becomes -1024 - (table slot)
-    for (uint32_t hm = DEDUP ? hmask : 0u; hm; hm &= hm - 1) {
-        const int kappa = __ffs(hm) - 1;
-        const int32_t r = L.nb[tid * K3 + kappa];
-        uint32_t h = ((uint32_t)r * 0x9E3779B1u) >> 21;  // 11 bits
-        bool in = false;
-        for (;;) {
-            const int32_t cur = ((volatile int32_t*)S.hash)[h];
-            if (cur == r) { in = true; break; }
-            if (cur < 0) {
-                if (((volatile int32_t*)&L.overflow)[0]) break;
-                const int32_t old = atomicCAS(&S.hash[h], -1, r);
-                if (old < 0) {
-                    const int pos = atomicAdd(&L.n_halo, 1);
-                    if (pos < kMaxHalo) { S.halo[pos] = r; S.halo_slot[pos] = (uint16_t)h; in = true; } else L.overflow = 1;
-                    break;
+            } else {
+                const TapAxes axes = tap_axes<K, INV>(stride, wn, j, k, par);
+#pragma unroll 1
+                for (int kappa = 0; kappa < K3; ++kappa) {
+                    int slot, n2, bit6;
+                    bool ok;
+                    tap_query(axes, kappa / (K * K), (kappa / K) % K, kappa % K, slot, n2, bit6, ok);
+                    uint64_t w;
+                    int32_t unused;
+                    neighbour_word(L, tin, nbr_row, lo, slot, n2, w, unused);
+                    mask |= (uint32_t)(ok && ((w >> bit6) & 1ull)) << kappa;
                 }
-                if (old == r) { in = true; break; }
             }
-            h = (h + 1) & (kHaloHashSlots - 1);
         }
-        if (in) L.nb[tid * K3 + kappa] = -1024 - (int32_t)h;
+        L.vox[tid] = vox;
+        L.slot_mask[tid] = mask;
     }
-    S.slot_mask[tid] = mask;
-    __syncthreads();
-    const bool direct = !DEDUP || L.overflow != 0;
-    const int n_halo = direct ? 0 : L.n_halo;
+    FX_STAMP(2);
 
-    FX_KSTAMP(2);
-    // ---- order outputs by mask; order halo rows by index; per-slot list base (direct tiles)
-    // The sort key keeps 23 of the 27 mask bits (the four corner taps of the lowest i-plane weigh
-    // least in the order and are dropped) so that key and slot fit 32 bits; S.key then holds the
-    // slot of every sorted position.
-    const uint32_t low9 = mask & 511u;
-    const uint32_t key23 = ((mask >> 9) << 5) | ((low9 >> 1) & 1u) | (((low9 >> 3) & 7u) << 1) | (((low9 >> 7) & 1u) << 4);
-    const uint32_t sorted = block_sort_keys32((key23 << 9) | (uint32_t)tid, S.key);
-    __syncthreads();
-    S.key[tid] = sorted & 511u;
-    __syncthreads();
-    FX_KSTAMP(3);
-    int32_t* my_rows = tile_rows + tile * (int64_t)row_stride;
-    if (!direct) {
-        // rank of every halo row among the halo rows (all distinct): its position in the
-        // ascending row list and, offset by win_n, its local id
-        for (int i = tid; i < n_halo; i += kPackThreads) {
-            const int32_t v = S.halo[i];
-            int rank = 0;
-            for (int j = 0; j < n_halo; ++j) rank += (S.halo[j] < v);
-            my_rows[rank] = v;
-            S.slot_rank[S.halo_slot[i]] = (uint16_t)rank;
-        }
-    }
-    FX_KSTAMP(4);
-    uint32_t n_list;
+    // ---- order the outputs by mask.  The sort key keeps 23 of the 27 mask bits (the four corner taps of the
+    // lowest i-plane weigh least in the order and are dropped) so that key and slot fit 32 bits.  From here on
+    // thread tid stands for position tid of the mask-sorted order: column tid % kGroup of sorted block tid / kGroup.
+    uint32_t my_slot;
     {
-        uint32_t total;
-        const uint32_t base = block_scan_excl(direct ? (uint32_t)__popc(mask) : 0u, L.wave_sums, &total);
-        if (direct) S.slot_base[tid] = base;
-        n_list = direct ? total : (uint32_t)n_halo;
+        const uint32_t low9 = mask & 511u;
+        const uint32_t key23 = ((mask >> 9) << 5) | ((low9 >> 1) & 1u) | (((low9 >> 3) & 7u) << 1) | (((low9 >> 7) & 1u) << 4);
+        my_slot = block_sort_keys32((key23 << 9) | (uint32_t)tid, L.key) & 511u;    // its barriers also publish vox / slot_mask
+        mask = L.slot_mask[my_slot];
+        // union of the masks of every column block: OR over the 32 lanes that hold it
+        uint32_t gm = mask;
+#pragma unroll
+        for (int d = 1; d < kGroup; d <<= 1) gm |= (uint32_t)__shfl_xor((int)gm, d);
+        if ((tid & (kGroup - 1)) == 0) L.group_mask[tid / kGroup] = gm;
     }
-    uint32_t my_gm = 0;
-    if (tid < kGroupsPerTile) {
-        for (int n = 0; n < kGroup; ++n) my_gm |= S.slot_mask[S.key[tid * kGroup + n]];
-        L.group_mask[tid] = my_gm;
-    }
+    const uint32_t my_vox = L.vox[my_slot];
     __syncthreads();
-    // Deal the column blocks to the consumer waves of the convolution by cost (offsets present =
-    // multiplies issued): rank the blocks by cost, heaviest first, and deal the ranks to the waves
-    // in serpentine order (0 1 2 3 3 2 1 0 ...), which evens out the sums.  Position
-    // tile_group_of(w, gi) of the final order takes block group_src[...] of the sorted order.
+    FX_STAMP(3);
+    // Deal the column blocks to the consumer waves of the convolution by cost (offsets present = multiplies
+    // issued): rank the blocks by cost, heaviest first, and deal the ranks to the waves in serpentine order
+    // (0 1 2 3 3 2 1 0 ...), which evens out the sums.  Sorted block s becomes block group_dst[s] of the final
+    // order (= tile_group_of(wave, wave slot)).  Tiles that list one row per pair go to the one-wave-per-block
+    // gather kernels, which gain nothing from the deal and run the mask-sorted order slightly faster: they keep it.
     if (tid < kGroupsPerTile) {
-        const int c = __popc(my_gm);
+        const int c = __popc(L.group_mask[tid]);
         int rank = 0;
+#pragma unroll
         for (int g = 0; g < kGroupsPerTile; ++g) {
             const int cg = __popc(L.group_mask[g]);
             rank += (cg > c) || (cg == c && g < tid);
         }
         const int gi = rank / kTileWaves, r = rank % kTileWaves;
-        // (tiles without staged rows go to the one-wave-per-block gather kernels, which gain nothing
-        // from the deal and run the mask-sorted order slightly faster: they keep it)
-        if (direct) L.group_src[tid] = (uint32_t)tid;
-        else L.group_src[tile_group_of((gi & 1) ? kTileWaves - 1 - r : r, gi)] = (uint32_t)tid;
+        L.group_dst[tid] = DEDUP ? (uint32_t)tile_group_of((gi & 1) ? kTileWaves - 1 - r : r, gi) : (uint32_t)tid;
     }
     __syncthreads();
-    const uint32_t dealt = S.key[L.group_src[tid / kGroup] * kGroup + tid % kGroup];   // slot at final position tid
-    if (tid < kGroupsPerTile) my_gm = L.group_mask[L.group_src[tid]];
-    __syncthreads();
-    S.key[tid] = dealt;
-    if (tid < kGroupsPerTile) L.group_mask[tid] = my_gm;
-    __syncthreads();
-    if (tid == 0) {
-        int run = 0, pairs = 0;
-        for (int w = 0; w < kTileWaves; ++w) {
-            uint32_t wm = 0;
-            for (int gi = 0; gi < kGroupsPerWave; ++gi) {
-                const uint32_t gm = L.group_mask[tile_group_of(w, gi)];
-                wm |= gm;
-                pairs += __popc(gm);
-            }
-            L.wave_mask[w] = wm;
-            L.wave_block0[w] = run;
-            run += __popc(wm);
-        }
-        L.n_blocks = run;
-        L.n_pair_blocks = pairs;
-    }
-    __syncthreads();
-
-    FX_KSTAMP(5);
-    const bool lds_codes = !direct && (win_n + n_halo <= kRowCap);
-
-    // ---- header, permutation, row list
-    TileHeader* H = tile_hdr + tile;
-    if (tid == 0) {
-        H->win_lo = direct ? 0 : win_lo; H->win_n = direct ? 0 : win_n; H->n_list = (int32_t)n_list;
-        H->n_blocks = L.n_blocks; H->n_out = n_valid; H->flags = direct ? kTileDirect : (lds_codes ? kTileLdsOffsets : 0);
-        H->n_pair_blocks = L.n_pair_blocks; H->pad = 0;
-        atomicAdd(&stats[0], (unsigned long long)L.n_pair_blocks * kGroup);
-        atomicAdd(&stats[1], (unsigned long long)(direct ? n_list : (uint32_t)(win_n + n_halo)));
-        if (direct) atomicAdd(&stats[2], 1ull);
-        atomicAdd(&stats[3], (unsigned long long)(sizeof(TileHeader) + sizeof(uint16_t) * kTileT + sizeof(int32_t) * n_list +
-                                                  sizeof(uint16_t) * kIdBlockElems * (size_t)L.n_blocks));
-    }
-    if (tid < kGroupsPerTile) H->group_mask[tid] = L.group_mask[tid];
-    if (tid < kTileWaves) { H->wave_mask[tid] = L.wave_mask[tid]; H->wave_block0[tid] = L.wave_block0[tid]; }
-    tile_perm[tile * kTileT + tid] = (uint16_t)dealt;
-    if (direct) {
-        uint32_t pos = S.slot_base[tid];
-        for (int kappa = 0; kappa < K3; ++kappa) {
-            const int32_t v = L.nb[tid * K3 + kappa];
-            if (v == -1) continue;
-            my_rows[pos++] = v >= 0 ? v : (v <= -1024 ? S.hash[-1024 - v] : win_lo + (-2 - v));
-        }
-    }
-
-    FX_KSTAMP(6);
-    // ---- id blocks: thread (wave w, voxel column n, share q) fills the entries [voxel n][group
-    // slots] of every kQuarters-th block of wave w, so that a block is written as 32 consecutive
-    // entries
-    {
-        constexpr int kQuarters = kPackThreads / (kTileWaves * kGroup);      // threads per (wave, voxel column)
-        constexpr int kEntryWords = kGroupsPerWave / 2;                     // 32-bit words per entry
-        const int w = tid / (kQuarters * kGroup), q = (tid / kGroup) % kQuarters, n = tid % kGroup;
-        int slot[kGroupsPerWave];
-        uint32_t smask[kGroupsPerWave], sbase[kGroupsPerWave];
+    const int my_g = (int)L.group_dst[tid / kGroup];                      // final block of this thread's column
+    const int cw = tile_wave_of(my_g), cgi = tile_slot_of(my_g), cn = tid % kGroup;
+    if (cn == 0) tile_hdr[tile].group_mask[my_g] = L.group_mask[tid / kGroup];
+    tile_perm[tile * kTileT + my_g * kGroup + cn] = (uint16_t)my_slot;
+    if (tid < kGroupsPerTile) {               // the union over the blocks of every convolution wave (cleared at the top)
+        atomicOr(&L.wave_mask[tile_wave_of((int)L.group_dst[tid])], L.group_mask[tid]);
+        uint32_t pairs = (uint32_t)__popc(L.group_mask[tid]);
 #pragma unroll
-        for (int gi = 0; gi < kGroupsPerWave; ++gi) {
-            slot[gi] = (int)S.key[tile_group_of(w, gi) * kGroup + n];
-            smask[gi] = S.slot_mask[slot[gi]];
-            sbase[gi] = direct ? S.slot_base[slot[gi]] : 0u;
-        }
-        uint32_t wm = L.wave_mask[w];
-        size_t blk = (size_t)tile * block_stride + L.wave_block0[w];
-        for (int bi = 0; wm; ++bi, ++blk, wm &= wm - 1) {
-            if ((bi % kQuarters) != q) continue;
-            const int kappa = __ffs(wm) - 1;
-            uint32_t ids[kGroupsPerWave];
+        for (int d = 1; d < kGroupsPerTile; d <<= 1) pairs += (uint32_t)__shfl_xor((int)pairs, d);
+        if (tid == 0) L.n_pair_blocks = (int32_t)pairs;
+    }
+    __syncthreads();                         // stage is dead from here on
+    const uint32_t my_cwm = L.wave_mask[cw];  // blocks exist for these offsets in this column's convolution wave
+    uint32_t blk0 = 0;
 #pragma unroll
-            for (int gi = 0; gi < kGroupsPerWave; ++gi) {
-                uint32_t id = kNoRow;
-                if ((smask[gi] >> kappa) & 1u) {
-                    if (direct) {
-                        id = sbase[gi] + __popc(smask[gi] & ((1u << kappa) - 1u));
-                    } else {
-                        const int32_t v = L.nb[slot[gi] * K3 + kappa];
-                        id = v <= -1024 ? (uint32_t)win_n + S.slot_rank[-1024 - v] : (uint32_t)(-2 - v);
+    for (int w = 0; w < kTileWaves; ++w) blk0 += w < cw ? (uint32_t)__popc(L.wave_mask[w]) : 0u;
+    // offsets this hardware wave (two sorted blocks with similar masks) looks up
+    const uint32_t um = (uint32_t)__builtin_amdgcn_readfirstlane((int)(L.group_mask[(tid >> 6) * 2] | L.group_mask[(tid >> 6) * 2 + 1]));
+    const int n_look = __popc(um);
+    FX_STAMP(4);
+
+    // ---- index pass
+    const int32_t win_lo = SUBM ? (int32_t)o0 : 0;
+    const int32_t win_n = SUBM ? n_valid : 0;
+    int32_t* my_rows = tile_rows + tile * (int64_t)row_stride;
+    const int lo = (int)(my_vox & 511u);
+    const TapAxes axes = tap_axes<K, INV>(stride, (int)((my_vox >> 9) & 7u), (int)((my_vox >> 15) & 7u), (int)((my_vox >> 12) & 7u),
+                                          (int)((my_vox >> 18) & 7u));
+    const int32_t* nbr_row = leaf_nbr + (int64_t)(f_lo + lo) * 27;
+    u32x16_t codes;                           // the thread's entries, two per word, in the order of the wave's offsets
+    bool direct = !DEDUP;
+    uint32_t n_list = 0;
+    for (;;) {
+        uint32_t list_base = 0;
+        if (direct) {
+            list_base = block_scan_excl((uint32_t)__popc(mask), L.wave_sums, &n_list);
+        } else {
+            for (int e = tid; e < kHaloHashSlots; e += kPackThreads) L.u.halo.hash[e] = -1;
+            if (SUBM && tid < kNearWords) L.u.halo.near_bits[tid] = 0;
+            __syncthreads();
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) codes[e] = 0;
+        uint32_t rest = um;
+        for (int kk = 0; kk < n_look; ++kk) {
+            const int kappa = __builtin_ctz(rest);
+            rest &= rest - 1;
+            int slot, n2, bit6;
+            bool ok;
+            tap_query(axes, kappa / (K * K), (kappa / K) % K, kappa % K, slot, n2, bit6, ok);
+            uint64_t w;
+            int32_t base;
+            neighbour_word(L, tin, nbr_row, lo, slot, n2, w, base);
+            uint32_t code = kCodeNone;
+            if ((mask >> kappa) & 1u) {
+                const int32_t idx = base + (int32_t)popc_below(w, bit6);
+                if (direct) {
+                    code = list_base + (uint32_t)__popc(mask & ((1u << kappa) - 1u));
+                    my_rows[code] = idx;
+                } else if ((uint32_t)(idx - win_lo) < (uint32_t)win_n) {
+                    code = (uint32_t)(idx - win_lo);
+                } else if (SUBM && (uint32_t)(idx - (win_lo - kNearSpan)) < (uint32_t)kNearBits) {
+                    const uint32_t off = (uint32_t)(idx - (win_lo - kNearSpan));
+                    (void)__hip_atomic_fetch_or(&L.u.halo.near_bits[off >> 5], 1u << (off & 31u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    code = kCodeNear | off;
+                } else {
+                    // a row far from the window: into the halo table (or found there)
+                    uint32_t h = ((uint32_t)idx * 0x9E3779B1u) >> 21;  // 11 bits
+                    for (;;) {
+                        const int32_t cur = lds_peek(&L.u.halo.hash[h]);
+                        if (cur == idx) { code = kCodeHalo | h; break; }
+                        if (cur < 0) {
+                            if (lds_peek(&L.overflow)) break;
+                            const int32_t old = atomicCAS(&L.u.halo.hash[h], -1, idx);
+                            if (old < 0) {
+                                const int at = atomicAdd(&L.n_halo, 1);
+                                if (at < kMaxHalo) { L.u.halo.halo[at] = idx; L.u.halo.halo_slot[at] = (uint16_t)h; code = kCodeHalo | h; }
+                                else L.overflow = 1;
+                                break;
+                            }
+                            if (old == idx) { code = kCodeHalo | h; break; }
+                        }
+                        h = (h + 1) & (kHaloHashSlots - 1);
                     }
                 }
-                if (lds_codes) id = lds_row_code(id == kNoRow ? (uint32_t)kRowCap : id);
-                ids[gi] = id & 0xFFFFu;
             }
-            uint32_t* dst = reinterpret_cast<uint32_t*>(tile_blocks + blk * kIdBlockElems + n * kGroupsPerWave);
+            codes[kk >> 1] |= code << (16 * (kk & 1));
+        }
+        __syncthreads();
+        if (direct || !L.overflow) break;
+        direct = true;                        // more rows than the table holds: the tile lists one row per pair
+        __syncthreads();                      // everyone has read the flag before the scan reuses LDS
+    }
+    FX_STAMP(5);
+
+    // ---- the halo list, ascending: first the rows near the window in bitmap order, then the far rows, ranked
+    // among themselves by counting (all distinct).  A row's place in the list, offset by win_n, is its local id.
+    uint16_t* slot_rank = reinterpret_cast<uint16_t*>(L.rec_mask);      // hash slot -> place; the records are dead
+    int n_halo = 0;
+    if (!direct) {
+        uint32_t n_near = 0;
+        if (SUBM) {
+            const uint32_t bits = tid < kNearWords ? L.u.halo.near_bits[tid] : 0u;
+            uint32_t at = block_scan_excl((uint32_t)__popc(bits), L.wave_sums, &n_near);
+            if (tid < kNearWords) L.u.halo.near_prefix[tid] = at;
+            for (uint32_t m = bits; m; m &= m - 1) my_rows[at++] = win_lo - kNearSpan + 32 * tid + (__ffs(m) - 1);
+        }
+        const int n_far = L.n_halo;
+        for (int i = tid; i < n_far; i += kPackThreads) {
+            const int32_t v = L.u.halo.halo[i];
+            int rank = (int)n_near;
+            int jx = 0;
+            for (; jx + 4 <= n_far; jx += 4) {
+                const i32x4_t q = *reinterpret_cast<const i32x4_t*>(&L.u.halo.halo[jx]);
+                rank += (q[0] < v) + (q[1] < v) + (q[2] < v) + (q[3] < v);
+            }
+            for (; jx < n_far; ++jx) rank += (L.u.halo.halo[jx] < v);
+            my_rows[rank] = v;
+            slot_rank[L.u.halo.halo_slot[i]] = (uint16_t)rank;
+        }
+        n_halo = (int)n_near + n_far;
+        n_list = (uint32_t)n_halo;
+    }
+    __syncthreads();
+    FX_STAMP(6);
+    const bool lds_codes = !direct && (win_n + n_halo <= kRowCap);
+
+    // ---- header
+    if (tid == 0) {
+        TileHeader* H = tile_hdr + tile;
+        int run = 0;
 #pragma unroll
-            for (int e = 0; e < kEntryWords; ++e) dst[e] = ids[2 * e] | (ids[2 * e + 1] << 16);
+        for (int w = 0; w < kTileWaves; ++w) { H->wave_mask[w] = L.wave_mask[w]; H->wave_block0[w] = (uint32_t)run; run += __popc(L.wave_mask[w]); }
+        H->win_lo = direct ? 0 : win_lo; H->win_n = direct ? 0 : win_n; H->n_list = (int32_t)n_list;
+        H->n_blocks = run; H->n_out = n_valid; H->flags = direct ? kTileDirect : (lds_codes ? kTileLdsOffsets : 0);
+        H->n_pair_blocks = L.n_pair_blocks; H->pad = 0;
+    }
+
+    // ---- id blocks.  Entry [voxel column][wave slot] of block (convolution wave, offset) belongs to this thread
+    // for every offset of its convolution wave's mask -- also those its own sorted block does not have (no input).
+    // The two sorted blocks of a hardware wave may sit in different convolution waves, so the loop runs over the
+    // union of both waves' offsets and every lane places its entry by its own wave's block numbering.
+    {
+        const uint32_t em = (uint32_t)__builtin_amdgcn_readlane((int)my_cwm, 0) | (uint32_t)__builtin_amdgcn_readlane((int)my_cwm, 32);
+        uint16_t* dst = tile_blocks + ((size_t)tile * block_stride + blk0) * kIdBlockElems + cn * kGroupsPerWave + cgi;
+        for (uint32_t rest = em; rest; rest &= rest - 1) {
+            const int kappa = __builtin_ctz(rest);
+            const uint32_t below = (1u << kappa) - 1u;
+            uint32_t code = kCodeNone;
+            if ((um >> kappa) & 1u) {                      // uniform: the wave looked this offset up
+                const int kk = __popc(um & below);
+                code = (codes[kk >> 1] >> (16 * (kk & 1))) & 0xFFFFu;
+            }
+            uint32_t id = kNoRow;
+            if (code != kCodeNone) {
+                if (code & kCodeHalo) id = (uint32_t)win_n + slot_rank[code & (kCodeHalo - 1u)];
+                else if (SUBM && (code & kCodeNear)) {
+                    const uint32_t off = code & (kCodeNear - 1u);
+                    id = (uint32_t)win_n + L.u.halo.near_prefix[off >> 5] + (uint32_t)__popc(L.u.halo.near_bits[off >> 5] & ((1u << (off & 31u)) - 1u));
+                } else id = code;
+            }
+            if (lds_codes) id = lds_row_code(id == kNoRow ? (uint32_t)kRowCap : id);
+            if ((my_cwm >> kappa) & 1u) dst[(size_t)__popc(my_cwm & below) * kIdBlockElems] = (uint16_t)id;
         }
     }
-    FX_KSTAMP(7);
+    FX_STAMP(7);
 }
 
 // global input row of a tile-local id
@@ -726,6 +801,27 @@ k_tiles_to_dense(const TileHeader* __restrict__ tile_hdr, const uint16_t* __rest
     __syncthreads();
     if (pairs && threadIdx.x < K3 && cnt[threadIdx.x])
         atomicAdd(&pairs[threadIdx.x], (unsigned long long)cnt[threadIdx.x]);
+}
+
+// The map's tiling statistics, summed over the tile headers on request: stats[0] MFMA columns issued, [1] rows
+// staged or listed, [2] direct tiles, [3] bytes of the tiled form (headers, permutations, row lists, id blocks).
+__global__ void k_tile_stats(const TileHeader* __restrict__ tile_hdr, int64_t n_tiles, unsigned long long* __restrict__ stats) {
+    unsigned long long v[4] = {0, 0, 0, 0};
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n_tiles; t += (int64_t)gridDim.x * blockDim.x) {
+        const TileHeader* H = tile_hdr + t;
+        const bool direct = (H->flags & kTileDirect) != 0;
+        v[0] += (unsigned long long)H->n_pair_blocks * kGroup;
+        v[1] += (unsigned long long)(direct ? H->n_list : H->win_n + H->n_list);
+        v[2] += direct ? 1ull : 0ull;
+        v[3] += sizeof(TileHeader) + sizeof(uint16_t) * kTileT + sizeof(int32_t) * (size_t)H->n_list +
+                sizeof(uint16_t) * kIdBlockElems * (size_t)H->n_blocks;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        unsigned long long x = v[q];
+        for (int d = 32; d >= 1; d >>= 1) x += shfl_xor_u64(x, d);
+        if ((threadIdx.x & 63) == 0 && x) atomicAdd(&stats[q], x);
+    }
 }
 
 __global__ void k_fill_i32(int32_t* __restrict__ p, int64_t n, int32_t v) {
@@ -793,9 +889,13 @@ fx_status kmap_ensure_dense(fx_kmap* km, hipStream_t st) {
 
 using namespace fx;
 
-#ifdef FX_KMAP_TIMING
-extern "C" int fx_debug_kmap_timing(unsigned long long* h_out, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(h_out, HIP_SYMBOL(g_kmap_timing), bytes);
+FX_DEV_TIMING_EXPORT(fx_debug_kmap_timing)
+#ifdef FX_DEV_TIMING
+extern "C" int fx_debug_kmap_occupancy(void) {     // resident tile builders per compute unit
+    int n = -1;
+    (void)hipFuncSetAttribute((const void*)k_build_tiles<3, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(PackLds));
+    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_build_tiles<3, true>, kPackThreads, sizeof(PackLds));
+    return n;
 }
 #endif
 
@@ -821,7 +921,6 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     }
     hipStream_t st = (hipStream_t)stream;
     fx_grid* gout = nullptr;
-    FX_HT("(outside)");
     if (stride == 1) { gout = g_in; fx_grid_retain(gout); }
     else FX_TRY(fx_grid_coarsen2(g_in, stream, &gout));
     fx_kmap* km = nullptr;
@@ -871,9 +970,7 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
     const size_t o_tb = take(tiled ? sizeof(uint16_t) * kIdBlockElems * (size_t)km->block_stride * nt : 0);
     const size_t o_ln = take(tiled ? sizeof(int32_t) * 27 * (size_t)std::max(gout->hdr.n_leaf, 1) : 0);
     const size_t o_tf = take(tiled ? sizeof(int32_t) * (nt + 1) : 0);
-    FX_HT("kmap: host setup");
     fx_status rc = dev_alloc(&km->d_alloc, off, st);
-    FX_HT("kmap: alloc");
     if (rc != FX_OK) { fx_kmap_destroy(km); return rc; }
     char* p = (char*)km->d_alloc;
     km->d_stats = (int64_t*)(p + o_st);
@@ -885,9 +982,7 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
     int32_t* d_tile_first = (int32_t*)(p + o_tf);
 
     hipError_t e = hipSuccess;
-    if (km->n_tiles == 0) e = hipMemsetAsync(km->d_stats, 0, sizeof(int64_t) * (size_t)(4 + km->K3), st);
     if (e == hipSuccess && km->n_tiles > 0) {
-        unsigned long long* stats = (unsigned long long*)km->d_stats;
         const size_t lds = sizeof(PackLds);
         const unsigned ntl = (unsigned)km->n_tiles;
         const TreeView tin = g_in->view(), tout = gout->view();
@@ -895,10 +990,10 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
             ProfScope ps(kProfLeafNeighbors, st);
             const int64_t ne = (int64_t)gout->hdr.n_leaf * 27;
             const unsigned nbk = (unsigned)((ne + 255) / 256);
-            if (K == 1) k_leaf_neighbors<1><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, stats);
-            else if (K == 2) k_leaf_neighbors<2><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, stats);
-            else if (inverse) k_leaf_neighbors<3, true><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, stats);
-            else k_leaf_neighbors<3><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, stats);
+            if (K == 1) k_leaf_neighbors<1><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
+            else if (K == 2) k_leaf_neighbors<2><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
+            else if (inverse) k_leaf_neighbors<3, true><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
+            else k_leaf_neighbors<3><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
         }
         ProfScope ps(kProfBuildTiles, st);
 #define FX_TILES(KV, SUBMV...)                                                                                 \
@@ -910,8 +1005,7 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
                                                                      km->n_out,                                \
                                                                      km->d_tile_hdr, km->d_tile_perm,          \
                                                                      km->d_tile_rows, km->row_stride,          \
-                                                                     km->d_tile_blocks, km->block_stride,      \
-                                                                     stats);                                   \
+                                                                     km->d_tile_blocks, km->block_stride);     \
     } while (0)
         const bool same_grid = g_in == gout;      // a stride-1 map onto another grid has no window of its own rows
         if (K == 1 && same_grid) FX_TILES(1, true);
@@ -928,7 +1022,6 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
 #undef FX_TILES
         if (e == hipSuccess) e = hipGetLastError();
     }
-    FX_HT("kmap: memset + launches");
     if (e != hipSuccess) {
         set_error("kernel-map build failed: %s", hipGetErrorString(e));
         fx_kmap_destroy(km);
@@ -958,8 +1051,10 @@ fx_status fx::kmap_fetch_stats(fx_kmap* km) {
     if (km->stats_valid) return FX_OK;
     hipStream_t st = km->stream;
     unsigned long long* pairs = (unsigned long long*)(km->d_stats + 4);
-    FX_HIP_TRY(hipMemsetAsync(pairs, 0, sizeof(int64_t) * (size_t)km->K3, st));
+    FX_HIP_TRY(hipMemsetAsync(km->d_stats, 0, sizeof(int64_t) * (size_t)(4 + km->K3), st));
     if (km->n_tiles > 0) {
+        k_tile_stats<<<(unsigned)std::min<int64_t>((km->n_tiles + 255) / 256, 256), 256, 0, st>>>(
+            km->d_tile_hdr, km->n_tiles, (unsigned long long*)km->d_stats);
         k_tiles_to_dense<<<(unsigned)km->n_tiles, kTileT, 0, st>>>(km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows,
                                                                   km->row_stride, km->d_tile_blocks, km->block_stride,
                                                                   km->K3, nullptr, pairs);
