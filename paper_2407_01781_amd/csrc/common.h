@@ -59,13 +59,6 @@ struct ProfScope {
     ~ProfScope() { if (on) prof_end(slot, s); }
 };
 
-// development aid (-DFX_HOST_TIMING): host time between consecutive marks, summed per label
-#ifdef FX_HOST_TIMING
-void ht_mark(const char* label);
-#define FX_HT(label) fx::ht_mark(label)
-#else
-#define FX_HT(label) do { } while (0)
-#endif
 
 // ------------------------------------------------------------------ tree layout
 // Node fan-outs of the VDB tree (Sec. 3.1): upper 32^3 children, lower 16^3, leaf 8^3 voxels.

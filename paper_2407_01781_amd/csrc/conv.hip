@@ -16,6 +16,7 @@
 // kernel for strided maps keeps the roles the other way round (weights as A, 32 consecutive
 // channels of one voxel per lane).
 #include "conv_common.h"
+#include "dev_timing.h"
 
 #include <mutex>
 
@@ -186,15 +187,6 @@ __device__ __forceinline__ void store_block_rows(const f32x16 (&acc)[2], const u
         store_block_rows_impl<T, OUT_F32, false>(acc, perm_g, base, row_bytes, lane_off, n_valid, 2 * n < cols, h);
 }
 
-#ifdef FX_CONV_TIMING
-// development aid: per-workgroup cycle totals, read back with fx_debug_conv_timing
-__device__ unsigned long long g_conv_timing[1024 * 8];
-#define FX_T0() const unsigned long long _t0 = __builtin_readcyclecounter()
-#define FX_TACC(var) var += __builtin_readcyclecounter() - _t0
-#else
-#define FX_T0() do { } while (0)
-#define FX_TACC(var) do { } while (0)
-#endif
 
 // ---------------------------------------------------------------------------------- MFMA kernel
 constexpr int kMetaSlots = 3;
@@ -513,23 +505,23 @@ __device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, cons
             w_after1 = more ? w_frag(nslice, w_kappa_stride, nsl, nc, first_offset(more)) : w_after0;
         }
         if (wave_mask) {
-            FX_T0();
+            FX_CYCLES_BEGIN();
             offsets_loop<T, GENERAL>(L.rows[(phase + c) & 1], L.blocks[mb], acc, gmask, wave_mask, wave_block0,
                                      reinterpret_cast<const vec8*>(wp), (uint32_t)lane * 16u,
                                      w_frag(nslice, w_kappa_stride, I.slice, c, 0), w_kappa_stride, wa, wb, wa_at, wb_at,
                                      w_after0, w_after1, n, h, I.n_staged, I.win_lo, I.win_n, my_rows, feat, pitch, c);
-            FX_TACC(tm[0]);
+            FX_CYCLES_ADD(tm[0]);
         }
-        { FX_T0(); __syncthreads(); FX_TACC(tm[1]); }
+        { FX_CYCLES_BEGIN(); __syncthreads(); FX_CYCLES_ADD(tm[1]); }
     }
-    FX_T0();
+    FX_CYCLES_BEGIN();
     unsigned char* tile_out = reinterpret_cast<unsigned char*>(out) +
                               ((I.tile * kTileT) * C_out + (int64_t)I.slice * kCoutSlice) * (OUT_F32 ? 4 : 2);
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi)
         store_block_rows<T, OUT_F32>(acc[gi], L.perm[pb] + tile_group_of(wave, gi) * kGroup, tile_out, C_out,
                                      min(kCoutSlice, C_out - I.slice * kCoutSlice), I.n_valid, n, h);
-    FX_TACC(tm[2]);
+    FX_CYCLES_ADD(tm[2]);
 }
 
 // Items whose rows are not all staged in LDS take this path: a real call, so that its registers
@@ -609,10 +601,6 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-#ifdef FX_CONV_TIMING
-        unsigned long long ptm = 0;
-        const unsigned long long pt_start = __builtin_readcyclecounter();
-#endif
         int phase = 0;
         for (int item_no = 0;; ++item_no) {
             const MetaSlot& M = L.meta[item_no % kMetaSlots];
@@ -641,27 +629,13 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
                     announce(L.meta[((phase + 2) / nchunk) % kMetaSlots], w, nslice, tile_hdr, lane);
                 }
                 __builtin_amdgcn_s_waitcnt(0);
-#ifdef FX_CONV_TIMING
-                const unsigned long long tb = __builtin_readcyclecounter();
-#endif
                 __syncthreads();
-#ifdef FX_CONV_TIMING
-                ptm += __builtin_readcyclecounter() - tb;
-#endif
             }
         }
-#ifdef FX_CONV_TIMING
-        if (tid == kTileWaves * 64 && blockIdx.x < 1024) {
-            unsigned long long* d = g_conv_timing + blockIdx.x * 8;
-            d[5] = ptm; d[6] = __builtin_readcyclecounter() - pt_start;
-        }
-#endif
     } else {
         // ---------------- consumers
         unsigned long long tm[4] = {0, 0, 0, 0};
-#ifdef FX_CONV_TIMING
-        const unsigned long long t_start = __builtin_readcyclecounter();
-#endif
+        const unsigned long long t_start = FX_CYCLES_NOW();
         __syncthreads();
         vec8 wa[4], wb[4];
         int wa_at, wb_at;
@@ -696,12 +670,12 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
             }
             ++n_items;
         }
-#ifdef FX_CONV_TIMING
-        if (tid == 0 && blockIdx.x < 1024) {
-            unsigned long long* d = g_conv_timing + blockIdx.x * 8;
-            d[0] = tm[0]; d[1] = tm[1]; d[2] = tm[2]; d[3] = __builtin_readcyclecounter() - t_start; d[4] = n_items;
+        // development builds: per-workgroup cycles of the first consumer wave (multiply, barrier waits, write-back, items)
+        if (tid == 0) {
+            FX_STAMP_VALUE(blockIdx.x, 0, tm[0]); FX_STAMP_VALUE(blockIdx.x, 1, tm[1]); FX_STAMP_VALUE(blockIdx.x, 2, tm[2]);
+            FX_STAMP_VALUE(blockIdx.x, 3, FX_CYCLES_NOW() - t_start); FX_STAMP_VALUE(blockIdx.x, 4, (unsigned long long)n_items);
         }
-#endif
+        (void)t_start;
     }
 }
 
@@ -1116,11 +1090,8 @@ static hipError_t launch_gather(const fx_kmap* km, const void* feat, const void*
 
 using namespace fx;
 
-#ifdef FX_CONV_TIMING
-extern "C" int fx_debug_conv_timing(unsigned long long* h_out, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(h_out, HIP_SYMBOL(g_conv_timing), bytes);
-}
-#endif
+FX_DEV_TIMING_EXPORT(fx_debug_conv_timing)
+
 
 
 // Device memory the matrix-unit kernels need beyond inputs and outputs: the packed weights and, behind them, the

@@ -72,20 +72,6 @@ __device__ __forceinline__ Floats<J> lds_floats(const float* p) {
     return r;
 }
 
-#ifdef FX_LEAF_TIMING
-// development aid: per-workgroup cycle totals of the phases, read back with fx_debug_leaf_timing
-__device__ unsigned long long g_leaf_timing[1024 * 8];
-#define FX_LT(slot)                                                              \
-    do {                                                                         \
-        if (lane == 0 && wave == 0) {            \
-            const unsigned long long _n = __builtin_readcyclecounter();          \
-            if (blockIdx.x < 1024) g_leaf_timing[blockIdx.x * 8 + (slot)] += _n - _tl; \
-            _tl = _n;                                                            \
-        }                                                                        \
-    } while (0)
-#else
-#define FX_LT(slot) do { } while (0)
-#endif
 
 // Records of the 27 leaves around (and including) leaf f into LDS: one tree descent per lane.
 template <typename LDS>
@@ -198,10 +184,6 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
     if (wave == kLeafWaves - 1 && f_begin < f_end) stage_records(t, L, f_begin, lane);
     __syncthreads();
 
-#ifdef FX_LEAF_TIMING
-    unsigned long long _tl = __builtin_readcyclecounter();
-    const unsigned long long _w0 = wall_clock64();
-#endif
     for (int f = f_begin; f < f_end; ++f) {
         // ---- densify: row of every window cell, its channels into LDS (zeros where inactive)
         {
@@ -240,9 +222,7 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
                 }
             }
         }
-        if (wave == 0) FX_LT(0);             // densify (wave 0's own work)
         __syncthreads();
-        if (wave == 0) FX_LT(1);             // wait for the others
 
         // ---- the leaf's active voxels in index order, and which taps each column tile needs
         const int n_act = (int)((L.prefix[13] >> 54) & 511) + __popcll(L.mask[13][7]);
@@ -267,7 +247,6 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
             }
         }
         __syncthreads();
-        if (wave == 0) FX_LT(2);             // masks phase incl. barrier
 
         if (wave == kLeafWaves - 1 && f + 1 < f_end) stage_records(t, L, f + 1, lane);
         {
@@ -320,17 +299,9 @@ __global__ __launch_bounds__(kLeafThreads, 4) void k_conv_leaf(TreeView t, const
                         if (FULLP || 16 * nt + 4 * q < n_produce) *reinterpret_cast<f32x4*>(o + 16 * nt) = acc[nt];
                 }
             }
-            if (wave == 0) FX_LT(3);         // multiply (wave 0's tiles)
         }
         __syncthreads();
-        if (wave == 0) FX_LT(4);             // wait at the end of the leaf
     }
-#ifdef FX_LEAF_TIMING
-    if (tid == 0 && blockIdx.x < 1024) {
-        g_leaf_timing[blockIdx.x * 8 + 7] = wall_clock64() - _w0;   // 100 MHz ticks
-        g_leaf_timing[blockIdx.x * 8 + 5] = _w0;
-    }
-#endif
 }
 
 // ---------------------------------------------------------------------------------- weight gradient, fp32, low depth
@@ -585,10 +556,6 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
     int f = uni(L.range[0]);
     int parity = 0;
 
-#ifdef FX_LEAF_TIMING
-    unsigned long long _tl = __builtin_readcyclecounter();
-    const unsigned long long _w0 = wall_clock64();
-#endif
     while (f < t.n_leaf) {
         parity ^= 1;
         if (tid0 == 64) L.range[parity] = atomicAdd(work_counter, 1);    // by the second wave (the first walks the tree); read after this leaf's barriers
@@ -631,7 +598,6 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
         }
         __syncthreads();
 
-        if (wave == 0) FX_LT(0);                 // leaf prologue: records, cell rows, lists
         // this wave's column tiles: tile gi * 4 + wave, voxel n of it in lanes n and n + 32
         const int n_tiles = (n_act + 31) >> 5;
         uint32_t gtaps[kLeaf16Groups];
@@ -657,9 +623,7 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
                 // ---- densify chunk c: direct-to-LDS loads, one 1 KB slab of 16 rows per wave instruction; lane l
                 // of a slab writes the 16 bytes at slab + 16 l, i.e. stored piece l & 3 of row l / 4, which is
                 // piece (l & 3) ^ ((row >> 2) & 3) of the cell's chunk; inactive cells load from a zero row
-                if (wave == 0) FX_LT(5);
                 __syncthreads();                 // the previous multiply has finished with the window
-                if (wave == 0) FX_LT(1);         // wait before densify
                 {
                     const int piece = (lane & 3) ^ ((lane >> 4) & 3);
                     // all row numbers first: a read of LDS after an asynchronous write to LDS has been issued
@@ -682,9 +646,7 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
                     }
                     __builtin_amdgcn_s_waitcnt(0);
                 }
-                if (wave == 0) FX_LT(2);         // densify own loads
                 __syncthreads();
-                if (wave == 0) FX_LT(3);         // wait after densify
 
                 // ---- multiply: the taps this wave's tiles need; the next tap's weights are in flight
                 const unsigned char* wq = wp + ((int64_t)c * nslice + s) * 4096 + lane * 16;
@@ -734,7 +696,6 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
                     }
                 }
             }
-            if (wave == 0) FX_LT(4);             // multiply (last chunk)
             // ---- write-back: register v of tile mt in lane (n, h) is channel 64 s + 2 n + mt of the
             // tile's voxel 8 (v / 4) + 4 h + v % 4; the leaf's outputs are consecutive rows
             const uint32_t esize = OUT_F32 ? 4u : 2u;
@@ -760,13 +721,9 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
                 }
             }
         }
-        if (wave == 0) FX_LT(6);                 // write-back
         __syncthreads();                         // records and lists are rewritten for the next leaf
         f = uni(L.range[parity]);
     }
-#ifdef FX_LEAF_TIMING
-    if (tid0 == 0 && blockIdx.x < 1024) g_leaf_timing[blockIdx.x * 8 + 7] = wall_clock64() - _w0;
-#endif
 }
 
 template <typename T, bool OUT_F32>
@@ -830,16 +787,6 @@ fx_status launch_leaf(const fx_grid* g, const float* feat, const float* w, float
 
 using namespace fx;
 
-#ifdef FX_LEAF_TIMING
-extern "C" int fx_debug_leaf_timing(unsigned long long* h_out, size_t bytes, int reset) {
-    if (reset) {
-        void* p = nullptr;
-        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_leaf_timing)) != hipSuccess) return -1;
-        return (int)hipMemset(p, 0, sizeof(unsigned long long) * 1024 * 8);
-    }
-    return (int)hipMemcpyFromSymbol(h_out, HIP_SYMBOL(g_leaf_timing), bytes);
-}
-#endif
 
 // The leaf-window convolution of `src` [N, C_contract] into `dst` [N, C_produce]; `mode` says how the
 // caller's weights are read (kWeightsForward, or kWeightsMirrored for the input gradient).

@@ -820,7 +820,6 @@ constexpr int64_t kPartitionMinRows = 65536;   // below this the direct path's f
 
 static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64_t* d_joff, int32_t B,
                                int cap_upper, int cap_lower, int cap_leaf, bool direct, hipStream_t st, fx_grid** out) {
-    FX_HT("(outside)");
     fx_grid* g = new (std::nothrow) fx_grid();
     if (!g) { set_error("host allocation failed"); return FX_ENOMEM; }
     g->B = B; g->stream = st;
@@ -877,7 +876,6 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     uint32_t* d_totals = (uint32_t*)(sp + o_tot);
     uint32_t* d_bucket_start = (uint32_t*)(sp + o_bst);
 
-    FX_HT("grid: allocs");
     auto fail = [&](fx_status s) { dev_free(scratch, st); fx_grid_destroy(g); return s; };
 #define FX_TRY_OR_FAIL(expr) do { hipError_t _e = (expr); if (_e != hipSuccess) { \
         set_error("%s failed: %s", #expr, hipGetErrorString(_e)); return fail(FX_EDEVICE); } } while (0)
@@ -888,7 +886,6 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
         // the partitioned path writes every mask it lists and clears the tile table in its first kernel
         if (!partition) FX_TRY_OR_FAIL(hipMemsetAsync(scratch, 0, clear_bytes, st));
     }
-    FX_HT("grid: memsets");
     const GridPtrs q = ptrs_of(g);
     if (n_rows > 0 && B > 0) {
         const unsigned nb_leaf = (unsigned)((g->cap_leaf + 255) / 256);
@@ -934,7 +931,6 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
         }
         FX_TRY_OR_FAIL(hipGetLastError());
     }
-    FX_HT("grid: kernel launches");
     // one read-back: counts + per-grid ranges (Sec. 3.3 step 10)
     const size_t hdr_bytes = sizeof(GridHeader);
     const size_t vb_bytes = sizeof(int64_t) * ((size_t)B + 1);
@@ -948,7 +944,6 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     *h_ticket = 0;
     k_publish<<<1, 256, 0, st>>>(g->d_hdr, g->d_vox_base, B, (unsigned char*)stage, (int32_t*)h_ticket, ticket);
     FX_TRY_OR_FAIL(hipGetLastError());
-    FX_HT("grid: d2h enqueue");
     {
         // poll the ticket for a while (a few hundred microseconds at most for the sizes where latency
         // matters), then fall back to waiting for the stream, which also reports any device error
@@ -960,11 +955,9 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
         if (!seen) FX_TRY_OR_FAIL(hipStreamSynchronize(st));
         std::atomic_thread_fence(std::memory_order_acquire);
     }
-    FX_HT("grid: sync");
     memcpy(&g->hdr, stage, hdr_bytes);
     memcpy(g->h_vox_base, (char*)stage + hdr_bytes, vb_bytes);
     dev_free(scratch, st);
-    FX_HT("grid: free scratch");
 #undef FX_TRY_OR_FAIL
     *out = g;
     return FX_OK;
@@ -1035,9 +1028,7 @@ extern "C" fx_status fx_build_index_grid(const int32_t* d_ijk, int64_t n_rows, c
     hipStream_t st = (hipStream_t)stream;
     int64_t* d_joff = nullptr;
     const size_t jb = sizeof(int64_t) * 2 * (size_t)std::max(B, 1);
-    FX_HT("(outside)");
     FX_TRY(dev_alloc((void**)&d_joff, jb, st));
-    FX_HT("grid: joff alloc");
     if (B > 0) {
         void* stage = nullptr;
         fx_status rc = host_staging(&stage, jb, 1);
@@ -1047,11 +1038,9 @@ extern "C" fx_status fx_build_index_grid(const int32_t* d_ijk, int64_t n_rows, c
         hipError_t e = hipMemcpyAsync(d_joff, stage, sizeof(int64_t) * 2 * (size_t)B, hipMemcpyHostToDevice, st);
         if (e != hipSuccess) { dev_free(d_joff, st); set_error("joffsets upload failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
     }
-    FX_HT("grid: joff upload+sync");
     fx_grid* g = nullptr;
     fx_status rc = build_index_grid_device_joff(d_ijk, n_rows, d_joff, B, st, &g);
     dev_free(d_joff, st);
-    FX_HT("grid: free joff");
     if (rc != FX_OK) return rc;
     *out = g;
     return FX_OK;

@@ -172,28 +172,6 @@ fx_status host_staging(void** p, size_t bytes, int area) {
     return FX_OK;
 }
 
-#ifdef FX_HOST_TIMING
-}  // namespace fx
-#include <chrono>
-#include <map>
-namespace fx {
-static std::map<std::string, std::pair<double, long>> g_ht;
-static std::vector<std::string> g_ht_order;
-static std::chrono::steady_clock::time_point g_ht_last = std::chrono::steady_clock::now();
-void ht_mark(const char* label) {
-    const auto now = std::chrono::steady_clock::now();
-    const double us = std::chrono::duration<double, std::micro>(now - g_ht_last).count();
-    g_ht_last = now;
-    auto it = g_ht.find(label);
-    if (it == g_ht.end()) { g_ht[label] = {us, 1}; g_ht_order.push_back(label); }
-    else { it->second.first += us; it->second.second++; }
-}
-extern "C" void fx_debug_host_timing_dump(int reset) {
-    for (auto& l : g_ht_order) printf("  %-28s %9.1f us avg over %ld\n", l.c_str(), g_ht[l].first / g_ht[l].second, g_ht[l].second);
-    if (reset) { g_ht.clear(); g_ht_order.clear(); }
-    g_ht_last = std::chrono::steady_clock::now();
-}
-#endif
 
 int compute_units() {
     static int n_cu = 0;
