@@ -69,17 +69,59 @@ def pmc_summary(directory):
             print(f"{name[:90]:90s} {ctr:28s} dispatches {len(v):4d}  mean {sum(v) / len(v):16.1f}  max {max(v):16.1f}")
 
 
+KERNEL_SOURCES = {          # the files whose contents decide what a kernel moves through HBM
+    "k_conv_mfma": ("conv.hip", "conv_common.h", "kmap.h"),
+    "k_conv_gather": ("conv.hip", "conv_common.h", "kmap.h"),
+    "k_build_tiles": ("kmap.hip", "kmap.h", "tree_device.h"),
+}
+
+
+def kernel_source_sha1(kernel):
+    """Fingerprint of a kernel's sources: a committed counter summary is quoted only while it matches."""
+    import hashlib
+    h = hashlib.sha1()
+    for f in KERNEL_SOURCES.get(kernel, ()):
+        h.update(open(os.path.join(ROOT, "paper_2407_01781_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def committed_traffic(kernel, workload):
-    """HBM bytes per launch measured with rocprofv3 counters and committed under profiles/
-    (a line `traffic_bytes_per_launch: N` in profiles/<kernel>_<workload>_hbm_traffic.md)."""
+    """HBM bytes per launch measured with rocprofv3 counters (rocprofv3 cannot run inside this process; the
+    FETCH_SIZE / WRITE_SIZE runs of this same command are summarised under profiles/ in
+    <kernel>_<workload>_hbm_traffic.md: `traffic_bytes_per_launch: N` and `kernel_source_sha1: H`).  Returns
+    (bytes, note): the figure is dropped, and the note says so, when the kernel's sources have changed since."""
     path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.md")
+    traffic, sha = None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+                traffic = float(line.split(":", 1)[1])
+            if line.startswith("kernel_source_sha1:"):
+                sha = line.split(":", 1)[1].strip()
     except OSError:
-        pass
-    return None
+        return None, "no counter summary committed for this kernel and workload"
+    if traffic is None:
+        return None, "no counter summary committed for this kernel and workload"
+    if sha != kernel_source_sha1(kernel):
+        return None, f"profiles/{os.path.basename(path)} was measured on other sources of this kernel ({sha}): not quoted"
+    return traffic, f"profiles/{os.path.basename(path)}, sources {sha}"
+
+
+def gpu_clocks():
+    """Current clocks / power state as rocm-smi prints them, when it is there and readable."""
+    import shutil
+    import subprocess
+    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    try:
+        out = subprocess.run([exe, "--showclocks", "--showperflevel", "--showpower", "--json"], capture_output=True, text=True,
+                             timeout=20)
+        if out.returncode != 0:
+            return None
+        card = next(iter(json.loads(out.stdout).values()))
+        keep = {k: v for k, v in card.items() if any(t in k.lower() for t in ("sclk", "mclk", "fclk", "performance", "power"))}
+        return keep or None
+    except Exception:
+        return None
 
 
 def main():
@@ -260,7 +302,7 @@ def main():
         kmv = fx.build_kernel_map(gv, 3, 1)
         v_pairs = kmv.info()[0]
         t_kmv = b2b(lambda: fx.build_kernel_map(gv, 3, 1), reps=5)
-        os.environ["FVDB_HOTPATH_LEAF_DISPATCH"] = "0"        # the comparison figures are the kernel-map kernels'
+        fx.set_option("leaf_dispatch", 0)        # the comparison figures are the kernel-map kernels'
         t_cv = b2b(lambda: fx.sparse_conv_fwd(kmv, v_feat, v_w), reps=5)
         v_flops = 2.0 * v_pairs * wv.c_in * wv.c_out
         v_bytes = nv * (wv.c_in + wv.c_out) * 4 + 27 * wv.c_in * wv.c_out * 4 + 96 * gv.counts()[0]
@@ -283,7 +325,7 @@ def main():
         h_w = (torch.randn((27, 64, 64), device="cuda") * (1.0 / (27 * 64)) ** 0.5).to(torch.bfloat16)
         t_l16 = b2b(lambda: fx.sparse_conv_leaf_fwd(gv, h_feat, h_w), reps=5)
         t_c16 = b2b(lambda: fx.sparse_conv_fwd(kmv, h_feat, h_w), reps=5)
-        del os.environ["FVDB_HOTPATH_LEAF_DISPATCH"]
+        fx.set_option("leaf_dispatch", -1)
         h_flops = 2.0 * v_pairs * 64 * 64
         low_depth["leaf_window_bf16_64"] = {
             "leaf_conv_ms": t_l16, "leaf_conv_effective_TFLOPs": h_flops / (t_l16 * 1e-3) / 1e12,
@@ -357,18 +399,24 @@ def main():
 
     dom = next(k for k in ("k_conv_mfma", "k_conv_gather", "k_conv_leaf", "k_conv_scalar") if k in kern_ms)
     dom_ms = kern_ms[dom]
-    if dom != "k_conv_scalar":
-        peak = MFMA_PEAK_TFLOPS[w.dtype]
-        roof = {"kernel": dom, "bound": "mfma", "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": peak,
-                "unit": "TFLOP/s"}
-    else:
-        roof = {"kernel": dom, "bound": "alu", "achieved": flops / (dom_ms * 1e-3) / 1e12,
-                "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = committed_traffic(dom, args.workload)
+    # Both roofs of the dominant kernel.  Algorithmic bytes of one launch: every input row and every output row once,
+    # the weights once, and the kernel map in the form the kernel reads (the tiled map's bytes).  The binding roof is
+    # min(matrix peak, intensity x HBM peak); `bound` names it and `frac_of_binding_roof` is measured against it.
+    peak = MFMA_PEAK_TFLOPS[w.dtype] if dom != "k_conv_scalar" else FP32_VALU_PEAK_TFLOPS
+    achieved = flops / (dom_ms * 1e-3) / 1e12
+    conv_bytes_with_map = conv_bytes + (tiled_bytes if dom in ("k_conv_mfma", "k_conv_gather") else (kmap_bytes if dom == "k_conv_scalar" else 0))
+    intensity = flops / conv_bytes_with_map
+    hbm_roof_tflops = intensity * HBM_PEAK_GBS / 1e3
+    binding = min(peak, hbm_roof_tflops)
+    roof = {"kernel": dom, "bound": ("hbm" if hbm_roof_tflops < peak else ("mfma" if dom != "k_conv_scalar" else "alu")),
+            "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+            "intensity_flop_per_byte": intensity, "hbm_roof_TFLOPs": hbm_roof_tflops,
+            "binding_roof_TFLOPs": binding, "frac_of_binding_roof": achieved / binding}
+    roof["traffic"], roof["traffic_source"] = committed_traffic(dom, args.workload)
     roof["avg_launch_ms"] = dom_ms
-    roof["hbm_view"] = {"algorithmic_bytes": conv_bytes, "GB/s": conv_bytes / (dom_ms * 1e-3) / 1e9,
-                        "frac_of_8TBs": conv_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    roof["hbm_view"] = {"algorithmic_bytes": conv_bytes_with_map, "of_which_kernel_map": conv_bytes_with_map - conv_bytes,
+                        "GB/s": conv_bytes_with_map / (dom_ms * 1e-3) / 1e9,
+                        "frac_of_8TBs": conv_bytes_with_map / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     # map build: bytes of the tiled map actually written + the 96-byte leaf records read once
     bt_ms = kern_ms.get("k_build_tiles")
     kmap_roof = None
@@ -377,7 +425,8 @@ def main():
         kmap_roof = {"kernel": "k_build_tiles", "bound": "hbm", "achieved": bt_bytes / (bt_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "avg_launch_ms": bt_ms, "algorithmic_bytes": bt_bytes,
                      "dense_map_equivalent_GBs": kmap_bytes / (bt_ms * 1e-3) / 1e9,
-                     "traffic": committed_traffic("k_build_tiles", args.workload)}
+                     "traffic": committed_traffic("k_build_tiles", args.workload)[0],
+                     "traffic_source": committed_traffic("k_build_tiles", args.workload)[1]}
         kmap_roof["frac"] = kmap_roof["achieved"] / HBM_PEAK_GBS
 
     # grid build: the rows read once plus the leaf table written (Sec. 3.3; no sort passes here)
@@ -415,13 +464,16 @@ def main():
         "padded_output": padded_output,
         "kernels_ms_per_launch": kern_ms,
         "kernels_ms_per_step": per_step_ms,
+        "clocks": gpu_clocks(),
         "roofline": roof,
         "roofline_kernel_map": kmap_roof,
         "roofline_grid_build": grid_roof,
         "paper_protocol": paper_protocol,
     }
 
-    # ---- CPU oracle on this machine's host cores (bounded sample, one thread)
+    # ---- CPU oracle on this machine's host cores: the oracle as it stands, on a bounded sample.  One thread first
+    # (the headline of this leg), then the convolution again with its output rows cut over all host cores (the same
+    # C routine on disjoint row ranges, one host thread per range).
     if not args.no_cpu_baseline:
         from oracle import cpu_oracle as O
         t = time.perf_counter()
@@ -438,11 +490,19 @@ def main():
         t_o3 = time.perf_counter() - t
         sample_pairs = int((nb[:rows] >= 0).sum())
         t_o3_full = t_o3 * pairs / max(sample_pairs, 1)
+        cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+        cores = max(1, min(cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
+        t = time.perf_counter()
+        O.conv(og, ogo, w.kernel_size, w.stride, f64, w64, 0, rows, threads=cores)
+        t_o3_mt = time.perf_counter() - t
         result["cpu_baseline"] = {
             "value": flops / (t_o1 + t_o2 + t_o3_full) / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
             "sample": f"grid build and kernel map on the full input ({t_o1:.2f} s, {t_o2:.2f} s); convolution "
                       f"on the first {rows} of {n_out} output rows ({t_o3:.2f} s), scaled by active pairs",
             "conv_only_TFLOPs": 2.0 * sample_pairs * w.c_in * w.c_out / t_o3 / 1e12,
+            "all_cores": {"cores": cores, "conv_only_TFLOPs": 2.0 * sample_pairs * w.c_in * w.c_out / t_o3_mt / 1e12,
+                          "conv_seconds": t_o3_mt,
+                          "note": "the same oracle routine on disjoint ranges of output rows, one host thread per range"},
             "host_cpus": os.cpu_count(),
         }
     print(json.dumps(result))

@@ -62,10 +62,38 @@ const char* fx_version(void);
 fx_status   fx_init(void);
 const char* fx_last_error(void);
 
-/* Device memory released by the library's calls is cached for reuse by later calls (bounded by
- * the environment variable FVDB_HOTPATH_CACHE_MB, default 16384).  This returns all cached blocks
- * to the driver; it waits for the device first. */
+/* Device memory that the library needs beyond the caller's buffers (grid and map handles, scratch).
+ *
+ * fx_set_allocator hands that to the caller's allocator -- PyTorch's caching allocator, say (the Python binding
+ * offers exactly that) -- so that one allocator owns the device's memory:
+ *     alloc(bytes, stream, ctx)   -> device pointer usable by work enqueued on `stream` (NULL: out of memory)
+ *     release(ptr, stream, ctx)    the block is no longer needed by work enqueued on `stream` after this call
+ * Both NULL restores the default.  Set it before handles exist: a block goes back to the allocator that is set
+ * when it is released.
+ *
+ * By default the library keeps the blocks its calls release and hands them to later requests of a similar size
+ * (hipMalloc / hipFree cost more than the kernels of a stage); at most option "cache_mb" MiB are kept (default
+ * 2048).  fx_release_cached_memory returns all cached blocks to the driver; it waits for the device first. */
+typedef void* (*fx_alloc_fn)(size_t bytes, void* stream, void* ctx);
+typedef void  (*fx_free_fn)(void* ptr, void* stream, void* ctx);
+fx_status fx_set_allocator(fx_alloc_fn alloc, fx_free_fn release, void* ctx);
 void fx_release_cached_memory(void);
+
+/* Process-wide switches (atomic; -1 = automatic, the default: the library decides).  They exist so that tests and
+ * measurements can send a call to every kernel that is able to serve it; results are the same within the stated
+ * tolerances.  Unknown names and values below -1 return FX_EINVAL.
+ *   "force_scalar"   1: convolution and both gradients on the scalar kernels (no matrix units)
+ *   "leaf_dispatch"  3x3x3 stride-1 maps: 0 never / 1 always (when the shape allows) hand the call to the
+ *                    leaf-window kernels; automatic: by mean leaf occupancy (see fx_sparse_conv_fwd)
+ *   "fp32_tiles"     1: FX_F32 takes the matrix-unit tile kernel at any grid size (automatic: from ~128 tiles on)
+ *   "conv_gather"    0 / 1: the LDS-staged / the gather kernel on every tiled map (automatic: by the kind of map)
+ *   "gather_lds"     0: the gather kernels fetch their weights per step instead of keeping them in LDS
+ *   "scalar_lds"     0: the scalar kernel reads its weights through L1 instead of LDS
+ *   "grid_direct"    1: the grid build skips the bucket pass (one global leaf table)
+ *   "cache_mb"       MiB of released device blocks kept for reuse (automatic: 2048)
+ *   "sync_alloc"     1: plain hipMalloc / hipFree, no cache                                                     */
+fx_status fx_set_option(const char* name, int32_t value);
+fx_status fx_get_option(const char* name, int32_t* value);
 
 /* ---------------------------------------------------------------------------------------
  * Index-grid build (Sec. 3.3: build an IndexGrid from N signed voxel coordinates; Sec. 3.2
@@ -205,11 +233,17 @@ void fx_kmap_destroy(fx_kmap* km);
  *   d_w     device [K^3, C_in, C_out] row-major, dtype in_dt
  *   d_out   device [N_out, C_out] row-major, dtype out_dt (= in_dt or FX_F32); every row is
  *           written (rows without any active tap become 0)
- * Products are exact in the input precision's product format and accumulated in fp32
- * (FX_F32 inputs: fp32 FMA; FX_F16 / FX_BF16: MFMA with fp32 accumulators); the result is
- * rounded to out_dt with round-to-nearest-even.
- * C_in, C_out >= 1.  The MFMA path needs C_in % 32 == 0 and C_out % 64 == 0; other
- * shapes and FX_F32 take the scalar path.
+ * Products are exact in the input precision's product format and accumulated in fp32; the result is
+ * rounded to out_dt with round-to-nearest-even.  C_in, C_out >= 1.
+ * Which kernel runs (all give the same sum within the stated tolerance):
+ *   - the matrix units (v_mfma_f32_32x32x16 for FX_F16 / FX_BF16; v_mfma_f32_32x32x2_f32, true fp32 products, for
+ *     FX_F32) when the map is tiled (K^3 <= 27), C_in * sizeof(element) is a multiple of 64 bytes (32 channels of
+ *     a 16-bit type, 16 of fp32) and C_out is even (padded to 64 with zero weights); FX_F32 only from about 128
+ *     tiles on (smaller grids are served faster by the scalar kernel spread over the chip);
+ *   - on a 3x3x3 stride-1 submanifold map whose grid is locally dense (mean leaf occupancy >= 0.40, or >= 0.08
+ *     for FX_F32 with C_in not a multiple of 16) and whose shape fx_sparse_conv_leaf_fwd serves: the
+ *     leaf-window kernels;
+ *   - everything else: a scalar kernel (fp32 FMA in offset-then-channel order).
  */
 fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w,
                              int32_t C_in, int32_t C_out, void* d_out, fx_dtype out_dt, void* stream);

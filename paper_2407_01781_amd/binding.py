@@ -14,7 +14,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("FVDB_HOTPATH_LIB") or os.path.join(_HERE, "libfvdb_hotpath.so")   # override: a development build
+LIB_PATH = os.path.join(_HERE, "libfvdb_hotpath.so")
 
 FX_OK = 0
 DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
@@ -99,6 +99,12 @@ def _load():
     L.fx_upsample2_bwd.argtypes = [vp, vp, C.c_int, i32, vp, vp]
     L.fx_upsample2.restype = C.c_int
     L.fx_upsample2.argtypes = [vp, vp, C.c_int, i32, vp, vp]
+    L.fx_set_option.restype = C.c_int
+    L.fx_set_option.argtypes = [C.c_char_p, i32]
+    L.fx_get_option.restype = C.c_int
+    L.fx_get_option.argtypes = [C.c_char_p, C.POINTER(i32)]
+    L.fx_set_allocator.restype = C.c_int
+    L.fx_set_allocator.argtypes = [vp, vp, vp]
     L.fx_release_cached_memory.restype = None
     L.fx_profile_enable.argtypes = [C.c_int]
     L.fx_profile_slot_count.restype = C.c_int
@@ -123,6 +129,45 @@ def _stream() -> int:
 
 def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def set_option(name: str, value: int) -> None:
+    """Process-wide switch of the library (fx_set_option); -1 restores the automatic choice."""
+    _check(lib.fx_set_option(name.encode(), int(value)))
+
+
+def get_option(name: str) -> int:
+    v = C.c_int32()
+    _check(lib.fx_get_option(name.encode(), C.byref(v)))
+    return v.value
+
+
+_ALLOC_CB = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p)
+_FREE_CB = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p, C.c_void_p)
+_torch_alloc_cbs = None          # the callback objects must outlive their use by the library
+
+
+def use_torch_allocator(enable: bool = True) -> None:
+    """Let PyTorch's caching allocator back all device memory the library needs (fx_set_allocator), or go back
+    to the library's own block cache.  Switch while no grid or kernel-map handle is alive."""
+    global _torch_alloc_cbs
+    if not enable:
+        _check(lib.fx_set_allocator(None, None, None))
+        _torch_alloc_cbs = None
+        return
+
+    def _alloc(nbytes, stream, _ctx):
+        try:
+            return torch.cuda.caching_allocator_alloc(int(nbytes), stream=int(stream or 0))
+        except Exception:          # out of memory: the library reports FX_ENOMEM
+            return None
+
+    def _free(ptr, _stream, _ctx):
+        torch.cuda.caching_allocator_delete(int(ptr))
+
+    cbs = (_ALLOC_CB(_alloc), _FREE_CB(_free))
+    _check(lib.fx_set_allocator(C.cast(cbs[0], C.c_void_p), C.cast(cbs[1], C.c_void_p), None))
+    _torch_alloc_cbs = cbs
 
 
 def version() -> str:

@@ -29,7 +29,16 @@ void set_error(const char* fmt, ...);
         if (_s != FX_OK) return _s;    \
     } while (0)
 
+// ------------------------------------------------------------------ options (fx_set_option)
+// -1 = automatic: the library decides; any other value is what the caller set.
+enum Option {
+    kOptForceScalar = 0, kOptLeafDispatch, kOptFp32Tiles, kOptConvGather, kOptGatherLds, kOptScalarLds, kOptGridDirect,
+    kOptCacheMb, kOptSyncAlloc, kOptCount
+};
+int option(Option o);
+
 // ------------------------------------------------------------------ device memory
+// From the caller's allocator when one is set (fx_set_allocator), else from the library's own cache of blocks.
 fx_status dev_alloc(void** p, size_t bytes, hipStream_t s);
 void dev_free(void* p, hipStream_t s);
 

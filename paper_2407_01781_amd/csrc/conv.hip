@@ -1063,8 +1063,7 @@ static hipError_t launch_gather(const fx_kmap* km, const void* feat, const void*
                                 hipStream_t st) {
     const int nslice = C_out / kCoutSlice;
     const size_t lds = (size_t)km->K3 * (C_in / kCinChunk) * 4096 + (size_t)kGatherLdsWaves * 2 * km->K3 * kGroup * sizeof(int32_t);
-    const char* fl = getenv("FVDB_HOTPATH_GATHER_LDS");     // "0": never keep the weights in LDS (tests)
-    if (lds <= 160 * 1024 && !(fl && fl[0] == '0')) {
+    if (lds <= 160 * 1024 && option(kOptGatherLds) != 0) {      // option gather_lds = 0: never keep the weights in LDS
         hipError_t e = hipFuncSetAttribute((const void*)k_conv_gather_ldsw<T, OUT_F32>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -1112,8 +1111,8 @@ static fx_status conv_tiles_with_scratch(const fx_kmap* km, const void* d_feat, 
     int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
     // maps whose tiles list one row per pair (strided; stride 1 back from a larger grid): the gather kernel;
     // others: the LDS-staged kernel
-    const char* fg = getenv("FVDB_HOTPATH_CONV_GATHER");
-    const bool gather = (fg ? fg[0] == '1' : !map_shares_rows(km)) && in_dt != FX_F32 && C_out % kCoutSlice == 0;
+    const int fg = option(kOptConvGather);          // 0 / 1: the LDS-staged / the gather kernel on every map
+    const bool gather = (fg >= 0 ? fg == 1 : !map_shares_rows(km)) && in_dt != FX_F32 && C_out % kCoutSlice == 0;
     launch_pack_weights(d_w, wp, km->K3, C_in, C_out, esize, counters, mode, gather ? kPackRows : kPackInterleaved, st);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && gather) {
@@ -1148,19 +1147,19 @@ static bool conv_tiles_shape_ok(const fx_kmap* km, fx_dtype in_dt, int C_in, int
 fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w, int32_t C_in,
                          int32_t C_out, void* d_out, fx_dtype out_dt, hipStream_t st, int mode) {
     const bool out_f32 = (out_dt == FX_F32);
-    const char* force = getenv("FVDB_HOTPATH_FORCE_SCALAR");
+    const bool force_scalar = option(kOptForceScalar) == 1;
     // Locally dense grids (Sec. 3.5 scenarios 1-2): on a 3x3x3 stride-1 map the leaf-window kernels compute the same
     // sum from the grid alone and are faster once the leaves are full enough -- the tiles of such a map need more
     // rows than the tile kernel's LDS holds -- and, at fp32 depths that the tile kernel does not take, almost
-    // everywhere.  FVDB_HOTPATH_LEAF_DISPATCH=0 keeps the kernel-map kernels, =1 takes the leaf kernels whenever
+    // everywhere.  Option leaf_dispatch = 0 keeps the kernel-map kernels, = 1 takes the leaf kernels whenever
     // they serve the shape.
     if (km->K == 3 && km->stride == 1 && km->gin == km->gout && (mode == kWeightsForward || mode == kWeightsMirrored) &&
-        leaf_shape_supported(in_dt, C_in, C_out) && !(force && force[0] == '1')) {
-        const char* ld = getenv("FVDB_HOTPATH_LEAF_DISPATCH");
+        leaf_shape_supported(in_dt, C_in, C_out) && !force_scalar) {
+        const int ld = option(kOptLeafDispatch);
         const double occupancy = (double)km->n_in / (512.0 * (double)std::max<int64_t>(1, km->gin->hdr.n_leaf));
         const bool scalar_otherwise = in_dt == FX_F32 && C_in % 16 != 0;
-        const bool take = ld ? ld[0] == '1' : occupancy >= (scalar_otherwise ? 0.08 : 0.40);
-        if (take && !(ld && ld[0] == '0'))
+        const bool take = ld >= 0 ? ld == 1 : occupancy >= (scalar_otherwise ? 0.08 : 0.40);
+        if (take)
             return leaf_apply("sparse convolution (leaf-window kernels)", km->gin, d_feat, in_dt, d_w, C_in, C_out, d_out, out_dt,
                               st, mode);
     }
@@ -1171,10 +1170,9 @@ fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, 
     // fp32 multiplies at 1/16 of the 16-bit rate on the matrix units, so a grid of few tiles (one
     // workgroup each) is served faster by the scalar kernel spread over the whole chip
     const int64_t n_items = km->n_tiles * (int64_t)((C_out + kCoutSlice - 1) / kCoutSlice);
-    const char* ft = getenv("FVDB_HOTPATH_FP32_TILES");      // "1": fp32 takes the tile kernel at any size (tests)
     const bool mfma = conv_tiles_shape_ok(km, in_dt, C_in, C_out) &&
-                      (in_dt != FX_F32 || n_items >= compute_units() / 2 || (ft && ft[0] == '1')) &&
-                      !(force && force[0] == '1');
+                      (in_dt != FX_F32 || n_items >= compute_units() / 2 || option(kOptFp32Tiles) == 1) &&   // fp32_tiles = 1: at any size
+                      !force_scalar;
     if (mfma) {
         void* wp = nullptr;
         FX_TRY(dev_alloc(&wp, conv_scratch_bytes(km->K3, C_in, C_out, esize), st));
@@ -1193,8 +1191,7 @@ fx_status fx::conv_scalar_on_table(const int32_t* d_table, int64_t n_rows, int K
     const bool four = C_in % 4 == 0 && C_out % 4 == 0;
     const int64_t total = n_rows * (four ? C_out / 4 : C_out);
     const size_t w_lds = sizeof(float) * (size_t)K3 * C_in * C_out;
-    const char* wl_env = getenv("FVDB_HOTPATH_SCALAR_LDS");          // "0": weights from L1 (tests run both)
-    const bool lds_w = four && w_lds <= 32 * 1024 && total >= 8 * 1024 && !(wl_env && wl_env[0] == '0');
+    const bool lds_w = four && w_lds <= 32 * 1024 && total >= 8 * 1024 && option(kOptScalarLds) != 0;   // scalar_lds = 0: weights from L1
     const unsigned nb = lds_w ? (unsigned)std::max<int64_t>(1, std::min<int64_t>((total + 255) / 256, (int64_t)compute_units() * 8))
                               : (unsigned)std::max<int64_t>(1, std::min<int64_t>((total + 255) / 256, 1 << 20));
 #define FX_SCALAR(DT)                                                                                            \

@@ -680,9 +680,8 @@ static hipError_t launch_reduce(const float* part, int n_ranges, int64_t total, 
 fx_status strided_pair_product(const fx_kmap* km, const void* d_src, fx_dtype dt, const void* d_w, int32_t C_contract,
                                int32_t C_produce, void* d_dst, fx_dtype out_dt, hipStream_t st, int mode) {
     const bool out_f32 = out_dt == FX_F32;
-    const char* force = getenv("FVDB_HOTPATH_FORCE_SCALAR");
     const bool mfma = dt != FX_F32 && km->n_tiles > 0 && C_contract % kCinChunk == 0 && C_produce % kCoutSlice == 0 &&
-                      !(force && force[0] == '1');
+                      option(kOptForceScalar) != 1;
     if (mfma) {
         void* wp = nullptr;
         const size_t wbytes = packed_weight_bytes(km->K3, C_contract, C_produce, 2);
@@ -692,8 +691,7 @@ fx_status strided_pair_product(const fx_kmap* km, const void* d_src, fx_dtype dt
         hipError_t e = hipGetLastError();
         const int nslice = C_produce / kCoutSlice, nchunk = C_contract / kCinChunk;
         const size_t lds = (size_t)km->K3 * nchunk * 4096 + (size_t)kDgradLdsWaves * km->K3 * kGroup * sizeof(int32_t);
-        const char* fl = getenv("FVDB_HOTPATH_GATHER_LDS");     // "0": never keep the weights in LDS (tests)
-        const bool lds_weights = lds <= 160 * 1024 && nchunk <= kDgradMaxChunks && !(fl && fl[0] == '0');
+        const bool lds_weights = lds <= 160 * 1024 && nchunk <= kDgradMaxChunks && option(kOptGatherLds) != 0;
         if (e == hipSuccess && lds_weights) {
             const int64_t n_blocks_total = km->n_tiles * (int64_t)kGroupsPerTile;
             int64_t grid = std::max(nslice, compute_units() / nslice * nslice);
@@ -771,8 +769,7 @@ static fx_status check_bwd_types(const char* who, fx_dtype dt, fx_dtype out_dt) 
 }
 
 static bool force_scalar() {
-    const char* force = getenv("FVDB_HOTPATH_FORCE_SCALAR");
-    return force && force[0] == '1';
+    return option(kOptForceScalar) == 1;
 }
 
 extern "C" fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_gout, fx_dtype dt, const void* d_w,
@@ -843,11 +840,10 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
         return FX_OK;
     }
     // fp32 at low depth on a 3x3x3 submanifold map: the leaf-window kernel sums on the matrix units straight from
-    // the grid, where everything below would take the scalar kernel (FVDB_HOTPATH_LEAF_DISPATCH=0 keeps that one)
+    // the grid, where everything below would take the scalar kernel (option leaf_dispatch = 0 keeps that one)
     if (km->K == 3 && km->stride == 1 && km->gin == km->gout && leaf_wgrad_shape_supported(dt, C_in, C_out) &&
         !force_scalar()) {
-        const char* ld = getenv("FVDB_HOTPATH_LEAF_DISPATCH");
-        if (!(ld && ld[0] == '0'))
+        if (option(kOptLeafDispatch) != 0)
             return leaf_wgrad("sparse convolution weight gradient (leaf-window kernel)", km->gin, d_feat, d_gout, dt, C_in,
                               C_out, d_gw, out_dt, st);
     }

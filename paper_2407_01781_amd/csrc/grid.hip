@@ -970,8 +970,7 @@ fx_status build_index_grid_device_joff(const int32_t* d_ijk, int64_t n_rows, con
     int cap_upper = B + 8;
     int cap_lower = (int)std::min<int64_t>(std::max<int64_t>(n_rows, 1), 64 * (int64_t)std::max(B, 1) + n_rows / 256);
     int cap_leaf = (int)std::min<int64_t>(std::max<int64_t>(n_rows, 1), 1024 + n_rows / 8);
-    const char* force = getenv("FVDB_HOTPATH_GRID_DIRECT");
-    bool direct = force && force[0] == '1';
+    bool direct = option(kOptGridDirect) == 1;
     for (int attempt = 0; attempt < 9; ++attempt) {
         fx_grid* g = nullptr;
         FX_TRY(build_attempt(d_ijk, n_rows, d_joff, B, cap_upper, cap_lower, cap_leaf, direct, st, &g));

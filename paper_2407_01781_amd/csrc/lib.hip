@@ -3,6 +3,7 @@
 
 #include <stdarg.h>
 #include <stdlib.h>
+#include <string.h>
 
 #include <mutex>
 #include <vector>
@@ -18,21 +19,24 @@ void set_error(const char* fmt, ...) {
     va_end(ap);
 }
 
-// Device memory comes from a cache of blocks owned by the library: a freed block is kept and
-// handed to the next request of a similar size, so steady-state calls (same shapes every step)
-// never reach the driver -- hipMallocAsync / hipFreeAsync cost 70-300 us per call here.  All
-// work of this library is stream-ordered, so a block released on stream S can be reused at once
-// by later work on S; reuse from another stream first waits for the device.
-// FVDB_HOTPATH_SYNC_ALLOC=1 switches to plain hipMalloc / hipFree; FVDB_HOTPATH_CACHE_MB bounds
-// the bytes kept (default 16384).
-static int use_sync_alloc() {
-    static int v = -1;
-    if (v < 0) {
-        const char* e = getenv("FVDB_HOTPATH_SYNC_ALLOC");
-        v = (e && e[0] == '1') ? 1 : 0;
-    }
-    return v;
-}
+// ---------------------------------------------------------------------------------- options
+static std::atomic<int> g_options[kOptCount] = {};          // stored as value + 1, so that zero-initialised = automatic
+static const char* const kOptionNames[kOptCount] = {"force_scalar", "leaf_dispatch", "fp32_tiles", "conv_gather", "gather_lds",
+                                                    "scalar_lds",   "grid_direct",   "cache_mb",   "sync_alloc"};
+int option(Option o) { return g_options[o].load(std::memory_order_relaxed) - 1; }
+
+// Device memory.  With a caller's allocator set (fx_set_allocator) every block comes from it and goes back to it.
+// Otherwise blocks come from a cache owned by the library: a freed block is kept and handed to the next request
+// of a similar size, so steady-state calls (same shapes every step) never reach the driver -- hipMallocAsync /
+// hipFreeAsync cost 70-300 us per call here.  All work of this library is stream-ordered, so a block released on
+// stream S can be reused at once by later work on S; reuse from another stream first waits for the device.
+// Option sync_alloc = 1 switches to plain hipMalloc / hipFree; option cache_mb bounds the bytes kept (2048 by
+// default).
+static fx_alloc_fn g_user_alloc = nullptr;
+static fx_free_fn g_user_free = nullptr;
+static void* g_user_ctx = nullptr;
+
+static int use_sync_alloc() { return option(kOptSyncAlloc) == 1; }
 
 struct Block { void* p; size_t bytes; hipStream_t stream; int device; };
 static std::mutex g_mem_mu;
@@ -41,13 +45,8 @@ static std::vector<Block> g_mem_live;
 static size_t g_mem_cached = 0;
 
 static size_t cache_limit() {
-    static size_t v = 0;
-    if (!v) {
-        const char* e = getenv("FVDB_HOTPATH_CACHE_MB");
-        const long mb = e ? atol(e) : 16384;
-        v = (size_t)(mb > 0 ? mb : 1) << 20;
-    }
-    return v;
+    const int mb = option(kOptCacheMb);
+    return (size_t)(mb >= 0 ? mb : 2048) << 20;
 }
 
 static size_t round_size(size_t bytes) {   // at most 12.5 % above the request, few distinct sizes
@@ -65,6 +64,11 @@ static void release_cached_locked() {
 
 fx_status dev_alloc(void** p, size_t bytes, hipStream_t s) {
     *p = nullptr;
+    if (g_user_alloc) {
+        *p = g_user_alloc(bytes ? bytes : 256, (void*)s, g_user_ctx);
+        if (!*p) { set_error("the caller's allocator returned no memory for %zu bytes", bytes); return FX_ENOMEM; }
+        return FX_OK;
+    }
     if (use_sync_alloc()) {
         hipError_t e = hipMalloc(p, bytes ? bytes : 256);
         if (e != hipSuccess) {
@@ -116,7 +120,6 @@ fx_status dev_alloc(void** p, size_t bytes, hipStream_t s) {
 
 void dev_free(void* p, hipStream_t s) {
     if (!p) return;
-    if (use_sync_alloc()) { (void)hipFree(p); return; }
     std::lock_guard<std::mutex> lock(g_mem_mu);
     for (int i = (int)g_mem_live.size() - 1; i >= 0; --i) {
         if (g_mem_live[i].p != p) continue;
@@ -133,7 +136,9 @@ void dev_free(void* p, hipStream_t s) {
         }
         return;
     }
-    (void)hipFree(p);   // not ours (allocated before a mode switch)
+    // not a block of the cache: the caller's allocator's, or a plain hipMalloc (sync_alloc)
+    if (g_user_free) g_user_free(p, (void*)s, g_user_ctx);
+    else (void)hipFree(p);
 }
 
 }  // namespace fx
@@ -257,6 +262,29 @@ extern "C" fx_status fx_profile_read(int slot, double* total_ms, int64_t* count)
     if (total_ms) *total_ms = fx::g_prof_ms[slot];
     if (count) *count = fx::g_prof_count[slot];
     return FX_OK;
+}
+
+extern "C" fx_status fx_set_allocator(fx_alloc_fn alloc, fx_free_fn release, void* ctx) {
+    if ((alloc == nullptr) != (release == nullptr)) { fx::set_error("fx_set_allocator: both functions or neither"); return FX_EINVAL; }
+    std::lock_guard<std::mutex> lock(fx::g_mem_mu);
+    fx::g_user_alloc = alloc; fx::g_user_free = release; fx::g_user_ctx = ctx;
+    return FX_OK;
+}
+
+extern "C" fx_status fx_set_option(const char* name, int32_t value) {
+    if (!name || value < -1) { fx::set_error("fx_set_option: null name or value below -1"); return FX_EINVAL; }
+    for (int o = 0; o < fx::kOptCount; ++o)
+        if (!strcmp(name, fx::kOptionNames[o])) { fx::g_options[o].store(value + 1); return FX_OK; }
+    fx::set_error("fx_set_option: unknown option '%s'", name);
+    return FX_EINVAL;
+}
+
+extern "C" fx_status fx_get_option(const char* name, int32_t* value) {
+    if (!name || !value) { fx::set_error("fx_get_option: null pointer"); return FX_EINVAL; }
+    for (int o = 0; o < fx::kOptCount; ++o)
+        if (!strcmp(name, fx::kOptionNames[o])) { *value = fx::option((fx::Option)o); return FX_OK; }
+    fx::set_error("fx_get_option: unknown option '%s'", name);
+    return FX_EINVAL;
 }
 
 extern "C" const char* fx_version(void) { return "fvdb-hotpath-gfx950 0.1"; }

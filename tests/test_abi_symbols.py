@@ -84,3 +84,18 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
 def test_leaf_record_is_96_bytes_with_an_80_byte_payload():
     from paper_2407_01781_amd.binding import LEAF_DTYPE
     assert LEAF_DTYPE.itemsize == 96 and LEAF_DTYPE.fields["origin"][1] == 80
+
+
+def test_options_and_allocator_hook_on_the_host(lib):
+    lib.fx_last_error.restype = C.c_char_p
+    v = C.c_int32(7)
+    assert lib.fx_get_option(b"leaf_dispatch", C.byref(v)) == 0 and v.value == -1          # automatic by default
+    assert lib.fx_set_option(b"leaf_dispatch", 0) == 0
+    assert lib.fx_get_option(b"leaf_dispatch", C.byref(v)) == 0 and v.value == 0
+    assert lib.fx_set_option(b"leaf_dispatch", -1) == 0
+    assert lib.fx_set_option(b"no_such_switch", 1) == -1 and b"no_such_switch" in lib.fx_last_error()
+    assert lib.fx_set_option(b"cache_mb", -2) == -1 and lib.fx_set_option(None, 1) == -1
+    assert lib.fx_get_option(b"cache_mb", None) == -1
+    cb = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p)(lambda n, s, c: None)
+    assert lib.fx_set_allocator(C.cast(cb, C.c_void_p), None, None) == -1             # both functions or neither
+    assert lib.fx_set_allocator(None, None, None) == 0

@@ -38,22 +38,22 @@ def test_mfma_path_small_workloads(name, out_f32):
 
 @pytest.mark.parametrize("name", ["lidar_small", "lidar_small_down", "sheets_small", "indoor_small"])
 @pytest.mark.parametrize("gather", ["0", "1"])
-def test_both_mfma_kernels_serve_every_map(name, gather, monkeypatch):
+def test_both_mfma_kernels_serve_every_map(name, gather, fx_opt):
     # by default strided maps take the gather kernel and the others the LDS-staged kernel; each kernel
     # must also be right on the other kind of map
-    monkeypatch.setenv("FVDB_HOTPATH_CONV_GATHER", gather)
+    fx_opt("conv_gather", gather)
     y, ref, dt, k3, c_in = _run(G.workload(name))
     H.conv_tolerance_check(y, ref, dt, k3, c_in)
 
 
 @pytest.mark.parametrize("lds_weights", ["0", "1"])
-def test_gather_kernel_with_and_without_weights_in_lds(lds_weights, monkeypatch):
+def test_gather_kernel_with_and_without_weights_in_lds(lds_weights, fx_opt):
     # strided maps: by default the packed weights of a slice sit in LDS when they fit; the switch
     # sends the same map to the kernel that fetches them per step
-    monkeypatch.setenv("FVDB_HOTPATH_GATHER_LDS", lds_weights)
+    fx_opt("gather_lds", lds_weights)
     for name, c_in, c_out in (("lidar_small_down", 64, 128), ("lidar_small_down", 32, 64), ("sheets_small", 32, 64)):
         if name == "sheets_small":
-            monkeypatch.setenv("FVDB_HOTPATH_CONV_GATHER", "1")      # K = 3: 27 x 32 channels no longer fit, falls back
+            fx_opt("conv_gather", "1")      # K = 3: 27 x 32 channels no longer fit, falls back
         y, ref, dt, k3, ci = _run(G.workload(name), c_in=c_in, c_out=c_out, dtype="bf16")
         H.conv_tolerance_check(y, ref, dt, k3, ci)
 
@@ -73,11 +73,11 @@ def test_channel_shapes_mfma_and_scalar(dtype, c_in, c_out):
 @pytest.mark.parametrize("dtype,c_in,c_out", [("bf16", 32, 40), ("f16", 64, 34), ("bf16", 96, 2), ("f32", 16, 16),
                                              ("f32", 32, 96), ("f32", 48, 6), ("f32", 64, 64)])
 @pytest.mark.parametrize("name", ["sheets_small", "lidar_small_down"])
-def test_tile_kernel_with_fp32_rows_and_padded_output_channels(name, dtype, c_in, c_out, monkeypatch):
+def test_tile_kernel_with_fp32_rows_and_padded_output_channels(name, dtype, c_in, c_out, fx_opt):
     # input rows in whole 64-byte chunks (32 channels of a 16-bit type, 16 of fp32) and an even number
     # of output channels run on the matrix units; fp32 keeps true fp32 products (the fp32 bar applies).
     # Small fp32 grids go to the scalar kernel by default; the switch sends them to the tile kernel.
-    monkeypatch.setenv("FVDB_HOTPATH_FP32_TILES", "1")
+    fx_opt("fp32_tiles", "1")
     y, ref, dt, k3, ci = _run(G.workload(name), c_in=c_in, c_out=c_out, dtype=dtype)
     H.conv_tolerance_check(y, ref, dt, k3, ci)
 
@@ -101,8 +101,8 @@ def test_pointwise_and_5x5x5_kernels(K, dtype, c_in, c_out):
 
 
 @pytest.mark.parametrize("tiles", ["0", "1"])
-def test_fp32_scalar_and_tile_kernels_on_config1(tiles, monkeypatch):
-    monkeypatch.setenv("FVDB_HOTPATH_FP32_TILES", tiles)
+def test_fp32_scalar_and_tile_kernels_on_config1(tiles, fx_opt):
+    fx_opt("fp32_tiles", tiles)
     y, ref, dt, k3, c_in = _run(G.workload("sphere64"))
     H.conv_tolerance_check(y, ref, dt, k3, c_in)
 
@@ -154,10 +154,10 @@ def test_3x3x3_stride_2(dtype, c_in, c_out):
 
 @pytest.mark.parametrize("lds_weights", ["0", "1"])
 @pytest.mark.parametrize("dtype,c_in,c_out", [("f32", 8, 16), ("bf16", 8, 16), ("f16", 4, 32), ("f32", 12, 8)])
-def test_low_depth_scalar_kernel_with_and_without_weights_in_lds(dtype, c_in, c_out, lds_weights, monkeypatch):
+def test_low_depth_scalar_kernel_with_and_without_weights_in_lds(dtype, c_in, c_out, lds_weights, fx_opt):
     # depths the matrix kernels do not take on a sparse grid: the scalar kernel, weights in LDS by default
-    monkeypatch.setenv("FVDB_HOTPATH_SCALAR_LDS", lds_weights)
-    monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", "0")
+    fx_opt("scalar_lds", lds_weights)
+    fx_opt("leaf_dispatch", "0")
     for name in ("lidar_small", "lidar_small_down"):
         y, ref, dt, k3, ci = _run(G.workload(name), c_in=c_in, c_out=c_out, dtype=dtype)
         H.conv_tolerance_check(y, ref, dt, k3, ci)
@@ -205,10 +205,10 @@ def test_scalar_and_mfma_paths_agree_with_oracle_on_empty_and_tiny_grids():
     H.conv_tolerance_check(y.float().cpu().numpy(), O.conv(og, og, 3, 1, feat, wt), "bf16", 27, 64)
 
 
-def test_dense_block_uses_rows_beyond_the_lds_budget(monkeypatch):
+def test_dense_block_uses_rows_beyond_the_lds_budget(fx_opt):
     # a dense 24^3 block: every tile is one full leaf whose 10^3 footprint has more distinct
     # input rows than the convolution stages in LDS, so part of them is read from global memory
-    monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", "0")      # this test is about the tile kernel's general variant
+    fx_opt("leaf_dispatch", "0")      # this test is about the tile kernel's general variant
     a = np.arange(24, dtype=np.int32)
     pts = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3)
     g, og = H.both_grids(pts, np.array([[0, pts.shape[0]]]))
@@ -220,13 +220,13 @@ def test_dense_block_uses_rows_beyond_the_lds_budget(monkeypatch):
 
 @pytest.mark.parametrize("name", ["lidar1m", "indoor4", "lidar1m_down", "sheets4", "volume1m_c64", "dense96",
                                   "volume1m_c64:tiles", "dense96:tiles"])
-def test_full_size_configs_sampled_rows(name, monkeypatch):
+def test_full_size_configs_sampled_rows(name, fx_opt):
     """Configs 3, 2, 4 and 5 at full size in the benchmark's launch configuration; the oracle
     computes a sample of output rows one by one (a few thousand rows spread over the grid, the
     first and the last rows included).  The volumetric and the dense grid run twice: through the
     leaf-window kernels, which the convolution picks for them, and (":tiles") through the tile kernel."""
     if name.endswith(":tiles"):
-        monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", "0")
+        fx_opt("leaf_dispatch", "0")
         name = name[:-6]
     w = G.workload(name)
     ijk, jo = w.jagged_ijk()

@@ -62,8 +62,8 @@ def test_mfma_paths_small_workloads(name, out_f32):
 
 
 @pytest.mark.parametrize("name", ["lidar_small", "lidar_small_down"])
-def test_scalar_paths_agree_with_the_oracle_too(name, monkeypatch):
-    monkeypatch.setenv("FVDB_HOTPATH_FORCE_SCALAR", "1")
+def test_scalar_paths_agree_with_the_oracle_too(name, fx_opt):
+    fx_opt("force_scalar", "1")
     _check_both(G.workload(name), c_in=16, c_out=24)
 
 
@@ -120,8 +120,8 @@ def test_empty_and_tiny_grids():
     _wgrad_check(gw, O.conv_bwd_weight(og, og, 3, 1, feat, gy), 2e-3)
 
 
-def test_dense_block_with_rows_beyond_the_lds_budget(monkeypatch):
-    monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", "0")      # this test is about the tile kernel's general variant
+def test_dense_block_with_rows_beyond_the_lds_budget(fx_opt):
+    fx_opt("leaf_dispatch", "0")      # this test is about the tile kernel's general variant
     a = np.arange(24, dtype=np.int32)
     pts = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3)
     g, og = H.both_grids(pts, np.array([[0, pts.shape[0]]]))

@@ -101,8 +101,8 @@ def test_empty_grid_and_empty_batch_member():
     _leaf_vs_oracle([w.grids[0], np.zeros((0, 3), np.int32), w.grids[1]], 8, 16, 73)
 
 
-def test_agrees_with_the_kernel_map_path(monkeypatch):
-    monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", "0")      # keep fx.sparse_conv_fwd on the kernel-map kernels
+def test_agrees_with_the_kernel_map_path(fx_opt):
+    fx_opt("leaf_dispatch", "0")      # keep fx.sparse_conv_fwd on the kernel-map kernels
     w = G.workload("volume_small")
     g, feat, wt, y = _leaf_vs_oracle(w.grids, 8, 16, w.feat_seed)
     km = fx.build_kernel_map(g, 3, 1)
@@ -168,8 +168,8 @@ def test_input_gradient_sixteen_bit(dtype, c_in, c_out, out_f32):
     _leaf_bwd_vs_oracle(w.grids, c_in, c_out, w.feat_seed, dtype, out_f32)
 
 
-def test_input_gradient_on_sparse_grid_and_against_the_kernel_map_path(monkeypatch):
-    monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", "0")
+def test_input_gradient_on_sparse_grid_and_against_the_kernel_map_path(fx_opt):
+    fx_opt("leaf_dispatch", "0")
     w = G.workload("lidar_small")
     g, gy, wt, gin = _leaf_bwd_vs_oracle(w.grids, 64, 64, w.feat_seed, "bf16")
     km = fx.build_kernel_map(g, 3, 1)
@@ -195,13 +195,11 @@ def test_input_gradient_is_the_adjoint_of_the_forward():
 
 # ---------------------------------------------------------------- dispatch from the kernel-map entry points
 @pytest.mark.parametrize("switch,expect_leaf", [(None, True), ("0", False), ("1", True)])
-def test_kernel_map_entry_points_take_the_leaf_kernels_on_dense_grids(switch, expect_leaf, monkeypatch):
+def test_kernel_map_entry_points_take_the_leaf_kernels_on_dense_grids(switch, expect_leaf, fx_opt):
     # a dense block: by default fx.sparse_conv_fwd / bwd_data on its (3,1) map run the leaf-window kernels; the
     # switch keeps the tile kernels.  Both must meet the oracle; which kernel ran is read from the profile slots.
-    if switch is None:
-        monkeypatch.delenv("FVDB_HOTPATH_LEAF_DISPATCH", raising=False)
-    else:
-        monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", switch)
+    if switch is not None:
+        fx_opt("leaf_dispatch", switch)
     a = np.arange(-12, 12, dtype=np.int32)
     blk = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3)
     g, og = H.both_grids(blk, np.array([[0, blk.shape[0]]]))
@@ -220,8 +218,7 @@ def test_kernel_map_entry_points_take_the_leaf_kernels_on_dense_grids(switch, ex
     H.conv_tolerance_check(gx.float().cpu().numpy(), O.conv_bwd_data(og, og, 3, 1, gy, wt), "bf16", 27, 64)
 
 
-def test_sparse_grids_stay_on_the_kernel_map_kernels(monkeypatch):
-    monkeypatch.delenv("FVDB_HOTPATH_LEAF_DISPATCH", raising=False)
+def test_sparse_grids_stay_on_the_kernel_map_kernels():
     w = G.workload("lidar_small")
     ijk, jo = w.jagged_ijk()
     g, og = H.both_grids(ijk, jo)
@@ -293,11 +290,9 @@ def test_weight_gradient_edge_cases_and_reproducibility():
 
 
 @pytest.mark.parametrize("switch", [None, "0"])
-def test_kernel_map_weight_gradient_takes_the_leaf_kernel_at_low_depth(switch, monkeypatch):
-    if switch is None:
-        monkeypatch.delenv("FVDB_HOTPATH_LEAF_DISPATCH", raising=False)
-    else:
-        monkeypatch.setenv("FVDB_HOTPATH_LEAF_DISPATCH", switch)
+def test_kernel_map_weight_gradient_takes_the_leaf_kernel_at_low_depth(switch, fx_opt):
+    if switch is not None:
+        fx_opt("leaf_dispatch", switch)
     w = G.workload("volume_small")
     ijk, jo = w.jagged_ijk()
     g, og = H.both_grids(ijk, jo)

@@ -41,7 +41,7 @@ def test_sparse_points_overflow_the_first_capacity_guess():
     H.check_grid(g, og)
 
 
-def test_large_inputs_take_the_bucket_path_and_agree_with_the_direct_path(monkeypatch):
+def test_large_inputs_take_the_bucket_path_and_agree_with_the_direct_path(fx_opt):
     # above 65536 rows the build scatters the rows into buckets first; the same input through the
     # direct path (one global table) must give the same bits, and both must match the oracle
     grids = [_cloud(31, 60000, -60, 60), np.zeros((0, 3), np.int32), _cloud(32, 50000, 4000, 4200),
@@ -49,7 +49,7 @@ def test_large_inputs_take_the_bucket_path_and_agree_with_the_direct_path(monkey
     ijk, jo = G.make_jagged(grids)
     g, og = H.both_grids(ijk, jo)
     H.check_grid(g, og)
-    monkeypatch.setenv("FVDB_HOTPATH_GRID_DIRECT", "1")
+    fx_opt("grid_direct", "1")
     g2, _ = H.both_grids(ijk, jo)
     H.check_grid(g2, og)
     assert g.leaf_table().tobytes() == g2.leaf_table().tobytes()

@@ -98,8 +98,8 @@ def test_transposed_convolution_on_a_submanifold_map(dtype, c_in, c_out):
     H.conv_tolerance_check(y.float().cpu().numpy(), O.conv_transpose(og, og, 3, 1, z, wt), dtype, 27, c_in)
 
 
-def test_scalar_path_of_the_transposed_convolution(monkeypatch):
-    monkeypatch.setenv("FVDB_HOTPATH_FORCE_SCALAR", "1")
+def test_scalar_path_of_the_transposed_convolution(fx_opt):
+    fx_opt("force_scalar", "1")
     km, og, ogc = _pair_map("lidar_small_down")
     z = _feat(55, ogc.num_voxels, 64, "bf16")
     _, wt = G.features_and_weights(56, 1, 64, 64, 8, "bf16")

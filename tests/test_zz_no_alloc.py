@@ -35,10 +35,10 @@ def _check(case):
     H.conv_tolerance_check(out.float().cpu().numpy(), ref, dtype, k3, c_in)
 
 
-def test_two_calls_in_a_row_the_second_smaller(monkeypatch):
+def test_two_calls_in_a_row_the_second_smaller(fx_opt):
     # small fp32 grids: the allocating entry point would pick its scalar kernel (another summation order); the
     # switch keeps it on the matrix-unit kernel that the no-allocation entry point always takes
-    monkeypatch.setenv("FVDB_HOTPATH_FP32_TILES", "1")
+    fx_opt("fp32_tiles", "1")
     big = _case(G.workload("lidar_small"), 64, 128, "bf16", False)          # 196 tiles x 2 slices, 27 x 64 x 128 weights
     small = _case(G.workload("sphere64"), 32, 64, "f16", True)              # 19 tiles, fewer and smaller weights
     strided = _case(G.workload("lidar_small_down"), 64, 128, "bf16", False)   # the gather kernel's tiles
