@@ -37,6 +37,8 @@ WORKLOAD_DESC = {
                 "3x3x3 submanifold, 8->16 fp32",
     "volume1m_c64": "volumetric class: the volume1m grid, 3x3x3 submanifold, 64->64 bf16",
     "dense96": "dense class: a full 96^3 block (884 736 voxels), 3x3x3 submanifold, 64->64 bf16",
+    "mixed1m": "mixed classes in one grid: LiDAR-like rings and boxes, thin shells and solid balls (697 301 voxels, 62 % of "
+               "them in locally dense leaves), 3x3x3 submanifold, 64->64 bf16",
 }
 
 
@@ -333,6 +335,27 @@ def main():
             "kernel_map_path_ms": {"kernel_map": t_kmv, "conv": t_c16}}
         del kmv, gv, v_feat, h_feat
 
+    # ---- per-leaf dispatch (the paper's future-work item; Sec. 3.5's scenarios are its regimes) on a grid that mixes
+    # the sparsity classes: the same convolution through the tile kernel alone, the leaf-window kernel alone, and
+    # split per leaf inside one call (not part of `value`)
+    per_leaf = None
+    if not args.no_low_depth:
+        wm = G.workload("mixed1m")
+        m_ijk, m_jo = wm.jagged_ijk()
+        gm = fx.build_index_grid(torch.from_numpy(m_ijk).cuda(), m_jo)
+        kmm = fx.build_kernel_map(gm, 3, 1)
+        m_pairs = kmm.info()[0]
+        m_feat = torch.randn((gm.num_voxels, 64), device="cuda").to(torch.bfloat16)
+        m_w = (torch.randn((27, 64, 64), device="cuda") * (1.0 / (27 * 64)) ** 0.5).to(torch.bfloat16)
+        m_out = torch.empty((gm.num_voxels, 64), dtype=torch.bfloat16, device="cuda")
+        per_leaf = {"workload": WORKLOAD_DESC["mixed1m"], "n_voxels": gm.num_voxels, "n_leaves": gm.counts()[0], "active_pairs": m_pairs}
+        for sw, key in ((0, "tile_kernel_only_ms"), (1, "leaf_window_kernel_only_ms"), (-1, "automatic_per_leaf_dispatch_ms")):
+            fx.set_option("leaf_dispatch", sw)
+            per_leaf[key] = b2b(lambda: fx.sparse_conv_fwd(kmm, m_feat, m_w, out=m_out), reps=5)
+        fx.set_option("leaf_dispatch", -1)
+        per_leaf["automatic_effective_TFLOPs"] = 2.0 * m_pairs * 64 * 64 / (per_leaf["automatic_per_leaf_dispatch_ms"] * 1e-3) / 1e12
+        del kmm, gm, m_feat, m_out
+
     # ---- grid build from xyz points (Sec. 4.1.1's benchmark input: normally distributed points), 10 M points,
     # sigma = 100 voxels (not part of `value`)
     points_build = None
@@ -462,6 +485,7 @@ def main():
         "low_depth": low_depth,
         "grid_from_points": points_build,
         "padded_output": padded_output,
+        "per_leaf_dispatch": per_leaf,
         "kernels_ms_per_launch": kern_ms,
         "kernels_ms_per_step": per_step_ms,
         "clocks": gpu_clocks(),

@@ -84,7 +84,8 @@ void fx_release_cached_memory(void);
  * tolerances.  Unknown names and values below -1 return FX_EINVAL.
  *   "force_scalar"   1: convolution and both gradients on the scalar kernels (no matrix units)
  *   "leaf_dispatch"  3x3x3 stride-1 maps: 0 never / 1 always (when the shape allows) hand the call to the
- *                    leaf-window kernels; automatic: by mean leaf occupancy (see fx_sparse_conv_fwd)
+ *                    leaf-window kernels, 2 always split it per leaf; automatic: by mean leaf occupancy and the
+ *                    share of voxels in dense leaves (see fx_sparse_conv_fwd)
  *   "fp32_tiles"     1: FX_F32 takes the matrix-unit tile kernel at any grid size (automatic: from ~128 tiles on)
  *   "conv_gather"    0 / 1: the LDS-staged / the gather kernel on every tiled map (automatic: by the kind of map)
  *   "gather_lds"     0: the gather kernels fetch their weights per step instead of keeping them in LDS
@@ -243,6 +244,10 @@ void fx_kmap_destroy(fx_kmap* km);
  *   - on a 3x3x3 stride-1 submanifold map whose grid is locally dense (mean leaf occupancy >= 0.40, or >= 0.08
  *     for FX_F32 with C_in not a multiple of 16) and whose shape fx_sparse_conv_leaf_fwd serves: the
  *     leaf-window kernels;
+ *   - per-leaf dispatch (16-bit types, shapes of the leaf-window kernel): a sparser grid of which at least 10 % of
+ *     the voxels sit in locally dense leaves (>= 205 of 512 voxels) is split inside the call -- those leaves go to
+ *     the leaf-window kernel, all other outputs to the tile kernel over a second copy of the map, built on the
+ *     first such call and kept with the map;
  *   - everything else: a scalar kernel (fp32 FMA in offset-then-channel order).
  */
 fx_status fx_sparse_conv_fwd(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, const void* d_w,

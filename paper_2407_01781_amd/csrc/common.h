@@ -73,6 +73,8 @@ struct ProfScope {
 // Node fan-outs of the VDB tree (Sec. 3.1): upper 32^3 children, lower 16^3, leaf 8^3 voxels.
 constexpr int kUpperWords = 32 * 32 * 32 / 64;  // 512 child-mask words per upper node
 constexpr int kLowerWords = 16 * 16 * 16 / 64;  // 64 child-mask words per lower node
+// a leaf counts as locally dense from 40 % occupancy on (Sec. 3.5: the dense-window operators win from there)
+constexpr int kDenseLeafVoxels = 205;
 constexpr int kMaxTiles = 65536;                // root tiles per batch (documented limit)
 constexpr int kTileHashSlots = 1 << 17;
 
@@ -86,7 +88,7 @@ struct GridHeader {
     int32_t n_leaf_raw;   // distinct leaves found by the voxel pass (may exceed capacity)
     int32_t pad[2];
     int64_t n_voxels;
-    int64_t pad2;
+    int64_t n_voxels_dense;   // voxels in leaves that hold at least kDenseLeafVoxels of them (what the convolution's per-leaf dispatch goes by)
 };
 
 // Device view of one GridBatch.  Internal nodes keep only a child bitmask and, per mask

@@ -174,14 +174,14 @@ k_conv_scalar4_ldsw(const int32_t* __restrict__ nbmap, int64_t n_out, int K3, co
 
 template <typename T, bool OUT_F32>
 __device__ __forceinline__ void store_block_rows(const f32x16 (&acc)[2], const uint16_t* perm_g, unsigned char* tile_out,
-                                                 int C_out, int cols, int n_valid, int n, int h) {
+                                                 int C_out, int cols, int n_valid, int n, int h, bool all_rows) {
     const uint32_t esize = OUT_F32 ? 4u : 2u;
     const uint32_t row_bytes = (uint32_t)C_out * esize, lane_off = 2u * (uint32_t)n * esize;
     // keep the base in scalar registers: the stores then take it as their scalar address operand
     const uint64_t bits = reinterpret_cast<uint64_t>(tile_out);
     const uint32_t lo = (uint32_t)uni((int)(uint32_t)bits), hi = (uint32_t)uni((int)(uint32_t)(bits >> 32));
     global_byte* base = (global_byte*)(((uint64_t)hi << 32) | lo);
-    if (n_valid == kTileT && cols == kCoutSlice)
+    if (all_rows && n_valid == kTileT && cols == kCoutSlice)      // otherwise: rows beyond the tile's end or left to another kernel (0xFFFF)
         store_block_rows_impl<T, OUT_F32, true>(acc, perm_g, base, row_bytes, lane_off, n_valid, true, h);
     else
         store_block_rows_impl<T, OUT_F32, false>(acc, perm_g, base, row_bytes, lane_off, n_valid, 2 * n < cols, h);
@@ -216,7 +216,7 @@ struct Item {
     int64_t tile;
     int slice;
     int win_lo, win_n, n_list, n_blocks, n_valid, n_staged;
-    bool general;
+    bool general, all_rows;
 };
 
 __device__ __forceinline__ int64_t slot_work(const MetaSlot& M) {
@@ -233,6 +233,7 @@ __device__ __forceinline__ Item item_of(const MetaSlot& M, int64_t work, int nsl
     const int flags = uni(M.hdr.flags);
     I.n_staged = (flags & kTileDirect) ? 0 : min(I.win_n + I.n_list, kRowCap);
     I.general = !(flags & kTileLdsOffsets);
+    I.all_rows = !(flags & kTilePartial);
     return I;
 }
 
@@ -520,7 +521,7 @@ __device__ __forceinline__ void consume_item(ConvLds& L, const MetaSlot& M, cons
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi)
         store_block_rows<T, OUT_F32>(acc[gi], L.perm[pb] + tile_group_of(wave, gi) * kGroup, tile_out, C_out,
-                                     min(kCoutSlice, C_out - I.slice * kCoutSlice), I.n_valid, n, h);
+                                     min(kCoutSlice, C_out - I.slice * kCoutSlice), I.n_valid, n, h, I.all_rows);
     FX_CYCLES_ADD(tm[2]);
 }
 
@@ -1157,8 +1158,27 @@ fx_status fx::conv_apply(const fx_kmap* km, const void* d_feat, fx_dtype in_dt, 
         leaf_shape_supported(in_dt, C_in, C_out) && !force_scalar) {
         const int ld = option(kOptLeafDispatch);
         const double occupancy = (double)km->n_in / (512.0 * (double)std::max<int64_t>(1, km->gin->hdr.n_leaf));
+        // Per-leaf dispatch: a grid that mixes locally dense leaves (solid bodies) with sparse ones (thin surfaces,
+        // scan lines) is split inside this one call -- the leaves with at least kDenseLeafVoxels voxels go to the
+        // leaf-window kernel, the outputs of all other leaves to the tile kernel over a copy of the map that leaves
+        // the dense leaves' outputs out.  Taken when the grid as a whole is too sparse for the leaf-window kernel
+        // (mean occupancy below 0.40) but at least 10 % of its voxels sit in dense leaves; leaf_dispatch = 2 forces it.
+        if (in_dt != FX_F32 && !km->is_inverse) {
+            const double dense = (double)km->gin->hdr.n_voxels_dense / (double)std::max<int64_t>(1, km->n_in);
+            if (ld == 2 || (ld < 0 && occupancy < 0.40 && dense >= 0.10)) {
+                fx_kmap* kmw = const_cast<fx_kmap*>(km);
+                FX_TRY(kmap_ensure_mixed(kmw, st));
+                void* wp = nullptr;
+                FX_TRY(dev_alloc(&wp, conv_scratch_bytes(27, C_in, C_out, 2), st));
+                fx_status rc = conv_tiles_with_scratch(km->mixed, d_feat, in_dt, d_w, C_in, C_out, d_out, out_dt, st, mode, wp);
+                dev_free(wp, st);
+                if (rc != FX_OK) return rc;
+                return leaf_apply("sparse convolution (per-leaf dispatch)", km->gin, d_feat, in_dt, d_w, C_in, C_out, d_out, out_dt, st,
+                                  mode, km->mixed->d_dense_leaves, km->mixed->d_n_dense);
+            }
+        }
         const bool scalar_otherwise = in_dt == FX_F32 && C_in % 16 != 0;
-        const bool take = ld >= 0 ? ld == 1 : occupancy >= (scalar_otherwise ? 0.08 : 0.40);
+        const bool take = ld >= 0 ? ld >= 1 : occupancy >= (scalar_otherwise ? 0.08 : 0.40);
         if (take)
             return leaf_apply("sparse convolution (leaf-window kernels)", km->gin, d_feat, in_dt, d_w, C_in, C_out, d_out, out_dt,
                               st, mode);

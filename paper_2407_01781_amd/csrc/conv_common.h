@@ -146,8 +146,10 @@ fx_status conv_noalloc_setup(void** out_ptr);
 // The 3x3x3 stride-1 convolution of `src` [N, C_contract] into `dst` [N, C_produce] straight from the grid, leaf by
 // leaf, without a kernel map (Sec. 3.5 scenario 1); `mode` is kWeightsForward or kWeightsMirrored (input gradient).
 // FX_EUNSUPPORTED for shapes its kernels do not serve.  leaf_shape_supported says so without setting an error.
+// leaf_list / n_list (device; 16-bit types only): work on these leaves only instead of on all of them.
 fx_status leaf_apply(const char* who, const fx_grid* g, const void* d_src, fx_dtype dt, const void* d_w, int32_t C_contract,
-                     int32_t C_produce, void* d_dst, fx_dtype out_dt, hipStream_t st, int mode);
+                     int32_t C_produce, void* d_dst, fx_dtype out_dt, hipStream_t st, int mode,
+                     const int32_t* leaf_list = nullptr, const int32_t* n_list = nullptr);
 inline bool leaf_shape_supported(fx_dtype dt, int C_contract, int C_produce) {
     if (dt == FX_F32) return C_contract % 4 == 0 && C_contract <= 16 && C_produce % 4 == 0 && C_produce <= 32;
     return C_contract % 32 == 0 && C_produce % 64 == 0;

@@ -540,7 +540,9 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
                                                                   const unsigned char* __restrict__ wp,
                                                                   unsigned char* __restrict__ out, int C_in, int C_out,
                                                                   int32_t* __restrict__ work_counter,
-                                                                  const unsigned char* __restrict__ zero_row) {
+                                                                  const unsigned char* __restrict__ zero_row,
+                                                                  const int32_t* __restrict__ leaf_list,
+                                                                  const int32_t* __restrict__ n_list) {
     typedef typename Elem<T>::vec8 vec8;
     extern __shared__ __align__(16) unsigned char smem[];
     Leaf16Lds& L = *reinterpret_cast<Leaf16Lds*>(smem);
@@ -551,12 +553,15 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
     // Leaves are claimed one at a time from a counter in global memory, in index order: workgroups that run
     // together then work on neighbouring leaves (whose windows overlap, so their rows meet in L2), and the
     // tail is one leaf long.  The next claim is made while the current leaf is processed.
+    // With a leaf list (per-leaf dispatch) the claimed numbers index the list: only those leaves are worked on.
+    const int n_work = leaf_list ? uni(*n_list) : t.n_leaf;
     if (tid0 == 0) L.range[0] = atomicAdd(work_counter, 1);
     __syncthreads();
-    int f = uni(L.range[0]);
+    int fi = uni(L.range[0]);
     int parity = 0;
 
-    while (f < t.n_leaf) {
+    while (fi < n_work) {
+        const int f = leaf_list ? uni(leaf_list[fi]) : fi;
         parity ^= 1;
         if (tid0 == 64) L.range[parity] = atomicAdd(work_counter, 1);    // by the second wave (the first walks the tree); read after this leaf's barriers
         // everything a thread derives from its number is recomputed per leaf (registers are needed
@@ -722,13 +727,13 @@ __global__ __launch_bounds__(kLeaf16Threads, 2) void k_conv_leaf16(TreeView t, c
             }
         }
         __syncthreads();                         // records and lists are rewritten for the next leaf
-        f = uni(L.range[parity]);
+        fi = uni(L.range[parity]);
     }
 }
 
 template <typename T, bool OUT_F32>
 fx_status launch_leaf16(const fx_grid* g, const void* feat, const void* wpacked, void* out, int C_in, int C_out,
-                        void* work_counter, const void* zero_row, hipStream_t st) {
+                        void* work_counter, const void* zero_row, const int32_t* leaf_list, const int32_t* n_list, hipStream_t st) {
     const size_t lds = sizeof(Leaf16Lds);
     static int per_cu = 0;
     if (per_cu == 0) {
@@ -742,7 +747,7 @@ fx_status launch_leaf16(const fx_grid* g, const void* feat, const void* wpacked,
     ProfScope ps(kProfConvLeaf, st);
     k_conv_leaf16<T, OUT_F32><<<n_wg, kLeaf16Threads, lds, st>>>(g->view(), (const unsigned char*)feat,
                                                                  (const unsigned char*)wpacked, (unsigned char*)out, C_in,
-                                                                 C_out, (int32_t*)work_counter, (const unsigned char*)zero_row);
+                                                                 C_out, (int32_t*)work_counter, (const unsigned char*)zero_row, leaf_list, n_list);
     FX_HIP_TRY(hipGetLastError());
     return FX_OK;
 }
@@ -791,7 +796,8 @@ using namespace fx;
 // The leaf-window convolution of `src` [N, C_contract] into `dst` [N, C_produce]; `mode` says how the
 // caller's weights are read (kWeightsForward, or kWeightsMirrored for the input gradient).
 fx_status fx::leaf_apply(const char* who, const fx_grid* g, const void* d_src, fx_dtype dt, const void* d_w,
-                            int32_t C_contract, int32_t C_produce, void* d_dst, fx_dtype out_dt, hipStream_t st, int mode) {
+                            int32_t C_contract, int32_t C_produce, void* d_dst, fx_dtype out_dt, hipStream_t st, int mode,
+                            const int32_t* leaf_list, const int32_t* n_list) {
     if (!g || !d_w || C_contract < 1 || C_produce < 1 || (g->hdr.n_voxels > 0 && (!d_src || !d_dst))) {
         set_error("%s: null pointer or non-positive channel count", who);
         return FX_EINVAL;
@@ -823,11 +829,11 @@ fx_status fx::leaf_apply(const char* who, const fx_grid* g, const void* d_src, f
                             kPackInterleaved, st);
         fx_status rc;
         if (dt == FX_BF16)
-            rc = out_dt == FX_F32 ? launch_leaf16<__bf16, true>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, st)
-                                  : launch_leaf16<__bf16, false>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, st);
+            rc = out_dt == FX_F32 ? launch_leaf16<__bf16, true>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, leaf_list, n_list, st)
+                                  : launch_leaf16<__bf16, false>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, leaf_list, n_list, st);
         else
-            rc = out_dt == FX_F32 ? launch_leaf16<_Float16, true>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, st)
-                                  : launch_leaf16<_Float16, false>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, st);
+            rc = out_dt == FX_F32 ? launch_leaf16<_Float16, true>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, leaf_list, n_list, st)
+                                  : launch_leaf16<_Float16, false>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, leaf_list, n_list, st);
         dev_free(wpk, st);
         return rc;
     }

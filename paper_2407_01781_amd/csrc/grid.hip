@@ -623,6 +623,14 @@ __global__ void __launch_bounds__(kScanThreads) k_scan_leaves_local(fx_leaf* __r
         }
         sum += cnt[q];
     }
+    {   // voxels that sit in locally dense leaves, summed over the grid
+        uint32_t dense = 0;
+#pragma unroll
+        for (int q = 0; q < kLeavesPerThread; ++q) dense += cnt[q] >= (uint32_t)kDenseLeafVoxels ? cnt[q] : 0u;
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) dense += (uint32_t)__shfl_xor((int)dense, d);
+        if ((threadIdx.x & 63) == 0 && dense) atomicAdd((unsigned long long*)&hdr->n_voxels_dense, (unsigned long long)dense);
+    }
     uint32_t total;
     uint32_t run = block_exclusive_scan(sum, &total);
 #pragma unroll

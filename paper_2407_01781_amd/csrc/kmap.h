@@ -42,6 +42,7 @@ constexpr int kMaxHalo = 1024;              // distinct halo rows a tile may de-
 constexpr uint16_t kNoRow = 0xFFFF;
 constexpr int32_t kTileDirect = 1;
 constexpr int32_t kTileLdsOffsets = 2;       // id blocks hold LDS byte offsets instead of row ids
+constexpr int32_t kTilePartial = 4;          // some outputs of the tile are left to another kernel (permutation entry 0xFFFF): never stored
 
 // LDS row layout of the convolution (shared with the builder, which pre-computes offsets):
 // rows of kCinChunk bf16/fp16 values (64 bytes); the 16-byte piece q of row r sits at
@@ -88,6 +89,12 @@ struct fx_kmap {
     int32_t* d_nbmap = nullptr;             // dense [n_out, K3]; only when the map is not tiled
     fx_kmap* inverse = nullptr;             // 3x3x3 stride 2: the inverse as a tiled map (produced rows = this map's inputs); built on demand
     bool is_inverse = false;
+    // Per-leaf dispatch (Sec. 6 names it as future work; Sec. 3.5's scenarios are its regimes): the same map with the
+    // outputs of locally dense leaves left out, and the list of those leaves for the leaf-window kernel.  Built on
+    // the first convolution that splits the grid; `mixed` owns the list.
+    fx_kmap* mixed = nullptr;
+    int32_t* d_dense_leaves = nullptr;      // [n_leaf] leaf ids with at least kDenseLeafVoxels voxels (first *d_n_dense entries)
+    int32_t* d_n_dense = nullptr;
     // tiled form
     int64_t n_tiles = 0;
     fx::TileHeader* d_tile_hdr = nullptr;   // [n_tiles]
@@ -116,7 +123,10 @@ inline bool map_shares_rows(const fx_kmap* km) {
 fx_status kmap_ensure_dense(fx_kmap* km, hipStream_t st);
 // the inverse of a 3x3x3 stride-2 map in tiled form (km->inverse), built on first use (not thread-safe)
 fx_status kmap_ensure_inverse(fx_kmap* km, hipStream_t st);
-fx_status build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool inverse, hipStream_t st, fx_kmap** out);
+fx_status build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool inverse, hipStream_t st, fx_kmap** out, int dense_min = 0);
+// the submanifold 3x3x3 map without the outputs of locally dense leaves + the list of those leaves (km->mixed),
+// built on first use (not thread-safe)
+fx_status kmap_ensure_mixed(fx_kmap* km, hipStream_t st);
 // host copies of the map's statistics (pairs per offset, tiling figures); synchronises the build stream once
 fx_status kmap_fetch_stats(fx_kmap* km);
 }

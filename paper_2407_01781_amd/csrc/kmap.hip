@@ -96,7 +96,8 @@ __device__ __forceinline__ int lookup_entry(const NbLeafLds& lds, int oi, int oj
 // the coarse grid.  A fine leaf at origin 8t touches coarse coordinates 4t-1 .. 4t+4: two leaves per axis.
 template <int K, bool INV = false>
 __global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int64_t n_out, int32_t* __restrict__ nbr,
-                                 int32_t* __restrict__ tile_first_leaf) {
+                                 int32_t* __restrict__ tile_first_leaf, int dense_min, int32_t* __restrict__ dense_leaves,
+                                 int32_t* __restrict__ n_dense) {
     constexpr int D0 = delta_min(K);
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (int64_t)tout.n_leaf * 27) return;
@@ -105,6 +106,8 @@ __global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int64_
     if (slot == 0) {
         const int64_t begin = lf->offset, end = f + 1 < tout.n_leaf ? tout.leaf[f + 1].offset : n_out;
         for (int64_t t = (begin + kTileT - 1) / kTileT; t * kTileT < end; ++t) tile_first_leaf[t] = f;
+        // per-leaf dispatch: the locally dense leaves are listed for the leaf-window kernel
+        if (dense_min > 0 && (int)(end - begin) >= dense_min) dense_leaves[atomicAdd(n_dense, 1)] = f;
     }
     const int oi = lf->origin[0], oj = lf->origin[1], ok = lf->origin[2];
     const int bi = INV ? ((oi - 1) >> 1) >> 3 : (stride * oi + D0) >> 3, bj = INV ? ((oj - 1) >> 1) >> 3 : (stride * oj + D0) >> 3,
@@ -242,7 +245,7 @@ struct PackLds {
     uint32_t wave_mask[kTileWaves];
     uint32_t wave_block0[kTileWaves];
     uint32_t wave_sums[kPackWaves];
-    int32_t n_halo, n_blocks, n_pair_blocks, overflow, n_rec;
+    int32_t n_halo, n_blocks, n_pair_blocks, overflow, n_rec, any_left_out;
 };
 static_assert(sizeof(PackLds) <= 40 * 1024, "four tile builders per compute unit");
 static_assert(sizeof(uint16_t) * kHaloHashSlots <= sizeof(uint64_t) * kMaxRecs * 8, "slot_rank lives in rec_mask");
@@ -410,7 +413,7 @@ __global__ void __launch_bounds__(kPackThreads, 8)
 k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict__ leaf_nbr,
               const int32_t* __restrict__ tile_first_leaf, int64_t n_out, TileHeader* __restrict__ tile_hdr,
               uint16_t* __restrict__ tile_perm, int32_t* __restrict__ tile_rows, int row_stride,
-              uint16_t* __restrict__ tile_blocks, int block_stride) {
+              uint16_t* __restrict__ tile_blocks, int block_stride, int dense_min) {
     constexpr int K3 = K * K * K;
     static_assert(K3 <= kMaxK3Tiled, "tiled path supports up to 27 offsets");
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -429,7 +432,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     const int f_hi = (tile + 1) * kTileT < n_out ? tile_first_leaf[tile + 1] : tout.n_leaf - 1;
     const int n_leaves = min(f_hi + 1 - f_lo, kTileT);
     static_assert(sizeof(L.u.stage.leaf_off) / sizeof(int32_t) >= kTileT, "one entry per possible leaf of a tile");
-    if (tid == 0) { L.n_halo = 0; L.n_blocks = 0; L.n_pair_blocks = 0; L.overflow = 0; L.n_rec = 0; }
+    if (tid == 0) { L.n_halo = 0; L.n_blocks = 0; L.n_pair_blocks = 0; L.overflow = 0; L.n_rec = 0; L.any_left_out = 0; }
     if (tid < kTileWaves) L.wave_mask[tid] = 0;
     for (int e = tid; e < kRecHashSlots; e += kPackThreads) { L.u.stage.rec_hash[e] = -1; L.u.stage.slot_rec[e] = 0xFFFF; }
     if (tid < 8) { L.rec_mask[kMaxRecs * 8 + tid] = 0; L.rec_base[kMaxRecs * 8 + tid] = 0; }
@@ -557,6 +560,13 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
                 }
             }
         }
+        // per-leaf dispatch (dense_min > 0): the outputs of a locally dense leaf are another kernel's; here they
+        // have no taps and are never stored
+        if (dense_min > 0 && tid < n_valid) {
+            const int lo = (int)(vox & 511u);
+            const int64_t end = f_lo + lo + 1 < tout.n_leaf ? tout.leaf[f_lo + lo + 1].offset : n_out;
+            if ((int)(end - tout.leaf[f_lo + lo].offset) >= dense_min) { mask = 0; vox |= 1u << 21; L.any_left_out = 1; }
+        }
         L.vox[tid] = vox;
         L.slot_mask[tid] = mask;
     }
@@ -600,7 +610,7 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
     const int my_g = (int)L.group_dst[tid / kGroup];                      // final block of this thread's column
     const int cw = tile_wave_of(my_g), cgi = tile_slot_of(my_g), cn = tid % kGroup;
     if (cn == 0) tile_hdr[tile].group_mask[my_g] = L.group_mask[tid / kGroup];
-    tile_perm[tile * kTileT + my_g * kGroup + cn] = (uint16_t)my_slot;
+    tile_perm[tile * kTileT + my_g * kGroup + cn] = ((my_vox >> 21) & 1u) ? (uint16_t)0xFFFF : (uint16_t)my_slot;
     if (tid < kGroupsPerTile) {               // the union over the blocks of every convolution wave (cleared at the top)
         atomicOr(&L.wave_mask[tile_wave_of((int)L.group_dst[tid])], L.group_mask[tid]);
         uint32_t pairs = (uint32_t)__popc(L.group_mask[tid]);
@@ -730,8 +740,10 @@ k_build_tiles(TreeView tin, TreeView tout, int stride, const int32_t* __restrict
         int run = 0;
 #pragma unroll
         for (int w = 0; w < kTileWaves; ++w) { H->wave_mask[w] = L.wave_mask[w]; H->wave_block0[w] = (uint32_t)run; run += __popc(L.wave_mask[w]); }
-        H->win_lo = direct ? 0 : win_lo; H->win_n = direct ? 0 : win_n; H->n_list = (int32_t)n_list;
-        H->n_blocks = run; H->n_out = n_valid; H->flags = direct ? kTileDirect : (lds_codes ? kTileLdsOffsets : 0);
+        const bool empty = L.n_pair_blocks == 0;      // nothing to multiply (all outputs left to another kernel): no rows staged
+        H->win_lo = direct ? 0 : win_lo; H->win_n = (direct || empty) ? 0 : win_n; H->n_list = (int32_t)n_list;
+        H->n_blocks = run; H->n_out = n_valid;
+        H->flags = (direct ? kTileDirect : (lds_codes ? kTileLdsOffsets : 0)) | (L.any_left_out ? kTilePartial : 0);
         H->n_pair_blocks = L.n_pair_blocks; H->pad = 0;
     }
 
@@ -905,6 +917,7 @@ extern "C" void fx_kmap_destroy(fx_kmap* km) {
     if (km->d_alloc) dev_free(km->d_alloc, km->stream);
     if (km->d_nbmap) dev_free(km->d_nbmap, km->stream);
     if (km->inverse) fx_kmap_destroy(km->inverse);
+    if (km->mixed) fx_kmap_destroy(km->mixed);
     if (km->gin) fx_grid_destroy(km->gin);
     if (km->gout) fx_grid_destroy(km->gout);
     free(km->h_pairs);
@@ -947,7 +960,7 @@ extern "C" fx_status fx_build_kernel_map_onto(fx_grid* g_in, fx_grid* g_out, int
 
 // The map from the voxels of `gout` (the rows that are produced) to the voxels of `g_in` (the rows that are
 // looked up).  Takes over the caller's reference to gout and retains g_in.  inverse: see k_leaf_neighbors.
-fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool inverse, hipStream_t st, fx_kmap** out) {
+fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool inverse, hipStream_t st, fx_kmap** out, int dense_min) {
     fx_kmap* km = new (std::nothrow) fx_kmap();
     if (!km) { fx_grid_destroy(gout); set_error("host allocation failed"); return FX_ENOMEM; }
     km->stream = st; km->gin = g_in; fx_grid_retain(g_in); km->gout = gout;
@@ -970,6 +983,7 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
     const size_t o_tb = take(tiled ? sizeof(uint16_t) * kIdBlockElems * (size_t)km->block_stride * nt : 0);
     const size_t o_ln = take(tiled ? sizeof(int32_t) * 27 * (size_t)std::max(gout->hdr.n_leaf, 1) : 0);
     const size_t o_tf = take(tiled ? sizeof(int32_t) * (nt + 1) : 0);
+    const size_t o_dl = take(dense_min > 0 ? sizeof(int32_t) * ((size_t)std::max(gout->hdr.n_leaf, 1) + 1) : 0);
     fx_status rc = dev_alloc(&km->d_alloc, off, st);
     if (rc != FX_OK) { fx_kmap_destroy(km); return rc; }
     char* p = (char*)km->d_alloc;
@@ -980,8 +994,12 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
     km->d_tile_blocks = (uint16_t*)(p + o_tb);
     int32_t* d_leaf_nbr = (int32_t*)(p + o_ln);
     int32_t* d_tile_first = (int32_t*)(p + o_tf);
+    int32_t* d_n_dense = dense_min > 0 ? (int32_t*)(p + o_dl) : nullptr;        // the count, then the list
+    int32_t* d_dense = dense_min > 0 ? d_n_dense + 1 : nullptr;
+    km->d_n_dense = d_n_dense; km->d_dense_leaves = d_dense;
 
     hipError_t e = hipSuccess;
+    if (d_n_dense) { k_fill_i32<<<1, 64, 0, st>>>(d_n_dense, 1, 0); e = hipGetLastError(); }
     if (e == hipSuccess && km->n_tiles > 0) {
         const size_t lds = sizeof(PackLds);
         const unsigned ntl = (unsigned)km->n_tiles;
@@ -990,10 +1008,10 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
             ProfScope ps(kProfLeafNeighbors, st);
             const int64_t ne = (int64_t)gout->hdr.n_leaf * 27;
             const unsigned nbk = (unsigned)((ne + 255) / 256);
-            if (K == 1) k_leaf_neighbors<1><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
-            else if (K == 2) k_leaf_neighbors<2><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
-            else if (inverse) k_leaf_neighbors<3, true><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
-            else k_leaf_neighbors<3><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first);
+            if (K == 1) k_leaf_neighbors<1><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, dense_min, d_dense, d_n_dense);
+            else if (K == 2) k_leaf_neighbors<2><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, dense_min, d_dense, d_n_dense);
+            else if (inverse) k_leaf_neighbors<3, true><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, dense_min, d_dense, d_n_dense);
+            else k_leaf_neighbors<3><<<nbk, 256, 0, st>>>(tin, tout, stride, km->n_out, d_leaf_nbr, d_tile_first, dense_min, d_dense, d_n_dense);
         }
         ProfScope ps(kProfBuildTiles, st);
 #define FX_TILES(KV, SUBMV...)                                                                                 \
@@ -1005,7 +1023,8 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
                                                                      km->n_out,                                \
                                                                      km->d_tile_hdr, km->d_tile_perm,          \
                                                                      km->d_tile_rows, km->row_stride,          \
-                                                                     km->d_tile_blocks, km->block_stride);     \
+                                                                     km->d_tile_blocks, km->block_stride,      \
+                                                                     dense_min);                               \
     } while (0)
         const bool same_grid = g_in == gout;      // a stride-1 map onto another grid has no window of its own rows
         if (K == 1 && same_grid) FX_TILES(1, true);
@@ -1045,6 +1064,16 @@ fx_status fx::kmap_ensure_inverse(fx_kmap* km, hipStream_t st) {
     if (!(strided3 || onto) || km->is_inverse) { set_error("no inverse map for this (kernel, stride)"); return FX_EUNSUPPORTED; }
     fx_grid_retain(km->gin);                  // build_map takes over one reference to the grid of the produced rows
     return build_map(km->gout, km->gin, km->K, km->stride, strided3, st, &km->inverse);
+}
+
+fx_status fx::kmap_ensure_mixed(fx_kmap* km, hipStream_t st) {
+    if (km->mixed) return FX_OK;
+    if (!(km->K == 3 && km->stride == 1 && km->gin == km->gout) || km->is_inverse) {
+        set_error("per-leaf dispatch serves the 3x3x3 submanifold map only");
+        return FX_EUNSUPPORTED;
+    }
+    fx_grid_retain(km->gout);                  // build_map takes over one reference to the grid of the produced rows
+    return build_map(km->gin, km->gout, 3, 1, false, st, &km->mixed, kDenseLeafVoxels);
 }
 
 fx_status fx::kmap_fetch_stats(fx_kmap* km) {

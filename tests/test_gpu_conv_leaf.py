@@ -213,7 +213,9 @@ def test_kernel_map_entry_points_take_the_leaf_kernels_on_dense_grids(switch, ex
     torch.cuda.synchronize()
     slots = fx.profile_read()
     fx.profile_enable(False)
-    assert ("k_conv_leaf" in slots) == expect_leaf and ("k_conv_mfma" in slots) == (not expect_leaf)
+    assert ("k_conv_leaf" in slots) == expect_leaf
+    if switch is not None:          # left alone, the block's partly filled border leaves go to the tile kernel (per-leaf dispatch)
+        assert ("k_conv_mfma" in slots) == (not expect_leaf)
     H.conv_tolerance_check(y.float().cpu().numpy(), O.conv(og, og, 3, 1, feat, wt), "bf16", 27, 64)
     H.conv_tolerance_check(gx.float().cpu().numpy(), O.conv_bwd_data(og, og, 3, 1, gy, wt), "bf16", 27, 64)
 

@@ -168,6 +168,33 @@ def volumetric_bodies(seed: int, extent: int = 192, n_bodies: int = 7, origin: i
     return (np.argwhere(m) + origin).astype(np.int32)
 
 
+def mixed_scene(seed: int, extent_xy: int = 768, n_rings: int = 24, n_boxes: int = 12, n_balls: int = 4,
+                n_shells: int = 4) -> np.ndarray:
+    """One grid that mixes the three sparsity classes of Sec. 4.1.3: LiDAR-like ground rings and hollow boxes
+    (leaf occupancy of a few per cent), thin spherical shells (one voxel thick) and solid balls (full leaves) --
+    the input per-leaf dispatch is for.  Everything lies in extent_xy x extent_xy x 96."""
+    rng = np.random.default_rng(seed)
+    parts = [lidar_like(seed + 1, extent_xy=extent_xy, n_rings=n_rings, n_boxes=n_boxes)]
+    zext = 96
+    a = np.arange(zext, dtype=np.float64) + 0.5
+    for b in range(n_balls + n_shells):
+        r = float(rng.uniform(18.0, 40.0))
+        cx, cy = rng.uniform(r + 1, extent_xy - r - 1, size=2)
+        cz = float(rng.uniform(r * 0.3, zext - 1))
+        lo_x, lo_y = int(cx - r - 1), int(cy - r - 1)
+        n = int(2 * r + 3)
+        ax, ay = np.arange(lo_x, lo_x + n) + 0.5, np.arange(lo_y, lo_y + n) + 0.5
+        d2 = ((ax - cx) ** 2)[:, None, None] + ((ay - cy) ** 2)[None, :, None] + ((a - cz) ** 2)[None, None, :]
+        m = d2 <= r * r
+        if b >= n_balls:
+            m &= d2 >= (r - 1.0) ** 2
+        v = np.argwhere(m)
+        v[:, 0] += lo_x
+        v[:, 1] += lo_y
+        parts.append(v.astype(np.int32))
+    return _unique_rows(np.concatenate(parts, axis=0))
+
+
 def gaussian_points(seed: int, n: int, sigma: float = 64.0) -> np.ndarray:
     """Integer coordinates of points drawn from an isotropic normal distribution.
 
@@ -328,6 +355,12 @@ def workload(name: str) -> Workload:
         a = np.arange(-48, 48, dtype=np.int32)
         blk = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3)
         return Workload(name, [blk], 3, 1, 64, 64, "bf16", 6400, 6401)
+    # ---- one grid mixing solid bodies, thin shells and LiDAR-like rings: the input of per-leaf dispatch ----
+    if name == "mixed1m":
+        return Workload(name, [mixed_scene(7100)], 3, 1, 64, 64, "bf16", 7200, 7101)
+    if name == "mixed_small":
+        return Workload(name, [mixed_scene(7101, extent_xy=192, n_rings=8, n_boxes=4, n_balls=2, n_shells=2)], 3, 1, 64, 64,
+                        "bf16", 7300, 7102)
     if name == "volume_small":
         return Workload(name, [volumetric_bodies(6001 + g, extent=40, n_bodies=3, origin=-13 * g) for g in range(2)],
                         3, 1, 8, 16, "f32", 6200, 6201)
