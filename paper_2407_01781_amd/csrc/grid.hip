@@ -890,7 +890,9 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
 
     {
         ProfScope ps(kProfMemset, st);
-        FX_TRY_OR_FAIL(hipMemsetAsync(g->buf, 0, g->buf_bytes, st));
+        // header, bases, root table and the child masks start at zero; the leaf records (most of the buffer) do not
+        // need to: every field of every leaf that exists is written by the build
+        FX_TRY_OR_FAIL(hipMemsetAsync(g->buf, 0, (size_t)((char*)g->d_leaf - (char*)g->buf), st));
         // the partitioned path writes every mask it lists and clears the tile table in its first kernel
         if (!partition) FX_TRY_OR_FAIL(hipMemsetAsync(scratch, 0, clear_bytes, st));
     }
