@@ -110,20 +110,28 @@ def committed_traffic(kernel, workload):
 
 
 def gpu_clocks():
-    """Current clocks / power state as rocm-smi prints them, when it is there and readable."""
-    import shutil
-    import subprocess
-    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
-    try:
-        out = subprocess.run([exe, "--showclocks", "--showperflevel", "--showpower", "--json"], capture_output=True, text=True,
-                             timeout=20)
-        if out.returncode != 0:
-            return None
-        card = next(iter(json.loads(out.stdout).values()))
-        keep = {k: v for k, v in card.items() if any(t in k.lower() for t in ("sclk", "mclk", "fclk", "performance", "power"))}
-        return keep or None
-    except Exception:
-        return None
+    """Current clock levels / power of the first GPU as the driver's sysfs files show them, when they are readable
+    (plain file reads: no child process is started from a process that holds the GPU)."""
+    import glob
+    out = {}
+    for card in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+        try:
+            for key, name in (("sclk", "pp_dpm_sclk"), ("mclk", "pp_dpm_mclk"), ("fclk", "pp_dpm_fclk")):
+                path = os.path.join(card, name)
+                if os.path.exists(path):
+                    cur = [l.split(":", 1)[1].replace("*", "").strip() for l in open(path) if "*" in l]
+                    if cur:
+                        out[key] = cur[0]
+            perf = os.path.join(card, "power_dpm_force_performance_level")
+            if os.path.exists(perf):
+                out["performance_level"] = open(perf).read().strip()
+            for hw in glob.glob(os.path.join(card, "hwmon", "hwmon*", "power1_average")):
+                out["power_W"] = int(open(hw).read().strip()) / 1e6
+        except OSError:
+            continue
+        if out:
+            break
+    return out or None
 
 
 def main():
