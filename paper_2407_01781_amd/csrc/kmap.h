@@ -89,7 +89,7 @@ struct fx_kmap {
     int32_t* d_nbmap = nullptr;             // dense [n_out, K3]; only when the map is not tiled
     fx_kmap* inverse = nullptr;             // 3x3x3 stride 2: the inverse as a tiled map (produced rows = this map's inputs); built on demand
     bool is_inverse = false;
-    // Per-leaf dispatch (Sec. 6 names it as future work; Sec. 3.5's scenarios are its regimes): the same map with the
+    // Per-leaf dispatch (Sec. 5 names it as future work; Sec. 3.5's scenarios are its regimes): the same map with the
     // outputs of locally dense leaves left out, and the list of those leaves for the leaf-window kernel.  Built on
     // the first convolution that splits the grid; `mixed` owns the list.
     fx_kmap* mixed = nullptr;
