@@ -84,7 +84,7 @@ struct GridHeader {
     int32_t n_upper;
     int32_t n_lower;
     int32_t n_leaf;
-    int32_t overflow;     // bit0: upper capacity, bit1: lower, bit2: leaf, bit3: tile limit, bit4: voxel count, bit5: leaf table full, bit6: a bucket's LDS table full
+    int32_t overflow;     // bit0: upper capacity, bit1: lower, bit2: leaf, bit3: tile limit, bit4: voxel count, bit5: leaf table full, bit6: a bucket's LDS table full, bit7: a scan's bounded wait expired
     int32_t n_leaf_raw;   // distinct leaves found by the voxel pass (may exceed capacity)
     int32_t pad[2];
     int64_t n_voxels;

@@ -17,6 +17,7 @@
 
 #include <algorithm>
 #include <new>
+#include <vector>
 
 namespace fx {
 
@@ -34,8 +35,17 @@ struct GridPtrs {
     int32_t cap_upper, cap_lower, cap_leaf, B;
 };
 
-// grid that owns row r (joffsets sorted, non-overlapping), or -1
-__device__ __forceinline__ int find_batch(const int64_t* __restrict__ joff, int B, int64_t r) {
+// Row ranges of the grids of a batch, as the build's kernels take them: a single grid travels in the kernel
+// arguments (no upload, no dependent load per row), more grids in a device array of (begin, end) pairs.
+struct BatchRanges {
+    const int64_t* d;
+    int64_t begin0, end0;
+};
+
+// grid that owns row r (ranges sorted, non-overlapping), or -1
+__device__ __forceinline__ int find_batch(const BatchRanges& J, int B, int64_t r) {
+    if (B == 1) return (r >= J.begin0 && r < J.end0) ? 0 : -1;
+    const int64_t* __restrict__ joff = J.d;
     int lo = 0, hi = B;  // last b with start_b <= r
     while (lo < hi) {
         int mid = (lo + hi) >> 1;
@@ -112,7 +122,7 @@ __device__ __forceinline__ uint32_t leaf_hash(int b, int li, int lj, int lk) {
 
 // ---- direct path
 __global__ void __launch_bounds__(256)
-k_voxels_to_leaves(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff, int B,
+k_voxels_to_leaves(const int32_t* __restrict__ ijk, int64_t n_rows, const BatchRanges joff, int B,
                    int32_t* __restrict__ slots, uint32_t slot_mask, LeafList L, GridHeader* hdr) {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int b = r < n_rows ? find_batch(joff, B, r) : -1;
@@ -170,7 +180,7 @@ constexpr int kBucketSlots = 1024;                               // LDS leaf tab
 struct PartRow { int i, j, k, b; uint32_t bucket; };
 
 __device__ __forceinline__ PartRow load_part_row(const int32_t* __restrict__ ijk, int64_t n_rows,
-                                                 const int64_t* __restrict__ joff, int B, int64_t r, uint32_t bucket_mask) {
+                                                 const BatchRanges& joff, int B, int64_t r, uint32_t bucket_mask) {
     PartRow p;
     p.b = r < n_rows ? find_batch(joff, B, r) : -1;
     p.i = p.j = p.k = 0; p.bucket = 0;
@@ -182,12 +192,22 @@ __device__ __forceinline__ PartRow load_part_row(const int32_t* __restrict__ ijk
 }
 
 // rows per (bucket, workgroup): hist[bucket * n_wg + wg]
+// What the first kernel of a build clears besides its own work: the head of the grid buffer (header, bases,
+// root table, child masks) and the head of the scratch buffer (scan tickets and block sums, root-tile table).
+// Nothing reads or updates either before the next launch.
+struct ClearRanges {
+    uint4* p[2];
+    uint32_t n16[2];   // 16-byte units
+};
+
 __global__ void __launch_bounds__(kPartThreads)
-k_bucket_count(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff, int B,
-               uint32_t bucket_mask, uint32_t* __restrict__ hist, int32_t* __restrict__ tile_slots) {
+k_bucket_count(const int32_t* __restrict__ ijk, int64_t n_rows, const BatchRanges joff, int B,
+               uint32_t bucket_mask, uint32_t* __restrict__ hist, ClearRanges clr) {
     __shared__ uint32_t cnt[kMaxBuckets];
-    // first launch of the build: also clears the root-tile table (used three launches later)
-    for (int e = blockIdx.x * kPartThreads + threadIdx.x; e < kTileHashSlots; e += gridDim.x * kPartThreads) tile_slots[e] = 0;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+        for (uint32_t e = blockIdx.x * kPartThreads + threadIdx.x; e < clr.n16[c]; e += gridDim.x * kPartThreads)
+            clr.p[c][e] = make_uint4(0u, 0u, 0u, 0u);
     for (uint32_t e = threadIdx.x; e <= bucket_mask; e += kPartThreads) cnt[e] = 0;
     __syncthreads();
     const int64_t r0 = (int64_t)blockIdx.x * kPartChunk + threadIdx.x;
@@ -225,7 +245,7 @@ __global__ void __launch_bounds__(256) k_bucket_scan(uint32_t* __restrict__ hist
 // scatter the rows into their buckets as (i, j, k, grid) records; the records of one workgroup
 // are ordered by bucket in LDS first so that each bucket receives one contiguous run
 __global__ void __launch_bounds__(kPartThreads)
-k_bucket_scatter(const int32_t* __restrict__ ijk, int64_t n_rows, const int64_t* __restrict__ joff, int B,
+k_bucket_scatter(const int32_t* __restrict__ ijk, int64_t n_rows, const BatchRanges joff, int B,
                  uint32_t bucket_mask, const uint32_t* __restrict__ hist, const uint32_t* __restrict__ totals,
                  uint32_t* __restrict__ bucket_start, int4* __restrict__ records) {
     extern __shared__ __align__(16) unsigned char part_lds[];
@@ -490,6 +510,39 @@ __global__ void k_insert(LeafList L, GridPtrs g) {
     insert_item<LEVEL>(L, g, (int)idx, key);
 }
 
+// LEVEL 0 for all leaves: thousands of leaves share every lower node, and atomics on one address queue up at
+// memory one after the other.  A workgroup therefore collects the bits of its 1024 leaves in LDS copies of the
+// first few upper nodes' masks and sends each touched word to memory once; leaves of further upper nodes (rare)
+// update memory directly.
+constexpr int kInsertUpperThreads = 1024;
+constexpr int kAggUpper = 4;
+__global__ void __launch_bounds__(kInsertUpperThreads) k_insert_upper(LeafList L, GridPtrs g) {
+    __shared__ unsigned long long bits[kAggUpper * kUpperWords];
+    if (g.hdr->overflow) return;
+    const int n_upper = g.hdr->n_upper;
+    const int n_agg_words = (n_upper < kAggUpper ? n_upper : kAggUpper) * kUpperWords;
+    for (int e = threadIdx.x; e < n_agg_words; e += kInsertUpperThreads) bits[e] = 0ull;
+    __syncthreads();
+    const int64_t idx = (int64_t)blockIdx.x * kInsertUpperThreads + threadIdx.x;
+    int4 key;
+    if (leaf_at(L, g.hdr, idx, &key)) {
+        const int i = key.x << 3, j = key.y << 3, k = key.z << 3;
+        const int u = find_upper(g.root_key, g.root_batch, n_upper, key.w, tile_key(i, j, k));
+        if (u >= 0) {
+            const int off = upper_off(i, j, k);
+            const int word = u * kUpperWords + (off >> 6);
+            const unsigned long long bit = 1ull << (off & 63);
+            if (word < n_agg_words) atomicOr(&bits[word], bit);
+            else atomicOr((unsigned long long*)g.upper_mask + word, bit);
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < n_agg_words; e += kInsertUpperThreads) {
+        const unsigned long long v = bits[e];
+        if (v) atomicOr((unsigned long long*)g.upper_mask + e, v);
+    }
+}
+
 // ---------------------------------------------------------------------------------- popcount scans
 // which level's masks a scan runs over
 struct LevelScan {
@@ -502,14 +555,61 @@ struct LevelScan {
     int32_t overflow_bit;
 };
 
-// phase A: block-local exclusive popcount prefix per word, block totals
-__global__ void __launch_bounds__(kScanThreads) k_scan_words_local(LevelScan s, GridHeader* hdr,
-                                                                    uint32_t* __restrict__ block_sums,
-                                                                    int single) {
-    if (hdr->overflow) return;
+// Single-pass scans over several workgroups.  Each scan has a ticket counter and one word per workgroup (both
+// start at zero).  A workgroup takes the next chunk in the order in which workgroups start running, publishes its
+// chunk's total as total + 1 in its word with one device-scope store -- the word carries the value, so no fence is
+// needed -- and then adds up the words of the chunks before it, waiting for those not yet written.  It only ever
+// waits for workgroups that started before it and that publish before they wait themselves, so every wait ends;
+// the wait is bounded all the same and an expired one is reported through the overflow word (bit 7).
+struct ScanSync {
+    uint32_t* ticket;
+    uint32_t* sums;
+};
+constexpr int kScanSpinLimit = 1 << 20;
+
+// the workgroup's chunk, or -1 when an earlier step of the build has failed (one thread decides for all)
+__device__ __forceinline__ int ordered_chunk(uint32_t* ticket, const GridHeader* hdr) {
+    __shared__ int chunk;
+    if (threadIdx.x == 0) chunk = hdr->overflow ? -1 : (int)atomicAdd(ticket, 1u);
+    __syncthreads();
+    return chunk;
+}
+
+// publishes `total` as the sum of chunk `mine`; returns the sum of the chunks before it (to every thread)
+__device__ __forceinline__ uint64_t publish_and_sum_before(const ScanSync& y, int mine, uint32_t total, GridHeader* hdr) {
+    __shared__ unsigned long long acc;
+    if (threadIdx.x == 0) {
+        acc = 0ull;
+        __hip_atomic_store(&y.sums[mine], total + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    unsigned long long sb = 0;
+    for (int i = threadIdx.x; i < mine; i += blockDim.x) {
+        uint32_t v = 0;
+        for (int spin = 0; spin < kScanSpinLimit; ++spin) {
+            v = __hip_atomic_load(&y.sums[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (v) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+        if (!v) { atomicOr(&hdr->overflow, 128); v = 1u; }
+        sb += v - 1u;
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) sb += (unsigned long long)__shfl_xor((long long)sb, d);
+    if ((threadIdx.x & 63) == 0 && sb) atomicAdd(&acc, sb);
+    __syncthreads();
+    const uint64_t before = acc;
+    __syncthreads();
+    return before;
+}
+
+// exclusive popcount prefix per mask word over all nodes of a level; the last chunk writes the number of children
+__global__ void __launch_bounds__(kScanThreads) k_scan_words(LevelScan s, GridHeader* hdr, ScanSync y) {
+    const int chunk = ordered_chunk(y.ticket, hdr);
+    if (chunk < 0) return;
     const int64_t n_words = (int64_t)(*s.n_nodes) * s.words_per_node;
-    const int64_t base = (int64_t)blockIdx.x * kWordChunk;
-    if (base >= n_words && !(single && blockIdx.x == 0)) return;
+    const int64_t base = (int64_t)chunk * kWordChunk;
+    if (base >= n_words && chunk != 0) return;
     const int64_t w0 = base + (int64_t)threadIdx.x * kWordsPerThread;
     uint32_t pc[kWordsPerThread];
     uint32_t sum = 0;
@@ -520,67 +620,18 @@ __global__ void __launch_bounds__(kScanThreads) k_scan_words_local(LevelScan s, 
     }
     uint32_t total;
     uint32_t run = block_exclusive_scan(sum, &total);
+    const uint64_t before = publish_and_sum_before(y, chunk, total, hdr);
+    run += (uint32_t)before;
 #pragma unroll
     for (int q = 0; q < kWordsPerThread; ++q) {
         if (w0 + q < n_words) s.prefix[w0 + q] = run;
         run += pc[q];
     }
-    if (threadIdx.x == 0) {
-        if (single) {
-            *s.n_children = (int32_t)total;
-            if ((int64_t)total > s.child_cap) atomicOr(&hdr->overflow, s.overflow_bit);
-        } else {
-            block_sums[blockIdx.x] = total;
-        }
+    if (threadIdx.x == 0 && base + kWordChunk >= n_words) {
+        const uint64_t all = before + total;
+        *s.n_children = (int32_t)(all < (uint64_t)INT32_MAX ? all : (uint64_t)INT32_MAX);
+        if ((int64_t)all > s.child_cap) atomicOr(&hdr->overflow, s.overflow_bit);
     }
-}
-
-// sums of the first `mine` block totals and of all `n_blocks` of them (every thread gets both)
-__device__ __forceinline__ void block_sums_before(const uint32_t* __restrict__ block_sums, int mine, int n_blocks,
-                                                  uint64_t* before, uint64_t* all) {
-    __shared__ unsigned long long acc[2];
-    if (threadIdx.x < 2) acc[threadIdx.x] = 0ull;
-    __syncthreads();
-    unsigned long long sb = 0, sa = 0;
-    for (int i = threadIdx.x; i < n_blocks; i += blockDim.x) {
-        const uint32_t v = block_sums[i];
-        sa += v;
-        if (i < mine) sb += v;
-    }
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) {
-        sb += (unsigned long long)__shfl_xor((long long)sb, d);
-        sa += (unsigned long long)__shfl_xor((long long)sa, d);
-    }
-    if ((threadIdx.x & 63) == 0) { atomicAdd(&acc[0], sb); atomicAdd(&acc[1], sa); }
-    __syncthreads();
-    *before = acc[0];
-    *all = acc[1];
-    __syncthreads();   // the next call may clear the sums
-}
-
-// phase B: every block adds the totals of the blocks before it; block 0 publishes the grand total
-__global__ void __launch_bounds__(kScanThreads) k_scan_words_apply(LevelScan s, GridHeader* hdr,
-                                                                    const uint32_t* __restrict__ block_sums) {
-    if (hdr->overflow) return;
-    const int64_t n_words = (int64_t)(*s.n_nodes) * s.words_per_node;
-    const int64_t base = (int64_t)blockIdx.x * kWordChunk;
-    if (base >= n_words) return;
-    const int n_blocks = (int)((n_words + kWordChunk - 1) / kWordChunk);
-    uint64_t before, all;
-    block_sums_before(block_sums, (int)blockIdx.x, n_blocks, &before, &all);
-    if (blockIdx.x == 0) {
-        if (threadIdx.x == 0) {
-            *s.n_children = (int32_t)(all < (uint64_t)INT32_MAX ? all : (uint64_t)INT32_MAX);
-            if ((int64_t)all > s.child_cap) atomicOr(&hdr->overflow, s.overflow_bit);
-        }
-        return;
-    }
-    const uint32_t add = (uint32_t)before;
-    const int64_t w0 = base + (int64_t)threadIdx.x * kWordsPerThread;
-#pragma unroll
-    for (int q = 0; q < kWordsPerThread; ++q)
-        if (w0 + q < n_words) s.prefix[w0 + q] += add;
 }
 
 // First voxel index of every grid of the batch (leaves are ordered by grid): the thread that owns
@@ -597,13 +648,13 @@ __device__ __forceinline__ void note_vox_base(const fx_leaf* __restrict__ leaf, 
 
 // Leaf level: mOffset = exclusive scan of the leaves' active-voxel counts; mPrefixSum = the
 // seven 9-bit inclusive word prefixes of Listing 1.
-__global__ void __launch_bounds__(kScanThreads) k_scan_leaves_local(fx_leaf* __restrict__ leaf, GridHeader* hdr,
-                                                                     uint32_t* __restrict__ block_sums, int single,
-                                                                     int64_t* __restrict__ vox_base, int B) {
-    if (hdr->overflow) return;
+__global__ void __launch_bounds__(kScanThreads) k_scan_leaves(fx_leaf* __restrict__ leaf, GridHeader* hdr, ScanSync y,
+                                                               int64_t* __restrict__ vox_base, int B) {
+    const int chunk = ordered_chunk(y.ticket, hdr);
+    if (chunk < 0) return;
     const int64_t n_leaf = hdr->n_leaf;
-    const int64_t base = (int64_t)blockIdx.x * kLeafChunk;
-    if (base >= n_leaf && !(single && blockIdx.x == 0)) return;
+    const int64_t base = (int64_t)chunk * kLeafChunk;
+    if (base >= n_leaf && chunk != 0) return;
     const int64_t l0 = base + (int64_t)threadIdx.x * kLeavesPerThread;
     uint32_t cnt[kLeavesPerThread];
     uint32_t sum = 0;
@@ -632,43 +683,24 @@ __global__ void __launch_bounds__(kScanThreads) k_scan_leaves_local(fx_leaf* __r
         if ((threadIdx.x & 63) == 0 && dense) atomicAdd((unsigned long long*)&hdr->n_voxels_dense, (unsigned long long)dense);
     }
     uint32_t total;
-    uint32_t run = block_exclusive_scan(sum, &total);
+    const uint32_t local = block_exclusive_scan(sum, &total);
+    const uint64_t before = publish_and_sum_before(y, chunk, total, hdr);
+    const bool last = base + kLeafChunk >= n_leaf;
+    const int64_t all = (int64_t)(before + total);      // the grid's voxel count, in the last chunk
+    int64_t run = (int64_t)before + local;
 #pragma unroll
     for (int q = 0; q < kLeavesPerThread; ++q) {
         if (l0 + q < n_leaf) {
-            leaf[l0 + q].offset = (int64_t)run;
-            if (single) note_vox_base(leaf, l0 + q, n_leaf, (int64_t)run, (int64_t)total, vox_base, B);
+            leaf[l0 + q].offset = run;
+            // only the last chunk holds the last leaf, the one reader of the grand total
+            note_vox_base(leaf, l0 + q, n_leaf, run, all, vox_base, B);
         }
         run += cnt[q];
     }
-    if (threadIdx.x == 0) {
-        if (single) hdr->n_voxels = (int64_t)total;
-        else block_sums[blockIdx.x] = total;
+    if (threadIdx.x == 0 && last) {
+        hdr->n_voxels = all;
+        if (all > (int64_t)INT32_MAX) atomicOr(&hdr->overflow, 16);
     }
-}
-
-__global__ void __launch_bounds__(kScanThreads) k_scan_leaves_apply(fx_leaf* __restrict__ leaf, GridHeader* hdr,
-                                                                     const uint32_t* __restrict__ block_sums,
-                                                                     int64_t* __restrict__ vox_base, int B) {
-    if (hdr->overflow) return;
-    const int64_t n_leaf = hdr->n_leaf;
-    const int64_t base = (int64_t)blockIdx.x * kLeafChunk;
-    if (base >= n_leaf) return;
-    const int n_blocks = (int)((n_leaf + kLeafChunk - 1) / kLeafChunk);
-    uint64_t before, all;
-    block_sums_before(block_sums, (int)blockIdx.x, n_blocks, &before, &all);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        hdr->n_voxels = (int64_t)all;
-        if (all > (uint64_t)INT32_MAX) atomicOr(&hdr->overflow, 16);
-    }
-    const int64_t l0 = base + (int64_t)threadIdx.x * kLeavesPerThread;
-#pragma unroll
-    for (int q = 0; q < kLeavesPerThread; ++q)
-        if (l0 + q < n_leaf) {
-            const int64_t off = leaf[l0 + q].offset + (int64_t)before;
-            leaf[l0 + q].offset = off;
-            note_vox_base(leaf, l0 + q, n_leaf, off, (int64_t)all, vox_base, B);
-        }
 }
 
 // The build's one read-back (Sec. 3.3 step 10): counts and per-grid voxel bases, written by the
@@ -809,15 +841,10 @@ static GridPtrs ptrs_of(const fx_grid* g) {
     return q;
 }
 
-static fx_status scan_level(const fx_grid* g, LevelScan s, int cap_nodes, uint32_t* d_block_sums, hipStream_t st) {
+static fx_status scan_level(const fx_grid* g, LevelScan s, int cap_nodes, ScanSync y, hipStream_t st) {
     const int64_t cap_words = (int64_t)cap_nodes * s.words_per_node;
     const int n_blocks = (int)std::max<int64_t>(1, (cap_words + kWordChunk - 1) / kWordChunk);
-    if (n_blocks == 1) {
-        k_scan_words_local<<<1, kScanThreads, 0, st>>>(s, g->d_hdr, d_block_sums, 1);
-    } else {
-        k_scan_words_local<<<n_blocks, kScanThreads, 0, st>>>(s, g->d_hdr, d_block_sums, 0);
-        k_scan_words_apply<<<n_blocks, kScanThreads, 0, st>>>(s, g->d_hdr, d_block_sums);
-    }
+    k_scan_words<<<n_blocks, kScanThreads, 0, st>>>(s, g->d_hdr, y);
     FX_HIP_TRY(hipGetLastError());
     return FX_OK;
 }
@@ -826,7 +853,7 @@ static fx_status scan_level(const fx_grid* g, LevelScan s, int cap_nodes, uint32
 // capacity was too small (the counts found so far are valid up to the overflowing level).
 constexpr int64_t kPartitionMinRows = 65536;   // below this the direct path's few kernels win
 
-static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64_t* d_joff, int32_t B,
+static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const BatchRanges& d_joff, int32_t B,
                                int cap_upper, int cap_lower, int cap_leaf, bool direct, hipStream_t st, fx_grid** out) {
     fx_grid* g = new (std::nothrow) fx_grid();
     if (!g) { set_error("host allocation failed"); return FX_ENOMEM; }
@@ -839,9 +866,10 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     g->h_vox_base = (int64_t*)calloc((size_t)B + 1, sizeof(int64_t));
 
     // Leaf list capacity and the way to it.  Scratch layout:
-    //   cleared:      [leaf masks | tile table | direct path: leaf table slots]
-    //   not cleared:  [leaf keys | mask indices | tile representatives | scan block sums |
-    //                  partitioned path: bucket records, histogram, totals, bucket starts]
+    //   cleared by both paths:    [scan tickets and block words | tile table]
+    //   cleared by the direct one [leaf table slots | leaf masks]
+    //   not cleared:              [leaf keys | mask indices | tile representatives |
+    //                              partitioned path: leaf masks, bucket records, histogram, totals, bucket starts]
     const int64_t max_items = std::max<int64_t>((int64_t)g->cap_lower * kLowerWords / kWordChunk,
                                                 std::max<int64_t>((int64_t)g->cap_upper * kUpperWords / kWordChunk,
                                                                   (int64_t)g->cap_leaf / kLeafChunk)) + 2;
@@ -854,14 +882,15 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     const int n_part_wg = (int)((n_rows + kPartChunk - 1) / kPartChunk);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-    const size_t o_mask = take(sizeof(uint64_t) * 8 * n_masks);
+    const size_t o_sync = take(sizeof(uint32_t) * 3 * (64 + (size_t)max_items));   // three scans: a ticket, then the words
     const size_t o_tslot = take(sizeof(int32_t) * kTileHashSlots);
+    const size_t clear_bytes_head = off;
     const size_t o_slots = take(sizeof(int32_t) * n_slots);
-    const size_t clear_bytes = off;
+    const size_t o_mask = take(sizeof(uint64_t) * 8 * n_masks);
+    const size_t clear_bytes = partition ? clear_bytes_head : off;
     const size_t o_key = take(sizeof(int4) * (size_t)g->cap_leaf);
     const size_t o_midx = take(sizeof(int32_t) * (size_t)g->cap_leaf);
     const size_t o_rep = take(sizeof(int32_t) * kMaxTiles);
-    const size_t o_bsum = take(sizeof(uint32_t) * (size_t)max_items);
     const size_t o_rec = take(partition ? sizeof(int4) * (size_t)n_rows : 0);
     const size_t o_hist = take(partition ? sizeof(uint32_t) * (size_t)n_buckets * n_part_wg : 0);
     const size_t o_tot = take(partition ? sizeof(uint32_t) * n_buckets : 0);
@@ -878,7 +907,10 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     int32_t* d_tile_slots = (int32_t*)(sp + o_tslot);
     int32_t* d_slots = (int32_t*)(sp + o_slots);
     int32_t* d_rep = (int32_t*)(sp + o_rep);
-    uint32_t* d_block_sums = (uint32_t*)(sp + o_bsum);
+    auto scan_sync = [&](int which) {
+        uint32_t* base = (uint32_t*)(sp + o_sync) + (size_t)which * (64 + (size_t)max_items);
+        return ScanSync{base, base + 64};
+    };
     int4* d_records = (int4*)(sp + o_rec);
     uint32_t* d_hist = (uint32_t*)(sp + o_hist);
     uint32_t* d_totals = (uint32_t*)(sp + o_tot);
@@ -888,13 +920,15 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
 #define FX_TRY_OR_FAIL(expr) do { hipError_t _e = (expr); if (_e != hipSuccess) { \
         set_error("%s failed: %s", #expr, hipGetErrorString(_e)); return fail(FX_EDEVICE); } } while (0)
 
-    {
+    // header, bases, root table and the child masks start at zero; the leaf records (most of the buffer) do not
+    // need to: every field of every leaf that exists is written by the build.  The partitioned path clears in its
+    // first kernel, the direct path (small inputs) with two fills.
+    const size_t grid_clear_bytes = (size_t)((char*)g->d_leaf - (char*)g->buf);
+    const bool kernel_clears = partition && n_rows > 0 && B > 0;
+    if (!kernel_clears) {
         ProfScope ps(kProfMemset, st);
-        // header, bases, root table and the child masks start at zero; the leaf records (most of the buffer) do not
-        // need to: every field of every leaf that exists is written by the build
-        FX_TRY_OR_FAIL(hipMemsetAsync(g->buf, 0, (size_t)((char*)g->d_leaf - (char*)g->buf), st));
-        // the partitioned path writes every mask it lists and clears the tile table in its first kernel
-        if (!partition) FX_TRY_OR_FAIL(hipMemsetAsync(scratch, 0, clear_bytes, st));
+        FX_TRY_OR_FAIL(hipMemsetAsync(g->buf, 0, grid_clear_bytes, st));
+        FX_TRY_OR_FAIL(hipMemsetAsync(scratch, 0, clear_bytes, st));
     }
     const GridPtrs q = ptrs_of(g);
     if (n_rows > 0 && B > 0) {
@@ -905,7 +939,10 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
             FX_TRY_OR_FAIL(hipFuncSetAttribute((const void*)k_bucket_scatter, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                (int)lds));
             { ProfScope ps(kProfBucketCount, st);
-              k_bucket_count<<<n_part_wg, kPartThreads, 0, st>>>(d_ijk, n_rows, d_joff, B, bucket_mask, d_hist, d_tile_slots); }
+              ClearRanges clr;
+              clr.p[0] = (uint4*)g->buf; clr.n16[0] = (uint32_t)(grid_clear_bytes / 16);
+              clr.p[1] = (uint4*)scratch; clr.n16[1] = (uint32_t)(clear_bytes / 16);
+              k_bucket_count<<<n_part_wg, kPartThreads, 0, st>>>(d_ijk, n_rows, d_joff, B, bucket_mask, d_hist, clr); }
             { ProfScope ps(kProfBucketScan, st);
               k_bucket_scan<<<(n_buckets * 64 + 255) / 256, 256, 0, st>>>(d_hist, n_part_wg, n_buckets, d_totals); }
             { ProfScope ps(kProfBucketScatter, st);
@@ -920,25 +957,19 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
         }
         { ProfScope ps(kProfFindTiles, st); k_find_tiles<<<nb_leaf, 256, 0, st>>>(L, d_tile_slots, d_rep, g->d_hdr); }
         { ProfScope ps(kProfRankTiles, st); k_rank_tiles<<<kMaxTiles / 256, 256, 0, st>>>(L, d_rep, q); }
-        { ProfScope ps(kProfInsertUpper, st); k_insert<0><<<nb_leaf, 256, 0, st>>>(L, q); }
+        { ProfScope ps(kProfInsertUpper, st);
+          k_insert_upper<<<(unsigned)((g->cap_leaf + kInsertUpperThreads - 1) / kInsertUpperThreads), kInsertUpperThreads, 0, st>>>(L, q); }
         LevelScan su{g->d_upper_mask, g->d_upper_prefix, &g->d_hdr->n_upper, kUpperWords, &g->d_hdr->n_lower,
                      g->cap_lower, 2};
-        { ProfScope ps(kProfScanUpper, st); if (scan_level(g, su, g->cap_upper, d_block_sums, st) != FX_OK) return fail(FX_EDEVICE); }
+        { ProfScope ps(kProfScanUpper, st); if (scan_level(g, su, g->cap_upper, scan_sync(0), st) != FX_OK) return fail(FX_EDEVICE); }
         { ProfScope ps(kProfInsertLower, st); k_insert<1><<<nb_leaf, 256, 0, st>>>(L, q); }
         LevelScan sl{g->d_lower_mask, g->d_lower_prefix, &g->d_hdr->n_lower, kLowerWords, &g->d_hdr->n_leaf,
                      g->cap_leaf, 4};
-        { ProfScope ps(kProfScanLower, st); if (scan_level(g, sl, g->cap_lower, d_block_sums, st) != FX_OK) return fail(FX_EDEVICE); }
+        { ProfScope ps(kProfScanLower, st); if (scan_level(g, sl, g->cap_lower, scan_sync(1), st) != FX_OK) return fail(FX_EDEVICE); }
         { ProfScope ps(kProfInsertLeaf, st); k_insert<2><<<nb_leaf, 256, 0, st>>>(L, q); }
         const int lb = std::max(1, (g->cap_leaf + kLeafChunk - 1) / kLeafChunk);
-        {
-        ProfScope ps(kProfScanLeaf, st);
-        if (lb == 1) {
-            k_scan_leaves_local<<<1, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums, 1, g->d_vox_base, B);
-        } else {
-            k_scan_leaves_local<<<lb, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums, 0, g->d_vox_base, B);
-            k_scan_leaves_apply<<<lb, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, d_block_sums, g->d_vox_base, B);
-        }
-        }
+        { ProfScope ps(kProfScanLeaf, st);
+          k_scan_leaves<<<lb, kScanThreads, 0, st>>>(g->d_leaf, g->d_hdr, scan_sync(2), g->d_vox_base, B); }
         FX_TRY_OR_FAIL(hipGetLastError());
     }
     // one read-back: counts + per-grid ranges (Sec. 3.3 step 10)
@@ -973,8 +1004,8 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const int64
     return FX_OK;
 }
 
-fx_status build_index_grid_device_joff(const int32_t* d_ijk, int64_t n_rows, const int64_t* d_joff, int32_t B,
-                                       hipStream_t st, fx_grid** out) {
+static fx_status build_with_ranges(const int32_t* d_ijk, int64_t n_rows, const BatchRanges& d_joff, int32_t B,
+                                    hipStream_t st, fx_grid** out) {
     // First attempt with capacities that fit typical occupancy; an attempt that overflows has
     // (almost always) counted the nodes of the overflowing level exactly and is repeated with those.
     int cap_upper = B + 8;
@@ -996,6 +1027,11 @@ fx_status build_index_grid_device_joff(const int32_t* d_ijk, int64_t n_rows, con
             set_error("more than 2^31-1 active voxels");
             return FX_ERANGE;
         }
+        if (ov & 128) {
+            fx_grid_destroy(g);
+            set_error("grid build: a workgroup of a scan waited for its predecessors beyond the limit");
+            return FX_EDEVICE;
+        }
         if (ov & 64) direct = true;   // a bucket held more leaves than its LDS table
         if (ov & 1) cap_upper = g->hdr.n_upper;
         if (ov & 2) { cap_upper = g->hdr.n_upper; cap_lower = g->hdr.n_lower; }
@@ -1010,6 +1046,30 @@ fx_status build_index_grid_device_joff(const int32_t* d_ijk, int64_t n_rows, con
     }
     set_error("grid build did not converge");
     return FX_EDEVICE;
+}
+
+// The build from rows already on the device; h_pairs = (begin, end) rows of every grid of the batch, on the host.
+// One grid needs no upload at all; more go through pinned staging into a device array that lives until the build
+// has synchronised the stream.
+fx_status build_index_grid_device(const int32_t* d_ijk, int64_t n_rows, const int64_t* h_pairs, int32_t B,
+                                  hipStream_t st, fx_grid** out) {
+    BatchRanges J{nullptr, 0, 0};
+    int64_t* d_pairs = nullptr;
+    if (B >= 1) { J.begin0 = h_pairs[0]; J.end0 = h_pairs[1]; }
+    if (B > 1) {
+        const size_t jb = sizeof(int64_t) * 2 * (size_t)B;
+        FX_TRY(dev_alloc((void**)&d_pairs, jb, st));
+        void* stage = nullptr;
+        fx_status rc = host_staging(&stage, jb, 1);
+        if (rc != FX_OK) { dev_free(d_pairs, st); return rc; }
+        memcpy(stage, h_pairs, jb);
+        const hipError_t e = hipMemcpyAsync(d_pairs, stage, jb, hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) { dev_free(d_pairs, st); set_error("joffsets upload failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
+        J.d = d_pairs;
+    }
+    const fx_status rc = build_with_ranges(d_ijk, n_rows, J, B, st, out);
+    if (d_pairs) dev_free(d_pairs, st);
+    return rc;
 }
 
 }  // namespace fx
@@ -1034,25 +1094,7 @@ extern "C" fx_status fx_build_index_grid(const int32_t* d_ijk, int64_t n_rows, c
         }
         prev_end = e;
     }
-    hipStream_t st = (hipStream_t)stream;
-    int64_t* d_joff = nullptr;
-    const size_t jb = sizeof(int64_t) * 2 * (size_t)std::max(B, 1);
-    FX_TRY(dev_alloc((void**)&d_joff, jb, st));
-    if (B > 0) {
-        void* stage = nullptr;
-        fx_status rc = host_staging(&stage, jb, 1);
-        if (rc != FX_OK) { dev_free(d_joff, st); return rc; }
-        memcpy(stage, h_joffsets, sizeof(int64_t) * 2 * (size_t)B);
-        // no wait here: the build below synchronises the stream before it returns
-        hipError_t e = hipMemcpyAsync(d_joff, stage, sizeof(int64_t) * 2 * (size_t)B, hipMemcpyHostToDevice, st);
-        if (e != hipSuccess) { dev_free(d_joff, st); set_error("joffsets upload failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
-    }
-    fx_grid* g = nullptr;
-    fx_status rc = build_index_grid_device_joff(d_ijk, n_rows, d_joff, B, st, &g);
-    dev_free(d_joff, st);
-    if (rc != FX_OK) return rc;
-    *out = g;
-    return FX_OK;
+    return build_index_grid_device(d_ijk, n_rows, h_joffsets, B, (hipStream_t)stream, out);
 }
 
 extern "C" fx_status fx_grid_info(const fx_grid* g, int64_t* n_voxels, int32_t* B, int64_t* h_voxel_joffsets,
@@ -1163,33 +1205,29 @@ extern "C" fx_status fx_build_index_grid_from_points(const float* d_xyz, int64_t
     return FX_OK;
 }
 
+// (begin, end) voxel rows of every grid of `g`, multiplied by `rows_per_voxel`: the row ranges of an array
+// derived from the grid's voxels
+static std::vector<int64_t> scaled_voxel_ranges(const fx_grid* g, int64_t rows_per_voxel) {
+    std::vector<int64_t> r(2 * (size_t)std::max(g->B, 1), 0);
+    for (int b = 0; b < g->B; ++b) { r[2 * b] = rows_per_voxel * g->h_vox_base[b]; r[2 * b + 1] = rows_per_voxel * g->h_vox_base[b + 1]; }
+    return r;
+}
+
 extern "C" fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** out) {
     if (!g || !out) { set_error("fx_grid_coarsen2: null pointer"); return FX_EINVAL; }
     hipStream_t st = (hipStream_t)stream;
     const int64_t n = g->hdr.n_voxels;
     int32_t* d_c = nullptr;
-    int64_t* d_joff = nullptr;
     FX_TRY(dev_alloc((void**)&d_c, sizeof(int32_t) * 3 * (size_t)std::max<int64_t>(n, 1), st));
-    fx_status rc = dev_alloc((void**)&d_joff, sizeof(int64_t) * 2 * (size_t)std::max(g->B, 1), st);
-    if (rc != FX_OK) { dev_free(d_c, st); return rc; }
-    auto cleanup = [&]() { dev_free(d_c, st); dev_free(d_joff, st); };
     if (g->hdr.n_leaf > 0) {
         const int64_t threads = (int64_t)g->hdr.n_leaf * 64;
         ProfScope ps(kProfGridIjk, st);
         k_grid_ijk<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(g->view(), d_c, nullptr, 1);
     }
-    if (g->B > 0) {
-        void* stage = nullptr;
-        rc = host_staging(&stage, sizeof(int64_t) * 2 * (size_t)g->B, 1);
-        if (rc != FX_OK) { cleanup(); return rc; }
-        int64_t* hj = (int64_t*)stage;
-        for (int b = 0; b < g->B; ++b) { hj[2 * b] = g->h_vox_base[b]; hj[2 * b + 1] = g->h_vox_base[b + 1]; }
-        hipError_t e = hipMemcpyAsync(d_joff, stage, sizeof(int64_t) * 2 * (size_t)g->B, hipMemcpyHostToDevice, st);
-        if (e != hipSuccess) { cleanup(); set_error("joffsets upload failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
-    }
+    const std::vector<int64_t> ranges = scaled_voxel_ranges(g, 1);
     fx_grid* o = nullptr;
-    rc = build_index_grid_device_joff(d_c, n, d_joff, g->B, st, &o);
-    cleanup();
+    const fx_status rc = build_index_grid_device(d_c, n, ranges.data(), g->B, st, &o);
+    dev_free(d_c, st);
     if (rc != FX_OK) return rc;
     *out = o;
     return FX_OK;
@@ -1201,28 +1239,16 @@ extern "C" fx_status fx_grid_subdivide2(const fx_grid* g, void* stream, fx_grid*
     const int64_t n = g->hdr.n_voxels;
     if (8 * n > 0x7FFFFFFFll) { set_error("fx_grid_subdivide2: more than 2^31-1 voxels"); return FX_ERANGE; }
     int32_t* d_c = nullptr;
-    int64_t* d_joff = nullptr;
     FX_TRY(dev_alloc((void**)&d_c, sizeof(int32_t) * 3 * 8 * (size_t)std::max<int64_t>(n, 1), st));
-    fx_status rc = dev_alloc((void**)&d_joff, sizeof(int64_t) * 2 * (size_t)std::max(g->B, 1), st);
-    if (rc != FX_OK) { dev_free(d_c, st); return rc; }
-    auto cleanup = [&]() { dev_free(d_c, st); dev_free(d_joff, st); };
     if (g->hdr.n_leaf > 0) {
         const int64_t threads = (int64_t)g->hdr.n_leaf * 64;
         ProfScope ps(kProfGridIjk, st);
         k_grid_children<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(g->view(), d_c);
     }
-    if (g->B > 0) {
-        void* stage = nullptr;
-        rc = host_staging(&stage, sizeof(int64_t) * 2 * (size_t)g->B, 1);
-        if (rc != FX_OK) { cleanup(); return rc; }
-        int64_t* hj = (int64_t*)stage;
-        for (int b = 0; b < g->B; ++b) { hj[2 * b] = 8 * g->h_vox_base[b]; hj[2 * b + 1] = 8 * g->h_vox_base[b + 1]; }
-        hipError_t e = hipMemcpyAsync(d_joff, stage, sizeof(int64_t) * 2 * (size_t)g->B, hipMemcpyHostToDevice, st);
-        if (e != hipSuccess) { cleanup(); set_error("joffsets upload failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
-    }
+    const std::vector<int64_t> ranges = scaled_voxel_ranges(g, 8);
     fx_grid* o = nullptr;
-    rc = build_index_grid_device_joff(d_c, 8 * n, d_joff, g->B, st, &o);
-    cleanup();
+    const fx_status rc = build_index_grid_device(d_c, 8 * n, ranges.data(), g->B, st, &o);
+    dev_free(d_c, st);
     if (rc != FX_OK) return rc;
     *out = o;
     return FX_OK;
@@ -1237,14 +1263,11 @@ extern "C" fx_status fx_grid_pad(const fx_grid* g, int32_t r, void* stream, fx_g
     const int64_t w3 = (int64_t)(2 * r + 1) * (2 * r + 1) * (2 * r + 1);
     if (w3 * n > 0x7FFFFFFFll) { set_error("fx_grid_pad: more than 2^31-1 candidate voxels"); return FX_ERANGE; }
     int32_t* d_c = nullptr;
-    int64_t* d_joff = nullptr;
     // the counter of coordinates that leave the int32 range sits behind the candidates, in the same allocation
     const size_t c_bytes = (sizeof(int32_t) * 3 * (size_t)std::max<int64_t>(w3 * n, 1) + 15) & ~size_t(15);
     FX_TRY(dev_alloc((void**)&d_c, c_bytes + 16, st));
     int32_t* d_bad = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(d_c) + c_bytes);
-    fx_status rc = dev_alloc((void**)&d_joff, sizeof(int64_t) * 2 * (size_t)std::max(g->B, 1), st);
-    if (rc != FX_OK) { dev_free(d_c, st); return rc; }
-    auto cleanup = [&]() { dev_free(d_c, st); dev_free(d_joff, st); };
+    auto cleanup = [&]() { dev_free(d_c, st); };
     hipError_t e = hipMemsetAsync(d_bad, 0, sizeof(int32_t), st);
     if (e == hipSuccess && g->hdr.n_leaf > 0) {
         const int64_t threads = (int64_t)g->hdr.n_leaf * 64;
@@ -1253,17 +1276,9 @@ extern "C" fx_status fx_grid_pad(const fx_grid* g, int32_t r, void* stream, fx_g
         e = hipGetLastError();
     }
     if (e != hipSuccess) { cleanup(); set_error("fx_grid_pad: launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
-    if (g->B > 0) {
-        void* stage = nullptr;
-        rc = host_staging(&stage, sizeof(int64_t) * 2 * (size_t)g->B, 1);
-        if (rc != FX_OK) { cleanup(); return rc; }
-        int64_t* hj = (int64_t*)stage;
-        for (int b = 0; b < g->B; ++b) { hj[2 * b] = w3 * g->h_vox_base[b]; hj[2 * b + 1] = w3 * g->h_vox_base[b + 1]; }
-        e = hipMemcpyAsync(d_joff, stage, sizeof(int64_t) * 2 * (size_t)g->B, hipMemcpyHostToDevice, st);
-        if (e != hipSuccess) { cleanup(); set_error("joffsets upload failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
-    }
+    const std::vector<int64_t> ranges = scaled_voxel_ranges(g, w3);
     fx_grid* o = nullptr;
-    rc = build_index_grid_device_joff(d_c, w3 * n, d_joff, g->B, st, &o);     // synchronises the stream
+    fx_status rc = build_index_grid_device(d_c, w3 * n, ranges.data(), g->B, st, &o);     // synchronises the stream
     int32_t bad = 0;
     if (rc == FX_OK) {
         e = hipMemcpy(&bad, d_bad, sizeof(int32_t), hipMemcpyDeviceToHost);
