@@ -110,6 +110,8 @@ fx_status fx_get_option(const char* name, int32_t* value);
  *              voxels in grids 0..b-1.
  * Synchronises `stream` internally (node counts are read back to size the tree: step 10).
  * Limits: at most 65536 root tiles (4096^3 regions) per batch, 2^31-1 voxels -> FX_ERANGE.
+ * FX_EDEVICE when a launch fails or a workgroup of the build's single-pass scans waited for its
+ * predecessors beyond the bound (no grid is returned; fx_last_error says which).
  */
 fx_status fx_build_index_grid(const int32_t* d_ijk, int64_t n_rows, const int64_t* h_joffsets,
                               int32_t B, void* stream, fx_grid** out);
