@@ -23,6 +23,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12      # one vector instruction per SIMD every 4 cycles, 64 lanes each: 39.3
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
 FP32_VALU_PEAK_TFLOPS = 157.3
 
@@ -107,6 +108,27 @@ def committed_traffic(kernel, workload):
     if sha != kernel_source_sha1(kernel):
         return None, f"profiles/{os.path.basename(path)} was measured on other sources of this kernel ({sha}): not quoted"
     return traffic, f"profiles/{os.path.basename(path)}, sources {sha}"
+
+
+def committed_valu_instructions(kernel, workload):
+    """Vector-ALU wave instructions per launch from the committed SQ_INSTS_VALU summary of this command
+    (profiles/<kernel>_<workload>_issue_counters.md: `valu_wave_instructions_per_launch: N` and the fingerprint of the
+    kernel's sources); (None, note) when there is none or the sources have changed since."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_issue_counters.md")
+    n, sha = None, None
+    try:
+        for line in open(path):
+            if line.startswith("valu_wave_instructions_per_launch:"):
+                n = float(line.split(":", 1)[1])
+            if line.startswith("kernel_source_sha1:"):
+                sha = line.split(":", 1)[1].strip()
+    except OSError:
+        return None, "no issue-counter summary committed for this kernel and workload"
+    if n is None:
+        return None, "no issue-counter summary committed for this kernel and workload"
+    if sha != kernel_source_sha1(kernel):
+        return None, f"profiles/{os.path.basename(path)} was measured on other sources of this kernel ({sha}): not quoted"
+    return n, f"profiles/{os.path.basename(path)}, sources {sha}"
 
 
 def gpu_clocks():
@@ -459,6 +481,18 @@ def main():
                      "traffic": committed_traffic("k_build_tiles", args.workload)[0],
                      "traffic_source": committed_traffic("k_build_tiles", args.workload)[1]}
         kmap_roof["frac"] = kmap_roof["achieved"] / HBM_PEAK_GBS
+        # What binds this kernel is the issue of vector-ALU instructions (integer work: bit tests, popcounts, a
+        # sort, address arithmetic), not memory: the instructions it executes per launch (counter summary under
+        # profiles/) against the chip's vector issue rate, 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations/s.
+        valu, valu_src = committed_valu_instructions("k_build_tiles", args.workload)
+        if valu:
+            lane_ops = valu * 64
+            kmap_roof["alu_view"] = {"bound": "alu", "unit": "Tlane-op/s", "peak": VALU_PEAK_TLANEOPS,
+                                     "valu_wave_instructions_per_launch": valu, "source": valu_src,
+                                     "achieved": lane_ops / (bt_ms * 1e-3) / 1e12,
+                                     "frac": lane_ops / (bt_ms * 1e-3) / 1e12 / VALU_PEAK_TLANEOPS}
+        else:
+            kmap_roof["alu_view"] = {"bound": "alu", "source": valu_src}
 
     # grid build: the rows read once plus the leaf table written (Sec. 3.3; no sort passes here)
     n_leaf_in = g.counts()[0]
