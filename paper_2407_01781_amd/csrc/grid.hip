@@ -65,9 +65,9 @@ __device__ __forceinline__ uint32_t mix32(uint32_t h, uint32_t v) {
 
 // ---------------------------------------------------------------------------------- block scan
 constexpr int kScanThreads = 1024;
-constexpr int kWordsPerThread = 8;
+constexpr int kWordsPerThread = 4;
 constexpr int kWordChunk = kScanThreads * kWordsPerThread;  // mask words per block
-constexpr int kLeavesPerThread = 2;
+constexpr int kLeavesPerThread = 1;
 constexpr int kLeafChunk = kScanThreads * kLeavesPerThread;
 
 // exclusive scan of one value per thread over a 1024-thread block; returns the block total
@@ -377,25 +377,39 @@ __device__ __forceinline__ bool leaf_at(const LeafList& L, const GridHeader* hdr
 
 // ---------------------------------------------------------------------------------- root tiles
 // Distinct (grid, tile) pairs of the leaves go into a small open-addressing table whose slots
-// hold a representative leaf (+1; 0 = empty).  Called by all lanes of a wave together (`has`:
-// this lane holds leaf `idx` with key `key`).
+// hold a representative leaf (+1; 0 = empty).  Called by all threads of a workgroup together (`has`:
+// this thread holds leaf `idx` with key `key`).
+constexpr int kFindTilesThreads = 1024;
+constexpr int kTileRounds = 16;
 __device__ __forceinline__ void find_tile_item(const LeafList& L, GridHeader* hdr, int idx, bool has, const int4& key,
                                                int32_t* __restrict__ tile_slots, int32_t* __restrict__ rep_leaves) {
-    const int b = key.w, ti = key.x >> 9, tj = key.y >> 9, tk = key.z >> 9;   // leaf coordinate >> 9 = voxel >> 12
-    // one lane per distinct tile of the wave inserts (accesses to one address from all over the
-    // device queue up at memory): repeatedly, the first lane still waiting becomes the speaker for
-    // all lanes with its tile
-    const int lane = threadIdx.x & 63;
+    const int4 tile = make_int4(key.x >> 9, key.y >> 9, key.z >> 9, key.w);   // leaf coordinate >> 9 = voxel >> 12
+    auto same = [](const int4& a, const int4& b) { return a.x == b.x && a.y == b.y && a.z == b.z && a.w == b.w; };
+    // One thread per distinct tile of the WORKGROUP goes to the table: accesses to one address from all over the
+    // device queue up at memory (a coherent read of one slot from each of 600 waves took longer than the rest of
+    // this launch), and nearly all leaves share one tile.  In rounds, the first thread still waiting proposes its
+    // tile (the first waiting lane of every wave bids with an LDS atomic; same-address LDS atomics run lane by lane,
+    // so not every lane) and every thread with that tile is done: two barriers and no memory access per distinct tile.
+    __shared__ int leader[kTileRounds];
+    __shared__ int4 leader_tile[kTileRounds];
+    const int tid = (int)threadIdx.x;
     bool waiting = has, speaker = false;
-    for (int round = 0; round < 64; ++round) {
-        const uint64_t pending = __ballot(waiting);
-        if (!pending) break;
-        const int leader = __ffsll((long long)pending) - 1;
-        const int lb = __shfl(b, leader), li = __shfl(ti, leader), lj = __shfl(tj, leader), lk = __shfl(tk, leader);
-        if (waiting && lb == b && li == ti && lj == tj && lk == tk) { waiting = false; speaker = (lane == leader); }
+    for (int batch = 0; batch < (int)blockDim.x / kTileRounds + 1; ++batch) {
+        if (tid < kTileRounds) leader[tid] = INT32_MAX;
+        if (!__syncthreads_or(waiting)) break;
+        for (int r = 0; r < kTileRounds; ++r) {
+            const uint64_t bids = __ballot(waiting);
+            if (bids && (tid & 63) == __ffsll((long long)bids) - 1) atomicMin(&leader[r], tid);
+            __syncthreads();
+            const int l = leader[r];
+            if (l == INT32_MAX) break;
+            if (tid == l) { leader_tile[r] = tile; speaker = true; }
+            __syncthreads();
+            if (waiting && same(tile, leader_tile[r])) waiting = false;
+        }
     }
     if (!speaker) return;
-    uint32_t h = mix32(mix32(mix32(mix32(0x811C9DC5u, (uint32_t)b), (uint32_t)ti), (uint32_t)tj), (uint32_t)tk);
+    uint32_t h = mix32(mix32(mix32(mix32(0x811C9DC5u, (uint32_t)tile.w), (uint32_t)tile.x), (uint32_t)tile.y), (uint32_t)tile.z);
     h &= (kTileHashSlots - 1);
     for (int probe = 0; probe < kTileHashSlots; ++probe) {
         // device-coherent read: once a tile is in, nobody else reaches the compare-and-swap
@@ -411,13 +425,13 @@ __device__ __forceinline__ void find_tile_item(const LeafList& L, GridHeader* hd
             s = old;
         }
         const int4 o = L.key[s - 1];
-        if (o.w == b && (o.x >> 9) == ti && (o.y >> 9) == tj && (o.z >> 9) == tk) break;
+        if (o.w == tile.w && (o.x >> 9) == tile.x && (o.y >> 9) == tile.y && (o.z >> 9) == tile.z) break;
         h = (h + 1) & (kTileHashSlots - 1);
     }
 }
 
-__global__ void k_find_tiles(LeafList L, int32_t* __restrict__ tile_slots, int32_t* __restrict__ rep_leaves,
-                             GridHeader* hdr) {
+__global__ void __launch_bounds__(kFindTilesThreads)
+k_find_tiles(LeafList L, int32_t* __restrict__ tile_slots, int32_t* __restrict__ rep_leaves, GridHeader* hdr) {
     if (hdr->overflow) return;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int4 key = make_int4(0, 0, 0, 0);
@@ -516,10 +530,51 @@ __global__ void k_insert(LeafList L, GridPtrs g) {
 // update memory directly.
 constexpr int kInsertUpperThreads = 1024;
 constexpr int kAggUpper = 4;
-__global__ void __launch_bounds__(kInsertUpperThreads) k_insert_upper(LeafList L, GridPtrs g) {
+// With at most kRankInBlock root tiles possible (the capacity of the upper level says so) the launch that ranks the
+// tiles is dropped: every workgroup ranks them itself into LDS (a handful of comparisons) and looks its leaves up
+// there; the first workgroup also writes the root table and the count for the launches that follow.
+constexpr int kRankInBlock = 16;
+__global__ void __launch_bounds__(kInsertUpperThreads) k_insert_upper(LeafList L, GridPtrs g,
+                                                                       const int32_t* __restrict__ rep_leaves, int rank_here) {
     __shared__ unsigned long long bits[kAggUpper * kUpperWords];
+    __shared__ uint64_t tile_keys[kRankInBlock], ranked_key[kRankInBlock];
+    __shared__ int32_t tile_batch[kRankInBlock], ranked_batch[kRankInBlock];
     if (g.hdr->overflow) return;
-    const int n_upper = g.hdr->n_upper;
+    const uint64_t* root_key = g.root_key;
+    const int32_t* root_batch = g.root_batch;
+    int n_upper;
+    if (rank_here) {
+        const int raw = g.hdr->n_tiles_raw;
+        const int T = raw < kMaxTiles ? raw : kMaxTiles;
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            int ov = 0;
+            if (raw > kMaxTiles) ov |= 8;
+            if (T > g.cap_upper) ov |= 1;
+            g.hdr->n_upper = T;
+            if (ov) atomicOr(&g.hdr->overflow, ov);
+        }
+        if (T > g.cap_upper) return;              // cap_upper <= kRankInBlock on this path
+        if ((int)threadIdx.x < T) {
+            const int4 me = L.key[rep_leaves[threadIdx.x]];
+            tile_keys[threadIdx.x] = tile_key(me.x << 3, me.y << 3, me.z << 3);
+            tile_batch[threadIdx.x] = me.w;
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < T) {
+            const uint64_t key = tile_keys[threadIdx.x];
+            const int32_t b = tile_batch[threadIdx.x];
+            int rank = 0;
+            for (int o = 0; o < T; ++o) rank += (tile_batch[o] < b) || (tile_batch[o] == b && tile_keys[o] < key);
+            ranked_key[rank] = key;
+            ranked_batch[rank] = b;
+            if (blockIdx.x == 0) { g.root_key[rank] = key; g.root_batch[rank] = b; }
+        }
+        n_upper = T;
+        root_key = ranked_key;
+        root_batch = ranked_batch;
+    } else {
+        n_upper = g.hdr->n_upper;
+    }
     const int n_agg_words = (n_upper < kAggUpper ? n_upper : kAggUpper) * kUpperWords;
     for (int e = threadIdx.x; e < n_agg_words; e += kInsertUpperThreads) bits[e] = 0ull;
     __syncthreads();
@@ -527,7 +582,7 @@ __global__ void __launch_bounds__(kInsertUpperThreads) k_insert_upper(LeafList L
     int4 key;
     if (leaf_at(L, g.hdr, idx, &key)) {
         const int i = key.x << 3, j = key.y << 3, k = key.z << 3;
-        const int u = find_upper(g.root_key, g.root_batch, n_upper, key.w, tile_key(i, j, k));
+        const int u = find_upper(root_key, root_batch, n_upper, key.w, tile_key(i, j, k));
         if (u >= 0) {
             const int off = upper_off(i, j, k);
             const int word = u * kUpperWords + (off >> 6);
@@ -639,6 +694,10 @@ __global__ void __launch_bounds__(kScanThreads) k_scan_words(LevelScan s, GridHe
 // owner of the last leaf writes the entries after it.  (The buffer starts zeroed: no leaves, all 0.)
 __device__ __forceinline__ void note_vox_base(const fx_leaf* __restrict__ leaf, int64_t l, int64_t n_leaf, int64_t offset,
                                               int64_t n_voxels, int64_t* __restrict__ vox_base, int B) {
+    if (B == 1) {      // a single grid: its bases are 0 (the buffer's initial value) and the voxel count, no record is read
+        if (l == n_leaf - 1) vox_base[1] = n_voxels;
+        return;
+    }
     const int bcur = leaf[l].batch;
     const int bprev = l ? leaf[l - 1].batch : -1;
     for (int b = bprev + 1; b <= bcur; ++b) vox_base[b] = offset;
@@ -955,10 +1014,12 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const Batch
             ProfScope ps(kProfVoxelsToLeaves, st);
             k_voxels_to_leaves<<<nb_rows, 256, 0, st>>>(d_ijk, n_rows, d_joff, B, d_slots, (uint32_t)(n_slots - 1), L, g->d_hdr);
         }
-        { ProfScope ps(kProfFindTiles, st); k_find_tiles<<<nb_leaf, 256, 0, st>>>(L, d_tile_slots, d_rep, g->d_hdr); }
-        { ProfScope ps(kProfRankTiles, st); k_rank_tiles<<<kMaxTiles / 256, 256, 0, st>>>(L, d_rep, q); }
+        { ProfScope ps(kProfFindTiles, st); k_find_tiles<<<(unsigned)((g->cap_leaf + kFindTilesThreads - 1) / kFindTilesThreads), kFindTilesThreads, 0, st>>>(L, d_tile_slots, d_rep, g->d_hdr); }
+        const bool rank_in_block = g->cap_upper <= kRankInBlock;
+        if (!rank_in_block) { ProfScope ps(kProfRankTiles, st); k_rank_tiles<<<kMaxTiles / 256, 256, 0, st>>>(L, d_rep, q); }
         { ProfScope ps(kProfInsertUpper, st);
-          k_insert_upper<<<(unsigned)((g->cap_leaf + kInsertUpperThreads - 1) / kInsertUpperThreads), kInsertUpperThreads, 0, st>>>(L, q); }
+          k_insert_upper<<<(unsigned)((g->cap_leaf + kInsertUpperThreads - 1) / kInsertUpperThreads), kInsertUpperThreads, 0, st>>>(
+              L, q, d_rep, rank_in_block ? 1 : 0); }
         LevelScan su{g->d_upper_mask, g->d_upper_prefix, &g->d_hdr->n_upper, kUpperWords, &g->d_hdr->n_lower,
                      g->cap_lower, 2};
         { ProfScope ps(kProfScanUpper, st); if (scan_level(g, su, g->cap_upper, scan_sync(0), st) != FX_OK) return fail(FX_EDEVICE); }

@@ -27,6 +27,7 @@ __device__ __forceinline__ int leaf_off(int i, int j, int k) {  // Listing 1
 __device__ __forceinline__ int find_upper(const uint64_t* __restrict__ root_key,
                                           const int32_t* __restrict__ root_batch, int n_upper, int b,
                                           uint64_t key) {
+    if (n_upper == 1) return (root_batch[0] == b && root_key[0] == key) ? 0 : -1;   // the usual case: one round of loads
     int lo = 0, hi = n_upper;
     while (lo < hi) {
         int mid = (lo + hi) >> 1;
