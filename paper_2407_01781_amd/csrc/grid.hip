@@ -482,7 +482,7 @@ template <int LEVEL>
 __device__ __forceinline__ void insert_item(const LeafList& L, const GridPtrs& g, int idx, const int4& key) {
     const int b = key.w;
     const int i = key.x << 3, j = key.y << 3, k = key.z << 3;   // the leaf's origin
-    const int u = find_upper(g.root_key, g.root_batch, g.hdr->n_upper, b, tile_key(i, j, k));
+    const int u = find_upper_short(g.root_key, g.root_batch, g.hdr->n_upper, b, tile_key(i, j, k));
     if (u < 0) return;
     if (LEVEL == 0) {
         const int off = upper_off(i, j, k);
@@ -582,7 +582,7 @@ __global__ void __launch_bounds__(kInsertUpperThreads) k_insert_upper(LeafList L
     int4 key;
     if (leaf_at(L, g.hdr, idx, &key)) {
         const int i = key.x << 3, j = key.y << 3, k = key.z << 3;
-        const int u = find_upper(root_key, root_batch, n_upper, key.w, tile_key(i, j, k));
+        const int u = find_upper_short(root_key, root_batch, n_upper, key.w, tile_key(i, j, k));
         if (u >= 0) {
             const int off = upper_off(i, j, k);
             const int word = u * kUpperWords + (off >> 6);

@@ -118,7 +118,7 @@ __global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int64_
     const int a = slot / 9, c = (slot / 3) % 3, d = slot % 3;
     int id = -1;
     if (bi + a <= hi_i && bj + c <= hi_j && bk + d <= hi_k)
-        id = find_leaf(tin, lf->batch, (bi + a) * 8, (bj + c) * 8, (bk + d) * 8);
+        id = find_leaf<true>(tin, lf->batch, (bi + a) * 8, (bj + c) * 8, (bk + d) * 8);
     nbr[e] = id;
 }
 
