@@ -777,24 +777,38 @@ __global__ void k_publish(const GridHeader* __restrict__ hdr, const int64_t* __r
 }
 
 // ---------------------------------------------------------------------------------- queries
-// one wave per leaf: lane = bit of the current mask word (ballot-free: every lane tests its bit)
-__global__ void k_grid_ijk(TreeView t, int32_t* __restrict__ ijk_out, int32_t* __restrict__ jidx_out, int shift) {
+// One wave per leaf.  The wave first lists the positions of the leaf's active voxels in LDS, in index order (lane =
+// bit of the current mask word: every lane tests its bit), then writes the leaf's 3 n coordinates as one contiguous
+// run of 4-byte words -- a voxel's three coordinates written by its own lane would be three 4-byte stores 12 bytes
+// apart per lane.
+__global__ void __launch_bounds__(256) k_grid_ijk(TreeView t, int32_t* __restrict__ ijk_out, int32_t* __restrict__ jidx_out,
+                                                   int shift) {
+    __shared__ uint16_t active[4][512];
     const int f = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     if (f >= t.n_leaf) return;
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const fx_leaf* lf = t.leaf + f;
     const uint64_t lt = (1ull << lane) - 1;
-    int64_t run = lf->offset;
+    int n = 0;
+#pragma unroll
     for (int w = 0; w < 8; ++w) {
         const uint64_t m = lf->mask[w];
-        if ((m >> lane) & 1) {
-            const int64_t o = run + __popcll(m & lt);
-            ijk_out[3 * o + 0] = (lf->origin[0] + w) >> shift;
-            ijk_out[3 * o + 1] = (lf->origin[1] + (lane >> 3)) >> shift;
-            ijk_out[3 * o + 2] = (lf->origin[2] + (lane & 7)) >> shift;
-            if (jidx_out) jidx_out[o] = lf->batch;
-        }
-        run += __popcll(m);
+        if ((m >> lane) & 1) active[wave][n + __popcll(m & lt)] = (uint16_t)(w * 64 + lane);
+        n += __popcll(m);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int64_t first = lf->offset;
+    const int o0 = lf->origin[0], o1 = lf->origin[1], o2 = lf->origin[2];
+    for (int e = lane; e < 3 * n; e += 64) {
+        const int v = e / 3, axis = e - 3 * v;
+        const int pos = active[wave][v];
+        const int c = axis == 0 ? o0 + (pos >> 6) : axis == 1 ? o1 + ((pos >> 3) & 7) : o2 + (pos & 7);
+        ijk_out[3 * first + e] = c >> shift;
+    }
+    if (jidx_out) {
+        const int b = lf->batch;
+        for (int e = lane; e < n; e += 64) jidx_out[first + e] = b;
     }
 }
 
