@@ -170,6 +170,76 @@ k_voxels_to_leaves(const int32_t* __restrict__ ijk, int64_t n_rows, const BatchR
     }
 }
 
+// ---- coarse grid straight from the fine grid's leaves (Sec. 3.6.2: the grid of floor(ijk / 2))
+// A fine leaf covers a 4x4x4 block of one coarse leaf: its 512-bit mask folds to 64 bits (a coarse voxel is active
+// when any of its 8 children is), 16 bits in each of four words of the coarse leaf's mask.  One thread per fine
+// leaf claims the coarse leaf in the table of the direct path (slots hold a representative fine leaf + 1) and ORs
+// its four words in -- tens of thousands of items instead of a row per fine voxel through the whole voxel pass.
+__global__ void __launch_bounds__(256)
+k_coarse_leaves(TreeView fine, int32_t* __restrict__ slots, uint32_t slot_mask, LeafList L, GridHeader* hdr) {
+    const int f = (int)((int64_t)blockIdx.x * blockDim.x + threadIdx.x);
+    const bool has = f < fine.n_leaf;
+    int li = 0, lj = 0, lk = 0, b = 0;
+    uint32_t h = 0;
+    bool claimed = false;
+    if (has) {
+        const fx_leaf* lf = fine.leaf + f;
+        const int oi = lf->origin[0], oj = lf->origin[1], ok = lf->origin[2];
+        b = lf->batch;
+        li = oi >> 4; lj = oj >> 4; lk = ok >> 4;                      // coarse leaf coordinate: (origin >> 1) >> 3
+        const int bi = (oi >> 1) & 7, bj = (oj >> 1) & 7, bk = (ok >> 1) & 7;   // 0 or 4: the block inside the coarse leaf
+        uint64_t word[4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            uint64_t m = lf->mask[2 * a] | lf->mask[2 * a + 1];         // pairs along i
+            m = (m | (m >> 1)) & 0x5555555555555555ull;                 // pairs along k, kept at the even bits
+            m = (m | (m >> 1)) & 0x3333333333333333ull;                 // ... gathered into the low nibble of every byte
+            m = (m | (m >> 2)) & 0x0F0F0F0F0F0F0F0Full;
+            m = (m | (m >> 8)) & 0x00FF00FF00FF00FFull;                 // pairs along j: bytes 0, 2, 4, 6
+            uint64_t r = 0;
+#pragma unroll
+            for (int cj = 0; cj < 4; ++cj) r |= ((m >> (16 * cj)) & 0xFull) << ((bj + cj) * 8 + bk);
+            word[a] = r;
+        }
+        h = leaf_hash(b, li, lj, lk) & slot_mask;
+        bool found = false;
+        for (uint32_t probe = 0; probe <= slot_mask; ++probe) {
+            int32_t sl = __hip_atomic_load(&slots[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (sl == 0) {
+                const int32_t old = atomicCAS(&slots[h], 0, f + 1);
+                if (old == 0) { found = claimed = true; break; }
+                sl = old;
+            }
+            const fx_leaf* o = fine.leaf + (sl - 1);
+            if ((o->origin[0] >> 4) == li && (o->origin[1] >> 4) == lj && (o->origin[2] >> 4) == lk && o->batch == b) {
+                found = true;
+                break;
+            }
+            h = (h + 1) & slot_mask;
+        }
+        if (!found) atomicOr(&hdr->overflow, 4 | 32);
+        else {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                if (word[a]) atomicOr((unsigned long long*)&L.mask[(size_t)h * 8 + bi + a], (unsigned long long)word[a]);
+        }
+    }
+    // list the newly claimed coarse leaves: one counter update per wave
+    const uint64_t cl = __ballot(claimed);
+    if (cl) {
+        const int lane = threadIdx.x & 63;
+        const int leader = __ffsll((long long)cl) - 1;
+        int base = 0;
+        if (lane == leader) base = atomicAdd(&hdr->n_leaf_raw, __popcll(cl));
+        base = __shfl(base, leader);
+        if (claimed) {
+            const int pos = base + __popcll(cl & ((1ull << lane) - 1));
+            if (pos < L.cap) { L.key[pos] = make_int4(li, lj, lk, b); L.mask_idx[pos] = (int32_t)h; }
+            else atomicOr(&hdr->overflow, 4);
+        }
+    }
+}
+
 // ---- partitioned path
 constexpr int kPartThreads = 1024;
 constexpr int kPartRowsPerThread = 4;
@@ -927,7 +997,8 @@ static fx_status scan_level(const fx_grid* g, LevelScan s, int cap_nodes, ScanSy
 constexpr int64_t kPartitionMinRows = 65536;   // below this the direct path's few kernels win
 
 static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const BatchRanges& d_joff, int32_t B,
-                               int cap_upper, int cap_lower, int cap_leaf, bool direct, hipStream_t st, fx_grid** out) {
+                               int cap_upper, int cap_lower, int cap_leaf, bool direct, hipStream_t st, fx_grid** out,
+                               const fx_grid* coarsen_of = nullptr) {
     fx_grid* g = new (std::nothrow) fx_grid();
     if (!g) { set_error("host allocation failed"); return FX_ENOMEM; }
     g->B = B; g->stream = st;
@@ -1026,7 +1097,10 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const Batch
         } else {
             const unsigned nb_rows = (unsigned)((n_rows + 255) / 256);
             ProfScope ps(kProfVoxelsToLeaves, st);
-            k_voxels_to_leaves<<<nb_rows, 256, 0, st>>>(d_ijk, n_rows, d_joff, B, d_slots, (uint32_t)(n_slots - 1), L, g->d_hdr);
+            if (coarsen_of)      // n_rows = the fine grid's leaves
+                k_coarse_leaves<<<nb_rows, 256, 0, st>>>(coarsen_of->view(), d_slots, (uint32_t)(n_slots - 1), L, g->d_hdr);
+            else
+                k_voxels_to_leaves<<<nb_rows, 256, 0, st>>>(d_ijk, n_rows, d_joff, B, d_slots, (uint32_t)(n_slots - 1), L, g->d_hdr);
         }
         { ProfScope ps(kProfFindTiles, st); k_find_tiles<<<(unsigned)((g->cap_leaf + kFindTilesThreads - 1) / kFindTilesThreads), kFindTilesThreads, 0, st>>>(L, d_tile_slots, d_rep, g->d_hdr); }
         const bool rank_in_block = g->cap_upper <= kRankInBlock;
@@ -1291,19 +1365,17 @@ static std::vector<int64_t> scaled_voxel_ranges(const fx_grid* g, int64_t rows_p
 extern "C" fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** out) {
     if (!g || !out) { set_error("fx_grid_coarsen2: null pointer"); return FX_EINVAL; }
     hipStream_t st = (hipStream_t)stream;
-    const int64_t n = g->hdr.n_voxels;
-    int32_t* d_c = nullptr;
-    FX_TRY(dev_alloc((void**)&d_c, sizeof(int32_t) * 3 * (size_t)std::max<int64_t>(n, 1), st));
-    if (g->hdr.n_leaf > 0) {
-        const int64_t threads = (int64_t)g->hdr.n_leaf * 64;
-        ProfScope ps(kProfGridIjk, st);
-        k_grid_ijk<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(g->view(), d_c, nullptr, 1);
-    }
-    const std::vector<int64_t> ranges = scaled_voxel_ranges(g, 1);
+    // The coarse grid has at most as many nodes per level as the fine one, so one attempt with the fine grid's
+    // counts as capacities always fits; its leaves come from the fine leaves, not from a row per voxel.
     fx_grid* o = nullptr;
-    const fx_status rc = build_index_grid_device(d_c, n, ranges.data(), g->B, st, &o);
-    dev_free(d_c, st);
-    if (rc != FX_OK) return rc;
+    const BatchRanges none{nullptr, 0, 0};
+    FX_TRY(build_attempt(nullptr, g->hdr.n_leaf, none, g->B, g->hdr.n_upper, g->hdr.n_lower, g->hdr.n_leaf, true, st, &o, g));
+    if (o->hdr.overflow) {
+        const int ov = o->hdr.overflow;
+        fx_grid_destroy(o);
+        set_error("fx_grid_coarsen2: the coarse grid did not fit the fine grid's node counts (flags %d)", ov);
+        return FX_EDEVICE;
+    }
     *out = o;
     return FX_OK;
 }
