@@ -240,6 +240,174 @@ k_coarse_leaves(TreeView fine, int32_t* __restrict__ slots, uint32_t slot_mask, 
     }
 }
 
+// ---- padded grid straight from the grid's leaves (Sec. 3.6.2 grid construction by padding; Sec. 3.3's dilation)
+// Dilation by r <= 8 moves a leaf's voxels into at most the 27 leaves around it, and a leaf of the padded grid
+// takes voxels from at most the 27 source leaves around it.  Two passes, neither with an atomic per voxel or per
+// mask word (atomics run at memory; an OR per word of every (leaf, neighbour) pair cost 220 us on a 38 k-leaf grid):
+//   k_pad_claim   thread = (source leaf, one of its 27 neighbour positions): the neighbour receives a voxel iff the
+//                 leaf has one within r of the shared face, edge or corner -- a mask test; such neighbours are
+//                 claimed in the direct path's leaf table (a slot's representative is (source leaf, position) + 1);
+//   k_pad_masks   wave = listed leaf of the padded grid: gathers the masks of the 27 source leaves around it into a
+//                 24^3 box, dilates axis by axis towards the centre 8^3 and stores the leaf's mask with plain stores.
+__device__ __forceinline__ uint32_t reach_bits(int p, int r) {
+    // positions 0..7 along one axis whose voxels reach the neighbour at p - 1 (p = 1: the leaf itself) under dilation by r
+    return p == 1 ? 0xFFu : (r == 0 ? 0u : (p == 0 ? (0xFFu >> (8 - r)) : ((0xFFu << (8 - r)) & 0xFFu)));
+}
+
+constexpr int kPadClaimThreads = 1024;
+__global__ void __launch_bounds__(kPadClaimThreads)
+k_pad_claim(TreeView src, int r, int32_t* __restrict__ slots, uint32_t slot_mask, LeafList L, GridHeader* hdr,
+            int32_t* __restrict__ bad) {
+    // Most leaves of the padded grid are leaves of the source grid.  Those are listed by their own thread (position
+    // 13, the leaf itself) without the table: their masks sit behind the table's, at slot_mask + 1 + leaf.  A
+    // neighbour position first looks its leaf up in the source tree (plain cached loads) and goes to the table only
+    // when the leaf is new -- table probes are loads and compare-and-swaps that must see other workgroups' writes,
+    // they run at memory, and one per (leaf, position) pair was 800 k of them on a 38 k-leaf grid (40 us).
+    // List positions come from one counter; an update per wave would be 19 k updates of one address (150 us, they
+    // run one after the other), so a workgroup counts its leaves in LDS and takes its run with one update.
+    __shared__ int block_claims, block_base;
+    const int lane = threadIdx.x & 63;
+    if (threadIdx.x == 0) block_claims = 0;
+    __syncthreads();
+    const int64_t t = (int64_t)blockIdx.x * kPadClaimThreads + threadIdx.x;
+    const int64_t f = t >> 5;
+    const int piece = (int)(t & 31);
+    int4 my_key = make_int4(0, 0, 0, 0);
+    int32_t my_slot = -1;
+    if (f < src.n_leaf && piece < 27) {
+        const fx_leaf* lf = src.leaf + f;
+        const int pa = piece / 9, pb = (piece / 3) % 3, pc = piece % 3;
+        const uint32_t ia = reach_bits(pa, r), jb = reach_bits(pb, r), kc = reach_bits(pc, r);
+        uint64_t region = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) if ((jb >> j) & 1) region |= (uint64_t)kc << (8 * j);
+        uint64_t any = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) if ((ia >> i) & 1) any |= lf->mask[i] & region;
+        const int b = lf->batch;
+        const int64_t pi = (int64_t)lf->origin[0] + 8 * (pa - 1), pj = (int64_t)lf->origin[1] + 8 * (pb - 1),
+                      pk = (int64_t)lf->origin[2] + 8 * (pc - 1);
+        const int64_t lo = INT32_MIN, hi = (int64_t)INT32_MAX - 7;
+        if (piece == 13) {
+            my_slot = (int32_t)(slot_mask + 1 + (uint32_t)f);
+            my_key = make_int4((int)(pi >> 3), (int)(pj >> 3), (int)(pk >> 3), b);
+        } else if (any) {
+            if (pi < lo || pi > hi || pj < lo || pj > hi || pk < lo || pk > hi) {
+                atomicAdd(bad, 1);
+            } else if (find_leaf<true>(src, b, (int)pi, (int)pj, (int)pk) < 0) {
+                const int li = (int)(pi >> 3), lj = (int)(pj >> 3), lk = (int)(pk >> 3);
+                uint32_t h = leaf_hash(b, li, lj, lk) & slot_mask;
+                bool found = false;
+                for (uint32_t probe = 0; probe <= slot_mask; ++probe) {
+                    int32_t sl = __hip_atomic_load(&slots[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (sl == 0) {
+                        const int32_t old = atomicCAS(&slots[h], 0, (int32_t)(f * 27 + piece + 1));
+                        if (old == 0) {
+                            found = true;
+                            my_slot = (int32_t)h;
+                            my_key = make_int4(li, lj, lk, b);
+                            break;
+                        }
+                        sl = old;
+                    }
+                    const int rf = (sl - 1) / 27, rp = (sl - 1) - 27 * rf;
+                    const fx_leaf* ro = src.leaf + rf;
+                    if ((ro->origin[0] >> 3) + (rp / 9 - 1) == li && (ro->origin[1] >> 3) + ((rp / 3) % 3 - 1) == lj &&
+                        (ro->origin[2] >> 3) + (rp % 3 - 1) == lk && ro->batch == b) {
+                        found = true;
+                        break;
+                    }
+                    h = (h + 1) & slot_mask;
+                }
+                if (!found) atomicOr(&hdr->overflow, 4 | 32);     // table full: the leaf count is incomplete
+            }
+        }
+    }
+    // positions: rank of the leaf inside the wave, the wave's run inside the workgroup, the workgroup's run
+    const uint64_t cl = __ballot(my_slot >= 0);
+    int wave_base = 0;
+    if (lane == 0 && cl) wave_base = atomicAdd(&block_claims, __popcll(cl));
+    wave_base = __shfl(wave_base, 0);
+    __syncthreads();
+    if (threadIdx.x == 0) block_base = block_claims ? atomicAdd(&hdr->n_leaf_raw, block_claims) : 0;
+    __syncthreads();
+    if (my_slot >= 0) {
+        const int pos = block_base + wave_base + __popcll(cl & ((1ull << lane) - 1));
+        if (pos < L.cap) { L.key[pos] = my_key; L.mask_idx[pos] = my_slot; }
+        else atomicOr(&hdr->overflow, 4);
+    }
+}
+
+constexpr int kPadWaves = 4;
+__global__ void __launch_bounds__(64 * kPadWaves)
+k_pad_masks(TreeView src, int r, LeafList L, const GridHeader* hdr) {
+    __shared__ uint32_t box[kPadWaves][24][24];           // [i][j], bit = k: the 27 source leaves, then dilated along k
+    __shared__ uint32_t along_j[kPadWaves][24][8];        // [i][centre j], 8 bits of k
+    __shared__ unsigned long long centre[kPadWaves][8];   // the leaf's mask, byte (i, j) written by lane (i, j)
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int pos = blockIdx.x * kPadWaves + wave;
+    const int n_listed = min(hdr->n_leaf_raw, L.cap);
+    if (pos >= n_listed) return;
+    auto wave_sync = [] { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); __builtin_amdgcn_wave_barrier(); };
+    const int4 key = L.key[pos];
+    // the source leaves around the leaf: lane < 27 looks one up
+    int around = -1;
+    if (lane < 27) {
+        const int64_t ni = (int64_t)key.x + (lane / 9 - 1), nj = (int64_t)key.y + ((lane / 3) % 3 - 1), nk = (int64_t)key.z + (lane % 3 - 1);
+        const int64_t lo = -(1ll << 28), hi = (1ll << 28) - 1;      // leaf coordinates of int32 voxels
+        if (ni >= lo && ni <= hi && nj >= lo && nj <= hi && nk >= lo && nk <= hi)
+            around = find_leaf<true>(src, key.w, (int)(ni * 8), (int)(nj * 8), (int)(nk * 8));
+    }
+    // box rows: task = (pa, pb, i) takes word i of the three leaves (pa, pb, 0..2) and writes rows j = 0..7 of plane
+    // 8 pa + i; only the planes and rows within r of the centre are read later
+    const int first = 8 - r, last = 15 + r, width = 8 + 2 * r;
+    for (int e = lane; e < 128; e += 64) {
+        const int pa = e / 24, pb = (e / 8) % 3, i = e & 7;      // e < 72 are tasks
+        const int plane = 8 * pa + i;
+        const bool wanted = e < 72 && plane >= first && plane <= last && 8 * pb + 7 >= first && 8 * pb <= last;
+        uint64_t w[3];
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc) {
+            const int from = e < 72 ? (pa * 3 + pb) * 3 + pc : 0;
+            const int f = __shfl(around, from);
+            w[pc] = (wanted && f >= 0) ? src.leaf[f].mask[i] : 0ull;
+        }
+        if (wanted) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                box[wave][plane][8 * pb + j] = (uint32_t)((w[0] >> (8 * j)) & 0xFF) | ((uint32_t)((w[1] >> (8 * j)) & 0xFF) << 8) |
+                                               ((uint32_t)((w[2] >> (8 * j)) & 0xFF) << 16);
+        }
+    }
+    wave_sync();
+    // along k: the centre byte of every row that the later steps read (|i - centre| and |j - centre| within r)
+    for (int e = lane; e < width * width; e += 64) {
+        const int a = e / width, ii = first + a, jj = first + (e - a * width);
+        const uint32_t row = box[wave][ii][jj];
+        uint32_t acc = 0;
+        for (int sft = 8 - r; sft <= 8 + r; ++sft) acc |= row >> sft;
+        box[wave][ii][jj] = acc & 0xFFu;
+    }
+    wave_sync();
+    // along j
+    for (int e = lane; e < width * 8; e += 64) {
+        const int ii = first + (e >> 3), j = e & 7;
+        uint32_t acc = 0;
+        for (int d = -r; d <= r; ++d) acc |= box[wave][ii][j + 8 + d];
+        along_j[wave][ii][j] = acc;
+    }
+    wave_sync();
+    // along i: lane = (i, j) of the leaf
+    {
+        const int i = lane >> 3, j = lane & 7;
+        uint32_t acc = 0;
+        for (int d = -r; d <= r; ++d) acc |= along_j[wave][i + 8 + d][j];
+        reinterpret_cast<unsigned char*>(centre[wave])[lane] = (unsigned char)acc;
+    }
+    wave_sync();
+    if (lane < 8) L.mask[(size_t)L.mask_idx[pos] * 8 + lane] = centre[wave][lane];
+}
+
 // ---- partitioned path
 constexpr int kPartThreads = 1024;
 constexpr int kPartRowsPerThread = 4;
@@ -905,37 +1073,6 @@ __global__ void k_grid_children(TreeView t, int32_t* __restrict__ ijk_out) {
     }
 }
 
-// the (2r+1)^3 voxels p + {-r..r}^3 around every active voxel p, as rows w3*o .. w3*o + w3 - 1 (offset-major as
-// in a kernel map: i slowest); coordinates that leave the int32 range are counted in *bad and written as p
-__global__ void k_grid_padded(TreeView t, int r, int32_t* __restrict__ ijk_out, int32_t* __restrict__ bad) {
-    const int f = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
-    if (f >= t.n_leaf) return;
-    const int lane = threadIdx.x & 63;
-    const fx_leaf* lf = t.leaf + f;
-    const uint64_t lt = (1ull << lane) - 1;
-    const int w1 = 2 * r + 1;
-    const int64_t w3 = (int64_t)w1 * w1 * w1;
-    int64_t run = lf->offset;
-    for (int w = 0; w < 8; ++w) {
-        const uint64_t m = lf->mask[w];
-        if ((m >> lane) & 1) {
-            const int64_t o = run + __popcll(m & lt);
-            const int64_t i = lf->origin[0] + w, j = lf->origin[1] + (lane >> 3), k = lf->origin[2] + (lane & 7);
-            const bool ok = i - r >= INT32_MIN && i + r <= INT32_MAX && j - r >= INT32_MIN && j + r <= INT32_MAX &&
-                            k - r >= INT32_MIN && k + r <= INT32_MAX;
-            if (!ok) atomicAdd(bad, 1);
-            int32_t* q = ijk_out + 3 * (w3 * o);
-            for (int a = -r; a <= r; ++a)
-                for (int b = -r; b <= r; ++b)
-                    for (int c = -r; c <= r; ++c) {
-                        q[0] = (int32_t)(ok ? i + a : i); q[1] = (int32_t)(ok ? j + b : j); q[2] = (int32_t)(ok ? k + c : k);
-                        q += 3;
-                    }
-        }
-        run += __popcll(m);
-    }
-}
-
 __global__ void k_ijk_to_index(TreeView t, const int32_t* __restrict__ ijk, const int32_t* __restrict__ jidx,
                                int64_t n, int32_t* __restrict__ out) {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -998,7 +1135,8 @@ constexpr int64_t kPartitionMinRows = 65536;   // below this the direct path's f
 
 static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const BatchRanges& d_joff, int32_t B,
                                int cap_upper, int cap_lower, int cap_leaf, bool direct, hipStream_t st, fx_grid** out,
-                               const fx_grid* coarsen_of = nullptr) {
+                               const fx_grid* coarsen_of = nullptr, const fx_grid* pad_of = nullptr, int pad_r = 0,
+                               int32_t* d_pad_bad = nullptr) {
     fx_grid* g = new (std::nothrow) fx_grid();
     if (!g) { set_error("host allocation failed"); return FX_ENOMEM; }
     g->B = B; g->stream = st;
@@ -1020,7 +1158,9 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const Batch
     const bool partition = !direct && n_rows >= kPartitionMinRows;
     size_t n_slots = 0;                       // direct path: table slots, masks indexed by slot
     if (!partition) { n_slots = 1024; while (n_slots < 2 * (size_t)g->cap_leaf) n_slots <<= 1; }
-    const size_t n_masks = partition ? (size_t)g->cap_leaf : n_slots;
+    if (n_slots + (size_t)(pad_of ? n_rows : 0) > 0x7FFFFFFFull) { fx_grid_destroy(g); set_error("grid build: too many leaves"); return FX_ERANGE; }
+    // (a padded grid keeps the masks of the source grid's own leaves behind the table's)
+    const size_t n_masks = partition ? (size_t)g->cap_leaf : n_slots + (pad_of ? (size_t)n_rows : 0);
     int n_buckets = 64;
     while (n_buckets < kMaxBuckets && (int64_t)n_buckets * 1024 < n_rows) n_buckets <<= 1;
     const int n_part_wg = (int)((n_rows + kPartChunk - 1) / kPartChunk);
@@ -1030,8 +1170,10 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const Batch
     const size_t o_tslot = take(sizeof(int32_t) * kTileHashSlots);
     const size_t clear_bytes_head = off;
     const size_t o_slots = take(sizeof(int32_t) * n_slots);
+    const size_t clear_bytes_slots = off;
     const size_t o_mask = take(sizeof(uint64_t) * 8 * n_masks);
-    const size_t clear_bytes = partition ? clear_bytes_head : off;
+    // the padded grid's masks are stored whole, the other direct builds OR theirs together
+    const size_t clear_bytes = partition ? clear_bytes_head : (pad_of ? clear_bytes_slots : off);
     const size_t o_key = take(sizeof(int4) * (size_t)g->cap_leaf);
     const size_t o_midx = take(sizeof(int32_t) * (size_t)g->cap_leaf);
     const size_t o_rep = take(sizeof(int32_t) * kMaxTiles);
@@ -1099,6 +1241,12 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const Batch
             ProfScope ps(kProfVoxelsToLeaves, st);
             if (coarsen_of)      // n_rows = the fine grid's leaves
                 k_coarse_leaves<<<nb_rows, 256, 0, st>>>(coarsen_of->view(), d_slots, (uint32_t)(n_slots - 1), L, g->d_hdr);
+            else if (pad_of) {   // n_rows = the source grid's leaves
+                k_pad_claim<<<(unsigned)((n_rows * 32 + kPadClaimThreads - 1) / kPadClaimThreads), kPadClaimThreads, 0, st>>>(pad_of->view(), pad_r, d_slots, (uint32_t)(n_slots - 1),
+                                                                                  L, g->d_hdr, d_pad_bad);
+                k_pad_masks<<<(unsigned)((g->cap_leaf + kPadWaves - 1) / kPadWaves), 64 * kPadWaves, 0, st>>>(pad_of->view(), pad_r, L,
+                                                                                                           g->d_hdr);
+            }
             else
                 k_voxels_to_leaves<<<nb_rows, 256, 0, st>>>(d_ijk, n_rows, d_joff, B, d_slots, (uint32_t)(n_slots - 1), L, g->d_hdr);
         }
@@ -1409,31 +1557,43 @@ extern "C" fx_status fx_grid_pad(const fx_grid* g, int32_t r, void* stream, fx_g
     const int64_t n = g->hdr.n_voxels;
     const int64_t w3 = (int64_t)(2 * r + 1) * (2 * r + 1) * (2 * r + 1);
     if (w3 * n > 0x7FFFFFFFll) { set_error("fx_grid_pad: more than 2^31-1 candidate voxels"); return FX_ERANGE; }
-    int32_t* d_c = nullptr;
-    // the counter of coordinates that leave the int32 range sits behind the candidates, in the same allocation
-    const size_t c_bytes = (sizeof(int32_t) * 3 * (size_t)std::max<int64_t>(w3 * n, 1) + 15) & ~size_t(15);
-    FX_TRY(dev_alloc((void**)&d_c, c_bytes + 16, st));
-    int32_t* d_bad = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(d_c) + c_bytes);
-    auto cleanup = [&]() { dev_free(d_c, st); };
-    hipError_t e = hipMemsetAsync(d_bad, 0, sizeof(int32_t), st);
-    if (e == hipSuccess && g->hdr.n_leaf > 0) {
-        const int64_t threads = (int64_t)g->hdr.n_leaf * 64;
-        ProfScope ps(kProfGridIjk, st);
-        k_grid_padded<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(g->view(), r, d_c, d_bad);
-        e = hipGetLastError();
-    }
-    if (e != hipSuccess) { cleanup(); set_error("fx_grid_pad: launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
-    const std::vector<int64_t> ranges = scaled_voxel_ranges(g, w3);
+    if ((int64_t)g->hdr.n_leaf * 27 > 0x7FFFFFFFll) { set_error("fx_grid_pad: too many leaves"); return FX_ERANGE; }
+    int32_t* d_bad = nullptr;     // pieces that would leave the int32 coordinate range
+    FX_TRY(dev_alloc((void**)&d_bad, 16, st));
+    // The padded grid's leaves come from the source grid's leaves (k_pad_claim, k_pad_masks); every leaf reaches at most the 27
+    // leaves around it.  First attempt with room for twice the nodes, then with the counts the attempt found.
+    const int64_t nl = g->hdr.n_leaf, nlo = g->hdr.n_lower, nu = g->hdr.n_upper;
+    int64_t cap_leaf = std::min<int64_t>(27 * nl, 2 * nl + 4096), cap_lower = std::min<int64_t>(27 * nlo, 2 * nlo + 64),
+            cap_upper = std::min<int64_t>(27 * nu, 8 * nu + 8);
     fx_grid* o = nullptr;
-    fx_status rc = build_index_grid_device(d_c, w3 * n, ranges.data(), g->B, st, &o);     // synchronises the stream
+    fx_status rc = FX_OK;
+    const BatchRanges none{nullptr, 0, 0};
+    for (int attempt = 0; attempt < 6; ++attempt) {
+        if (hipMemsetAsync(d_bad, 0, sizeof(int32_t), st) != hipSuccess) { rc = FX_EDEVICE; set_error("fx_grid_pad: fill failed"); break; }
+        rc = build_attempt(nullptr, nl, none, g->B, (int)cap_upper, (int)cap_lower, (int)cap_leaf, true, st, &o, nullptr, g, r, d_bad);
+        if (rc != FX_OK) break;
+        const int ov = o->hdr.overflow;
+        if (!ov) break;
+        if (ov & (8 | 16 | 128) || attempt == 5) {
+            fx_grid_destroy(o); o = nullptr;
+            set_error(ov & 8 ? "more than %d root tiles (4096^3 regions) in the batch" : "fx_grid_pad: the build failed (flags %d)",
+                      ov & 8 ? kMaxTiles : ov);
+            rc = ov & (8 | 16) ? FX_ERANGE : FX_EDEVICE;
+            break;
+        }
+        if (ov & 1) cap_upper = o->hdr.n_upper;
+        if (ov & 2) { cap_upper = o->hdr.n_upper; cap_lower = o->hdr.n_lower; }
+        if (ov & 4) cap_leaf = (ov & 32) ? std::min<int64_t>(27 * nl, 4 * cap_leaf) : std::max<int64_t>(o->hdr.n_leaf_raw, cap_leaf + 1);
+        fx_grid_destroy(o); o = nullptr;
+    }
     int32_t bad = 0;
     if (rc == FX_OK) {
-        e = hipMemcpy(&bad, d_bad, sizeof(int32_t), hipMemcpyDeviceToHost);
+        const hipError_t e = hipMemcpy(&bad, d_bad, sizeof(int32_t), hipMemcpyDeviceToHost);
         if (e != hipSuccess) { rc = FX_EDEVICE; set_error("read-back failed: %s", hipGetErrorString(e)); }
     }
-    cleanup();
+    dev_free(d_bad, st);
     if (rc == FX_OK && bad > 0) {
-        set_error("fx_grid_pad: %d voxels lie within %d of the int32 coordinate limits", bad, r);
+        set_error("fx_grid_pad: %d leaf blocks of the padded grid lie beyond the int32 coordinate limits (a voxel lies within %d of them)", bad, r);
         rc = FX_ERANGE;
     }
     if (rc != FX_OK) { if (o) fx_grid_destroy(o); return rc; }

@@ -35,6 +35,27 @@ def test_padded_workload_grids(name):
     H.check_grid(g.pad(1), og.pad(1))
 
 
+@pytest.mark.parametrize("r", [3, 5, 8])
+def test_wide_padding_across_leaves(r):
+    """Padding wider than a voxel or two: every leaf reaches all 27 leaves around it at r = 8."""
+    grids = [_cloud(861, 250, -20, 20), _cloud(862, 60, 4090, 4102), np.array([[-4097, 7, 8]], np.int32)]
+    ijk, jo = G.make_jagged(grids)
+    g, og = H.both_grids(ijk, jo)
+    H.check_grid(g.pad(r), og.pad(r))
+
+
+@pytest.mark.parametrize("stride,side", [(64, 18), (128, 14), (4096, 2)])
+def test_padding_that_multiplies_the_nodes(stride, side):
+    """Voxels on the corners of leaves, of lower nodes and of upper nodes: padding by one voxel puts eight leaves
+    (lower nodes, upper nodes) where there was one, which is more than the first attempt of the build leaves room for."""
+    ax = (np.arange(side, dtype=np.int64) - side // 2) * stride
+    ijk = np.stack(np.meshgrid(ax, ax, ax, indexing="ij"), -1).reshape(-1, 3).astype(np.int32)
+    g, og = H.both_grids(ijk, np.array([[0, len(ijk)]]))
+    gp, ogp = g.pad(1), og.pad(1)
+    H.check_grid(gp, ogp)
+    assert gp.num_voxels == 27 * len(ijk) and gp.counts()[0] == 8 * len(ijk)
+
+
 def test_padding_edge_cases_and_errors():
     e, _ = H.both_grids(np.zeros((0, 3), np.int32), np.array([[0, 0]]))
     assert e.pad(1).num_voxels == 0 and e.pad(0).num_voxels == 0
