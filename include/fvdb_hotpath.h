@@ -160,7 +160,8 @@ fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** out);
 /* The subdivided grid of Sec. 3.6.2 (the grid that upsampling produces): active set =
  * all eight children 2*ijk + {0,1}^3 of every active voxel, per grid of the batch.  The kernel map
  * fx_build_kernel_map(*out, 2, 2) then has g as its output grid (same voxels, same order).
- * FX_ERANGE beyond 2^31-1 voxels.  Synchronises `stream`. */
+ * FX_ERANGE beyond 2^31-1 voxels, or if a leaf of g holds coordinates outside [-2^30, 2^30) (their doubles
+ * leave the int32 coordinate limits).  The caller owns *out.  Synchronises `stream`. */
 fx_status fx_grid_subdivide2(const fx_grid* g, void* stream, fx_grid** out);
 
 /* The padded grid of Sec. 3.6.2 (a grid made from another by padding; the dilation that Sec. 3.3 names as

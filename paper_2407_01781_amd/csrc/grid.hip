@@ -408,6 +408,69 @@ k_pad_masks(TreeView src, int r, LeafList L, const GridHeader* hdr) {
     if (lane < 8) L.mask[(size_t)L.mask_idx[pos] * 8 + lane] = centre[wave][lane];
 }
 
+// ---- subdivided grid straight from the grid's leaves (Sec. 3.6.2 grid construction by subdivision)
+// A leaf of the fine grid is one octant (4^3 voxels) of a coarse leaf with every voxel doubled along each axis;
+// it has exactly one source, so there is no table and no claim: thread = (coarse leaf, octant) expands the octant's
+// 64 bits into the fine leaf's 512 (mask slot 8 * leaf + octant) and lists the leaf if the octant is not empty.
+constexpr int kSubdivideThreads = 1024;
+__global__ void __launch_bounds__(kSubdivideThreads)
+k_subdivide_leaves(TreeView coarse, LeafList L, GridHeader* hdr, int32_t* __restrict__ bad) {
+    __shared__ int block_count, block_base;
+    const int lane = threadIdx.x & 63;
+    if (threadIdx.x == 0) block_count = 0;
+    __syncthreads();
+    const int64_t t = (int64_t)blockIdx.x * kSubdivideThreads + threadIdx.x;
+    const int64_t f = t >> 3;
+    const int q = (int)(t & 7), bi = q >> 2, bj = (q >> 1) & 1, bk = q & 1;
+    bool listed = false;
+    int4 key = make_int4(0, 0, 0, 0);
+    if (f < coarse.n_leaf) {
+        const fx_leaf* lf = coarse.leaf + f;
+        uint64_t fine[4];
+        uint64_t any = 0;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const uint64_t w = lf->mask[4 * bi + a];
+            uint64_t rows = 0;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                uint32_t x = (uint32_t)(w >> (8 * (4 * bj + jj) + 4 * bk)) & 0xFu;     // k = 4 bk .. 4 bk + 3 of row j
+                x = (x | (x << 2)) & 0x33u;
+                x = (x | (x << 1)) & 0x55u;
+                x |= x << 1;                                                           // every bit twice
+                rows |= (uint64_t)(x | (x << 8)) << (16 * jj);                         // the row twice
+            }
+            fine[a] = rows;
+            any |= rows;
+        }
+        if (any) {
+            const int o0 = lf->origin[0], o1 = lf->origin[1], o2 = lf->origin[2];
+            const int lo = -(1 << 30), hi = (1 << 30) - 8;                             // doubled coordinates stay int32
+            if (o0 < lo || o0 > hi || o1 < lo || o1 > hi || o2 < lo || o2 > hi) {
+                atomicAdd(bad, 1);
+            } else {
+                listed = true;
+                key = make_int4(2 * (o0 >> 3) + bi, 2 * (o1 >> 3) + bj, 2 * (o2 >> 3) + bk, lf->batch);
+                uint64_t* m = L.mask + (size_t)t * 8;
+#pragma unroll
+                for (int a = 0; a < 4; ++a) { m[2 * a] = fine[a]; m[2 * a + 1] = fine[a]; }      // the plane twice
+            }
+        }
+    }
+    const uint64_t li = __ballot(listed);
+    int wave_base = 0;
+    if (lane == 0 && li) wave_base = atomicAdd(&block_count, __popcll(li));
+    wave_base = __shfl(wave_base, 0);
+    __syncthreads();
+    if (threadIdx.x == 0) block_base = block_count ? atomicAdd(&hdr->n_leaf_raw, block_count) : 0;
+    __syncthreads();
+    if (listed) {
+        const int pos = block_base + wave_base + __popcll(li & ((1ull << lane) - 1));
+        if (pos < L.cap) { L.key[pos] = key; L.mask_idx[pos] = (int32_t)t; }
+        else atomicOr(&hdr->overflow, 4);
+    }
+}
+
 // ---- partitioned path
 constexpr int kPartThreads = 1024;
 constexpr int kPartRowsPerThread = 4;
@@ -1050,29 +1113,6 @@ __global__ void __launch_bounds__(256) k_grid_ijk(TreeView t, int32_t* __restric
     }
 }
 
-// the eight children 2*ijk + {0,1}^3 of every active voxel, as rows 8*o .. 8*o+7 (child d = 4*di + 2*dj + dk)
-__global__ void k_grid_children(TreeView t, int32_t* __restrict__ ijk_out) {
-    const int f = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
-    if (f >= t.n_leaf) return;
-    const int lane = threadIdx.x & 63;
-    const fx_leaf* lf = t.leaf + f;
-    const uint64_t lt = (1ull << lane) - 1;
-    int64_t run = lf->offset;
-    for (int w = 0; w < 8; ++w) {
-        const uint64_t m = lf->mask[w];
-        if ((m >> lane) & 1) {
-            const int64_t o = run + __popcll(m & lt);
-            const int i = 2 * (lf->origin[0] + w), j = 2 * (lf->origin[1] + (lane >> 3)), k = 2 * (lf->origin[2] + (lane & 7));
-#pragma unroll
-            for (int d = 0; d < 8; ++d) {
-                int32_t* q = ijk_out + 3 * (8 * o + d);
-                q[0] = i + ((d >> 2) & 1); q[1] = j + ((d >> 1) & 1); q[2] = k + (d & 1);
-            }
-        }
-        run += __popcll(m);
-    }
-}
-
 __global__ void k_ijk_to_index(TreeView t, const int32_t* __restrict__ ijk, const int32_t* __restrict__ jidx,
                                int64_t n, int32_t* __restrict__ out) {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1133,10 +1173,18 @@ static fx_status scan_level(const fx_grid* g, LevelScan s, int cap_nodes, ScanSy
 // capacity was too small (the counts found so far are valid up to the overflowing level).
 constexpr int64_t kPartitionMinRows = 65536;   // below this the direct path's few kernels win
 
+// Where the leaves of a grid come from when not from rows of voxel coordinates: the leaves of another grid
+// (n_rows of build_attempt is then that grid's leaf count, and the direct path is taken).
+struct LeafSource {
+    enum Kind { kRows, kCoarsen, kPad, kSubdivide } kind = kRows;
+    const fx_grid* grid = nullptr;
+    int r = 0;                    // kPad: the padding
+    int32_t* d_bad = nullptr;     // kPad, kSubdivide: counter of leaves beyond the int32 coordinate range
+};
+
 static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const BatchRanges& d_joff, int32_t B,
                                int cap_upper, int cap_lower, int cap_leaf, bool direct, hipStream_t st, fx_grid** out,
-                               const fx_grid* coarsen_of = nullptr, const fx_grid* pad_of = nullptr, int pad_r = 0,
-                               int32_t* d_pad_bad = nullptr) {
+                               const LeafSource& from = LeafSource()) {
     fx_grid* g = new (std::nothrow) fx_grid();
     if (!g) { set_error("host allocation failed"); return FX_ENOMEM; }
     g->B = B; g->stream = st;
@@ -1157,10 +1205,13 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const Batch
                                                                   (int64_t)g->cap_leaf / kLeafChunk)) + 2;
     const bool partition = !direct && n_rows >= kPartitionMinRows;
     size_t n_slots = 0;                       // direct path: table slots, masks indexed by slot
+    const bool no_table = from.kind == LeafSource::kSubdivide;       // every leaf has one source: masks by (leaf, octant)
     if (!partition) { n_slots = 1024; while (n_slots < 2 * (size_t)g->cap_leaf) n_slots <<= 1; }
-    if (n_slots + (size_t)(pad_of ? n_rows : 0) > 0x7FFFFFFFull) { fx_grid_destroy(g); set_error("grid build: too many leaves"); return FX_ERANGE; }
+    if (no_table) n_slots = 0;
     // (a padded grid keeps the masks of the source grid's own leaves behind the table's)
-    const size_t n_masks = partition ? (size_t)g->cap_leaf : n_slots + (pad_of ? (size_t)n_rows : 0);
+    const size_t n_masks = partition ? (size_t)g->cap_leaf
+                         : no_table ? 8 * (size_t)n_rows : n_slots + (from.kind == LeafSource::kPad ? (size_t)n_rows : 0);
+    if (n_masks > 0x7FFFFFFFull) { fx_grid_destroy(g); set_error("grid build: too many leaves"); return FX_ERANGE; }
     int n_buckets = 64;
     while (n_buckets < kMaxBuckets && (int64_t)n_buckets * 1024 < n_rows) n_buckets <<= 1;
     const int n_part_wg = (int)((n_rows + kPartChunk - 1) / kPartChunk);
@@ -1173,7 +1224,8 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const Batch
     const size_t clear_bytes_slots = off;
     const size_t o_mask = take(sizeof(uint64_t) * 8 * n_masks);
     // the padded grid's masks are stored whole, the other direct builds OR theirs together
-    const size_t clear_bytes = partition ? clear_bytes_head : (pad_of ? clear_bytes_slots : off);
+    const bool whole_masks = from.kind == LeafSource::kPad || from.kind == LeafSource::kSubdivide;
+    const size_t clear_bytes = partition ? clear_bytes_head : (whole_masks ? clear_bytes_slots : off);
     const size_t o_key = take(sizeof(int4) * (size_t)g->cap_leaf);
     const size_t o_midx = take(sizeof(int32_t) * (size_t)g->cap_leaf);
     const size_t o_rep = take(sizeof(int32_t) * kMaxTiles);
@@ -1239,14 +1291,16 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const Batch
         } else {
             const unsigned nb_rows = (unsigned)((n_rows + 255) / 256);
             ProfScope ps(kProfVoxelsToLeaves, st);
-            if (coarsen_of)      // n_rows = the fine grid's leaves
-                k_coarse_leaves<<<nb_rows, 256, 0, st>>>(coarsen_of->view(), d_slots, (uint32_t)(n_slots - 1), L, g->d_hdr);
-            else if (pad_of) {   // n_rows = the source grid's leaves
-                k_pad_claim<<<(unsigned)((n_rows * 32 + kPadClaimThreads - 1) / kPadClaimThreads), kPadClaimThreads, 0, st>>>(pad_of->view(), pad_r, d_slots, (uint32_t)(n_slots - 1),
-                                                                                  L, g->d_hdr, d_pad_bad);
-                k_pad_masks<<<(unsigned)((g->cap_leaf + kPadWaves - 1) / kPadWaves), 64 * kPadWaves, 0, st>>>(pad_of->view(), pad_r, L,
-                                                                                                           g->d_hdr);
-            }
+            if (from.kind == LeafSource::kCoarsen)
+                k_coarse_leaves<<<nb_rows, 256, 0, st>>>(from.grid->view(), d_slots, (uint32_t)(n_slots - 1), L, g->d_hdr);
+            else if (from.kind == LeafSource::kPad) {
+                k_pad_claim<<<(unsigned)((n_rows * 32 + kPadClaimThreads - 1) / kPadClaimThreads), kPadClaimThreads, 0, st>>>(
+                    from.grid->view(), from.r, d_slots, (uint32_t)(n_slots - 1), L, g->d_hdr, from.d_bad);
+                k_pad_masks<<<(unsigned)((g->cap_leaf + kPadWaves - 1) / kPadWaves), 64 * kPadWaves, 0, st>>>(from.grid->view(), from.r,
+                                                                                                           L, g->d_hdr);
+            } else if (from.kind == LeafSource::kSubdivide)
+                k_subdivide_leaves<<<(unsigned)((n_rows * 8 + kSubdivideThreads - 1) / kSubdivideThreads), kSubdivideThreads, 0, st>>>(
+                    from.grid->view(), L, g->d_hdr, from.d_bad);
             else
                 k_voxels_to_leaves<<<nb_rows, 256, 0, st>>>(d_ijk, n_rows, d_joff, B, d_slots, (uint32_t)(n_slots - 1), L, g->d_hdr);
         }
@@ -1502,14 +1556,6 @@ extern "C" fx_status fx_build_index_grid_from_points(const float* d_xyz, int64_t
     return FX_OK;
 }
 
-// (begin, end) voxel rows of every grid of `g`, multiplied by `rows_per_voxel`: the row ranges of an array
-// derived from the grid's voxels
-static std::vector<int64_t> scaled_voxel_ranges(const fx_grid* g, int64_t rows_per_voxel) {
-    std::vector<int64_t> r(2 * (size_t)std::max(g->B, 1), 0);
-    for (int b = 0; b < g->B; ++b) { r[2 * b] = rows_per_voxel * g->h_vox_base[b]; r[2 * b + 1] = rows_per_voxel * g->h_vox_base[b + 1]; }
-    return r;
-}
-
 extern "C" fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** out) {
     if (!g || !out) { set_error("fx_grid_coarsen2: null pointer"); return FX_EINVAL; }
     hipStream_t st = (hipStream_t)stream;
@@ -1517,7 +1563,9 @@ extern "C" fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** 
     // counts as capacities always fits; its leaves come from the fine leaves, not from a row per voxel.
     fx_grid* o = nullptr;
     const BatchRanges none{nullptr, 0, 0};
-    FX_TRY(build_attempt(nullptr, g->hdr.n_leaf, none, g->B, g->hdr.n_upper, g->hdr.n_lower, g->hdr.n_leaf, true, st, &o, g));
+    LeafSource from;
+    from.kind = LeafSource::kCoarsen; from.grid = g;
+    FX_TRY(build_attempt(nullptr, g->hdr.n_leaf, none, g->B, g->hdr.n_upper, g->hdr.n_lower, g->hdr.n_leaf, true, st, &o, from));
     if (o->hdr.overflow) {
         const int ov = o->hdr.overflow;
         fx_grid_destroy(o);
@@ -1533,18 +1581,32 @@ extern "C" fx_status fx_grid_subdivide2(const fx_grid* g, void* stream, fx_grid*
     hipStream_t st = (hipStream_t)stream;
     const int64_t n = g->hdr.n_voxels;
     if (8 * n > 0x7FFFFFFFll) { set_error("fx_grid_subdivide2: more than 2^31-1 voxels"); return FX_ERANGE; }
-    int32_t* d_c = nullptr;
-    FX_TRY(dev_alloc((void**)&d_c, sizeof(int32_t) * 3 * 8 * (size_t)std::max<int64_t>(n, 1), st));
-    if (g->hdr.n_leaf > 0) {
-        const int64_t threads = (int64_t)g->hdr.n_leaf * 64;
-        ProfScope ps(kProfGridIjk, st);
-        k_grid_children<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(g->view(), d_c);
-    }
-    const std::vector<int64_t> ranges = scaled_voxel_ranges(g, 8);
+    // The fine grid's leaves are the non-empty octants of the coarse leaves (k_subdivide_leaves); a fine node of
+    // any level covers an octant of the coarse node of that level, so eight times the coarse counts always fit.
+    const int64_t cap_leaf = 8 * (int64_t)g->hdr.n_leaf, cap_lower = 8 * (int64_t)g->hdr.n_lower, cap_upper = 8 * (int64_t)g->hdr.n_upper;
+    if (cap_leaf > 0x7FFFFFFFll / 8) { set_error("fx_grid_subdivide2: too many leaves"); return FX_ERANGE; }
+    int32_t* d_bad = nullptr;     // octants whose doubled coordinates would leave the int32 range
+    FX_TRY(dev_alloc((void**)&d_bad, 16, st));
+    if (hipMemsetAsync(d_bad, 0, sizeof(int32_t), st) != hipSuccess) { dev_free(d_bad, st); set_error("fx_grid_subdivide2: fill failed"); return FX_EDEVICE; }
+    LeafSource from;
+    from.kind = LeafSource::kSubdivide; from.grid = g; from.d_bad = d_bad;
+    const BatchRanges none{nullptr, 0, 0};
     fx_grid* o = nullptr;
-    const fx_status rc = build_index_grid_device(d_c, 8 * n, ranges.data(), g->B, st, &o);
-    dev_free(d_c, st);
-    if (rc != FX_OK) return rc;
+    fx_status rc = build_attempt(nullptr, g->hdr.n_leaf, none, g->B, (int)cap_upper, (int)cap_lower, (int)cap_leaf, true, st, &o, from);
+    int32_t bad = 0;
+    if (rc == FX_OK && hipMemcpy(&bad, d_bad, sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess) {
+        rc = FX_EDEVICE; set_error("fx_grid_subdivide2: read-back failed");
+    }
+    dev_free(d_bad, st);
+    if (rc == FX_OK && bad > 0) {
+        set_error("fx_grid_subdivide2: %d leaves hold coordinates beyond +-2^30, whose doubles leave the int32 coordinate limits", bad);
+        rc = FX_ERANGE;
+    }
+    if (rc == FX_OK && o->hdr.overflow) {
+        set_error("fx_grid_subdivide2: the fine grid did not fit eight times the coarse grid's node counts (flags %d)", o->hdr.overflow);
+        rc = (o->hdr.overflow & 16) ? FX_ERANGE : FX_EDEVICE;
+    }
+    if (rc != FX_OK) { if (o) fx_grid_destroy(o); return rc; }
     *out = o;
     return FX_OK;
 }
@@ -1568,9 +1630,11 @@ extern "C" fx_status fx_grid_pad(const fx_grid* g, int32_t r, void* stream, fx_g
     fx_grid* o = nullptr;
     fx_status rc = FX_OK;
     const BatchRanges none{nullptr, 0, 0};
+    LeafSource from;
+    from.kind = LeafSource::kPad; from.grid = g; from.r = r; from.d_bad = d_bad;
     for (int attempt = 0; attempt < 6; ++attempt) {
         if (hipMemsetAsync(d_bad, 0, sizeof(int32_t), st) != hipSuccess) { rc = FX_EDEVICE; set_error("fx_grid_pad: fill failed"); break; }
-        rc = build_attempt(nullptr, nl, none, g->B, (int)cap_upper, (int)cap_lower, (int)cap_leaf, true, st, &o, nullptr, g, r, d_bad);
+        rc = build_attempt(nullptr, nl, none, g->B, (int)cap_upper, (int)cap_lower, (int)cap_leaf, true, st, &o, from);
         if (rc != FX_OK) break;
         const int ov = o->hdr.overflow;
         if (!ov) break;

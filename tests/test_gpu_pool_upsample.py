@@ -206,3 +206,20 @@ def test_gradients_on_empty_grid_and_full_size_identities():
     assert float(count[:, 0].sum()) == g.num_voxels and float(count.min()) >= 1 and float(count.max()) <= 8
     ga = fx.pool2_bwd(km, torch.ones((km.n_out, 8), dtype=torch.float32, device="cuda"), "avg")
     assert torch.equal(ga, fx.upsample2(km, 1.0 / count))
+
+
+def test_subdivision_of_a_batch_with_negative_coordinates_and_its_limits():
+    grids = [np.random.default_rng(871).integers(-70, 70, size=(3000, 3)).astype(np.int32), np.zeros((0, 3), np.int32),
+             np.random.default_rng(872).integers(4000, 4200, size=(2000, 3)).astype(np.int32),
+             np.array([[-1, -8, 7], [2 ** 30 - 1, -2 ** 30, 0]], np.int32)]
+    ijk, jo = G.make_jagged(grids)
+    g, og = H.both_grids(ijk, jo)
+    fine, ofine = g.subdivide2(), og.subdivide2()
+    H.check_grid(fine, ofine)
+    assert fine.num_voxels == 8 * g.num_voxels
+    H.check_grid(fine.coarsen2(), og)
+    # one step beyond +-2^30 the doubled coordinate no longer fits
+    for c in (2 ** 30, -2 ** 30 - 1):
+        far, _ = H.both_grids(np.array([[0, c, 0]], np.int32), np.array([[0, 1]]))
+        with pytest.raises(fx.FxError, match="coordinate limits"):
+            far.subdivide2()
