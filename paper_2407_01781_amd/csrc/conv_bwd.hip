@@ -12,10 +12,10 @@
 // straight to the inputs the map names (k_dgrad_strided).
 //
 // Weight gradient: a contraction over voxels, so both MFMA operands must hold 8 consecutive
-// *voxels* per lane while the rows in memory hold consecutive *channels*.  The gout tile is
-// transposed once while it is staged in LDS; the gathered feature rows are transposed on the
-// matrix unit itself (a multiplication with the identity leaves a 32x32 block of them in the
-// accumulator layout, which is exactly the operand layout with voxels along k), see k_wgrad_mfma.
+// *voxels* per lane while the rows in memory hold consecutive *channels*.  Both operands are staged
+// in LDS as rows and read with the transposing LDS read of this hardware (ds_read_b64_tr_b16: four
+// lanes that each address four channels of a different voxel's row receive four voxels of one
+// channel each), see k_wgrad_mfma.
 #include "conv_common.h"
 
 namespace fx {
@@ -328,42 +328,55 @@ __global__ void k_conv_transpose_scalar(const int32_t* __restrict__ nbmap, int64
 // A workgroup owns a block of 32 input channels x 64 output channels of every gw[kappa] and a
 // contiguous range of tiles; its 16 waves split the offsets (wave w: kappa = w, w+16), so a wave
 // keeps 2 offsets x 2 accumulator tiles (32 ci x 32 co) in registers over the whole range, and four
-// waves per SIMD hide each other's LDS and matrix latencies (the per-block chain read -> identity
-// product -> rounding -> products is not software-pipelined).  Per tile the workgroup stages, single-buffered: the tile's input rows (32 channels,
-// the forward kernel's LDS row layout, so the map's precomputed LDS offsets apply), its id
-// blocks, and the gout rows of its 512 outputs transposed to [channel][slot] (2 bytes per element,
-// row stride padded by 8 bytes so a fragment read of 32 channels spreads over all banks).
+// waves per SIMD hide each other's LDS and matrix latencies.  Per tile the workgroup stages,
+// single-buffered and all with loads that go straight from global memory to LDS: the tile's input rows
+// (32 channels, the forward kernel's LDS row layout, so the map's precomputed LDS offsets apply), its id
+// blocks, and the gout rows of its 512 output slots (64 channels = 128 bytes per slot; 16-byte piece p of
+// slot s sits at position p ^ 4*((s >> 1) & 1), which spreads a fragment read over all banks).
+//
+// Transposing read (tr_read4): in every group of 16 lanes, lane 4q+e receives, as element j, element e of
+// the 8 bytes that lane 4j+q addresses.  With lane 4j+q pointing at channels 4q..4q+3 of voxel j's row,
+// lane c of the group ends up with channel c of voxels 0..3: rows in, operand columns out.
 //
 // For one (column block g, offset kappa) a wave:
-//   1. reads the A fragments of the gathered rows exactly as the forward kernel reads its B
-//      fragments (lane (voxel n, half h): channels 8h..8h+7 and 16+8h..16+8h+7 of the row of voxel n);
-//   2. multiplies them with the identity: D[voxel][channel] = feat[voxel][channel], which in the
-//      accumulator layout gives lane (channel, h) the voxels 8b+4h+r (b, r = 0..3) in register 4b+r;
-//   3. rounds those 16 values to the storage type (exact) -- they are the A operand
-//      [channel][voxel] of two k-steps whose k index runs over voxels in the order
-//      (b, r) -> 16*ks + 8*(b&1) + 4h + r;
-//   4. reads the matching B fragments from the transposed gout tile (two 8-byte reads per k-step:
-//      slots 32g + 16ks + 4h .. +3 and +8 .. +11 of channel n) and accumulates
+//   1. takes, per k-step ks and half t, the id of voxel 16ks + 8h + 4t + j of the block (h = lane / 32,
+//      j = (lane / 4) % 4) -- the row its address contributes -- and reads the A fragment
+//      [channel lane % 32][voxels 16ks + 8h .. + 7] of the gathered rows with two transposing reads;
+//   2. reads the B fragments [voxel][co] of the gout slots 32g + 16ks + 8h .. + 7 the same way
+//      (channels 32cb + lane % 32) and accumulates
 //      gw[kappa][ci][co] += sum_voxel feat[voxel][ci] * gout[voxel][co].
 // A voxel of the block without that tap reads the zero row and adds nothing; a slot past the end
-// of the last tile has a zero gout column.
+// of the last tile has a zero gout row.  Tiles whose rows are not all staged in LDS keep the older form
+// of step 1: the lane reads the row of voxel lane % 32 (from LDS or from global memory), and a product with
+// the identity on the matrix unit leaves the block in the accumulator layout, which is the operand layout
+// with voxels along k; rounding back to the storage type is exact.
 // Partial sums go to part[range][kappa][ci][co] (fp32); k_wgrad_reduce adds the ranges in
 // ascending order, so the result does not depend on scheduling.
 constexpr int kWgWaves = 16;
 constexpr int kWgThreads = 64 * kWgWaves;
 constexpr int kWgCi = kCinChunk;            // 32: the row chunk staged in LDS
 constexpr int kWgCo = 64;
-constexpr int kGtStride = kTileT * 2 + 8;   // bytes per channel of the transposed gout tile
+constexpr int kGoutRowBytes = kWgCo * 2;    // one slot of the staged gout tile
+constexpr int kGoutSlabs = kTileT * kGoutRowBytes / 1024;     // 1 KB slabs: 8 slots each
+constexpr int kGoutSlabsPerWave = kGoutSlabs / kWgWaves;
 constexpr int kWgOffsetsPerWave = (kMaxK3Tiled + kWgWaves - 1) / kWgWaves;   // 4
 
 struct WgradLds {
     unsigned char rows[kRowBufBytes];
     unsigned char blocks[kBlockBufBytes];
-    unsigned char gt[kWgCo * kGtStride];
+    unsigned char gt[kTileT * kGoutRowBytes];
 };
 static_assert(sizeof(WgradLds) <= 160 * 1024, "LDS budget of one compute unit");
-static_assert(kWgThreads % kTileT == 0 && (kWgCo / 8) % (kWgThreads / kTileT) == 0, "threads per output slot when staging gout");
+static_assert(kGoutSlabs % kWgWaves == 0, "gout slabs per wave");
 static_assert(kGroupsPerWave == 4 && kTileWaves == 4, "id blocks of four column blocks, 8 bytes per voxel");
+
+typedef short tr_v4s __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x2 tr_read4(const unsigned char* p) {
+    const tr_v4s v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr_v4s*)p);
+    u32x2 w;
+    __builtin_memcpy(&w, &v, 8);
+    return w;
+}
 
 template <typename T>
 __global__ void __launch_bounds__(kWgThreads, 1)
@@ -414,13 +427,12 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][cb][v] = 0.f;
 
-    const uint32_t hsel = (uint32_t)h << 4;
-    // kSlotThreads threads stage one output slot, each kPieces 16-byte pieces of its gout row
-    constexpr int kSlotThreads = kWgThreads / kTileT, kPieces = kWgCo / 8 / kSlotThreads;
+    // what this lane's address contributes to a transposing read: voxel jv of four, channels 16*g1 + 4*q .. + 3
+    const int q = lane & 3, jv = (lane >> 2) & 3, g1 = (lane >> 4) & 1;
+    const uint32_t a_piece = (uint32_t)(2 * g1 + (q >> 1)) << 4, half8 = (uint32_t)(q & 1) << 3;
     constexpr int kWgSlabs = ((kRowCap + 15) / 16 + kWgWaves - 1) / kWgWaves;   // 1 KB row slabs per wave
-    const int slot = tid % kTileT, part_of_row = tid / kTileT;
     int32_t nx_gr[kWgSlabs];
-    int nx_local = 0;
+    int nx_local[kGoutSlabsPerWave];      // output row (inside the tile) of the slot this lane stages in each of its slabs
     auto resolve = [&](int64_t t) {
         const TileHeader* Ht = tile_hdr + t;
         const int fl = uni(Ht->flags), wl = uni(Ht->win_lo), wn = uni(Ht->win_n), nl = uni(Ht->n_list);
@@ -432,7 +444,8 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
             nx_gr[j] = -1;
             if (r < ns) nx_gr[j] = r < wn ? wl + r : rows_t[r - wn];
         }
-        nx_local = tile_perm[t * kTileT + slot];
+#pragma unroll
+        for (int j = 0; j < kGoutSlabsPerWave; ++j) nx_local[j] = tile_perm[t * kTileT + 8 * (wave + kWgWaves * j) + (lane >> 3)];
     };
     if (t0 < t1) resolve(t0);
     for (int64_t tile = t0; tile < t1; ++tile) {
@@ -452,20 +465,33 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
 #pragma unroll
         for (int g = 0; g < kGroupsPerTile; ++g) gmask[g] = (uint32_t)uni((int)H->group_mask[g]);
 
-        // ---- stage: input rows (32 channels of this block), id blocks, transposed gout.  The global
-        // row of every slab piece and the output row of the thread's slot were resolved while the
+        // ---- stage: input rows (32 channels of this block), id blocks, gout rows.  The global
+        // row of every slab piece and the output rows of the lane's slots were resolved while the
         // previous tile was staged, so all of this tile's loads leave at once.
         {
             const int piece = (lane & 3) ^ ((lane >> 4) & 3);
             int32_t gr[kWgSlabs];
 #pragma unroll
             for (int j = 0; j < kWgSlabs; ++j) gr[j] = nx_gr[j];
-            const int local = nx_local;
+            int local[kGoutSlabsPerWave];
+#pragma unroll
+            for (int j = 0; j < kGoutSlabsPerWave; ++j) local[j] = nx_local[j];
 #pragma unroll
             for (int j = 0; j < kWgSlabs; ++j) {
                 if (gr[j] >= 0) {
                     const uint16_t* src = feat + (int64_t)gr[j] * C_in + cib * kWgCi + piece * 8;
                     __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(L.rows + (wave + kWgWaves * j) * 1024), 16, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kGoutSlabsPerWave; ++j) {
+                const int slab = wave + kWgWaves * j, slot = 8 * slab + (lane >> 3);
+                const int gpiece = (lane & 7) ^ (((slot >> 1) & 1) << 2);        // the piece stored at position lane & 7
+                if (local[j] < n_valid) {
+                    const uint16_t* src = gout + (tile * kTileT + local[j]) * (int64_t)C_out + cob * kWgCo + gpiece * 8;
+                    __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(L.gt + slab * 1024), 16, 0, 0);
+                } else {
+                    *reinterpret_cast<u32x4*>(L.gt + slab * 1024 + lane * 16) = u32x4{0, 0, 0, 0};
                 }
             }
             const unsigned char* bsrc =
@@ -475,29 +501,7 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
                 const int off = s * 1024 + lane * 16;
                 if (off < bytes) __builtin_amdgcn_global_load_lds(bsrc + off, (lds_ptr_t)(L.blocks + s * 1024), 16, 0, 0);
             }
-            const uint16_t* grow = gout + (tile * kTileT + local) * (int64_t)C_out + cob * kWgCo + part_of_row * kPieces * 8;
-            u32x4 gv[kPieces];
-#pragma unroll
-            for (int q = 0; q < kPieces; ++q)
-                gv[q] = local < n_valid ? *reinterpret_cast<const u32x4*>(grow + q * 8) : u32x4{0, 0, 0, 0};
             if (tile + 1 < t1) resolve(tile + 1);
-            // Transposed store, two slots per 4-byte word: a thread pair (slots 2p, 2p+1) exchanges words
-            // across lanes; the even thread then writes the channels of the low halves (channel 2j of
-            // word j), the odd thread those of the high halves (channel 2j+1), each as the word
-            // (value of slot 2p) | (value of slot 2p+1) << 16 at gt[channel][slot 2p].
-            const int odd = tid & 1;
-#pragma unroll
-            for (int q = 0; q < kPieces; ++q)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t mine = gv[q][j];
-                    const uint32_t other = (uint32_t)__shfl_xor((int)mine, 1);
-                    const uint32_t lo_slot = odd ? other : mine, hi_slot = odd ? mine : other;   // words of slots 2p, 2p+1
-                    const uint32_t word = odd ? ((lo_slot >> 16) | (hi_slot & 0xFFFF0000u))
-                                              : ((lo_slot & 0xFFFFu) | (hi_slot << 16));
-                    const int ch = (part_of_row * kPieces + q) * 8 + 2 * j + odd;
-                    *reinterpret_cast<uint32_t*>(L.gt + ch * kGtStride + (slot & ~1) * 2) = word;
-                }
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
@@ -512,42 +516,63 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
                 const uint32_t wm = wmask[fw];
                 if (!((wm >> kappa) & 1u)) continue;
                 const int b = block0[fw] + __popc(wm & ((1u << kappa) - 1u));
-                const u32x2 ids = *reinterpret_cast<const u32x2*>(L.blocks + ((size_t)b * kGroup + n) * 8);
+                const unsigned char* blk = L.blocks + (size_t)b * kGroup * 8;
+                u32x2 ids = u32x2{0, 0}, idv[2][2];
+                if (general) {
+                    ids = *reinterpret_cast<const u32x2*>(blk + n * 8);
+                } else {
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                        for (int t = 0; t < 2; ++t) idv[ks][t] = *reinterpret_cast<const u32x2*>(blk + (16 * ks + 8 * h + 4 * t + jv) * 8);
+                }
 #pragma unroll
                 for (int gi = 0; gi < kGroupsPerWave; ++gi) {
                     const int g = tile_group_of(fw, gi);
                     if (!((gmask[g] >> kappa) & 1u)) continue;
-                    const uint32_t id = (ids[gi >> 1] >> (16 * (gi & 1))) & 0xFFFFu;
-                    vec8 a0, a1;
+                    vec8 fT[2];
                     if (!general) {
-                        const uint32_t ad = id ^ hsel;
-                        a0 = *reinterpret_cast<const vec8*>(L.rows + ad);
-                        a1 = *reinterpret_cast<const vec8*>(L.rows + (ad ^ 32u));
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks) {
+                            u32x2 w[2];
+#pragma unroll
+                            for (int t = 0; t < 2; ++t) {
+                                const uint32_t id = (idv[ks][t][gi >> 1] >> (16 * (gi & 1))) & 0xFFFFu;
+                                w[t] = tr_read4(L.rows + ((id ^ a_piece) + half8));
+                            }
+                            fT[ks] = vec8_from_words<T>(u32x4{w[0][0], w[0][1], w[1][0], w[1][1]});
+                        }
                     } else {
+                        const uint32_t id = (ids[gi >> 1] >> (16 * (gi & 1))) & 0xFFFFu;
                         const bool staged = id < (uint32_t)n_staged;
                         const int row = staged ? (int)id : kRowCap;
-                        a0 = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, h));
-                        a1 = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, h + 2));
+                        vec8 a0 = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, h));
+                        vec8 a1 = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, h + 2));
                         if (!staged && id != kNoRow) {
                             const int64_t gr = id < (uint32_t)win_n ? (int64_t)win_lo + id : (int64_t)my_rows[id - win_n];
                             const uint16_t* src = feat + gr * C_in + cib * kWgCi + h * 8;
                             a0 = *reinterpret_cast<const vec8*>(src);
                             a1 = *reinterpret_cast<const vec8*>(src + 16);
                         }
-                    }
-                    f32x16 t;
+                        f32x16 t;
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) t[v] = 0.f;
-                    t = Elem<T>::mfma(a0, ident[0], t);
-                    t = Elem<T>::mfma(a1, ident[1], t);
-                    const vec8 fT[2] = {pack8<T>(t, 0), pack8<T>(t, 8)};
+                        for (int v = 0; v < 16; ++v) t[v] = 0.f;
+                        t = Elem<T>::mfma(a0, ident[0], t);
+                        t = Elem<T>::mfma(a1, ident[1], t);
+                        fT[0] = pack8<T>(t, 0);
+                        fT[1] = pack8<T>(t, 8);
+                    }
 #pragma unroll
                     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
                         for (int ks = 0; ks < 2; ++ks) {
-                            const unsigned char* src = L.gt + (cb * 32 + n) * kGtStride + (g * kGroup + 16 * ks + 4 * h) * 2;
-                            const u32x2 lo = *reinterpret_cast<const u32x2*>(src);
-                            const u32x2 hi = *reinterpret_cast<const u32x2*>(src + 16);
+                            // slots 32g + 16ks + 8h + jv (+ 4), channels 32cb + 16g1 + 4q .. + 3: piece 4cb + 2g1 + q/2
+                            // (after the identity product the A fragment holds voxels 4h .. 4h + 3 and 8 + 4h .. 8 + 4h + 3 instead)
+                            const int slot = g * kGroup + 16 * ks + (general ? 4 : 8) * h + jv;
+                            const uint32_t pos = (uint32_t)((4 * cb + 2 * g1 + (q >> 1)) ^ (((slot >> 1) & 1) << 2)) << 4;
+                            const unsigned char* src = L.gt + slot * kGoutRowBytes + pos + half8;
+                            const u32x2 lo = tr_read4(src);
+                            const u32x2 hi = tr_read4(src + (general ? 8 : 4) * kGoutRowBytes);
                             acc[j][cb] = Elem<T>::mfma(fT[ks], vec8_from_words<T>(u32x4{lo[0], lo[1], hi[0], hi[1]}), acc[j][cb]);
                         }
                 }
