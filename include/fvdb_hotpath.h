@@ -297,9 +297,10 @@ fx_status fx_sparse_conv_fwd_noalloc(const fx_kmap* km, const void* d_feat, fx_d
  * (a tiled map of its own, built on the first such call and kept with km; no atomics, fixed order).
  * MFMA paths: FX_F16 / FX_BF16 with C_in % 64 == 0 and C_out % 64 == 0 (bwd_data: C_in % 64 == 0
  * and C_out % 32 == 0; bwd_weight: C_in % 32 == 0 and C_out % 64 == 0) on tiled maps; everything
- * else takes scalar kernels.  In the MFMA weight-gradient kernel operands are transposed by a
- * multiplication with the identity, so a non-finite value in feat or gout makes the whole
- * 32-channel block of gw that it touches NaN rather than only its own row or column.
+ * else takes scalar kernels.  In the MFMA weight-gradient kernel a tile whose input rows do not all
+ * fit the kernel's local memory has its operand transposed by a multiplication with the identity; on
+ * such a tile a non-finite value in feat makes the whole 32-channel block of gw that it touches NaN
+ * rather than only its own row.
  */
 fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_gout, fx_dtype dt, const void* d_w,
                                   int32_t C_in, int32_t C_out, void* d_gin, fx_dtype out_dt, void* stream);
