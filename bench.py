@@ -317,6 +317,14 @@ def main():
         ops["conv_transpose_effective_TFLOPs"] = 2.0 * n_in * 2 * c * c / (t_tc * 1e-3) / 1e12
         tc_bytes = (n_c * 2 * c + n_in * c) * elem
         ops["conv_transpose_GBs"] = tc_bytes / (t_tc * 1e-3) / 1e9
+    # the grids of the two directions, made from the input grid's leaves: the coarse grid of pooling / strided
+    # convolution and the subdivided grid of upsampling (8 children per voxel)
+    ops["grid_coarsen_ms"] = b2b(lambda: g.coarsen2(), reps=5)
+    if 8 * n_in <= 2 ** 31 - 1:
+        g_fine = g.subdivide2()
+        ops["grid_subdivide_ms"] = b2b(lambda: g.subdivide2(), reps=5)
+        ops["n_fine"] = g_fine.num_voxels
+        del g_fine
     del pooled
 
     # ---- the low-depth operator (Sec. 3.5 scenario 1) on the volumetric class of Sec. 4.1.3 (leaf occupancy

@@ -223,3 +223,23 @@ def test_subdivision_of_a_batch_with_negative_coordinates_and_its_limits():
         far, _ = H.both_grids(np.array([[0, c, 0]], np.int32), np.array([[0, 1]]))
         with pytest.raises(fx.FxError, match="coordinate limits"):
             far.subdivide2()
+
+
+def test_full_size_subdivision_and_back():
+    """Benchmark-size grid: the subdivided grid has eight voxels per voxel, every child is active, and its coarse
+    grid is the grid it came from, leaf record for leaf record (checked against the oracle's grid)."""
+    w = G.workload("lidar1m")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    fine = g.subdivide2()
+    assert fine.num_voxels == 8 * og.num_voxels
+    H.check_grid(fine.coarsen2(), og)
+    rng = np.random.default_rng(881)
+    oc, ob = og.ijk()
+    rows = np.sort(rng.choice(og.num_voxels, 4096, replace=False))
+    for d in (0, 3, 7):
+        child = 2 * oc[rows] + np.array([(d >> 2) & 1, (d >> 1) & 1, d & 1], np.int32)
+        idx = fine.ijk_to_index(torch.from_numpy(child.astype(np.int32)).cuda(), torch.from_numpy(ob[rows]).cuda()).cpu().numpy()
+        assert (idx >= 0).all() and np.unique(idx).size == rows.size
+    km = fx.build_kernel_map(fine, 2, 2)
+    assert km.n_out == og.num_voxels and km.info()[0] == 8 * og.num_voxels
