@@ -168,7 +168,7 @@ fx_status fx_grid_subdivide2(const fx_grid* g, void* stream, fx_grid** out);
  * the case that changes topology): active set = every voxel within Chebyshev distance r of an active one,
  * { p + d : p active, d in {-r..r}^3 }, per grid of the batch.  r = 0 gives a copy; r = 1 is the set of sites
  * a 3x3x3 stencil reaches the grid from.  0 <= r <= 8 (FX_EINVAL below, FX_EUNSUPPORTED above);
- * FX_ERANGE if (2r+1)^3 * voxels exceeds 2^31-1 or a voxel lies within r of the int32 coordinate limits.
+ * FX_ERANGE if the padded grid has more than 2^31-1 voxels or a voxel lies within r of the int32 coordinate limits.
  * The caller owns *out.  Synchronises `stream`. */
 fx_status fx_grid_pad(const fx_grid* g, int32_t r, void* stream, fx_grid** out);
 

@@ -1616,9 +1616,6 @@ extern "C" fx_status fx_grid_pad(const fx_grid* g, int32_t r, void* stream, fx_g
     if (r < 0) { set_error("fx_grid_pad: negative padding %d", r); return FX_EINVAL; }
     if (r > 8) { set_error("fx_grid_pad: padding %d is above the supported 8 voxels", r); return FX_EUNSUPPORTED; }
     hipStream_t st = (hipStream_t)stream;
-    const int64_t n = g->hdr.n_voxels;
-    const int64_t w3 = (int64_t)(2 * r + 1) * (2 * r + 1) * (2 * r + 1);
-    if (w3 * n > 0x7FFFFFFFll) { set_error("fx_grid_pad: more than 2^31-1 candidate voxels"); return FX_ERANGE; }
     if ((int64_t)g->hdr.n_leaf * 27 > 0x7FFFFFFFll) { set_error("fx_grid_pad: too many leaves"); return FX_ERANGE; }
     int32_t* d_bad = nullptr;     // pieces that would leave the int32 coordinate range
     FX_TRY(dev_alloc((void**)&d_bad, 16, st));
@@ -1640,8 +1637,9 @@ extern "C" fx_status fx_grid_pad(const fx_grid* g, int32_t r, void* stream, fx_g
         if (!ov) break;
         if (ov & (8 | 16 | 128) || attempt == 5) {
             fx_grid_destroy(o); o = nullptr;
-            set_error(ov & 8 ? "more than %d root tiles (4096^3 regions) in the batch" : "fx_grid_pad: the build failed (flags %d)",
-                      ov & 8 ? kMaxTiles : ov);
+            if (ov & 8) set_error("more than %d root tiles (4096^3 regions) in the batch", kMaxTiles);
+            else if (ov & 16) set_error("fx_grid_pad: the padded grid has more than 2^31-1 active voxels");
+            else set_error("fx_grid_pad: the build failed (flags %d)", ov);
             rc = ov & (8 | 16) ? FX_ERANGE : FX_EDEVICE;
             break;
         }

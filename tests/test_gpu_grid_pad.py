@@ -56,6 +56,18 @@ def test_padding_that_multiplies_the_nodes(stride, side):
     assert gp.num_voxels == 27 * len(ijk) and gp.counts()[0] == 8 * len(ijk)
 
 
+def test_wide_padding_of_a_large_grid_composes():
+    """r = 8 on a grid whose (2r+1)^3 candidates per voxel would not fit 32 bits: no candidate is ever made, and
+    padding by 8 is padding by 3 and then by 5 (dilations by cubes compose), leaf record for leaf record."""
+    ijk, jo = G.workload("lidar1m").jagged_ijk()
+    g = fx.build_index_grid(torch.from_numpy(ijk).cuda(), jo)
+    assert 17 ** 3 * g.num_voxels > 2 ** 31 - 1
+    p8, p35 = g.pad(8), g.pad(3).pad(5)
+    assert p8.num_voxels == p35.num_voxels and p8.counts() == p35.counts()
+    assert p8.leaf_table().tobytes() == p35.leaf_table().tobytes()
+    assert np.array_equal(p8.voxel_joffsets(), p35.voxel_joffsets())
+
+
 def test_padding_edge_cases_and_errors():
     e, _ = H.both_grids(np.zeros((0, 3), np.int32), np.array([[0, 0]]))
     assert e.pad(1).num_voxels == 0 and e.pad(0).num_voxels == 0
