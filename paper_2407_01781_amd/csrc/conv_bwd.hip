@@ -26,13 +26,6 @@ template <typename T> __device__ __forceinline__ uint16_t one_bits();
 template <> __device__ __forceinline__ uint16_t one_bits<__bf16>() { return 0x3F80; }
 template <> __device__ __forceinline__ uint16_t one_bits<_Float16>() { return 0x3C00; }
 
-template <typename T>
-__device__ __forceinline__ typename Elem<T>::vec8 vec8_from_words(u32x4 w) {
-    typename Elem<T>::vec8 v;
-    __builtin_memcpy(&v, &w, 16);
-    return v;
-}
-
 // eight fp32 values that are exactly representable in T -> one operand fragment
 template <typename T>
 __device__ __forceinline__ typename Elem<T>::vec8 pack8(const f32x16& t, int first) {
@@ -369,14 +362,6 @@ struct WgradLds {
 static_assert(sizeof(WgradLds) <= 160 * 1024, "LDS budget of one compute unit");
 static_assert(kGoutSlabs % kWgWaves == 0, "gout slabs per wave");
 static_assert(kGroupsPerWave == 4 && kTileWaves == 4, "id blocks of four column blocks, 8 bytes per voxel");
-
-typedef short tr_v4s __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ u32x2 tr_read4(const unsigned char* p) {
-    const tr_v4s v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr_v4s*)p);
-    u32x2 w;
-    __builtin_memcpy(&w, &v, 8);
-    return w;
-}
 
 template <typename T>
 __global__ void __launch_bounds__(kWgThreads, 1)
@@ -866,9 +851,15 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
     }
     // fp32 at low depth on a 3x3x3 submanifold map: the leaf-window kernel sums on the matrix units straight from
     // the grid, where everything below would take the scalar kernel (option leaf_dispatch = 0 keeps that one)
+    // The 16-bit types at depth >= 32 take it on locally dense grids only (mean leaf occupancy of 0.40 and above, the
+    // forward pass's rule): there the tiles of the map need more rows than the tile kernel's LDS holds
+    // (option leaf_dispatch = 1 takes it on any grid).
     if (km->K == 3 && km->stride == 1 && km->gin == km->gout && leaf_wgrad_shape_supported(dt, C_in, C_out) &&
         !force_scalar()) {
-        if (option(kOptLeafDispatch) != 0)
+        const int ld = option(kOptLeafDispatch);
+        const double occupancy = (double)km->n_in / (512.0 * (double)std::max<int64_t>(1, km->gin->hdr.n_leaf));
+        const bool take = dt == FX_F32 ? ld != 0 : (ld >= 0 ? ld == 1 : occupancy >= 0.40);
+        if (take)
             return leaf_wgrad("sparse convolution weight gradient (leaf-window kernel)", km->gin, d_feat, d_gout, dt, C_in,
                               C_out, d_gw, out_dt, st);
     }

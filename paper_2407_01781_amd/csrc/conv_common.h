@@ -155,13 +155,34 @@ inline bool leaf_shape_supported(fx_dtype dt, int C_contract, int C_produce) {
     return C_contract % 32 == 0 && C_produce % 64 == 0;
 }
 
-// Weight gradient of the 3x3x3 submanifold convolution from the leaf window (fp32, low depth), and the ordered
+template <typename T>
+__device__ __forceinline__ typename Elem<T>::vec8 vec8_from_words(u32x4 w) {
+    typename Elem<T>::vec8 v;
+    __builtin_memcpy(&v, &w, 16);
+    return v;
+}
+
+// The transposing LDS read of 16-bit elements (ds_read_b64_tr_b16): in every group of 16 lanes, lane 4q + e receives,
+// as element j, element e of the 8 bytes that lane 4j + q addresses.  With lane 4j + q pointing at channels
+// 4q .. 4q + 3 of voxel j's row, lane c of the group ends up with channel c of voxels 0..3: rows in, operand columns
+// with the voxels along k out.  All 64 lanes must be active.
+typedef short tr_v4s __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x2 tr_read4(const unsigned char* p) {
+    const tr_v4s v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr_v4s*)p);
+    u32x2 w;
+    __builtin_memcpy(&w, &v, 8);
+    return w;
+}
+
+// Weight gradient of the 3x3x3 submanifold convolution from the leaf window (fp32 at low depth; f16 / bf16 at
+// C_in % 32 == 0 and C_out % 64 == 0), and the ordered
 // reduction of per-range partial sums part[n_ranges][total] into gw that all weight-gradient kernels end with
 // (n_ranges = 0: gw = 0).
 fx_status leaf_wgrad(const char* who, const fx_grid* g, const void* d_feat, const void* d_gout, fx_dtype dt, int32_t C_in,
                      int32_t C_out, void* d_gw, fx_dtype out_dt, hipStream_t st);
 inline bool leaf_wgrad_shape_supported(fx_dtype dt, int C_in, int C_out) {
-    return dt == FX_F32 && (C_in == 4 || C_in == 8 || C_in == 12 || C_in == 16) && C_out >= 4 && C_out % 4 == 0 && C_out <= 32;
+    if (dt != FX_F32) return C_in % 32 == 0 && C_out % 64 == 0;
+    return (C_in == 4 || C_in == 8 || C_in == 12 || C_in == 16) && C_out >= 4 && C_out % 4 == 0 && C_out <= 32;
 }
 fx_status wgrad_reduce_ranges(const float* part, int n_ranges, int64_t total, void* gw, fx_dtype out_dt, hipStream_t st);
 

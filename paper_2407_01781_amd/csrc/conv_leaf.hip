@@ -752,6 +752,252 @@ fx_status launch_leaf16(const fx_grid* g, const void* feat, const void* wpacked,
     return FX_OK;
 }
 
+// ---------------------------------------------------------------------------------- weight gradient, 16-bit types, depth >= 32
+// gw[kappa][ci][co] = sum over the active voxels o with an active neighbour at tap kappa of
+// feat[nb(o, kappa)][ci] * gout[o][co], leaf by leaf from the same window as k_conv_leaf16: no kernel map, a tap is an
+// address offset.  A workgroup owns a block of 32 input x 64 output channels of every gw[kappa] and a range of leaves
+// of equal estimated cost; its 16 waves split the taps (wave w: kappa = w and w + 16) and keep their accumulator
+// tiles over the whole range.  Per leaf it stages the window (one 32-channel chunk of every cell, inactive cells
+// zero) and the gout rows of the leaf's active voxels (consecutive rows of the tensor; 128 bytes per voxel, 16-byte
+// pieces swizzled by the voxel's rank), both straight from global memory to LDS.  The voxels are the contracted
+// dimension, so both operands are read with the transposing LDS read (tr_read4): per column tile of 32 voxels a wave
+// reads the gout fragments once for its two taps and, per tap, the window rows of the voxels' neighbours.
+// A (tile, tap) in which no voxel has that neighbour is skipped; ranks past the leaf's last voxel contribute
+// zeros on both sides.  Partial sums go to part[range][kappa][ci][co]; the ordered reduction adds the ranges.
+constexpr int kWg16Waves = 16;
+constexpr int kWg16Threads = 64 * kWg16Waves;
+constexpr int kWg16Offsets = (27 + kWg16Waves - 1) / kWg16Waves;
+constexpr int kWg16GoutRow = 128;            // 64 output channels of a 16-bit type
+
+struct Wg16Lds {
+    uint64_t mask[27][8];
+    uint64_t prefix[27];
+    int32_t offset[27];
+    uint32_t act_row[100];
+    int32_t cell_row[kWinCells];
+    uint16_t cell_of_rank[512];
+    uint32_t tile_taps[16];                  // per column tile of 32 voxels
+    int32_t range[2];
+    unsigned char win[kWinSlabs * 1024] __attribute__((aligned(16)));   // 64-byte rows, in slabs of 16, as in k_conv_leaf16
+    unsigned char gt[512 * kWg16GoutRow] __attribute__((aligned(16)));  // gout row of rank r at r * 128, piece p at p ^ 4 * ((r >> 1) & 1)
+};
+static_assert(sizeof(Wg16Lds) <= 160 * 1024, "LDS budget of one compute unit");
+
+template <typename T>
+__global__ __launch_bounds__(kWg16Threads, 1) void k_wgrad_leaf16(TreeView t, const uint16_t* __restrict__ feat,
+                                                                  const uint16_t* __restrict__ gout, int C_in, int C_out,
+                                                                  int n_ranges, int64_t n_voxels, float* __restrict__ part) {
+    typedef typename Elem<T>::vec8 vec8;
+    extern __shared__ __align__(16) unsigned char smem[];
+    Wg16Lds& L = *reinterpret_cast<Wg16Lds*>(smem);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    const int n_cib = C_in / 32, n_cblk = n_cib * (C_out / 64);
+    // workgroup b runs on XCD b % 8: the channel blocks of one range of leaves share an XCD and its L2
+    int blk = blockIdx.x % n_cblk, range = blockIdx.x / n_cblk;
+    if (n_ranges % 8 == 0) {
+        blk = (blockIdx.x >> 3) % n_cblk;
+        range = (int)(blockIdx.x / (8 * n_cblk)) * 8 + (blockIdx.x & 7);
+    }
+    const int cib = blk % n_cib, cob = blk / n_cib;
+
+    if (wave < 2) {
+        const int64_t first_index = t.leaf[0].offset;
+        const int64_t total = kLeafFixedCost * t.n_leaf + n_voxels;
+        const int b = range + wave;
+        const int f = b >= n_ranges ? t.n_leaf : first_leaf_at_cost<kLeafFixedCost>(t, first_index, total * b / (int64_t)n_ranges, lane);
+        if (lane == 0) L.range[wave] = f;
+    }
+    __syncthreads();
+    const int f_begin = uni(L.range[0]), f_end = uni(L.range[1]);
+
+    f32x16 acc[kWg16Offsets][2];
+#pragma unroll
+    for (int j = 0; j < kWg16Offsets; ++j)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][cb][v] = 0.f;
+
+    // what this lane's address contributes to a transposing read: voxel jv of four, channels 16*g1 + 4*q .. + 3
+    const int q = lane & 3, jv = (lane >> 2) & 3, g1 = (lane >> 4) & 1;
+    const int a_piece = 2 * g1 + (q >> 1);
+    const uint32_t half8 = (uint32_t)(q & 1) << 3;
+
+    if (wave == kWg16Waves - 1 && f_begin < f_end) stage_records(t, L, f_begin, lane);
+    __syncthreads();
+    for (int f = f_begin; f < f_end; ++f) {
+        // ---- from the leaf's 27 records (fetched while the leaf before was multiplied): per cell its input row,
+        // activity bits per window row (as in k_conv_leaf16)
+        if (tid < 16) L.tile_taps[tid] = 0;
+        if (tid >= 128 && tid < 228) {
+            const int xy = tid - 128;
+            const int x = xy / 10, y = xy % 10;
+            const int s9 = ((x + 7) >> 3) * 9 + ((y + 7) >> 3) * 3, lx = (x - 1) & 7, sh = ((y - 1) & 7) * 8;
+            L.act_row[xy] = (uint32_t)((L.mask[s9][lx] >> (sh + 7)) & 1) | (uint32_t)((L.mask[s9 + 1][lx] >> sh) & 0xff) << 1 |
+                            (uint32_t)((L.mask[s9 + 2][lx] >> sh) & 1) << 9;
+        }
+        if (tid < kWinCells) {
+            const int cell = tid;
+            const int x = cell / 100, y = (cell / 10) % 10, z = cell % 10;
+            const int slot = ((x + 7) >> 3) * 9 + ((y + 7) >> 3) * 3 + ((z + 7) >> 3);
+            L.cell_row[cell] = staged_value(L, slot, (x - 1) & 7, (y - 1) & 7, (z - 1) & 7);
+        }
+        __syncthreads();
+        const int n_act = uni((int)((L.prefix[13] >> 54) & 511) + __popcll(L.mask[13][7]));
+        const int64_t base = uni(L.offset[13]);
+        if (tid < 512) {
+            const int lx = tid >> 6, ly = (tid >> 3) & 7, lz = tid & 7;
+            const int row = L.cell_row[window_cell(lx + 1, ly + 1, lz + 1)];
+            if (row >= 0) {
+                const int r = row - (int)base;
+                L.cell_of_rank[r] = (uint16_t)window_cell(lx + 1, ly + 1, lz + 1);
+                uint32_t taps = 0;
+#pragma unroll
+                for (int ab = 0; ab < 9; ++ab)
+                    taps |= ((L.act_row[(lx + ab / 3) * 10 + ly + ab % 3] >> lz) & 7u) << (3 * ab);
+                atomicOr(&L.tile_taps[r >> 5], taps);
+            }
+        }
+        __syncthreads();
+
+        // ---- stage the window (chunk cib of every cell) and the gout rows of the leaf's voxels.  All reads of LDS
+        // and all plain stores come before the first asynchronous load is issued.
+        {
+            constexpr int kSlabsPerWave = (kWinSlabs + kWg16Waves - 1) / kWg16Waves;
+            constexpr int kGoutSlabsPerWave = 512 * kWg16GoutRow / 1024 / kWg16Waves;
+            int rows[kSlabsPerWave];
+#pragma unroll
+            for (int j = 0; j < kSlabsPerWave; ++j) {
+                const int sl = wave + j * kWg16Waves, cell = 16 * sl + (lane >> 2);
+                rows[j] = (sl < kWinSlabs && cell < kWinCells) ? L.cell_row[cell] : -1;
+            }
+#pragma unroll
+            for (int j = 0; j < kSlabsPerWave; ++j) {
+                const int sl = wave + j * kWg16Waves;
+                if (sl < kWinSlabs && rows[j] < 0) *reinterpret_cast<u32x4*>(L.win + sl * 1024 + lane * 16) = u32x4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int j = 0; j < kGoutSlabsPerWave; ++j) {
+                const int slab = wave + j * kWg16Waves, r = 8 * slab + (lane >> 3);
+                if (r >= n_act) *reinterpret_cast<u32x4*>(L.gt + slab * 1024 + lane * 16) = u32x4{0, 0, 0, 0};
+            }
+            const int piece = (lane & 3) ^ ((lane >> 4) & 3);
+#pragma unroll
+            for (int j = 0; j < kSlabsPerWave; ++j) {
+                const int sl = wave + j * kWg16Waves;
+                if (sl < kWinSlabs && rows[j] >= 0)
+                    __builtin_amdgcn_global_load_lds(feat + (int64_t)rows[j] * C_in + cib * 32 + piece * 8, (leaf_lds_ptr)(L.win + sl * 1024), 16, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < kGoutSlabsPerWave; ++j) {
+                const int slab = wave + j * kWg16Waves, r = 8 * slab + (lane >> 3);
+                const int gpiece = (lane & 7) ^ (((r >> 1) & 1) << 2);
+                if (r < n_act)
+                    __builtin_amdgcn_global_load_lds(gout + (base + r) * (int64_t)C_out + cob * 64 + gpiece * 8, (leaf_lds_ptr)(L.gt + slab * 1024), 16, 0, 0);
+            }
+            __builtin_amdgcn_s_waitcnt(0);
+        }
+        __syncthreads();
+
+        // ---- multiply; the last wave first walks the tree for the next leaf's records, which nobody reads meanwhile
+        if (wave == kWg16Waves - 1 && f + 1 < f_end) stage_records(t, L, f + 1, lane);
+        const int n_tiles = (n_act + 31) >> 5;
+        for (int g = 0; g < n_tiles; ++g) {
+            const uint32_t taps = (uint32_t)uni((int)L.tile_taps[g]);
+            bool on[kWg16Offsets];
+            bool any = false;
+#pragma unroll
+            for (int j = 0; j < kWg16Offsets; ++j) {
+                const int kappa = wave + kWg16Waves * j;
+                on[j] = kappa < 27 && ((taps >> kappa) & 1u);
+                any = any || on[j];
+            }
+            if (!any) continue;
+            // the voxels whose rows this lane's addresses contribute: ranks 32g + 16ks + 8h + 4tt + jv
+            int cell[2][2];
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt) cell[ks][tt] = L.cell_of_rank[min(32 * g + 16 * ks + 8 * h + 4 * tt + jv, n_act - 1)];
+            vec8 bfr[2][2];
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    const int r = 32 * g + 16 * ks + 8 * h + jv;
+                    const uint32_t pos = (uint32_t)((4 * cb + 2 * g1 + (q >> 1)) ^ (((r >> 1) & 1) << 2)) << 4;
+                    const unsigned char* src = L.gt + r * kWg16GoutRow + pos + half8;
+                    const u32x2 lo = tr_read4(src);
+                    const u32x2 hi = tr_read4(src + 4 * kWg16GoutRow);
+                    bfr[cb][ks] = vec8_from_words<T>(u32x4{lo[0], lo[1], hi[0], hi[1]});
+                }
+            const bool tail = 32 * g + 32 > n_act;       // ranks past the last voxel: their A elements are cleared too
+#pragma unroll
+            for (int j = 0; j < kWg16Offsets; ++j) {
+                if (!on[j]) continue;
+                const int d = tap_delta(wave + kWg16Waves * j);
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    u32x2 w[2];
+#pragma unroll
+                    for (int tt = 0; tt < 2; ++tt) {
+                        w[tt] = tr_read4(L.win + win_piece_offset(cell[ks][tt] + d, a_piece) + half8);
+                        if (tail) {      // element e of this read is the voxel of rank 32g + 16ks + 8h + 4tt + e
+                            const int left = n_act - (32 * g + 16 * ks + 8 * h + 4 * tt);
+                            w[tt][0] &= left >= 2 ? 0xFFFFFFFFu : (left == 1 ? 0x0000FFFFu : 0u);
+                            w[tt][1] &= left >= 4 ? 0xFFFFFFFFu : (left == 3 ? 0x0000FFFFu : 0u);
+                        }
+                    }
+                    const vec8 fT = vec8_from_words<T>(u32x4{w[0][0], w[0][1], w[1][0], w[1][1]});
+#pragma unroll
+                    for (int cb = 0; cb < 2; ++cb) acc[j][cb] = Elem<T>::mfma(fT, bfr[cb][ks], acc[j][cb]);
+                }
+            }
+        }
+        __syncthreads();                 // window, gout rows and records are rewritten for the next leaf
+    }
+
+    // ---- partial sums of this range: lane (co = n, h), register 4b + r  ->  ci = 8b + 4h + r
+#pragma unroll
+    for (int j = 0; j < kWg16Offsets; ++j) {
+        const int kappa = wave + kWg16Waves * j;
+        if (kappa >= 27) continue;
+        float* dst = part + (((int64_t)range * 27 + kappa) * C_in + cib * 32) * C_out + cob * 64 + n;
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) dst[(int64_t)(8 * (v >> 2) + 4 * h + (v & 3)) * C_out + cb * 32] = acc[j][cb][v];
+    }
+}
+
+template <typename T>
+fx_status launch_wgrad_leaf16(const fx_grid* g, const void* feat, const void* gout, int C_in, int C_out, void* gw, fx_dtype out_dt,
+                              hipStream_t st) {
+    const size_t lds = sizeof(Wg16Lds);
+    static bool attr_set = false;
+    if (!attr_set) {
+        FX_HIP_TRY(hipFuncSetAttribute((const void*)k_wgrad_leaf16<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    const int n_cblk = (C_in / 32) * (C_out / 64);
+    int n_ranges = (int)std::max<int64_t>(1, std::min<int64_t>(g->hdr.n_leaf, compute_units() / std::max(1, n_cblk)));
+    if (n_ranges > 8) n_ranges -= n_ranges % 8;   // see the block-to-XCD mapping in the kernel
+    const int64_t total = (int64_t)27 * C_in * C_out;
+    float* part = nullptr;
+    FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * n_ranges, st));
+    {
+        ProfScope ps(kProfWgrad, st);
+        k_wgrad_leaf16<T><<<(unsigned)(n_cblk * n_ranges), kWg16Threads, lds, st>>>(g->view(), (const uint16_t*)feat, (const uint16_t*)gout,
+                                                                                    C_in, C_out, n_ranges, g->hdr.n_voxels, part);
+    }
+    fx_status rc = FX_OK;
+    if (hipGetLastError() != hipSuccess) { set_error("leaf-window weight gradient: launch failed"); rc = FX_EDEVICE; }
+    if (rc == FX_OK) rc = wgrad_reduce_ranges(part, n_ranges, total, gw, out_dt, st);
+    dev_free(part, st);
+    return rc;
+}
+
 constexpr bool leaf_weights_in_registers(int J, int NT) { return 27 * J * NT <= 64; }
 
 size_t leaf_lds_bytes(int J, int NT) {
@@ -873,13 +1119,15 @@ fx_status fx::leaf_wgrad(const char* who, const fx_grid* g, const void* d_feat, 
         return FX_EUNSUPPORTED;
     }
     if (!leaf_wgrad_shape_supported(dt, C_in, C_out)) {
-        set_error("%s: serves fp32 with 4, 8, 12 or 16 input channels and a multiple of 4 up to 32 output channels "
-                  "(got %d -> %d); use the kernel-map path", who, C_in, C_out);
+        set_error("%s: serves fp32 with 4, 8, 12 or 16 input channels and a multiple of 4 up to 32 output channels, f16 / bf16 "
+                  "with a multiple of 32 input and of 64 output channels (got %d -> %d); use the kernel-map path", who, C_in, C_out);
         return FX_EUNSUPPORTED;
     }
     const float* x = (const float*)d_feat;
     const float* gy = (const float*)d_gout;
     if (g->hdr.n_voxels == 0) return wgrad_reduce_ranges(nullptr, 0, (int64_t)27 * C_in * C_out, d_gw, out_dt, st);
+    if (dt == FX_BF16) return launch_wgrad_leaf16<__bf16>(g, d_feat, d_gout, C_in, C_out, d_gw, out_dt, st);
+    if (dt == FX_F16) return launch_wgrad_leaf16<_Float16>(g, d_feat, d_gout, C_in, C_out, d_gw, out_dt, st);
     const bool wide = C_out > 16;
     switch (C_in) {
         case 4: return wide ? launch_wgrad_leaf<4, 2>(g, x, gy, C_out, d_gw, out_dt, st) : launch_wgrad_leaf<4, 1>(g, x, gy, C_out, d_gw, out_dt, st);

@@ -320,3 +320,76 @@ def test_weight_gradient_full_size_volume():
     gy = np.random.default_rng(w.feat_seed + 3).standard_normal((og.num_voxels, 16)).astype(np.float32)
     gw = fx.sparse_conv_leaf_bwd_weight(g, H.to_device_storage(feat, "f32"), H.to_device_storage(gy, "f32"))
     assert _wgrad_rel(gw.cpu().numpy(), O.conv_bwd_weight(og, og, 3, 1, feat, gy)) <= 1e-4
+
+
+# ---------------------------------------------------------------------------------- weight gradient, 16-bit types at depth >= 32
+def _leaf_wgrad16_vs_oracle(grids, dtype, c_in, c_out, out_f32, seed, dup=0.01):
+    """Per offset, ||gw[kappa] - ref||_F relative to ||ref||_F: products are exact and summed in fp32, so the error is
+    the one rounding of the result (2e-2 in the storage type) or the fp32 summation order (2e-3 with an fp32 result)."""
+    ijk, jo = G.make_jagged([G.shuffle_and_duplicate(g, seed + b, dup) for b, g in enumerate(grids)])
+    g, og = H.both_grids(ijk, jo)
+    feat, _ = G.features_and_weights(seed, og.num_voxels, c_in, c_out, 27, dtype)
+    gy = G.round_to_dtype(np.random.default_rng(seed + 11).standard_normal((og.num_voxels, c_out)).astype(np.float32), dtype)
+    d_x, d_gy = H.to_device_storage(feat, dtype), H.to_device_storage(gy, dtype)
+    gw = fx.sparse_conv_leaf_bwd_weight(g, d_x, d_gy, out_dtype=torch.float32 if out_f32 else None)
+    assert gw.shape == (27, c_in, c_out)
+    ref = O.conv_bwd_weight(og, og, 3, 1, feat, gy)
+    assert _wgrad_rel(gw.float().cpu().numpy(), ref) <= (2e-3 if out_f32 else 2e-2)
+    return g, og, d_x, d_gy, gw
+
+
+@pytest.mark.parametrize("name", ["volume_small", "lidar_small", "sheets_small"])
+@pytest.mark.parametrize("dtype,c_in,c_out,out_f32", [("bf16", 64, 64, False), ("f16", 32, 128, True), ("bf16", 96, 64, True)])
+def test_weight_gradient_16_bit_from_the_leaf_window(name, dtype, c_in, c_out, out_f32):
+    w = G.workload(name)
+    _leaf_wgrad16_vs_oracle(w.grids, dtype, c_in, c_out, out_f32, w.feat_seed)
+
+
+def test_weight_gradient_16_bit_edge_cases_and_reproducibility():
+    a = np.arange(-9, 9)
+    blk = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3).astype(np.int32)
+    far = (np.random.default_rng(9).integers(-3000, 3000, size=(300, 3)) * 16).astype(np.int32)
+    g, og, d_x, d_gy, gw = _leaf_wgrad16_vs_oracle([blk + np.array([4090, 120, -8], np.int32), np.zeros((0, 3), np.int32), far],
+                                                    "bf16", 32, 64, True, 93)
+    assert torch.equal(gw, fx.sparse_conv_leaf_bwd_weight(g, d_x, d_gy, out_dtype=torch.float32))     # fixed order: identical bits
+    _, _, _, _, gw1 = _leaf_wgrad16_vs_oracle([np.array([[3, -4, 5]], np.int32)], "f16", 32, 64, True, 94, dup=0.0)
+    assert (gw1.cpu().numpy()[np.arange(27) != 13] == 0).all()
+    # a leaf whose voxel count is not a multiple of 32, next to full leaves: 8x8x8 plus a 3x3x3 corner in the next leaf
+    c = np.arange(0, 8)
+    full = np.stack(np.meshgrid(c, c, c, indexing="ij"), axis=-1).reshape(-1, 3).astype(np.int32)
+    d = np.arange(8, 11)
+    corner = np.stack(np.meshgrid(d, d, d, indexing="ij"), axis=-1).reshape(-1, 3).astype(np.int32)
+    _leaf_wgrad16_vs_oracle([np.concatenate([full, corner])], "bf16", 64, 64, True, 95, dup=0.0)
+    e, _ = H.both_grids(np.zeros((0, 3), np.int32), np.array([[0, 0]]))
+    z = fx.sparse_conv_leaf_bwd_weight(e, torch.zeros((0, 32), device="cuda", dtype=torch.bfloat16),
+                                       torch.zeros((0, 64), device="cuda", dtype=torch.bfloat16))
+    assert z.shape == (27, 32, 64) and (z == 0).all()
+    for c_in, c_out in ((48, 64), (32, 32), (8, 16)):
+        with pytest.raises(fx.FxError):
+            fx.sparse_conv_leaf_bwd_weight(g, torch.zeros((g.num_voxels, c_in), device="cuda", dtype=torch.float16),
+                                           torch.zeros((g.num_voxels, c_out), device="cuda", dtype=torch.float16))
+
+
+@pytest.mark.parametrize("switch", [None, "0", "1"])
+def test_kernel_map_weight_gradient_takes_the_leaf_kernel_on_dense_grids(switch, fx_opt):
+    """A solid 24^3 block is locally dense (the forward pass takes its leaf-window kernel there): so does the weight
+    gradient, unless leaf_dispatch = 0; on the sparse LiDAR grid it does only when leaf_dispatch = 1."""
+    if switch is not None:
+        fx_opt("leaf_dispatch", switch)
+    a = np.arange(0, 24)
+    block = np.stack(np.meshgrid(a, a, a, indexing="ij"), axis=-1).reshape(-1, 3).astype(np.int32) + np.array([-8, 4096, 40], np.int32)
+    for name, dense in (("block", True), ("lidar_small", False)):
+        if name == "block":
+            ijk, jo = G.make_jagged([block])
+        else:
+            ijk, jo = G.workload(name).jagged_ijk()
+        g, og = H.both_grids(ijk, jo)
+        km = fx.build_kernel_map(g, 3, 1)
+        feat, _ = G.features_and_weights(7, og.num_voxels, 64, 64, 27, "bf16")
+        gy = G.round_to_dtype(np.random.default_rng(8).standard_normal((og.num_voxels, 64)).astype(np.float32), "bf16")
+        d_x, d_gy = H.to_device_storage(feat, "bf16"), H.to_device_storage(gy, "bf16")
+        gw = fx.sparse_conv_bwd_weight(km, d_x, d_gy, out_dtype=torch.float32)
+        assert _wgrad_rel(gw.cpu().numpy(), O.conv_bwd_weight(og, og, 3, 1, feat, gy)) <= 2e-3
+        leaf = fx.sparse_conv_leaf_bwd_weight(g, d_x, d_gy, out_dtype=torch.float32)
+        taken = switch == "1" or (switch is None and dense)
+        assert torch.equal(gw, leaf) == taken
