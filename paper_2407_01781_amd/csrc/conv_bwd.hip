@@ -863,15 +863,38 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
             return leaf_wgrad("sparse convolution weight gradient (leaf-window kernel)", km->gin, d_feat, d_gout, dt, C_in,
                               C_out, d_gw, out_dt, st);
     }
-    const bool mfma = dt != FX_F32 && km->n_tiles > 0 && C_in % kWgCi == 0 && C_out % kWgCo == 0 && !force_scalar();
+    bool mfma = dt != FX_F32 && km->n_tiles > 0 && C_in % kWgCi == 0 && C_out % kWgCo == 0 && !force_scalar();
+    // Per-leaf dispatch, as in the forward pass: on a grid that mixes locally dense leaves with sparse ones the pairs
+    // of the dense leaves' outputs are summed by the leaf-window kernel (over the list of those leaves) and all
+    // others by the tile kernel over the copy of the map that leaves those outputs out; both write partial sums of
+    // the same form and one ordered reduction adds them.  leaf_dispatch = 2 forces it.
+    int leaf_ranges = 0;
+    if (mfma && km->K == 3 && km->stride == 1 && km->gin == km->gout && !km->is_inverse && leaf_wgrad_shape_supported(dt, C_in, C_out)) {
+        const int ld = option(kOptLeafDispatch);
+        const double occupancy = (double)km->n_in / (512.0 * (double)std::max<int64_t>(1, km->gin->hdr.n_leaf));
+        const double dense = (double)km->gin->hdr.n_voxels_dense / (double)std::max<int64_t>(1, km->n_in);
+        if (ld == 2 || (ld < 0 && occupancy < 0.40 && dense >= 0.10)) {
+            FX_TRY(kmap_ensure_mixed(const_cast<fx_kmap*>(km), st));
+            leaf_ranges = leaf_wgrad16_ranges(km->gin, C_in, C_out);
+        }
+    }
+    const fx_kmap* kmt = leaf_ranges ? km->mixed : km;      // the map whose tiles are walked
+    mfma = mfma && kmt->n_tiles > 0;
     float* part = nullptr;
     hipError_t e = hipSuccess;
     int n_ranges = 1;
     if (mfma) {
+        const fx_kmap* km_all = km;
+        km = kmt;
         const int n_cblk = (C_in / kWgCi) * (C_out / kWgCo);
         n_ranges = (int)std::max<int64_t>(1, std::min<int64_t>(km->n_tiles, compute_units() / n_cblk));
         if (n_ranges > 8) n_ranges -= n_ranges % 8;   // see the block-to-XCD mapping in the kernel
-        FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * n_ranges, st));
+        FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * (n_ranges + leaf_ranges), st));
+        if (leaf_ranges) {
+            const fx_status rl = leaf_wgrad16_partial(km_all->gin, d_feat, d_gout, dt, C_in, C_out, km->d_dense_leaves, km->d_n_dense,
+                                                      part + (size_t)total * n_ranges, leaf_ranges, st);
+            if (rl != FX_OK) { dev_free(part, st); return rl; }
+        }
         const size_t lds = sizeof(WgradLds);
         ProfScope ps(kProfWgrad, st);
 #define FX_WGRAD(T)                                                                                                    \
@@ -901,7 +924,7 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
         e = hipGetLastError();
     }
     fx_status rc_red = FX_OK;
-    if (e == hipSuccess) rc_red = wgrad_reduce_ranges(part, n_ranges, total, d_gw, out_dt, st);
+    if (e == hipSuccess) rc_red = wgrad_reduce_ranges(part, n_ranges + (mfma ? leaf_ranges : 0), total, d_gw, out_dt, st);
     dev_free(part, st);
     if (e != hipSuccess) { set_error("weight-gradient launch failed: %s", hipGetErrorString(e)); return FX_EDEVICE; }
     return rc_red;

@@ -185,6 +185,11 @@ inline bool leaf_wgrad_shape_supported(fx_dtype dt, int C_in, int C_out) {
     return (C_in == 4 || C_in == 8 || C_in == 12 || C_in == 16) && C_out >= 4 && C_out % 4 == 0 && C_out <= 32;
 }
 fx_status wgrad_reduce_ranges(const float* part, int n_ranges, int64_t total, void* gw, fx_dtype out_dt, hipStream_t st);
+// The 16-bit leaf-window weight gradient as partial sums only: part[n_ranges][27][C_in][C_out] with
+// n_ranges = leaf_wgrad16_ranges(...), over all leaves of g or over the first *n_list leaves of leaf_list.
+int leaf_wgrad16_ranges(const fx_grid* g, int C_in, int C_out);
+fx_status leaf_wgrad16_partial(const fx_grid* g, const void* d_feat, const void* d_gout, fx_dtype dt, int32_t C_in, int32_t C_out,
+                               const int32_t* leaf_list, const int32_t* n_list, float* part, int n_ranges, hipStream_t st);
 
 // The same sum through a dense table [n_rows, K3] of source rows (-1: none), one thread per output element
 // (or per four): out[r,:] = sum over kappa with table[r][kappa] >= 0 of src[table[r][kappa],:] . W'[kappa], W' read

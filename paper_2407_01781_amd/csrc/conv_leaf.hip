@@ -786,7 +786,9 @@ static_assert(sizeof(Wg16Lds) <= 160 * 1024, "LDS budget of one compute unit");
 template <typename T>
 __global__ __launch_bounds__(kWg16Threads, 1) void k_wgrad_leaf16(TreeView t, const uint16_t* __restrict__ feat,
                                                                   const uint16_t* __restrict__ gout, int C_in, int C_out,
-                                                                  int n_ranges, int64_t n_voxels, float* __restrict__ part) {
+                                                                  int n_ranges, int64_t n_voxels, float* __restrict__ part,
+                                                                  const int32_t* __restrict__ leaf_list,
+                                                                  const int32_t* __restrict__ n_list) {
     typedef typename Elem<T>::vec8 vec8;
     extern __shared__ __align__(16) unsigned char smem[];
     Wg16Lds& L = *reinterpret_cast<Wg16Lds*>(smem);
@@ -801,15 +803,23 @@ __global__ __launch_bounds__(kWg16Threads, 1) void k_wgrad_leaf16(TreeView t, co
     }
     const int cib = blk % n_cib, cob = blk / n_cib;
 
+    // With a leaf list (per-leaf dispatch: the locally dense leaves of a mixed grid) the ranges are equal shares of the
+    // list and the numbers below index it; without one they are ranges of leaves of equal estimated cost.
     if (wave < 2) {
-        const int64_t first_index = t.leaf[0].offset;
-        const int64_t total = kLeafFixedCost * t.n_leaf + n_voxels;
         const int b = range + wave;
-        const int f = b >= n_ranges ? t.n_leaf : first_leaf_at_cost<kLeafFixedCost>(t, first_index, total * b / (int64_t)n_ranges, lane);
+        int f;
+        if (leaf_list) {
+            f = (int)((int64_t)uni(*n_list) * min(b, n_ranges) / n_ranges);
+        } else {
+            const int64_t first_index = t.leaf[0].offset;
+            const int64_t total = kLeafFixedCost * t.n_leaf + n_voxels;
+            f = b >= n_ranges ? t.n_leaf : first_leaf_at_cost<kLeafFixedCost>(t, first_index, total * b / (int64_t)n_ranges, lane);
+        }
         if (lane == 0) L.range[wave] = f;
     }
     __syncthreads();
     const int f_begin = uni(L.range[0]), f_end = uni(L.range[1]);
+    auto leaf_of = [&](int i) { return leaf_list ? uni(leaf_list[i]) : i; };
 
     f32x16 acc[kWg16Offsets][2];
 #pragma unroll
@@ -824,7 +834,7 @@ __global__ __launch_bounds__(kWg16Threads, 1) void k_wgrad_leaf16(TreeView t, co
     const int a_piece = 2 * g1 + (q >> 1);
     const uint32_t half8 = (uint32_t)(q & 1) << 3;
 
-    if (wave == kWg16Waves - 1 && f_begin < f_end) stage_records(t, L, f_begin, lane);
+    if (wave == kWg16Waves - 1 && f_begin < f_end) stage_records(t, L, leaf_of(f_begin), lane);
     __syncthreads();
     for (int f = f_begin; f < f_end; ++f) {
         // ---- from the leaf's 27 records (fetched while the leaf before was multiplied): per cell its input row,
@@ -901,7 +911,7 @@ __global__ __launch_bounds__(kWg16Threads, 1) void k_wgrad_leaf16(TreeView t, co
         __syncthreads();
 
         // ---- multiply; the last wave first walks the tree for the next leaf's records, which nobody reads meanwhile
-        if (wave == kWg16Waves - 1 && f + 1 < f_end) stage_records(t, L, f + 1, lane);
+        if (wave == kWg16Waves - 1 && f + 1 < f_end) stage_records(t, L, leaf_of(f + 1), lane);
         const int n_tiles = (n_act + 31) >> 5;
         for (int g = 0; g < n_tiles; ++g) {
             const uint32_t taps = (uint32_t)uni((int)L.tile_taps[g]);
@@ -971,9 +981,17 @@ __global__ __launch_bounds__(kWg16Threads, 1) void k_wgrad_leaf16(TreeView t, co
     }
 }
 
+// ranges (= partial sums) of the 16-bit leaf-window weight gradient on grid g
+int wgrad_leaf16_ranges(const fx_grid* g, int C_in, int C_out) {
+    const int n_cblk = (C_in / 32) * (C_out / 64);
+    int n_ranges = (int)std::max<int64_t>(1, std::min<int64_t>(g->hdr.n_leaf, compute_units() / std::max(1, n_cblk)));
+    if (n_ranges > 8) n_ranges -= n_ranges % 8;   // see the block-to-XCD mapping in the kernel
+    return n_ranges;
+}
+
 template <typename T>
-fx_status launch_wgrad_leaf16(const fx_grid* g, const void* feat, const void* gout, int C_in, int C_out, void* gw, fx_dtype out_dt,
-                              hipStream_t st) {
+fx_status launch_wgrad_leaf16(const fx_grid* g, const void* feat, const void* gout, int C_in, int C_out, const int32_t* leaf_list,
+                              const int32_t* n_list, float* part, int n_ranges, hipStream_t st) {
     const size_t lds = sizeof(Wg16Lds);
     static bool attr_set = false;
     if (!attr_set) {
@@ -981,22 +999,24 @@ fx_status launch_wgrad_leaf16(const fx_grid* g, const void* feat, const void* go
         attr_set = true;
     }
     const int n_cblk = (C_in / 32) * (C_out / 64);
-    int n_ranges = (int)std::max<int64_t>(1, std::min<int64_t>(g->hdr.n_leaf, compute_units() / std::max(1, n_cblk)));
-    if (n_ranges > 8) n_ranges -= n_ranges % 8;   // see the block-to-XCD mapping in the kernel
-    const int64_t total = (int64_t)27 * C_in * C_out;
-    float* part = nullptr;
-    FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * n_ranges, st));
-    {
-        ProfScope ps(kProfWgrad, st);
-        k_wgrad_leaf16<T><<<(unsigned)(n_cblk * n_ranges), kWg16Threads, lds, st>>>(g->view(), (const uint16_t*)feat, (const uint16_t*)gout,
-                                                                                    C_in, C_out, n_ranges, g->hdr.n_voxels, part);
-    }
-    fx_status rc = FX_OK;
-    if (hipGetLastError() != hipSuccess) { set_error("leaf-window weight gradient: launch failed"); rc = FX_EDEVICE; }
-    if (rc == FX_OK) rc = wgrad_reduce_ranges(part, n_ranges, total, gw, out_dt, st);
-    dev_free(part, st);
-    return rc;
+    ProfScope ps(kProfWgrad, st);
+    k_wgrad_leaf16<T><<<(unsigned)(n_cblk * n_ranges), kWg16Threads, lds, st>>>(g->view(), (const uint16_t*)feat, (const uint16_t*)gout,
+                                                                                C_in, C_out, n_ranges, g->hdr.n_voxels, part, leaf_list, n_list);
+    if (hipGetLastError() != hipSuccess) { set_error("leaf-window weight gradient: launch failed"); return FX_EDEVICE; }
+    return FX_OK;
 }
+
+}  // namespace
+
+int leaf_wgrad16_ranges(const fx_grid* g, int C_in, int C_out) { return wgrad_leaf16_ranges(g, C_in, C_out); }
+
+fx_status leaf_wgrad16_partial(const fx_grid* g, const void* d_feat, const void* d_gout, fx_dtype dt, int32_t C_in, int32_t C_out,
+                               const int32_t* leaf_list, const int32_t* n_list, float* part, int n_ranges, hipStream_t st) {
+    if (dt == FX_BF16) return launch_wgrad_leaf16<__bf16>(g, d_feat, d_gout, C_in, C_out, leaf_list, n_list, part, n_ranges, st);
+    return launch_wgrad_leaf16<_Float16>(g, d_feat, d_gout, C_in, C_out, leaf_list, n_list, part, n_ranges, st);
+}
+
+namespace {
 
 constexpr bool leaf_weights_in_registers(int J, int NT) { return 27 * J * NT <= 64; }
 
@@ -1126,8 +1146,16 @@ fx_status fx::leaf_wgrad(const char* who, const fx_grid* g, const void* d_feat, 
     const float* x = (const float*)d_feat;
     const float* gy = (const float*)d_gout;
     if (g->hdr.n_voxels == 0) return wgrad_reduce_ranges(nullptr, 0, (int64_t)27 * C_in * C_out, d_gw, out_dt, st);
-    if (dt == FX_BF16) return launch_wgrad_leaf16<__bf16>(g, d_feat, d_gout, C_in, C_out, d_gw, out_dt, st);
-    if (dt == FX_F16) return launch_wgrad_leaf16<_Float16>(g, d_feat, d_gout, C_in, C_out, d_gw, out_dt, st);
+    if (dt != FX_F32) {
+        const int n_ranges = leaf_wgrad16_ranges(g, C_in, C_out);
+        const int64_t total = (int64_t)27 * C_in * C_out;
+        float* part = nullptr;
+        FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * n_ranges, st));
+        fx_status rc = leaf_wgrad16_partial(g, d_feat, d_gout, dt, C_in, C_out, nullptr, nullptr, part, n_ranges, st);
+        if (rc == FX_OK) rc = wgrad_reduce_ranges(part, n_ranges, total, d_gw, out_dt, st);
+        dev_free(part, st);
+        return rc;
+    }
     const bool wide = C_out > 16;
     switch (C_in) {
         case 4: return wide ? launch_wgrad_leaf<4, 2>(g, x, gy, C_out, d_gw, out_dt, st) : launch_wgrad_leaf<4, 1>(g, x, gy, C_out, d_gw, out_dt, st);

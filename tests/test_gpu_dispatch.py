@@ -41,6 +41,13 @@ def _check_forward_and_input_gradient(pts, jo, dtype, c_in, c_out, expect_both, 
     gx = gx.cpu().numpy()
     assert np.isfinite(gx).all()
     H.conv_tolerance_check(gx, O.conv_bwd_data(og, og, 3, 1, gy, wt, threads=min(4, H.ORACLE_THREADS)), dtype, 27, c_out)
+    # the weight gradient is split the same way: dense leaves' pairs from the leaf window, the others from the tiles
+    gw, wslots = _kernels_of(lambda: fx.sparse_conv_bwd_weight(km, d_x, d_gy, out_dtype=torch.float32))
+    ref = O.conv_bwd_weight(og, og, 3, 1, feat, gy)
+    num = np.sqrt(((gw.cpu().numpy().astype(np.float64) - ref) ** 2).sum(axis=(1, 2)))
+    den = np.maximum(np.sqrt((ref ** 2).sum(axis=(1, 2))), 1e-3 * np.sqrt(c_in * c_out))
+    assert (num / den).max() <= 2e-3
+    assert torch.equal(gw, fx.sparse_conv_bwd_weight(km, d_x, d_gy, out_dtype=torch.float32))      # fixed order of the sums
     return g
 
 
