@@ -300,7 +300,10 @@ fx_status fx_sparse_conv_fwd_noalloc(const fx_kmap* km, const void* d_feat, fx_d
  * else takes scalar kernels.  In the MFMA weight-gradient kernel a tile whose input rows do not all
  * fit the kernel's local memory has its operand transposed by a multiplication with the identity; on
  * such a tile a non-finite value in feat makes the whole 32-channel block of gw that it touches NaN
- * rather than only its own row.
+ * rather than only its own row.  On the (3,1) map of one grid bwd_weight follows the forward pass's rule for
+ * the leaf-window kernels: at those shapes a locally dense grid (mean leaf occupancy >= 0.40) is summed leaf by
+ * leaf without the map (fx_sparse_conv_leaf_bwd_weight), and a grid that mixes dense and sparse leaves is split per
+ * leaf between that kernel and the tile kernel inside the call (option leaf_dispatch as for the forward pass).
  */
 fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_gout, fx_dtype dt, const void* d_w,
                                   int32_t C_in, int32_t C_out, void* d_gin, fx_dtype out_dt, void* stream);
@@ -393,14 +396,16 @@ fx_status fx_sparse_conv_leaf_fwd(const fx_grid* g, const void* d_feat, fx_dtype
 fx_status fx_sparse_conv_leaf_bwd_data(const fx_grid* g, const void* d_gout, fx_dtype dt, const void* d_w,
                                        int32_t C_in, int32_t C_out, void* d_gin, fx_dtype out_dt, void* stream);
 
-/* Weight gradient of the same convolution without a kernel map (fp32, low depth):
+/* Weight gradient of the same convolution without a kernel map (fp32 at low depth; f16 / bf16 at depth >= 32):
  *     gw[kappa,:,:] = sum over voxels o whose neighbour i at offset kappa is active of  feat[i,:]^T gout[o,:]
  * with the voxels as the contracted dimension of the matrix instructions, straight from the leaf window; same
  * result as fx_sparse_conv_bwd_weight on the (3,1) map of g.
  *   d_feat [N, C_in] and d_gout [N, C_out] device, dtype dt, 16-byte aligned; d_gw [27, C_in, C_out] device,
  *   dtype out_dt; every element is written (zeros for an empty grid).
  * Supported: dt = FX_F32 with C_in in {4, 8, 12, 16} and C_out a multiple of 4 up to 32 (the forward's shapes; C_in
- * of 12 or 16 with more than 16 output channels takes two launches); out_dt = FX_F32; others FX_EUNSUPPORTED.  True fp32 products, fp32 sums in a
+ * of 12 or 16 with more than 16 output channels takes two launches), out_dt = FX_F32; dt = FX_F16 / FX_BF16 with
+ * C_in % 32 == 0 and C_out % 64 == 0, out_dt = dt or FX_F32 (exact products, one rounding of the result); others
+ * FX_EUNSUPPORTED.  fp32 sums in a
  * fixed order (leaves in fixed ranges per workgroup, the workgroups' partial sums added in index order): repeated
  * calls give identical bits.  Allocates the partial sums (one [27, C_in, C_out] fp32 block per workgroup, at
  * most a few thousand) for the call.  Does not synchronise. */
