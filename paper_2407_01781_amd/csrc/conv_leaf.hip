@@ -756,15 +756,17 @@ fx_status launch_leaf16(const fx_grid* g, const void* feat, const void* wpacked,
 // gw[kappa][ci][co] = sum over the active voxels o with an active neighbour at tap kappa of
 // feat[nb(o, kappa)][ci] * gout[o][co], leaf by leaf from the same window as k_conv_leaf16: no kernel map, a tap is an
 // address offset.  A workgroup owns a block of 32 input x 64 output channels of every gw[kappa] and a range of leaves
-// of equal estimated cost; its 16 waves split the taps (wave w: kappa = w and w + 16) and keep their accumulator
-// tiles over the whole range.  Per leaf it stages the window (one 32-channel chunk of every cell, inactive cells
+// of equal estimated cost; its 8 waves split the taps (wave w: kappa = w, w + 8, w + 16 and, for w < 3, w + 24) and keep
+// their accumulator tiles over the whole range (128 registers; two waves per SIMD).  Measured with 4, 12 and 16
+// waves as well: 408, 329 and 335 us on a dense 96^3 grid against 298 -- fewer waves read every gout fragment for
+// more taps, but one wave per SIMD no longer covers its own waits.  Per leaf it stages the window (one 32-channel chunk of every cell, inactive cells
 // zero) and the gout rows of the leaf's active voxels (consecutive rows of the tensor; 128 bytes per voxel, 16-byte
 // pieces swizzled by the voxel's rank), both straight from global memory to LDS.  The voxels are the contracted
 // dimension, so both operands are read with the transposing LDS read (tr_read4): per column tile of 32 voxels a wave
-// reads the gout fragments once for its two taps and, per tap, the window rows of the voxels' neighbours.
+// reads the gout fragments once for its taps and, per tap, the window rows of the voxels' neighbours.
 // A (tile, tap) in which no voxel has that neighbour is skipped; ranks past the leaf's last voxel contribute
 // zeros on both sides.  Partial sums go to part[range][kappa][ci][co]; the ordered reduction adds the ranges.
-constexpr int kWg16Waves = 16;
+constexpr int kWg16Waves = 8;
 constexpr int kWg16Threads = 64 * kWg16Waves;
 constexpr int kWg16Offsets = (27 + kWg16Waves - 1) / kWg16Waves;
 constexpr int kWg16GoutRow = 128;            // 64 output channels of a 16-bit type
@@ -847,8 +849,7 @@ __global__ __launch_bounds__(kWg16Threads, 1) void k_wgrad_leaf16(TreeView t, co
             L.act_row[xy] = (uint32_t)((L.mask[s9][lx] >> (sh + 7)) & 1) | (uint32_t)((L.mask[s9 + 1][lx] >> sh) & 0xff) << 1 |
                             (uint32_t)((L.mask[s9 + 2][lx] >> sh) & 1) << 9;
         }
-        if (tid < kWinCells) {
-            const int cell = tid;
+        for (int cell = tid; cell < kWinCells; cell += kWg16Threads) {
             const int x = cell / 100, y = (cell / 10) % 10, z = cell % 10;
             const int slot = ((x + 7) >> 3) * 9 + ((y + 7) >> 3) * 3 + ((z + 7) >> 3);
             L.cell_row[cell] = staged_value(L, slot, (x - 1) & 7, (y - 1) & 7, (z - 1) & 7);
@@ -856,8 +857,8 @@ __global__ __launch_bounds__(kWg16Threads, 1) void k_wgrad_leaf16(TreeView t, co
         __syncthreads();
         const int n_act = uni((int)((L.prefix[13] >> 54) & 511) + __popcll(L.mask[13][7]));
         const int64_t base = uni(L.offset[13]);
-        if (tid < 512) {
-            const int lx = tid >> 6, ly = (tid >> 3) & 7, lz = tid & 7;
+        for (int m = tid; m < 512; m += kWg16Threads) {
+            const int lx = m >> 6, ly = (m >> 3) & 7, lz = m & 7;
             const int row = L.cell_row[window_cell(lx + 1, ly + 1, lz + 1)];
             if (row >= 0) {
                 const int r = row - (int)base;
@@ -875,7 +876,7 @@ __global__ __launch_bounds__(kWg16Threads, 1) void k_wgrad_leaf16(TreeView t, co
         // and all plain stores come before the first asynchronous load is issued.
         {
             constexpr int kSlabsPerWave = (kWinSlabs + kWg16Waves - 1) / kWg16Waves;
-            constexpr int kGoutSlabsPerWave = 512 * kWg16GoutRow / 1024 / kWg16Waves;
+            constexpr int kGoutSlabs = 512 * kWg16GoutRow / 1024, kGoutSlabsPerWave = (kGoutSlabs + kWg16Waves - 1) / kWg16Waves;
             int rows[kSlabsPerWave];
 #pragma unroll
             for (int j = 0; j < kSlabsPerWave; ++j) {
@@ -890,7 +891,7 @@ __global__ __launch_bounds__(kWg16Threads, 1) void k_wgrad_leaf16(TreeView t, co
 #pragma unroll
             for (int j = 0; j < kGoutSlabsPerWave; ++j) {
                 const int slab = wave + j * kWg16Waves, r = 8 * slab + (lane >> 3);
-                if (r >= n_act) *reinterpret_cast<u32x4*>(L.gt + slab * 1024 + lane * 16) = u32x4{0, 0, 0, 0};
+                if (slab < kGoutSlabs && r >= n_act) *reinterpret_cast<u32x4*>(L.gt + slab * 1024 + lane * 16) = u32x4{0, 0, 0, 0};
             }
             const int piece = (lane & 3) ^ ((lane >> 4) & 3);
 #pragma unroll
@@ -903,14 +904,14 @@ __global__ __launch_bounds__(kWg16Threads, 1) void k_wgrad_leaf16(TreeView t, co
             for (int j = 0; j < kGoutSlabsPerWave; ++j) {
                 const int slab = wave + j * kWg16Waves, r = 8 * slab + (lane >> 3);
                 const int gpiece = (lane & 7) ^ (((r >> 1) & 1) << 2);
-                if (r < n_act)
+                if (slab < kGoutSlabs && r < n_act)
                     __builtin_amdgcn_global_load_lds(gout + (base + r) * (int64_t)C_out + cob * 64 + gpiece * 8, (leaf_lds_ptr)(L.gt + slab * 1024), 16, 0, 0);
             }
             __builtin_amdgcn_s_waitcnt(0);
         }
         __syncthreads();
 
-        // ---- multiply; the last wave first walks the tree for the next leaf's records, which nobody reads meanwhile
+        // ---- multiply; the last wave (three taps, not four) first walks the tree for the next leaf's records, which nobody reads meanwhile
         if (wave == kWg16Waves - 1 && f + 1 < f_end) stage_records(t, L, leaf_of(f + 1), lane);
         const int n_tiles = (n_act + 31) >> 5;
         for (int g = 0; g < n_tiles; ++g) {
