@@ -319,9 +319,10 @@ __global__ void k_conv_transpose_scalar(const int32_t* __restrict__ nbmap, int64
 
 // ---------------------------------------------------------------------------------- weight gradient, MFMA
 // A workgroup owns a block of 32 input channels x 64 output channels of every gw[kappa] and a
-// contiguous range of tiles; its 16 waves split the offsets (wave w: kappa = w, w+16), so a wave
-// keeps 2 offsets x 2 accumulator tiles (32 ci x 32 co) in registers over the whole range, and four
-// waves per SIMD hide each other's LDS and matrix latencies.  Per tile the workgroup stages,
+// contiguous range of tiles; its 8 waves split the offsets (wave w: kappa = w, w+8, w+16, w+24), so a wave
+// keeps up to 4 offsets x 2 accumulator tiles (32 ci x 32 co) in registers over the whole range, and two
+// waves per SIMD hide each other's LDS and matrix latencies (16 waves with two offsets each have 128 registers
+// per wave, which the loop does not fit without spilling: 261 us against 208 on a 1 M-voxel LiDAR grid; 4 waves 279).  Per tile the workgroup stages,
 // single-buffered and all with loads that go straight from global memory to LDS: the tile's input rows
 // (32 channels, the forward kernel's LDS row layout, so the map's precomputed LDS offsets apply), its id
 // blocks, and the gout rows of its 512 output slots (64 channels = 128 bytes per slot; 16-byte piece p of
@@ -345,14 +346,14 @@ __global__ void k_conv_transpose_scalar(const int32_t* __restrict__ nbmap, int64
 // with voxels along k; rounding back to the storage type is exact.
 // Partial sums go to part[range][kappa][ci][co] (fp32); k_wgrad_reduce adds the ranges in
 // ascending order, so the result does not depend on scheduling.
-constexpr int kWgWaves = 16;
+constexpr int kWgWaves = 8;
 constexpr int kWgThreads = 64 * kWgWaves;
 constexpr int kWgCi = kCinChunk;            // 32: the row chunk staged in LDS
 constexpr int kWgCo = 64;
 constexpr int kGoutRowBytes = kWgCo * 2;    // one slot of the staged gout tile
 constexpr int kGoutSlabs = kTileT * kGoutRowBytes / 1024;     // 1 KB slabs: 8 slots each
 constexpr int kGoutSlabsPerWave = kGoutSlabs / kWgWaves;
-constexpr int kWgOffsetsPerWave = (kMaxK3Tiled + kWgWaves - 1) / kWgWaves;   // 4
+constexpr int kWgOffsetsPerWave = (kMaxK3Tiled + kWgWaves - 1) / kWgWaves;
 
 struct WgradLds {
     unsigned char rows[kRowBufBytes];
