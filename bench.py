@@ -365,13 +365,17 @@ def main():
         h_w = (torch.randn((27, 64, 64), device="cuda") * (1.0 / (27 * 64)) ** 0.5).to(torch.bfloat16)
         t_l16 = b2b(lambda: fx.sparse_conv_leaf_fwd(gv, h_feat, h_w), reps=5)
         t_c16 = b2b(lambda: fx.sparse_conv_fwd(kmv, h_feat, h_w), reps=5)
+        h_gy = torch.randn((nv, 64), device="cuda").to(torch.bfloat16)
+        t_lw16 = b2b(lambda: fx.sparse_conv_leaf_bwd_weight(gv, h_feat, h_gy), reps=5)
+        t_tw16 = b2b(lambda: fx.sparse_conv_bwd_weight(kmv, h_feat, h_gy), reps=3)      # dispatch is off: the tile kernel
         fx.set_option("leaf_dispatch", -1)
         h_flops = 2.0 * v_pairs * 64 * 64
         low_depth["leaf_window_bf16_64"] = {
             "leaf_conv_ms": t_l16, "leaf_conv_effective_TFLOPs": h_flops / (t_l16 * 1e-3) / 1e12,
             "frac_of_bf16_mfma_peak": h_flops / (t_l16 * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS["bf16"],
-            "kernel_map_path_ms": {"kernel_map": t_kmv, "conv": t_c16}}
-        del kmv, gv, v_feat, h_feat
+            "leaf_bwd_weight_ms": t_lw16, "leaf_bwd_weight_effective_TFLOPs": h_flops / (t_lw16 * 1e-3) / 1e12,
+            "kernel_map_path_ms": {"kernel_map": t_kmv, "conv": t_c16, "bwd_weight_tiles": t_tw16}}
+        del kmv, gv, v_feat, h_feat, h_gy
 
     # ---- per-leaf dispatch (the paper's future-work item; Sec. 3.5's scenarios are its regimes) on a grid that mixes
     # the sparsity classes: the same convolution through the tile kernel alone, the leaf-window kernel alone, and
