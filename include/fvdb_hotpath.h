@@ -88,7 +88,9 @@ void fx_release_cached_memory(void);
  *                    share of voxels in dense leaves (see fx_sparse_conv_fwd)
  *   "fp32_tiles"     1: FX_F32 takes the matrix-unit tile kernel at any grid size (automatic: from ~128 tiles on)
  *   "conv_gather"    0 / 1: the LDS-staged / the gather kernel on every tiled map (automatic: by the kind of map)
- *   "gather_lds"     0: the gather kernels fetch their weights per step instead of keeping them in LDS
+ *   "gather_lds"     0: the gather kernels fetch their weights per step instead of keeping them in LDS; 1: the
+ *                    forward gather kernel keeps one 64-channel output slice's weights in LDS (automatic: two
+ *                    slices when both fit, so that a gathered row serves 128 output channels)
  *   "scalar_lds"     0: the scalar kernel reads its weights through L1 instead of LDS
  *   "grid_direct"    1: the grid build skips the bucket pass (one global leaf table)
  *   "cache_mb"       MiB of released device blocks kept for reuse (automatic: 2048)

@@ -769,12 +769,13 @@ k_conv_gather(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restric
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wa[mt * 2 + ks], ba[ks], acc[mt]);
-        if (step + 1 >= n_steps) break;
         if (step + 2 < n_steps) fetch(ba, wa, step + 2, rest, kappa);
+        if (step + 1 < n_steps) {       // a guard, not an early exit: one loop exit keeps one copy of the accumulators
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
+            for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wb[mt * 2 + ks], bb[ks], acc[mt]);
+                for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wb[mt * 2 + ks], bb[ks], acc[mt]);
+        }
     }
 
     const int local = tile_perm[tile * kTileT + g * kGroup + n];
@@ -808,13 +809,21 @@ k_conv_gather(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restric
 // is bound by the load path of the compute unit (one wave-wide 16-byte load occupies it for at
 // least 16 cycles).  When the packed weights of one 64-channel output slice fit in LDS next to
 // the row tables (K^3 * C_in * 128 bytes; 64 KB for a 2x2x2 kernel with 64 input channels), a
-// persistent workgroup of 16 waves copies them there once, and each wave then walks column
-// blocks of that slice exactly as k_conv_gather does, with its A fragments read from LDS: two
-// vector loads per four multiplies.  Workgroup b serves slice b % nslice.
+// persistent workgroup copies them there once, and each wave then walks column blocks exactly as
+// k_conv_gather does, with its A fragments read from LDS: two vector loads per four multiplies.
+// What bounds the kernel then is the gather itself (rows in flight per compute unit), so when the
+// weights of two adjacent slices fit together (NS = 2) a gathered fragment feeds the multiplies of
+// both and the gather is issued once per 128 output channels; that form runs twelve waves with a
+// third more registers (64 more accumulators), and with CP = 2 a step covers two 32-channel chunks,
+// so its four loads use the whole 128-byte line of a 64-channel row while it is in L1 instead of
+// coming back for the second half a step later.  Workgroup b serves slice set b % (nslice / NS).
+// NS = output slices per workgroup, CP = 32-channel chunks per step, W = waves per workgroup,
+// D = fragment sets in flight.
 constexpr int kGatherLdsWaves = 16;
+constexpr int kGatherPairWaves = 12;
 
-template <typename T, bool OUT_F32>
-__global__ void __launch_bounds__(64 * kGatherLdsWaves, 1)
+template <typename T, bool OUT_F32, int NS, int CP, int W, int D>
+__global__ void __launch_bounds__(64 * W, 1)
 k_conv_gather_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
                    const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
                    int block_stride, int64_t n_blocks_total, int K3, const uint16_t* __restrict__ feat,
@@ -822,16 +831,17 @@ k_conv_gather_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __re
     typedef typename Elem<T>::vec8 vec8;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice;
-    const int slice = blockIdx.x % nslice;
-    const int wg = blockIdx.x / nslice, n_wg = gridDim.x / nslice;      // the launch makes gridDim a multiple of nslice
-    unsigned char* wlds = lds_raw;                                       // [kappa][chunk][4 fragments][64 lanes][16 bytes]
-    const int w_bytes = K3 * nchunk * 4096;
+    const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice, nset = nslice / NS;
+    const int npair = nchunk / CP;                                       // steps per offset (the launch checks CP | nchunk)
+    const int slice = (blockIdx.x % nset) * NS;                          // first slice of this workgroup's set
+    const int wg = blockIdx.x / nset, n_wg = gridDim.x / nset;           // the launch makes gridDim a multiple of nset
+    unsigned char* wlds = lds_raw;                                       // [kappa][chunk][slice of the set][4 fragments][64 lanes][16 bytes]
+    const int w_bytes = K3 * nchunk * NS * 4096;
     int32_t* row_of = reinterpret_cast<int32_t*>(lds_raw + w_bytes) + wave * 2 * K3 * kGroup;   // two tables [rank][voxel]
 
-    for (int sl = wave; sl * 1024 < w_bytes; sl += kGatherLdsWaves) {   // 1 KB = one fragment of all lanes
-        const int kc = sl >> 2, f = sl & 3;                              // (kappa * nchunk + chunk), fragment
-        const unsigned char* src = reinterpret_cast<const unsigned char*>(wp) + ((size_t)(kc * nslice + slice) * 4 + f) * 1024 + lane * 16;
+    for (int sl = wave; sl * 1024 < w_bytes; sl += W) {                  // 1 KB = one fragment of all lanes
+        const int kc = sl / (4 * NS), sn = (sl >> 2) % NS, f = sl & 3;   // (kappa * nchunk + chunk), slice of the set, fragment
+        const unsigned char* src = reinterpret_cast<const unsigned char*>(wp) + ((size_t)(kc * nslice + slice + sn) * 4 + f) * 1024 + lane * 16;
         __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(wlds + sl * 1024), 16, 0, 0);
     }
     __builtin_amdgcn_s_waitcnt(0);
@@ -869,8 +879,8 @@ k_conv_gather_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __re
     };
     // Two row tables per wave: the next block's table is resolved (two dependent global loads) while
     // the current block multiplies.
-    const int64_t tg_stride = (int64_t)n_wg * kGatherLdsWaves;
-    int64_t tg = (int64_t)wg * kGatherLdsWaves + wave;
+    const int64_t tg_stride = (int64_t)n_wg * W;
+    int64_t tg = (int64_t)wg * W + wave;
     int cur = 0;
     uint32_t gm_next = tg < n_blocks_total ? resolve(tg, row_of) : 0u;
 #pragma unroll 1
@@ -884,73 +894,92 @@ k_conv_gather_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __re
         __builtin_amdgcn_wave_barrier();
         if (tg + tg_stride < n_blocks_total) gm_next = resolve(tg + tg_stride, row_of + (cur ^ 1) * K3 * kGroup);
 
-        f32x16 acc[2];
+        f32x16 acc[2 * NS];
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int mt = 0; mt < 2 * NS; ++mt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
-        const int n_steps = __popc(gm) * nchunk;        // step = (offset rank, chunk), chunk fastest
+        const int n_steps = __popc(gm) * npair;         // step = (offset rank, CP chunks), chunks fastest
         // B fragments of step `step` into b; returns where the step's A fragments start in LDS
-        // fetches come in step order: (offset rank, chunk) advance with them
-        int f_rank = -1, f_c = nchunk - 1;
-        auto fetch = [&](vec8 (&b)[2], int step, uint32_t& rest, int& kappa) {
-            if (++f_c == nchunk) { f_c = 0; ++f_rank; kappa = __ffs(rest | 0x80000000u) - 1; rest &= rest - 1; }
+        // fetches come in step order: (offset rank, chunk pair) advance with them
+        int f_rank = -1, f_c = npair - 1;
+        auto fetch = [&](vec8 (&b)[2 * CP], int step, uint32_t& rest, int& kappa) {
+            if (++f_c == npair) { f_c = 0; ++f_rank; kappa = __ffs(rest | 0x80000000u) - 1; rest &= rest - 1; }
             const int32_t r = step < n_steps ? tab[f_rank * kGroup + n] : -1;
-            b[0] = zero; b[1] = zero;
+#pragma unroll
+            for (int j = 0; j < 2 * CP; ++j) b[j] = zero;
             if (r >= 0) {
-                const uint16_t* src = feat + (int64_t)r * C_in + f_c * kCinChunk + h * 8;
-                b[0] = *reinterpret_cast<const vec8*>(src);
-                b[1] = *reinterpret_cast<const vec8*>(src + 16);
+                const uint16_t* src = feat + (int64_t)r * C_in + f_c * (CP * kCinChunk) + h * 8;
+#pragma unroll
+                for (int j = 0; j < 2 * CP; ++j) b[j] = *reinterpret_cast<const vec8*>(src + 16 * j);
             }
-            return (kappa * nchunk + f_c) * 4096 + lane * 16;
+            return (kappa * nchunk + f_c * CP) * NS * 4096 + lane * 16;
         };
-        auto multiply = [&](const vec8 (&b)[2], int w_at) {
-            vec8 wf[4];
+        auto multiply = [&](const vec8 (&b)[2 * CP], int w_at) {
 #pragma unroll
-            for (int f = 0; f < 4; ++f) wf[f] = *reinterpret_cast<const vec8*>(wlds + w_at + f * 1024);
+            for (int c = 0; c < CP; ++c)
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
+                for (int sn = 0; sn < NS; ++sn) {
+                    vec8 wf[4];
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wf[mt * 2 + ks], b[ks], acc[mt]);
+                    for (int f = 0; f < 4; ++f)
+                        wf[f] = *reinterpret_cast<const vec8*>(wlds + w_at + (c * NS + sn) * 4096 + f * 1024);
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                        for (int mt = 0; mt < 2; ++mt)
+                            acc[2 * sn + mt] = Elem<T>::mfma(wf[mt * 2 + ks], b[2 * c + ks], acc[2 * sn + mt]);
+                }
         };
         // the gather of the next step is in flight while one multiplies (two fragment sets; a deeper
         // ring at three waves per SIMD measured slower: 85 us against 79 at config 4)
-        vec8 ba[2], bb[2];
+        // D fragment sets: the gathers of the next D - 1 steps are in flight while one multiplies.  The loop has one
+        // exit and guards instead of breaks: with early exits between the multiplies the compiler kept a second
+        // copy of the accumulators (80 registers more).
+        vec8 ring[D][2 * CP];
+        int w_at[D];
         uint32_t rest = gm;
-        int kappa = 0, wa_at = 0, wb_at = 0;
-        if (n_steps > 0) wa_at = fetch(ba, 0, rest, kappa);
+        int kappa = 0;
+#pragma unroll
+        for (int d = 0; d < D - 1; ++d) { w_at[d] = 0; if (d < n_steps) w_at[d] = fetch(ring[d], d, rest, kappa); }
+        w_at[D - 1] = 0;
 #pragma unroll 1
-        for (int step = 0; step < n_steps; step += 2) {
-            if (step + 1 < n_steps) wb_at = fetch(bb, step + 1, rest, kappa);
-            multiply(ba, wa_at);
-            if (step + 1 >= n_steps) break;
-            if (step + 2 < n_steps) wa_at = fetch(ba, step + 2, rest, kappa);
-            multiply(bb, wb_at);
+        for (int step = 0; step < n_steps; step += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                if (step + d + D - 1 < n_steps) w_at[(d + D - 1) % D] = fetch(ring[(d + D - 1) % D], step + d + D - 1, rest, kappa);
+                if (step + d < n_steps) multiply(ring[d], w_at[d]);
+            }
         }
 
         const int local = tile_perm[tile * kTileT + g * kGroup + n];
         if (local < n_valid) {
             const int64_t o = tile * kTileT + local;
-            const int64_t col = (int64_t)slice * kCoutSlice + 32 * h;
-            if (OUT_F32) {
-                float* dst = reinterpret_cast<float*>(out) + o * C_out + col;
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
+            for (int sn = 0; sn < NS; ++sn) {
+                const int64_t col = (int64_t)(slice + sn) * kCoutSlice + 32 * h;
+                if (OUT_F32) {
+                    float* dst = reinterpret_cast<float*>(out) + o * C_out + col;
 #pragma unroll
-                    for (int v4 = 0; v4 < 4; ++v4)
-                        *reinterpret_cast<f32x4*>(dst + 16 * mt + 4 * v4) =
-                            f32x4{acc[mt][4 * v4], acc[mt][4 * v4 + 1], acc[mt][4 * v4 + 2], acc[mt][4 * v4 + 3]};
-            } else {
-                uint16_t* dst = reinterpret_cast<uint16_t*>(out) + o * C_out + col;
+                    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
+                        for (int v4 = 0; v4 < 4; ++v4)
+                            *reinterpret_cast<f32x4*>(dst + 16 * mt + 4 * v4) =
+                                f32x4{acc[2 * sn + mt][4 * v4], acc[2 * sn + mt][4 * v4 + 1], acc[2 * sn + mt][4 * v4 + 2],
+                                      acc[2 * sn + mt][4 * v4 + 3]};
+                } else {
+                    uint16_t* dst = reinterpret_cast<uint16_t*>(out) + o * C_out + col;
 #pragma unroll
-                    for (int v8 = 0; v8 < 2; ++v8) {
-                        u32x4 pk;
+                    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) pk[e] = Elem<T>::pack2(acc[mt][8 * v8 + 2 * e], acc[mt][8 * v8 + 2 * e + 1]);
-                        *reinterpret_cast<u32x4*>(dst + 16 * mt + 8 * v8) = pk;
-                    }
+                        for (int v8 = 0; v8 < 2; ++v8) {
+                            u32x4 pk;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                pk[e] = Elem<T>::pack2(acc[2 * sn + mt][8 * v8 + 2 * e], acc[2 * sn + mt][8 * v8 + 2 * e + 1]);
+                            *reinterpret_cast<u32x4*>(dst + 16 * mt + 8 * v8) = pk;
+                        }
+                }
             }
         }
     }
@@ -1062,20 +1091,36 @@ static hipError_t launch_mfma(const fx_kmap* km, const void* feat, const void* w
 template <typename T, bool OUT_F32>
 static hipError_t launch_gather(const fx_kmap* km, const void* feat, const void* wp, int C_in, int C_out, void* out,
                                 hipStream_t st) {
-    const int nslice = C_out / kCoutSlice;
-    const size_t lds = (size_t)km->K3 * (C_in / kCinChunk) * 4096 + (size_t)kGatherLdsWaves * 2 * km->K3 * kGroup * sizeof(int32_t);
-    if (lds <= 160 * 1024 && option(kOptGatherLds) != 0) {      // option gather_lds = 0: never keep the weights in LDS
-        hipError_t e = hipFuncSetAttribute((const void*)k_conv_gather_ldsw<T, OUT_F32>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+    const int nslice = C_out / kCoutSlice, nchunk = C_in / kCinChunk;
+    const size_t w_slice = (size_t)km->K3 * nchunk * 4096;                   // packed weights of one output slice
+    auto tables = [&](int waves) { return (size_t)waves * 2 * km->K3 * kGroup * sizeof(int32_t); };
+    if (w_slice + tables(kGatherLdsWaves) <= 160 * 1024 && option(kOptGatherLds) != 0) {   // option gather_lds = 0: never keep the weights in LDS
+        // two slices per workgroup, at twelve waves with a third more registers each, when their weights fit
+        // together (option gather_lds = 1: always one slice)
+        const int ns = (nslice % 2 == 0 && 2 * w_slice + tables(kGatherPairWaves) <= 160 * 1024 && option(kOptGatherLds) != 1) ? 2 : 1;
+        const int cp = (ns == 2 && nchunk % 2 == 0) ? 2 : 1;
+        const int waves = ns == 2 ? kGatherPairWaves : kGatherLdsWaves;
+        const size_t lds = ns * w_slice + tables(waves);
         const int64_t n_blocks_total = km->n_tiles * (int64_t)kGroupsPerTile;
-        // one workgroup per compute unit, a multiple of the slice count, no more than there is work for
-        int64_t grid = std::max(nslice, compute_units() / nslice * nslice);
-        grid = std::min<int64_t>(grid, (n_blocks_total + kGatherLdsWaves - 1) / kGatherLdsWaves * nslice);
-        k_conv_gather_ldsw<T, OUT_F32><<<(unsigned)grid, 64 * kGatherLdsWaves, lds, st>>>(
-            km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows, km->row_stride, km->d_tile_blocks, km->block_stride,
-            n_blocks_total, km->K3, (const uint16_t*)feat, (const uint16_t*)wp, C_in, C_out, out);
-        return hipGetLastError();
+        // one workgroup per compute unit, a multiple of the number of slice sets, no more than there is work for
+        const int nset = nslice / ns;
+        int64_t grid = std::max(nset, compute_units() / nset * nset);
+        grid = std::min<int64_t>(grid, (n_blocks_total + waves - 1) / waves * nset);
+#define FX_GATHER_LDSW(NS_, CP_, W_, D_)                                                                                 \
+        if (ns == NS_ && cp == CP_) {                                                                                    \
+            hipError_t e = hipFuncSetAttribute((const void*)k_conv_gather_ldsw<T, OUT_F32, NS_, CP_, W_, D_>,            \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                   \
+            if (e != hipSuccess) return e;                                                                               \
+            k_conv_gather_ldsw<T, OUT_F32, NS_, CP_, W_, D_><<<(unsigned)grid, 64 * W_, lds, st>>>(                      \
+                km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows, km->row_stride, km->d_tile_blocks, km->block_stride,   \
+                n_blocks_total, km->K3, (const uint16_t*)feat, (const uint16_t*)wp, C_in, C_out, out);                   \
+            return hipGetLastError();                                                                                    \
+        }
+        // measured at config 4 (64 -> 128): 58 us for (2, 2, 12 waves, 3 sets), 58-59 for 8 waves with 2 to 4 sets,
+        // 63-64 for one chunk per step, 79-81 for one slice per workgroup
+        FX_GATHER_LDSW(1, 1, kGatherLdsWaves, 4) FX_GATHER_LDSW(2, 1, kGatherPairWaves, 4) FX_GATHER_LDSW(2, 2, kGatherPairWaves, 3)
+#undef FX_GATHER_LDSW
+        return hipErrorInvalidValue;
     }
     const int64_t n_items = km->n_tiles * (int64_t)kGroupsPerTile * (C_out / kCoutSlice);
     const unsigned grid = (unsigned)((n_items + kGatherWaves - 1) / kGatherWaves);

@@ -46,12 +46,14 @@ def test_both_mfma_kernels_serve_every_map(name, gather, fx_opt):
     H.conv_tolerance_check(y, ref, dt, k3, c_in)
 
 
-@pytest.mark.parametrize("lds_weights", ["0", "1"])
+@pytest.mark.parametrize("lds_weights", ["0", "1", "-1"])
 def test_gather_kernel_with_and_without_weights_in_lds(lds_weights, fx_opt):
-    # strided maps: by default the packed weights of a slice sit in LDS when they fit; the switch
-    # sends the same map to the kernel that fetches them per step
+    # strided maps: by default the packed weights of one or two output slices sit in LDS when they fit
+    # (64 -> 128 and 32 -> 256: two slices; 32 -> 64 and 64 -> 192: one); the switch sends the same map to
+    # the one-slice form or to the kernel that fetches them per step
     fx_opt("gather_lds", lds_weights)
-    for name, c_in, c_out in (("lidar_small_down", 64, 128), ("lidar_small_down", 32, 64), ("sheets_small", 32, 64)):
+    for name, c_in, c_out in (("lidar_small_down", 64, 128), ("lidar_small_down", 32, 64), ("lidar_small_down", 32, 256),
+                              ("lidar_small_down", 64, 192), ("sheets_small", 32, 64)):
         if name == "sheets_small":
             fx_opt("conv_gather", "1")      # K = 3: 27 x 32 channels no longer fit, falls back
         y, ref, dt, k3, ci = _run(G.workload(name), c_in=c_in, c_out=c_out, dtype="bf16")
