@@ -148,66 +148,89 @@ k_dgrad_strided(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restr
 
 // The same product with the packed weights of one produced slice kept in LDS and the block's B
 // fragments kept in registers for all offsets (at most kDgradMaxChunks 32-channel chunks): the
-// offset loop then issues no vector loads at all.  Persistent workgroups of 16 waves; workgroup b
+// offset loop then issues no vector loads at all.  Persistent workgroups of W waves; workgroup b
 // serves produced slice b % nslice and walks column blocks with a stride.
-constexpr int kDgradLdsWaves = 16;
+//
+// What a block needs before its first multiply hangs on chains of dependent loads (tile header ->
+// id block -> row list; output permutation -> gout rows), and a wave that walked them block by block
+// spent most of its time waiting.  The chains are therefore cut into stages that run one or two
+// blocks ahead: the header and permutation entry of block i + 2 are requested while block i
+// multiplies, the ids and the gout fragments of block i + 1 are requested before block i's offset
+// loop (into a second fragment set) and turned into the row table after it.  R = offset ranks a lane
+// half resolves (ceil(K^3 / 2)).
+//
+// Operand roles: A = gout rows (32 voxels x 16 contracted channels), B = packed weights in the
+// interleaved layout (column n of n-tile t = produced channel 2n + t), so the produced rows lie along
+// the accumulator registers and the channels across the lanes: a half-wave stores one produced row's
+// 64-channel slice as one contiguous 128-byte (bf16) piece, where the other assignment wrote sixteen
+// bytes per lane to 64 different rows per instruction.
+constexpr int kDgradLdsWaves = 12;
 constexpr int kDgradMaxChunks = 4;
 
-template <typename T, bool OUT_F32>
-__global__ void __launch_bounds__(64 * kDgradLdsWaves, 1)
+template <typename T, bool OUT_F32, int W, int R>
+__global__ void __launch_bounds__(64 * W, 1)
 k_dgrad_strided_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
                      const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
                      int block_stride, int64_t n_blocks_total, int K3, const uint16_t* __restrict__ gout,
                      const uint16_t* __restrict__ wp, int C_contract, int C_produce, void* __restrict__ gin) {
     typedef typename Elem<T>::vec8 vec8;
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = uni((int)(threadIdx.x >> 6));
     const int nchunk = C_contract / kCinChunk, nslice = C_produce / kCoutSlice;
     const int slice = blockIdx.x % nslice;
     const int wg = blockIdx.x / nslice, n_wg = gridDim.x / nslice;
     unsigned char* wlds = lds_raw;                                       // [kappa][chunk][4 fragments][64 lanes][16 bytes]
     const int w_bytes = K3 * nchunk * 4096;
-    int32_t* row_of = reinterpret_cast<int32_t*>(lds_raw + w_bytes) + wave * K3 * kGroup;   // [rank][voxel]
-    for (int sl = wave; sl * 1024 < w_bytes; sl += kDgradLdsWaves) {
+    int32_t* tab = reinterpret_cast<int32_t*>(lds_raw + w_bytes) + wave * K3 * kGroup;   // [rank][voxel]
+    for (int sl = wave; sl * 1024 < w_bytes; sl += W) {
         const int kc = sl >> 2, f = sl & 3;
         const unsigned char* src = reinterpret_cast<const unsigned char*>(wp) + ((size_t)(kc * nslice + slice) * 4 + f) * 1024 + lane * 16;
         __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(wlds + sl * 1024), 16, 0, 0);
     }
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
 
     const int n = lane & 31, h = lane >> 5;
     vec8 zero;
 #pragma unroll
     for (int e = 0; e < 8; ++e) zero[e] = 0;
-#pragma unroll 1
-    for (int64_t tg = (int64_t)wg * kDgradLdsWaves + wave; tg < n_blocks_total; tg += (int64_t)n_wg * kDgradLdsWaves) {
+    const int64_t tg_stride = (int64_t)n_wg * W;
+    const int64_t tg0 = (int64_t)wg * W + wave;
+
+    struct Hdr { uint32_t gm, wm, blk0; int flags, win_lo, win_n, n_out; };
+    // the header fields of block tg (uniform addresses: scalar loads)
+    auto load_hdr = [&](int64_t tg) -> Hdr {
+        Hdr d = {0u, 0u, 0u, 0, 0, 0, 0};
+        if (tg < n_blocks_total) {
+            const int g = (int)(tg % kGroupsPerTile);
+            const TileHeader* H = tile_hdr + tg / kGroupsPerTile;
+            const int w = tile_wave_of(g);
+            d.gm = H->group_mask[g]; d.wm = H->wave_mask[w]; d.blk0 = H->wave_block0[w];
+            d.flags = H->flags; d.win_lo = H->win_lo; d.win_n = H->win_n; d.n_out = H->n_out;
+        }
+        return d;
+    };
+    auto load_perm = [&](int64_t tg) -> int {
+        return tg < n_blocks_total ? (int)tile_perm[tg / kGroupsPerTile * kTileT + (tg % kGroupsPerTile) * kGroup + n] : 0;
+    };
+    // requests the local row ids of block tg: lane (n, h) takes the offset ranks of parity h, slot j = rank / 2
+    auto issue_ids = [&](int64_t tg, const Hdr& d, uint32_t (&idv)[R]) {
         const int g = (int)(tg % kGroupsPerTile);
-        const int64_t tile = tg / kGroupsPerTile;
-        const TileHeader* H = tile_hdr + tile;
-        const int w = tile_wave_of(g), gi = tile_slot_of(g);
-        const uint32_t gm = (uint32_t)uni((int)H->group_mask[g]);
-        const uint32_t wm = (uint32_t)uni((int)H->wave_mask[w]);
-        const int n_valid = uni(H->n_out);
-        {
-            const int flags = uni(H->flags), win_lo = uni(H->win_lo), win_n = uni(H->win_n);
-            const size_t blk0 = (size_t)tile * block_stride + (uint32_t)uni((int)H->wave_block0[w]);
-            const int32_t* rows = tile_rows + tile * (int64_t)row_stride;
-            int rank = 0;
-#pragma unroll 1
-            for (uint32_t m = gm; m; m &= m - 1, ++rank) {
-                if ((rank & 1) != h) continue;
+        const int gi = tile_slot_of(g);
+        const size_t blk0 = (size_t)(tg / kGroupsPerTile) * block_stride + d.blk0;
+        uint32_t m = d.gm;
+#pragma unroll
+        for (int j = 0; j < 2 * R; ++j) {
+            if (m) {
                 const int kappa = __ffs(m) - 1;
-                const size_t blk = blk0 + __popc(wm & ((1u << kappa) - 1u));
-                const uint32_t id = tile_blocks[blk * kIdBlockElems + n * kGroupsPerWave + gi];
-                row_of[rank * kGroup + n] = tile_row_of(id, flags, win_lo, win_n, rows);
+                m &= m - 1;
+                if ((j & 1) == h)
+                    idv[j >> 1] = tile_blocks[(blk0 + __popc(d.wm & ((1u << kappa) - 1u))) * kIdBlockElems + n * kGroupsPerWave + gi];
             }
         }
-        // the block's rows of the contracted side, all chunks, for every offset
-        const int local = tile_perm[tile * kTileT + g * kGroup + n];
-        const bool valid = local < n_valid;
-        const uint16_t* grow = gout + (tile * kTileT + (valid ? local : 0)) * (int64_t)C_contract + h * 8;
-        vec8 b[kDgradMaxChunks][2];
+    };
+    // requests the block's rows of the contracted side, all chunks
+    auto issue_rows = [&](int64_t tg, const Hdr& d, int local, vec8 (&b)[kDgradMaxChunks][2]) {
+        const bool valid = local < d.n_out;
+        const uint16_t* grow = gout + (tg / kGroupsPerTile * kTileT + (valid ? local : 0)) * (int64_t)C_contract + h * 8;
 #pragma unroll
         for (int c = 0; c < kDgradMaxChunks; ++c) {
             b[c][0] = zero; b[c][1] = zero;
@@ -216,12 +239,49 @@ k_dgrad_strided_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __
                 b[c][1] = *reinterpret_cast<const vec8*>(grow + c * kCinChunk + 16);
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    };
+    // ids -> global produced rows (a second load for ids outside the tile's window), into the wave's table
+    auto finish_table = [&](int64_t tg, const Hdr& d, const uint32_t (&idv)[R]) {
+        const int32_t* rows = tile_rows + tg / kGroupsPerTile * (int64_t)row_stride;
+        const int n_k = __popc(d.gm);
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const int rank = 2 * j + h;
+            if (rank < n_k) tab[rank * kGroup + n] = tile_row_of(idv[j], d.flags, d.win_lo, d.win_n, rows);
+        }
+    };
+
+    Hdr h0 = load_hdr(tg0), h1 = load_hdr(tg0 + tg_stride);
+    int p0 = load_perm(tg0), p1 = load_perm(tg0 + tg_stride);
+    uint32_t idv[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) idv[j] = kNoRow;
+    vec8 bc[kDgradMaxChunks][2], bn[kDgradMaxChunks][2];
+#pragma unroll
+    for (int c = 0; c < kDgradMaxChunks; ++c) { bc[c][0] = zero; bc[c][1] = zero; bn[c][0] = zero; bn[c][1] = zero; }
+    if (tg0 < n_blocks_total) {
+        issue_ids(tg0, h0, idv);
+        issue_rows(tg0, h0, p0, bc);
+        finish_table(tg0, h0, idv);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();                       // the weights are in LDS
+
+#pragma unroll 1
+    for (int64_t tg = tg0; tg < n_blocks_total; tg += tg_stride) {
+        const Hdr h2 = load_hdr(tg + 2 * tg_stride);
+        const int p2 = load_perm(tg + 2 * tg_stride);
+        const bool more = tg + tg_stride < n_blocks_total;
+        if (more) {
+            issue_ids(tg + tg_stride, h1, idv);
+            issue_rows(tg + tg_stride, h1, p1, bn);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // a wave's LDS accesses are processed in order
         __builtin_amdgcn_wave_barrier();
 
         int rank = 0;
 #pragma unroll 1
-        for (uint32_t m = gm; m; m &= m - 1, ++rank) {
+        for (uint32_t m = h0.gm; m; m &= m - 1, ++rank) {
             const int kappa = __ffs(m) - 1;
             f32x16 acc[2];
 #pragma unroll
@@ -238,34 +298,33 @@ k_dgrad_strided_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                        for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wf[mt * 2 + ks], b[c][ks], acc[mt]);
+                        for (int nt = 0; nt < 2; ++nt) acc[nt] = Elem<T>::mfma(bc[c][ks], wf[nt * 2 + ks], acc[nt]);
                 }
             }
-            const int32_t r = row_of[rank * kGroup + n];
-            if (r < 0) continue;
-            const int64_t col = (int64_t)slice * kCoutSlice + 32 * h;
-            if (OUT_F32) {
-                float* dst = reinterpret_cast<float*>(gin) + (int64_t)r * C_produce + col;
+            // accumulator register v of lane (n, h) is voxel 8 * (v / 4) + 4 * h + v % 4 of the block, channels 2n and
+            // 2n + 1 of the slice (one per n-tile): the 32 lanes of a half-wave store one whole 64-channel row slice
+            const int64_t col = (int64_t)slice * kCoutSlice + 2 * n;
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
+            for (int q = 0; q < 4; ++q) {
+                const i32x4 r4 = *reinterpret_cast<const i32x4*>(tab + rank * kGroup + 8 * q + 4 * h);
 #pragma unroll
-                    for (int v4 = 0; v4 < 4; ++v4)
-                        *reinterpret_cast<f32x4*>(dst + 16 * mt + 4 * v4) =
-                            f32x4{acc[mt][4 * v4], acc[mt][4 * v4 + 1], acc[mt][4 * v4 + 2], acc[mt][4 * v4 + 3]};
-            } else {
-                uint16_t* dst = reinterpret_cast<uint16_t*>(gin) + (int64_t)r * C_produce + col;
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int v8 = 0; v8 < 2; ++v8) {
-                        u32x4 pk;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) pk[e] = Elem<T>::pack2(acc[mt][8 * v8 + 2 * e], acc[mt][8 * v8 + 2 * e + 1]);
-                        *reinterpret_cast<u32x4*>(dst + 16 * mt + 8 * v8) = pk;
-                    }
+                for (int j = 0; j < 4; ++j) {
+                    const int32_t r = r4[j];
+                    if (r < 0) continue;
+                    if (OUT_F32)
+                        *reinterpret_cast<f32x2*>(reinterpret_cast<float*>(gin) + (int64_t)r * C_produce + col) =
+                            f32x2{acc[0][4 * q + j], acc[1][4 * q + j]};
+                    else
+                        *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(gin) + (int64_t)r * C_produce + col) =
+                            Elem<T>::pack2(acc[0][4 * q + j], acc[1][4 * q + j]);
+                }
             }
         }
         __builtin_amdgcn_wave_barrier();     // the row table is rewritten for the next block
+        if (more) finish_table(tg + tg_stride, h1, idv);
+        h0 = h1; h1 = h2; p0 = p1; p1 = p2;
+#pragma unroll
+        for (int c = 0; c < kDgradMaxChunks; ++c) { bc[c][0] = bn[c][0]; bc[c][1] = bn[c][1]; }
     }
 }
 
@@ -698,28 +757,32 @@ fx_status strided_pair_product(const fx_kmap* km, const void* d_src, fx_dtype dt
         const size_t wbytes = packed_weight_bytes(km->K3, C_contract, C_produce, 2);
         FX_TRY(dev_alloc(&wp, wbytes + 8 * sizeof(int32_t), st));
         int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wp) + wbytes);
-        launch_pack_weights(d_w, wp, km->K3, C_contract, C_produce, 2, counters, mode, kPackRows, st);
-        hipError_t e = hipGetLastError();
         const int nslice = C_produce / kCoutSlice, nchunk = C_contract / kCinChunk;
         const size_t lds = (size_t)km->K3 * nchunk * 4096 + (size_t)kDgradLdsWaves * km->K3 * kGroup * sizeof(int32_t);
-        const bool lds_weights = lds <= 160 * 1024 && nchunk <= kDgradMaxChunks && option(kOptGatherLds) != 0;
+        const bool lds_weights = lds <= 160 * 1024 && nchunk <= kDgradMaxChunks && km->K3 <= 27 && option(kOptGatherLds) != 0;
+        // the kernel with the weights in LDS takes them as the B operand (interleaved channels), the other as A
+        launch_pack_weights(d_w, wp, km->K3, C_contract, C_produce, 2, counters, mode, lds_weights ? kPackInterleaved : kPackRows, st);
+        hipError_t e = hipGetLastError();
         if (e == hipSuccess && lds_weights) {
             const int64_t n_blocks_total = km->n_tiles * (int64_t)kGroupsPerTile;
             int64_t grid = std::max(nslice, compute_units() / nslice * nslice);
             grid = std::min<int64_t>(grid, (n_blocks_total + kDgradLdsWaves - 1) / kDgradLdsWaves * nslice);
             ProfScope ps(kProfDgradStrided, st);
-#define FX_DGRAD(T, F32)                                                                                              \
+#define FX_DGRAD_R(T, F32, R)                                                                                         \
     do {                                                                                                              \
-        e = hipFuncSetAttribute((const void*)k_dgrad_strided_ldsw<T, F32>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                (int)lds);                                                                            \
+        e = hipFuncSetAttribute((const void*)k_dgrad_strided_ldsw<T, F32, kDgradLdsWaves, R>,                         \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                                \
         if (e == hipSuccess)                                                                                          \
-            k_dgrad_strided_ldsw<T, F32><<<(unsigned)grid, 64 * kDgradLdsWaves, lds, st>>>(                            \
+            k_dgrad_strided_ldsw<T, F32, kDgradLdsWaves, R><<<(unsigned)grid, 64 * kDgradLdsWaves, lds, st>>>(         \
                 km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows, km->row_stride, km->d_tile_blocks, km->block_stride, \
                 n_blocks_total, km->K3, (const uint16_t*)d_src, (const uint16_t*)wp, C_contract, C_produce, d_dst);    \
     } while (0)
+#define FX_DGRAD(T, F32)                                                                                              \
+    do { if (km->K3 <= 8) FX_DGRAD_R(T, F32, 4); else FX_DGRAD_R(T, F32, 14); } while (0)
             if (dt == FX_BF16) { if (out_f32) FX_DGRAD(__bf16, true); else FX_DGRAD(__bf16, false); }
             else { if (out_f32) FX_DGRAD(_Float16, true); else FX_DGRAD(_Float16, false); }
 #undef FX_DGRAD
+#undef FX_DGRAD_R
             if (e == hipSuccess) e = hipGetLastError();
         } else if (e == hipSuccess) {
             const int64_t n_items = km->n_tiles * (int64_t)kGroupsPerTile * (C_produce / kCoutSlice);

@@ -11,7 +11,9 @@
 
 namespace fx {
 
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -44,7 +46,6 @@ template <> struct Elem<__bf16> {
     }
     static __device__ __forceinline__ uint32_t pack2(float a, float b) {  // two RNE conversions, a in the low half
         typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-        typedef __attribute__((ext_vector_type(2))) float f32x2;
         const bf16x2 h = __builtin_convertvector(f32x2{a, b}, bf16x2);
         uint32_t bits;
         __builtin_memcpy(&bits, &h, 4);
