@@ -809,20 +809,29 @@ k_conv_gather(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restric
 // is bound by the load path of the compute unit (one wave-wide 16-byte load occupies it for at
 // least 16 cycles).  When the packed weights of one 64-channel output slice fit in LDS next to
 // the row tables (K^3 * C_in * 128 bytes; 64 KB for a 2x2x2 kernel with 64 input channels), a
-// persistent workgroup copies them there once, and each wave then walks column blocks exactly as
-// k_conv_gather does, with its A fragments read from LDS: two vector loads per four multiplies.
-// What bounds the kernel then is the gather itself (rows in flight per compute unit), so when the
-// weights of two adjacent slices fit together (NS = 2) a gathered fragment feeds the multiplies of
-// both and the gather is issued once per 128 output channels; that form runs twelve waves with a
-// third more registers (64 more accumulators), and with CP = 2 a step covers two 32-channel chunks,
-// so its four loads use the whole 128-byte line of a 64-channel row while it is in L1 instead of
-// coming back for the second half a step later.  Workgroup b serves slice set b % (nslice / NS).
-// NS = output slices per workgroup, CP = 32-channel chunks per step, W = waves per workgroup,
-// D = fragment sets in flight.
+// persistent workgroup copies them there once, and each wave then walks column blocks with its
+// weight fragments read from LDS: two vector loads per four multiplies.
+// * When the weights of two adjacent slices fit together (NS = 2) a gathered fragment feeds the
+//   multiplies of both and the gather is issued once per 128 output channels; that form runs twelve
+//   waves with a third more registers (64 more accumulators).  With CP = 2 a step covers two
+//   32-channel chunks, so its four loads use the whole 128-byte line of a 64-channel row while it
+//   is in L1 instead of coming back for the second half a step later.
+// * Operand roles: A = gathered rows (32 voxels x 16 input channels), B = packed weights in the
+//   interleaved layout (column n of n-tile t = output channel 2n + t), so the output rows lie along
+//   the accumulator registers and the channels across the lanes: a half-wave stores one output row's
+//   64-channel slice as one contiguous piece.
+// * What a block needs before its first gather hangs on a chain of dependent loads (tile header ->
+//   id block -> row list), and so does its write-back (output permutation).  The chain is cut into
+//   stages that run ahead: the header and permutation entry of block i + 2 are requested while block
+//   i multiplies, the ids of block i + 1 before block i's step loop, and they are turned into the
+//   row table after it.
+// Workgroup b serves slice set b % (nslice / NS).  NS = output slices per workgroup, CP = 32-channel
+// chunks per step, W = waves per workgroup, D = fragment sets in flight, R = offset ranks a lane half
+// resolves (ceil(K^3 / 2)).
 constexpr int kGatherLdsWaves = 16;
 constexpr int kGatherPairWaves = 12;
 
-template <typename T, bool OUT_F32, int NS, int CP, int W, int D>
+template <typename T, bool OUT_F32, int NS, int CP, int W, int D, int R>
 __global__ void __launch_bounds__(64 * W, 1)
 k_conv_gather_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
                    const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
@@ -830,77 +839,110 @@ k_conv_gather_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __re
                    const uint16_t* __restrict__ wp, int C_in, int C_out, void* __restrict__ out) {
     typedef typename Elem<T>::vec8 vec8;
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = uni((int)(threadIdx.x >> 6));
     const int nchunk = C_in / kCinChunk, nslice = C_out / kCoutSlice, nset = nslice / NS;
     const int npair = nchunk / CP;                                       // steps per offset (the launch checks CP | nchunk)
     const int slice = (blockIdx.x % nset) * NS;                          // first slice of this workgroup's set
     const int wg = blockIdx.x / nset, n_wg = gridDim.x / nset;           // the launch makes gridDim a multiple of nset
     unsigned char* wlds = lds_raw;                                       // [kappa][chunk][slice of the set][4 fragments][64 lanes][16 bytes]
     const int w_bytes = K3 * nchunk * NS * 4096;
-    int32_t* row_of = reinterpret_cast<int32_t*>(lds_raw + w_bytes) + wave * 2 * K3 * kGroup;   // two tables [rank][voxel]
+    // per wave: [rank][voxel] global input rows of the current block, then [voxel] its output rows within the tile (-1: none)
+    int32_t* tab = reinterpret_cast<int32_t*>(lds_raw + w_bytes) + wave * (K3 + 1) * kGroup;
+    int32_t* out_of = tab + K3 * kGroup;
 
     for (int sl = wave; sl * 1024 < w_bytes; sl += W) {                  // 1 KB = one fragment of all lanes
         const int kc = sl / (4 * NS), sn = (sl >> 2) % NS, f = sl & 3;   // (kappa * nchunk + chunk), slice of the set, fragment
         const unsigned char* src = reinterpret_cast<const unsigned char*>(wp) + ((size_t)(kc * nslice + slice + sn) * 4 + f) * 1024 + lane * 16;
         __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(wlds + sl * 1024), 16, 0, 0);
     }
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
 
     const int n = lane & 31, h = lane >> 5;
     vec8 zero;
 #pragma unroll
     for (int e = 0; e < 8; ++e) zero[e] = 0;
-    // (offset rank, voxel) -> global input row of column block tg, into table `tab`; lane (n, h)
-    // resolves every second offset.  Returns the block's offset mask.
-    auto resolve = [&](int64_t tg, int32_t* tab) -> uint32_t {
-        const int g = (int)(tg % kGroupsPerTile);
-        const int64_t tile = tg / kGroupsPerTile;
-        const TileHeader* H = tile_hdr + tile;
-        const int w = tile_wave_of(g), gi = tile_slot_of(g);
-        const uint32_t gm = (uint32_t)uni((int)H->group_mask[g]);
-        const uint32_t wm = (uint32_t)uni((int)H->wave_mask[w]);
-        const int flags = uni(H->flags), win_lo = uni(H->win_lo), win_n = uni(H->win_n);
-        const size_t blk0 = (size_t)tile * block_stride + (uint32_t)uni((int)H->wave_block0[w]);
-        const int32_t* rows = tile_rows + tile * (int64_t)row_stride;
-        int rank = 0;
-#pragma unroll 1
-        for (uint32_t m = gm; m; m &= m - 1, ++rank) {
-            if ((rank & 1) != h) continue;
-            const int kappa = __ffs(m) - 1;
-            const size_t blk = blk0 + __popc(wm & ((1u << kappa) - 1u));
-            uint32_t id = tile_blocks[blk * kIdBlockElems + n * kGroupsPerWave + gi];
-            if (flags & kTileLdsOffsets) id = (id / kRowBytes == (uint32_t)kRowCap) ? kNoRow : id / kRowBytes;
-            int32_t r = -1;
-            if (id != kNoRow) r = id < (uint32_t)win_n ? win_lo + (int32_t)id : rows[id - (uint32_t)win_n];
-            tab[rank * kGroup + n] = r;
-        }
-        return gm;
-    };
-    // Two row tables per wave: the next block's table is resolved (two dependent global loads) while
-    // the current block multiplies.
     const int64_t tg_stride = (int64_t)n_wg * W;
-    int64_t tg = (int64_t)wg * W + wave;
-    int cur = 0;
-    uint32_t gm_next = tg < n_blocks_total ? resolve(tg, row_of) : 0u;
-#pragma unroll 1
-    for (; tg < n_blocks_total; tg += tg_stride, cur ^= 1) {
+    const int64_t tg0 = (int64_t)wg * W + wave;
+
+    struct Hdr { uint32_t gm, wm, blk0; int flags, win_lo, win_n, n_out; };
+    // the header fields of block tg (uniform addresses: scalar loads)
+    auto load_hdr = [&](int64_t tg) -> Hdr {
+        Hdr d = {0u, 0u, 0u, 0, 0, 0, 0};
+        if (tg < n_blocks_total) {
+            const int g = (int)(tg % kGroupsPerTile);
+            const TileHeader* H = tile_hdr + tg / kGroupsPerTile;
+            const int w = tile_wave_of(g);
+            d.gm = H->group_mask[g]; d.wm = H->wave_mask[w]; d.blk0 = H->wave_block0[w];
+            d.flags = H->flags; d.win_lo = H->win_lo; d.win_n = H->win_n; d.n_out = H->n_out;
+        }
+        return d;
+    };
+    auto load_perm = [&](int64_t tg) -> int {
+        return tg < n_blocks_total ? (int)tile_perm[tg / kGroupsPerTile * kTileT + (tg % kGroupsPerTile) * kGroup + n] : 0;
+    };
+    // requests the local row ids of block tg: lane (n, h) takes the offset ranks of parity h, slot j = rank / 2
+    auto issue_ids = [&](int64_t tg, const Hdr& d, uint32_t (&idv)[R]) {
         const int g = (int)(tg % kGroupsPerTile);
-        const int64_t tile = tg / kGroupsPerTile;
-        const int n_valid = uni(tile_hdr[tile].n_out);
-        const uint32_t gm = gm_next;
-        const int32_t* tab = row_of + cur * K3 * kGroup;
+        const int gi = tile_slot_of(g);
+        const size_t blk0 = (size_t)(tg / kGroupsPerTile) * block_stride + d.blk0;
+        uint32_t m = d.gm;
+#pragma unroll
+        for (int j = 0; j < 2 * R; ++j) {
+            if (m) {
+                const int kappa = __ffs(m) - 1;
+                m &= m - 1;
+                if ((j & 1) == h)
+                    idv[j >> 1] = tile_blocks[(blk0 + __popc(d.wm & ((1u << kappa) - 1u))) * kIdBlockElems + n * kGroupsPerWave + gi];
+            }
+        }
+    };
+    // ids -> global input rows (a second load for ids outside the tile's window) and the voxels' output rows, into the
+    // wave's table
+    auto finish_table = [&](int64_t tg, const Hdr& d, const uint32_t (&idv)[R], int local) {
+        const int32_t* rows = tile_rows + tg / kGroupsPerTile * (int64_t)row_stride;
+        const int n_k = __popc(d.gm);
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const int rank = 2 * j + h;
+            if (rank < n_k) {
+                uint32_t id = idv[j];
+                if (d.flags & kTileLdsOffsets) id = (id / kRowBytes == (uint32_t)kRowCap) ? kNoRow : id / kRowBytes;
+                int32_t r = -1;
+                if (id != kNoRow) r = id < (uint32_t)d.win_n ? d.win_lo + (int32_t)id : rows[id - (uint32_t)d.win_n];
+                tab[rank * kGroup + n] = r;
+            }
+        }
+        if (h == 0) out_of[n] = local < d.n_out ? local : -1;
+    };
+
+    Hdr h0 = load_hdr(tg0), h1 = load_hdr(tg0 + tg_stride);
+    int p0 = load_perm(tg0), p1 = load_perm(tg0 + tg_stride);
+    uint32_t idv[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) idv[j] = kNoRow;
+    if (tg0 < n_blocks_total) {
+        issue_ids(tg0, h0, idv);
+        finish_table(tg0, h0, idv, p0);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();                       // the weights are in LDS
+
+#pragma unroll 1
+    for (int64_t tg = tg0; tg < n_blocks_total; tg += tg_stride) {
+        const Hdr h2 = load_hdr(tg + 2 * tg_stride);
+        const int p2 = load_perm(tg + 2 * tg_stride);
+        const bool more = tg + tg_stride < n_blocks_total;
+        if (more) issue_ids(tg + tg_stride, h1, idv);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // a wave's LDS accesses are processed in order
         __builtin_amdgcn_wave_barrier();
-        if (tg + tg_stride < n_blocks_total) gm_next = resolve(tg + tg_stride, row_of + (cur ^ 1) * K3 * kGroup);
 
+        const uint32_t gm = h0.gm;
         f32x16 acc[2 * NS];
 #pragma unroll
-        for (int mt = 0; mt < 2 * NS; ++mt)
+        for (int t = 0; t < 2 * NS; ++t)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
+            for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
         const int n_steps = __popc(gm) * npair;         // step = (offset rank, CP chunks), chunks fastest
-        // B fragments of step `step` into b; returns where the step's A fragments start in LDS
+        // A fragments of step `step` into b; returns where the step's B fragments start in LDS
         // fetches come in step order: (offset rank, chunk pair) advance with them
         int f_rank = -1, f_c = npair - 1;
         auto fetch = [&](vec8 (&b)[2 * CP], int step, uint32_t& rest, int& kappa) {
@@ -927,12 +969,10 @@ k_conv_gather_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __re
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                        for (int mt = 0; mt < 2; ++mt)
-                            acc[2 * sn + mt] = Elem<T>::mfma(wf[mt * 2 + ks], b[2 * c + ks], acc[2 * sn + mt]);
+                        for (int nt = 0; nt < 2; ++nt)
+                            acc[2 * sn + nt] = Elem<T>::mfma(b[2 * c + ks], wf[nt * 2 + ks], acc[2 * sn + nt]);
                 }
         };
-        // the gather of the next step is in flight while one multiplies (two fragment sets; a deeper
-        // ring at three waves per SIMD measured slower: 85 us against 79 at config 4)
         // D fragment sets: the gathers of the next D - 1 steps are in flight while one multiplies.  The loop has one
         // exit and guards instead of breaks: with early exits between the multiplies the compiler kept a second
         // copy of the accumulators (80 registers more).
@@ -952,36 +992,30 @@ k_conv_gather_ldsw(const TileHeader* __restrict__ tile_hdr, const uint16_t* __re
             }
         }
 
-        const int local = tile_perm[tile * kTileT + g * kGroup + n];
-        if (local < n_valid) {
-            const int64_t o = tile * kTileT + local;
+        // accumulator register v of lane (n, h) is voxel 8 * (v / 4) + 4 * h + v % 4 of the block, channels 2n and
+        // 2n + 1 of a slice (one per n-tile): the 32 lanes of a half-wave store one whole 64-channel row slice
+        const int64_t row0 = tg / kGroupsPerTile * kTileT;
 #pragma unroll
-            for (int sn = 0; sn < NS; ++sn) {
-                const int64_t col = (int64_t)(slice + sn) * kCoutSlice + 32 * h;
-                if (OUT_F32) {
-                    float* dst = reinterpret_cast<float*>(out) + o * C_out + col;
+        for (int q = 0; q < 4; ++q) {
+            const i32x4 o4 = *reinterpret_cast<const i32x4*>(out_of + 8 * q + 4 * h);
 #pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
+            for (int j = 0; j < 4; ++j) {
+                if (o4[j] < 0) continue;
+                const int64_t at = (row0 + o4[j]) * C_out + (int64_t)slice * kCoutSlice + 2 * n;
 #pragma unroll
-                        for (int v4 = 0; v4 < 4; ++v4)
-                            *reinterpret_cast<f32x4*>(dst + 16 * mt + 4 * v4) =
-                                f32x4{acc[2 * sn + mt][4 * v4], acc[2 * sn + mt][4 * v4 + 1], acc[2 * sn + mt][4 * v4 + 2],
-                                      acc[2 * sn + mt][4 * v4 + 3]};
-                } else {
-                    uint16_t* dst = reinterpret_cast<uint16_t*>(out) + o * C_out + col;
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                        for (int v8 = 0; v8 < 2; ++v8) {
-                            u32x4 pk;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                pk[e] = Elem<T>::pack2(acc[2 * sn + mt][8 * v8 + 2 * e], acc[2 * sn + mt][8 * v8 + 2 * e + 1]);
-                            *reinterpret_cast<u32x4*>(dst + 16 * mt + 8 * v8) = pk;
-                        }
+                for (int sn = 0; sn < NS; ++sn) {
+                    if (OUT_F32)
+                        *reinterpret_cast<f32x2*>(reinterpret_cast<float*>(out) + at + sn * kCoutSlice) =
+                            f32x2{acc[2 * sn][4 * q + j], acc[2 * sn + 1][4 * q + j]};
+                    else
+                        *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(out) + at + sn * kCoutSlice) =
+                            Elem<T>::pack2(acc[2 * sn][4 * q + j], acc[2 * sn + 1][4 * q + j]);
                 }
             }
         }
+        __builtin_amdgcn_wave_barrier();     // the table is rewritten for the next block
+        if (more) finish_table(tg + tg_stride, h1, idv, p1);
+        h0 = h1; h1 = h2; p0 = p1; p1 = p2;
     }
 }
 
@@ -1088,37 +1122,55 @@ static hipError_t launch_mfma(const fx_kmap* km, const void* feat, const void* w
     return hipGetLastError();
 }
 
+// How the gather kernel with its weights in LDS would serve a map and shape: ns = 0 if it cannot (the weights of
+// one 64-channel output slice and the waves' tables exceed 160 KB, or option gather_lds = 0), else the slices per
+// workgroup (two when their weights fit together and option gather_lds is not 1), chunks per step, waves and the
+// dynamic LDS bytes.  Maps with more than eight offsets take twelve waves (their tables are larger).
+struct GatherLdsPlan { int ns, cp, waves; size_t lds; };
+static GatherLdsPlan gather_lds_plan(const fx_kmap* km, int C_in, int C_out) {
+    const int nslice = C_out / kCoutSlice, nchunk = C_in / kCinChunk;
+    const size_t w_slice = (size_t)km->K3 * nchunk * 4096;                   // packed weights of one output slice
+    auto tables = [&](int waves) { return (size_t)waves * (km->K3 + 1) * kGroup * sizeof(int32_t); };
+    GatherLdsPlan p = {0, 1, 0, 0};
+    if (option(kOptGatherLds) == 0 || km->K3 > 27) return p;
+    if (km->K3 <= 8 && nslice % 2 == 0 && 2 * w_slice + tables(kGatherPairWaves) <= 160 * 1024 && option(kOptGatherLds) != 1) {
+        p.ns = 2; p.cp = nchunk % 2 == 0 ? 2 : 1; p.waves = kGatherPairWaves;
+    } else if (km->K3 <= 8 && w_slice + tables(kGatherLdsWaves) <= 160 * 1024) {
+        p.ns = 1; p.waves = kGatherLdsWaves;
+    } else if (km->K3 > 8 && w_slice + tables(kGatherPairWaves) <= 160 * 1024) {
+        p.ns = 1; p.waves = kGatherPairWaves;
+    }
+    p.lds = p.ns * w_slice + tables(p.waves);
+    return p;
+}
+
 template <typename T, bool OUT_F32>
 static hipError_t launch_gather(const fx_kmap* km, const void* feat, const void* wp, int C_in, int C_out, void* out,
                                 hipStream_t st) {
-    const int nslice = C_out / kCoutSlice, nchunk = C_in / kCinChunk;
-    const size_t w_slice = (size_t)km->K3 * nchunk * 4096;                   // packed weights of one output slice
-    auto tables = [&](int waves) { return (size_t)waves * 2 * km->K3 * kGroup * sizeof(int32_t); };
-    if (w_slice + tables(kGatherLdsWaves) <= 160 * 1024 && option(kOptGatherLds) != 0) {   // option gather_lds = 0: never keep the weights in LDS
-        // two slices per workgroup, at twelve waves with a third more registers each, when their weights fit
-        // together (option gather_lds = 1: always one slice)
-        const int ns = (nslice % 2 == 0 && 2 * w_slice + tables(kGatherPairWaves) <= 160 * 1024 && option(kOptGatherLds) != 1) ? 2 : 1;
-        const int cp = (ns == 2 && nchunk % 2 == 0) ? 2 : 1;
-        const int waves = ns == 2 ? kGatherPairWaves : kGatherLdsWaves;
-        const size_t lds = ns * w_slice + tables(waves);
+    const GatherLdsPlan plan = gather_lds_plan(km, C_in, C_out);
+    if (plan.ns) {
+        const int ns = plan.ns, cp = plan.cp, waves = plan.waves;
+        const int nslice = C_out / kCoutSlice;
+        const bool few = km->K3 <= 8;            // ranks per lane half: 4, else 14
         const int64_t n_blocks_total = km->n_tiles * (int64_t)kGroupsPerTile;
         // one workgroup per compute unit, a multiple of the number of slice sets, no more than there is work for
         const int nset = nslice / ns;
         int64_t grid = std::max(nset, compute_units() / nset * nset);
         grid = std::min<int64_t>(grid, (n_blocks_total + waves - 1) / waves * nset);
-#define FX_GATHER_LDSW(NS_, CP_, W_, D_)                                                                                 \
-        if (ns == NS_ && cp == CP_) {                                                                                    \
-            hipError_t e = hipFuncSetAttribute((const void*)k_conv_gather_ldsw<T, OUT_F32, NS_, CP_, W_, D_>,            \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                   \
+#define FX_GATHER_LDSW(NS_, CP_, W_, D_, R_)                                                                             \
+        if (ns == NS_ && cp == CP_ && waves == W_ && few == (R_ == 4)) {                                                 \
+            hipError_t e = hipFuncSetAttribute((const void*)k_conv_gather_ldsw<T, OUT_F32, NS_, CP_, W_, D_, R_>,        \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)plan.lds);              \
             if (e != hipSuccess) return e;                                                                               \
-            k_conv_gather_ldsw<T, OUT_F32, NS_, CP_, W_, D_><<<(unsigned)grid, 64 * W_, lds, st>>>(                      \
+            k_conv_gather_ldsw<T, OUT_F32, NS_, CP_, W_, D_, R_><<<(unsigned)grid, 64 * W_, plan.lds, st>>>(             \
                 km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows, km->row_stride, km->d_tile_blocks, km->block_stride,   \
                 n_blocks_total, km->K3, (const uint16_t*)feat, (const uint16_t*)wp, C_in, C_out, out);                   \
             return hipGetLastError();                                                                                    \
         }
-        // measured at config 4 (64 -> 128): 58 us for (2, 2, 12 waves, 3 sets), 58-59 for 8 waves with 2 to 4 sets,
-        // 63-64 for one chunk per step, 79-81 for one slice per workgroup
-        FX_GATHER_LDSW(1, 1, kGatherLdsWaves, 4) FX_GATHER_LDSW(2, 1, kGatherPairWaves, 4) FX_GATHER_LDSW(2, 2, kGatherPairWaves, 3)
+        // measured at config 4 (64 -> 128) before the staged look-ahead: 58 us for (2, 2, 12 waves, 3 sets), 58-59
+        // for 8 waves with 2 to 4 sets, 63-64 for one chunk per step, 79-81 for one slice per workgroup
+        FX_GATHER_LDSW(1, 1, kGatherLdsWaves, 4, 4) FX_GATHER_LDSW(1, 1, kGatherPairWaves, 2, 14)
+        FX_GATHER_LDSW(2, 1, kGatherPairWaves, 4, 4) FX_GATHER_LDSW(2, 2, kGatherPairWaves, 3, 4)
 #undef FX_GATHER_LDSW
         return hipErrorInvalidValue;
     }
@@ -1159,7 +1211,9 @@ static fx_status conv_tiles_with_scratch(const fx_kmap* km, const void* d_feat, 
     // others: the LDS-staged kernel
     const int fg = option(kOptConvGather);          // 0 / 1: the LDS-staged / the gather kernel on every map
     const bool gather = (fg >= 0 ? fg == 1 : !map_shares_rows(km)) && in_dt != FX_F32 && C_out % kCoutSlice == 0;
-    launch_pack_weights(d_w, wp, km->K3, C_in, C_out, esize, counters, mode, gather ? kPackRows : kPackInterleaved, st);
+    // the gather kernel that fetches its weights per step takes them as the A operand, all other kernels as B
+    const bool rows_layout = gather && gather_lds_plan(km, C_in, C_out).ns == 0;
+    launch_pack_weights(d_w, wp, km->K3, C_in, C_out, esize, counters, mode, rows_layout ? kPackRows : kPackInterleaved, st);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && gather) {
         ProfScope ps(kProfConvGather, st);
