@@ -563,6 +563,7 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
                 const int b = block0[fw] + __popc(wm & ((1u << kappa) - 1u));
                 const unsigned char* blk = L.blocks + (size_t)b * kGroup * 8;
                 u32x2 ids = u32x2{0, 0}, idv[2][2];
+                vec8 ga[2][2];
                 if (general) {
                     ids = *reinterpret_cast<const u32x2*>(blk + n * 8);
                 } else {
@@ -573,6 +574,25 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
                 }
 #pragma unroll
                 for (int gi = 0; gi < kGroupsPerWave; ++gi) {
+                    // general tiles: the rows of voxel lane % 32 in two groups are requested before the first of their
+                    // products, so that the two latencies overlap (all four at once do not fit the registers)
+                    if (general && (gi & 1) == 0) {
+#pragma unroll
+                        for (int gj = gi; gj < gi + 2; ++gj) {
+                            if (!((gmask[tile_group_of(fw, gj)] >> kappa) & 1u)) continue;
+                            const uint32_t id = (ids[gj >> 1] >> (16 * (gj & 1))) & 0xFFFFu;
+                            const bool staged = id < (uint32_t)n_staged;
+                            const int row = staged ? (int)id : kRowCap;
+                            ga[gj & 1][0] = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, h));
+                            ga[gj & 1][1] = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, h + 2));
+                            if (!staged && id != kNoRow) {
+                                const int64_t gr = id < (uint32_t)win_n ? (int64_t)win_lo + id : (int64_t)my_rows[id - win_n];
+                                const uint16_t* src = feat + gr * C_in + cib * kWgCi + h * 8;
+                                ga[gj & 1][0] = *reinterpret_cast<const vec8*>(src);
+                                ga[gj & 1][1] = *reinterpret_cast<const vec8*>(src + 16);
+                            }
+                        }
+                    }
                     const int g = tile_group_of(fw, gi);
                     if (!((gmask[g] >> kappa) & 1u)) continue;
                     vec8 fT[2];
@@ -588,22 +608,11 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
                             fT[ks] = vec8_from_words<T>(u32x4{w[0][0], w[0][1], w[1][0], w[1][1]});
                         }
                     } else {
-                        const uint32_t id = (ids[gi >> 1] >> (16 * (gi & 1))) & 0xFFFFu;
-                        const bool staged = id < (uint32_t)n_staged;
-                        const int row = staged ? (int)id : kRowCap;
-                        vec8 a0 = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, h));
-                        vec8 a1 = *reinterpret_cast<const vec8*>(L.rows + lds_row_offset(row, h + 2));
-                        if (!staged && id != kNoRow) {
-                            const int64_t gr = id < (uint32_t)win_n ? (int64_t)win_lo + id : (int64_t)my_rows[id - win_n];
-                            const uint16_t* src = feat + gr * C_in + cib * kWgCi + h * 8;
-                            a0 = *reinterpret_cast<const vec8*>(src);
-                            a1 = *reinterpret_cast<const vec8*>(src + 16);
-                        }
                         f32x16 t;
 #pragma unroll
                         for (int v = 0; v < 16; ++v) t[v] = 0.f;
-                        t = Elem<T>::mfma(a0, ident[0], t);
-                        t = Elem<T>::mfma(a1, ident[1], t);
+                        t = Elem<T>::mfma(ga[gi & 1][0], ident[0], t);
+                        t = Elem<T>::mfma(ga[gi & 1][1], ident[1], t);
                         fT[0] = pack8<T>(t, 0);
                         fT[1] = pack8<T>(t, 8);
                     }
