@@ -13,8 +13,7 @@
 // channels with the channels across lanes; the two weight tiles of a 64-channel slice interleave
 // the channels (column n of tile t = channel 2n + t), so lane n holds two adjacent channels of
 // every voxel and the 32 lanes of a half-wave store one whole output row at a time.  The gather
-// kernel for strided maps keeps the roles the other way round (weights as A, 32 consecutive
-// channels of one voxel per lane).
+// kernels for strided maps keep the same roles with their A fragments read straight from global memory.
 #include "conv_common.h"
 #include "dev_timing.h"
 
@@ -23,20 +22,15 @@
 namespace fx {
 
 // ---------------------------------------------------------------------------------- weight packing
-// Wp[kappa][cin chunk][cout slice][mtile 0..1][kstep 0..1][lane 0..63][8]: the 16-byte A-operand
-// fragment of each lane for one (offset, 32 input channels, 64 output channels).  A-row m of
-// m-tile t holds output channel 32*((m>>2)&1) + 16*t + 4*(m>>3) + (m&3) of the slice: with the
-// 32x32 accumulator layout (lane half h, register v -> row 8*(v/4) + 4*h + v%4) a lane's
-// accumulators are then the 32 consecutive channels 32*h .. 32*h+31 (m-tile t = channels
-// 32*h + 16*t + v).
-//
-// Layout kPackInterleaved serves kernels that take the features as the A operand and the weights
-// as B: column n of n-tile t is output channel 2n + t of the slice, so that lane n of an
-// accumulator row holds two adjacent channels (one per n-tile) and the 32 lanes of a half-wave
-// store one whole output row.
+// Wp[kappa][cin chunk][cout slice][ntile 0..1][kstep 0..1][lane 0..63][8]: the 16-byte B-operand
+// fragment of each lane for one (offset, 32 input channels, 64 output channels): lane (n, kq) holds
+// the eight input channels 16 * kstep + 8 * kq .. + 7 of column n.  Column n of n-tile t is output
+// channel 2n + t of the slice, so that lane n of an accumulator row (32x32 accumulator layout: lane
+// half h, register v -> voxel row 8*(v/4) + 4*h + v%4) holds two adjacent channels, one per n-tile,
+// and the 32 lanes of a half-wave store one whole output row.
 template <typename E>   // uint16_t or uint32_t: the bits of one element
 __global__ void k_pack_weights(const E* __restrict__ w, E* __restrict__ wp, int K3, int C_in, int C_out,
-                               int32_t* __restrict__ counters, int mode, int layout) {
+                               int32_t* __restrict__ counters, int mode) {
     if (blockIdx.x == 0 && threadIdx.x < 8) counters[threadIdx.x] = 0;   // the convolution's work-list counters
     constexpr int EPL = 16 / (int)sizeof(E);     // elements per lane fragment
     constexpr int kChunk = 4 * EPL;              // input channels per 64-byte row chunk
@@ -47,14 +41,13 @@ __global__ void k_pack_weights(const E* __restrict__ w, E* __restrict__ wp, int 
         const int el = (int)(r % EPL); r /= EPL;
         const int lane = (int)(r & 63); r >>= 6;
         const int ks = (int)(r & 1); r >>= 1;
-        const int mt = (int)(r & 1); r >>= 1;
+        const int nt = (int)(r & 1); r >>= 1;
         const int s = (int)(r % nslice); r /= nslice;
         const int c = (int)(r % nchunk); r /= nchunk;
         const int kappa = (int)r;
         const int m = lane & 31, kq = lane >> 5;
         const int cin = c * kChunk + ks * 2 * EPL + kq * EPL + el;
-        const int cout = layout == kPackInterleaved ? s * kCoutSlice + 2 * m + mt
-                                                    : s * kCoutSlice + 32 * ((m >> 2) & 1) + 16 * mt + 4 * (m >> 3) + (m & 3);
+        const int cout = s * kCoutSlice + 2 * m + nt;
         E v = 0;
         if (cout < C_out) {
             const int64_t kw = (mode & kWeightsFlipped) ? K3 - 1 - kappa : kappa;
@@ -70,14 +63,14 @@ size_t packed_weight_bytes(int K3, int C_in, int C_out, int elem_bytes) {
 }
 
 void launch_pack_weights(const void* d_w, void* wp, int K3, int C_in, int C_out, int elem_bytes, int32_t* counters,
-                         int mode, int layout, hipStream_t st) {
+                         int mode, hipStream_t st) {
     const int64_t total = (int64_t)(packed_weight_bytes(K3, C_in, C_out, elem_bytes) / elem_bytes);
     const unsigned nb = (unsigned)std::min<int64_t>((total + 255) / 256, 4096);
     ProfScope ps(kProfPackWeights, st);
     if (elem_bytes == 2)
-        k_pack_weights<uint16_t><<<nb, 256, 0, st>>>((const uint16_t*)d_w, (uint16_t*)wp, K3, C_in, C_out, counters, mode, layout);
+        k_pack_weights<uint16_t><<<nb, 256, 0, st>>>((const uint16_t*)d_w, (uint16_t*)wp, K3, C_in, C_out, counters, mode);
     else
-        k_pack_weights<uint32_t><<<nb, 256, 0, st>>>((const uint32_t*)d_w, (uint32_t*)wp, K3, C_in, C_out, counters, mode, layout);
+        k_pack_weights<uint32_t><<<nb, 256, 0, st>>>((const uint32_t*)d_w, (uint32_t*)wp, K3, C_in, C_out, counters, mode);
 }
 
 // Write-back of one column block computed with the features as the A operand: register v of
@@ -684,9 +677,10 @@ k_conv_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict_
 // For maps whose input rows are used (almost) once -- strided maps, where staging rows in LDS buys no
 // reuse.  One wave owns one column block (32 outputs) x one 64-channel output slice for all
 // offsets: it first resolves the block's (offset, voxel) -> input row table into LDS with independent
-// loads, then walks the offsets, reading each lane's 16-byte B fragments straight from the feature
-// rows (one step ahead) and the packed weights from L2.  No barriers, ~110 registers, so several
-// waves per SIMD hide the gather latency.
+// loads, then walks the offsets, reading each lane's 16-byte A fragments straight from the feature
+// rows (one step ahead) and the packed weights (the B operand, interleaved channels) from L2; a
+// half-wave stores one output row's 64-channel slice in one piece.  No barriers, ~100 registers, so
+// several waves per SIMD hide the gather latency.
 constexpr int kGatherWaves = 4;
 
 template <typename T, bool OUT_F32>
@@ -697,6 +691,7 @@ k_conv_gather(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restric
               int C_in, int C_out, void* __restrict__ out) {
     typedef typename Elem<T>::vec8 vec8;
     __shared__ int32_t row_of[kGatherWaves][kMaxK3Tiled][kGroup];
+    __shared__ __align__(16) int32_t out_of[kGatherWaves][kGroup];      // the block's output rows within the tile (-1: none)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t item = (int64_t)blockIdx.x * kGatherWaves + wave;
     if (item >= n_items) return;
@@ -711,6 +706,10 @@ k_conv_gather(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restric
     const uint32_t wm = (uint32_t)uni((int)H->wave_mask[w]);
     const int n = lane & 31, h = lane >> 5;
     const int n_valid = uni(H->n_out);
+    if (h == 0) {
+        const int local = tile_perm[tile * kTileT + g * kGroup + n];
+        out_of[wave][n] = local < n_valid ? local : -1;
+    }
 
     // (offset, voxel) -> global input row (-1: none); lane (n, h) resolves every second offset
     {
@@ -768,39 +767,30 @@ k_conv_gather(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restric
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wa[mt * 2 + ks], ba[ks], acc[mt]);
+            for (int nt = 0; nt < 2; ++nt) acc[nt] = Elem<T>::mfma(ba[ks], wa[nt * 2 + ks], acc[nt]);
         if (step + 2 < n_steps) fetch(ba, wa, step + 2, rest, kappa);
         if (step + 1 < n_steps) {       // a guard, not an early exit: one loop exit keeps one copy of the accumulators
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wb[mt * 2 + ks], bb[ks], acc[mt]);
+                for (int nt = 0; nt < 2; ++nt) acc[nt] = Elem<T>::mfma(bb[ks], wb[nt * 2 + ks], acc[nt]);
         }
     }
 
-    const int local = tile_perm[tile * kTileT + g * kGroup + n];
-    if (local >= n_valid) return;
-    const int64_t o = tile * kTileT + local;
-    const int64_t col = (int64_t)slice * kCoutSlice + 32 * h;
-    if (OUT_F32) {
-        float* dst = reinterpret_cast<float*>(out) + o * C_out + col;
+    // accumulator register v of lane (n, h) is voxel 8 * (v / 4) + 4 * h + v % 4 of the block, channels 2n and 2n + 1
+    // of the slice (one per n-tile): the 32 lanes of a half-wave store one whole 64-channel row slice
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+    for (int q = 0; q < 4; ++q) {
+        const i32x4 o4 = *reinterpret_cast<const i32x4*>(&out_of[wave][8 * q + 4 * h]);
 #pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4)
-                *reinterpret_cast<f32x4*>(dst + 16 * mt + 4 * v4) =
-                    f32x4{acc[mt][4 * v4], acc[mt][4 * v4 + 1], acc[mt][4 * v4 + 2], acc[mt][4 * v4 + 3]};
-    } else {
-        uint16_t* dst = reinterpret_cast<uint16_t*>(out) + o * C_out + col;
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int v8 = 0; v8 < 2; ++v8) {
-                u32x4 pk;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) pk[e] = Elem<T>::pack2(acc[mt][8 * v8 + 2 * e], acc[mt][8 * v8 + 2 * e + 1]);
-                *reinterpret_cast<u32x4*>(dst + 16 * mt + 8 * v8) = pk;
-            }
+        for (int j = 0; j < 4; ++j) {
+            if (o4[j] < 0) continue;
+            const int64_t at = (tile * kTileT + o4[j]) * C_out + (int64_t)slice * kCoutSlice + 2 * n;
+            if (OUT_F32)
+                *reinterpret_cast<f32x2*>(reinterpret_cast<float*>(out) + at) = f32x2{acc[0][4 * q + j], acc[1][4 * q + j]};
+            else
+                *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(out) + at) = Elem<T>::pack2(acc[0][4 * q + j], acc[1][4 * q + j]);
+        }
     }
 }
 
@@ -1211,9 +1201,7 @@ static fx_status conv_tiles_with_scratch(const fx_kmap* km, const void* d_feat, 
     // others: the LDS-staged kernel
     const int fg = option(kOptConvGather);          // 0 / 1: the LDS-staged / the gather kernel on every map
     const bool gather = (fg >= 0 ? fg == 1 : !map_shares_rows(km)) && in_dt != FX_F32 && C_out % kCoutSlice == 0;
-    // the gather kernel that fetches its weights per step takes them as the A operand, all other kernels as B
-    const bool rows_layout = gather && gather_lds_plan(km, C_in, C_out).ns == 0;
-    launch_pack_weights(d_w, wp, km->K3, C_in, C_out, esize, counters, mode, rows_layout ? kPackRows : kPackInterleaved, st);
+    launch_pack_weights(d_w, wp, km->K3, C_in, C_out, esize, counters, mode, st);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && gather) {
         ProfScope ps(kProfConvGather, st);

@@ -44,11 +44,12 @@ __device__ __forceinline__ int32_t tile_row_of(uint32_t id, int flags, int win_l
 }
 
 // ---------------------------------------------------------------------------------- input gradient, K = stride
-// One wave per (tile, column block of 32 outputs, 64 produced channels).  The B operand of every
+// One wave per (tile, column block of 32 outputs, 64 produced channels).  The A operand of every
 // offset is the same: the gout rows of the block's outputs (re-read per offset, they stay in L1);
-// the A operand is W[kappa]^T in the packed fragment order.  After the chunks of one offset the
-// accumulators hold gin rows of the 32 inputs map(o, kappa): each lane stores its 32 channels to
-// the row of its voxel and the accumulators start again from zero.
+// the B operand is W[kappa]^T in the packed fragment order (interleaved channels).  After the chunks
+// of one offset the accumulators hold gin rows of the 32 inputs map(o, kappa), the rows along the
+// registers and the channels across the lanes: a half-wave stores one row's 64-channel slice in one
+// piece, and the accumulators start again from zero.
 constexpr int kDgradWaves = 4;
 
 template <typename T, bool OUT_F32>
@@ -58,7 +59,7 @@ k_dgrad_strided(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restr
                 int block_stride, int64_t n_items, const uint16_t* __restrict__ gout, const uint16_t* __restrict__ wp,
                 int C_contract, int C_produce, void* __restrict__ gin) {
     typedef typename Elem<T>::vec8 vec8;
-    __shared__ int32_t row_of[kDgradWaves][kMaxK3Tiled][kGroup];
+    __shared__ __align__(16) int32_t row_of[kDgradWaves][kMaxK3Tiled][kGroup];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t item = (int64_t)blockIdx.x * kDgradWaves + wave;
     if (item >= n_items) return;
@@ -118,30 +119,25 @@ k_dgrad_strided(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restr
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt) acc[mt] = Elem<T>::mfma(wf[mt * 2 + ks], b[ks], acc[mt]);
+                for (int nt = 0; nt < 2; ++nt) acc[nt] = Elem<T>::mfma(b[ks], wf[nt * 2 + ks], acc[nt]);
         }
-        const int32_t r = row_of[wave][rank][n];
-        if (r < 0) continue;
-        const int64_t col = (int64_t)slice * kCoutSlice + 32 * h;
-        if (OUT_F32) {
-            float* dst = reinterpret_cast<float*>(gin) + (int64_t)r * C_produce + col;
+        // accumulator register v of lane (n, h) is voxel 8 * (v / 4) + 4 * h + v % 4 of the block, channels 2n and
+        // 2n + 1 of the slice (one per n-tile)
+        const int64_t col = (int64_t)slice * kCoutSlice + 2 * n;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+        for (int q = 0; q < 4; ++q) {
+            const i32x4 r4 = *reinterpret_cast<const i32x4*>(&row_of[wave][rank][8 * q + 4 * h]);
 #pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4)
-                    *reinterpret_cast<f32x4*>(dst + 16 * mt + 4 * v4) =
-                        f32x4{acc[mt][4 * v4], acc[mt][4 * v4 + 1], acc[mt][4 * v4 + 2], acc[mt][4 * v4 + 3]};
-        } else {
-            uint16_t* dst = reinterpret_cast<uint16_t*>(gin) + (int64_t)r * C_produce + col;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int v8 = 0; v8 < 2; ++v8) {
-                    u32x4 pk;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) pk[e] = Elem<T>::pack2(acc[mt][8 * v8 + 2 * e], acc[mt][8 * v8 + 2 * e + 1]);
-                    *reinterpret_cast<u32x4*>(dst + 16 * mt + 8 * v8) = pk;
-                }
+            for (int j = 0; j < 4; ++j) {
+                const int32_t r = r4[j];
+                if (r < 0) continue;
+                if (OUT_F32)
+                    *reinterpret_cast<f32x2*>(reinterpret_cast<float*>(gin) + (int64_t)r * C_produce + col) =
+                        f32x2{acc[0][4 * q + j], acc[1][4 * q + j]};
+                else
+                    *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(gin) + (int64_t)r * C_produce + col) =
+                        Elem<T>::pack2(acc[0][4 * q + j], acc[1][4 * q + j]);
+            }
         }
     }
 }
@@ -769,8 +765,7 @@ fx_status strided_pair_product(const fx_kmap* km, const void* d_src, fx_dtype dt
         const int nslice = C_produce / kCoutSlice, nchunk = C_contract / kCinChunk;
         const size_t lds = (size_t)km->K3 * nchunk * 4096 + (size_t)kDgradLdsWaves * km->K3 * kGroup * sizeof(int32_t);
         const bool lds_weights = lds <= 160 * 1024 && nchunk <= kDgradMaxChunks && km->K3 <= 27 && option(kOptGatherLds) != 0;
-        // the kernel with the weights in LDS takes them as the B operand (interleaved channels), the other as A
-        launch_pack_weights(d_w, wp, km->K3, C_contract, C_produce, 2, counters, mode, lds_weights ? kPackInterleaved : kPackRows, st);
+        launch_pack_weights(d_w, wp, km->K3, C_contract, C_produce, 2, counters, mode, st);
         hipError_t e = hipGetLastError();
         if (e == hipSuccess && lds_weights) {
             const int64_t n_blocks_total = km->n_tiles * (int64_t)kGroupsPerTile;

@@ -122,12 +122,9 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 //   kWeightsMirrored       fragment (kappa, a, b)      = W[K^3-1-kappa][b][a]      (both)
 enum WeightMode { kWeightsForward = 0, kWeightsTransposed = 1, kWeightsFlipped = 2, kWeightsMirrored = 3 };
 
-// Which produced channel a fragment row / column m of tile t holds (within a slice of 64):
-//   kPackRows          32*((m>>2)&1) + 16*t + 4*(m>>3) + (m&3)   weights as the A operand: a lane's accumulators
-//                                                               are 32 consecutive channels of one voxel
-//   kPackInterleaved   2*m + t                                  weights as the B operand: lane m holds two adjacent
-//                                                               channels of the voxel of each accumulator register
-enum PackLayout { kPackRows = 0, kPackInterleaved = 1 };
+// Every matrix-unit kernel takes the weights as the B operand: column m of n-tile t of a 64-channel slice holds
+// produced channel 2*m + t, so lane m holds two adjacent channels of the voxel of each accumulator register and
+// the 32 lanes of a half-wave store one whole row slice.
 
 // Packs the weights (C_in = contracted channels, C_out = produced channels, in the sense of the
 // mode) and zeroes the eight work-list counters behind them.
@@ -135,7 +132,7 @@ enum PackLayout { kPackRows = 0, kPackInterleaved = 1 };
 // and the produced channels are padded with zeros to a multiple of 64.  Returns the bytes packed.
 size_t packed_weight_bytes(int K3, int C_in, int C_out, int elem_bytes);
 void launch_pack_weights(const void* d_w, void* wp, int K3, int C_in, int C_out, int elem_bytes, int32_t* counters,
-                         int mode, int layout, hipStream_t st);
+                         int mode, hipStream_t st);
 
 // The forward multiply-accumulate over a map with the weights read in the given mode: d_out[o,:]
 // = sum over kappa of d_feat[map(o,kappa),:] . Wmode[kappa], C_in channels in, C_out channels out.

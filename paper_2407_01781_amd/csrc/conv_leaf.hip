@@ -1092,8 +1092,7 @@ fx_status fx::leaf_apply(const char* who, const fx_grid* g, const void* d_src, f
             set_error("%s: memset failed", who);
             return FX_EDEVICE;
         }
-        launch_pack_weights(d_w, wpk, 27, C_contract, C_produce, 2, reinterpret_cast<int32_t*>((char*)wpk + wbytes), mode,
-                            kPackInterleaved, st);
+        launch_pack_weights(d_w, wpk, 27, C_contract, C_produce, 2, reinterpret_cast<int32_t*>((char*)wpk + wbytes), mode, st);
         fx_status rc;
         if (dt == FX_BF16)
             rc = out_dt == FX_F32 ? launch_leaf16<__bf16, true>(g, d_src, wpk, d_dst, C_contract, C_produce, (char*)wpk + wbytes, zero_row, leaf_list, n_list, st)

@@ -78,6 +78,15 @@ def test_strided_channel_shapes():
     _check_both(G.workload("lidar_small_down"), c_in=64, c_out=96)
 
 
+def test_strided_input_gradient_with_weights_fetched_per_step(fx_opt):
+    # the kernel that keeps the weights in LDS serves up to 128 contracted channels; the switch and a deeper layer
+    # both lead to the one that fetches them per step
+    _check_both(G.workload("lidar_small_down"), c_in=64, c_out=320)
+    fx_opt("gather_lds", 0)
+    _check_both(G.workload("lidar_small_down"), c_in=64, c_out=128)
+    _check_both(G.workload("lidar_small_down"), c_in=64, c_out=128, out_f32=True)
+
+
 def test_weight_gradient_is_reproducible_bit_for_bit():
     km, d_x, d_gy = _check_both(G.workload("lidar_small"), out_f32=True)
     a = fx.sparse_conv_bwd_weight(km, d_x, d_gy, out_dtype=torch.float32)

@@ -86,6 +86,16 @@ def test_transposed_convolution_on_strided_maps(name, dtype, c_in, c_out):
     H.conv_tolerance_check(y.float().cpu().numpy(), ref, dtype, 8, c_in)
 
 
+def test_transposed_convolution_with_weights_fetched_per_step(fx_opt):
+    km, og, ogc = _pair_map("lidar_small_down")
+    for c_in, c_out, lds in ((320, 64, -1), (128, 64, 0)):          # too deep for LDS / switched off
+        fx_opt("gather_lds", lds)
+        z = _feat(53, ogc.num_voxels, c_in, "bf16")
+        _, wt = G.features_and_weights(54, 1, c_in, c_out, 8, "bf16")
+        y = fx.sparse_conv_transpose_fwd(km, H.to_device_storage(z, "bf16"), H.to_device_storage(wt, "bf16"))
+        H.conv_tolerance_check(y.float().cpu().numpy(), O.conv_transpose(og, ogc, 2, 2, z, wt), "bf16", 8, c_in)
+
+
 @pytest.mark.parametrize("dtype,c_in,c_out", [("bf16", 64, 64), ("f32", 8, 12)])
 def test_transposed_convolution_on_a_submanifold_map(dtype, c_in, c_out):
     w = G.workload("lidar_small")
