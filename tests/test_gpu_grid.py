@@ -56,7 +56,7 @@ def test_large_inputs_take_the_bucket_path_and_agree_with_the_direct_path(fx_opt
 
 
 def test_sparse_large_input_overflows_the_bucket_tables():
-    # one voxel per leaf and about a thousand rows per bucket: some bucket holds more leaves than
+    # one voxel per leaf and about two thousand rows per bucket: every bucket holds more leaves than
     # its LDS table, so the build repeats through the direct path (and with a larger leaf capacity)
     pts = _cloud(41, 500000, -40000, 40000)
     g, og = H.both_grids(pts, np.array([[0, pts.shape[0]]]))
