@@ -181,6 +181,47 @@ def test_identity_tap_is_bit_exact_in_bf16():
         assert np.array_equal(y, expect)
 
 
+@pytest.mark.parametrize("lds_weights", ["-1", "1", "0"])
+def test_identity_taps_on_a_strided_map_are_bit_exact(lds_weights, fx_opt):
+    # 2x2x2 stride 2, 64 -> 128: W[kappa] = [I | 2 I] for one offset copies the child's row into both output slices
+    # (every gather kernel: two slices per workgroup, one, weights fetched per step); then the input gradient and
+    # the transposed convolution of the same map with one-offset weights, which copy parents' rows to children
+    fx_opt("gather_lds", lds_weights)
+    w = G.workload("lidar_small_down")
+    ijk, jo = w.jagged_ijk()
+    g, og = H.both_grids(ijk, jo)
+    km = fx.build_kernel_map(g, 2, 2)
+    ogc = og.coarsen2()
+    nb = O.kernel_map(og, ogc, 2, 2)
+    feat = G.round_to_dtype(np.random.default_rng(6).standard_normal((og.num_voxels, 64)).astype(np.float32), "bf16")
+    d_feat = H.to_device_storage(feat, "bf16")
+    for kappa in (0, 3, 7):
+        wt = np.zeros((8, 64, 128), dtype=np.float32)
+        wt[kappa, :, :64] = np.eye(64)
+        wt[kappa, :, 64:] = 2.0 * np.eye(64)
+        y = fx.sparse_conv_fwd(km, d_feat, H.to_device_storage(wt, "bf16")).float().cpu().numpy()
+        child = np.where(nb[:, kappa:kappa + 1] >= 0, feat[np.maximum(nb[:, kappa], 0)], 0.0)
+        assert np.array_equal(y, np.concatenate([child, 2.0 * child], axis=1))
+    gy = G.round_to_dtype(np.random.default_rng(7).standard_normal((ogc.num_voxels, 128)).astype(np.float32), "bf16")
+    d_gy = H.to_device_storage(gy, "bf16")
+    for kappa in (1, 6):
+        # input gradient: gin[child] = W[kappa] . gout[parent] = first half of the parent's row for children at kappa
+        wt = np.zeros((8, 64, 128), dtype=np.float32)
+        wt[kappa, :, :64] = np.eye(64)
+        gx = fx.sparse_conv_bwd_data(km, d_gy, H.to_device_storage(wt, "bf16")).float().cpu().numpy()
+        expect = np.zeros((og.num_voxels, 64), dtype=np.float32)
+        has = nb[:, kappa] >= 0
+        expect[nb[has, kappa]] = gy[has, :64]
+        assert np.array_equal(gx, expect)
+        # transposed convolution 128 -> 64 with W[kappa] = [0 ; I]: the second half of the parent's row
+        wtt = np.zeros((8, 128, 64), dtype=np.float32)
+        wtt[kappa, 64:, :] = np.eye(64)
+        up = fx.sparse_conv_transpose_fwd(km, d_gy, H.to_device_storage(wtt, "bf16")).float().cpu().numpy()
+        expect = np.zeros((og.num_voxels, 64), dtype=np.float32)
+        expect[nb[has, kappa]] = gy[has, 64:]
+        assert np.array_equal(up, expect)
+
+
 def test_all_ones_counts_neighbours_exactly_in_f16():
     w = G.workload("sheets_small")
     ijk, jo = w.jagged_ijk()
