@@ -93,6 +93,9 @@ void fx_release_cached_memory(void);
  *                    slices when both fit, so that a gathered row serves 128 output channels)
  *   "scalar_lds"     0: the scalar kernel reads its weights through L1 instead of LDS
  *   "grid_direct"    1: the grid build skips the bucket pass (one global leaf table)
+ *   "leaf_links"     0: the grid build does not prepare the table of the leaves around every leaf behind its last
+ *                    step (automatic: it does, and the kernel map of a 3x3x3 convolution of the grid onto itself on
+ *                    the grid's stream starts from it)
  *   "cache_mb"       MiB of released device blocks kept for reuse (automatic: 2048)
  *   "sync_alloc"     1: plain hipMalloc / hipFree, no cache                                                     */
 fx_status fx_set_option(const char* name, int32_t value);

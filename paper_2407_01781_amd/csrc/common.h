@@ -33,7 +33,7 @@ void set_error(const char* fmt, ...);
 // -1 = automatic: the library decides; any other value is what the caller set.
 enum Option {
     kOptForceScalar = 0, kOptLeafDispatch, kOptFp32Tiles, kOptConvGather, kOptGatherLds, kOptScalarLds, kOptGridDirect,
-    kOptCacheMb, kOptSyncAlloc, kOptCount
+    kOptLeafLinks, kOptCacheMb, kOptSyncAlloc, kOptCount
 };
 int option(Option o);
 
@@ -126,6 +126,12 @@ struct fx_grid {
     uint64_t* d_lower_mask = nullptr;
     uint32_t* d_lower_prefix = nullptr;
     fx_leaf* d_leaf = nullptr;
+    // Prepared by the grid build behind its last step, while the host waits for the counts (see enqueue_leaf_links):
+    // [27 * cap_leaf] the leaves around every leaf (-1: none), the table the map of a 3x3x3 convolution of the grid
+    // onto itself starts from, then [cap_leaf + 2] the leaf that holds the first voxel of every run of 512 voxels.
+    // Valid for work on `stream` only.  Null when not prepared.
+    int32_t* d_leaf_links = nullptr;
+    int32_t* d_tile_first_leaf = nullptr;
     fx::TreeView view() const {
         fx::TreeView v;
         v.root_key = d_root_key; v.root_batch = d_root_batch;
@@ -136,3 +142,14 @@ struct fx_grid {
         return v;
     }
 };
+
+namespace fx {
+// Called by the grid build right after its last kernel: allocates g->d_leaf_links / d_tile_first_leaf and enqueues
+// the kernel that fills them from the finished tree, reading the counts from the device header (the host does not
+// know them yet).  The kernel runs while the host waits for the counts and returns to its caller, a stretch in
+// which the device would otherwise idle; the kernel map of a 3x3x3 convolution of the grid onto itself, the common
+// next call, then starts with its tile builder.  A grid whose build overflowed a capacity is skipped by the kernel.
+// Failure to allocate is not an error: the map build then makes the table itself.
+void enqueue_leaf_links(fx_grid* g, hipStream_t st);
+}  // namespace fx
+

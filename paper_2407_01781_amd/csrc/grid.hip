@@ -1342,6 +1342,7 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const Batch
     *h_ticket = 0;
     k_publish<<<1, 256, 0, st>>>(g->d_hdr, g->d_vox_base, B, (unsigned char*)stage, (int32_t*)h_ticket, ticket);
     FX_TRY_OR_FAIL(hipGetLastError());
+    enqueue_leaf_links(g, st);      // runs on the device while the host waits for the ticket and returns to its caller
     {
         // poll the ticket for a while (a few hundred microseconds at most for the sizes where latency
         // matters), then fall back to waiting for the stream, which also reports any device error
@@ -1677,6 +1678,7 @@ extern "C" void fx_grid_destroy(fx_grid* g) {
     if (!g) return;
     if (g->refs.fetch_sub(1) != 1) return;
     if (g->buf) dev_free(g->buf, g->stream);
+    if (g->d_leaf_links) dev_free(g->d_leaf_links, g->stream);
     free(g->h_vox_base);
     delete g;
 }

@@ -94,13 +94,11 @@ __device__ __forceinline__ int lookup_entry(const NbLeafLds& lds, int oi, int oj
 // "neighbours" the coarse voxels (p - delta) / 2 for the offsets delta in {-1,0,1}^3 with p - delta even on
 // every axis (exactly the pairs (coarse o, offset delta) of the forward map with 2 o + delta = p); tin is
 // the coarse grid.  A fine leaf at origin 8t touches coarse coordinates 4t-1 .. 4t+4: two leaves per axis.
-template <int K, bool INV = false>
-__global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int64_t n_out, int32_t* __restrict__ nbr,
-                                 int32_t* __restrict__ tile_first_leaf, int dense_min, int32_t* __restrict__ dense_leaves,
-                                 int32_t* __restrict__ n_dense) {
+template <int K, bool INV>
+__device__ __forceinline__ void leaf_neighbors_item(const TreeView& tin, const TreeView& tout, int stride, int64_t n_out,
+                                                    int64_t e, int32_t* __restrict__ nbr, int32_t* __restrict__ tile_first_leaf,
+                                                    int dense_min, int32_t* __restrict__ dense_leaves, int32_t* __restrict__ n_dense) {
     constexpr int D0 = delta_min(K);
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= (int64_t)tout.n_leaf * 27) return;
     const int f = (int)(e / 27), slot = (int)(e - (int64_t)f * 27);
     const fx_leaf* lf = tout.leaf + f;
     if (slot == 0) {
@@ -120,6 +118,26 @@ __global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int64_
     if (bi + a <= hi_i && bj + c <= hi_j && bk + d <= hi_k)
         id = find_leaf<true>(tin, lf->batch, (bi + a) * 8, (bj + c) * 8, (bk + d) * 8);
     nbr[e] = id;
+}
+
+template <int K, bool INV = false>
+__global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int64_t n_out, int32_t* __restrict__ nbr,
+                                 int32_t* __restrict__ tile_first_leaf, int dense_min, int32_t* __restrict__ dense_leaves,
+                                 int32_t* __restrict__ n_dense) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (int64_t)tout.n_leaf * 27) return;
+    leaf_neighbors_item<K, INV>(tin, tout, stride, n_out, e, nbr, tile_first_leaf, dense_min, dense_leaves, n_dense);
+}
+
+// The table of a 3x3x3 stride-1 map of a grid onto itself, launched by the grid build before the host knows the
+// counts: they come from the device header (the view's own are not set), the launch covers the leaf capacity.
+__global__ void k_leaf_links(TreeView t, const GridHeader* __restrict__ hdr, int32_t* __restrict__ nbr,
+                             int32_t* __restrict__ tile_first_leaf) {
+    if (hdr->overflow) return;                 // a level did not fit: the tree is incomplete and the build is repeated
+    t.n_upper = hdr->n_upper; t.n_lower = hdr->n_lower; t.n_leaf = hdr->n_leaf;
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (int64_t)t.n_leaf * 27) return;
+    leaf_neighbors_item<3, false>(t, t, 1, hdr->n_voxels, e, nbr, tile_first_leaf, 0, nullptr, nullptr);
 }
 
 // stage_leaf with the neighbour leaves read from the table
@@ -958,6 +976,18 @@ extern "C" fx_status fx_build_kernel_map_onto(fx_grid* g_in, fx_grid* g_out, int
     return build_map(g_in, g_out, K, 1, false, (hipStream_t)stream, out);    // takes over that reference
 }
 
+void fx::enqueue_leaf_links(fx_grid* g, hipStream_t st) {
+    if (option(kOptLeafLinks) == 0 || g->d_leaf_links) return;
+    void* p = nullptr;
+    const size_t n_links = 27 * (size_t)g->cap_leaf, n_first = (size_t)g->cap_leaf + 2;     // runs of 512 voxels <= leaves + 1
+    if (dev_alloc(&p, sizeof(int32_t) * (n_links + n_first), st) != FX_OK) return;
+    g->d_leaf_links = (int32_t*)p;
+    g->d_tile_first_leaf = g->d_leaf_links + n_links;
+    const unsigned nb = (unsigned)((n_links + 255) / 256);
+    k_leaf_links<<<nb, 256, 0, st>>>(g->view(), g->d_hdr, g->d_leaf_links, g->d_tile_first_leaf);
+    if (hipGetLastError() != hipSuccess) { dev_free(p, st); g->d_leaf_links = nullptr; g->d_tile_first_leaf = nullptr; }
+}
+
 // The map from the voxels of `gout` (the rows that are produced) to the voxels of `g_in` (the rows that are
 // looked up).  Takes over the caller's reference to gout and retains g_in.  inverse: see k_leaf_neighbors.
 fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool inverse, hipStream_t st, fx_kmap** out, int dense_min) {
@@ -981,8 +1011,12 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
     const size_t o_tp = take(sizeof(uint16_t) * kTileT * nt);
     const size_t o_tr = take(tiled ? sizeof(int32_t) * (size_t)km->row_stride * nt : 0);
     const size_t o_tb = take(tiled ? sizeof(uint16_t) * kIdBlockElems * (size_t)km->block_stride * nt : 0);
-    const size_t o_ln = take(tiled ? sizeof(int32_t) * 27 * (size_t)std::max(gout->hdr.n_leaf, 1) : 0);
-    const size_t o_tf = take(tiled ? sizeof(int32_t) * (nt + 1) : 0);
+    // the table the grid build prepared serves a 3x3x3 map of the grid onto itself (work on the grid's own stream only:
+    // the kernel that fills it may still be running there)
+    const bool links = tiled && K == 3 && stride == 1 && !inverse && g_in == gout && dense_min <= 0 && gout->d_leaf_links &&
+                       st == gout->stream && option(kOptLeafLinks) != 0;
+    const size_t o_ln = take(tiled && !links ? sizeof(int32_t) * 27 * (size_t)std::max(gout->hdr.n_leaf, 1) : 0);
+    const size_t o_tf = take(tiled && !links ? sizeof(int32_t) * (nt + 1) : 0);
     const size_t o_dl = take(dense_min > 0 ? sizeof(int32_t) * ((size_t)std::max(gout->hdr.n_leaf, 1) + 1) : 0);
     fx_status rc = dev_alloc(&km->d_alloc, off, st);
     if (rc != FX_OK) { fx_kmap_destroy(km); return rc; }
@@ -992,8 +1026,8 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
     km->d_tile_perm = (uint16_t*)(p + o_tp);
     km->d_tile_rows = (int32_t*)(p + o_tr);
     km->d_tile_blocks = (uint16_t*)(p + o_tb);
-    int32_t* d_leaf_nbr = (int32_t*)(p + o_ln);
-    int32_t* d_tile_first = (int32_t*)(p + o_tf);
+    int32_t* d_leaf_nbr = links ? gout->d_leaf_links : (int32_t*)(p + o_ln);
+    int32_t* d_tile_first = links ? gout->d_tile_first_leaf : (int32_t*)(p + o_tf);
     int32_t* d_n_dense = dense_min > 0 ? (int32_t*)(p + o_dl) : nullptr;        // the count, then the list
     int32_t* d_dense = dense_min > 0 ? d_n_dense + 1 : nullptr;
     km->d_n_dense = d_n_dense; km->d_dense_leaves = d_dense;
@@ -1004,7 +1038,7 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
         const size_t lds = sizeof(PackLds);
         const unsigned ntl = (unsigned)km->n_tiles;
         const TreeView tin = g_in->view(), tout = gout->view();
-        {
+        if (!links) {
             ProfScope ps(kProfLeafNeighbors, st);
             const int64_t ne = (int64_t)gout->hdr.n_leaf * 27;
             const unsigned nbk = (unsigned)((ne + 255) / 256);

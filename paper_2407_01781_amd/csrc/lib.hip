@@ -22,7 +22,7 @@ void set_error(const char* fmt, ...) {
 // ---------------------------------------------------------------------------------- options
 static std::atomic<int> g_options[kOptCount] = {};          // stored as value + 1, so that zero-initialised = automatic
 static const char* const kOptionNames[kOptCount] = {"force_scalar", "leaf_dispatch", "fp32_tiles", "conv_gather", "gather_lds",
-                                                    "scalar_lds",   "grid_direct",   "cache_mb",   "sync_alloc"};
+                                                    "scalar_lds",   "grid_direct",   "leaf_links", "cache_mb",   "sync_alloc"};
 int option(Option o) { return g_options[o].load(std::memory_order_relaxed) - 1; }
 
 // Device memory.  With a caller's allocator set (fx_set_allocator) every block comes from it and goes back to it.

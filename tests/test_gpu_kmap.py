@@ -41,6 +41,29 @@ def test_workload_maps_match_oracle(name, K, s):
     _check_map(g, og, K, s)
 
 
+def test_map_with_and_without_the_leaf_table_of_the_grid_build(fx_opt):
+    # the grid build prepares the table of the leaves around every leaf on its own stream; a 3x3x3 map of the grid
+    # onto itself starts from it -- unless it is switched off or the map is built on another stream, in which case the
+    # map build makes the table itself.  All three give the oracle's map; so does a grid made from another (padding).
+    grids = [_cloud(21, 30000, -40, 40), _cloud(22, 20000, 4000, 4100), _cloud(23, 500, -4100, -4090)]
+    ijk, jo = G.make_jagged(grids)
+    g, og = H.both_grids(ijk, jo)
+    ref = O.kernel_map(og, og, 3, 1)
+    assert np.array_equal(fx.build_kernel_map(g, 3, 1).dense().cpu().numpy(), ref)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        km = fx.build_kernel_map(g, 3, 1)
+        got = km.dense()
+    side.synchronize()
+    assert np.array_equal(got.cpu().numpy(), ref)
+    gp, ogp = g.pad(1), og.pad(1)
+    assert np.array_equal(fx.build_kernel_map(gp, 3, 1).dense().cpu().numpy(), O.kernel_map(ogp, ogp, 3, 1))
+    fx_opt("leaf_links", 0)
+    g2, _ = H.both_grids(ijk, jo)
+    assert np.array_equal(fx.build_kernel_map(g2, 3, 1).dense().cpu().numpy(), ref)
+
+
 @pytest.mark.parametrize("K,s", [(3, 1), (2, 2), (3, 2)])
 def test_negative_coordinates_and_tile_borders(K, s):
     grids = [_cloud(1, 4000, -20, 20), _cloud(2, 4000, 4080, 4112), np.zeros((0, 3), np.int32),
