@@ -127,11 +127,14 @@ struct fx_grid {
     uint32_t* d_lower_prefix = nullptr;
     fx_leaf* d_leaf = nullptr;
     // Prepared by the grid build behind its last step, while the host waits for the counts (see enqueue_leaf_links):
-    // [27 * cap_leaf] the leaves around every leaf (-1: none), the table the map of a 3x3x3 convolution of the grid
-    // onto itself starts from, then [cap_leaf + 2] the leaf that holds the first voxel of every run of 512 voxels.
+    // [27 * cap_leaf] the leaves of the input grid around every leaf (-1: none) -- the table a kernel map onto this
+    // grid starts from: by default the 3x3x3 stride-1 map of the grid onto itself; for the coarse grid that a strided
+    // map makes for itself, that map's (links_K, links_stride; its input grid is the one the map is being built from)
+    // -- then [cap_leaf + 2] the leaf that holds the first voxel of every run of 512 voxels.
     // Valid for work on `stream` only.  Null when not prepared.
     int32_t* d_leaf_links = nullptr;
     int32_t* d_tile_first_leaf = nullptr;
+    int32_t links_K = 0, links_stride = 0;
     fx::TreeView view() const {
         fx::TreeView v;
         v.root_key = d_root_key; v.root_batch = d_root_batch;
@@ -147,9 +150,13 @@ namespace fx {
 // Called by the grid build right after its last kernel: allocates g->d_leaf_links / d_tile_first_leaf and enqueues
 // the kernel that fills them from the finished tree, reading the counts from the device header (the host does not
 // know them yet).  The kernel runs while the host waits for the counts and returns to its caller, a stretch in
-// which the device would otherwise idle; the kernel map of a 3x3x3 convolution of the grid onto itself, the common
-// next call, then starts with its tile builder.  A grid whose build overflowed a capacity is skipped by the kernel.
-// Failure to allocate is not an error: the map build then makes the table itself.
-void enqueue_leaf_links(fx_grid* g, hipStream_t st);
+// which the device would otherwise idle; the kernel map that comes next then starts with its tile builder.
+// g_in = nullptr: the table of the 3x3x3 stride-1 map of the grid onto itself (the common next call); otherwise
+// that of the (K, stride) map from g_in onto g, for the coarse grid a strided map build makes for itself.
+// A grid whose build overflowed a capacity is skipped by the kernel.  Failure to allocate is not an error: the map
+// build then makes the table itself.
+void enqueue_leaf_links(fx_grid* g, hipStream_t st, const fx_grid* g_in, int K, int stride);
+// fx_grid_coarsen2 for the output grid of a (K, 2) kernel map from g: prepares that map's table (see above)
+fx_status grid_coarsen2_for_map(const fx_grid* g, int K, hipStream_t st, fx_grid** out);
 }  // namespace fx
 

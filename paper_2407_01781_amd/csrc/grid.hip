@@ -1181,6 +1181,7 @@ struct LeafSource {
     const fx_grid* grid = nullptr;
     int r = 0;                    // kPad: the padding
     int32_t* d_bad = nullptr;     // kPad, kSubdivide: counter of leaves beyond the int32 coordinate range
+    int link_K = 0;               // kCoarsen: the grid becomes the output of a (link_K, 2) kernel map from `grid` (0: no)
 };
 
 static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const BatchRanges& d_joff, int32_t B,
@@ -1342,7 +1343,9 @@ static fx_status build_attempt(const int32_t* d_ijk, int64_t n_rows, const Batch
     *h_ticket = 0;
     k_publish<<<1, 256, 0, st>>>(g->d_hdr, g->d_vox_base, B, (unsigned char*)stage, (int32_t*)h_ticket, ticket);
     FX_TRY_OR_FAIL(hipGetLastError());
-    enqueue_leaf_links(g, st);      // runs on the device while the host waits for the ticket and returns to its caller
+    // runs on the device while the host waits for the ticket and returns to its caller
+    if (from.kind == LeafSource::kCoarsen && from.link_K) enqueue_leaf_links(g, st, from.grid, from.link_K, 2);
+    else enqueue_leaf_links(g, st, nullptr, 3, 1);
     {
         // poll the ticket for a while (a few hundred microseconds at most for the sizes where latency
         // matters), then fall back to waiting for the stream, which also reports any device error
@@ -1563,15 +1566,13 @@ extern "C" fx_status fx_build_index_grid_from_points(const float* d_xyz, int64_t
     return FX_OK;
 }
 
-extern "C" fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** out) {
-    if (!g || !out) { set_error("fx_grid_coarsen2: null pointer"); return FX_EINVAL; }
-    hipStream_t st = (hipStream_t)stream;
+fx_status fx::grid_coarsen2_for_map(const fx_grid* g, int K, hipStream_t st, fx_grid** out) {
     // The coarse grid has at most as many nodes per level as the fine one, so one attempt with the fine grid's
     // counts as capacities always fits; its leaves come from the fine leaves, not from a row per voxel.
     fx_grid* o = nullptr;
     const BatchRanges none{nullptr, 0, 0};
     LeafSource from;
-    from.kind = LeafSource::kCoarsen; from.grid = g;
+    from.kind = LeafSource::kCoarsen; from.grid = g; from.link_K = K;
     FX_TRY(build_attempt(nullptr, g->hdr.n_leaf, none, g->B, g->hdr.n_upper, g->hdr.n_lower, g->hdr.n_leaf, true, st, &o, from));
     if (o->hdr.overflow) {
         const int ov = o->hdr.overflow;
@@ -1581,6 +1582,11 @@ extern "C" fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** 
     }
     *out = o;
     return FX_OK;
+}
+
+extern "C" fx_status fx_grid_coarsen2(const fx_grid* g, void* stream, fx_grid** out) {
+    if (!g || !out) { set_error("fx_grid_coarsen2: null pointer"); return FX_EINVAL; }
+    return grid_coarsen2_for_map(g, 0, (hipStream_t)stream, out);
 }
 
 extern "C" fx_status fx_grid_subdivide2(const fx_grid* g, void* stream, fx_grid** out) {

@@ -123,7 +123,9 @@ inline bool map_shares_rows(const fx_kmap* km) {
 fx_status kmap_ensure_dense(fx_kmap* km, hipStream_t st);
 // the inverse of a 3x3x3 stride-2 map in tiled form (km->inverse), built on first use (not thread-safe)
 fx_status kmap_ensure_inverse(fx_kmap* km, hipStream_t st);
-fx_status build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool inverse, hipStream_t st, fx_kmap** out, int dense_min = 0);
+// gout_made_for_map: gout was made by grid_coarsen2_for_map(g_in, K) for this very map (its prepared table applies)
+fx_status build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool inverse, hipStream_t st, fx_kmap** out, int dense_min = 0,
+                    bool gout_made_for_map = false);
 // the submanifold 3x3x3 map without the outputs of locally dense leaves + the list of those leaves (km->mixed),
 // built on first use (not thread-safe)
 fx_status kmap_ensure_mixed(fx_kmap* km, hipStream_t st);

@@ -129,15 +129,18 @@ __global__ void k_leaf_neighbors(TreeView tin, TreeView tout, int stride, int64_
     leaf_neighbors_item<K, INV>(tin, tout, stride, n_out, e, nbr, tile_first_leaf, dense_min, dense_leaves, n_dense);
 }
 
-// The table of a 3x3x3 stride-1 map of a grid onto itself, launched by the grid build before the host knows the
-// counts: they come from the device header (the view's own are not set), the launch covers the leaf capacity.
-__global__ void k_leaf_links(TreeView t, const GridHeader* __restrict__ hdr, int32_t* __restrict__ nbr,
-                             int32_t* __restrict__ tile_first_leaf) {
+// The table of the map that is expected next, launched by the grid build before the host knows the counts of the
+// grid it has just built (tout): they come from the device header (the view's own are not set) and the launch covers
+// the leaf capacity.  self: the map of the grid onto itself (tin is ignored).
+template <int K>
+__global__ void k_leaf_links(TreeView tin, TreeView tout, int self, int stride, const GridHeader* __restrict__ hdr,
+                             int32_t* __restrict__ nbr, int32_t* __restrict__ tile_first_leaf) {
     if (hdr->overflow) return;                 // a level did not fit: the tree is incomplete and the build is repeated
-    t.n_upper = hdr->n_upper; t.n_lower = hdr->n_lower; t.n_leaf = hdr->n_leaf;
+    tout.n_upper = hdr->n_upper; tout.n_lower = hdr->n_lower; tout.n_leaf = hdr->n_leaf;
+    if (self) tin = tout;
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= (int64_t)t.n_leaf * 27) return;
-    leaf_neighbors_item<3, false>(t, t, 1, hdr->n_voxels, e, nbr, tile_first_leaf, 0, nullptr, nullptr);
+    if (e >= (int64_t)tout.n_leaf * 27) return;
+    leaf_neighbors_item<K, false>(tin, tout, stride, hdr->n_voxels, e, nbr, tile_first_leaf, 0, nullptr, nullptr);
 }
 
 // stage_leaf with the neighbour leaves read from the table
@@ -953,9 +956,9 @@ extern "C" fx_status fx_build_kernel_map(fx_grid* g_in, int32_t K, int32_t strid
     hipStream_t st = (hipStream_t)stream;
     fx_grid* gout = nullptr;
     if (stride == 1) { gout = g_in; fx_grid_retain(gout); }
-    else FX_TRY(fx_grid_coarsen2(g_in, stream, &gout));
+    else FX_TRY(grid_coarsen2_for_map(g_in, K, st, &gout));
     fx_kmap* km = nullptr;
-    FX_TRY(build_map(g_in, gout, K, stride, false, st, &km));     // takes over the reference to gout
+    FX_TRY(build_map(g_in, gout, K, stride, false, st, &km, 0, stride != 1));     // takes over the reference to gout
     *g_out = gout;
     fx_grid_retain(gout);
     *out = km;
@@ -976,21 +979,25 @@ extern "C" fx_status fx_build_kernel_map_onto(fx_grid* g_in, fx_grid* g_out, int
     return build_map(g_in, g_out, K, 1, false, (hipStream_t)stream, out);    // takes over that reference
 }
 
-void fx::enqueue_leaf_links(fx_grid* g, hipStream_t st) {
-    if (option(kOptLeafLinks) == 0 || g->d_leaf_links) return;
+void fx::enqueue_leaf_links(fx_grid* g, hipStream_t st, const fx_grid* g_in, int K, int stride) {
+    if (option(kOptLeafLinks) == 0 || g->d_leaf_links || (K != 2 && K != 3)) return;
     void* p = nullptr;
     const size_t n_links = 27 * (size_t)g->cap_leaf, n_first = (size_t)g->cap_leaf + 2;     // runs of 512 voxels <= leaves + 1
     if (dev_alloc(&p, sizeof(int32_t) * (n_links + n_first), st) != FX_OK) return;
     g->d_leaf_links = (int32_t*)p;
     g->d_tile_first_leaf = g->d_leaf_links + n_links;
+    g->links_K = K; g->links_stride = stride;
     const unsigned nb = (unsigned)((n_links + 255) / 256);
-    k_leaf_links<<<nb, 256, 0, st>>>(g->view(), g->d_hdr, g->d_leaf_links, g->d_tile_first_leaf);
+    const TreeView tout = g->view(), tin = g_in ? g_in->view() : tout;
+    if (K == 2) k_leaf_links<2><<<nb, 256, 0, st>>>(tin, tout, g_in ? 0 : 1, stride, g->d_hdr, g->d_leaf_links, g->d_tile_first_leaf);
+    else k_leaf_links<3><<<nb, 256, 0, st>>>(tin, tout, g_in ? 0 : 1, stride, g->d_hdr, g->d_leaf_links, g->d_tile_first_leaf);
     if (hipGetLastError() != hipSuccess) { dev_free(p, st); g->d_leaf_links = nullptr; g->d_tile_first_leaf = nullptr; }
 }
 
 // The map from the voxels of `gout` (the rows that are produced) to the voxels of `g_in` (the rows that are
 // looked up).  Takes over the caller's reference to gout and retains g_in.  inverse: see k_leaf_neighbors.
-fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool inverse, hipStream_t st, fx_kmap** out, int dense_min) {
+fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool inverse, hipStream_t st, fx_kmap** out, int dense_min,
+                        bool gout_made_for_map) {
     fx_kmap* km = new (std::nothrow) fx_kmap();
     if (!km) { fx_grid_destroy(gout); set_error("host allocation failed"); return FX_ENOMEM; }
     km->stream = st; km->gin = g_in; fx_grid_retain(g_in); km->gout = gout;
@@ -1011,10 +1018,11 @@ fx_status fx::build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool in
     const size_t o_tp = take(sizeof(uint16_t) * kTileT * nt);
     const size_t o_tr = take(tiled ? sizeof(int32_t) * (size_t)km->row_stride * nt : 0);
     const size_t o_tb = take(tiled ? sizeof(uint16_t) * kIdBlockElems * (size_t)km->block_stride * nt : 0);
-    // the table the grid build prepared serves a 3x3x3 map of the grid onto itself (work on the grid's own stream only:
-    // the kernel that fills it may still be running there)
-    const bool links = tiled && K == 3 && stride == 1 && !inverse && g_in == gout && dense_min <= 0 && gout->d_leaf_links &&
-                       st == gout->stream && option(kOptLeafLinks) != 0;
+    // the table the grid build prepared: that of the 3x3x3 map of the grid onto itself, or of the strided map whose
+    // build made gout (work on the grid's own stream only: the kernel that fills it may still be running there)
+    const bool links = tiled && !inverse && dense_min <= 0 && gout->d_leaf_links && st == gout->stream &&
+                       option(kOptLeafLinks) != 0 && gout->links_K == K && gout->links_stride == stride &&
+                       (stride == 1 ? (K == 3 && g_in == gout) : gout_made_for_map);
     const size_t o_ln = take(tiled && !links ? sizeof(int32_t) * 27 * (size_t)std::max(gout->hdr.n_leaf, 1) : 0);
     const size_t o_tf = take(tiled && !links ? sizeof(int32_t) * (nt + 1) : 0);
     const size_t o_dl = take(dense_min > 0 ? sizeof(int32_t) * ((size_t)std::max(gout->hdr.n_leaf, 1) + 1) : 0);
