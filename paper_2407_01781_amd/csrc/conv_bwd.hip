@@ -401,14 +401,10 @@ __global__ void k_conv_transpose_scalar(const int32_t* __restrict__ nbmap, int64
 // with voxels along k; rounding back to the storage type is exact.
 // Partial sums go to part[range][kappa][ci][co] (fp32); k_wgrad_reduce adds the ranges in
 // ascending order, so the result does not depend on scheduling.
-constexpr int kWgWaves = 8;
-constexpr int kWgThreads = 64 * kWgWaves;
 constexpr int kWgCi = kCinChunk;            // 32: the row chunk staged in LDS
 constexpr int kWgCo = 64;
 constexpr int kGoutRowBytes = kWgCo * 2;    // one slot of the staged gout tile
 constexpr int kGoutSlabs = kTileT * kGoutRowBytes / 1024;     // 1 KB slabs: 8 slots each
-constexpr int kGoutSlabsPerWave = kGoutSlabs / kWgWaves;
-constexpr int kWgOffsetsPerWave = (kMaxK3Tiled + kWgWaves - 1) / kWgWaves;
 
 struct WgradLds {
     unsigned char rows[kRowBufBytes];
@@ -416,15 +412,32 @@ struct WgradLds {
     unsigned char gt[kTileT * kGoutRowBytes];
 };
 static_assert(sizeof(WgradLds) <= 160 * 1024, "LDS budget of one compute unit");
-static_assert(kGoutSlabs % kWgWaves == 0, "gout slabs per wave");
 static_assert(kGroupsPerWave == 4 && kTileWaves == 4, "id blocks of four column blocks, 8 bytes per voxel");
 
-template <typename T>
-__global__ void __launch_bounds__(kWgThreads, 1)
+// Which tiles a launch takes.  Tiles whose rows are all staged in LDS (kTileLdsOffsets; all but one or two of a
+// sparse grid's) need neither the identity fragments nor the fallback loads of the older form: without that code the
+// kernel fits 128 registers, runs sixteen waves with two offsets each -- four waves per SIMD to cover each other's
+// LDS latencies -- and took 150 us where the eight-wave kernel with both forms took 204 (1 M-voxel LiDAR grid,
+// 64 -> 64); 30 us of those 204 were one workgroup's single tile of the other kind, which costs as much as four
+// staged ones.  When the map has at most kMaxListedTiles such tiles (counted once per map), kWgStaged (16 waves)
+// takes the staged tiles of the ranges, and kWgOthers (8 waves, both forms) takes the listed tiles with one
+// workgroup per column block of a tile, so that no workgroup carries a whole one: workgroup s sums column block s
+// of every listed tile into partial sum n_ranges + s.  Other maps (strided, between two grids, dense grids, whose
+// tiles mostly list one row per pair) take one launch of kWgAll (8 waves, both forms, every tile of the range).
+// Either way a partial sum is made of the same terms in a fixed order.
+enum WgradMode { kWgAll = 0, kWgStaged = 1, kWgOthers = 2 };
+
+template <typename T, int W, int MODE>
+__global__ void __launch_bounds__(64 * W, 1)
 k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict__ tile_perm,
              const int32_t* __restrict__ tile_rows, int row_stride, const uint16_t* __restrict__ tile_blocks,
              int block_stride, int64_t n_tiles, int n_ranges, const uint16_t* __restrict__ feat,
-             const uint16_t* __restrict__ gout, int C_in, int C_out, int K3, float* __restrict__ part) {
+             const uint16_t* __restrict__ gout, int C_in, int C_out, int K3, float* __restrict__ part,
+             const int32_t* __restrict__ tile_list, int n_listed) {
+    constexpr int kWgWaves = W;
+    constexpr int kGoutSlabsPerWave = kGoutSlabs / kWgWaves;
+    constexpr int kWgOffsetsPerWave = (kMaxK3Tiled + kWgWaves - 1) / kWgWaves;
+    static_assert(kGoutSlabs % kWgWaves == 0, "gout slabs per wave");
     typedef typename Elem<T>::vec8 vec8;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     WgradLds& L = *reinterpret_cast<WgradLds*>(lds_raw);
@@ -434,13 +447,13 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
     // Workgroup b runs on XCD b % 8.  The channel blocks of one tile range read the same gout tiles and
     // id blocks: with the number of ranges a multiple of 8 they get block indices 8 apart, so they share
     // an XCD and its L2 and run side by side.
-    int blk = blockIdx.x % n_cblk, range = blockIdx.x / n_cblk;
-    if (n_ranges % 8 == 0) {
+    int blk = blockIdx.x % n_cblk, range = blockIdx.x / n_cblk;      // kWgOthers: range = the column block it sums
+    if (MODE != kWgOthers && n_ranges % 8 == 0) {
         blk = (blockIdx.x >> 3) % n_cblk;
         range = (int)(blockIdx.x / (8 * n_cblk)) * 8 + (blockIdx.x & 7);
     }
     const int cib = blk % n_cib, cob = blk / n_cib;
-    const int64_t t0 = n_tiles * range / n_ranges, t1 = n_tiles * (range + 1) / n_ranges;
+    const int64_t t0 = MODE == kWgOthers ? 0 : n_tiles * range / n_ranges, t1 = MODE == kWgOthers ? n_listed : n_tiles * (range + 1) / n_ranges;
 
     if (tid < kRowBytes / 16) reinterpret_cast<u32x4*>(L.rows + kRowCap * kRowBytes)[tid] = u32x4{0, 0, 0, 0};
 
@@ -488,13 +501,24 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
 #pragma unroll
         for (int j = 0; j < kGoutSlabsPerWave; ++j) nx_local[j] = tile_perm[t * kTileT + 8 * (wave + kWgWaves * j) + (lane >> 3)];
     };
-    if (t0 < t1) resolve(t0);
-    for (int64_t tile = t0; tile < t1; ++tile) {
+    // the tiles that this workgroup takes, in order: positions t0 .. t1 of its range (kWgStaged: the staged ones
+    // among them) or of the list
+    auto tile_of = [&](int64_t c) -> int64_t { return MODE == kWgOthers ? (int64_t)uni(tile_list[c]) : c; };
+    auto next_mine = [&](int64_t c) {
+        if (MODE == kWgStaged)
+            while (c < t1 && !(uni(tile_hdr[c].flags) & kTileLdsOffsets)) ++c;
+        return c;
+    };
+    int64_t cur = next_mine(t0);
+    if (cur < t1) resolve(tile_of(cur));
+    while (cur < t1) {
+        const int64_t cur_next = next_mine(cur + 1);
+        const int64_t tile = tile_of(cur);
         const TileHeader* H = tile_hdr + tile;
         const int flags = uni(H->flags), win_lo = uni(H->win_lo), win_n = uni(H->win_n), n_list = uni(H->n_list);
         const int n_blocks = uni(H->n_blocks), n_valid = uni(H->n_out);
         const int n_staged = (flags & kTileDirect) ? 0 : min(win_n + n_list, kRowCap);
-        const bool general = !(flags & kTileLdsOffsets);
+        const bool general = MODE == kWgStaged ? false : MODE == kWgOthers ? true : !(flags & kTileLdsOffsets);
         const int32_t* my_rows = tile_rows + tile * (int64_t)row_stride;
         uint32_t wmask[kTileWaves], gmask[kGroupsPerTile];
         int block0[kTileWaves];
@@ -542,7 +566,7 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
                 const int off = s * 1024 + lane * 16;
                 if (off < bytes) __builtin_amdgcn_global_load_lds(bsrc + off, (lds_ptr_t)(L.blocks + s * 1024), 16, 0, 0);
             }
-            if (tile + 1 < t1) resolve(tile + 1);
+            if (cur_next < t1) resolve(tile_of(cur_next));
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
@@ -554,6 +578,7 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
             if (kappa >= K3) continue;
 #pragma unroll
             for (int fw = 0; fw < kTileWaves; ++fw) {
+                if (MODE == kWgOthers && fw != tile_wave_of(range)) continue;     // the column block this workgroup sums
                 const uint32_t wm = wmask[fw];
                 if (!((wm >> kappa) & 1u)) continue;
                 const int b = block0[fw] + __popc(wm & ((1u << kappa) - 1u));
@@ -575,6 +600,7 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
                     if (general && (gi & 1) == 0) {
 #pragma unroll
                         for (int gj = gi; gj < gi + 2; ++gj) {
+                            if (MODE == kWgOthers && tile_group_of(fw, gj) != range) continue;
                             if (!((gmask[tile_group_of(fw, gj)] >> kappa) & 1u)) continue;
                             const uint32_t id = (ids[gj >> 1] >> (16 * (gj & 1))) & 0xFFFFu;
                             const bool staged = id < (uint32_t)n_staged;
@@ -590,6 +616,7 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
                         }
                     }
                     const int g = tile_group_of(fw, gi);
+                    if (MODE == kWgOthers && g != range) continue;
                     if (!((gmask[g] >> kappa) & 1u)) continue;
                     vec8 fT[2];
                     if (!general) {
@@ -629,14 +656,16 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
             }
         }
         __syncthreads();
+        cur = cur_next;
     }
 
     // ---- partial sums of this range: lane (co = n, h), register 4b + r  ->  ci = 8b + 4h + r
+    const int range_out = MODE == kWgOthers ? n_ranges + range : range;
 #pragma unroll
     for (int j = 0; j < kWgOffsetsPerWave; ++j) {
         const int kappa = wave + kWgWaves * j;
         if (kappa >= K3) continue;
-        float* dst = part + (((int64_t)range * K3 + kappa) * C_in + cib * kWgCi) * C_out + cob * kWgCo + n;
+        float* dst = part + (((int64_t)range_out * K3 + kappa) * C_in + cib * kWgCi) * C_out + cob * kWgCo + n;
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
@@ -880,12 +909,12 @@ extern "C" fx_status fx_sparse_conv_bwd_data(const fx_kmap* km, const void* d_go
     return strided_pair_product(km, d_gout, dt, d_w, C_out, C_in, d_gin, out_dt, st, kWeightsTransposed);
 }
 
-// Adds the ranges of part[n_ranges][total] in ascending order into gw; above 128 ranges in two levels (groups of
+// Adds the ranges of part[n_ranges][total] in ascending order into gw; above 192 ranges in two levels (groups of
 // 64, then the groups), so that the first level runs at full occupancy.  The bracketing depends on n_ranges only.
 fx_status fx::wgrad_reduce_ranges(const float* part, int n_ranges, int64_t total, void* gw, fx_dtype out_dt, hipStream_t st) {
     constexpr int kReduceGroup = 64;
     hipError_t e;
-    if (n_ranges > 2 * kReduceGroup) {
+    if (n_ranges > 3 * kReduceGroup) {
         float* part2 = nullptr;
         const int n_groups = (n_ranges + kReduceGroup - 1) / kReduceGroup;
         FX_TRY(dev_alloc((void**)&part2, sizeof(float) * (size_t)total * n_groups, st));
@@ -957,7 +986,19 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
         const int n_cblk = (C_in / kWgCi) * (C_out / kWgCo);
         n_ranges = (int)std::max<int64_t>(1, std::min<int64_t>(km->n_tiles, compute_units() / n_cblk));
         if (n_ranges > 8) n_ranges -= n_ranges % 8;   // see the block-to-XCD mapping in the kernel
-        FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * (n_ranges + leaf_ranges), st));
+        // Sparse submanifold maps with at most a few tiles that are not staged in LDS: the sixteen-wave launch for the
+        // staged tiles and, if there are others, the launch that spreads those over one workgroup per column block
+        // (see WgradMode).  Strided maps, maps between two grids, dense grids and maps split per leaf: one launch that
+        // takes every tile.
+        const double occ = (double)km->n_in / (512.0 * (double)std::max<int64_t>(1, km->gin->hdr.n_leaf));
+        bool split = km->stride == 1 && km->gin == km->gout && !km->is_inverse && occ < 0.20 && leaf_ranges == 0;
+        if (split) {
+            FX_TRY(kmap_unstaged_tiles(const_cast<fx_kmap*>(km), st));
+            split = km->h_n_unstaged <= kMaxListedTiles;
+        }
+        const int n_listed = split ? km->h_n_unstaged : 0;
+        const int list_ranges = n_listed > 0 ? kGroupsPerTile : 0;       // one partial sum per column block of the listed tiles
+        FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * (n_ranges + list_ranges + leaf_ranges), st));
         if (leaf_ranges) {
             const fx_status rl = leaf_wgrad16_partial(km_all->gin, d_feat, d_gout, dt, C_in, C_out, km->d_dense_leaves, km->d_n_dense,
                                                       part + (size_t)total * n_ranges, leaf_ranges, st);
@@ -965,16 +1006,30 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
         }
         const size_t lds = sizeof(WgradLds);
         ProfScope ps(kProfWgrad, st);
+#define FX_WGRAD_ONE(T, W, MODE, NWG)                                                                                  \
+    do {                                                                                                               \
+        if (e == hipSuccess)                                                                                           \
+            e = hipFuncSetAttribute((const void*)k_wgrad_mfma<T, W, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                    (int)lds);                                                                         \
+        if (e == hipSuccess) {                                                                                         \
+            k_wgrad_mfma<T, W, MODE><<<(unsigned)(n_cblk * (NWG)), 64 * W, lds, st>>>(                                 \
+                km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows, km->row_stride, km->d_tile_blocks, km->block_stride, \
+                km->n_tiles, n_ranges, (const uint16_t*)d_feat, (const uint16_t*)d_gout, C_in, C_out, km->K3, part,    \
+                km->d_unstaged_list, n_listed);                                                                        \
+            e = hipGetLastError();                                                                                     \
+        }                                                                                                              \
+    } while (0)
 #define FX_WGRAD(T)                                                                                                    \
     do {                                                                                                               \
-        e = hipFuncSetAttribute((const void*)k_wgrad_mfma<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);   \
-        if (e == hipSuccess)                                                                                           \
-            k_wgrad_mfma<T><<<(unsigned)(n_cblk * n_ranges), kWgThreads, lds, st>>>(                                   \
-                km->d_tile_hdr, km->d_tile_perm, km->d_tile_rows, km->row_stride, km->d_tile_blocks, km->block_stride, \
-                km->n_tiles, n_ranges, (const uint16_t*)d_feat, (const uint16_t*)d_gout, C_in, C_out, km->K3, part);   \
+        if (split) {                                                                                                   \
+            FX_WGRAD_ONE(T, 16, kWgStaged, n_ranges);                                                                  \
+            if (n_listed > 0) FX_WGRAD_ONE(T, 8, kWgOthers, kGroupsPerTile);                                           \
+        } else FX_WGRAD_ONE(T, 8, kWgAll, n_ranges);                                                                   \
     } while (0)
         if (dt == FX_BF16) FX_WGRAD(__bf16); else FX_WGRAD(_Float16);
+        n_ranges += list_ranges;      // what the reduction adds up
 #undef FX_WGRAD
+#undef FX_WGRAD_ONE
         if (e == hipSuccess) e = hipGetLastError();
     } else {
         fx_status rc = kmap_ensure_dense(const_cast<fx_kmap*>(km), st);

@@ -104,6 +104,10 @@ struct fx_kmap {
     int32_t row_stride = 0, block_stride = 0;
     int64_t* d_stats = nullptr;             // [4 + K3]: MFMA rows issued, staged rows, direct tiles, tiled bytes, pairs per offset
     void* d_alloc = nullptr;                // single allocation backing all of the above
+    // Tiles whose rows are not all staged in LDS (no kTileLdsOffsets): their number (-1: not counted yet) and the
+    // first kMaxListedTiles of them in ascending order; counted on the first weight gradient over the map.
+    int32_t h_n_unstaged = -1;
+    int32_t* d_unstaged_list = nullptr;
     bool stats_valid = false;
     int64_t h_stats[4] = {0, 0, 0, 0};
     int64_t* h_pairs = nullptr;             // [K3]
@@ -131,4 +135,7 @@ fx_status build_map(fx_grid* g_in, fx_grid* gout, int K, int stride, bool invers
 fx_status kmap_ensure_mixed(fx_kmap* km, hipStream_t st);
 // host copies of the map's statistics (pairs per offset, tiling figures); synchronises the build stream once
 fx_status kmap_fetch_stats(fx_kmap* km);
+constexpr int kMaxListedTiles = 16;
+// km->h_n_unstaged / d_unstaged_list, counting (one small kernel and a wait for its result) on first use
+fx_status kmap_unstaged_tiles(fx_kmap* km, hipStream_t st);
 }

@@ -937,6 +937,7 @@ extern "C" void fx_kmap_destroy(fx_kmap* km) {
     if (km->refs.fetch_sub(1) != 1) return;
     if (km->d_alloc) dev_free(km->d_alloc, km->stream);
     if (km->d_nbmap) dev_free(km->d_nbmap, km->stream);
+    if (km->d_unstaged_list) dev_free(km->d_unstaged_list, km->stream);
     if (km->inverse) fx_kmap_destroy(km->inverse);
     if (km->mixed) fx_kmap_destroy(km->mixed);
     if (km->gin) fx_grid_destroy(km->gin);
@@ -1116,6 +1117,59 @@ fx_status fx::kmap_ensure_mixed(fx_kmap* km, hipStream_t st) {
     }
     fx_grid_retain(km->gout);                  // build_map takes over one reference to the grid of the produced rows
     return build_map(km->gin, km->gout, 3, 1, false, st, &km->mixed, kDenseLeafVoxels);
+}
+
+// One workgroup: the tiles without kTileLdsOffsets, counted and (the first `cap`) listed in ascending order; the count
+// goes to pinned host memory, then the ticket.
+__global__ void __launch_bounds__(1024) k_list_unstaged_tiles(const TileHeader* __restrict__ tile_hdr, int64_t n_tiles,
+                                                              int32_t* __restrict__ list, int cap, int32_t* __restrict__ host_count,
+                                                              int32_t* __restrict__ host_ticket, int32_t ticket) {
+    __shared__ uint32_t wave_count[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t base = 0;
+    for (int64_t t0 = 0; t0 < n_tiles; t0 += 1024) {
+        const int64_t t = t0 + tid;
+        const bool hit = t < n_tiles && !(tile_hdr[t].flags & kTileLdsOffsets);
+        const uint64_t votes = __ballot(hit);
+        if (lane == 0) wave_count[wave] = (uint32_t)__popcll(votes);
+        __syncthreads();
+        uint32_t before = 0, total = 0;
+        for (int w = 0; w < 16; ++w) { const uint32_t c = wave_count[w]; total += c; if (w < wave) before += c; }
+        const uint32_t pos = base + before + (uint32_t)__popcll(votes & ((1ull << lane) - 1ull));
+        if (hit && pos < (uint32_t)cap) list[pos] = (int32_t)t;
+        base += total;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        *host_count = (int32_t)base;
+        __threadfence_system();
+        __hip_atomic_store(host_ticket, ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+}
+
+fx_status fx::kmap_unstaged_tiles(fx_kmap* km, hipStream_t st) {
+    if (km->h_n_unstaged >= 0) return FX_OK;
+    if (km->n_tiles == 0) { km->h_n_unstaged = 0; return FX_OK; }
+    if (!km->d_unstaged_list) FX_TRY(dev_alloc((void**)&km->d_unstaged_list, sizeof(int32_t) * kMaxListedTiles, st));
+    void* stage = nullptr;
+    FX_TRY(host_staging(&stage, 128));      // the area of read-backs that the host waits for
+    volatile int32_t* h_count = reinterpret_cast<volatile int32_t*>(stage);
+    volatile int32_t* h_ticket = reinterpret_cast<volatile int32_t*>((char*)stage + 64);
+    static thread_local int32_t next_ticket = 0;
+    const int32_t ticket = ++next_ticket == 0 ? ++next_ticket : next_ticket;   // never 0
+    *h_ticket = 0;
+    k_list_unstaged_tiles<<<1, 1024, 0, st>>>(km->d_tile_hdr, km->n_tiles, km->d_unstaged_list, kMaxListedTiles,
+                                               (int32_t*)h_count, (int32_t*)h_ticket, ticket);
+    FX_HIP_TRY(hipGetLastError());
+    bool seen = false;
+    for (int spin = 0; spin < 200000 && !seen; ++spin) {
+        seen = (*h_ticket == ticket);
+        if (!seen) __builtin_ia32_pause();
+    }
+    if (!seen) FX_HIP_TRY(hipStreamSynchronize(st));
+    std::atomic_thread_fence(std::memory_order_acquire);
+    km->h_n_unstaged = *h_count;
+    return FX_OK;
 }
 
 fx_status fx::kmap_fetch_stats(fx_kmap* km) {
