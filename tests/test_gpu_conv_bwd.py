@@ -129,6 +129,30 @@ def test_empty_and_tiny_grids():
     _wgrad_check(gw, O.conv_bwd_weight(og, og, 3, 1, feat, gy), 2e-3)
 
 
+@pytest.mark.parametrize("dims,out_f32", [((16, 16, 16), False), ((40, 24, 8), True), ((26, 26, 26), True)])
+def test_sparse_grid_with_a_few_dense_spots(dims, out_f32, fx_opt):
+    # a sparse cloud (leaf occupancy far below 0.2) with one solid block.  A tile in the block's interior has more
+    # rows than the tile kernel stages in LDS (a full leaf with both neighbours on two axes: 10 x 10 x 8 = 800 > 792):
+    # none in 16^3 (every leaf is a corner: 9^3 = 729 rows), a few in 40 x 24 x 8 -- spread over one workgroup per
+    # column block beside the sixteen-wave launch for the staged tiles --, more than 16 in 26^3, which sends the whole
+    # map to the one launch that takes every tile.  Every element against the oracle, and twice with identical bits.
+    fx_opt("leaf_dispatch", "0")
+    rng = np.random.default_rng(90 + dims[0])
+    cloud = rng.integers(-300, 300, size=(40000, 3)).astype(np.int32)
+    ax = [np.arange(d, dtype=np.int32) + 1000 for d in dims]
+    block = np.stack(np.meshgrid(*ax, indexing="ij"), axis=-1).reshape(-1, 3)
+    pts = np.concatenate([cloud, block])[rng.permutation(40000 + block.shape[0])]
+    g, og = H.both_grids(pts, np.array([[0, pts.shape[0]]]))
+    km = fx.build_kernel_map(g, 3, 1)
+    feat, wt = G.features_and_weights(13, og.num_voxels, 64, 64, 27, "bf16")
+    gy = G.round_to_dtype(np.random.default_rng(14).standard_normal((og.num_voxels, 64)).astype(np.float32), "bf16")
+    d_x, d_gy = H.to_device_storage(feat, "bf16"), H.to_device_storage(gy, "bf16")
+    odt = torch.float32 if out_f32 else None
+    gw = fx.sparse_conv_bwd_weight(km, d_x, d_gy, out_dtype=odt)
+    _wgrad_check(gw.float().cpu().numpy(), O.conv_bwd_weight(og, og, 3, 1, feat, gy), 2e-3 if out_f32 else 2e-2)
+    assert torch.equal(gw, fx.sparse_conv_bwd_weight(km, d_x, d_gy, out_dtype=odt))
+
+
 def test_dense_block_with_rows_beyond_the_lds_budget(fx_opt):
     fx_opt("leaf_dispatch", "0")      # this test is about the tile kernel's general variant
     a = np.arange(24, dtype=np.int32)
