@@ -551,6 +551,7 @@ k_wgrad_mfma(const TileHeader* __restrict__ tile_hdr, const uint16_t* __restrict
 #pragma unroll
             for (int j = 0; j < kGoutSlabsPerWave; ++j) {
                 const int slab = wave + kWgWaves * j, slot = 8 * slab + (lane >> 3);
+                if (MODE == kWgOthers && slab / (kGroup / 8) != range) continue;   // only the slots of this workgroup's column block
                 const int gpiece = (lane & 7) ^ (((slot >> 1) & 1) << 2);        // the piece stored at position lane & 7
                 if (local[j] < n_valid) {
                     const uint16_t* src = gout + (tile * kTileT + local[j]) * (int64_t)C_out + cob * kWgCo + gpiece * 8;
