@@ -989,10 +989,10 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
         if (n_ranges > 8) n_ranges -= n_ranges % 8;   // see the block-to-XCD mapping in the kernel
         // Sparse submanifold maps with at most a few tiles that are not staged in LDS: the sixteen-wave launch for the
         // staged tiles and, if there are others, the launch that spreads those over one workgroup per column block
-        // (see WgradMode).  Strided maps, maps between two grids, dense grids and maps split per leaf: one launch that
-        // takes every tile.
+        // (see WgradMode).  Strided maps, maps between two grids and dense grids: one launch that
+        // takes every tile.  (With a per-leaf split the tiles walked are those of the map without the dense leaves.)
         const double occ = (double)km->n_in / (512.0 * (double)std::max<int64_t>(1, km->gin->hdr.n_leaf));
-        bool split = km->stride == 1 && km->gin == km->gout && !km->is_inverse && occ < 0.20 && leaf_ranges == 0;
+        bool split = km->stride == 1 && km->gin == km->gout && !km->is_inverse && occ < 0.20;
         if (split) {
             FX_TRY(kmap_unstaged_tiles(const_cast<fx_kmap*>(km), st));
             split = km->h_n_unstaged <= kMaxListedTiles;
@@ -1002,7 +1002,7 @@ extern "C" fx_status fx_sparse_conv_bwd_weight(const fx_kmap* km, const void* d_
         FX_TRY(dev_alloc((void**)&part, sizeof(float) * (size_t)total * (n_ranges + list_ranges + leaf_ranges), st));
         if (leaf_ranges) {
             const fx_status rl = leaf_wgrad16_partial(km_all->gin, d_feat, d_gout, dt, C_in, C_out, km->d_dense_leaves, km->d_n_dense,
-                                                      part + (size_t)total * n_ranges, leaf_ranges, st);
+                                                      part + (size_t)total * (n_ranges + list_ranges), leaf_ranges, st);
             if (rl != FX_OK) { dev_free(part, st); return rl; }
         }
         const size_t lds = sizeof(WgradLds);
