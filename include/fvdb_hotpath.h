@@ -294,7 +294,9 @@ fx_status fx_sparse_conv_fwd_noalloc(const fx_kmap* km, const void* d_feat, fx_d
  *   d_gw    device [K^3, C_in, C_out], dtype out_dt (= dt or FX_F32); every element is written
  * Products are exact and accumulated in fp32, one rounding (RNE) to out_dt at the end.  The
  * weight gradient is summed in a fixed order (per-workgroup partial sums over contiguous tile
- * ranges, then one ordered reduction): repeated calls give identical bits.
+ * ranges, then one ordered reduction): repeated calls give identical bits.  The first bwd_weight call
+ * over a sparse stride-1 map counts the map's tiles whose rows do not fit the kernel's LDS stage (one small
+ * kernel whose result the host waits for; kept with km) and picks its launches by that count.
  * bwd_data on a stride-1 map is the forward kernel run on the same map with the offsets
  * mirrored and W[kappa] transposed (the map of a submanifold convolution is symmetric); on a
  * K = stride map every input has exactly one pair and its row is written once; on the 3x3x3 stride-2
