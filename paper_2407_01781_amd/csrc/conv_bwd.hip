@@ -683,6 +683,15 @@ __global__ void k_wgrad_reduce(const float* __restrict__ part, int n_ranges, int
     for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < n4; q += (int64_t)gridDim.x * blockDim.x) {
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
         int r = 0;
+        for (; r + 8 <= n_ranges; r += 8) {   // eight loads in flight, added in ascending order
+            f32x4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4*>(part + (int64_t)(r + u) * total + 4 * q);
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s[e] += v[u][e];
+        }
         for (; r + 4 <= n_ranges; r += 4) {   // four loads in flight, added in ascending order
             const f32x4 a = *reinterpret_cast<const f32x4*>(part + (int64_t)r * total + 4 * q);
             const f32x4 b = *reinterpret_cast<const f32x4*>(part + (int64_t)(r + 1) * total + 4 * q);
@@ -770,11 +779,14 @@ __global__ void k_wgrad_reduce_groups(const float* __restrict__ part, int n_rang
 }
 
 static hipError_t launch_reduce(const float* part, int n_ranges, int64_t total, void* gw, fx_dtype out_dt, hipStream_t st) {
-    const unsigned nb = (unsigned)std::max<int64_t>(1, std::min<int64_t>((total / 4 + 255) / 256, 1 << 16));
+    // small weight tensors (27 x 64 x 64 / 4 = 27 648 threads) in workgroups of one wave: 108 workgroups of 256 left
+    // more than half the compute units without one (13.6 -> 11 us); large ones keep 256 (one wave each was slower)
+    const unsigned bs = total / 4 <= 65536 ? 64u : 256u;
+    const unsigned nb = (unsigned)std::max<int64_t>(1, std::min<int64_t>((total / 4 + bs - 1) / bs, 1 << 16));
     ProfScope ps(kProfWgradReduce, st);
-    if (out_dt == FX_F32) k_wgrad_reduce<FX_F32><<<nb, 256, 0, st>>>(part, n_ranges, total, gw);
-    else if (out_dt == FX_F16) k_wgrad_reduce<FX_F16><<<nb, 256, 0, st>>>(part, n_ranges, total, gw);
-    else k_wgrad_reduce<FX_BF16><<<nb, 256, 0, st>>>(part, n_ranges, total, gw);
+    if (out_dt == FX_F32) k_wgrad_reduce<FX_F32><<<nb, bs, 0, st>>>(part, n_ranges, total, gw);
+    else if (out_dt == FX_F16) k_wgrad_reduce<FX_F16><<<nb, bs, 0, st>>>(part, n_ranges, total, gw);
+    else k_wgrad_reduce<FX_BF16><<<nb, bs, 0, st>>>(part, n_ranges, total, gw);
     return hipGetLastError();
 }
 
